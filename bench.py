@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the pattern-sparse 3x3 convolution path on one MI355X.
+
+Default run: the VGG-16 conv3_x-shaped layer (256 -> 256 channels, 56x56, batch 1, fp32, 8-pattern library,
+connectivity keep 0.28), inputs resident in HBM, K launches of pconv_conv3x3 timed after W warm-up launches.
+Prints ONE JSON line: effective GMAC/s over non-zero weights, the roofline position of the kernel and the CPU oracle
+timed on the host cores of the same box.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py --layers vgg_n1|resnet_n32|vgg_n64 [--K 8] [--keep 0.28]   per-layer table (stderr) + JSON line
+    python bench.py --tune                                                     every tiling variant on the workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_VECTOR_TFLOPS = 157.3    # MI355X published fp32 vector peak (256 CUs x 2.4 GHz x 256 flop/clk/CU)
+PEAK_HBM_GBS = 8000.0              # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(spec, n_kept: int) -> int:
+    """Bytes the method itself must move once: activations in, outputs out, four weights and a 16-bit channel
+    index per kept kernel, group pointers, bias."""
+    b = 2 if spec.dtype == "f16" else 4
+    return (b * (spec.N * spec.C * spec.H * spec.W + spec.N * spec.F * spec.Ho * spec.Wo + 4 * n_kept)
+            + 2 * n_kept + 4 * (spec.F * spec.K + 1) + 4 * spec.F)
+
+
+def effective_macs(spec, n_kept: int) -> int:
+    return spec.N * spec.Ho * spec.Wo * 4 * n_kept
+
+
+class DeviceLayer:
+    def __init__(self, spec, batch_from_one_image=False):
+        import torch
+        import paper_2001_07710_amd as pc
+        from workloads import layers as L
+        self.spec, self.pc, self.torch = spec, pc, torch
+        self.w = L.gen_weights(spec)
+        self.lib = spec.library()
+        w32 = self.w.astype(np.float32)
+        t0 = time.perf_counter()
+        self.pid = L.gen_uniform_pattern_ids(spec) if spec.assign == "uniform" else pc.assign_patterns(w32, self.lib)
+        t1 = time.perf_counter()
+        self.mask = (L.gen_bernoulli_mask(spec) if spec.conn == "bernoulli"
+                     else pc.select_connectivity(w32, self.lib, self.pid, spec.keep))
+        t2 = time.perf_counter()
+        self.packed = pc.pack(self.w, self.lib, self.pid, self.mask)
+        t3 = time.perf_counter()
+        self.host_ms = {"assign_ms": (t1 - t0) * 1e3, "select_ms": (t2 - t1) * 1e3, "pack_ms": (t3 - t2) * 1e3}
+        self.n_kept = self.packed.n_kept
+        self.bias = L.gen_bias(spec)
+        if batch_from_one_image and spec.N > 1:
+            # big batches: four seeded images repeated (values do not steer the kernel's control flow)
+            base = L.gen_activations(spec, images=[0, 1, 2, 3][: min(4, spec.N)])
+            reps = (spec.N + base.shape[0] - 1) // base.shape[0]
+            self.x = np.concatenate([base] * reps, axis=0)[: spec.N]
+        else:
+            self.x = L.gen_activations(spec)
+        self.dx = torch.from_numpy(self.x).cuda()
+        self.db = torch.from_numpy(self.bias).cuda()
+        tdt = torch.float16 if spec.dtype == "f16" else torch.float32
+        self.dy = torch.empty((spec.N, spec.F, spec.Ho, spec.Wo), dtype=tdt, device="cuda")
+        self.dtype_code = pc.F16 if spec.dtype == "f16" else pc.F32
+
+    def launch(self, stream, **tuning):
+        s = self.spec
+        flags = self.pc.FLAG_RELU if s.relu else 0
+        if tuning:
+            self.pc.conv3x3_tuned(self.dx, self.dy, self.packed, self.db, s.N, s.H, s.W, s.stride, s.pad, flags, stream,
+                                  **tuning)
+        else:
+            self.pc.conv3x3(self.dx, self.dy, self.packed, self.db, s.N, s.H, s.W, s.stride, s.pad, flags, stream)
+
+    def launch_dense(self, stream, dw):
+        s = self.spec
+        self.pc.dense_conv3x3(self.dx, self.dy, dw, self.db, self.dtype_code, s.N, s.C, s.F, s.H, s.W, s.stride, s.pad,
+                              self.pc.FLAG_RELU if s.relu else 0, stream)
+
+
+def time_launches(torch, fn, steps: int, warmup: int):
+    """(wall ms per step, HIP-event ms per step) for `steps` launches after `warmup` untimed ones."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline(spec, layer, budget_s: float = 12.0):
+    """The oracle as it stands, timed on the host cores, on the same layer (one image for batched workloads)."""
+    import oracle
+    x = layer.x[:1]
+    wm = oracle.mask_weights(layer.w, layer.pid, layer.mask, layer.lib)
+    oracle.conv3x3(x, wm, layer.bias, spec.stride, spec.pad, spec.relu)   # warm the pages
+    runs, t0 = 0, time.perf_counter()
+    while True:
+        oracle.conv3x3(x, wm, layer.bias, spec.stride, spec.pad, spec.relu)
+        runs += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or runs >= 200:
+            break
+    macs = spec.Ho * spec.Wo * 4 * layer.n_kept
+    return {"value": macs * runs / el / 1e9, "unit": "effective GMAC/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{runs} runs of one image of the workload layer ({macs / 1e6:.1f} effective MMAC each), "
+                      f"{el:.1f} s of wall time"}
+
+
+def read_traffic(path: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--layers", default="")
+    ap.add_argument("--K", type=int, default=8)
+    ap.add_argument("--keep", type=float, default=0.28)
+    ap.add_argument("--tune", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (batches shard over GPUs without any exchange)")
+
+    import torch
+    import paper_2001_07710_amd as pc
+    from workloads import layers as L
+    pc.ensure_built()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; there is no CPU fallback")
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    if args.layers:
+        return layer_table(args, torch, pc, L, stream)
+
+    spec = L.config1()
+    layer = DeviceLayer(spec)
+    macs = effective_macs(spec, layer.n_kept)
+    abytes = algorithmic_bytes(spec, layer.n_kept)
+
+    if args.tune:
+        for r, nf, wv in [(7, 1, 4), (7, 1, 8), (7, 1, 16), (7, 2, 4), (7, 2, 8), (4, 1, 4), (4, 1, 8), (4, 1, 16),
+                          (4, 2, 4), (4, 2, 8), (4, 4, 4), (4, 4, 8)]:
+            t = dict(kernel=pc.KERNEL_TILED, rows=r, filters_per_wave=nf, waves=wv)
+            _, ev = time_launches(torch, lambda: layer.launch(stream, **t), 300, 30)
+            log(f"tune rows={r} nf={nf} waves={wv}: {ev * 1e3:8.2f} us  {macs / ev / 1e6:9.1f} GMAC/s")
+
+    wall_ms, ev_ms = time_launches(torch, lambda: layer.launch(stream), args.steps, args.warmup)
+
+    # launch floor: an (almost) empty launch of the same entry point, for context at batch 1
+    tiny = L.shrink(spec, C=1, F=1, H=3, W=3)
+    tl = DeviceLayer(tiny)
+    _, floor_ms = time_launches(torch, lambda: tl.launch(stream), 500, 50)
+
+    dense = None
+    if not args.no_dense:
+        wm = np.where(layer.mask[:, :, None, None] != 0, layer.w, 0).astype(layer.w.dtype)
+        dw = torch.from_numpy(np.ascontiguousarray(wm)).cuda()
+        _, dense_ms = time_launches(torch, lambda: layer.launch_dense(stream, dw), 20, 3)
+        dense = {"ms": dense_ms, "dense_GMACs": spec.N * spec.Ho * spec.Wo * 9 * spec.C * spec.F / dense_ms / 1e6,
+                 "kind": "plain HIP direct convolution, fp32 vector ALU"}
+
+    flops = 2.0 * macs
+    achieved = flops / (ev_ms * 1e-3) / 1e12
+    out = {
+        "metric": "effective GMAC/s (nonzero weights), VGG-16 conv3_x-shaped 3x3 layer",
+        "value": macs / (wall_ms * 1e-3) / 1e9,
+        "unit": "GMAC/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: 3x3 conv 256->256 @56x56, batch 1, fp32, K=8 patterns, keep 0.28 "
+                               f"({layer.n_kept} kept kernels)", "step": "one pconv_conv3x3 launch (weights packed once)"},
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_VECTOR_TFLOPS,
+                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "tiled_kernel_config1_counters.txt")),
+                     "kernel": "tiled_kernel", "kernel_ms": ev_ms, "flops_per_launch": flops,
+                     "algorithmic_bytes_per_launch": abytes, "algorithmic_GBs": abytes / (ev_ms * 1e-3) / 1e9,
+                     "hbm_frac_of_8TBs": abytes / (ev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "note": "plain (unpacked) fp32 FMA tops out at half of the quoted peak"},
+        "launch_floor_ms": floor_ms,
+        "host_once": layer.host_ms,
+        "dense_baseline": dense,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(spec, layer)
+    print(json.dumps(out), flush=True)
+
+
+def layer_table(args, torch, pc, L, stream):
+    """Per-layer timings for one of the layer sweeps (written to stderr as a table, and one JSON line)."""
+    if args.layers == "vgg_n1":
+        specs = L.config2()
+    elif args.layers == "resnet_n32":
+        specs = L.config3(32)
+    elif args.layers == "resnet_n1":
+        specs = L.config3(1)
+    elif args.layers == "vgg_n64":
+        specs = L.config4(args.K, args.keep, 64)
+    else:
+        sys.exit("unknown --layers")
+    rows, tot_macs, tot_ms = [], 0, 0.0
+    for spec in specs:
+        layer = DeviceLayer(spec, batch_from_one_image=True)
+        macs = effective_macs(spec, layer.n_kept)
+        steps = max(10, min(1000, int(2e10 / max(macs, 1))))
+        _, ev = time_launches(torch, lambda: layer.launch(stream), steps, max(3, steps // 10))
+        ab = algorithmic_bytes(spec, layer.n_kept)
+        row = {"layer": spec.name, "C": spec.C, "F": spec.F, "H": spec.H, "N": spec.N, "stride": spec.stride,
+               "dtype": spec.dtype, "keep": spec.keep, "K": spec.K, "n_kept": layer.n_kept, "us": ev * 1e3,
+               "eff_GMACs": macs / ev / 1e6, "alu_frac": 2 * macs / (ev * 1e-3) / 1e12 / PEAK_FP32_VECTOR_TFLOPS,
+               "alg_GBs": ab / (ev * 1e-3) / 1e9, "hbm_frac": ab / (ev * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        if not args.no_dense:
+            wm = np.where(layer.mask[:, :, None, None] != 0, layer.w, 0).astype(layer.w.dtype)
+            dw = torch.from_numpy(np.ascontiguousarray(wm)).cuda()
+            _, dms = time_launches(torch, lambda: layer.launch_dense(stream, dw), 3, 1)
+            row["dense_us"] = dms * 1e3
+        rows.append(row)
+        tot_macs += macs
+        tot_ms += ev
+        log(" ".join(f"{k}={v:.4g}" if isinstance(v, float) else f"{k}={v}" for k, v in row.items()))
+        layer.packed.free()
+        del layer
+        torch.cuda.empty_cache()
+    print(json.dumps({"layers": args.layers, "K": args.K, "keep": args.keep, "total_eff_GMACs": tot_macs / tot_ms / 1e6,
+                      "total_ms": tot_ms, "rows": rows}), flush=True)
+
+
+if __name__ == "__main__":
+    main()

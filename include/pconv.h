@@ -1,0 +1,167 @@
+/*
+ * pconv — pattern-sparse 3x3 convolution for AMD MI355X (gfx950).  C ABI.
+ *
+ * The operation is the forward 3x3 convolution of a layer pruned with pattern-based sparsity:
+ *   - pattern sparsity: every surviving 3x3 kernel keeps exactly four of its nine weights, at the positions of one
+ *     binary mask M_j out of a small pattern library {M_1..M_K}; pruning is the element-wise product W o M_j
+ *     (paper, sections 3, 4.1 and eq. (1) of section 5.1);
+ *   - connectivity sparsity: whole kernels between an input channel c and an output filter f are removed
+ *     (paper, sections 3 and 6.1).
+ * The result is exactly that of a dense convolution whose weight tensor carries explicit zeros.
+ *
+ * Conventions used by every entry point
+ *   - weights are OIHW, contiguous: w[f][c][ky][kx], F filters, C channels (section 6.1 names them F and C);
+ *   - the tap index of a kernel position is t = 3*ky + kx; a pattern mask is a 9-bit integer with bit t set where the
+ *     weight is kept; the convolution does not flip the kernel (cross-correlation);
+ *   - activations are NCHW, contiguous; Ho = floor((H + 2*pad - 3)/stride) + 1, likewise Wo; positions outside the
+ *     image read as zero;
+ *   - dtype is the STORAGE type of x, y and w (PCONV_F32 or PCONV_F16); sums are always accumulated in fp32, the
+ *     bias is always fp32, fp16 results are rounded to nearest even once, at the store;
+ *   - every function returns PCONV_OK (0) or a negative error code; nothing throws; the library keeps no global
+ *     mutable state and distinct handles may be used from distinct threads;
+ *   - "host" / "device" in a parameter comment says where the pointer must point.  Device buffers are owned by the
+ *     caller; the library owns what it allocates behind a pconv_packed handle until pconv_free.
+ */
+#ifndef PCONV_H
+#define PCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pconv_packed pconv_packed; /* opaque packed layer */
+
+enum { PCONV_F32 = 0, PCONV_F16 = 1 };
+
+enum {
+    PCONV_OK = 0,
+    PCONV_EINVAL = -1,       /* null pointer, bad enum or flag */
+    PCONV_EPATTERN = -2,     /* library mask without exactly four bits in its low nine, K outside [1,126], pattern id >= K */
+    PCONV_ESHAPE = -3,       /* zero or negative extent, C >= 65536, empty output, size overflow */
+    PCONV_EUNSUPPORTED = -4, /* stride not 1 or 2, pad not 0 or 1 */
+    PCONV_ENOMEM = -5,       /* host or device allocation failed */
+    PCONV_EHIP = -6,         /* a HIP call failed (pconv_last_hip_error() has the runtime's text) */
+    PCONV_ESTATE = -7        /* handle was packed host-only and has no device copy */
+};
+
+enum { PCONV_FLAG_RELU = 1u };      /* conv flags: y = max(y, 0) after the bias */
+enum { PCONV_PACK_HOST_ONLY = 1u }; /* pack flags: build the packed form on the host, allocate nothing on the device */
+
+/*
+ * Pattern assignment (host).  For every kernel picks the library mask that keeps the largest part of the kernel's
+ * squared L2 norm, i.e. the Euclidean projection of the kernel onto the library — the hard one-hot selection that
+ * ends section 5.1 of the paper.  Squares and sums are taken in double, taps ascending; ties go to the lowest index.
+ *   w_oihw   host, float[F*C*9]
+ *   lib      host, uint16[K], each with exactly four of the low nine bits set
+ *   pid_out  host, uint8[F*C], written
+ * K must be in [1,126].
+ */
+int pconv_assign_patterns(const float* w_oihw, int F, int C, const uint16_t* lib, int K, uint8_t* pid_out);
+
+/*
+ * Connectivity selection (host).  Scores every kernel by the squared L2 norm that its assigned pattern keeps (the
+ * connectivity score gamma of section 6.1, squared, on the pattern-pruned kernel) and keeps the
+ * k = floor(keep*F*C + 0.5) kernels of the layer with the largest score; ties by ascending index f*C + c.
+ *   pid       host, uint8[F*C] (from pconv_assign_patterns or the caller's own)
+ *   keep      fraction in [0,1]
+ *   mask_out  host, uint8[F*C], written: 1 = kernel kept, 0 = removed
+ */
+int pconv_select_connectivity(const float* w_oihw, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
+                              double keep, uint8_t* mask_out);
+
+/*
+ * Pack: dense weights + per-kernel pattern id + connectivity mask -> pattern-grouped compressed weights.  This is
+ * the filter/kernel re-ordering and compact weight storage of section 6.2, in this library's own layout: filters
+ * ordered by kept-kernel count, and inside a filter the kernels with the same pattern stored together.
+ *   w_oihw   host, dtype-typed [F*C*9]; weights are copied bit for bit, entries outside the pattern are ignored
+ *   dtype    PCONV_F32 or PCONV_F16: type of w_oihw here and of x and y in pconv_conv3x3
+ *   pid      host, uint8[F*C]; entries of removed kernels are ignored
+ *   mask     host, uint8[F*C]; non-zero = kept
+ *   flags    0, or PCONV_PACK_HOST_ONLY
+ *   out      receives the handle; release with pconv_free
+ * Unless PCONV_PACK_HOST_ONLY is given, the packed arrays are copied to the current HIP device (synchronously) and
+ * the handle is tied to that device.
+ */
+int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
+               const uint8_t* mask, unsigned flags, pconv_packed** out);
+
+/*
+ * Canonical packed form, for inspection, storage and bit-exact comparison (all host pointers, caller-allocated):
+ *   filter_order uint32[F]      filters by (kept count descending, filter index ascending)
+ *   grp_ptr      uint32[F*K+1]  grp_ptr[i*K+j] .. grp_ptr[i*K+j+1] = entries of filter filter_order[i] with mask j
+ *   cin          uint16[n_kept] input channel of each entry, ascending inside a group
+ *   w4           dtype[n_kept*4] the four kept weights of each entry, taps ascending, bit-identical to the input
+ *   n_kept       receives the number of kept kernels
+ * Any array pointer may be NULL to skip it (call once with all NULL to learn n_kept).
+ */
+int pconv_packed_export(const pconv_packed* p, uint32_t* filter_order, uint32_t* grp_ptr, uint16_t* cin, void* w4,
+                        size_t* n_kept);
+
+/* Shape of a packed layer; any output pointer may be NULL. */
+int pconv_packed_stats(const pconv_packed* p, int* F, int* C, int* K, int* dtype, size_t* n_kept);
+
+/* Releases host and device memory of a handle (NULL is allowed).  The caller makes sure no launch still uses it. */
+void pconv_free(pconv_packed* p);
+
+/*
+ * The pruned layer (section 3; the computation the paper's inference framework of section 6.2 accelerates):
+ *   y[n][f][oy][ox] = bias[f] + sum over kept kernels (f,c), over the four taps t of their pattern, of
+ *                     w[f][c][t] * x[n][c][oy*stride + ky - pad][ox*stride + kx - pad]
+ * optionally followed by max(.,0).  Asynchronous on `stream`.
+ *   x       device, dtype[N*C*H*W], read only; must not overlap y
+ *   y       device, dtype[N*F*Ho*Wo], every element written
+ *   wp      handle from pconv_pack (with a device copy, on the current device)
+ *   bias    device, float[F], or NULL for no bias
+ *   stride  1 or 2;  pad 0 or 1
+ *   flags   0 or PCONV_FLAG_RELU
+ *   stream  a hipStream_t passed as void* (NULL = the default stream)
+ * Launch errors are returned; execution errors surface at the caller's next synchronisation.  N = 0 is a no-op.
+ */
+int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W, int stride,
+                  int pad, unsigned flags, void* stream);
+
+/*
+ * pconv_conv3x3 with the kernel choice in the caller's hands, for tuning sweeps and for tests that must reach every
+ * kernel.  A NULL `tuning`, or a field left 0, means "choose automatically" (what pconv_conv3x3 does).
+ *   kernel            PCONV_KERNEL_TILED (stride 1 only: activations staged in LDS, weights in scalar registers)
+ *                     or PCONV_KERNEL_GENERIC (any stride and pad, straight from global memory)
+ *   rows              tiled: output rows held per lane, 4 or 7
+ *   filters_per_wave  tiled: filters accumulated at once by one wave, 1, 2 (or 4 with rows = 4)
+ *   waves             tiled: waves per workgroup, 1..16
+ * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
+ */
+enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2 };
+typedef struct pconv_tuning {
+    int kernel;
+    int rows;
+    int filters_per_wave;
+    int waves;
+} pconv_tuning;
+int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
+                        int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning);
+
+/*
+ * Dense 3x3 convolution of the same shape, for comparison: all nine taps of all F*C kernels (give it the masked
+ * dense tensor to compute the same function as pconv_conv3x3).  Same conventions and argument meaning.
+ *   w_oihw  device, dtype[F*C*9]
+ */
+int pconv_dense_conv3x3(const void* x, void* y, const void* w_oihw, const float* bias, int dtype, int N, int C, int F,
+                        int H, int W, int stride, int pad, unsigned flags, void* stream);
+
+/* 2x2 max-pool with stride 2 (between the VGG-16 stages): y[n][c][oy][ox] over floor(H/2) x floor(W/2) outputs.
+ *   x device dtype[N*C*H*W]; y device dtype[N*C*(H/2)*(W/2)]. */
+int pconv_maxpool2x2(const void* x, void* y, int dtype, int N, int C, int H, int W, void* stream);
+
+/* Text for an error code (static storage). */
+const char* pconv_strerror(int code);
+
+/* Text of the last HIP error seen by the calling thread inside this library (static or thread-local storage). */
+const char* pconv_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCONV_H */

@@ -1,0 +1,209 @@
+"""Python binding of libpconv (pattern-sparse 3x3 convolution for MI355X).
+
+Argument marshalling only: every step of the path runs inside the C-ABI library declared in include/pconv.h; the
+functions here have the same names minus the `pconv_` prefix.  Host arrays are numpy arrays; device buffers are
+anything with a `data_ptr()` (torch tensors on the GPU), used only for their address.  There is no CPU fallback: a
+missing or broken library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+F32, F16 = 0, 1
+FLAG_RELU = 1
+PACK_HOST_ONLY = 1
+KERNEL_AUTO, KERNEL_TILED, KERNEL_GENERIC = 0, 1, 2
+OK, EINVAL, EPATTERN, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpconv.so")
+_lib = None
+
+
+class PconvError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        text = _load().pconv_strerror(code).decode()
+        hip = _load().pconv_last_hip_error().decode() if code == EHIP else ""
+        super().__init__(f"{where}: {text} (code {code})" + (f" [{hip}]" if hip else ""))
+
+
+class _Tuning(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int), ("rows", ctypes.c_int), ("filters_per_wave", ctypes.c_int),
+                ("waves", ctypes.c_int)]
+
+
+def ensure_built() -> str:
+    """Build the library if no built one is there (tests, smoke and bench call this; the binding itself never builds)."""
+    if not os.path.exists(LIB_PATH):
+        from .build import build_library
+        build_library()
+    return LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, u = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint
+    lib.pconv_assign_patterns.argtypes = [vp, i, i, vp, i, vp]
+    lib.pconv_select_connectivity.argtypes = [vp, i, i, vp, i, vp, ctypes.c_double, vp]
+    lib.pconv_pack.argtypes = [vp, i, i, i, vp, i, vp, vp, u, ctypes.POINTER(vp)]
+    lib.pconv_packed_export.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.pconv_packed_stats.argtypes = [vp, ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
+                                       ctypes.POINTER(ctypes.c_size_t)]
+    lib.pconv_free.argtypes = [vp]
+    lib.pconv_free.restype = None
+    lib.pconv_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp]
+    lib.pconv_conv3x3_tuned.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp, ctypes.POINTER(_Tuning)]
+    lib.pconv_dense_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, u, vp]
+    lib.pconv_maxpool2x2.argtypes = [vp, vp, i, i, i, i, i, vp]
+    for name in ("pconv_assign_patterns", "pconv_select_connectivity", "pconv_pack", "pconv_packed_export",
+                 "pconv_packed_stats", "pconv_conv3x3", "pconv_conv3x3_tuned", "pconv_dense_conv3x3",
+                 "pconv_maxpool2x2"):
+        getattr(lib, name).restype = i
+    lib.pconv_strerror.argtypes = [i]
+    lib.pconv_strerror.restype = ctypes.c_char_p
+    lib.pconv_last_hip_error.argtypes = []
+    lib.pconv_last_hip_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise PconvError(rc, where)
+
+
+def _host(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def _dp(t):
+    return None if t is None else int(t.data_ptr())
+
+
+def _dtype_code(np_dtype) -> int:
+    if np.dtype(np_dtype) == np.float32:
+        return F32
+    if np.dtype(np_dtype) == np.float16:
+        return F16
+    raise TypeError("storage type must be float32 or float16")
+
+
+def strerror(code: int) -> str:
+    return _load().pconv_strerror(code).decode()
+
+
+def assign_patterns(w_oihw, lib) -> np.ndarray:
+    w = _host(w_oihw, np.float32)
+    F, C = w.shape[:2]
+    lb = _host(lib, np.uint16)
+    pid = np.empty((F, C), dtype=np.uint8)
+    _check(_load().pconv_assign_patterns(_hp(w), F, C, _hp(lb), int(lb.size), _hp(pid)), "pconv_assign_patterns")
+    return pid
+
+
+def select_connectivity(w_oihw, lib, pid, keep: float) -> np.ndarray:
+    w = _host(w_oihw, np.float32)
+    F, C = w.shape[:2]
+    lb = _host(lib, np.uint16)
+    pd = _host(pid, np.uint8)
+    mask = np.empty((F, C), dtype=np.uint8)
+    _check(_load().pconv_select_connectivity(_hp(w), F, C, _hp(lb), int(lb.size), _hp(pd), float(keep), _hp(mask)),
+           "pconv_select_connectivity")
+    return mask
+
+
+class Packed:
+    """Owner of a pconv_packed handle."""
+
+    def __init__(self, handle: int, F: int, C: int, K: int, np_dtype):
+        self.handle, self.F, self.C, self.K, self.np_dtype = handle, F, C, K, np.dtype(np_dtype)
+
+    @property
+    def n_kept(self) -> int:
+        n = ctypes.c_size_t(0)
+        _check(_load().pconv_packed_stats(self.handle, None, None, None, None, ctypes.byref(n)), "pconv_packed_stats")
+        return int(n.value)
+
+    def free(self):
+        if self.handle:
+            _load().pconv_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def pack(w_oihw, lib, pid, mask, flags: int = 0) -> Packed:
+    w = np.ascontiguousarray(w_oihw)
+    code = _dtype_code(w.dtype)
+    F, C = w.shape[:2]
+    lb = _host(lib, np.uint16)
+    pd = _host(pid, np.uint8)
+    mk = _host(mask, np.uint8)
+    out = ctypes.c_void_p(None)
+    _check(_load().pconv_pack(_hp(w), code, F, C, _hp(lb), int(lb.size), _hp(pd), _hp(mk), int(flags),
+                              ctypes.byref(out)), "pconv_pack")
+    return Packed(out.value, F, C, int(lb.size), w.dtype)
+
+
+def packed_stats(p: Packed):
+    F, C, K, dt = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    n = ctypes.c_size_t()
+    _check(_load().pconv_packed_stats(p.handle, ctypes.byref(F), ctypes.byref(C), ctypes.byref(K), ctypes.byref(dt),
+                                      ctypes.byref(n)), "pconv_packed_stats")
+    return F.value, C.value, K.value, dt.value, int(n.value)
+
+
+def packed_export(p: Packed):
+    n = p.n_kept
+    fo = np.empty(p.F, dtype=np.uint32)
+    gp = np.empty(p.F * p.K + 1, dtype=np.uint32)
+    cin = np.empty(n, dtype=np.uint16)
+    w4 = np.empty((n, 4), dtype=p.np_dtype)
+    nk = ctypes.c_size_t(0)
+    _check(_load().pconv_packed_export(p.handle, _hp(fo), _hp(gp), _hp(cin), _hp(w4), ctypes.byref(nk)),
+           "pconv_packed_export")
+    assert nk.value == n
+    return fo, gp, cin, w4
+
+
+def conv3x3(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad: int = 1, flags: int = 0,
+            stream: int = 0):
+    _check(_load().pconv_conv3x3(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, pad, flags, stream or None),
+           "pconv_conv3x3")
+
+
+def conv3x3_tuned(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad: int = 1, flags: int = 0,
+                  stream: int = 0, kernel: int = 0, rows: int = 0, filters_per_wave: int = 0, waves: int = 0):
+    t = _Tuning(kernel, rows, filters_per_wave, waves)
+    _check(_load().pconv_conv3x3_tuned(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, pad, flags,
+                                       stream or None, ctypes.byref(t)), "pconv_conv3x3_tuned")
+
+
+def dense_conv3x3(x, y, w_oihw_dev, bias, dtype: int, N: int, C: int, F: int, H: int, W: int, stride: int = 1,
+                  pad: int = 1, flags: int = 0, stream: int = 0):
+    _check(_load().pconv_dense_conv3x3(_dp(x), _dp(y), _dp(w_oihw_dev), _dp(bias), dtype, N, C, F, H, W, stride, pad,
+                                       flags, stream or None), "pconv_dense_conv3x3")
+
+
+def maxpool2x2(x, y, dtype: int, N: int, C: int, H: int, W: int, stream: int = 0):
+    _check(_load().pconv_maxpool2x2(_dp(x), _dp(y), dtype, N, C, H, W, stream or None), "pconv_maxpool2x2")

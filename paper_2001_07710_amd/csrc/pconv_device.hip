@@ -1,0 +1,633 @@
+// Device side of libpconv for gfx950 (MI355X): kernels, launch selection, device upload of the packed weights.
+//
+// Kernels in this file
+//   tiled_kernel    pattern-sparse 3x3 convolution, stride 1: activations staged in LDS in a lane-shaped layout,
+//                   one filter (or a few) per wave, weights in scalar registers, one code section per pattern
+//   generic_kernel  the same sum for any stride and pad, one thread per output, straight from global memory
+//   dense_kernel    dense 3x3 convolution of the same shape (comparison baseline)
+//   maxpool_kernel  2x2 max-pool
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+
+#include "pconv_internal.h"
+
+namespace pconv {
+
+// ---------------------------------------------------------------------------------------------------------------
+// error text
+// ---------------------------------------------------------------------------------------------------------------
+
+static thread_local char g_hip_error[256] = "";
+
+void set_hip_error(const char* what, int hip_code) {
+    std::snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString((hipError_t)hip_code));
+}
+
+#define PCONV_HIP(call)                                  \
+    do {                                                 \
+        hipError_t e_ = (call);                          \
+        if (e_ != hipSuccess) {                          \
+            pconv::set_hip_error(#call, (int)e_);        \
+            return PCONV_EHIP;                           \
+        }                                                \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------------------------------
+// upload / release
+// ---------------------------------------------------------------------------------------------------------------
+
+int upload_packed(pconv_packed* p) {
+    int dev = -1;
+    PCONV_HIP(hipGetDevice(&dev));
+    const size_t n_ent = std::max<size_t>(p->ent.size(), 1);
+    PCONV_HIP(hipMalloc((void**)&p->d_ent, n_ent * sizeof(DevEntry)));
+    PCONV_HIP(hipMalloc((void**)&p->d_eptr, p->eptr.size() * sizeof(uint32_t)));
+    PCONV_HIP(hipMalloc((void**)&p->d_forder, p->filter_order.size() * sizeof(uint32_t)));
+    if (!p->ent.empty())
+        PCONV_HIP(hipMemcpy(p->d_ent, p->ent.data(), p->ent.size() * sizeof(DevEntry), hipMemcpyHostToDevice));
+    else
+        PCONV_HIP(hipMemset(p->d_ent, 0, sizeof(DevEntry)));
+    PCONV_HIP(hipMemcpy(p->d_eptr, p->eptr.data(), p->eptr.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+    PCONV_HIP(hipMemcpy(p->d_forder, p->filter_order.data(), p->filter_order.size() * sizeof(uint32_t),
+                        hipMemcpyHostToDevice));
+    p->device = dev;
+    return PCONV_OK;
+}
+
+void release_device(pconv_packed* p) {
+    if (p->d_ent) (void)hipFree(p->d_ent);
+    if (p->d_eptr) (void)hipFree(p->d_eptr);
+    if (p->d_forder) (void)hipFree(p->d_forder);
+    p->d_ent = nullptr;
+    p->d_eptr = nullptr;
+    p->d_forder = nullptr;
+    p->device = -1;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// small device helpers
+// ---------------------------------------------------------------------------------------------------------------
+
+template <typename T>
+__device__ __forceinline__ float to_f32(T v);
+template <>
+__device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ float to_f32<__half>(__half v) { return __half2float(v); }
+
+template <typename T>
+__device__ __forceinline__ T from_f32(float v);
+template <>
+__device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ __half from_f32<__half>(float v) { return __float2half_rn(v); }
+
+// Raw buffer descriptor over `bytes` bytes at `base`: loads whose per-lane offset is at or beyond `bytes` return
+// zero without touching memory, which is how padding and ragged tiles are read.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+constexpr uint32_t kInvalidOffset = 0x80000000u;
+
+template <typename T>
+__device__ __forceinline__ float buffer_load_f32(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff);
+template <>
+__device__ __forceinline__ float buffer_load_f32<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+}
+template <>
+__device__ __forceinline__ float buffer_load_f32<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    const unsigned short h = __builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
+    return __half2float(__builtin_bit_cast(__half, h));
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// the 126 masks with four of nine bits, ascending, at compile time
+// ---------------------------------------------------------------------------------------------------------------
+
+struct MaskTable {
+    unsigned v[126];
+};
+constexpr MaskTable build_mask_table() {
+    MaskTable t{};
+    int n = 0;
+    for (unsigned m = 0; m < 512; ++m) {
+        int bits = 0;
+        for (int b = 0; b < 9; ++b) bits += (m >> b) & 1u;
+        if (bits == 4) t.v[n++] = m;
+    }
+    return t;
+}
+constexpr MaskTable kMasks = build_mask_table();
+
+// ---------------------------------------------------------------------------------------------------------------
+// tiled kernel (stride 1)
+//
+// Lane layout.  A wave owns S segments of LW lanes.  A segment is OWS consecutive output columns of R consecutive
+// output rows of one image, plus one halo lane on each side; lane t of a segment holds INPUT column
+// ix = os + t - pad and, in registers, the R+2 input rows that its R output rows read.  A tap (ky,kx) of a kernel
+// multiplies the lane's own column: acc[kx][r] += w * x[r + ky].  The three accumulator sets (one per kx) belong to
+// output columns ix+1, ix, ix-1 (+pad-1) and are added across neighbouring lanes once, after the last channel.
+// So the inner loop has no cross-lane traffic and no address arithmetic: 4*R multiply-adds per kept kernel, weights
+// from scalar registers.
+//
+// LDS layout.  tile[cc][i][lane]: channel-in-chunk, patch row i = r + ky, lane.  Every read and write of a wave is
+// 64 consecutive dwords.
+//
+// Work split.  A workgroup is one slot (the S segments) times FW*NF filters: wave w accumulates NF filters.  All
+// waves share the staged activations.  Entries of a filter are bucketed by channel chunk; inside a bucket they are
+// sorted by pattern, and the pattern selects one of 126 straight-line code sections through a scalar branch tree,
+// so a wave never diverges (the per-pattern generated code of section 6.2 of the paper, as compiled-in sections).
+// ---------------------------------------------------------------------------------------------------------------
+
+struct TiledParams {
+    const void* x;
+    void* y;
+    const DevEntry* ent;
+    const uint32_t* eptr;
+    const uint32_t* forder;
+    const float* bias;
+    int N, C, F, H, W, Ho, Wo, pad, relu;
+    int nch;                 // channel chunks
+    int LW, S, OWS, NCS, NRB, NSEG;
+    int NG;                  // filter groups per slot
+    int nblocks;             // NG * slots (the grid is padded to a multiple of 8)
+    unsigned long long x_bytes;
+    unsigned img_bytes;      // C*H*W*sizeof(T)
+    unsigned plane_bytes;    // H*W*sizeof(T)
+};
+
+template <unsigned MASK, int R>
+__device__ __forceinline__ void apply_pattern(float (&acc)[3][R], const float (&xp)[R + 2], const float (&w)[4]) {
+    int q = 0;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        if ((MASK >> t) & 1u) {
+            const int ky = t / 3, kx = t % 3;
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[kx][r] = fmaf(w[q], xp[r + ky], acc[kx][r]);
+            ++q;
+        }
+    }
+}
+
+template <int LO, int HI, int R>
+__device__ __forceinline__ void dispatch_pattern(unsigned m, float (&acc)[3][R], const float (&xp)[R + 2],
+                                                 const float (&w)[4]) {
+    if constexpr (HI - LO == 1) {
+        apply_pattern<kMasks.v[LO], R>(acc, xp, w);
+    } else {
+        constexpr int MID = (LO + HI) / 2;
+        if (m < kMasks.v[MID])
+            dispatch_pattern<LO, MID, R>(m, acc, xp, w);
+        else
+            dispatch_pattern<MID, HI, R>(m, acc, xp, w);
+    }
+}
+
+struct EntryRegs {
+    float w[4];
+    unsigned cc, mask9;
+};
+
+__device__ __forceinline__ EntryRegs load_entry(const DevEntry* __restrict__ ent, unsigned e) {
+    // e is wave-uniform: the compiler turns this into scalar loads
+    const uint4 a = *reinterpret_cast<const uint4*>(&ent[e].w[0]);
+    const uint2 b = *reinterpret_cast<const uint2*>(&ent[e].cc);
+    EntryRegs r;
+    r.w[0] = __builtin_bit_cast(float, a.x);
+    r.w[1] = __builtin_bit_cast(float, a.y);
+    r.w[2] = __builtin_bit_cast(float, a.z);
+    r.w[3] = __builtin_bit_cast(float, a.w);
+    r.cc = b.x;
+    r.mask9 = b.y;
+    return r;
+}
+
+template <int R>
+__device__ __forceinline__ void load_patch(float (&xp)[R + 2], const float* tile_lane, unsigned cc) {
+    const float* p = tile_lane + cc * ((R + 2) * 64);
+#pragma unroll
+    for (int i = 0; i < R + 2; ++i) xp[i] = p[i * 64];
+}
+
+// All kept kernels of the filter at position `pos` of the sorted filter order whose channel lies in chunk k.
+// Entry e+1 and its activations are fetched while entry e is being multiplied (two register sets, swapped by
+// unrolling the loop once).
+template <int R>
+__device__ __forceinline__ void accumulate_filter(float (&acc)[3][R], const TiledParams& p, const float* tile_lane,
+                                                  int pos, int k) {
+    if (pos >= p.F) return;
+    unsigned e = p.eptr[pos * p.nch + k];
+    const unsigned e1 = p.eptr[pos * p.nch + k + 1];
+    if (e >= e1) return;
+    EntryRegs ea = load_entry(p.ent, e);
+    float xa[R + 2], xb[R + 2];
+    load_patch<R>(xa, tile_lane, ea.cc);
+    while (true) {
+        const bool has_b = e + 1 < e1;
+        const EntryRegs eb = load_entry(p.ent, has_b ? e + 1 : e);
+        load_patch<R>(xb, tile_lane, eb.cc);
+        dispatch_pattern<0, 126, R>(ea.mask9, acc, xa, ea.w);
+        if (!has_b) break;
+        const bool has_a = e + 2 < e1;
+        ea = load_entry(p.ent, has_a ? e + 2 : e + 1);
+        load_patch<R>(xa, tile_lane, ea.cc);
+        dispatch_pattern<0, 126, R>(eb.mask9, acc, xb, eb.w);
+        if (!has_a) break;
+        e += 2;
+    }
+}
+
+template <int R, int NF, int MAXT, typename T>
+__global__ __launch_bounds__(MAXT) void tiled_kernel(const TiledParams p) {
+    extern __shared__ float tile[];   // [chunk][R+2][64]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int FW = blockDim.x >> 6;
+
+    // Consecutive workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous range of logical ids so
+    // that the filter groups of one slot, which read the same activations, share one L2.
+    const int per_xcd = gridDim.x >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= p.nblocks) return;
+    const int slot = logical / p.NG;
+    const int grp = logical - slot * p.NG;
+
+    // lane -> (segment, column)
+    const int s_local = lane / p.LW;
+    const int t = lane - s_local * p.LW;
+    const int gseg = slot * p.S + s_local;
+    const bool active = (s_local < p.S) && (gseg < p.NSEG);
+    const int segs_per_img = p.NCS * p.NRB;
+    const int n0 = (slot * p.S) / segs_per_img;   // image of the slot's first segment (uniform)
+    const int gs = active ? gseg : slot * p.S;
+    const int n = gs / segs_per_img;
+    const int rem = gs - n * segs_per_img;
+    const int rb = rem / p.NCS;
+    const int cs = rem - rb * p.NCS;
+    const int ox = cs * p.OWS + t - 1;
+    const int ix = ox + 1 - p.pad;
+    const int r0 = rb * R;
+
+    unsigned voff[R + 2];
+#pragma unroll
+    for (int i = 0; i < R + 2; ++i) {
+        const int iy = r0 + i - p.pad;
+        const bool ok = active && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W;
+        voff[i] = ok ? (unsigned)(n - n0) * p.img_bytes + (unsigned)(iy * p.W + ix) * (unsigned)sizeof(T)
+                     : kInvalidOffset;
+    }
+    const unsigned long long base_off = (unsigned long long)n0 * p.img_bytes;
+    const unsigned long long left = p.x_bytes - base_off;
+    const __amdgpu_buffer_rsrc_t rsrc =
+        make_rsrc(static_cast<const char*>(p.x) + base_off, (uint32_t)(left < 0x7FFFFFFFull ? left : 0x7FFFFFFFull));
+
+    float acc[NF][3][R];
+#pragma unroll
+    for (int a = 0; a < NF; ++a)
+#pragma unroll
+        for (int b = 0; b < 3; ++b)
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[a][b][r] = 0.f;
+
+    const float* tile_lane = tile + lane;
+    const int pos_base = grp * (FW * NF) + wave;   // wave w takes positions pos_base + a*FW in the sorted filter order
+
+    for (int k = 0; k < p.nch; ++k) {
+        const int c0 = k * kChunk;
+        const int ncc = min(kChunk, p.C - c0);
+        // ---- stage chunk k: each wave copies whole channels, all R+2 patch rows of its lanes
+        for (int cc = wave; cc < ncc; cc += FW) {
+            const unsigned soff = (unsigned)(c0 + cc) * p.plane_bytes;
+            float v[R + 2];
+#pragma unroll
+            for (int i = 0; i < R + 2; ++i) v[i] = buffer_load_f32<T>(rsrc, voff[i], soff);
+#pragma unroll
+            for (int i = 0; i < R + 2; ++i) tile[(cc * (R + 2) + i) * 64 + lane] = v[i];
+        }
+        __syncthreads();
+
+        // ---- multiply-accumulate the kept kernels of this chunk
+        if constexpr (NF > 0) accumulate_filter<R>(acc[0], p, tile_lane, pos_base + 0 * FW, k);
+        if constexpr (NF > 1) accumulate_filter<R>(acc[1], p, tile_lane, pos_base + 1 * FW, k);
+        if constexpr (NF > 2) accumulate_filter<R>(acc[2], p, tile_lane, pos_base + 2 * FW, k);
+        if constexpr (NF > 3) accumulate_filter<R>(acc[3], p, tile_lane, pos_base + 3 * FW, k);
+        static_assert(NF <= 4, "at most four filters per wave");
+        __syncthreads();
+    }
+
+    // ---- epilogue: add the three accumulator sets across neighbouring lanes, bias, ReLU, store
+    T* __restrict__ y = static_cast<T*>(p.y);
+    const bool col_ok = active && t >= 1 && t <= p.OWS && ox < p.Wo;
+#pragma unroll
+    for (int a = 0; a < NF; ++a) {
+        const int pos = pos_base + a * FW;
+        if (pos >= p.F) continue;   // uniform per wave
+        const unsigned f = p.forder[pos];
+        const float b = p.bias ? p.bias[f] : 0.f;
+        const size_t ybase = (((size_t)n * p.F + f) * p.Ho) * (size_t)p.Wo;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float from_left = __shfl_up(acc[a][0][r], 1, 64);     // lane t-1 holds column ix-1: its kx=0 sum
+            const float from_right = __shfl_down(acc[a][2][r], 1, 64);  // lane t+1 holds column ix+1: its kx=2 sum
+            float v = acc[a][1][r] + from_left + from_right + b;
+            if (p.relu) v = fmaxf(v, 0.f);
+            const int oy = r0 + r;
+            if (col_ok && oy < p.Ho) y[ybase + (size_t)oy * p.Wo + ox] = from_f32<T>(v);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// generic kernel: any stride / pad; one thread per output, one filter per workgroup row
+// ---------------------------------------------------------------------------------------------------------------
+
+template <typename T>
+__global__ __launch_bounds__(256) void generic_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                      const DevEntry* __restrict__ ent,
+                                                      const uint32_t* __restrict__ eptr,
+                                                      const uint32_t* __restrict__ forder,
+                                                      const float* __restrict__ bias, int C, int F, int H, int W, int Ho,
+                                                      int Wo, int stride, int pad, int nch, int relu) {
+    const int pos = blockIdx.y, n = blockIdx.z;
+    const int pix = blockIdx.x * 256 + threadIdx.x;
+    const bool ok = pix < Ho * Wo;
+    const int oy = ok ? pix / Wo : 0, ox = ok ? pix - (pix / Wo) * Wo : 0;
+    const unsigned f = forder[pos];
+    const unsigned e0 = eptr[pos * nch], e1 = eptr[(pos + 1) * nch];
+    const size_t plane = (size_t)H * W;
+    const T* xn = x + (size_t)n * C * plane;
+    float acc = 0.f;
+    for (unsigned e = e0; e < e1; ++e) {
+        const EntryRegs d = load_entry(ent, e);
+        const unsigned c = ent[e].c;
+        const T* xc = xn + (size_t)c * plane;
+        int q = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            if ((d.mask9 >> t) & 1u) {
+                const int iy = oy * stride + t / 3 - pad, ix = ox * stride + t % 3 - pad;
+                const float wv = q == 0 ? d.w[0] : q == 1 ? d.w[1] : q == 2 ? d.w[2] : d.w[3];
+                if (ok && iy >= 0 && iy < H && ix >= 0 && ix < W) acc = fmaf(wv, to_f32<T>(xc[(size_t)iy * W + ix]), acc);
+                ++q;
+            }
+        }
+    }
+    if (ok) {
+        float v = acc + (bias ? bias[f] : 0.f);
+        if (relu) v = fmaxf(v, 0.f);
+        y[(((size_t)n * F + f) * Ho + oy) * (size_t)Wo + ox] = from_f32<T>(v);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// dense 3x3 baseline: one thread per output, one filter per workgroup row, all nine taps of all channels
+// ---------------------------------------------------------------------------------------------------------------
+
+template <typename T>
+__global__ __launch_bounds__(256) void dense_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                    const T* __restrict__ w, const float* __restrict__ bias, int C,
+                                                    int F, int H, int W, int Ho, int Wo, int stride, int pad, int relu) {
+    const int f = blockIdx.y, n = blockIdx.z;
+    const int pix = blockIdx.x * 256 + threadIdx.x;
+    const bool ok = pix < Ho * Wo;
+    const int oy = ok ? pix / Wo : 0, ox = ok ? pix - (pix / Wo) * Wo : 0;
+    const size_t plane = (size_t)H * W;
+    const T* xn = x + (size_t)n * C * plane;
+    const T* wf = w + (size_t)f * C * 9;
+    float acc = 0.f;
+    for (int c = 0; c < C; ++c) {
+        const T* xc = xn + (size_t)c * plane;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int iy = oy * stride + t / 3 - pad, ix = ox * stride + t % 3 - pad;
+            const float wv = to_f32<T>(wf[c * 9 + t]);
+            if (ok && iy >= 0 && iy < H && ix >= 0 && ix < W) acc = fmaf(wv, to_f32<T>(xc[(size_t)iy * W + ix]), acc);
+        }
+    }
+    if (ok) {
+        float v = acc + (bias ? bias[f] : 0.f);
+        if (relu) v = fmaxf(v, 0.f);
+        y[(((size_t)n * F + f) * Ho + oy) * (size_t)Wo + ox] = from_f32<T>(v);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T* __restrict__ y, long long planes,
+                                                      int H, int W) {
+    const int Ho = H / 2, Wo = W / 2;
+    const long long total = planes * Ho * Wo;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const int ox = (int)(i % Wo);
+        const long long r = i / Wo;
+        const int oy = (int)(r % Ho);
+        const long long pl = r / Ho;
+        const T* xp = x + (pl * H + 2 * oy) * (long long)W + 2 * ox;
+        const float a = to_f32<T>(xp[0]), b = to_f32<T>(xp[1]), c = to_f32<T>(xp[W]), d = to_f32<T>(xp[W + 1]);
+        y[i] = from_f32<T>(fmaxf(fmaxf(a, b), fmaxf(c, d)));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// launch selection
+// ---------------------------------------------------------------------------------------------------------------
+
+// Dynamic LDS above 64 KiB has to be allowed per kernel function.  The attribute is set on every launch that needs
+// it: it is a cheap host-side call and keeps the library free of global mutable state.
+static hipError_t allow_big_lds(const void* fn, size_t lds) {
+    if (lds <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+}
+
+template <int R, int NF, typename T>
+static int launch_tiled_rn(const TiledParams& p, int waves, int slots, hipStream_t stream) {
+    const int nblocks = p.nblocks;
+    const int grid = (nblocks + 7) / 8 * 8;
+    const size_t lds = (size_t)std::min(kChunk, p.C) * (R + 2) * 64 * sizeof(float);
+    (void)slots;
+    if (waves <= 8) {
+        auto kern = tiled_kernel<R, NF, 512, T>;
+        PCONV_HIP(allow_big_lds((const void*)kern, lds));
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), lds, stream, p);
+    } else {
+        auto kern = tiled_kernel<R, NF, 1024, T>;
+        PCONV_HIP(allow_big_lds((const void*)kern, lds));
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), lds, stream, p);
+    }
+    PCONV_HIP(hipGetLastError());
+    return PCONV_OK;
+}
+
+template <typename T>
+static int launch_tiled(TiledParams& p, int R, int NF, int waves, hipStream_t stream) {
+    // tile geometry
+    const int Wo = p.Wo, Ho = p.Ho;
+    const int ncs = (Wo + 61) / 62;
+    p.OWS = (Wo + ncs - 1) / ncs;
+    p.NCS = (Wo + p.OWS - 1) / p.OWS;
+    p.LW = p.OWS + 2;
+    p.S = 64 / p.LW;
+    p.NRB = (Ho + R - 1) / R;
+    const long long nseg = (long long)p.N * p.NRB * p.NCS;
+    if (nseg > 0x7FFFFFFF) return PCONV_ESHAPE;
+    p.NSEG = (int)nseg;
+    const int slots = (int)((nseg + p.S - 1) / p.S);
+    p.NG = (p.F + waves * NF - 1) / (waves * NF);
+    const long long nb = (long long)slots * p.NG;
+    if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
+    p.nblocks = (int)nb;
+#define PCONV_CASE(RR, FF) \
+    if (R == RR && NF == FF) return launch_tiled_rn<RR, FF, T>(p, waves, slots, stream);
+    PCONV_CASE(7, 1)
+    PCONV_CASE(7, 2)
+    PCONV_CASE(4, 1)
+    PCONV_CASE(4, 2)
+    PCONV_CASE(4, 4)
+#undef PCONV_CASE
+    return PCONV_EUNSUPPORTED;
+}
+
+static bool tiled_applicable(int N, int C, int H, int W, int stride, size_t esize) {
+    if (stride != 1) return false;
+    // 32-bit byte offsets inside the buffer descriptor: one image, times the few images one slot can span
+    const unsigned long long img = (unsigned long long)C * H * W * esize;
+    const int lw = std::min(W, 62) + 2;
+    const int s = std::max(1, 64 / lw);
+    (void)N;
+    return img * (unsigned long long)(s + 1) < 0x7FFFFFFFull;
+}
+
+}  // namespace pconv
+
+// ---------------------------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------------------------
+
+using namespace pconv;
+
+extern "C" const char* pconv_last_hip_error(void) { return g_hip_error; }
+
+static int check_conv_args(const void* x, const void* y, int N, int C, int F, int H, int W, int stride, int pad,
+                           unsigned flags, int* Ho, int* Wo) {
+    if (!x || !y) return PCONV_EINVAL;
+    if (flags & ~(unsigned)PCONV_FLAG_RELU) return PCONV_EINVAL;
+    if (stride != 1 && stride != 2) return PCONV_EUNSUPPORTED;
+    if (pad != 0 && pad != 1) return PCONV_EUNSUPPORTED;
+    if (N < 0 || C <= 0 || F <= 0 || H <= 0 || W <= 0) return PCONV_ESHAPE;
+    if (H + 2 * pad < 3 || W + 2 * pad < 3) return PCONV_ESHAPE;
+    *Ho = (H + 2 * pad - 3) / stride + 1;
+    *Wo = (W + 2 * pad - 3) / stride + 1;
+    if ((long long)*Ho * *Wo > 0x7FFFFFFF || N > 65535 || F > 65535) return PCONV_ESHAPE;
+    if ((unsigned long long)N * C * H * W >= (1ull << 40) || (unsigned long long)N * F * *Ho * *Wo >= (1ull << 40))
+        return PCONV_ESHAPE;
+    return PCONV_OK;
+}
+
+extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H,
+                                   int W, int stride, int pad, unsigned flags, void* stream,
+                                   const pconv_tuning* tuning) {
+    if (!wp) return PCONV_EINVAL;
+    int Ho = 0, Wo = 0;
+    if (int rc = check_conv_args(x, y, N, wp->C, wp->F, H, W, stride, pad, flags, &Ho, &Wo)) return rc;
+    if (!wp->d_ent) return PCONV_ESTATE;
+    int dev = -1;
+    PCONV_HIP(hipGetDevice(&dev));
+    if (dev != wp->device) return PCONV_ESTATE;
+    if (N == 0) return PCONV_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t esize = wp->dtype == PCONV_F16 ? 2 : 4;
+    const int relu = (flags & PCONV_FLAG_RELU) ? 1 : 0;
+
+    int kernel = tuning ? tuning->kernel : PCONV_KERNEL_AUTO;
+    int R = tuning ? tuning->rows : 0, NF = tuning ? tuning->filters_per_wave : 0, waves = tuning ? tuning->waves : 0;
+    const bool can_tile = tiled_applicable(N, wp->C, H, W, stride, esize);
+    if (kernel == PCONV_KERNEL_AUTO) kernel = can_tile ? PCONV_KERNEL_TILED : PCONV_KERNEL_GENERIC;
+    if (kernel == PCONV_KERNEL_TILED && !can_tile) return PCONV_EUNSUPPORTED;
+
+    if (kernel == PCONV_KERNEL_TILED) {
+        if (R == 0) R = (Ho % 7 == 0 || Ho > 16) ? 7 : 4;
+        if (waves == 0) waves = 8;
+        if (NF == 0) NF = 1;
+        if (waves < 1 || waves > 16) return PCONV_EUNSUPPORTED;
+        TiledParams p{};
+        p.x = x;
+        p.y = y;
+        p.ent = wp->d_ent;
+        p.eptr = wp->d_eptr;
+        p.forder = wp->d_forder;
+        p.bias = bias;
+        p.N = N;
+        p.C = wp->C;
+        p.F = wp->F;
+        p.H = H;
+        p.W = W;
+        p.Ho = Ho;
+        p.Wo = Wo;
+        p.pad = pad;
+        p.relu = relu;
+        p.nch = wp->n_chunks;
+        p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
+        p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
+        p.plane_bytes = (unsigned)((size_t)H * W * esize);
+        return wp->dtype == PCONV_F16 ? launch_tiled<__half>(p, R, NF, waves, st)
+                                      : launch_tiled<float>(p, R, NF, waves, st);
+    }
+    if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
+    const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);
+    if (wp->dtype == PCONV_F16)
+        hipLaunchKernelGGL(generic_kernel<__half>, grid, dim3(256), 0, st, (const __half*)x, (__half*)y, wp->d_ent,
+                           wp->d_eptr, wp->d_forder, bias, wp->C, wp->F, H, W, Ho, Wo, stride, pad, wp->n_chunks, relu);
+    else
+        hipLaunchKernelGGL(generic_kernel<float>, grid, dim3(256), 0, st, (const float*)x, (float*)y, wp->d_ent,
+                           wp->d_eptr, wp->d_forder, bias, wp->C, wp->F, H, W, Ho, Wo, stride, pad, wp->n_chunks, relu);
+    PCONV_HIP(hipGetLastError());
+    return PCONV_OK;
+}
+
+extern "C" int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
+                             int stride, int pad, unsigned flags, void* stream) {
+    return pconv_conv3x3_tuned(x, y, wp, bias, N, H, W, stride, pad, flags, stream, nullptr);
+}
+
+extern "C" int pconv_dense_conv3x3(const void* x, void* y, const void* w, const float* bias, int dtype, int N, int C,
+                                   int F, int H, int W, int stride, int pad, unsigned flags, void* stream) {
+    if (!w) return PCONV_EINVAL;
+    if (dtype != PCONV_F32 && dtype != PCONV_F16) return PCONV_EINVAL;
+    int Ho = 0, Wo = 0;
+    if (int rc = check_conv_args(x, y, N, C, F, H, W, stride, pad, flags, &Ho, &Wo)) return rc;
+    if (N == 0) return PCONV_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int relu = (flags & PCONV_FLAG_RELU) ? 1 : 0;
+    const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)F, (unsigned)N);
+    if (dtype == PCONV_F16)
+        hipLaunchKernelGGL(dense_kernel<__half>, grid, dim3(256), 0, st, (const __half*)x, (__half*)y, (const __half*)w,
+                           bias, C, F, H, W, Ho, Wo, stride, pad, relu);
+    else
+        hipLaunchKernelGGL(dense_kernel<float>, grid, dim3(256), 0, st, (const float*)x, (float*)y, (const float*)w,
+                           bias, C, F, H, W, Ho, Wo, stride, pad, relu);
+    PCONV_HIP(hipGetLastError());
+    return PCONV_OK;
+}
+
+extern "C" int pconv_maxpool2x2(const void* x, void* y, int dtype, int N, int C, int H, int W, void* stream) {
+    if (!x || !y) return PCONV_EINVAL;
+    if (dtype != PCONV_F32 && dtype != PCONV_F16) return PCONV_EINVAL;
+    if (N < 0 || C <= 0 || H < 2 || W < 2) return PCONV_ESHAPE;
+    if (N == 0) return PCONV_OK;
+    const long long planes = (long long)N * C;
+    const long long total = planes * (H / 2) * (W / 2);
+    const unsigned grid = (unsigned)std::min<long long>((total + 255) / 256, 1 << 20);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == PCONV_F16)
+        hipLaunchKernelGGL(maxpool_kernel<__half>, dim3(grid), dim3(256), 0, st, (const __half*)x, (__half*)y, planes, H, W);
+    else
+        hipLaunchKernelGGL(maxpool_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)x, (float*)y, planes, H, W);
+    PCONV_HIP(hipGetLastError());
+    return PCONV_OK;
+}

@@ -1,0 +1,56 @@
+// Shared between the host packer and the device code of libpconv.  Not part of the public ABI.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "pconv.h"
+
+namespace pconv {
+
+// Channels are processed in chunks of this many; the kernels stage one chunk of activations in LDS at a time and
+// the packed entries of a filter are bucketed by chunk.
+constexpr int kChunk = 32;
+
+// One kept kernel in the device layout (32 bytes so that one scalar load of eight dwords fetches it).
+struct DevEntry {
+    float w[4];       // the four kept weights, taps ascending, widened to fp32 (exact for fp16 storage)
+    uint32_t cc;      // input channel inside its chunk: c % kChunk
+    uint32_t mask9;   // the pattern mask itself (bit t = 3*ky + kx)
+    uint32_t c;       // input channel
+    uint32_t unused;
+};
+static_assert(sizeof(DevEntry) == 32, "DevEntry must be 32 bytes");
+
+}  // namespace pconv
+
+struct pconv_packed {
+    int F = 0, C = 0, K = 0, dtype = 0;
+    size_t n_kept = 0;
+    std::vector<uint16_t> lib;
+
+    // canonical form (what pconv_packed_export returns)
+    std::vector<uint32_t> filter_order;   // [F]
+    std::vector<uint32_t> grp_ptr;        // [F*K+1]
+    std::vector<uint16_t> cin;            // [n_kept]
+    std::vector<unsigned char> w4;        // [n_kept*4] in the storage dtype, raw bytes
+
+    // device layout, host copy: entries ordered by (position i in filter_order, channel chunk, pattern, channel)
+    int n_chunks = 0;
+    std::vector<pconv::DevEntry> ent;     // [n_kept]
+    std::vector<uint32_t> eptr;           // [F*n_chunks + 1]: entries of (i, chunk) are eptr[i*n_chunks+chunk] ..
+
+    // device copies (null when packed host-only)
+    int device = -1;
+    pconv::DevEntry* d_ent = nullptr;
+    uint32_t* d_eptr = nullptr;
+    uint32_t* d_forder = nullptr;
+};
+
+namespace pconv {
+// implemented in pconv_device.hip
+int upload_packed(pconv_packed* p);
+void release_device(pconv_packed* p);
+void set_hip_error(const char* what, int hip_code);
+}  // namespace pconv

@@ -1,0 +1,281 @@
+"""GPU parity: libpconv (through its C ABI) against the CPU oracle, element by element, on the same seeded bytes.
+
+Tolerances (max relative error, see gpu_util.rel_err): 1e-4 for fp32, 2e-3 for fp16 storage with fp32 accumulation.
+Pattern assignment, connectivity selection and packing are compared bit for bit (gpu_util.sparsity and
+test_host_logic).  Every test prints the case it is about to run, flushed, before touching the GPU.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2001_07710_amd as pc
+from workloads import layers as L
+from workloads import rng
+
+from gpu_util import TOL, GpuLayer, rel_err
+
+pytestmark = pytest.mark.gpu
+
+T, G = pc.KERNEL_TILED, pc.KERNEL_GENERIC
+TILED_TUNINGS = [dict(kernel=T, rows=r, filters_per_wave=nf, waves=w)
+                 for r, nf, w in [(7, 1, 8), (7, 2, 8), (7, 1, 16), (7, 2, 3), (4, 1, 8), (4, 2, 8), (4, 4, 4), (4, 1, 1),
+                                  (4, 4, 16)]]
+ALL_TUNINGS = [dict(kernel=G)] + TILED_TUNINGS + [dict()]
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    pc.ensure_built()
+
+
+def check(layer: GpuLayer, x, tunings, relu=None, tol=None):
+    ref = layer.oracle(x, relu)
+    tol = TOL[layer.spec.dtype] if tol is None else tol
+    for t in tunings:
+        say(layer.spec.name, layer.spec.dtype, "x", x.shape, "tuning", t)
+        got = layer.run(x, relu, **t)
+        assert got.shape == ref.shape
+        err = rel_err(got, ref)
+        assert err <= tol, (layer.spec, t, err)
+    return ref
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# config 0: the small case, every kernel variant
+# ------------------------------------------------------------------------------------------------------------------
+
+def test_config0_every_kernel_variant():
+    spec = L.config0()
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    assert abs(layer.mask.mean() - 0.5) < 0.1 and set(np.unique(layer.pid)) == {0, 1, 2, 3}
+    check(layer, x, ALL_TUNINGS)
+    check(layer, x, [dict(), dict(kernel=G)], relu=True)
+    layer.free()
+
+
+def test_every_one_of_the_126_patterns():
+    spec = L.LayerSpec(cfg=9, idx=0, name="all126", N=2, C=126, F=20, H=9, W=12, K=126, keep=0.6, lib_kind="all126",
+                       assign="uniform", conn="bernoulli")
+    layer = GpuLayer(spec)
+    assert len(np.unique(layer.pid[layer.mask != 0])) == 126
+    check(layer, L.gen_activations(spec), [dict(), dict(kernel=G), TILED_TUNINGS[1], TILED_TUNINGS[6]])
+    layer.free()
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# ragged shapes, both pads, both strides, both storage types, several images
+# ------------------------------------------------------------------------------------------------------------------
+
+RAGGED = [  # N, C, F, H, W, stride, pad
+    (1, 5, 3, 1, 1, 1, 1), (2, 33, 17, 9, 11, 1, 1), (3, 40, 20, 13, 70, 1, 1), (1, 7, 9, 5, 130, 1, 0),
+    (2, 64, 10, 8, 8, 1, 0), (2, 16, 8, 3, 3, 1, 0), (2, 31, 13, 15, 17, 2, 1), (1, 8, 8, 8, 8, 2, 0),
+    (5, 12, 6, 7, 7, 1, 1), (2, 3, 64, 30, 62, 1, 1), (1, 96, 130, 6, 63, 1, 1), (2, 20, 5, 16, 9, 2, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("case", RAGGED, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}s{c[5]}p{c[6]}" for c in RAGGED])
+def test_ragged_shapes(case, dtype):
+    N, C, F, H, W, stride, pad = case
+    spec = L.LayerSpec(cfg=10, idx=RAGGED.index(case), name="ragged", N=N, C=C, F=F, H=H, W=W, stride=stride, pad=pad,
+                       dtype=dtype, K=8, keep=0.4)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    tunings = [dict(), dict(kernel=G)]
+    if stride == 1:
+        tunings += [TILED_TUNINGS[0], TILED_TUNINGS[3], TILED_TUNINGS[6], TILED_TUNINGS[7]]
+    check(layer, x, tunings)
+    check(layer, x, [dict()], relu=True)
+    layer.free()
+
+
+def test_no_bias_negative_inputs_and_empty_filters():
+    spec = L.LayerSpec(cfg=11, idx=0, name="nobias", N=2, C=48, F=24, H=14, W=14, K=8, keep=0.1)
+    w = L.gen_weights(spec)
+    layer = GpuLayer(spec, w=w, use_bias=False)
+    assert (layer.mask.sum(axis=1) == 0).any() or layer.mask.sum() < 0.11 * layer.mask.size
+    x = (rng.normal(77, 2 * 48 * 14 * 14).astype(np.float32) * 3).reshape(2, 48, 14, 14)   # signed, not rectified
+    check(layer, x, [dict(), dict(kernel=G), TILED_TUNINGS[1]])
+    layer.free()
+    # a layer with nothing kept computes the bias alone
+    spec0 = L.shrink(spec, keep=0.0, idx=1)
+    layer0 = GpuLayer(spec0)
+    assert layer0.mask.sum() == 0
+    y = layer0.run(x)
+    assert np.array_equal(y, np.broadcast_to(layer0.bias[None, :, None, None], y.shape))
+    layer0.free()
+
+
+def test_batch_zero_is_a_no_op_and_runs_are_deterministic():
+    spec = L.shrink(L.config1(), C=64, F=32, H=28, W=28)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    a = layer.run(x)
+    b = layer.run(x)
+    assert a.tobytes() == b.tobytes()
+    import torch
+    dummy = torch.zeros(4, device="cuda")
+    pc.conv3x3(dummy, dummy, layer.packed, None, 0, 28, 28)
+    layer.free()
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# config 1: VGG-16 conv3_x-shaped layer at full size (the benchmark workload)
+# ------------------------------------------------------------------------------------------------------------------
+
+def test_config1_full_size():
+    spec = L.config1()
+    layer = GpuLayer(spec)
+    assert layer.packed.n_kept == 18350
+    x = L.gen_activations(spec)
+    ref = check(layer, x, [dict(), dict(kernel=G)] + TILED_TUNINGS[:7])
+    # invariant on the GPU side as well: a removed kernel contributes nothing
+    f, c = np.argwhere(layer.mask == 0)[0]
+    w2 = layer.w.copy()
+    w2[f, c] += 100.0
+    layer2 = GpuLayer(spec, w=w2)
+    if np.array_equal(layer2.mask, layer.mask) and np.array_equal(layer2.pid[layer.mask != 0], layer.pid[layer.mask != 0]):
+        assert layer2.run(x).tobytes() == layer.run(x).tobytes()
+    layer2.free()
+    layer.free()
+    assert np.isfinite(ref).all()
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# config 2: the 13 VGG-16 layers in sequence, ReLU fused, 2x2 max-pool between stages
+# ------------------------------------------------------------------------------------------------------------------
+
+def test_config2_vgg16_chain():
+    import torch
+    specs = L.config2()
+    layers = [GpuLayer(s) for s in specs]
+    assert [l.packed.n_kept for l in layers] == [192, 1434, 2867, 5734, 9175, 18350, 18350, 26214] + [52429] * 5
+    x = L.gen_activations(specs[0])
+    # oracle chain; every layer of the GPU path is also checked on the oracle's own input for that layer
+    xo = x
+    for s, layer in zip(specs, layers):
+        say("chain layer", s.name, xo.shape)
+        yo = layer.oracle(xo).astype(np.float32)
+        got = layer.run(xo)
+        assert rel_err(got, yo) <= TOL["f32"], s.name
+        xo = oracle.maxpool2x2(yo) if s.pool_after else yo
+    # the GPU chain end to end (its own activations all the way): rounding differences compound over 13 layers, so
+    # the end result is held to 13x the single-layer tolerance
+    st = torch.cuda.current_stream().cuda_stream
+    cur = torch.from_numpy(x).cuda()
+    for s, layer in zip(specs, layers):
+        y = torch.empty((1, s.F, s.Ho, s.Wo), dtype=torch.float32, device="cuda")
+        pc.conv3x3(cur, y, layer.packed, layer.d_bias, 1, s.H, s.W, 1, 1, pc.FLAG_RELU, st)
+        if s.pool_after:
+            z = torch.empty((1, s.F, s.Ho // 2, s.Wo // 2), dtype=torch.float32, device="cuda")
+            pc.maxpool2x2(y, z, pc.F32, 1, s.F, s.Ho, s.Wo, st)
+            y = z
+        cur = y
+    torch.cuda.synchronize()
+    assert tuple(cur.shape) == (1, 512, 7, 7) and xo.shape == (1, 512, 7, 7)
+    assert rel_err(cur.cpu().numpy(), xo) <= 13 * TOL["f32"]
+    for l in layers:
+        l.free()
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# config 3: ResNet-50 bottleneck 3x3 shapes, fp16 storage, batch 1 and batch 32
+# ------------------------------------------------------------------------------------------------------------------
+
+def sampled_coords(seed, N, F, Ho, Wo, npts=65536):
+    r = rng.raw_u64(seed, 4 * npts).reshape(npts, 4)
+    return np.stack([r[:, 0] % N, r[:, 1] % F, r[:, 2] % Ho, r[:, 3] % Wo], axis=1).astype(np.int32)
+
+
+def check_batched(layer: GpuLayer, x, tunings=(dict(),)):
+    """Whole first and last image against the oracle, plus 65,536 sampled outputs over the batch."""
+    s = layer.spec
+    N = x.shape[0]
+    coords = sampled_coords(1000 + s.idx, N, s.F, s.Ho, s.Wo)
+    ref_pts = layer.oracle_at(x, coords)
+    ref_first, ref_last = layer.oracle(x[:1]), layer.oracle(x[N - 1:])
+    for t in tunings:
+        say(s.name, s.dtype, "batch", N, "tuning", t)
+        got = layer.run(x, **t)
+        tol = TOL[s.dtype]
+        assert rel_err(got[0], ref_first[0]) <= tol and rel_err(got[N - 1], ref_last[0]) <= tol
+        pts = got[coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]]
+        rms = float(np.sqrt(np.mean(ref_first ** 2)))
+        assert np.max(np.abs(pts.astype(np.float64) - ref_pts) / np.maximum(np.abs(ref_pts), rms)) <= tol
+
+
+@pytest.mark.parametrize("N", [1, 32])
+def test_config3_resnet50_shapes(N):
+    for spec in L.config3(N):
+        layer = GpuLayer(spec)
+        x = L.gen_activations(spec)
+        if N == 1:
+            tun = [dict(), dict(kernel=G)] + ([TILED_TUNINGS[1], TILED_TUNINGS[5]] if spec.stride == 1 else [])
+            check(layer, x, tun)
+        else:
+            check_batched(layer, x)
+        layer.free()
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# config 4: VGG-16 shapes at batch 64, fp16 storage; library sizes 4/8/12, keep fractions 0.5/0.28/0.15
+# ------------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("K,keep", [(4, 0.5), (4, 0.15), (8, 0.28), (12, 0.5), (12, 0.15)])
+def test_config4_sweep_points_small_batch(K, keep):
+    for spec in L.config4(K, keep, N=2):
+        if spec.name not in ("conv1_1", "conv1_2", "conv3_2", "conv5_1"):
+            continue
+        layer = GpuLayer(spec)
+        check(layer, L.gen_activations(spec), [dict()])
+        layer.free()
+
+
+@pytest.mark.parametrize("name", ["conv1_1", "conv1_2", "conv4_2", "conv5_1"])
+def test_config4_full_batch(name):
+    spec = [s for s in L.config4(8, 0.28, N=64) if s.name == name][0]
+    layer = GpuLayer(spec)
+    say("generating", name, "batch 64")
+    x = L.gen_activations(spec)
+    check_batched(layer, x)
+    layer.free()
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# the comparison kernels: dense 3x3 baseline and max-pool
+# ------------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1), (1, 0)])
+def test_dense_baseline(dtype, stride, pad):
+    import torch
+    spec = L.LayerSpec(cfg=12, idx=stride * 2 + pad, name="dense", N=2, C=24, F=10, H=17, W=19, stride=stride, pad=pad,
+                       dtype=dtype)
+    w, x, b = L.gen_weights(spec), L.gen_activations(spec), L.gen_bias(spec)
+    say("dense", dtype, stride, pad)
+    tdt = torch.float16 if dtype == "f16" else torch.float32
+    dx, dw, db = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
+    dy = torch.empty((2, 10, spec.Ho, spec.Wo), dtype=tdt, device="cuda")
+    pc.dense_conv3x3(dx, dy, dw, db, pc.F16 if dtype == "f16" else pc.F32, 2, 24, 10, 17, 19, stride, pad, pc.FLAG_RELU,
+                     torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ref = oracle.conv3x3(x, w, b, stride, pad, relu=True)
+    assert rel_err(dy.cpu().numpy(), ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_maxpool(dtype):
+    import torch
+    x = L.gen_activations(L.LayerSpec(cfg=13, idx=0, name="pool", N=3, C=5, F=1, H=14, W=10, dtype=dtype))
+    x = x - x.dtype.type(0.3)
+    say("maxpool", dtype)
+    dx = torch.from_numpy(x).cuda()
+    dy = torch.empty((3, 5, 7, 5), dtype=dx.dtype, device="cuda")
+    pc.maxpool2x2(dx, dy, pc.F16 if dtype == "f16" else pc.F32, 3, 5, 14, 10, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(dy.cpu().numpy().astype(np.float32), oracle.maxpool2x2(x))

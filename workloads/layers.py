@@ -58,7 +58,7 @@ class LayerSpec:
     dtype: str = "f32"          # storage type of x, y, w: "f32" or "f16"; accumulation is always fp32 on the GPU
     K: int = 8
     keep: float = 1.0
-    lib_kind: str = "draw"      # "fixed4" (config 0) or "draw"
+    lib_kind: str = "draw"      # "fixed4" (config 0), "draw" (seeded nested draw) or "all126" (every mask; tests)
     assign: str = "argmax"      # "uniform" (config 0: seeded uniform ids) or "argmax" (retained-norm projection)
     conn: str = "topk"          # "bernoulli" (config 0) or "topk"
     relu: bool = False
@@ -79,6 +79,8 @@ class LayerSpec:
     def library(self) -> np.ndarray:
         if self.lib_kind == "fixed4":
             return np.asarray(FIXED4[: self.K], dtype=np.uint16)
+        if self.lib_kind == "all126":
+            return np.asarray(all_masks_4of9()[: self.K], dtype=np.uint16)
         return drawn_library(self.cfg, self.K)
 
     def n_keep_target(self) -> int:
