@@ -128,9 +128,11 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  * kernel.  A NULL `tuning`, or a field left 0, means "choose automatically" (what pconv_conv3x3 does).
  *   kernel            PCONV_KERNEL_TILED (stride 1 only: activations staged in LDS, weights in scalar registers)
  *                     or PCONV_KERNEL_GENERIC (any stride and pad, straight from global memory)
- *   rows              tiled: output rows held per lane, 4 or 7
- *   filters_per_wave  tiled: filters accumulated at once by one wave, 1, 2 (or 4 with rows = 4)
+ *   rows              tiled: output rows held per lane (7)
+ *   filters_per_wave  tiled: filters accumulated at once by one wave (1, 2 or 3)
  *   waves             tiled: waves per workgroup, 1..16
+ *   channels_per_wave tiled: channels each wave stages per chunk (1, 2 or 4); waves * channels_per_wave, the
+ *                     channels resident in LDS at a time, must be a multiple of 16
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
 enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2 };
@@ -139,6 +141,7 @@ typedef struct pconv_tuning {
     int rows;
     int filters_per_wave;
     int waves;
+    int channels_per_wave;
 } pconv_tuning;
 int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                         int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning);

@@ -21,6 +21,13 @@ HIPCC_FLAGS = [
 
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    # per-pattern code sections of the tiled kernel (generated source, not committed)
+    sys.path.insert(0, CSRC)
+    try:
+        import gen_pattern_leaves
+        gen_pattern_leaves.main(os.path.join(CSRC, "pattern_leaves.inc"))
+    finally:
+        sys.path.pop(0)
     cmd = [hipcc, *HIPCC_FLAGS, "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-o", LIB,
            *[os.path.join(CSRC, s) for s in SOURCES]]
     if verbose:

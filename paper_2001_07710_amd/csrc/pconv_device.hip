@@ -107,43 +107,32 @@ __device__ __forceinline__ float buffer_load_f32<__half>(__amdgpu_buffer_rsrc_t 
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// the 126 masks with four of nine bits, ascending, at compile time
-// ---------------------------------------------------------------------------------------------------------------
-
-struct MaskTable {
-    unsigned v[126];
-};
-constexpr MaskTable build_mask_table() {
-    MaskTable t{};
-    int n = 0;
-    for (unsigned m = 0; m < 512; ++m) {
-        int bits = 0;
-        for (int b = 0; b < 9; ++b) bits += (m >> b) & 1u;
-        if (bits == 4) t.v[n++] = m;
-    }
-    return t;
-}
-constexpr MaskTable kMasks = build_mask_table();
-
-// ---------------------------------------------------------------------------------------------------------------
 // tiled kernel (stride 1)
 //
-// Lane layout.  A wave owns S segments of LW lanes.  A segment is OWS consecutive output columns of R consecutive
-// output rows of one image, plus one halo lane on each side; lane t of a segment holds INPUT column
+// Lane layout.  A wave owns S segments of LW lanes.  A segment is OWS consecutive output columns of R = 7
+// consecutive output rows of one image, plus one halo lane on each side; lane t of a segment holds INPUT column
 // ix = os + t - pad and, in registers, the R+2 input rows that its R output rows read.  A tap (ky,kx) of a kernel
 // multiplies the lane's own column: acc[kx][r] += w * x[r + ky].  The three accumulator sets (one per kx) belong to
 // output columns ix+1, ix, ix-1 (+pad-1) and are added across neighbouring lanes once, after the last channel.
-// So the inner loop has no cross-lane traffic and no address arithmetic: 4*R multiply-adds per kept kernel, weights
-// from scalar registers.
+// So the inner loop has no cross-lane traffic: 4*R multiply-adds per kept kernel, weights from scalar registers.
 //
-// LDS layout.  tile[cc][i][lane]: channel-in-chunk, patch row i = r + ky, lane.  Every read and write of a wave is
-// 64 consecutive dwords.
+// LDS layout.  tile[cc][lane][PR]: channel-in-chunk, lane, patch row i = r + ky, with PR = R+2 rounded up to a
+// multiple of four (12) so that a lane fetches its patch with three 128-bit reads (twice the LDS rate of 32-bit
+// reads on this chip); a lane stride of 12 dwords spreads 16 lanes over 64 distinct banks.
 //
 // Work split.  A workgroup is one slot (the S segments) times FW*NF filters: wave w accumulates NF filters.  All
-// waves share the staged activations.  Entries of a filter are bucketed by channel chunk; inside a bucket they are
-// sorted by pattern, and the pattern selects one of 126 straight-line code sections through a scalar branch tree,
-// so a wave never diverges (the per-pattern generated code of section 6.2 of the paper, as compiled-in sections).
+// waves share the staged activations.  Channels are staged in chunks of CC = CPW*FW (each wave copies CPW whole
+// channels); the global loads of chunk k+1 are in flight, in registers, while chunk k is being multiplied.
+//
+// Per-pattern code.  The 4*R multiply-adds of a kept kernel are one of 126 straight-line sections (one per possible
+// pattern), generated ahead of time by gen_pattern_leaves.py and reached with ONE computed jump, so a wave never
+// diverges and never walks a branch tree (the per-pattern generated access code of section 6.2 of the paper).  A
+// scalar branch tree costs several hundred clocks per kernel on this chip, against 112 clocks of multiply-adds.
+// The sections are inline assembly; their accumulators live in fixed registers above the budget that the compiler
+// is given for this kernel (amdgpu_num_vgpr), see pattern_leaves.inc.
 // ---------------------------------------------------------------------------------------------------------------
+
+#include "pattern_leaves.inc"
 
 struct TiledParams {
     const void* x;
@@ -153,7 +142,7 @@ struct TiledParams {
     const uint32_t* forder;
     const float* bias;
     int N, C, F, H, W, Ho, Wo, pad, relu;
-    int nch;                 // channel chunks
+    int nbk;                 // channel buckets of the packed layout
     int LW, S, OWS, NCS, NRB, NSEG;
     int NG;                  // filter groups per slot
     int nblocks;             // NG * slots (the grid is padded to a multiple of 8)
@@ -162,94 +151,129 @@ struct TiledParams {
     unsigned plane_bytes;    // H*W*sizeof(T)
 };
 
-template <unsigned MASK, int R>
-__device__ __forceinline__ void apply_pattern(float (&acc)[3][R], const float (&xp)[R + 2], const float (&w)[4]) {
-    int q = 0;
-#pragma unroll
-    for (int t = 0; t < 9; ++t) {
-        if ((MASK >> t) & 1u) {
-            const int ky = t / 3, kx = t % 3;
-#pragma unroll
-            for (int r = 0; r < R; ++r) acc[kx][r] = fmaf(w[q], xp[r + ky], acc[kx][r]);
-            ++q;
-        }
-    }
-}
-
-template <int LO, int HI, int R>
-__device__ __forceinline__ void dispatch_pattern(unsigned m, float (&acc)[3][R], const float (&xp)[R + 2],
-                                                 const float (&w)[4]) {
-    if constexpr (HI - LO == 1) {
-        apply_pattern<kMasks.v[LO], R>(acc, xp, w);
-    } else {
-        constexpr int MID = (LO + HI) / 2;
-        if (m < kMasks.v[MID])
-            dispatch_pattern<LO, MID, R>(m, acc, xp, w);
-        else
-            dispatch_pattern<MID, HI, R>(m, acc, xp, w);
-    }
-}
+constexpr int kR = 7;                 // output rows per lane
+constexpr int kPR = 12;               // patch rows per lane in LDS (R + 2, padded to a multiple of four)
+constexpr int kChDwords = 64 * kPR;   // one channel of one slot in LDS
 
 struct EntryRegs {
-    float w[4];
-    unsigned cc, mask9;
+    unsigned w[4];   // bit patterns of the fp32 weights (kept as integers so that they stay in scalar registers)
+    unsigned c, mask9, code;
 };
 
-__device__ __forceinline__ EntryRegs load_entry(const DevEntry* __restrict__ ent, unsigned e) {
-    // e is wave-uniform: the compiler turns this into scalar loads
-    const uint4 a = *reinterpret_cast<const uint4*>(&ent[e].w[0]);
-    const uint2 b = *reinterpret_cast<const uint2*>(&ent[e].cc);
+// Packed weights and pointers never change while a kernel runs: reading them through the constant address space
+// makes every such load a scalar load (wave-uniform address, result in scalar registers).
+typedef unsigned u32x8 __attribute__((ext_vector_type(8)));
+typedef const u32x8 __attribute__((address_space(4)))* const_u32x8_ptr;
+typedef const unsigned __attribute__((address_space(4)))* const_u32_ptr;
+
+__device__ __forceinline__ unsigned scalar_load_u32(const uint32_t* p) {
+    return *(const_u32_ptr)(unsigned long long)p;
+}
+
+__device__ __forceinline__ EntryRegs load_entry(const DevEntry* ent, unsigned e) {
+    const u32x8 v = *(const_u32x8_ptr)(unsigned long long)(ent + e);
     EntryRegs r;
-    r.w[0] = __builtin_bit_cast(float, a.x);
-    r.w[1] = __builtin_bit_cast(float, a.y);
-    r.w[2] = __builtin_bit_cast(float, a.z);
-    r.w[3] = __builtin_bit_cast(float, a.w);
-    r.cc = b.x;
-    r.mask9 = b.y;
+    r.w[0] = v[0];
+    r.w[1] = v[1];
+    r.w[2] = v[2];
+    r.w[3] = v[3];
+    r.c = v[4];
+    r.mask9 = v[5];
+    r.code = v[6];
     return r;
 }
 
-template <int R>
-__device__ __forceinline__ void load_patch(float (&xp)[R + 2], const float* tile_lane, unsigned cc) {
-    const float* p = tile_lane + cc * ((R + 2) * 64);
+// The lane's patch of channel cc: three 128-bit LDS reads (rows 9..11 are padding).
+__device__ __forceinline__ void load_patch(float (&xp)[kPR], const float* tile_lane, unsigned cc) {
+    const float* base = tile_lane + cc * kChDwords;
 #pragma unroll
-    for (int i = 0; i < R + 2; ++i) xp[i] = p[i * 64];
-}
-
-// All kept kernels of the filter at position `pos` of the sorted filter order whose channel lies in chunk k.
-// Entry e+1 and its activations are fetched while entry e is being multiplied (two register sets, swapped by
-// unrolling the loop once).
-template <int R>
-__device__ __forceinline__ void accumulate_filter(float (&acc)[3][R], const TiledParams& p, const float* tile_lane,
-                                                  int pos, int k) {
-    if (pos >= p.F) return;
-    unsigned e = p.eptr[pos * p.nch + k];
-    const unsigned e1 = p.eptr[pos * p.nch + k + 1];
-    if (e >= e1) return;
-    EntryRegs ea = load_entry(p.ent, e);
-    float xa[R + 2], xb[R + 2];
-    load_patch<R>(xa, tile_lane, ea.cc);
-    while (true) {
-        const bool has_b = e + 1 < e1;
-        const EntryRegs eb = load_entry(p.ent, has_b ? e + 1 : e);
-        load_patch<R>(xb, tile_lane, eb.cc);
-        dispatch_pattern<0, 126, R>(ea.mask9, acc, xa, ea.w);
-        if (!has_b) break;
-        const bool has_a = e + 2 < e1;
-        ea = load_entry(p.ent, has_a ? e + 2 : e + 1);
-        load_patch<R>(xa, tile_lane, ea.cc);
-        dispatch_pattern<0, 126, R>(eb.mask9, acc, xb, eb.w);
-        if (!has_a) break;
-        e += 2;
+    for (int q = 0; q < kPR / 4; ++q) {
+        const float4 v = *reinterpret_cast<const float4*>(base + 4 * q);
+        xp[4 * q + 0] = v.x;
+        xp[4 * q + 1] = v.y;
+        xp[4 * q + 2] = v.z;
+        xp[4 * q + 3] = v.w;
     }
 }
 
-template <int R, int NF, int MAXT, typename T>
-__global__ __launch_bounds__(MAXT) void tiled_kernel(const TiledParams p) {
-    extern __shared__ float tile[];   // [chunk][R+2][64]
+// One kept kernel into the accumulators of filter slot SLOT: computed jump into the section of its pattern.
+template <int SLOT>
+__device__ __forceinline__ void pattern_fma(const EntryRegs& e, const float (&xp)[kPR]) {
+    const unsigned off = e.code * PCONV_LEAF_BYTES_R7 + PCONV_LEAF_ENTRY_OFFSET;   // wave-uniform
+#define PCONV_LEAF_OPERANDS                                                                                     \
+    [off] "s"(off), [w0] "s"(e.w[0]), [w1] "s"(e.w[1]), [w2] "s"(e.w[2]), [w3] "s"(e.w[3]), [x0] "v"(xp[0]),    \
+        [x1] "v"(xp[1]), [x2] "v"(xp[2]), [x3] "v"(xp[3]), [x4] "v"(xp[4]), [x5] "v"(xp[5]), [x6] "v"(xp[6]),   \
+        [x7] "v"(xp[7]), [x8] "v"(xp[8])
+    if constexpr (SLOT == 0)
+        asm volatile(PCONV_LEAVES_R7_S0 : : PCONV_LEAF_OPERANDS : "s60", "s61", "scc", PCONV_ACC_CLOBBERS_R7_S0);
+    else if constexpr (SLOT == 1)
+        asm volatile(PCONV_LEAVES_R7_S1 : : PCONV_LEAF_OPERANDS : "s60", "s61", "scc", PCONV_ACC_CLOBBERS_R7_S1);
+    else
+        asm volatile(PCONV_LEAVES_R7_S2 : : PCONV_LEAF_OPERANDS : "s60", "s61", "scc", PCONV_ACC_CLOBBERS_R7_S2);
+#undef PCONV_LEAF_OPERANDS
+}
+
+template <int SLOT>
+__device__ __forceinline__ void zero_acc() {
+    if constexpr (SLOT == 0) asm volatile(PCONV_ACC_ZERO_R7_S0 : : : PCONV_ACC_CLOBBERS_R7_S0);
+    else if constexpr (SLOT == 1) asm volatile(PCONV_ACC_ZERO_R7_S1 : : : PCONV_ACC_CLOBBERS_R7_S1);
+    else asm volatile(PCONV_ACC_ZERO_R7_S2 : : : PCONV_ACC_CLOBBERS_R7_S2);
+}
+
+template <int SLOT>
+__device__ __forceinline__ void read_acc(float (&a)[3][kR]) {
+#define PCONV_ACC_OUTPUTS                                                                                           \
+    "=v"(a[0][0]), "=v"(a[0][1]), "=v"(a[0][2]), "=v"(a[0][3]), "=v"(a[0][4]), "=v"(a[0][5]), "=v"(a[0][6]),        \
+        "=v"(a[1][0]), "=v"(a[1][1]), "=v"(a[1][2]), "=v"(a[1][3]), "=v"(a[1][4]), "=v"(a[1][5]), "=v"(a[1][6]),    \
+        "=v"(a[2][0]), "=v"(a[2][1]), "=v"(a[2][2]), "=v"(a[2][3]), "=v"(a[2][4]), "=v"(a[2][5]), "=v"(a[2][6])
+    if constexpr (SLOT == 0) asm volatile(PCONV_ACC_READ_R7_S0 : PCONV_ACC_OUTPUTS);
+    else if constexpr (SLOT == 1) asm volatile(PCONV_ACC_READ_R7_S1 : PCONV_ACC_OUTPUTS);
+    else asm volatile(PCONV_ACC_READ_R7_S2 : PCONV_ACC_OUTPUTS);
+#undef PCONV_ACC_OUTPUTS
+}
+
+// All kept kernels of the filter at position `pos` of the sorted filter order whose channel lies in buckets
+// [b0, b1).  Software pipeline over pairs of entries: the next pair is being fetched into scalar registers and the
+// activations of the next entry into a second set of vector registers while the current entry is multiplied.
+// Prefetches past the end re-read the last entry (always a valid address) and are dropped.
+template <int SLOT>
+__device__ __forceinline__ void accumulate_filter(const TiledParams& p, const float* tile_lane, int pos, int b0,
+                                                  int b1, int c0) {
+    if (pos >= p.F) return;
+    unsigned e = scalar_load_u32(p.eptr + pos * p.nbk + b0);
+    const unsigned e1 = scalar_load_u32(p.eptr + pos * p.nbk + b1);
+    if (e >= e1) return;
+    const unsigned last = e1 - 1;
+    EntryRegs ea = load_entry(p.ent, e);
+    EntryRegs eb = load_entry(p.ent, min(e + 1, last));
+    float xa[kPR], xb[kPR];
+    load_patch(xa, tile_lane, ea.c - c0);
+    while (e + 1 < e1) {
+        // Everything in flight here was issued at least one section ago.  Waiting for all of it now keeps the waits
+        // the compiler adds below from also covering the prefetches issued next (scalar loads return out of order,
+        // so any later wait on the LDS/scalar counter is a wait for everything outstanding).
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), other counters untouched
+        load_patch(xb, tile_lane, eb.c - c0);
+        const EntryRegs ec = load_entry(p.ent, min(e + 2, last));
+        const EntryRegs ed = load_entry(p.ent, min(e + 3, last));
+        pattern_fma<SLOT>(ea, xa);
+        load_patch(xa, tile_lane, ec.c - c0);
+        pattern_fma<SLOT>(eb, xb);
+        ea = ec;
+        eb = ed;
+        e += 2;
+    }
+    if (e < e1) pattern_fma<SLOT>(ea, xa);
+}
+
+template <int NF, int CPW, typename T>
+__device__ __forceinline__ void tiled_body(const TiledParams& p) {
+    constexpr int R = kR;
+    extern __shared__ __align__(16) float tile[];   // [CC][64][kPR]
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int FW = blockDim.x >> 6;
+    const int CC = CPW * FW;                        // channels per chunk; a multiple of kBucket (checked on the host)
 
     // Consecutive workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous range of logical ids so
     // that the filter groups of one slot, which read the same activations, share one L2.
@@ -288,60 +312,98 @@ __global__ __launch_bounds__(MAXT) void tiled_kernel(const TiledParams p) {
     const __amdgpu_buffer_rsrc_t rsrc =
         make_rsrc(static_cast<const char*>(p.x) + base_off, (uint32_t)(left < 0x7FFFFFFFull ? left : 0x7FFFFFFFull));
 
-    float acc[NF][3][R];
-#pragma unroll
-    for (int a = 0; a < NF; ++a)
-#pragma unroll
-        for (int b = 0; b < 3; ++b)
-#pragma unroll
-            for (int r = 0; r < R; ++r) acc[a][b][r] = 0.f;
+    float* const tile_lane = tile + lane * kPR;
+    if constexpr (NF > 0) zero_acc<0>();
+    if constexpr (NF > 1) zero_acc<1>();
+    if constexpr (NF > 2) zero_acc<2>();
+    static_assert(NF >= 1 && NF <= 3, "one to three filters per wave");
 
-    const float* tile_lane = tile + lane;
     const int pos_base = grp * (FW * NF) + wave;   // wave w takes positions pos_base + a*FW in the sorted filter order
+    const int nchunks = (p.C + CC - 1) / CC;
+    const int bpc = CC / kBucket;                  // buckets per chunk
 
-    for (int k = 0; k < p.nch; ++k) {
-        const int c0 = k * kChunk;
-        const int ncc = min(kChunk, p.C - c0);
-        // ---- stage chunk k: each wave copies whole channels, all R+2 patch rows of its lanes
-        for (int cc = wave; cc < ncc; cc += FW) {
-            const unsigned soff = (unsigned)(c0 + cc) * p.plane_bytes;
-            float v[R + 2];
+    float pre[CPW][R + 2];                         // the wave's share of the next chunk, in flight
+    auto issue_loads = [&](int k) {
 #pragma unroll
-            for (int i = 0; i < R + 2; ++i) v[i] = buffer_load_f32<T>(rsrc, voff[i], soff);
+        for (int j = 0; j < CPW; ++j) {
+            const int c = k * CC + wave + j * FW;
+            if (c < p.C) {
+                const unsigned soff = (unsigned)c * p.plane_bytes;
 #pragma unroll
-            for (int i = 0; i < R + 2; ++i) tile[(cc * (R + 2) + i) * 64 + lane] = v[i];
+                for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_f32<T>(rsrc, voff[i], soff);
+            }
         }
-        __syncthreads();
+    };
+    auto write_lds = [&](int k) {
+#pragma unroll
+        for (int j = 0; j < CPW; ++j) {
+            const int cc = wave + j * FW;
+            if (k * CC + cc < p.C) {
+                float* dst = tile_lane + cc * kChDwords;
+                *reinterpret_cast<float4*>(dst + 0) = make_float4(pre[j][0], pre[j][1], pre[j][2], pre[j][3]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(pre[j][4], pre[j][5], pre[j][6], pre[j][7]);
+                *reinterpret_cast<float4*>(dst + 8) = make_float4(pre[j][8], 0.f, 0.f, 0.f);
+            }
+        }
+    };
 
-        // ---- multiply-accumulate the kept kernels of this chunk
-        if constexpr (NF > 0) accumulate_filter<R>(acc[0], p, tile_lane, pos_base + 0 * FW, k);
-        if constexpr (NF > 1) accumulate_filter<R>(acc[1], p, tile_lane, pos_base + 1 * FW, k);
-        if constexpr (NF > 2) accumulate_filter<R>(acc[2], p, tile_lane, pos_base + 2 * FW, k);
-        if constexpr (NF > 3) accumulate_filter<R>(acc[3], p, tile_lane, pos_base + 3 * FW, k);
-        static_assert(NF <= 4, "at most four filters per wave");
-        __syncthreads();
+    issue_loads(0);
+    write_lds(0);
+    __syncthreads();
+    for (int k = 0; k < nchunks; ++k) {
+        const bool more = k + 1 < nchunks;
+        if (more) issue_loads(k + 1);
+        const int b0 = k * bpc, b1 = min(p.nbk, b0 + bpc), c0 = k * CC;
+        if constexpr (NF > 0) accumulate_filter<0>(p, tile_lane, pos_base + 0 * FW, b0, b1, c0);
+        if constexpr (NF > 1) accumulate_filter<1>(p, tile_lane, pos_base + 1 * FW, b0, b1, c0);
+        if constexpr (NF > 2) accumulate_filter<2>(p, tile_lane, pos_base + 2 * FW, b0, b1, c0);
+        __syncthreads();           // every wave is done reading chunk k
+        if (more) {
+            write_lds(k + 1);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue: add the three accumulator sets across neighbouring lanes, bias, ReLU, store
     T* __restrict__ y = static_cast<T*>(p.y);
     const bool col_ok = active && t >= 1 && t <= p.OWS && ox < p.Wo;
-#pragma unroll
-    for (int a = 0; a < NF; ++a) {
-        const int pos = pos_base + a * FW;
-        if (pos >= p.F) continue;   // uniform per wave
+    auto store_filter = [&](const float (&acc)[3][R], int pos) {
+        if (pos >= p.F) return;   // uniform per wave
         const unsigned f = p.forder[pos];
         const float b = p.bias ? p.bias[f] : 0.f;
         const size_t ybase = (((size_t)n * p.F + f) * p.Ho) * (size_t)p.Wo;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const float from_left = __shfl_up(acc[a][0][r], 1, 64);     // lane t-1 holds column ix-1: its kx=0 sum
-            const float from_right = __shfl_down(acc[a][2][r], 1, 64);  // lane t+1 holds column ix+1: its kx=2 sum
-            float v = acc[a][1][r] + from_left + from_right + b;
+            const float from_left = __shfl_up(acc[0][r], 1, 64);     // lane t-1 holds column ix-1: its kx=0 sum
+            const float from_right = __shfl_down(acc[2][r], 1, 64);  // lane t+1 holds column ix+1: its kx=2 sum
+            float v = acc[1][r] + from_left + from_right + b;
             if (p.relu) v = fmaxf(v, 0.f);
             const int oy = r0 + r;
             if (col_ok && oy < p.Ho) y[ybase + (size_t)oy * p.Wo + ox] = from_f32<T>(v);
         }
-    }
+    };
+    float acc[3][R];
+    if constexpr (NF > 0) { read_acc<0>(acc); store_filter(acc, pos_base + 0 * FW); }
+    if constexpr (NF > 1) { read_acc<1>(acc); store_filter(acc, pos_base + 1 * FW); }
+    if constexpr (NF > 2) { read_acc<2>(acc); store_filter(acc, pos_base + 2 * FW); }
+}
+
+// The compiler may allocate 2*n vector registers under amdgpu_num_vgpr(n) on this target; the accumulators of the
+// pattern sections sit above that: 21 registers per filter slot, ending at v127.
+template <int CPW, typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(53))) void tiled_kernel_nf1(const TiledParams p) {
+    static_assert(PCONV_ACC_BASE_R7_S0 >= 2 * 53, "accumulators overlap the compiler's registers");
+    tiled_body<1, CPW, T>(p);
+}
+template <int CPW, typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(43))) void tiled_kernel_nf2(const TiledParams p) {
+    static_assert(PCONV_ACC_BASE_R7_S1 >= 2 * 43, "accumulators overlap the compiler's registers");
+    tiled_body<2, CPW, T>(p);
+}
+template <int CPW, typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(32))) void tiled_kernel_nf3(const TiledParams p) {
+    static_assert(PCONV_ACC_BASE_R7_S2 >= 2 * 32, "accumulators overlap the compiler's registers");
+    tiled_body<3, CPW, T>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -366,14 +428,13 @@ __global__ __launch_bounds__(256) void generic_kernel(const T* __restrict__ x, T
     float acc = 0.f;
     for (unsigned e = e0; e < e1; ++e) {
         const EntryRegs d = load_entry(ent, e);
-        const unsigned c = ent[e].c;
-        const T* xc = xn + (size_t)c * plane;
+        const T* xc = xn + (size_t)d.c * plane;
         int q = 0;
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
             if ((d.mask9 >> t) & 1u) {
                 const int iy = oy * stride + t / 3 - pad, ix = ox * stride + t % 3 - pad;
-                const float wv = q == 0 ? d.w[0] : q == 1 ? d.w[1] : q == 2 ? d.w[2] : d.w[3];
+                const float wv = __builtin_bit_cast(float, q == 0 ? d.w[0] : q == 1 ? d.w[1] : q == 2 ? d.w[2] : d.w[3]);
                 if (ok && iy >= 0 && iy < H && ix >= 0 && ix < W) acc = fmaf(wv, to_f32<T>(xc[(size_t)iy * W + ix]), acc);
                 ++q;
             }
@@ -445,27 +506,20 @@ static hipError_t allow_big_lds(const void* fn, size_t lds) {
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
-template <int R, int NF, typename T>
-static int launch_tiled_rn(const TiledParams& p, int waves, int slots, hipStream_t stream) {
-    const int nblocks = p.nblocks;
-    const int grid = (nblocks + 7) / 8 * 8;
-    const size_t lds = (size_t)std::min(kChunk, p.C) * (R + 2) * 64 * sizeof(float);
-    (void)slots;
-    if (waves <= 8) {
-        auto kern = tiled_kernel<R, NF, 512, T>;
-        PCONV_HIP(allow_big_lds((const void*)kern, lds));
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), lds, stream, p);
-    } else {
-        auto kern = tiled_kernel<R, NF, 1024, T>;
-        PCONV_HIP(allow_big_lds((const void*)kern, lds));
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), lds, stream, p);
-    }
+template <typename K>
+static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int CPW, hipStream_t stream) {
+    const int grid = (p.nblocks + 7) / 8 * 8;
+    const size_t lds = (size_t)CPW * waves * kChDwords * sizeof(float);
+    if (lds > 160 * 1024) return PCONV_EUNSUPPORTED;
+    PCONV_HIP(allow_big_lds((const void*)kern, lds));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), lds, stream, p);
     PCONV_HIP(hipGetLastError());
     return PCONV_OK;
 }
 
 template <typename T>
-static int launch_tiled(TiledParams& p, int R, int NF, int waves, hipStream_t stream) {
+static int launch_tiled(TiledParams& p, int NF, int waves, int CPW, hipStream_t stream) {
+    if ((CPW * waves) % kBucket != 0) return PCONV_EUNSUPPORTED;   // a chunk is a whole number of buckets
     // tile geometry
     const int Wo = p.Wo, Ho = p.Ho;
     const int ncs = (Wo + 61) / 62;
@@ -473,7 +527,7 @@ static int launch_tiled(TiledParams& p, int R, int NF, int waves, hipStream_t st
     p.NCS = (Wo + p.OWS - 1) / p.OWS;
     p.LW = p.OWS + 2;
     p.S = 64 / p.LW;
-    p.NRB = (Ho + R - 1) / R;
+    p.NRB = (Ho + kR - 1) / kR;
     const long long nseg = (long long)p.N * p.NRB * p.NCS;
     if (nseg > 0x7FFFFFFF) return PCONV_ESHAPE;
     p.NSEG = (int)nseg;
@@ -482,13 +536,11 @@ static int launch_tiled(TiledParams& p, int R, int NF, int waves, hipStream_t st
     const long long nb = (long long)slots * p.NG;
     if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
     p.nblocks = (int)nb;
-#define PCONV_CASE(RR, FF) \
-    if (R == RR && NF == FF) return launch_tiled_rn<RR, FF, T>(p, waves, slots, stream);
-    PCONV_CASE(7, 1)
-    PCONV_CASE(7, 2)
-    PCONV_CASE(4, 1)
-    PCONV_CASE(4, 2)
-    PCONV_CASE(4, 4)
+#define PCONV_CASE(FF, PP) \
+    if (NF == FF && CPW == PP) return launch_tiled_inst(tiled_kernel_nf##FF<PP, T>, p, waves, CPW, stream);
+    PCONV_CASE(1, 1) PCONV_CASE(1, 2) PCONV_CASE(1, 4)
+    PCONV_CASE(2, 1) PCONV_CASE(2, 2) PCONV_CASE(2, 4)
+    PCONV_CASE(3, 1) PCONV_CASE(3, 2)
 #undef PCONV_CASE
     return PCONV_EUNSUPPORTED;
 }
@@ -546,14 +598,17 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
 
     int kernel = tuning ? tuning->kernel : PCONV_KERNEL_AUTO;
     int R = tuning ? tuning->rows : 0, NF = tuning ? tuning->filters_per_wave : 0, waves = tuning ? tuning->waves : 0;
+    int CPW = tuning ? tuning->channels_per_wave : 0;
     const bool can_tile = tiled_applicable(N, wp->C, H, W, stride, esize);
     if (kernel == PCONV_KERNEL_AUTO) kernel = can_tile ? PCONV_KERNEL_TILED : PCONV_KERNEL_GENERIC;
     if (kernel == PCONV_KERNEL_TILED && !can_tile) return PCONV_EUNSUPPORTED;
 
     if (kernel == PCONV_KERNEL_TILED) {
-        if (R == 0) R = (Ho % 7 == 0 || Ho > 16) ? 7 : 4;
+        if (R == 0) R = kR;
+        if (R != kR) return PCONV_EUNSUPPORTED;
         if (waves == 0) waves = 8;
         if (NF == 0) NF = 1;
+        if (CPW == 0) CPW = waves >= 16 ? 1 : 16 / waves;
         if (waves < 1 || waves > 16) return PCONV_EUNSUPPORTED;
         TiledParams p{};
         p.x = x;
@@ -571,21 +626,21 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.Wo = Wo;
         p.pad = pad;
         p.relu = relu;
-        p.nch = wp->n_chunks;
+        p.nbk = wp->n_buckets;
         p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
         p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
         p.plane_bytes = (unsigned)((size_t)H * W * esize);
-        return wp->dtype == PCONV_F16 ? launch_tiled<__half>(p, R, NF, waves, st)
-                                      : launch_tiled<float>(p, R, NF, waves, st);
+        return wp->dtype == PCONV_F16 ? launch_tiled<__half>(p, NF, waves, CPW, st)
+                                      : launch_tiled<float>(p, NF, waves, CPW, st);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);
     if (wp->dtype == PCONV_F16)
         hipLaunchKernelGGL(generic_kernel<__half>, grid, dim3(256), 0, st, (const __half*)x, (__half*)y, wp->d_ent,
-                           wp->d_eptr, wp->d_forder, bias, wp->C, wp->F, H, W, Ho, Wo, stride, pad, wp->n_chunks, relu);
+                           wp->d_eptr, wp->d_forder, bias, wp->C, wp->F, H, W, Ho, Wo, stride, pad, wp->n_buckets, relu);
     else
         hipLaunchKernelGGL(generic_kernel<float>, grid, dim3(256), 0, st, (const float*)x, (float*)y, wp->d_ent,
-                           wp->d_eptr, wp->d_forder, bias, wp->C, wp->F, H, W, Ho, Wo, stride, pad, wp->n_chunks, relu);
+                           wp->d_eptr, wp->d_forder, bias, wp->C, wp->F, H, W, Ho, Wo, stride, pad, wp->n_buckets, relu);
     PCONV_HIP(hipGetLastError());
     return PCONV_OK;
 }

@@ -53,6 +53,14 @@ inline float half_bits_to_float(uint16_t h) {
     return f;
 }
 
+// Rank of a four-bit mask among the 126 such masks in ascending order (the pattern code of the device layout).
+inline uint32_t mask_rank(unsigned m) {
+    uint32_t rank = 0;
+    for (unsigned v = 0; v < m; ++v)
+        if (popcount9(v) == 4) ++rank;
+    return rank;
+}
+
 // Retained squared norm of one kernel under one mask: squares in double, added in ascending tap order.
 inline double retained(const float* k9, unsigned m) {
     double acc = 0.0;
@@ -189,18 +197,18 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
         }
         p->grp_ptr[(size_t)F * K] = (uint32_t)e;
 
-        // device layout, derived from the canonical one: per (position i, channel chunk) the entries by pattern,
+        // device layout, derived from the canonical one: per (position i, channel bucket) the entries by pattern,
         // then channel; weights widened to fp32
-        const int chunk = pconv::kChunk;
-        p->n_chunks = (C + chunk - 1) / chunk;
+        const int chunk = pconv::kBucket;
+        p->n_buckets = (C + chunk - 1) / chunk;
         p->ent.resize(n_kept);
-        p->eptr.assign((size_t)F * p->n_chunks + 1, 0);
+        p->eptr.assign((size_t)F * p->n_buckets + 1, 0);
         std::vector<uint32_t> cursor((size_t)K);
         size_t d = 0;
         for (int i = 0; i < F; ++i) {
             for (int j = 0; j < K; ++j) cursor[(size_t)j] = p->grp_ptr[(size_t)i * K + j];
-            for (int k = 0; k < p->n_chunks; ++k) {
-                p->eptr[(size_t)i * p->n_chunks + k] = (uint32_t)d;
+            for (int k = 0; k < p->n_buckets; ++k) {
+                p->eptr[(size_t)i * p->n_buckets + k] = (uint32_t)d;
                 const int c_end = std::min(C, (k + 1) * chunk);
                 for (int j = 0; j < K; ++j) {
                     const uint32_t g_end = p->grp_ptr[(size_t)i * K + j + 1];
@@ -217,15 +225,15 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
                             }
                         }
                         de.c = p->cin[cur];
-                        de.cc = de.c % (uint32_t)chunk;
                         de.mask9 = lib[j];
+                        de.code = mask_rank(lib[j]);
                         de.unused = 0;
                         ++cur;
                     }
                 }
             }
         }
-        p->eptr[(size_t)F * p->n_chunks] = (uint32_t)d;
+        p->eptr[(size_t)F * p->n_buckets] = (uint32_t)d;
     } catch (const std::bad_alloc&) {
         delete p;
         return PCONV_ENOMEM;

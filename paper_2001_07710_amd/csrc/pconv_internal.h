@@ -9,16 +9,16 @@
 
 namespace pconv {
 
-// Channels are processed in chunks of this many; the kernels stage one chunk of activations in LDS at a time and
-// the packed entries of a filter are bucketed by chunk.
-constexpr int kChunk = 32;
+// The packed entries of a filter are bucketed by input channel in buckets of this many channels.  The tiled kernel
+// stages a chunk of 1, 2 or 4 consecutive buckets of activations in LDS at a time.
+constexpr int kBucket = 16;
 
 // One kept kernel in the device layout (32 bytes so that one scalar load of eight dwords fetches it).
 struct DevEntry {
     float w[4];       // the four kept weights, taps ascending, widened to fp32 (exact for fp16 storage)
-    uint32_t cc;      // input channel inside its chunk: c % kChunk
-    uint32_t mask9;   // the pattern mask itself (bit t = 3*ky + kx)
     uint32_t c;       // input channel
+    uint32_t mask9;   // the pattern mask itself (bit t = 3*ky + kx)
+    uint32_t code;    // rank of the mask among the 126 masks with four of nine bits, ascending (0..125)
     uint32_t unused;
 };
 static_assert(sizeof(DevEntry) == 32, "DevEntry must be 32 bytes");
@@ -36,10 +36,10 @@ struct pconv_packed {
     std::vector<uint16_t> cin;            // [n_kept]
     std::vector<unsigned char> w4;        // [n_kept*4] in the storage dtype, raw bytes
 
-    // device layout, host copy: entries ordered by (position i in filter_order, channel chunk, pattern, channel)
-    int n_chunks = 0;
+    // device layout, host copy: entries ordered by (position i in filter_order, channel bucket, pattern, channel)
+    int n_buckets = 0;
     std::vector<pconv::DevEntry> ent;     // [n_kept]
-    std::vector<uint32_t> eptr;           // [F*n_chunks + 1]: entries of (i, chunk) are eptr[i*n_chunks+chunk] ..
+    std::vector<uint32_t> eptr;           // [F*n_buckets + 1]: entries of (i, bucket) are eptr[i*n_buckets+bucket] ..
 
     // device copies (null when packed host-only)
     int device = -1;
