@@ -114,25 +114,27 @@ __device__ __forceinline__ float buffer_load_f32<__half>(__amdgpu_buffer_rsrc_t 
 // ix = os + t - pad and, in registers, the R+2 input rows that its R output rows read.  A tap (ky,kx) of a kernel
 // multiplies the lane's own column: acc[kx][r] += w * x[r + ky].  The three accumulator sets (one per kx) belong to
 // output columns ix+1, ix, ix-1 (+pad-1) and are added across neighbouring lanes once, after the last channel.
-// So the inner loop has no cross-lane traffic: 4*R multiply-adds per kept kernel, weights from scalar registers.
+// So the inner loop has no cross-lane traffic: 4*R multiply-adds per kept kernel.
 //
-// LDS layout.  tile[cc][lane][PR]: channel-in-chunk, lane, patch row i = r + ky, with PR = R+2 rounded up to a
-// multiple of four (12) so that a lane fetches its patch with three 128-bit reads (twice the LDS rate of 32-bit
-// reads on this chip); a lane stride of 12 dwords spreads 16 lanes over 64 distinct banks.
+// LDS layout.  tile[cc][lane][12]: channel-in-chunk, lane, patch row i = r + ky (R+2 = 9 rows padded to 12) so that
+// a lane fetches its patch with 128-bit reads (twice the LDS rate of 32-bit reads on this chip); behind the tile,
+// per wave and filter slot, the kept kernels ("entries") of that filter in the staged chunk.
 //
 // Work split.  A workgroup is one slot (the S segments) times FW*NF filters: wave w accumulates NF filters.  All
-// waves share the staged activations.  Channels are staged in chunks of CC = CPW*FW (each wave copies CPW whole
-// channels); the global loads of chunk k+1 are in flight, in registers, while chunk k is being multiplied.
+// waves share the staged activations.  Channels are staged in chunks of CC = CPW*FW = 16*NB (each wave copies CPW
+// whole channels and the entries of its own filters); the global loads of chunk k+1 are in flight, in registers,
+// while chunk k is being multiplied.
 //
-// Per-pattern code.  The 4*R multiply-adds of a kept kernel are one of 126 straight-line sections (one per possible
-// pattern), generated ahead of time by gen_pattern_leaves.py and reached with ONE computed jump, so a wave never
-// diverges and never walks a branch tree (the per-pattern generated access code of section 6.2 of the paper).  A
-// scalar branch tree costs several hundred clocks per kernel on this chip, against 112 clocks of multiply-adds.
-// The sections are inline assembly; their accumulators live in fixed registers above the budget that the compiler
-// is given for this kernel (amdgpu_num_vgpr), see pattern_leaves.inc.
+// Inner loop.  Threaded code, generated by gen_pattern_leaves.py into pattern_leaves.inc: one 256-byte code section
+// per possible pattern; a section multiplies one kept kernel, fetches the next one and jumps straight to ITS
+// section.  No branch tree (which costs several hundred clocks per kernel on this chip, against 112 clocks of
+// multiply-adds), no divergence: the per-pattern generated access code of section 6.2 of the paper.  The sections
+// are inline assembly with fixed registers; the accumulators sit above the register budget that the compiler is
+// given for these kernels (amdgpu_num_vgpr).
 // ---------------------------------------------------------------------------------------------------------------
 
 #include "pattern_leaves.inc"
+static_assert(PCONV_LEAF_STRIDE == kLeafStride, "host packer and generated code disagree on the section stride");
 
 struct TiledParams {
     const void* x;
@@ -151,73 +153,22 @@ struct TiledParams {
     unsigned plane_bytes;    // H*W*sizeof(T)
 };
 
-constexpr int kR = 7;                 // output rows per lane
-constexpr int kPR = 12;               // patch rows per lane in LDS (R + 2, padded to a multiple of four)
-constexpr int kChDwords = 64 * kPR;   // one channel of one slot in LDS
-
-struct EntryRegs {
-    unsigned w[4];   // bit patterns of the fp32 weights (kept as integers so that they stay in scalar registers)
-    unsigned c, mask9, code;
-};
+constexpr int kR = 7;                       // output rows per lane
+constexpr int kPR = 12;                     // patch rows per lane in LDS (R + 2, padded to a multiple of four)
+constexpr int kChBytes = 64 * kPR * 4;      // one channel of one slot in LDS
 
 // Packed weights and pointers never change while a kernel runs: reading them through the constant address space
 // makes every such load a scalar load (wave-uniform address, result in scalar registers).
-typedef unsigned u32x8 __attribute__((ext_vector_type(8)));
-typedef const u32x8 __attribute__((address_space(4)))* const_u32x8_ptr;
 typedef const unsigned __attribute__((address_space(4)))* const_u32_ptr;
-
 __device__ __forceinline__ unsigned scalar_load_u32(const uint32_t* p) {
     return *(const_u32_ptr)(unsigned long long)p;
 }
 
-__device__ __forceinline__ EntryRegs load_entry(const DevEntry* ent, unsigned e) {
-    const u32x8 v = *(const_u32x8_ptr)(unsigned long long)(ent + e);
-    EntryRegs r;
-    r.w[0] = v[0];
-    r.w[1] = v[1];
-    r.w[2] = v[2];
-    r.w[3] = v[3];
-    r.c = v[4];
-    r.mask9 = v[5];
-    r.code = v[6];
-    return r;
-}
-
-// The lane's patch of channel cc: three 128-bit LDS reads (rows 9..11 are padding).
-__device__ __forceinline__ void load_patch(float (&xp)[kPR], const float* tile_lane, unsigned cc) {
-    const float* base = tile_lane + cc * kChDwords;
-#pragma unroll
-    for (int q = 0; q < kPR / 4; ++q) {
-        const float4 v = *reinterpret_cast<const float4*>(base + 4 * q);
-        xp[4 * q + 0] = v.x;
-        xp[4 * q + 1] = v.y;
-        xp[4 * q + 2] = v.z;
-        xp[4 * q + 3] = v.w;
-    }
-}
-
-// One kept kernel into the accumulators of filter slot SLOT: computed jump into the section of its pattern.
-template <int SLOT>
-__device__ __forceinline__ void pattern_fma(const EntryRegs& e, const float (&xp)[kPR]) {
-    const unsigned off = e.code * PCONV_LEAF_BYTES_R7 + PCONV_LEAF_ENTRY_OFFSET;   // wave-uniform
-#define PCONV_LEAF_OPERANDS                                                                                     \
-    [off] "s"(off), [w0] "s"(e.w[0]), [w1] "s"(e.w[1]), [w2] "s"(e.w[2]), [w3] "s"(e.w[3]), [x0] "v"(xp[0]),    \
-        [x1] "v"(xp[1]), [x2] "v"(xp[2]), [x3] "v"(xp[3]), [x4] "v"(xp[4]), [x5] "v"(xp[5]), [x6] "v"(xp[6]),   \
-        [x7] "v"(xp[7]), [x8] "v"(xp[8])
-    if constexpr (SLOT == 0)
-        asm volatile(PCONV_LEAVES_R7_S0 : : PCONV_LEAF_OPERANDS : "s60", "s61", "scc", PCONV_ACC_CLOBBERS_R7_S0);
-    else if constexpr (SLOT == 1)
-        asm volatile(PCONV_LEAVES_R7_S1 : : PCONV_LEAF_OPERANDS : "s60", "s61", "scc", PCONV_ACC_CLOBBERS_R7_S1);
-    else
-        asm volatile(PCONV_LEAVES_R7_S2 : : PCONV_LEAF_OPERANDS : "s60", "s61", "scc", PCONV_ACC_CLOBBERS_R7_S2);
-#undef PCONV_LEAF_OPERANDS
-}
-
 template <int SLOT>
 __device__ __forceinline__ void zero_acc() {
-    if constexpr (SLOT == 0) asm volatile(PCONV_ACC_ZERO_R7_S0 : : : PCONV_ACC_CLOBBERS_R7_S0);
-    else if constexpr (SLOT == 1) asm volatile(PCONV_ACC_ZERO_R7_S1 : : : PCONV_ACC_CLOBBERS_R7_S1);
-    else asm volatile(PCONV_ACC_ZERO_R7_S2 : : : PCONV_ACC_CLOBBERS_R7_S2);
+    if constexpr (SLOT == 0) asm volatile(PCONV_ACC_ZERO_S0 : : : PCONV_ACC_CLOBBERS_S0);
+    else if constexpr (SLOT == 1) asm volatile(PCONV_ACC_ZERO_S1 : : : PCONV_ACC_CLOBBERS_S1);
+    else asm volatile(PCONV_ACC_ZERO_S2 : : : PCONV_ACC_CLOBBERS_S2);
 }
 
 template <int SLOT>
@@ -226,54 +177,44 @@ __device__ __forceinline__ void read_acc(float (&a)[3][kR]) {
     "=v"(a[0][0]), "=v"(a[0][1]), "=v"(a[0][2]), "=v"(a[0][3]), "=v"(a[0][4]), "=v"(a[0][5]), "=v"(a[0][6]),        \
         "=v"(a[1][0]), "=v"(a[1][1]), "=v"(a[1][2]), "=v"(a[1][3]), "=v"(a[1][4]), "=v"(a[1][5]), "=v"(a[1][6]),    \
         "=v"(a[2][0]), "=v"(a[2][1]), "=v"(a[2][2]), "=v"(a[2][3]), "=v"(a[2][4]), "=v"(a[2][5]), "=v"(a[2][6])
-    if constexpr (SLOT == 0) asm volatile(PCONV_ACC_READ_R7_S0 : PCONV_ACC_OUTPUTS);
-    else if constexpr (SLOT == 1) asm volatile(PCONV_ACC_READ_R7_S1 : PCONV_ACC_OUTPUTS);
-    else asm volatile(PCONV_ACC_READ_R7_S2 : PCONV_ACC_OUTPUTS);
+    if constexpr (SLOT == 0) asm volatile(PCONV_ACC_READ_S0 : PCONV_ACC_OUTPUTS);
+    else if constexpr (SLOT == 1) asm volatile(PCONV_ACC_READ_S1 : PCONV_ACC_OUTPUTS);
+    else asm volatile(PCONV_ACC_READ_S2 : PCONV_ACC_OUTPUTS);
 #undef PCONV_ACC_OUTPUTS
 }
 
-// All kept kernels of the filter at position `pos` of the sorted filter order whose channel lies in buckets
-// [b0, b1).  Software pipeline over pairs of entries: the next pair is being fetched into scalar registers and the
-// activations of the next entry into a second set of vector registers while the current entry is multiplied.
-// Prefetches past the end re-read the last entry (always a valid address) and are dropped.
-template <int SLOT>
-__device__ __forceinline__ void accumulate_filter(const TiledParams& p, const float* tile_lane, int pos, int b0,
-                                                  int b1, int c0) {
-    if (pos >= p.F) return;
-    unsigned e = scalar_load_u32(p.eptr + pos * p.nbk + b0);
-    const unsigned e1 = scalar_load_u32(p.eptr + pos * p.nbk + b1);
-    if (e >= e1) return;
-    const unsigned last = e1 - 1;
-    EntryRegs ea = load_entry(p.ent, e);
-    EntryRegs eb = load_entry(p.ent, min(e + 1, last));
-    float xa[kPR], xb[kPR];
-    load_patch(xa, tile_lane, ea.c - c0);
-    while (e + 1 < e1) {
-        // Everything in flight here was issued at least one section ago.  Waiting for all of it now keeps the waits
-        // the compiler adds below from also covering the prefetches issued next (scalar loads return out of order,
-        // so any later wait on the LDS/scalar counter is a wait for everything outstanding).
-        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), other counters untouched
-        load_patch(xb, tile_lane, eb.c - c0);
-        const EntryRegs ec = load_entry(p.ent, min(e + 2, last));
-        const EntryRegs ed = load_entry(p.ent, min(e + 3, last));
-        pattern_fma<SLOT>(ea, xa);
-        load_patch(xa, tile_lane, ec.c - c0);
-        pattern_fma<SLOT>(eb, xb);
-        ea = ec;
-        eb = ed;
-        e += 2;
-    }
-    if (e < e1) pattern_fma<SLOT>(ea, xa);
+// Runs `count` (>= 1) entries stored in LDS from byte address `entry_addr` on, for the filter in slot SLOT of a
+// kernel with NF slots.  `lane_addr` is the LDS byte address of this lane's patch of channel 0 of the chunk.
+template <int NF, int SLOT>
+__device__ __forceinline__ void run_entries(unsigned lane_addr, unsigned entry_addr, unsigned count) {
+    const unsigned cnt = __builtin_amdgcn_readfirstlane(count);
+#define PCONV_LOOP(NFv, Sv)                                                                     \
+    asm volatile(PCONV_ENTRY_LOOP_NF##NFv##_S##Sv                                               \
+                 :                                                                              \
+                 : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr), [cnt] "s"(cnt)             \
+                 : "memory", PCONV_ENTRY_LOOP_CLOBBERS_NF##NFv##_S##Sv)
+    if constexpr (NF == 1) { PCONV_LOOP(1, 0); }
+    else if constexpr (NF == 2 && SLOT == 0) { PCONV_LOOP(2, 0); }
+    else if constexpr (NF == 2 && SLOT == 1) { PCONV_LOOP(2, 1); }
+    else if constexpr (NF == 3 && SLOT == 0) { PCONV_LOOP(3, 0); }
+    else if constexpr (NF == 3 && SLOT == 1) { PCONV_LOOP(3, 1); }
+    else { PCONV_LOOP(3, 2); }
+#undef PCONV_LOOP
 }
 
-template <int NF, int CPW, typename T>
+template <int NF, int CPW, int NB, typename T>
 __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     constexpr int R = kR;
-    extern __shared__ __align__(16) float tile[];   // [CC][64][kPR]
+    constexpr int CC = 16 * NB;          // channels per chunk
+    constexpr int FW = CC / CPW;         // waves per workgroup
+    static_assert(CC % CPW == 0 && (FW == 4 || FW == 8 || FW == 16), "bad tiling");
+    static_assert(NF >= 1 && NF <= 3, "one to three filters per wave");
+    constexpr unsigned kEntRegion = (CC + 1) * 32;          // bytes of LDS for the entries of one filter and chunk
+    constexpr unsigned kEntBase = CC * kChBytes;             // entries start behind the tile
+    extern __shared__ __align__(16) unsigned char lds[];     // [CC][64][12] floats, then [FW][NF][CC+1] entries
+    const unsigned lds0 = (unsigned)(unsigned long long)lds; // LDS byte address of the allocation (low 32 bits)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int FW = blockDim.x >> 6;
-    const int CC = CPW * FW;                        // channels per chunk; a multiple of kBucket (checked on the host)
 
     // Consecutive workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous range of logical ids so
     // that the filter groups of one slot, which read the same activations, share one L2.
@@ -312,17 +253,18 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     const __amdgpu_buffer_rsrc_t rsrc =
         make_rsrc(static_cast<const char*>(p.x) + base_off, (uint32_t)(left < 0x7FFFFFFFull ? left : 0x7FFFFFFFull));
 
-    float* const tile_lane = tile + lane * kPR;
+    const unsigned lane_addr = lds0 + lane * (kPR * 4);
     if constexpr (NF > 0) zero_acc<0>();
     if constexpr (NF > 1) zero_acc<1>();
     if constexpr (NF > 2) zero_acc<2>();
-    static_assert(NF >= 1 && NF <= 3, "one to three filters per wave");
 
     const int pos_base = grp * (FW * NF) + wave;   // wave w takes positions pos_base + a*FW in the sorted filter order
     const int nchunks = (p.C + CC - 1) / CC;
-    const int bpc = CC / kBucket;                  // buckets per chunk
 
-    float pre[CPW][R + 2];                         // the wave's share of the next chunk, in flight
+    float pre[CPW][R + 2];       // the wave's share of the next chunk's activations, in flight
+    uint2 epre[NF][NB];          // ... and of the next chunk's entries (lane l holds dwords 2l, 2l+1 of 16 entries)
+    unsigned ecnt[NF];           // entries of each of the wave's filters in the chunk that is staged or in flight
+
     auto issue_loads = [&](int k) {
 #pragma unroll
         for (int j = 0; j < CPW; ++j) {
@@ -333,17 +275,45 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
                 for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_f32<T>(rsrc, voff[i], soff);
             }
         }
+        const int b0 = k * NB, b1 = min(p.nbk, b0 + NB);
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            const int pos = pos_base + a * FW;
+            unsigned cnt = 0;
+            if (pos < p.F) {
+                const unsigned e0 = scalar_load_u32(p.eptr + pos * p.nbk + b0);
+                cnt = scalar_load_u32(p.eptr + pos * p.nbk + b1) - e0;
+                const uint2* src = reinterpret_cast<const uint2*>(p.ent + e0);
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+                    if ((unsigned)(lane >> 2) + 16u * j < cnt) epre[a][j] = src[lane + 64 * j];
+            }
+            ecnt[a] = cnt;
+        }
     };
     auto write_lds = [&](int k) {
 #pragma unroll
         for (int j = 0; j < CPW; ++j) {
             const int cc = wave + j * FW;
             if (k * CC + cc < p.C) {
-                float* dst = tile_lane + cc * kChDwords;
+                float* dst = reinterpret_cast<float*>(lds + cc * kChBytes + lane * (kPR * 4));
                 *reinterpret_cast<float4*>(dst + 0) = make_float4(pre[j][0], pre[j][1], pre[j][2], pre[j][3]);
                 *reinterpret_cast<float4*>(dst + 4) = make_float4(pre[j][4], pre[j][5], pre[j][6], pre[j][7]);
                 *reinterpret_cast<float4*>(dst + 8) = make_float4(pre[j][8], 0.f, 0.f, 0.f);
             }
+        }
+        // entries: the channel (dword 4 of an entry) becomes the byte offset of that channel inside the chunk
+        const unsigned c0 = (unsigned)k * CC;
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            uint2* dst = reinterpret_cast<uint2*>(lds + kEntBase + (wave * NF + a) * kEntRegion);
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                if ((unsigned)(lane >> 2) + 16u * j < ecnt[a]) {
+                    uint2 v = epre[a][j];
+                    if ((lane & 3) == 2) v.x = (v.x - c0) * (unsigned)kChBytes;
+                    dst[lane + 64 * j] = v;
+                }
         }
     };
 
@@ -352,11 +322,14 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     __syncthreads();
     for (int k = 0; k < nchunks; ++k) {
         const bool more = k + 1 < nchunks;
+        unsigned cnt_now[NF];
+#pragma unroll
+        for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
         if (more) issue_loads(k + 1);
-        const int b0 = k * bpc, b1 = min(p.nbk, b0 + bpc), c0 = k * CC;
-        if constexpr (NF > 0) accumulate_filter<0>(p, tile_lane, pos_base + 0 * FW, b0, b1, c0);
-        if constexpr (NF > 1) accumulate_filter<1>(p, tile_lane, pos_base + 1 * FW, b0, b1, c0);
-        if constexpr (NF > 2) accumulate_filter<2>(p, tile_lane, pos_base + 2 * FW, b0, b1, c0);
+        const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
+        if constexpr (NF > 0) { if (cnt_now[0]) run_entries<NF, 0>(lane_addr, ent_addr + 0 * kEntRegion, cnt_now[0]); }
+        if constexpr (NF > 1) { if (cnt_now[1]) run_entries<NF, 1>(lane_addr, ent_addr + 1 * kEntRegion, cnt_now[1]); }
+        if constexpr (NF > 2) { if (cnt_now[2]) run_entries<NF, 2>(lane_addr, ent_addr + 2 * kEntRegion, cnt_now[2]); }
         __syncthreads();           // every wave is done reading chunk k
         if (more) {
             write_lds(k + 1);
@@ -390,20 +363,20 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
 
 // The compiler may allocate 2*n vector registers under amdgpu_num_vgpr(n) on this target; the accumulators of the
 // pattern sections sit above that: 21 registers per filter slot, ending at v127.
-template <int CPW, typename T>
+template <int CPW, int NB, typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(53))) void tiled_kernel_nf1(const TiledParams p) {
-    static_assert(PCONV_ACC_BASE_R7_S0 >= 2 * 53, "accumulators overlap the compiler's registers");
-    tiled_body<1, CPW, T>(p);
+    static_assert(PCONV_ACC_BASE_S0 >= 2 * 53, "accumulators overlap the compiler's registers");
+    tiled_body<1, CPW, NB, T>(p);
 }
-template <int CPW, typename T>
+template <int CPW, int NB, typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(43))) void tiled_kernel_nf2(const TiledParams p) {
-    static_assert(PCONV_ACC_BASE_R7_S1 >= 2 * 43, "accumulators overlap the compiler's registers");
-    tiled_body<2, CPW, T>(p);
+    static_assert(PCONV_ACC_BASE_S1 >= 2 * 43, "accumulators overlap the compiler's registers");
+    tiled_body<2, CPW, NB, T>(p);
 }
-template <int CPW, typename T>
+template <int CPW, int NB, typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(32))) void tiled_kernel_nf3(const TiledParams p) {
-    static_assert(PCONV_ACC_BASE_R7_S2 >= 2 * 32, "accumulators overlap the compiler's registers");
-    tiled_body<3, CPW, T>(p);
+    static_assert(PCONV_ACC_BASE_S2 >= 2 * 32, "accumulators overlap the compiler's registers");
+    tiled_body<3, CPW, NB, T>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -427,14 +400,14 @@ __global__ __launch_bounds__(256) void generic_kernel(const T* __restrict__ x, T
     const T* xn = x + (size_t)n * C * plane;
     float acc = 0.f;
     for (unsigned e = e0; e < e1; ++e) {
-        const EntryRegs d = load_entry(ent, e);
+        const DevEntry d = ent[e];   // wave-uniform address
         const T* xc = xn + (size_t)d.c * plane;
         int q = 0;
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
             if ((d.mask9 >> t) & 1u) {
                 const int iy = oy * stride + t / 3 - pad, ix = ox * stride + t % 3 - pad;
-                const float wv = __builtin_bit_cast(float, q == 0 ? d.w[0] : q == 1 ? d.w[1] : q == 2 ? d.w[2] : d.w[3]);
+                const float wv = q == 0 ? d.w[0] : q == 1 ? d.w[1] : q == 2 ? d.w[2] : d.w[3];
                 if (ok && iy >= 0 && iy < H && ix >= 0 && ix < W) acc = fmaf(wv, to_f32<T>(xc[(size_t)iy * W + ix]), acc);
                 ++q;
             }
@@ -507,9 +480,9 @@ static hipError_t allow_big_lds(const void* fn, size_t lds) {
 }
 
 template <typename K>
-static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int CPW, hipStream_t stream) {
+static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int NF, int CC, hipStream_t stream) {
     const int grid = (p.nblocks + 7) / 8 * 8;
-    const size_t lds = (size_t)CPW * waves * kChDwords * sizeof(float);
+    const size_t lds = (size_t)CC * kChBytes + (size_t)waves * NF * (CC + 1) * 32;
     if (lds > 160 * 1024) return PCONV_EUNSUPPORTED;
     PCONV_HIP(allow_big_lds((const void*)kern, lds));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), lds, stream, p);
@@ -519,7 +492,9 @@ static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int CPW, h
 
 template <typename T>
 static int launch_tiled(TiledParams& p, int NF, int waves, int CPW, hipStream_t stream) {
-    if ((CPW * waves) % kBucket != 0) return PCONV_EUNSUPPORTED;   // a chunk is a whole number of buckets
+    const int CC = CPW * waves;
+    if (CC % kBucket != 0) return PCONV_EUNSUPPORTED;   // a chunk is a whole number of buckets
+    const int NB = CC / kBucket;
     // tile geometry
     const int Wo = p.Wo, Ho = p.Ho;
     const int ncs = (Wo + 61) / 62;
@@ -536,11 +511,13 @@ static int launch_tiled(TiledParams& p, int NF, int waves, int CPW, hipStream_t 
     const long long nb = (long long)slots * p.NG;
     if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
     p.nblocks = (int)nb;
-#define PCONV_CASE(FF, PP) \
-    if (NF == FF && CPW == PP) return launch_tiled_inst(tiled_kernel_nf##FF<PP, T>, p, waves, CPW, stream);
-    PCONV_CASE(1, 1) PCONV_CASE(1, 2) PCONV_CASE(1, 4)
-    PCONV_CASE(2, 1) PCONV_CASE(2, 2) PCONV_CASE(2, 4)
-    PCONV_CASE(3, 1) PCONV_CASE(3, 2)
+    // (filters per wave, channels per wave and chunk, buckets per chunk); waves = 16 * NB / CPW
+#define PCONV_CASE(FF, PP, BB) \
+    if (NF == FF && CPW == PP && NB == BB) \
+        return launch_tiled_inst(tiled_kernel_nf##FF<PP, BB, T>, p, waves, NF, CC, stream);
+    PCONV_CASE(1, 1, 1) PCONV_CASE(1, 2, 1) PCONV_CASE(1, 4, 1) PCONV_CASE(1, 2, 2) PCONV_CASE(1, 4, 2)
+    PCONV_CASE(2, 1, 1) PCONV_CASE(2, 2, 1) PCONV_CASE(2, 4, 1) PCONV_CASE(2, 2, 2) PCONV_CASE(2, 4, 2)
+    PCONV_CASE(3, 1, 1) PCONV_CASE(3, 2, 1) PCONV_CASE(3, 2, 2)
 #undef PCONV_CASE
     return PCONV_EUNSUPPORTED;
 }

@@ -227,7 +227,7 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
                         de.c = p->cin[cur];
                         de.mask9 = lib[j];
                         de.code = mask_rank(lib[j]);
-                        de.unused = 0;
+                        de.joff = de.code * (uint32_t)pconv::kLeafStride;
                         ++cur;
                     }
                 }

@@ -13,13 +13,16 @@ namespace pconv {
 // stages a chunk of 1, 2 or 4 consecutive buckets of activations in LDS at a time.
 constexpr int kBucket = 16;
 
+// Bytes between the code sections of two patterns in the tiled kernel's generated inner loop.
+constexpr int kLeafStride = 256;
+
 // One kept kernel in the device layout (32 bytes so that one scalar load of eight dwords fetches it).
 struct DevEntry {
     float w[4];       // the four kept weights, taps ascending, widened to fp32 (exact for fp16 storage)
     uint32_t c;       // input channel
+    uint32_t joff;    // code * kLeafStride: byte offset of the pattern's code section in the tiled kernel
     uint32_t mask9;   // the pattern mask itself (bit t = 3*ky + kx)
     uint32_t code;    // rank of the mask among the 126 masks with four of nine bits, ascending (0..125)
-    uint32_t unused;
 };
 static_assert(sizeof(DevEntry) == 32, "DevEntry must be 32 bytes");
 
