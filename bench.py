@@ -179,6 +179,14 @@ def main():
             _, ev = time_launches(torch, lambda: layer.launch(stream, **t), 300, 30)
             log(f"tune rows={r} nf={nf} waves={wv} cpw={cpw}: {ev * 1e3:8.2f} us  {macs / ev / 1e6:9.1f} GMAC/s")
 
+    # one plain device-to-device copy of known size (256 MiB read + 256 MiB written): the calibration point for the
+    # FETCH_SIZE / WRITE_SIZE counters when this command runs under rocprofv3 --pmc
+    calib = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    calib2 = torch.empty_like(calib)
+    calib2.copy_(calib)
+    torch.cuda.synchronize()
+    del calib, calib2
+
     wall_ms, ev_ms = time_launches(torch, lambda: layer.launch(stream), args.steps, args.warmup)
 
     # launch floor: an (almost) empty launch of the same entry point, for context at batch 1
@@ -213,7 +221,7 @@ def main():
                                f"({layer.n_kept} kept kernels)", "step": "one pconv_conv3x3 launch (weights packed once)"},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_VECTOR_TFLOPS,
-                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "tiled_kernel_config1_counters.txt")),
+                     "traffic": read_traffic(os.path.join(ROOT, "profiles", "tiled_kernel_config1_hbm_counters.txt")),
                      "kernel": "tiled_kernel", "kernel_ms": ev_ms, "flops_per_launch": flops,
                      "algorithmic_bytes_per_launch": abytes, "algorithmic_GBs": abytes / (ev_ms * 1e-3) / 1e9,
                      "hbm_frac_of_8TBs": abytes / (ev_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
@@ -245,11 +253,24 @@ def layer_table(args, torch, pc, L, stream):
         macs = effective_macs(spec, layer.n_kept)
         steps = max(10, min(1000, int(2e10 / max(macs, 1))))
         _, ev = time_launches(torch, lambda: layer.launch(stream), steps, max(3, steps // 10))
+        best = None
+        if args.tune and spec.stride == 1:
+            for nf, wv, cpw in [(1, 8, 2), (1, 8, 4), (1, 16, 1), (1, 16, 2), (2, 8, 2), (2, 8, 4), (2, 16, 1), (2, 16, 2),
+                                (3, 8, 2), (3, 16, 1), (3, 16, 2), (1, 4, 4), (2, 4, 4)]:
+                t = dict(kernel=pc.KERNEL_TILED, rows=7, filters_per_wave=nf, waves=wv, channels_per_wave=cpw)
+                try:
+                    _, tv = time_launches(torch, lambda: layer.launch(stream, **t), max(5, steps // 4), 2)
+                except pc.PconvError:
+                    continue
+                if best is None or tv < best[0]:
+                    best = (tv, nf, wv, cpw)
         ab = algorithmic_bytes(spec, layer.n_kept)
         row = {"layer": spec.name, "C": spec.C, "F": spec.F, "H": spec.H, "N": spec.N, "stride": spec.stride,
                "dtype": spec.dtype, "keep": spec.keep, "K": spec.K, "n_kept": layer.n_kept, "us": ev * 1e3,
                "eff_GMACs": macs / ev / 1e6, "alu_frac": 2 * macs / (ev * 1e-3) / 1e12 / PEAK_FP32_VECTOR_TFLOPS,
                "alg_GBs": ab / (ev * 1e-3) / 1e9, "hbm_frac": ab / (ev * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        if best:
+            row["best_us"], row["best_cfg"] = best[0] * 1e3, f"nf{best[1]}w{best[2]}c{best[3]}"
         if not args.no_dense:
             wm = np.where(layer.mask[:, :, None, None] != 0, layer.w, 0).astype(layer.w.dtype)
             dw = torch.from_numpy(np.ascontiguousarray(wm)).cuda()

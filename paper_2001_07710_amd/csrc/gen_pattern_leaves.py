@@ -64,7 +64,7 @@ def fetch_next(rg: Regs) -> list:
         f"v_add_u32 v{rg.va}, s64, %[vlane]",
         f"ds_read_b128 v[{x}:{x + 3}], v{rg.va}",
         f"ds_read_b128 v[{x + 4}:{x + 7}], v{rg.va} offset:16",
-        f"ds_read_b32 v{x + 8}, v{rg.va} offset:32",
+        f"ds_read_b128 v[{x + 8}:{x + 11}], v{rg.va} offset:32",
         f"ds_read_b128 v[{w}:{w + 3}], v{rg.ve}",
         f"v_add_u32 v{rg.ve}, 32, v{rg.ve}",
         "s_add_u32 s62, s60, s65",

@@ -583,9 +583,21 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     if (kernel == PCONV_KERNEL_TILED) {
         if (R == 0) R = kR;
         if (R != kR) return PCONV_EUNSUPPORTED;
+        if (waves == 0 && NF == 0 && CPW == 0) {
+            // Automatic tiling: as many filters per workgroup as still leaves enough workgroups to fill 256 CUs
+            // (more filters per workgroup = fewer re-reads of the same activations from L2).
+            const int ncs = (Wo + 61) / 62, ows = (Wo + ncs - 1) / ncs;
+            const int segs_per_wave = 64 / (ows + 2);
+            const long long nseg = (long long)N * ((Ho + kR - 1) / kR) * ((Wo + ows - 1) / ows);
+            const long long slots = (nseg + segs_per_wave - 1) / segs_per_wave;
+            auto blocks = [&](int nf, int w) { return slots * ((wp->F + nf * w - 1) / (nf * w)); };
+            if (blocks(2, 16) >= 512) { NF = 2; waves = 16; CPW = 2; }
+            else if (blocks(1, 16) >= 256) { NF = 1; waves = 16; CPW = 2; }
+            else { NF = 1; waves = 8; CPW = 4; }
+        }
         if (waves == 0) waves = 8;
         if (NF == 0) NF = 1;
-        if (CPW == 0) CPW = waves >= 16 ? 1 : 16 / waves;
+        if (CPW == 0) CPW = waves >= 16 ? 2 : 32 / waves;
         if (waves < 1 || waves > 16) return PCONV_EUNSUPPORTED;
         TiledParams p{};
         p.x = x;
