@@ -150,6 +150,7 @@ def main():
     ap.add_argument("--tune", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--only", default="", help="with --layers: only the layer of this name")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (batches shard over GPUs without any exchange)")
@@ -249,6 +250,8 @@ def layer_table(args, torch, pc, L, stream):
         sys.exit("unknown --layers")
     rows, tot_macs, tot_ms = [], 0, 0.0
     for spec in specs:
+        if args.only and spec.name != args.only:
+            continue
         layer = DeviceLayer(spec, batch_from_one_image=True)
         macs = effective_macs(spec, layer.n_kept)
         steps = max(10, min(1000, int(2e10 / max(macs, 1))))

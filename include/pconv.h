@@ -103,6 +103,17 @@ int pconv_packed_export(const pconv_packed* p, uint32_t* filter_order, uint32_t*
 /* Shape of a packed layer; any output pointer may be NULL. */
 int pconv_packed_stats(const pconv_packed* p, int* F, int* C, int* K, int* dtype, size_t* n_kept);
 
+/*
+ * Load balance of the tiled kernel's staging order (introspection, host).  The waves of a workgroup meet at a barrier
+ * after every chunk of 32 staged channels, so the wave with the most kept kernels in a chunk sets the pace.  For the
+ * tiling (waves, filters_per_wave) this returns the mean number of kept kernels per wave and chunk and the mean,
+ * over workgroups and chunks, of the maximum over the waves; their ratio is the share of the multiply phase that an
+ * average wave spends working.  balanced = 0: channels staged in their own order; 1: in the balanced order computed
+ * at pack time (PCONV_EUNSUPPORTED if the handle has none for this tiling).
+ */
+int pconv_packed_balance(const pconv_packed* p, int waves, int filters_per_wave, int balanced, double* mean_per_wave,
+                         double* mean_of_max);
+
 /* Releases host and device memory of a handle (NULL is allowed).  The caller makes sure no launch still uses it. */
 void pconv_free(pconv_packed* p);
 
@@ -133,15 +144,21 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *   waves             tiled: waves per workgroup, 1..16
  *   channels_per_wave tiled: channels each wave stages per chunk (1, 2 or 4); waves * channels_per_wave, the
  *                     channels resident in LDS at a time, must be a multiple of 16
+ *   channel_order     tiled: PCONV_ORDER_PLAIN stages the input channels in their own order; PCONV_ORDER_BALANCED
+ *                     uses the per-workgroup order computed at pack time that gives every wave the same number of
+ *                     kept kernels per chunk (exists for waves x filters_per_wave = 16x2, 16x1, 8x1 with 32
+ *                     channels per chunk); PCONV_ORDER_AUTO takes the balanced order where it exists
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
 enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2 };
+enum { PCONV_ORDER_AUTO = 0, PCONV_ORDER_PLAIN = 1, PCONV_ORDER_BALANCED = 2 };
 typedef struct pconv_tuning {
     int kernel;
     int rows;
     int filters_per_wave;
     int waves;
     int channels_per_wave;
+    int channel_order;
 } pconv_tuning;
 int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                         int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning);

@@ -17,6 +17,7 @@ F32, F16 = 0, 1
 FLAG_RELU = 1
 PACK_HOST_ONLY = 1
 KERNEL_AUTO, KERNEL_TILED, KERNEL_GENERIC = 0, 1, 2
+ORDER_AUTO, ORDER_PLAIN, ORDER_BALANCED = 0, 1, 2
 OK, EINVAL, EPATTERN, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -34,7 +35,7 @@ class PconvError(RuntimeError):
 
 class _Tuning(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int), ("rows", ctypes.c_int), ("filters_per_wave", ctypes.c_int),
-                ("waves", ctypes.c_int), ("channels_per_wave", ctypes.c_int)]
+                ("waves", ctypes.c_int), ("channels_per_wave", ctypes.c_int), ("channel_order", ctypes.c_int)]
 
 
 def ensure_built() -> str:
@@ -60,6 +61,8 @@ def _load():
     lib.pconv_packed_export.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_size_t)]
     lib.pconv_packed_stats.argtypes = [vp, ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
                                        ctypes.POINTER(ctypes.c_size_t)]
+    lib.pconv_packed_balance.argtypes = [vp, i, i, i, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.pconv_packed_balance.restype = i
     lib.pconv_free.argtypes = [vp]
     lib.pconv_free.restype = None
     lib.pconv_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp]
@@ -173,6 +176,14 @@ def packed_stats(p: Packed):
     return F.value, C.value, K.value, dt.value, int(n.value)
 
 
+def packed_balance(p: Packed, waves: int, filters_per_wave: int, balanced: bool):
+    """(mean kept kernels per wave and chunk, mean over chunks of the maximum over the waves)."""
+    a, b = ctypes.c_double(), ctypes.c_double()
+    _check(_load().pconv_packed_balance(p.handle, waves, filters_per_wave, int(balanced), ctypes.byref(a),
+                                        ctypes.byref(b)), "pconv_packed_balance")
+    return a.value, b.value
+
+
 def packed_export(p: Packed):
     n = p.n_kept
     fo = np.empty(p.F, dtype=np.uint32)
@@ -194,8 +205,8 @@ def conv3x3(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad
 
 def conv3x3_tuned(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad: int = 1, flags: int = 0,
                   stream: int = 0, kernel: int = 0, rows: int = 0, filters_per_wave: int = 0, waves: int = 0,
-                  channels_per_wave: int = 0):
-    t = _Tuning(kernel, rows, filters_per_wave, waves, channels_per_wave)
+                  channels_per_wave: int = 0, channel_order: int = 0):
+    t = _Tuning(kernel, rows, filters_per_wave, waves, channels_per_wave, channel_order)
     _check(_load().pconv_conv3x3_tuned(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, pad, flags,
                                        stream or None, ctypes.byref(t)), "pconv_conv3x3_tuned")
 

@@ -16,9 +16,9 @@ paper's section 6.2, emitted for every possible pattern ahead of time.
 
 Entries are read from LDS (the wave copied them there with the chunk); an entry is 8 dwords:
     w0 w1 w2 w3   the four kept weights, taps ascending (fp32)
-    lds_off       byte offset of the entry's channel inside the staged chunk
-    joff          pattern code * 256
-    (two unused)
+    header        low half: byte offset of the entry's channel inside the staged chunk, divided by 16;
+                  high half: pattern code
+    (three unused)
 
 Registers.  Accumulators: 3*R registers per filter slot, fixed, ending at v127 (slot s of a kernel with NF slots
 starts at v[128 - 3*R*(s+1)]); the kernel limits the compiler's own budget so that it never allocates them.  Scratch
@@ -59,8 +59,11 @@ def fetch_next(rg: Regs) -> list:
     """Header of the next entry has arrived: fetch its activations and weights, advance, jump to its section."""
     x, w, m = rg.x, rg.w, rg.m
     return [
-        f"v_readfirstlane_b32 s64, v{m}",
-        f"v_readfirstlane_b32 s65, v{m + 1}",
+        f"v_readfirstlane_b32 s65, v{m}",
+        "s_and_b32 s64, s65, 0xffff",
+        "s_lshl_b32 s64, s64, 4",
+        "s_lshr_b32 s65, s65, 16",
+        "s_lshl_b32 s65, s65, 8",
         f"v_add_u32 v{rg.va}, s64, %[vlane]",
         f"ds_read_b128 v[{x}:{x + 3}], v{rg.va}",
         f"ds_read_b128 v[{x + 4}:{x + 7}], v{rg.va} offset:16",
@@ -85,7 +88,6 @@ def entry_loop(nf: int, slot: int) -> list:
         "s_add_u32 s60, s60, 3f-1b",
         "s_addc_u32 s61, s61, 0",
         f"ds_read_b32 v{m}, v{rg.ve} offset:16",
-        f"ds_read_b32 v{m + 1}, v{rg.ve} offset:20",
         "s_waitcnt lgkmcnt(0)",
     ] + fetch_next(rg)
     for i, mask in enumerate(masks()):
@@ -95,7 +97,6 @@ def entry_loop(nf: int, slot: int) -> list:
         lines += [
             "s_waitcnt lgkmcnt(0)",
             f"ds_read_b32 v{m}, v{rg.ve} offset:16",
-            f"ds_read_b32 v{m + 1}, v{rg.ve} offset:20",
         ]
         q = 0
         for t in range(9):

@@ -54,6 +54,16 @@ int upload_packed(pconv_packed* p) {
     PCONV_HIP(hipMemcpy(p->d_eptr, p->eptr.data(), p->eptr.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     PCONV_HIP(hipMemcpy(p->d_forder, p->filter_order.data(), p->filter_order.size() * sizeof(uint32_t),
                         hipMemcpyHostToDevice));
+    for (BalancedLayout& b : p->balanced) {
+        PCONV_HIP(hipMalloc((void**)&b.d_ent, std::max<size_t>(b.ent.size(), 1) * sizeof(DevEntry)));
+        PCONV_HIP(hipMalloc((void**)&b.d_eptr, b.eptr.size() * sizeof(uint32_t)));
+        PCONV_HIP(hipMalloc((void**)&b.d_perm, std::max<size_t>(b.perm.size(), 1) * sizeof(uint32_t)));
+        if (!b.ent.empty())
+            PCONV_HIP(hipMemcpy(b.d_ent, b.ent.data(), b.ent.size() * sizeof(DevEntry), hipMemcpyHostToDevice));
+        PCONV_HIP(hipMemcpy(b.d_eptr, b.eptr.data(), b.eptr.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+        if (!b.perm.empty())
+            PCONV_HIP(hipMemcpy(b.d_perm, b.perm.data(), b.perm.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+    }
     p->device = dev;
     return PCONV_OK;
 }
@@ -62,6 +72,14 @@ void release_device(pconv_packed* p) {
     if (p->d_ent) (void)hipFree(p->d_ent);
     if (p->d_eptr) (void)hipFree(p->d_eptr);
     if (p->d_forder) (void)hipFree(p->d_forder);
+    for (BalancedLayout& b : p->balanced) {
+        if (b.d_ent) (void)hipFree(b.d_ent);
+        if (b.d_eptr) (void)hipFree(b.d_eptr);
+        if (b.d_perm) (void)hipFree(b.d_perm);
+        b.d_ent = nullptr;
+        b.d_eptr = nullptr;
+        b.d_perm = nullptr;
+    }
     p->d_ent = nullptr;
     p->d_eptr = nullptr;
     p->d_forder = nullptr;
@@ -144,7 +162,10 @@ struct TiledParams {
     const uint32_t* forder;
     const float* bias;
     int N, C, F, H, W, Ho, Wo, pad, relu;
-    int nbk;                 // channel buckets of the packed layout
+    const uint32_t* perm;    // [groups][perm_stride] channel staged at each position, or null for channel order
+    int perm_stride;
+    int nbk;                 // eptr entries per filter position (buckets of 16 channels, or chunks of a balanced layout)
+    int bpc;                 // eptr entries per chunk of the kernel (NB for buckets, 1 for a balanced layout)
     int LW, S, OWS, NCS, NRB, NSEG;
     int NG;                  // filter groups per slot
     int nblocks;             // NG * slots (the grid is padded to a multiple of 8)
@@ -259,23 +280,31 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     if constexpr (NF > 2) zero_acc<2>();
 
     const int pos_base = grp * (FW * NF) + wave;   // wave w takes positions pos_base + a*FW in the sorted filter order
-    const int nchunks = (p.C + CC - 1) / CC;
+    const int nchunks = p.perm ? p.nbk : (p.C + CC - 1) / CC;
 
     float pre[CPW][R + 2];       // the wave's share of the next chunk's activations, in flight
     uint2 epre[NF][NB];          // ... and of the next chunk's entries (lane l holds dwords 2l, 2l+1 of 16 entries)
     unsigned ecnt[NF];           // entries of each of the wave's filters in the chunk that is staged or in flight
 
+    // channel staged at position `pos` of this workgroup's staging order (kNoChannel: nothing to stage there)
+    auto channel_at = [&](int pos) -> unsigned {
+        if (pos >= nchunks * CC) return kNoChannel;
+        if (!p.perm) return pos < p.C ? (unsigned)pos : kNoChannel;
+        return scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + pos);
+    };
+    unsigned staged[CPW];        // channels in flight (kNoChannel: none)
     auto issue_loads = [&](int k) {
 #pragma unroll
         for (int j = 0; j < CPW; ++j) {
-            const int c = k * CC + wave + j * FW;
-            if (c < p.C) {
-                const unsigned soff = (unsigned)c * p.plane_bytes;
+            const unsigned c = channel_at(k * CC + wave + j * FW);
+            staged[j] = c;
+            if (c < (unsigned)p.C) {
+                const unsigned soff = c * p.plane_bytes;
 #pragma unroll
                 for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_f32<T>(rsrc, voff[i], soff);
             }
         }
-        const int b0 = k * NB, b1 = min(p.nbk, b0 + NB);
+        const int b0 = k * p.bpc, b1 = min(p.nbk, b0 + p.bpc);
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
             const int pos = pos_base + a * FW;
@@ -295,14 +324,14 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
 #pragma unroll
         for (int j = 0; j < CPW; ++j) {
             const int cc = wave + j * FW;
-            if (k * CC + cc < p.C) {
+            if (staged[j] < (unsigned)p.C) {
                 float* dst = reinterpret_cast<float*>(lds + cc * kChBytes + lane * (kPR * 4));
                 *reinterpret_cast<float4*>(dst + 0) = make_float4(pre[j][0], pre[j][1], pre[j][2], pre[j][3]);
                 *reinterpret_cast<float4*>(dst + 4) = make_float4(pre[j][4], pre[j][5], pre[j][6], pre[j][7]);
                 *reinterpret_cast<float4*>(dst + 8) = make_float4(pre[j][8], 0.f, 0.f, 0.f);
             }
         }
-        // entries: the channel (dword 4 of an entry) becomes the byte offset of that channel inside the chunk
+        // entries: channel and section offset (dwords 4, 5 of an entry) are packed into one header dword
         const unsigned c0 = (unsigned)k * CC;
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
@@ -311,7 +340,8 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             for (int j = 0; j < NB; ++j)
                 if ((unsigned)(lane >> 2) + 16u * j < ecnt[a]) {
                     uint2 v = epre[a][j];
-                    if ((lane & 3) == 2) v.x = (v.x - c0) * (unsigned)kChBytes;
+                    // header dword: LDS offset of the channel / 16 in the low half, pattern code in the high half
+                    if ((lane & 3) == 2) v.x = ((v.x - c0) * (unsigned)(kChBytes / 16)) | (v.y << 8);
                     dst[lane + 64 * j] = v;
                 }
         }
@@ -616,6 +646,23 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.pad = pad;
         p.relu = relu;
         p.nbk = wp->n_buckets;
+        p.bpc = (CPW * waves) / kBucket;
+        p.perm = nullptr;
+        p.perm_stride = 0;
+        // a balanced layout exists for the tilings of the automatic choice
+        const int order = tuning ? tuning->channel_order : PCONV_ORDER_AUTO;
+        if (order != PCONV_ORDER_PLAIN) {
+            for (const BalancedLayout& b : wp->balanced)
+                if (b.fw == waves && b.nf == NF && b.cc == CPW * waves && b.d_ent) {
+                    p.ent = b.d_ent;
+                    p.eptr = b.d_eptr;
+                    p.perm = b.d_perm;
+                    p.perm_stride = b.n_chunks * b.cc;
+                    p.nbk = b.n_chunks;
+                    p.bpc = 1;
+                }
+            if (order == PCONV_ORDER_BALANCED && !p.perm) return PCONV_EUNSUPPORTED;
+        }
         p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
         p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
         p.plane_bytes = (unsigned)((size_t)H * W * esize);

@@ -129,6 +129,108 @@ extern "C" int pconv_select_connectivity(const float* w, int F, int C, const uin
     return PCONV_OK;
 }
 
+namespace {
+
+// Builds the balanced layout of `p` for one tiling (see pconv::BalancedLayout).
+void build_balanced(const pconv_packed* p, int fw, int nf, int cc, pconv::BalancedLayout* out) {
+    const int F = p->F, C = p->C, K = p->K;
+    const int fg = fw * nf;
+    out->fw = fw;
+    out->nf = nf;
+    out->cc = cc;
+    out->n_groups = (F + fg - 1) / fg;
+    out->n_chunks = (C + cc - 1) / cc;
+    const int nch = out->n_chunks, npos = nch * cc;
+    out->perm.assign((size_t)out->n_groups * npos, pconv::kNoChannel);
+    out->ent.resize(p->n_kept);
+    out->eptr.assign((size_t)F * nch + 1, 0);
+
+    // kept kernels of every filter position as (channel, canonical entry index), from the canonical arrays
+    std::vector<std::vector<std::pair<uint16_t, uint32_t>>> kept((size_t)F);
+    for (int i = 0; i < F; ++i)
+        for (uint32_t e = p->grp_ptr[(size_t)i * K]; e < p->grp_ptr[(size_t)(i + 1) * K]; ++e)
+            kept[(size_t)i].push_back({p->cin[e], e});
+    std::vector<uint8_t> pattern_of(p->n_kept);
+    for (int i = 0; i < F; ++i)
+        for (int j = 0; j < K; ++j)
+            for (uint32_t e = p->grp_ptr[(size_t)i * K + j]; e < p->grp_ptr[(size_t)i * K + j + 1]; ++e)
+                pattern_of[e] = (uint8_t)j;
+
+    std::vector<uint32_t> pos_of((size_t)C);          // position of a channel in the group's staging order
+    std::vector<std::vector<uint8_t>> uses;           // [wave][channel] kept kernels of the wave's filters
+    size_t d = 0;
+    std::vector<std::vector<std::pair<uint32_t, uint32_t>>> per_chunk;   // scratch: (sort key, entry) per chunk
+    // entries must be emitted in filter-position order; groups are consecutive positions, so go group by group
+    for (int g = 0; g < out->n_groups; ++g) {
+        const int i0 = g * fg, i1 = std::min(F, i0 + fg);
+        uses.assign((size_t)fw, std::vector<uint8_t>((size_t)C, 0));
+        std::vector<uint32_t> weight((size_t)C, 0);
+        for (int i = i0; i < i1; ++i) {
+            const int w = (i - i0) % fw;                 // wave w holds positions i0 + w + a*fw
+            for (auto& ce : kept[(size_t)i]) {
+                ++uses[(size_t)w][ce.first];
+                ++weight[ce.first];
+            }
+        }
+        // channels by decreasing number of users (unused ones are dropped), then index
+        std::vector<uint32_t> order;
+        for (int c = 0; c < C; ++c)
+            if (weight[(size_t)c]) order.push_back((uint32_t)c);
+        std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return weight[a] > weight[b]; });
+        // greedy vector bin packing: put each channel into the chunk where the busiest wave stays least busy
+        std::vector<std::vector<uint32_t>> load((size_t)nch, std::vector<uint32_t>((size_t)fw, 0));
+        std::vector<uint32_t> fill((size_t)nch, 0), total((size_t)nch, 0);
+        std::vector<std::vector<uint32_t>> members((size_t)nch);
+        for (uint32_t c : order) {
+            int best = -1;
+            uint32_t best_max = 0, best_total = 0;
+            for (int k = 0; k < nch; ++k) {
+                if ((int)fill[(size_t)k] >= cc) continue;
+                uint32_t mx = 0;
+                for (int w = 0; w < fw; ++w) mx = std::max(mx, load[(size_t)k][(size_t)w] + uses[(size_t)w][c]);
+                if (best < 0 || mx < best_max || (mx == best_max && total[(size_t)k] < best_total)) {
+                    best = k;
+                    best_max = mx;
+                    best_total = total[(size_t)k];
+                }
+            }
+            for (int w = 0; w < fw; ++w) load[(size_t)best][(size_t)w] += uses[(size_t)w][c];
+            total[(size_t)best] += weight[c];
+            ++fill[(size_t)best];
+            members[(size_t)best].push_back(c);
+        }
+        for (int k = 0; k < nch; ++k) {
+            std::sort(members[(size_t)k].begin(), members[(size_t)k].end());
+            for (size_t m = 0; m < members[(size_t)k].size(); ++m) {
+                const uint32_t c = members[(size_t)k][m];
+                pos_of[c] = (uint32_t)(k * cc + (int)m);
+                out->perm[(size_t)g * npos + pos_of[c]] = c;
+            }
+        }
+        // entries of the group's filters: by chunk, then pattern, then position
+        for (int i = i0; i < i1; ++i) {
+            per_chunk.assign((size_t)nch, {});
+            for (auto& ce : kept[(size_t)i]) {
+                const uint32_t pos = pos_of[ce.first];
+                per_chunk[pos / (uint32_t)cc].push_back({((uint32_t)pattern_of[ce.second] << 20) | pos, ce.second});
+            }
+            for (int k = 0; k < nch; ++k) {
+                out->eptr[(size_t)i * nch + k] = (uint32_t)d;
+                auto& v = per_chunk[(size_t)k];
+                std::sort(v.begin(), v.end());
+                for (auto& ke : v) {
+                    pconv::DevEntry de = p->ent[p->ent_of_canonical[ke.second]];
+                    de.c = ke.first & 0xFFFFFu;
+                    out->ent[d++] = de;
+                }
+            }
+        }
+    }
+    out->eptr[(size_t)F * nch] = (uint32_t)d;
+}
+
+}  // namespace
+
 extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
                           const uint8_t* mask, unsigned flags, pconv_packed** out) {
     if (!out) return PCONV_EINVAL;
@@ -202,6 +304,7 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
         const int chunk = pconv::kBucket;
         p->n_buckets = (C + chunk - 1) / chunk;
         p->ent.resize(n_kept);
+        p->ent_of_canonical.resize(n_kept);
         p->eptr.assign((size_t)F * p->n_buckets + 1, 0);
         std::vector<uint32_t> cursor((size_t)K);
         size_t d = 0;
@@ -214,6 +317,7 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
                     const uint32_t g_end = p->grp_ptr[(size_t)i * K + j + 1];
                     uint32_t& cur = cursor[(size_t)j];
                     while (cur < g_end && (int)p->cin[cur] < c_end) {
+                        p->ent_of_canonical[cur] = (uint32_t)d;
                         pconv::DevEntry& de = p->ent[d++];
                         for (int q = 0; q < 4; ++q) {
                             if (dtype == PCONV_F16) {
@@ -234,6 +338,11 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
             }
         }
         p->eptr[(size_t)F * p->n_buckets] = (uint32_t)d;
+
+        // balanced layouts for the three tilings of the automatic choice (waves, filters per wave; chunks of 32)
+        static const int tilings[3][2] = {{16, 2}, {16, 1}, {8, 1}};
+        p->balanced.resize(3);
+        for (int t = 0; t < 3; ++t) build_balanced(p, tilings[t][0], tilings[t][1], 32, &p->balanced[(size_t)t]);
     } catch (const std::bad_alloc&) {
         delete p;
         return PCONV_ENOMEM;
@@ -259,6 +368,45 @@ extern "C" int pconv_packed_export(const pconv_packed* p, uint32_t* filter_order
     if (cin && !p->cin.empty()) std::memcpy(cin, p->cin.data(), p->cin.size() * sizeof(uint16_t));
     if (w4 && !p->w4.empty()) std::memcpy(w4, p->w4.data(), p->w4.size());
     if (n_kept) *n_kept = p->n_kept;
+    return PCONV_OK;
+}
+
+extern "C" int pconv_packed_balance(const pconv_packed* p, int waves, int filters_per_wave, int balanced,
+                                    double* mean_per_wave, double* mean_of_max) {
+    if (!p || !mean_per_wave || !mean_of_max) return PCONV_EINVAL;
+    if (waves < 1 || filters_per_wave < 1) return PCONV_EINVAL;
+    const int F = p->F, fg = waves * filters_per_wave, cc = 32;
+    const pconv::BalancedLayout* bl = nullptr;
+    for (const pconv::BalancedLayout& b : p->balanced)
+        if (b.fw == waves && b.nf == filters_per_wave && b.cc == cc) bl = &b;
+    if (balanced && !bl) return PCONV_EUNSUPPORTED;
+    const int nch = balanced ? bl->n_chunks : (p->C + cc - 1) / cc;
+    const int per = cc / pconv::kBucket;
+    auto count = [&](int pos, int k) -> uint32_t {
+        if (balanced) return bl->eptr[(size_t)pos * nch + k + 1] - bl->eptr[(size_t)pos * nch + k];
+        const int b0 = k * per, b1 = std::min(p->n_buckets, b0 + per);
+        return p->eptr[(size_t)pos * p->n_buckets + b1] - p->eptr[(size_t)pos * p->n_buckets + b0];
+    };
+    double sum = 0.0, sum_max = 0.0;
+    long long n_wave_chunks = 0, n_chunks = 0;
+    for (int g = 0; g * fg < F; ++g)
+        for (int k = 0; k < nch; ++k) {
+            uint32_t mx = 0;
+            for (int w = 0; w < waves; ++w) {
+                uint32_t load = 0;
+                for (int a = 0; a < filters_per_wave; ++a) {
+                    const int pos = g * fg + w + a * waves;
+                    if (pos < F) load += count(pos, k);
+                }
+                mx = std::max(mx, load);
+                sum += load;
+                ++n_wave_chunks;
+            }
+            sum_max += mx;
+            ++n_chunks;
+        }
+    *mean_per_wave = n_wave_chunks ? sum / (double)n_wave_chunks : 0.0;
+    *mean_of_max = n_chunks ? sum_max / (double)n_chunks : 0.0;
     return PCONV_OK;
 }
 

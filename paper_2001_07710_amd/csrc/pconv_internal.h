@@ -26,6 +26,25 @@ struct DevEntry {
 };
 static_assert(sizeof(DevEntry) == 32, "DevEntry must be 32 bytes");
 
+// A device layout for one tiling of the tiled kernel (FW waves per workgroup, NF filters per wave, chunks of CC
+// channels).  The filters of a workgroup (FW*NF consecutive positions of filter_order) share one order in which the
+// input channels are staged; that order is chosen, per workgroup, so that every wave finds (nearly) the same number
+// of kept kernels in every chunk: the waves of a workgroup meet at a barrier per chunk, so the slowest one sets the
+// pace.  This is the kernel re-ordering for load balance of section 6.2 of the paper, applied to channels.
+// Channels that no filter of the workgroup keeps are not staged at all.
+struct BalancedLayout {
+    int fw = 0, nf = 0, cc = 0;
+    int n_groups = 0, n_chunks = 0;
+    std::vector<DevEntry> ent;       // [n_kept]; DevEntry::c is the POSITION of the channel in the staging order
+    std::vector<uint32_t> eptr;      // [F*n_chunks + 1]: entries of (filter position i, chunk k)
+    std::vector<uint32_t> perm;      // [n_groups][n_chunks*cc]: channel staged at each position, 0xFFFFFFFF = none
+    DevEntry* d_ent = nullptr;
+    uint32_t* d_eptr = nullptr;
+    uint32_t* d_perm = nullptr;
+};
+
+constexpr uint32_t kNoChannel = 0xFFFFFFFFu;
+
 }  // namespace pconv
 
 struct pconv_packed {
@@ -43,6 +62,10 @@ struct pconv_packed {
     int n_buckets = 0;
     std::vector<pconv::DevEntry> ent;     // [n_kept]
     std::vector<uint32_t> eptr;           // [F*n_buckets + 1]: entries of (i, bucket) are eptr[i*n_buckets+bucket] ..
+    std::vector<uint32_t> ent_of_canonical;   // [n_kept]: index in `ent` of each canonical entry
+
+    // balanced layouts for the tilings that the automatic choice uses (see pconv::BalancedLayout)
+    std::vector<pconv::BalancedLayout> balanced;
 
     // device copies (null when packed host-only)
     int device = -1;

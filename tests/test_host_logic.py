@@ -164,3 +164,21 @@ def test_error_codes():
     assert "pattern" in pc.strerror(pc.EPATTERN)
     p.free()
     raw.pconv_free(None)
+
+
+def test_balanced_staging_order_evens_out_the_waves():
+    spec = L.shrink(L.config1(), C=128, F=64)
+    w, lib = _layer(spec)
+    pid = pc.assign_patterns(w, lib)
+    mask = pc.select_connectivity(w, lib, pid, spec.keep)
+    p = pc.pack(w, lib, pid, mask, pc.PACK_HOST_ONLY)
+    for waves, nf in ((16, 2), (16, 1), (8, 1)):
+        mean_plain, max_plain = pc.packed_balance(p, waves, nf, False)
+        mean_bal, max_bal = pc.packed_balance(p, waves, nf, True)
+        # same kernels, same number of wave-chunks: the mean cannot move; the slowest wave per chunk gets faster
+        assert abs(mean_plain - mean_bal) < 1e-9
+        assert max_bal <= max_plain and max_bal >= mean_bal
+        assert mean_bal / max_bal > 0.8
+    with pytest.raises(pc.PconvError):
+        pc.packed_balance(p, 4, 1, True)
+    p.free()
