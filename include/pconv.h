@@ -140,7 +140,7 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *   kernel            PCONV_KERNEL_TILED (stride 1 only: activations staged in LDS, weights in scalar registers)
  *                     or PCONV_KERNEL_GENERIC (any stride and pad, straight from global memory)
  *   rows              tiled: output rows held per lane (7)
- *   filters_per_wave  tiled: filters accumulated at once by one wave (1, 2 or 3)
+ *   filters_per_wave  tiled: filters accumulated at once by one wave (1 or 2)
  *   waves             tiled: waves per workgroup, 1..16
  *   channels_per_wave tiled: channels each wave stages per chunk (1, 2 or 4); waves * channels_per_wave, the
  *                     channels resident in LDS at a time, must be a multiple of 16

@@ -2,35 +2,39 @@
 """Generates pattern_leaves.inc: the inner loop of the tiled kernel as inline-assembly text for gfx950.
 
 One block (macro PCONV_ENTRY_LOOP_NF<n>_S<slot>) runs all kept kernels ("entries") that one filter has in the staged
-channel chunk.  It is threaded code: for each of the 126 masks with four of nine taps (ascending mask value =
-pattern code 0..125) there is one 256-byte-aligned section that
+channel chunk.  It is threaded code, software-pipelined one entry deep over two register sets A and B: for each of
+the 126 masks with four of nine taps (ascending mask value = pattern code 0..125) there are two 256-byte-aligned
+sections, one per register set.  The section of entry i (set P, the other set is Q)
 
-    waits for the entry's activations and weights (LDS reads issued by the previous section),
-    starts the LDS read of the next entry's header,
-    does the 4*R multiply-adds of its pattern:   acc[kx][r] += w[q] * x[r + ky]   for every kept tap t = 3*ky + kx,
-    then fetches the next entry's activations and weights and jumps straight to that entry's section
-    (s_setpc to table + code*256), or leaves the loop after the last entry.
+    waits for what the section before it requested: activations and weights of entry i (in P), header of entry i+1,
+    requests from LDS the activations and weights of entry i+1 (into Q) and the header of entry i+2,
+    does the 4*R multiply-adds of its pattern on P:   acc[kx][r] += w[q] * x[r + ky]   for every kept tap t = 3*ky + kx,
+    and jumps straight to the section of entry i+1's pattern for set Q (s_setpc to table_Q + code*256), or leaves
+    the loop after the last entry.
 
-So a kept kernel costs one jump and no branch tree, and a wave never diverges: the per-pattern access code of the
-paper's section 6.2, emitted for every possible pattern ahead of time.
+So a kept kernel costs one jump and no branch tree, a wave never diverges, and the LDS latency of an entry is covered
+by the multiply-adds of the entry before it: the per-pattern access code of the paper's section 6.2, emitted for
+every possible pattern ahead of time.
 
 Entries are read from LDS (the wave copied them there with the chunk); an entry is 8 dwords:
     w0 w1 w2 w3   the four kept weights, taps ascending (fp32)
-    header        low half: byte offset of the entry's channel inside the staged chunk, divided by 16;
-                  high half: pattern code
+    header        bits 0..7: index of the entry's channel inside the staged chunk; bits 8..: pattern code
     (three unused)
+The loop reads up to two entries past the last one (a header, four weights, one patch); the channel index is masked
+to the chunk size, so these reads stay inside the workgroup's LDS whatever the bytes there, and nothing uses them.
 
 Registers.  Accumulators: 3*R registers per filter slot, fixed, ending at v127 (slot s of a kernel with NF slots
 starts at v[128 - 3*R*(s+1)]); the kernel limits the compiler's own budget so that it never allocates them.  Scratch
-registers of the loop (activations x0..x11, weights, header, addresses) are fixed too, directly below the
-accumulators of the last slot; they are listed as clobbered, so the compiler keeps nothing there across the block.
-Scalar scratch: s[60:66].
+registers of the loop (activations x0..x9 and weights of both sets, header, addresses) are fixed too, directly below
+the accumulators of the last slot; they are listed as clobbered, so the compiler keeps nothing there across the
+block.  Scalar scratch: s[58:66].
 """
 import sys
 
 TOP = 128   # one past the highest vector register of the kernel (four waves per SIMD on a 512-entry file)
 R = 7
 LEAF_ALIGN_LOG2 = 8
+CH_BYTES = 64 * 12 * 4   # one staged channel in LDS: 64 lanes x 12 patch rows
 
 
 def masks():
@@ -46,32 +50,40 @@ class Regs:
 
     def __init__(self, nf: int):
         low = acc_base(nf - 1)
-        self.x = (low - 12) & ~1   # x0..x11 (x9..x11 are never read); register tuples start at even registers
-        self.w = self.x - 4        # w0..w3
-        self.m = self.w - 2        # header: lds_off, joff
-        self.va = self.m - 1       # LDS address of the activations
-        self.ve = self.m - 2       # LDS address of the next entry
+        xa = (low - 10) & ~1            # x0..x9 (x9 is never read); register tuples start at even registers
+        self.x = (xa, xa - 10)
+        self.w = (xa - 14, xa - 18)     # w0..w3 of each set
+        self.m = xa - 19                # header of the entry after the next
+        self.va = xa - 20               # LDS address of the activations
+        self.ve = xa - 21               # LDS address of the next entry
         self.first = self.ve
         self.count = low - self.first
 
 
-def fetch_next(rg: Regs) -> list:
-    """Header of the next entry has arrived: fetch its activations and weights, advance, jump to its section."""
-    x, w, m = rg.x, rg.w, rg.m
+def request_next(rg: Regs, q: int) -> list:
+    """The header of the next entry is in v[m]: request that entry's activations and weights into set q and the
+    header of the entry after it.  Leaves the next entry's section offset in s65."""
+    x, w = rg.x[q], rg.w[q]
     return [
-        f"v_readfirstlane_b32 s65, v{m}",
-        "s_and_b32 s64, s65, 0xffff",
-        "s_lshl_b32 s64, s64, 4",
-        "s_lshr_b32 s65, s65, 16",
-        "s_lshl_b32 s65, s65, 8",
+        f"v_readfirstlane_b32 s65, v{rg.m}",
+        "s_and_b32 s64, s65, %[ccmask]",
+        f"s_mul_i32 s64, s64, {CH_BYTES}",
         f"v_add_u32 v{rg.va}, s64, %[vlane]",
         f"ds_read_b128 v[{x}:{x + 3}], v{rg.va}",
         f"ds_read_b128 v[{x + 4}:{x + 7}], v{rg.va} offset:16",
-        f"ds_read_b128 v[{x + 8}:{x + 11}], v{rg.va} offset:32",
+        f"ds_read_b64 v[{x + 8}:{x + 9}], v{rg.va} offset:32",
         f"ds_read_b128 v[{w}:{w + 3}], v{rg.ve}",
+        f"ds_read_b32 v{rg.m}, v{rg.ve} offset:48",
         f"v_add_u32 v{rg.ve}, 32, v{rg.ve}",
-        "s_add_u32 s62, s60, s65",
-        "s_addc_u32 s63, s61, 0",
+        "s_and_b32 s65, s65, 0xffffff00",
+    ]
+
+
+def jump(q: int) -> list:
+    base = 60 if q == 0 else 58
+    return [
+        f"s_add_u32 s62, s{base}, s65",
+        f"s_addc_u32 s63, s{base + 1}, 0",
         "s_setpc_b64 s[62:63]",
     ]
 
@@ -79,38 +91,37 @@ def fetch_next(rg: Regs) -> list:
 def entry_loop(nf: int, slot: int) -> list:
     rg = Regs(nf)
     base = acc_base(slot)
-    m = rg.m
+    ms = masks()
     lines = [
-        "s_mov_b32 s66, %[cnt]",
+        "s_sub_u32 s66, %[cnt], 1",                    # entries still to run after the current one
         f"v_mov_b32 v{rg.ve}, %[ventry]",
         "s_getpc_b64 s[60:61]",
         "1:",
-        "s_add_u32 s60, s60, 3f-1b",
+        "s_add_u32 s60, s60, 3f-1b",                   # s[60:61]: sections of set A
         "s_addc_u32 s61, s61, 0",
-        f"ds_read_b32 v{m}, v{rg.ve} offset:16",
+        f"s_add_u32 s58, s60, {len(ms) << LEAF_ALIGN_LOG2}",   # s[58:59]: sections of set B
+        "s_addc_u32 s59, s61, 0",
+        f"ds_read_b32 v{rg.m}, v{rg.ve} offset:16",
         "s_waitcnt lgkmcnt(0)",
-    ] + fetch_next(rg)
-    for i, mask in enumerate(masks()):
-        lines.append(f".p2align {LEAF_ALIGN_LOG2}")
-        if i == 0:
-            lines.append("3:")
-        lines += [
-            "s_waitcnt lgkmcnt(0)",
-            f"ds_read_b32 v{m}, v{rg.ve} offset:16",
-        ]
-        q = 0
-        for t in range(9):
-            if (mask >> t) & 1:
-                ky, kx = divmod(t, 3)
-                for r in range(R):
-                    lines.append(f"v_fmac_f32 v{base + kx * R + r}, v{rg.w + q}, v{rg.x + r + ky}")
-                q += 1
-        lines += [
-            "s_sub_u32 s66, s66, 1",
-            "s_cmp_eq_u32 s66, 0",
-            "s_cbranch_scc1 9f",
-            "s_waitcnt lgkmcnt(0)",
-        ] + fetch_next(rg)
+    ] + request_next(rg, 0) + jump(0)
+    for p in (0, 1):
+        for i, mask in enumerate(ms):
+            lines.append(f".p2align {LEAF_ALIGN_LOG2}")
+            if p == 0 and i == 0:
+                lines.append("3:")
+            lines.append("s_waitcnt lgkmcnt(0)")
+            lines += request_next(rg, 1 - p)
+            q = 0
+            for t in range(9):
+                if (mask >> t) & 1:
+                    ky, kx = divmod(t, 3)
+                    for r in range(R):
+                        lines.append(f"v_fmac_f32 v{base + kx * R + r}, v{rg.w[p] + q}, v{rg.x[p] + r + ky}")
+                    q += 1
+            lines += [
+                "s_sub_u32 s66, s66, 1",               # borrow: this was the last entry
+                "s_cbranch_scc1 9f",
+            ] + jump(1 - p)
     lines += [f".p2align {LEAF_ALIGN_LOG2}", "9:", "s_waitcnt lgkmcnt(0)"]
     return lines
 
@@ -122,7 +133,7 @@ def as_c_string(lines: list) -> str:
 def clobbers(nf: int, slot: int) -> str:
     rg = Regs(nf)
     regs = [f'"v{rg.first + i}"' for i in range(rg.count)] + [f'"v{acc_base(slot) + i}"' for i in range(3 * R)]
-    regs += [f'"s{i}"' for i in range(60, 67)] + ['"scc"']
+    regs += [f'"s{i}"' for i in range(58, 67)] + ['"scc"']
     return ", ".join(regs)
 
 
@@ -136,7 +147,7 @@ def main(out_path: str):
         out.append(f"#define PCONV_ACC_ZERO_S{s} " + " ".join(f'"v_mov_b32 v{b + i}, 0\\n"' for i in range(3 * R)))
         out.append(f"#define PCONV_ACC_READ_S{s} " + " ".join(f'"v_mov_b32 %{i}, v{b + i}\\n"' for i in range(3 * R)))
         out.append("")
-    for nf in (1, 2, 3):
+    for nf in (1, 2):
         out.append(f"#define PCONV_SCRATCH_FIRST_NF{nf} {Regs(nf).first}")
         for s in range(nf):
             out.append(f"#define PCONV_ENTRY_LOOP_NF{nf}_S{s} \\\n    {as_c_string(entry_loop(nf, s))}")

@@ -206,20 +206,17 @@ __device__ __forceinline__ void read_acc(float (&a)[3][kR]) {
 
 // Runs `count` (>= 1) entries stored in LDS from byte address `entry_addr` on, for the filter in slot SLOT of a
 // kernel with NF slots.  `lane_addr` is the LDS byte address of this lane's patch of channel 0 of the chunk.
-template <int NF, int SLOT>
+template <int NF, int SLOT, int CC>
 __device__ __forceinline__ void run_entries(unsigned lane_addr, unsigned entry_addr, unsigned count) {
     const unsigned cnt = __builtin_amdgcn_readfirstlane(count);
 #define PCONV_LOOP(NFv, Sv)                                                                     \
     asm volatile(PCONV_ENTRY_LOOP_NF##NFv##_S##Sv                                               \
                  :                                                                              \
-                 : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr), [cnt] "s"(cnt)             \
+                 : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr), [cnt] "s"(cnt), [ccmask] "n"(CC - 1) \
                  : "memory", PCONV_ENTRY_LOOP_CLOBBERS_NF##NFv##_S##Sv)
     if constexpr (NF == 1) { PCONV_LOOP(1, 0); }
     else if constexpr (NF == 2 && SLOT == 0) { PCONV_LOOP(2, 0); }
-    else if constexpr (NF == 2 && SLOT == 1) { PCONV_LOOP(2, 1); }
-    else if constexpr (NF == 3 && SLOT == 0) { PCONV_LOOP(3, 0); }
-    else if constexpr (NF == 3 && SLOT == 1) { PCONV_LOOP(3, 1); }
-    else { PCONV_LOOP(3, 2); }
+    else { PCONV_LOOP(2, 1); }
 #undef PCONV_LOOP
 }
 
@@ -229,10 +226,12 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     constexpr int CC = 16 * NB;          // channels per chunk
     constexpr int FW = CC / CPW;         // waves per workgroup
     static_assert(CC % CPW == 0 && (FW == 4 || FW == 8 || FW == 16), "bad tiling");
-    static_assert(NF >= 1 && NF <= 3, "one to three filters per wave");
-    constexpr unsigned kEntRegion = (CC + 1) * 32;          // bytes of LDS for the entries of one filter and chunk
+    static_assert(NF >= 1 && NF <= 2, "one or two filters per wave");
+    static_assert(CC == 16 || CC == 32, "the section code masks the channel index to the chunk size");
+    // bytes of LDS for the entries of one filter and chunk; the loop reads (and ignores) up to two entries past the last
+    constexpr unsigned kEntRegion = (CC + 2) * 32;
     constexpr unsigned kEntBase = CC * kChBytes;             // entries start behind the tile
-    extern __shared__ __align__(16) unsigned char lds[];     // [CC][64][12] floats, then [FW][NF][CC+1] entries
+    extern __shared__ __align__(16) unsigned char lds[];     // [CC][64][12] floats, then [FW][NF][CC+2] entries
     const unsigned lds0 = (unsigned)(unsigned long long)lds; // LDS byte address of the allocation (low 32 bits)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -277,7 +276,6 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     const unsigned lane_addr = lds0 + lane * (kPR * 4);
     if constexpr (NF > 0) zero_acc<0>();
     if constexpr (NF > 1) zero_acc<1>();
-    if constexpr (NF > 2) zero_acc<2>();
 
     const int pos_base = grp * (FW * NF) + wave;   // wave w takes positions pos_base + a*FW in the sorted filter order
     const int nchunks = p.perm ? p.nbk : (p.C + CC - 1) / CC;
@@ -331,19 +329,13 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
                 *reinterpret_cast<float4*>(dst + 8) = make_float4(pre[j][8], 0.f, 0.f, 0.f);
             }
         }
-        // entries: channel and section offset (dwords 4, 5 of an entry) are packed into one header dword
-        const unsigned c0 = (unsigned)k * CC;
+        // entries, as they are
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
             uint2* dst = reinterpret_cast<uint2*>(lds + kEntBase + (wave * NF + a) * kEntRegion);
 #pragma unroll
             for (int j = 0; j < NB; ++j)
-                if ((unsigned)(lane >> 2) + 16u * j < ecnt[a]) {
-                    uint2 v = epre[a][j];
-                    // header dword: LDS offset of the channel / 16 in the low half, pattern code in the high half
-                    if ((lane & 3) == 2) v.x = ((v.x - c0) * (unsigned)(kChBytes / 16)) | (v.y << 8);
-                    dst[lane + 64 * j] = v;
-                }
+                if ((unsigned)(lane >> 2) + 16u * j < ecnt[a]) dst[lane + 64 * j] = epre[a][j];
         }
     };
 
@@ -357,9 +349,8 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
         for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
         if (more) issue_loads(k + 1);
         const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
-        if constexpr (NF > 0) { if (cnt_now[0]) run_entries<NF, 0>(lane_addr, ent_addr + 0 * kEntRegion, cnt_now[0]); }
-        if constexpr (NF > 1) { if (cnt_now[1]) run_entries<NF, 1>(lane_addr, ent_addr + 1 * kEntRegion, cnt_now[1]); }
-        if constexpr (NF > 2) { if (cnt_now[2]) run_entries<NF, 2>(lane_addr, ent_addr + 2 * kEntRegion, cnt_now[2]); }
+        if constexpr (NF > 0) { if (cnt_now[0]) run_entries<NF, 0, CC>(lane_addr, ent_addr + 0 * kEntRegion, cnt_now[0]); }
+        if constexpr (NF > 1) { if (cnt_now[1]) run_entries<NF, 1, CC>(lane_addr, ent_addr + 1 * kEntRegion, cnt_now[1]); }
         __syncthreads();           // every wave is done reading chunk k
         if (more) {
             write_lds(k + 1);
@@ -388,7 +379,6 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     float acc[3][R];
     if constexpr (NF > 0) { read_acc<0>(acc); store_filter(acc, pos_base + 0 * FW); }
     if constexpr (NF > 1) { read_acc<1>(acc); store_filter(acc, pos_base + 1 * FW); }
-    if constexpr (NF > 2) { read_acc<2>(acc); store_filter(acc, pos_base + 2 * FW); }
 }
 
 // The compiler may allocate 2*n vector registers under amdgpu_num_vgpr(n) on this target; the accumulators of the
@@ -402,11 +392,6 @@ template <int CPW, int NB, typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(43))) void tiled_kernel_nf2(const TiledParams p) {
     static_assert(PCONV_ACC_BASE_S1 >= 2 * 43, "accumulators overlap the compiler's registers");
     tiled_body<2, CPW, NB, T>(p);
-}
-template <int CPW, int NB, typename T>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(32))) void tiled_kernel_nf3(const TiledParams p) {
-    static_assert(PCONV_ACC_BASE_S2 >= 2 * 32, "accumulators overlap the compiler's registers");
-    tiled_body<3, CPW, NB, T>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -512,7 +497,7 @@ static hipError_t allow_big_lds(const void* fn, size_t lds) {
 template <typename K>
 static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int NF, int CC, hipStream_t stream) {
     const int grid = (p.nblocks + 7) / 8 * 8;
-    const size_t lds = (size_t)CC * kChBytes + (size_t)waves * NF * (CC + 1) * 32;
+    const size_t lds = (size_t)CC * kChBytes + (size_t)waves * NF * (CC + 2) * 32;
     if (lds > 160 * 1024) return PCONV_EUNSUPPORTED;
     PCONV_HIP(allow_big_lds((const void*)kern, lds));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), lds, stream, p);
@@ -546,8 +531,7 @@ static int launch_tiled(TiledParams& p, int NF, int waves, int CPW, hipStream_t 
     if (NF == FF && CPW == PP && NB == BB) \
         return launch_tiled_inst(tiled_kernel_nf##FF<PP, BB, T>, p, waves, NF, CC, stream);
     PCONV_CASE(1, 1, 1) PCONV_CASE(1, 2, 1) PCONV_CASE(1, 4, 1) PCONV_CASE(1, 2, 2) PCONV_CASE(1, 4, 2)
-    PCONV_CASE(2, 1, 1) PCONV_CASE(2, 2, 1) PCONV_CASE(2, 4, 1) PCONV_CASE(2, 2, 2) PCONV_CASE(2, 4, 2)
-    PCONV_CASE(3, 1, 1) PCONV_CASE(3, 2, 1) PCONV_CASE(3, 2, 2)
+    PCONV_CASE(2, 1, 1) PCONV_CASE(2, 2, 1) PCONV_CASE(2, 2, 2)
 #undef PCONV_CASE
     return PCONV_EUNSUPPORTED;
 }

@@ -221,6 +221,7 @@ void build_balanced(const pconv_packed* p, int fw, int nf, int cc, pconv::Balanc
                 for (auto& ke : v) {
                     pconv::DevEntry de = p->ent[p->ent_of_canonical[ke.second]];
                     de.c = ke.first & 0xFFFFFu;
+                    de.hdr = (de.c & 0xFFu) | (de.code << 8);
                     out->ent[d++] = de;
                 }
             }
@@ -331,7 +332,7 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
                         de.c = p->cin[cur];
                         de.mask9 = lib[j];
                         de.code = mask_rank(lib[j]);
-                        de.joff = de.code * (uint32_t)pconv::kLeafStride;
+                        de.hdr = (de.c & 0xFFu) | (de.code << 8);
                         ++cur;
                     }
                 }

@@ -19,8 +19,10 @@ constexpr int kLeafStride = 256;
 // One kept kernel in the device layout (32 bytes so that one scalar load of eight dwords fetches it).
 struct DevEntry {
     float w[4];       // the four kept weights, taps ascending, widened to fp32 (exact for fp16 storage)
+    uint32_t hdr;     // what the tiled kernel's inner loop reads: bits 0..7 = c mod 256 (chunks are 16 or 32 channels
+                      // and start at multiples of their size, so the low bits are the index inside the chunk),
+                      // bits 8.. = code; code * kLeafStride is the byte offset of the pattern's code section
     uint32_t c;       // input channel
-    uint32_t joff;    // code * kLeafStride: byte offset of the pattern's code section in the tiled kernel
     uint32_t mask9;   // the pattern mask itself (bit t = 3*ky + kx)
     uint32_t code;    // rank of the mask among the 126 masks with four of nine bits, ascending (0..125)
 };

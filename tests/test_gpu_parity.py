@@ -18,8 +18,8 @@ pytestmark = pytest.mark.gpu
 
 T, G = pc.KERNEL_TILED, pc.KERNEL_GENERIC
 TILED_TUNINGS = [dict(kernel=T, rows=7, filters_per_wave=nf, waves=w, channels_per_wave=cpw)
-                 for nf, w, cpw in [(1, 8, 2), (2, 8, 2), (1, 16, 1), (1, 4, 4), (3, 8, 2), (2, 16, 1), (2, 4, 4), (1, 8, 4),
-                                    (3, 16, 1), (2, 16, 2), (1, 16, 2), (3, 16, 2), (2, 8, 4)]]
+                 for nf, w, cpw in [(1, 8, 2), (2, 8, 2), (1, 16, 1), (1, 4, 4), (2, 16, 1), (1, 8, 4),
+                                    (2, 16, 2), (1, 16, 2)]]
 ALL_TUNINGS = [dict(kernel=G)] + TILED_TUNINGS + [dict()]
 
 
