@@ -130,6 +130,13 @@ void pconv_free(pconv_packed* p);
  *   flags   0 or PCONV_FLAG_RELU
  *   stream  a hipStream_t passed as void* (NULL = the default stream)
  * Launch errors are returned; execution errors surface at the caller's next synchronisation.  N = 0 is a no-op.
+ *
+ * Workspace.  When a layer has too few output tiles to occupy the GPU (small batch, small feature map) the library
+ * splits the input channels of each tile over several workgroups, which add their partial sums in a workspace that
+ * belongs to the handle; the sum is taken in a fixed order, so results are reproducible run to run.  The workspace
+ * is allocated (hipMalloc, which synchronises) the first time a shape needs it and kept until pconv_free; a later
+ * call with the same or a smaller shape allocates nothing.  Because of it, calls that share one handle must not
+ * overlap in time: issue them on one stream, or order them with events.
  */
 int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W, int stride,
                   int pad, unsigned flags, void* stream);
@@ -148,6 +155,9 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *                     uses the per-workgroup order computed at pack time that gives every wave the same number of
  *                     kept kernels per chunk (exists for waves x filters_per_wave = 16x2, 16x1, 8x1 with 32
  *                     channels per chunk); PCONV_ORDER_AUTO takes the balanced order where it exists
+ *   channel_splits    tiled: workgroups that share one output tile, each taking a contiguous range of the channel
+ *                     chunks (1 = no split, no workspace; at most the number of chunks; 0 = as many as give one
+ *                     round of workgroups over the GPU's compute units)
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
 enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2 };
@@ -159,6 +169,7 @@ typedef struct pconv_tuning {
     int waves;
     int channels_per_wave;
     int channel_order;
+    int channel_splits;
 } pconv_tuning;
 int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                         int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning);

@@ -80,10 +80,37 @@ void release_device(pconv_packed* p) {
         b.d_eptr = nullptr;
         b.d_perm = nullptr;
     }
+    if (p->d_ws) (void)hipFree(p->d_ws);
+    if (p->d_counters) (void)hipFree(p->d_counters);
+    p->d_ws = nullptr;
+    p->ws_floats = 0;
+    p->d_counters = nullptr;
+    p->n_counters = 0;
     p->d_ent = nullptr;
     p->d_eptr = nullptr;
     p->d_forder = nullptr;
     p->device = -1;
+}
+
+// Makes the handle's workspace at least `floats` partial sums and `counters` arrival counters large.  Counters are
+// zero when allocated and every kernel leaves them zero.
+static int ensure_workspace(const pconv_packed* p, size_t floats, size_t counters) {
+    if (floats > p->ws_floats) {
+        if (p->d_ws) PCONV_HIP(hipFree(p->d_ws));   // hipFree waits for work that may still use it
+        p->d_ws = nullptr;
+        p->ws_floats = 0;
+        PCONV_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_ws), floats * sizeof(float)));
+        p->ws_floats = floats;
+    }
+    if (counters > p->n_counters) {
+        if (p->d_counters) PCONV_HIP(hipFree(p->d_counters));
+        p->d_counters = nullptr;
+        p->n_counters = 0;
+        PCONV_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_counters), counters * sizeof(unsigned)));
+        PCONV_HIP(hipMemset(p->d_counters, 0, counters * sizeof(unsigned)));
+        p->n_counters = counters;
+    }
+    return PCONV_OK;
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -168,7 +195,10 @@ struct TiledParams {
     int bpc;                 // eptr entries per chunk of the kernel (NB for buckets, 1 for a balanced layout)
     int LW, S, OWS, NCS, NRB, NSEG;
     int NG;                  // filter groups per slot
-    int nblocks;             // NG * slots (the grid is padded to a multiple of 8)
+    int KS;                  // workgroups that share one output tile, each taking a range of the channel chunks
+    float* ws;               // KS > 1: [KS][N][F][Ho][Wo] partial sums
+    unsigned* counters;      // KS > 1: [slots * NG] arrivals, zero between launches
+    int nblocks;             // NG * slots * KS (the grid is padded to a multiple of 8)
     unsigned long long x_bytes;
     unsigned img_bytes;      // C*H*W*sizeof(T)
     unsigned plane_bytes;    // H*W*sizeof(T)
@@ -241,8 +271,10 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     const int per_xcd = gridDim.x >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= p.nblocks) return;
-    const int slot = logical / p.NG;
-    const int grp = logical - slot * p.NG;
+    const int tile = p.KS == 1 ? logical : logical / p.KS;     // (slot, filter group)
+    const int split = logical - tile * p.KS;
+    const int slot = tile / p.NG;
+    const int grp = tile - slot * p.NG;
 
     // lane -> (segment, column)
     const int s_local = lane / p.LW;
@@ -278,7 +310,20 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     if constexpr (NF > 1) zero_acc<1>();
 
     const int pos_base = grp * (FW * NF) + wave;   // wave w takes positions pos_base + a*FW in the sorted filter order
+    // the wave's filters and their biases, fetched now (scalar registers) so that the epilogue does not wait for them
+    unsigned filt[NF];
+    float filt_bias[NF];
+#pragma unroll
+    for (int a = 0; a < NF; ++a) {
+        const int pos = pos_base + a * FW;
+        filt[a] = pos < p.F ? scalar_load_u32(p.forder + pos) : 0u;
+        filt_bias[a] = (p.bias && pos < p.F)
+                           ? __builtin_bit_cast(float, scalar_load_u32(reinterpret_cast<const uint32_t*>(p.bias + filt[a])))
+                           : 0.f;
+    }
     const int nchunks = p.perm ? p.nbk : (p.C + CC - 1) / CC;
+    // this workgroup's range of chunks (all of them unless the channels are split)
+    const int k_begin = (int)((long long)split * nchunks / p.KS), k_end = (int)((long long)(split + 1) * nchunks / p.KS);
 
     float pre[CPW][R + 2];       // the wave's share of the next chunk's activations, in flight
     uint2 epre[NF][NB];          // ... and of the next chunk's entries (lane l holds dwords 2l, 2l+1 of 16 entries)
@@ -339,11 +384,11 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
         }
     };
 
-    issue_loads(0);
-    write_lds(0);
+    issue_loads(k_begin);
+    write_lds(k_begin);
     __syncthreads();
-    for (int k = 0; k < nchunks; ++k) {
-        const bool more = k + 1 < nchunks;
+    for (int k = k_begin; k < k_end; ++k) {
+        const bool more = k + 1 < k_end;
         unsigned cnt_now[NF];
 #pragma unroll
         for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
@@ -361,24 +406,115 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     // ---- epilogue: add the three accumulator sets across neighbouring lanes, bias, ReLU, store
     T* __restrict__ y = static_cast<T*>(p.y);
     const bool col_ok = active && t >= 1 && t <= p.OWS && ox < p.Wo;
-    auto store_filter = [&](const float (&acc)[3][R], int pos) {
-        if (pos >= p.F) return;   // uniform per wave
-        const unsigned f = p.forder[pos];
-        const float b = p.bias ? p.bias[f] : 0.f;
-        const size_t ybase = (((size_t)n * p.F + f) * p.Ho) * (size_t)p.Wo;
+    const size_t plane_out = (size_t)p.Ho * p.Wo;
+    auto combine = [&](const float (&acc)[3][R], float (&v)[R]) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const float from_left = __shfl_up(acc[0][r], 1, 64);     // lane t-1 holds column ix-1: its kx=0 sum
             const float from_right = __shfl_down(acc[2][r], 1, 64);  // lane t+1 holds column ix+1: its kx=2 sum
-            float v = acc[1][r] + from_left + from_right + b;
-            if (p.relu) v = fmaxf(v, 0.f);
-            const int oy = r0 + r;
-            if (col_ok && oy < p.Ho) y[ybase + (size_t)oy * p.Wo + ox] = from_f32<T>(v);
+            v[r] = acc[1][r] + from_left + from_right;
         }
     };
-    float acc[3][R];
-    if constexpr (NF > 0) { read_acc<0>(acc); store_filter(acc, pos_base + 0 * FW); }
-    if constexpr (NF > 1) { read_acc<1>(acc); store_filter(acc, pos_base + 1 * FW); }
+    auto store_filter = [&](const float (&v)[R], unsigned f, float b) {
+        const size_t ybase = ((size_t)n * p.F + f) * plane_out;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float o = v[r] + b;
+            if (p.relu) o = fmaxf(o, 0.f);
+            const int oy = r0 + r;
+            if (col_ok && oy < p.Ho) y[ybase + (size_t)oy * p.Wo + ox] = from_f32<T>(o);
+        }
+    };
+    float acc[3][R], v[R];
+    if (p.KS == 1) {
+#define PCONV_FINISH(a)                                                   \
+        if (pos_base + a * FW < p.F) {   /* uniform per wave */            \
+            read_acc<a>(acc);                                             \
+            combine(acc, v);                                              \
+            store_filter(v, filt[a], filt_bias[a]);                       \
+        }
+        if constexpr (NF > 0) { PCONV_FINISH(0) }
+        if constexpr (NF > 1) { PCONV_FINISH(1) }
+#undef PCONV_FINISH
+        return;
+    }
+
+    // The channels of this tile are split over KS workgroups.  Each writes its partial sums to the workspace; the one
+    // that arrives last adds them up, always in the order of the splits, so the result does not depend on which
+    // workgroup that is.
+    //
+    // Partial sums and the arrival counter are accessed with device-scope atomic (relaxed) stores, loads and adds
+    // only: such accesses are performed at the point where all compute units of the device agree, so no cache
+    // write-back or invalidation is needed (a device-scope fence here writes back and invalidates the whole L2 and
+    // costs more than the split saves).  Order: a wave's stores have been performed when its vmcnt is zero; the
+    // barrier puts that before the arrival is counted; the last workgroup's loads are issued after its count returned.
+    // The accesses go through buffer descriptors (one per split's partial sums) with the device-scope cache policy;
+    // lanes without an output get an offset outside the descriptor, so there is no branch per access.
+    const size_t split_stride = (size_t)p.N * p.F * plane_out;
+    constexpr int kDeviceScope = 16;   // cache-policy bit "sc1" of gfx942/gfx950 buffer instructions
+    auto ws_rsrc = [&](int s) { return make_rsrc(p.ws + (size_t)s * split_stride, (uint32_t)(split_stride * sizeof(float))); };
+    unsigned woff[R];
+    auto ws_offsets = [&](unsigned f) {
+        const unsigned at = ((unsigned)n * p.F + f) * (unsigned)plane_out + (unsigned)(r0 * p.Wo + ox);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            woff[r] = (col_ok && r0 + r < p.Ho) ? (at + (unsigned)(r * p.Wo)) * 4u : kInvalidOffset;
+    };
+    const __amdgpu_buffer_rsrc_t mine = ws_rsrc(split);
+#define PCONV_PARTIAL(a)                                                                            \
+    if (pos_base + a * FW < p.F) {                                                                  \
+        read_acc<a>(acc);                                                                           \
+        combine(acc, v);                                                                            \
+        ws_offsets(filt[a]);                                                                        \
+        _Pragma("unroll") for (int r = 0; r < R; ++r)                                               \
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[r]), mine, (int)woff[r], 0, kDeviceScope); \
+    }
+    if constexpr (NF > 0) { PCONV_PARTIAL(0) }
+    if constexpr (NF > 1) { PCONV_PARTIAL(1) }
+#undef PCONV_PARTIAL
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                 // (also: nobody reads the staged chunk any more, LDS can carry the flag)
+    volatile unsigned* flag = reinterpret_cast<volatile unsigned*>(lds);
+    if (threadIdx.x == 0) {
+        const unsigned arrived = __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = arrived == (unsigned)p.KS - 1u;
+        // everybody has arrived: leave the counter ready for the next launch
+        if (last) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *flag = last ? 1u : 0u;
+    }
+    __syncthreads();
+    if (*flag == 0u) return;
+    // partial sums of up to four splits are requested together, then added in split order
+#define PCONV_REDUCE(a)                                                                             \
+    if (pos_base + a * FW < p.F) {                                                                  \
+        read_acc<a>(acc);                                                                           \
+        combine(acc, v);                                                                            \
+        ws_offsets(filt[a]);                                                                        \
+        float sum[R];                                                                               \
+        _Pragma("unroll") for (int r = 0; r < R; ++r) sum[r] = 0.f;                                 \
+        for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
+            float part[4][R];                                                                       \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
+                const int s = min(s0 + j, p.KS - 1);                                                \
+                const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s);                                   \
+                _Pragma("unroll") for (int r = 0; r < R; ++r)                                       \
+                    part[j][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[r], 0, kDeviceScope)); \
+            }                                                                                       \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
+                const int s = s0 + j;                                                               \
+                if (s < p.KS) {                                                                     \
+                    _Pragma("unroll") for (int r = 0; r < R; ++r) {                                 \
+                        const float q = s == split ? v[r] : part[j][r];                             \
+                        sum[r] = s == 0 ? q : sum[r] + q;                                           \
+                    }                                                                               \
+                }                                                                                   \
+            }                                                                                       \
+        }                                                                                           \
+        store_filter(sum, filt[a], filt_bias[a]);                                                   \
+    }
+    if constexpr (NF > 0) { PCONV_REDUCE(0) }
+    if constexpr (NF > 1) { PCONV_REDUCE(1) }
+#undef PCONV_REDUCE
 }
 
 // The compiler may allocate 2*n vector registers under amdgpu_num_vgpr(n) on this target; the accumulators of the
@@ -506,7 +642,7 @@ static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int NF, in
 }
 
 template <typename T>
-static int launch_tiled(TiledParams& p, int NF, int waves, int CPW, hipStream_t stream) {
+static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int waves, int CPW, int KS, hipStream_t stream) {
     const int CC = CPW * waves;
     if (CC % kBucket != 0) return PCONV_EUNSUPPORTED;   // a chunk is a whole number of buckets
     const int NB = CC / kBucket;
@@ -523,9 +659,28 @@ static int launch_tiled(TiledParams& p, int NF, int waves, int CPW, hipStream_t 
     p.NSEG = (int)nseg;
     const int slots = (int)((nseg + p.S - 1) / p.S);
     p.NG = (p.F + waves * NF - 1) / (waves * NF);
-    const long long nb = (long long)slots * p.NG;
+    const int nchunks = p.perm ? p.nbk : (p.C + CC - 1) / CC;
+    if (KS == 0) {
+        // Automatic: one round of workgroups over the 256 CUs when the tiles alone are fewer than that
+        const long long tiles = (long long)slots * p.NG;
+        KS = (int)std::max<long long>(1, std::min<long long>(256 / std::max<long long>(tiles, 1), 16));
+        KS = std::min(KS, nchunks);
+    }
+    if (KS < 1 || KS > nchunks || KS > 64) return PCONV_EUNSUPPORTED;
+    const long long nb = (long long)slots * p.NG * KS;
     if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
     p.nblocks = (int)nb;
+    p.KS = KS;
+    p.ws = nullptr;
+    p.counters = nullptr;
+    if (KS > 1) {
+        const size_t floats = (size_t)KS * p.N * p.F * p.Ho * p.Wo;
+        // the kernel addresses one split's partial sums with 32-bit indices
+        if ((size_t)p.N * p.F * p.Ho * p.Wo >= ((size_t)1 << 30)) return PCONV_EUNSUPPORTED;
+        if (int rc = ensure_workspace(wp, floats, (size_t)slots * p.NG)) return rc;
+        p.ws = wp->d_ws;
+        p.counters = wp->d_counters;
+    }
     // (filters per wave, channels per wave and chunk, buckets per chunk); waves = 16 * NB / CPW
 #define PCONV_CASE(FF, PP, BB) \
     if (NF == FF && CPW == PP && NB == BB) \
@@ -590,6 +745,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     int kernel = tuning ? tuning->kernel : PCONV_KERNEL_AUTO;
     int R = tuning ? tuning->rows : 0, NF = tuning ? tuning->filters_per_wave : 0, waves = tuning ? tuning->waves : 0;
     int CPW = tuning ? tuning->channels_per_wave : 0;
+    int KS = tuning ? tuning->channel_splits : 0;
     const bool can_tile = tiled_applicable(N, wp->C, H, W, stride, esize);
     if (kernel == PCONV_KERNEL_AUTO) kernel = can_tile ? PCONV_KERNEL_TILED : PCONV_KERNEL_GENERIC;
     if (kernel == PCONV_KERNEL_TILED && !can_tile) return PCONV_EUNSUPPORTED;
@@ -598,17 +754,35 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         if (R == 0) R = kR;
         if (R != kR) return PCONV_EUNSUPPORTED;
         if (waves == 0 && NF == 0 && CPW == 0) {
-            // Automatic tiling: as many filters per workgroup as still leaves enough workgroups to fill 256 CUs
-            // (more filters per workgroup = fewer re-reads of the same activations from L2).
+            // Automatic tiling: the candidate with the smallest estimated time.  The estimate is a count of clocks
+            // per workgroup from measured phase costs of this kernel on MI355X (one workgroup per CU at a time):
+            // a fixed start-up, per chunk the larger of multiply-add issue and the global-load rate of the staging
+            // plus the LDS write and barriers, and the cost of combining partial sums when channels are split.
             const int ncs = (Wo + 61) / 62, ows = (Wo + ncs - 1) / ncs;
             const int segs_per_wave = 64 / (ows + 2);
             const long long nseg = (long long)N * ((Ho + kR - 1) / kR) * ((Wo + ows - 1) / ows);
             const long long slots = (nseg + segs_per_wave - 1) / segs_per_wave;
-            auto blocks = [&](int nf, int w) { return slots * ((wp->F + nf * w - 1) / (nf * w)); };
-            if (blocks(2, 16) >= 512) { NF = 2; waves = 16; CPW = 2; }
-            else if (blocks(1, 16) >= 256) { NF = 1; waves = 16; CPW = 2; }
-            else { NF = 1; waves = 8; CPW = 4; }
+            static const int cand[4][3] = {{2, 16, 2}, {1, 16, 2}, {1, 8, 4}, {2, 16, 1}};   // NF, waves, CPW
+            double best = 0.0;
+            for (int i = 0; i < 4; ++i) {
+                const int nf = cand[i][0], w = cand[i][1], cpw = cand[i][2], cc = w * cpw;
+                if (cc == 16 && wp->C > 16) continue;   // half-size chunks only pay for layers with few channels
+                const long long tiles = slots * ((wp->F + nf * w - 1) / (nf * w));
+                const int nch = (wp->C + cc - 1) / cc;
+                const double per_filter_chunk = (double)wp->n_kept / ((double)wp->F * nch);
+                for (int ks = 1; ks <= std::min(nch, 16); ks *= 2) {
+                    const double issue = (w / 4) * nf * per_filter_chunk * 128.0 + 750.0;
+                    const double staging = std::min(wp->C, cc) * 9.0 * 18.0;
+                    const double chunk = std::max(issue, staging) + 3400.0;
+                    const double combine = ks == 1 ? 1500.0 * nf : nf == 1 ? 1200.0 * ks : 4500.0 + 2400.0 * ks;
+                    const double wg = 9000.0 + (double)((nch + ks - 1) / ks) * chunk + combine;
+                    const double rounds = (double)((tiles * ks + 255) / 256);
+                    const double t = rounds * wg;
+                    if (best == 0.0 || t < best) { best = t; NF = nf; waves = w; CPW = cpw; KS = ks; }
+                }
+            }
         }
+        if (KS < 0) return PCONV_EINVAL;
         if (waves == 0) waves = 8;
         if (NF == 0) NF = 1;
         if (CPW == 0) CPW = waves >= 16 ? 2 : 32 / waves;
@@ -650,8 +824,8 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
         p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
         p.plane_bytes = (unsigned)((size_t)H * W * esize);
-        return wp->dtype == PCONV_F16 ? launch_tiled<__half>(p, NF, waves, CPW, st)
-                                      : launch_tiled<float>(p, NF, waves, CPW, st);
+        return wp->dtype == PCONV_F16 ? launch_tiled<__half>(p, wp, NF, waves, CPW, KS, st)
+                                      : launch_tiled<float>(p, wp, NF, waves, CPW, KS, st);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);

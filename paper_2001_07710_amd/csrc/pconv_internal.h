@@ -69,6 +69,13 @@ struct pconv_packed {
     // balanced layouts for the tilings that the automatic choice uses (see pconv::BalancedLayout)
     std::vector<pconv::BalancedLayout> balanced;
 
+    // Workspace of the tiled kernel when it splits the input channels of one output tile over several workgroups:
+    // their partial sums and one arrival counter per tile.  Grown on demand by the convolution call, so calls that
+    // share a handle must not overlap in time.
+    mutable float* d_ws = nullptr;
+    mutable size_t ws_floats = 0;
+    mutable unsigned* d_counters = nullptr;
+    mutable size_t n_counters = 0;
     // device copies (null when packed host-only)
     int device = -1;
     pconv::DevEntry* d_ent = nullptr;

@@ -124,6 +124,39 @@ def test_batch_zero_is_a_no_op_and_runs_are_deterministic():
     layer.free()
 
 
+def test_channel_splits_agree_and_leave_the_workspace_reusable():
+    """Input channels of a tile split over 1..8 workgroups: every split count matches the oracle, the same launch
+    repeated gives the same bytes (fixed summation order, counters back at zero), and a larger shape after a smaller
+    one (workspace grows) and a smaller one after it (workspace reused) are still right."""
+    spec = L.shrink(L.config1(), C=160, F=72, H=20, W=33)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    ref = layer.oracle(x)
+    for nf, wv, cpw in [(2, 16, 2), (1, 16, 2), (1, 8, 4), (2, 8, 2), (1, 8, 2)]:
+        nch = -(-spec.C // (wv * cpw))
+        for ks in sorted({1, 2, 3, nch}):
+            t = dict(kernel=T, rows=7, filters_per_wave=nf, waves=wv, channels_per_wave=cpw, channel_splits=ks)
+            say("splits", t)
+            a = layer.run(x, **t)
+            assert rel_err(a, ref) <= TOL[spec.dtype], t
+            b = layer.run(x, **t)
+            assert a.tobytes() == b.tobytes(), t
+        with pytest.raises(pc.PconvError):
+            layer.run(x, kernel=T, rows=7, filters_per_wave=nf, waves=wv, channels_per_wave=cpw,
+                      channel_splits=nch + 1)
+    # a larger problem on the same handle, then the first one again; ReLU and fp16 output through the split path
+    big = L.gen_activations(L.shrink(spec, N=3))
+    t = dict(kernel=T, rows=7, filters_per_wave=2, waves=16, channels_per_wave=2, channel_splits=4)
+    assert rel_err(layer.run(big, **t), layer.oracle(big)) <= TOL[spec.dtype]
+    assert rel_err(layer.run(x, relu=True, **t), layer.oracle(x, True)) <= TOL[spec.dtype]
+    layer.free()
+    spec16 = L.shrink(spec, dtype="f16", idx=3)
+    layer16 = GpuLayer(spec16)
+    x16 = L.gen_activations(spec16)
+    check(layer16, x16, [dict(), dict(t, channel_splits=2), dict(t, channel_splits=5)])
+    layer16.free()
+
+
 # ------------------------------------------------------------------------------------------------------------------
 # config 1: VGG-16 conv3_x-shaped layer at full size (the benchmark workload)
 # ------------------------------------------------------------------------------------------------------------------
