@@ -114,6 +114,19 @@ int pconv_packed_stats(const pconv_packed* p, int* F, int* C, int* K, int* dtype
 int pconv_packed_balance(const pconv_packed* p, int waves, int filters_per_wave, int balanced, double* mean_per_wave,
                          double* mean_of_max);
 
+/*
+ * Introspection of the stride-2 path.  A stride-2 layer runs as a stride-1 layer over the four row/column parity
+ * planes of its input: input channel 4*c + 2*a + b of that form is the plane x[c][2i+a][2j+b], and tap (ky,kx) of
+ * kernel (f,c) becomes tap (ky',kx') of kernel (f, 4*c + 2*a + b) with a = (ky-pad) mod 2, ky' = floor((ky-pad)/2)
+ * + pad (columns likewise); a four-tap kernel thus falls apart into up to four kernels of one to four taps, 4*F*C
+ * kernels in all.  pconv_packed_parity_form returns that layer as a new host-only handle (the caller frees it with
+ * pconv_free); its canonical arrays come from pconv_packed_export, its masks (one to four bits each, ascending, at
+ * most 255) from pconv_packed_library.  pad is 0 or 1.
+ *   lib_out  host, uint16_t[K] with K from pconv_packed_stats
+ */
+int pconv_packed_parity_form(const pconv_packed* p, int pad, pconv_packed** out);
+int pconv_packed_library(const pconv_packed* p, uint16_t* lib_out);
+
 /* Releases host and device memory of a handle (NULL is allowed).  The caller makes sure no launch still uses it. */
 void pconv_free(pconv_packed* p);
 

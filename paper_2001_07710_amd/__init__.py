@@ -63,6 +63,8 @@ def _load():
                                        ctypes.POINTER(ctypes.c_size_t)]
     lib.pconv_packed_balance.argtypes = [vp, i, i, i, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.pconv_packed_balance.restype = i
+    lib.pconv_packed_parity_form.argtypes = [vp, i, ctypes.POINTER(vp)]
+    lib.pconv_packed_library.argtypes = [vp, vp]
     lib.pconv_free.argtypes = [vp]
     lib.pconv_free.restype = None
     lib.pconv_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp]
@@ -70,7 +72,7 @@ def _load():
     lib.pconv_dense_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, u, vp]
     lib.pconv_maxpool2x2.argtypes = [vp, vp, i, i, i, i, i, vp]
     for name in ("pconv_assign_patterns", "pconv_select_connectivity", "pconv_pack", "pconv_packed_export",
-                 "pconv_packed_stats", "pconv_conv3x3", "pconv_conv3x3_tuned", "pconv_dense_conv3x3",
+                 "pconv_packed_stats", "pconv_packed_parity_form", "pconv_packed_library", "pconv_conv3x3", "pconv_conv3x3_tuned", "pconv_dense_conv3x3",
                  "pconv_maxpool2x2"):
         getattr(lib, name).restype = i
     lib.pconv_strerror.argtypes = [i]
@@ -182,6 +184,21 @@ def packed_balance(p: Packed, waves: int, filters_per_wave: int, balanced: bool)
     _check(_load().pconv_packed_balance(p.handle, waves, filters_per_wave, int(balanced), ctypes.byref(a),
                                         ctypes.byref(b)), "pconv_packed_balance")
     return a.value, b.value
+
+
+def packed_parity_form(p: Packed, pad: int) -> Packed:
+    """The layer as the stride-2 path runs it (4*C parity-plane channels, kernels of one to four taps), host only."""
+    out = ctypes.c_void_p(None)
+    _check(_load().pconv_packed_parity_form(p.handle, int(pad), ctypes.byref(out)), "pconv_packed_parity_form")
+    q = Packed(out.value, p.F, 4 * p.C, 0, p.np_dtype)
+    q.K = packed_stats(q)[2]
+    return q
+
+
+def packed_library(p: Packed) -> np.ndarray:
+    lib = np.empty(p.K, dtype=np.uint16)
+    _check(_load().pconv_packed_library(p.handle, _hp(lib)), "pconv_packed_library")
+    return lib
 
 
 def packed_export(p: Packed):

@@ -3,7 +3,7 @@
 
 One block (macro PCONV_ENTRY_LOOP_NF<n>_S<slot>) runs all kept kernels ("entries") that one filter has in the staged
 channel chunk.  It is threaded code, software-pipelined one entry deep over two register sets A and B: for each of
-the 126 masks with four of nine taps (ascending mask value = pattern code 0..125) there are two 256-byte-aligned
+the 255 masks with one to four of nine taps (ascending mask value = pattern code 0..254) there are two 256-byte-aligned
 sections, one per register set.  The section of entry i (set P, the other set is Q)
 
     waits for what the section before it requested: activations and weights of entry i (in P), header of entry i+1,
@@ -38,7 +38,10 @@ CH_BYTES = 64 * 12 * 4   # one staged channel in LDS: 64 lanes x 12 patch rows
 
 
 def masks():
-    return [m for m in range(512) if bin(m).count("1") == 4]
+    """Every mask a kept kernel can have: one to four of the nine taps.  Four-tap masks are the paper's patterns;
+    masks with fewer taps come from stride-2 layers, which run as stride-1 layers over the four row/column parity
+    planes of the input, where a four-tap kernel falls apart into up to four kernels with fewer taps."""
+    return [m for m in range(1, 512) if 1 <= bin(m).count("1") <= 4]
 
 
 def acc_base(slot: int) -> int:
@@ -92,6 +95,7 @@ def entry_loop(nf: int, slot: int) -> list:
     rg = Regs(nf)
     base = acc_base(slot)
     ms = masks()
+    table_b = (len(ms) + 1) << LEAF_ALIGN_LOG2          # the exit stub sits between the two tables
     lines = [
         "s_sub_u32 s66, %[cnt], 1",                    # entries still to run after the current one
         f"v_mov_b32 v{rg.ve}, %[ventry]",
@@ -99,7 +103,7 @@ def entry_loop(nf: int, slot: int) -> list:
         "1:",
         "s_add_u32 s60, s60, 3f-1b",                   # s[60:61]: sections of set A
         "s_addc_u32 s61, s61, 0",
-        f"s_add_u32 s58, s60, {len(ms) << LEAF_ALIGN_LOG2}",   # s[58:59]: sections of set B
+        f"s_add_u32 s58, s60, {table_b}",              # s[58:59]: sections of set B
         "s_addc_u32 s59, s61, 0",
         f"ds_read_b32 v{rg.m}, v{rg.ve} offset:16",
         "s_waitcnt lgkmcnt(0)",
@@ -120,9 +124,11 @@ def entry_loop(nf: int, slot: int) -> list:
                     q += 1
             lines += [
                 "s_sub_u32 s66, s66, 1",               # borrow: this was the last entry
-                "s_cbranch_scc1 9f",
+                "s_cbranch_scc1 9f" if p == 0 else "s_cbranch_scc1 9b",   # the exit stub sits behind the sections of set A
             ] + jump(1 - p)
-    lines += [f".p2align {LEAF_ALIGN_LOG2}", "9:", "s_waitcnt lgkmcnt(0)"]
+        if p == 0:
+            lines += [f".p2align {LEAF_ALIGN_LOG2}", "9:", "s_waitcnt lgkmcnt(0)", "s_branch 8f"]
+    lines += [f".p2align {LEAF_ALIGN_LOG2}", "8:"]
     return lines
 
 

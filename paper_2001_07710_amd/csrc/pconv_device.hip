@@ -82,6 +82,9 @@ void release_device(pconv_packed* p) {
     }
     if (p->d_ws) (void)hipFree(p->d_ws);
     if (p->d_counters) (void)hipFree(p->d_counters);
+    if (p->d_planes) (void)hipFree(p->d_planes);
+    p->d_planes = nullptr;
+    p->planes_bytes = 0;
     p->d_ws = nullptr;
     p->ws_floats = 0;
     p->d_counters = nullptr;
@@ -619,6 +622,24 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T
     }
 }
 
+// Splits every input plane into its four row/column parity planes: out[pl][2a+b][i][j] = x[pl][2i+a][2j+b] (zero
+// where that is outside the image).  A stride-2 convolution reads each parity plane at unit stride.
+template <typename T>
+__global__ __launch_bounds__(256) void parity_planes_kernel(const T* __restrict__ x, T* __restrict__ out,
+                                                            long long planes, int H, int W, int Hs, int Ws) {
+    const long long total = planes * 4 * Hs * Ws;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const int j = (int)(i % Ws);
+        long long r = i / Ws;
+        const int row = (int)(r % Hs);
+        r /= Hs;
+        const int ab = (int)(r & 3);
+        const long long pl = r >> 2;
+        const int iy = 2 * row + (ab >> 1), ix = 2 * j + (ab & 1);
+        out[i] = (iy < H && ix < W) ? x[(pl * H + iy) * (long long)W + ix] : from_f32<T>(0.f);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // launch selection
 // ---------------------------------------------------------------------------------------------------------------
@@ -746,9 +767,41 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     int R = tuning ? tuning->rows : 0, NF = tuning ? tuning->filters_per_wave : 0, waves = tuning ? tuning->waves : 0;
     int CPW = tuning ? tuning->channels_per_wave : 0;
     int KS = tuning ? tuning->channel_splits : 0;
-    const bool can_tile = tiled_applicable(N, wp->C, H, W, stride, esize);
+    // What the tiled kernel sees: the layer itself at stride 1; at stride 2 the layer re-packed over the four
+    // row/column parity planes of the input (a stride-1 problem with 4*C channels of half the height and width).
+    const int tH = stride == 1 ? H : (H + 1) / 2, tW = stride == 1 ? W : (W + 1) / 2;
+    const int tC = stride == 1 ? wp->C : 4 * wp->C;
+    const bool can_tile = tC < 65536 && tiled_applicable(N, tC, tH, tW, 1, esize);
     if (kernel == PCONV_KERNEL_AUTO) kernel = can_tile ? PCONV_KERNEL_TILED : PCONV_KERNEL_GENERIC;
     if (kernel == PCONV_KERNEL_TILED && !can_tile) return PCONV_EUNSUPPORTED;
+    const pconv_packed* lay = wp;
+    const void* tx = x;
+    if (kernel == PCONV_KERNEL_TILED && stride == 2) {
+        if (!wp->by_parity[pad]) {
+            pconv_packed* child = nullptr;
+            if (int rc = derive_for_stride2(wp, pad, true, &child)) return rc;
+            wp->by_parity[pad] = child;
+        }
+        lay = wp->by_parity[pad];
+        const size_t need = (size_t)N * tC * tH * tW * esize;
+        if (need > wp->planes_bytes) {
+            if (wp->d_planes) PCONV_HIP(hipFree(wp->d_planes));   // hipFree waits for work that may still use it
+            wp->d_planes = nullptr;
+            wp->planes_bytes = 0;
+            PCONV_HIP(hipMalloc(&wp->d_planes, need));
+            wp->planes_bytes = need;
+        }
+        const long long total = (long long)N * tC * tH * tW;
+        const unsigned grid = (unsigned)std::min<long long>((total + 255) / 256, 1 << 20);
+        if (wp->dtype == PCONV_F16)
+            hipLaunchKernelGGL(parity_planes_kernel<__half>, dim3(grid), dim3(256), 0, st, (const __half*)x,
+                               (__half*)wp->d_planes, (long long)N * wp->C, H, W, tH, tW);
+        else
+            hipLaunchKernelGGL(parity_planes_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)x,
+                               (float*)wp->d_planes, (long long)N * wp->C, H, W, tH, tW);
+        PCONV_HIP(hipGetLastError());
+        tx = wp->d_planes;
+    }
 
     if (kernel == PCONV_KERNEL_TILED) {
         if (R == 0) R = kR;
@@ -766,13 +819,13 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
             double best = 0.0;
             for (int i = 0; i < 4; ++i) {
                 const int nf = cand[i][0], w = cand[i][1], cpw = cand[i][2], cc = w * cpw;
-                if (cc == 16 && wp->C > 16) continue;   // half-size chunks only pay for layers with few channels
-                const long long tiles = slots * ((wp->F + nf * w - 1) / (nf * w));
-                const int nch = (wp->C + cc - 1) / cc;
-                const double per_filter_chunk = (double)wp->n_kept / ((double)wp->F * nch);
+                if (cc == 16 && lay->C > 16) continue;   // half-size chunks only pay for layers with few channels
+                const long long tiles = slots * ((lay->F + nf * w - 1) / (nf * w));
+                const int nch = (lay->C + cc - 1) / cc;
+                const double per_filter_chunk = (double)lay->n_kept / ((double)lay->F * nch);
                 for (int ks = 1; ks <= std::min(nch, 16); ks *= 2) {
                     const double issue = (w / 4) * nf * per_filter_chunk * 128.0 + 750.0;
-                    const double staging = std::min(wp->C, cc) * 9.0 * 18.0;
+                    const double staging = std::min(lay->C, cc) * 9.0 * 18.0;
                     const double chunk = std::max(issue, staging) + 3400.0;
                     const double combine = ks == 1 ? 1500.0 * nf : nf == 1 ? 1200.0 * ks : 4500.0 + 2400.0 * ks;
                     const double wg = 9000.0 + (double)((nch + ks - 1) / ks) * chunk + combine;
@@ -788,29 +841,29 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         if (CPW == 0) CPW = waves >= 16 ? 2 : 32 / waves;
         if (waves < 1 || waves > 16) return PCONV_EUNSUPPORTED;
         TiledParams p{};
-        p.x = x;
+        p.x = tx;
         p.y = y;
-        p.ent = wp->d_ent;
-        p.eptr = wp->d_eptr;
-        p.forder = wp->d_forder;
+        p.ent = lay->d_ent;
+        p.eptr = lay->d_eptr;
+        p.forder = lay->d_forder;
         p.bias = bias;
         p.N = N;
-        p.C = wp->C;
-        p.F = wp->F;
-        p.H = H;
-        p.W = W;
+        p.C = lay->C;
+        p.F = lay->F;
+        p.H = tH;
+        p.W = tW;
         p.Ho = Ho;
         p.Wo = Wo;
         p.pad = pad;
         p.relu = relu;
-        p.nbk = wp->n_buckets;
+        p.nbk = lay->n_buckets;
         p.bpc = (CPW * waves) / kBucket;
         p.perm = nullptr;
         p.perm_stride = 0;
         // a balanced layout exists for the tilings of the automatic choice
         const int order = tuning ? tuning->channel_order : PCONV_ORDER_AUTO;
         if (order != PCONV_ORDER_PLAIN) {
-            for (const BalancedLayout& b : wp->balanced)
+            for (const BalancedLayout& b : lay->balanced)
                 if (b.fw == waves && b.nf == NF && b.cc == CPW * waves && b.d_ent) {
                     p.ent = b.d_ent;
                     p.eptr = b.d_eptr;
@@ -821,10 +874,10 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
                 }
             if (order == PCONV_ORDER_BALANCED && !p.perm) return PCONV_EUNSUPPORTED;
         }
-        p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
-        p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
-        p.plane_bytes = (unsigned)((size_t)H * W * esize);
-        return wp->dtype == PCONV_F16 ? launch_tiled<__half>(p, wp, NF, waves, CPW, KS, st)
+        p.x_bytes = (unsigned long long)N * lay->C * tH * tW * esize;
+        p.img_bytes = (unsigned)((size_t)lay->C * tH * tW * esize);
+        p.plane_bytes = (unsigned)((size_t)tH * tW * esize);
+        return lay->dtype == PCONV_F16 ? launch_tiled<__half>(p, wp, NF, waves, CPW, KS, st)
                                       : launch_tiled<float>(p, wp, NF, waves, CPW, KS, st);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;

@@ -22,6 +22,15 @@ int check_library(const uint16_t* lib, int K) {
     return PCONV_OK;
 }
 
+// The library of a layer re-packed over parity planes: any masks with one to four bits.
+int check_partial_library(const uint16_t* lib, int K) {
+    if (!lib) return PCONV_EINVAL;
+    if (K < 1 || K > 255) return PCONV_EPATTERN;
+    for (int j = 0; j < K; ++j)
+        if (lib[j] >= 512u || popcount9(lib[j]) < 1 || popcount9(lib[j]) > 4) return PCONV_EPATTERN;
+    return PCONV_OK;
+}
+
 int check_fc(int F, int C) {
     if (F <= 0 || C <= 0 || C >= 65536) return PCONV_ESHAPE;
     if ((long long)F * (long long)C > (1ll << 31) / 9) return PCONV_ESHAPE;
@@ -53,11 +62,12 @@ inline float half_bits_to_float(uint16_t h) {
     return f;
 }
 
-// Rank of a four-bit mask among the 126 such masks in ascending order (the pattern code of the device layout).
+// Rank of a mask among the 255 masks with one to four bits in ascending order (the pattern code of the device
+// layout: the tiled kernel has one code section per such mask).
 inline uint32_t mask_rank(unsigned m) {
     uint32_t rank = 0;
-    for (unsigned v = 0; v < m; ++v)
-        if (popcount9(v) == 4) ++rank;
+    for (unsigned v = 1; v < m; ++v)
+        if (popcount9(v) >= 1 && popcount9(v) <= 4) ++rank;
     return rank;
 }
 
@@ -232,14 +242,16 @@ void build_balanced(const pconv_packed* p, int fw, int nf, int cc, pconv::Balanc
 
 }  // namespace
 
-extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
-                          const uint8_t* mask, unsigned flags, pconv_packed** out) {
+// pconv_pack, and the packing of a layer re-packed over parity planes (`partial`: masks of one to four taps, up to
+// 255 of them; missing taps of a kernel are stored as zero weights).
+static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
+                     const uint8_t* mask, unsigned flags, bool partial, pconv_packed** out) {
     if (!out) return PCONV_EINVAL;
     *out = nullptr;
     if (!w_oihw || !pid || !mask) return PCONV_EINVAL;
     if (dtype != PCONV_F32 && dtype != PCONV_F16) return PCONV_EINVAL;
     if (flags & ~(unsigned)PCONV_PACK_HOST_ONLY) return PCONV_EINVAL;
-    if (int rc = check_library(lib, K)) return rc;
+    if (int rc = partial ? check_partial_library(lib, K) : check_library(lib, K)) return rc;
     if (int rc = check_fc(F, C)) return rc;
     const size_t esize = dtype == PCONV_F16 ? 2 : 4;
     const unsigned char* wb = static_cast<const unsigned char*>(w_oihw);
@@ -256,8 +268,8 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
         p->dtype = dtype;
         p->lib.assign(lib, lib + K);
 
-        // taps of every mask, ascending
-        std::vector<int> taps((size_t)K * 4);
+        // taps of every mask, ascending (-1: the mask has fewer than four)
+        std::vector<int> taps((size_t)K * 4, -1);
         for (int j = 0; j < K; ++j) {
             int q = 0;
             for (int t = 0; t < 9; ++t)
@@ -292,8 +304,11 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
                     const size_t fc = (size_t)f * C + c;
                     if (!mask[fc] || pid[fc] != j) continue;
                     p->cin[e] = (uint16_t)c;
-                    for (int q = 0; q < 4; ++q)
-                        std::memcpy(&p->w4[(e * 4 + q) * esize], wb + (fc * 9 + taps[(size_t)j * 4 + q]) * esize, esize);
+                    for (int q = 0; q < 4; ++q) {
+                        const int t = taps[(size_t)j * 4 + q];
+                        if (t >= 0) std::memcpy(&p->w4[(e * 4 + q) * esize], wb + (fc * 9 + t) * esize, esize);
+                        else std::memset(&p->w4[(e * 4 + q) * esize], 0, esize);
+                    }
                     ++e;
                 }
             }
@@ -361,6 +376,79 @@ extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uin
     return PCONV_OK;
 }
 
+extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
+                          const uint8_t* mask, unsigned flags, pconv_packed** out) {
+    return pack_impl(w_oihw, dtype, F, C, lib, K, pid, mask, flags, false, out);
+}
+
+int pconv::derive_for_stride2(const pconv_packed* p, int pad, bool upload, pconv_packed** out) {
+    if (!p || !out || (pad != 0 && pad != 1)) return PCONV_EINVAL;
+    *out = nullptr;
+    const int F = p->F, C = p->C, K = p->K, C4 = 4 * C;
+    if (C4 >= 65536) return PCONV_EUNSUPPORTED;
+    const size_t esize = p->dtype == PCONV_F16 ? 2 : 4;
+    try {
+        // where tap t of a kernel goes: plane (0..3) and tap inside the plane's kernel
+        int plane_of[9], tap_of[9];
+        for (int t = 0; t < 9; ++t) {
+            const int dy = t / 3 - pad, dx = t % 3 - pad;            // -1..2
+            const int a = dy & 1, b = dx & 1;                          // parity (two's complement: -1 & 1 == 1)
+            const int ky = (dy - a) / 2 + pad, kx = (dx - b) / 2 + pad;   // floor(d/2) + pad, in {0,1}
+            plane_of[t] = 2 * a + b;
+            tap_of[t] = 3 * ky + kx;
+        }
+        std::vector<unsigned char> w((size_t)F * C4 * 9 * esize, 0);
+        std::vector<uint16_t> m9((size_t)F * C4, 0);
+        for (int i = 0; i < F; ++i) {
+            const uint32_t f = p->filter_order[(size_t)i];
+            for (int j = 0; j < K; ++j) {
+                int taps[4], q = 0;
+                for (int t = 0; t < 9; ++t)
+                    if ((p->lib[(size_t)j] >> t) & 1u) taps[q++] = t;
+                for (uint32_t e = p->grp_ptr[(size_t)i * K + j]; e < p->grp_ptr[(size_t)i * K + j + 1]; ++e) {
+                    const size_t c = p->cin[e];
+                    for (int k = 0; k < 4; ++k) {
+                        const size_t fc = (size_t)f * C4 + 4 * c + (size_t)plane_of[taps[k]];
+                        std::memcpy(&w[(fc * 9 + (size_t)tap_of[taps[k]]) * esize], &p->w4[((size_t)e * 4 + k) * esize], esize);
+                        m9[fc] |= (uint16_t)(1u << tap_of[taps[k]]);
+                    }
+                }
+            }
+        }
+        // library of the re-packed layer: the masks that occur, ascending
+        std::vector<int> index_of(512, -1);
+        std::vector<uint16_t> lib;
+        std::vector<char> used(512, 0);
+        for (size_t i = 0; i < m9.size(); ++i) used[m9[i]] = 1;
+        for (unsigned v = 1; v < 512; ++v)
+            if (used[v]) {
+                index_of[v] = (int)lib.size();
+                lib.push_back((uint16_t)v);
+            }
+        if (lib.empty()) lib.push_back(1);   // a layer with nothing kept
+        std::vector<uint8_t> pid(m9.size(), 0), mask(m9.size(), 0);
+        for (size_t i = 0; i < m9.size(); ++i)
+            if (m9[i]) {
+                pid[i] = (uint8_t)index_of[m9[i]];
+                mask[i] = 1;
+            }
+        return pack_impl(w.data(), p->dtype, F, C4, lib.data(), (int)lib.size(), pid.data(), mask.data(),
+                         upload ? 0u : (unsigned)PCONV_PACK_HOST_ONLY, true, out);
+    } catch (const std::bad_alloc&) {
+        return PCONV_ENOMEM;
+    }
+}
+
+extern "C" int pconv_packed_parity_form(const pconv_packed* p, int pad, pconv_packed** out) {
+    return pconv::derive_for_stride2(p, pad, false, out);
+}
+
+extern "C" int pconv_packed_library(const pconv_packed* p, uint16_t* lib_out) {
+    if (!p || !lib_out) return PCONV_EINVAL;
+    std::memcpy(lib_out, p->lib.data(), p->lib.size() * sizeof(uint16_t));
+    return PCONV_OK;
+}
+
 extern "C" int pconv_packed_export(const pconv_packed* p, uint32_t* filter_order, uint32_t* grp_ptr, uint16_t* cin,
                                    void* w4, size_t* n_kept) {
     if (!p) return PCONV_EINVAL;
@@ -423,6 +511,10 @@ extern "C" int pconv_packed_stats(const pconv_packed* p, int* F, int* C, int* K,
 
 extern "C" void pconv_free(pconv_packed* p) {
     if (!p) return;
+    for (pconv_packed*& child : p->by_parity) {
+        pconv_free(child);
+        child = nullptr;
+    }
     pconv::release_device(p);
     delete p;
 }

@@ -24,7 +24,7 @@ struct DevEntry {
                       // bits 8.. = code; code * kLeafStride is the byte offset of the pattern's code section
     uint32_t c;       // input channel
     uint32_t mask9;   // the pattern mask itself (bit t = 3*ky + kx)
-    uint32_t code;    // rank of the mask among the 126 masks with four of nine bits, ascending (0..125)
+    uint32_t code;    // rank of the mask among the 255 masks with one to four of nine bits, ascending (0..254)
 };
 static_assert(sizeof(DevEntry) == 32, "DevEntry must be 32 bytes");
 
@@ -76,6 +76,12 @@ struct pconv_packed {
     mutable size_t ws_floats = 0;
     mutable unsigned* d_counters = nullptr;
     mutable size_t n_counters = 0;
+    // Stride-2 layers run as stride-1 layers over the four row/column parity planes of the input.  Per padding
+    // (0, 1): the layer re-packed for that form (4*C input channels, kernels of one to four taps), made by the
+    // first stride-2 call that needs it; and the buffer that holds the input split into planes.
+    mutable pconv_packed* by_parity[2] = {nullptr, nullptr};
+    mutable void* d_planes = nullptr;
+    mutable size_t planes_bytes = 0;
     // device copies (null when packed host-only)
     int device = -1;
     pconv::DevEntry* d_ent = nullptr;
@@ -84,6 +90,11 @@ struct pconv_packed {
 };
 
 namespace pconv {
+// implemented in pconv_host.cpp
+// The same layer for stride 2 and padding `pad`, as a stride-1 layer over parity planes: input channel 4*c + 2*a + b
+// is the plane x[c][2i+a][2j+b]; tap (ky,kx) of kernel (f,c) becomes tap (ky',kx') of kernel (f, 4*c + 2*a + b) with
+// a = (ky-pad) mod 2, ky' = floor((ky-pad)/2) + pad, likewise for columns.  Weights keep their storage type.
+int derive_for_stride2(const pconv_packed* p, int pad, bool upload, pconv_packed** out);
 // implemented in pconv_device.hip
 int upload_packed(pconv_packed* p);
 void release_device(pconv_packed* p);

@@ -86,9 +86,8 @@ def test_ragged_shapes(case, dtype):
                        dtype=dtype, K=8, keep=0.4)
     layer = GpuLayer(spec)
     x = L.gen_activations(spec)
-    tunings = [dict(), dict(kernel=G)]
-    if stride == 1:
-        tunings += [TILED_TUNINGS[0], TILED_TUNINGS[3], TILED_TUNINGS[6], TILED_TUNINGS[7]]
+    # stride 2 reaches the tiled kernels through the parity-plane form of the layer
+    tunings = [dict(), dict(kernel=G), TILED_TUNINGS[0], TILED_TUNINGS[3], TILED_TUNINGS[6], TILED_TUNINGS[7]]
     check(layer, x, tunings)
     check(layer, x, [dict()], relu=True)
     layer.free()
@@ -248,7 +247,7 @@ def test_config3_resnet50_shapes(N):
         layer = GpuLayer(spec)
         x = L.gen_activations(spec)
         if N == 1:
-            tun = [dict(), dict(kernel=G)] + ([TILED_TUNINGS[1], TILED_TUNINGS[5]] if spec.stride == 1 else [])
+            tun = [dict(), dict(kernel=G), TILED_TUNINGS[1], TILED_TUNINGS[5]]
             check(layer, x, tun)
         else:
             check_batched(layer, x)

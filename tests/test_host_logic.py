@@ -182,3 +182,49 @@ def test_balanced_staging_order_evens_out_the_waves():
     with pytest.raises(pc.PconvError):
         pc.packed_balance(p, 4, 1, True)
     p.free()
+
+
+@pytest.mark.parametrize("pad", [0, 1])
+@pytest.mark.parametrize("hw", [(9, 11), (8, 6)])
+def test_parity_form_of_a_stride2_layer_computes_the_same_function(pad, hw):
+    """The re-packed layer that the stride-2 path runs, checked on the CPU against the definition: the oracle's
+    stride-2 convolution of x equals its stride-1 convolution of the four parity planes of x with the re-packed
+    weights."""
+    H, W = hw
+    spec = L.LayerSpec(cfg=12, idx=pad, name="s2", N=2, C=10, F=12, H=H, W=W, stride=2, pad=pad, K=8, keep=0.5)
+    w, lib = _layer(spec)
+    pid = pc.assign_patterns(w, lib)
+    mask = pc.select_connectivity(w, lib, pid, spec.keep)
+    p = pc.pack(w, lib, pid, mask, pc.PACK_HOST_ONLY)
+    q = pc.packed_parity_form(p, pad)
+    F, C4, K2, _, n2 = pc.packed_stats(q)
+    assert (F, C4) == (spec.F, 4 * spec.C) and 1 <= K2 <= 255
+    lib2 = pc.packed_library(q)
+    assert np.all(np.diff(lib2.astype(int)) > 0)
+    bits = np.array([[(int(m) >> t) & 1 for t in range(9)] for m in lib2])
+    assert np.all((bits.sum(axis=1) >= 1) & (bits.sum(axis=1) <= 4)) and np.all(bits[:, [2, 5, 6, 7, 8]] == 0)
+    fo, gp, cin, w4 = pc.packed_export(q)
+    w2 = np.zeros((F, C4, 9), np.float32)
+    n_taps = 0
+    for i in range(F):
+        for j in range(K2):
+            taps = np.nonzero(bits[j])[0]
+            for e in range(int(gp[i * K2 + j]), int(gp[i * K2 + j + 1])):
+                w2[int(fo[i]), int(cin[e]), taps] = w4[e][:len(taps)]
+                assert np.all(w4[e][len(taps):] == 0)
+                n_taps += len(taps)
+    assert n_taps == 4 * int(mask.sum())          # every kept tap went to exactly one plane kernel
+    x = L.gen_activations(spec)
+    Hs, Ws = (H + 1) // 2, (W + 1) // 2
+    planes = np.zeros((spec.N, spec.C, 4, Hs + 1, Ws + 1), np.float32)   # one spare zero row/column for pad 0
+    for a in range(2):
+        for b in range(2):
+            sub = x[:, :, a::2, b::2]
+            planes[:, :, 2 * a + b, :sub.shape[2], :sub.shape[3]] = sub
+    planes = planes.reshape(spec.N, C4, Hs + 1, Ws + 1)
+    ref = oracle.pattern_conv3x3(x, w, pid, mask, lib, None, 2, pad)
+    via = oracle.conv3x3(planes, w2.reshape(F, C4, 3, 3), None, 1, pad)[:, :, :ref.shape[2], :ref.shape[3]]
+    assert via.shape == ref.shape
+    assert np.max(np.abs(via - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+    q.free()
+    p.free()
