@@ -173,16 +173,16 @@ def main():
     abytes = algorithmic_bytes(spec, layer.n_kept)
 
     if args.tune:
-        for r, nf, wv, cpw in [(7, 1, 4, 4), (7, 1, 8, 2), (7, 1, 8, 4), (7, 1, 16, 1), (7, 1, 16, 2), (7, 2, 8, 2),
-                               (7, 2, 16, 1), (7, 2, 16, 2)]:
+        for r, nf, wv, cpw, nbuf in [(7, 1, 8, 4, 1), (7, 1, 16, 2, 1), (7, 2, 8, 2, 1), (7, 2, 16, 2, 1),
+                                     (7, 1, 16, 1, 2), (7, 2, 16, 1, 2), (7, 1, 8, 2, 2), (7, 2, 8, 2, 2)]:
             for ks in (1, 2, 4, 8):
                 t = dict(kernel=pc.KERNEL_TILED, rows=r, filters_per_wave=nf, waves=wv, channels_per_wave=cpw,
-                         channel_splits=ks)
+                         channel_splits=ks, buffers=nbuf)
                 try:
                     _, ev = time_launches(torch, lambda: layer.launch(stream, **t), 300, 30)
                 except pc.PconvError:
                     continue
-                log(f"tune rows={r} nf={nf} waves={wv} cpw={cpw} splits={ks}: {ev * 1e3:8.2f} us  "
+                log(f"tune rows={r} nf={nf} waves={wv} cpw={cpw} buffers={nbuf} splits={ks}: {ev * 1e3:8.2f} us  "
                     f"{macs / ev / 1e6:9.1f} GMAC/s")
 
     # one plain device-to-device copy of known size (256 MiB read + 256 MiB written): the calibration point for the
@@ -263,24 +263,24 @@ def layer_table(args, torch, pc, L, stream):
         _, ev = time_launches(torch, lambda: layer.launch(stream), steps, max(3, steps // 10))
         best = None
         if args.tune and spec.stride == 1:
-            for nf, wv, cpw in [(1, 8, 2), (1, 8, 4), (1, 16, 1), (1, 16, 2), (2, 8, 2), (2, 16, 1), (2, 16, 2),
-                                (1, 4, 4)]:
+            for nf, wv, cpw, nbuf in [(1, 8, 4, 1), (1, 16, 2, 1), (2, 16, 2, 1), (2, 16, 1, 1), (1, 16, 1, 2),
+                                      (2, 16, 1, 2), (1, 8, 2, 2), (2, 8, 2, 2)]:
                 for ks in (1, 2, 4, 8, 16):
                     t = dict(kernel=pc.KERNEL_TILED, rows=7, filters_per_wave=nf, waves=wv, channels_per_wave=cpw,
-                             channel_splits=ks)
+                             channel_splits=ks, buffers=nbuf)
                     try:
                         _, tv = time_launches(torch, lambda: layer.launch(stream, **t), max(5, steps // 4), 2)
                     except pc.PconvError:
                         continue
                     if best is None or tv < best[0]:
-                        best = (tv, nf, wv, cpw, ks)
+                        best = (tv, nf, wv, cpw, ks, nbuf)
         ab = algorithmic_bytes(spec, layer.n_kept)
         row = {"layer": spec.name, "C": spec.C, "F": spec.F, "H": spec.H, "N": spec.N, "stride": spec.stride,
                "dtype": spec.dtype, "keep": spec.keep, "K": spec.K, "n_kept": layer.n_kept, "us": ev * 1e3,
                "eff_GMACs": macs / ev / 1e6, "alu_frac": 2 * macs / (ev * 1e-3) / 1e12 / PEAK_FP32_VECTOR_TFLOPS,
                "alg_GBs": ab / (ev * 1e-3) / 1e9, "hbm_frac": ab / (ev * 1e-3) / 1e9 / PEAK_HBM_GBS}
         if best:
-            row["best_us"], row["best_cfg"] = best[0] * 1e3, f"nf{best[1]}w{best[2]}c{best[3]}s{best[4]}"
+            row["best_us"], row["best_cfg"] = best[0] * 1e3, f"nf{best[1]}w{best[2]}c{best[3]}s{best[4]}b{best[5]}"
         if not args.no_dense:
             wm = np.where(layer.mask[:, :, None, None] != 0, layer.w, 0).astype(layer.w.dtype)
             dw = torch.from_numpy(np.ascontiguousarray(wm)).cuda()

@@ -171,6 +171,9 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *   channel_splits    tiled: workgroups that share one output tile, each taking a contiguous range of the channel
  *                     chunks (1 = no split, no workspace; at most the number of chunks; 0 = as many as give one
  *                     round of workgroups over the GPU's compute units)
+ *   buffers           tiled: 1 = one chunk buffer in LDS and two barriers per chunk; 2 = two buffers of 16
+ *                     channels (waves * channels_per_wave must be 16) and one barrier per chunk, the LDS writes of
+ *                     one chunk running beside the multiply-adds of the chunk before
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
 enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2 };
@@ -183,6 +186,7 @@ typedef struct pconv_tuning {
     int channels_per_wave;
     int channel_order;
     int channel_splits;
+    int buffers;
 } pconv_tuning;
 int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                         int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning);

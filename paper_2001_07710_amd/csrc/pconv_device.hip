@@ -253,7 +253,11 @@ __device__ __forceinline__ void run_entries(unsigned lane_addr, unsigned entry_a
 #undef PCONV_LOOP
 }
 
-template <int NF, int CPW, int NB, typename T>
+// DB: two chunk buffers in LDS.  A wave multiplies chunk k out of one buffer, then writes its share of chunk k+1 into
+// the other and meets the others at ONE barrier per chunk, so the LDS writes of the waves that finish early run
+// beside the multiply-adds of the others.  Without DB there is one buffer and two barriers per chunk (everybody done
+// reading, everybody done writing).
+template <int NF, int CPW, int NB, bool DB, typename T>
 __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     constexpr int R = kR;
     constexpr int CC = 16 * NB;          // channels per chunk
@@ -263,8 +267,12 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     static_assert(CC == 16 || CC == 32, "the section code masks the channel index to the chunk size");
     // bytes of LDS for the entries of one filter and chunk; the loop reads (and ignores) up to two entries past the last
     constexpr unsigned kEntRegion = (CC + 2) * 32;
-    constexpr unsigned kEntBase = CC * kChBytes;             // entries start behind the tile
-    extern __shared__ __align__(16) unsigned char lds[];     // [CC][64][12] floats, then [FW][NF][CC+2] entries
+    constexpr unsigned kBuffers = DB ? 2 : 1;
+    constexpr unsigned kTileBytes = CC * kChBytes;           // one chunk buffer
+    constexpr unsigned kEntBase = kBuffers * kTileBytes;     // entries start behind the tile(s)
+    constexpr unsigned kEntBytes = FW * NF * kEntRegion;     // entries of one buffer
+    // [buffers][CC][64][12] floats, then [buffers][FW][NF][CC+2] entries
+    extern __shared__ __align__(16) unsigned char lds[];
     const unsigned lds0 = (unsigned)(unsigned long long)lds; // LDS byte address of the allocation (low 32 bits)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -366,12 +374,12 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             ecnt[a] = cnt;
         }
     };
-    auto write_lds = [&](int k) {
+    auto write_lds = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < CPW; ++j) {
             const int cc = wave + j * FW;
             if (staged[j] < (unsigned)p.C) {
-                float* dst = reinterpret_cast<float*>(lds + cc * kChBytes + lane * (kPR * 4));
+                float* dst = reinterpret_cast<float*>(lds + buf * kTileBytes + cc * kChBytes + lane * (kPR * 4));
                 *reinterpret_cast<float4*>(dst + 0) = make_float4(pre[j][0], pre[j][1], pre[j][2], pre[j][3]);
                 *reinterpret_cast<float4*>(dst + 4) = make_float4(pre[j][4], pre[j][5], pre[j][6], pre[j][7]);
                 *reinterpret_cast<float4*>(dst + 8) = make_float4(pre[j][8], 0.f, 0.f, 0.f);
@@ -380,29 +388,59 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
         // entries, as they are
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
-            uint2* dst = reinterpret_cast<uint2*>(lds + kEntBase + (wave * NF + a) * kEntRegion);
+            uint2* dst = reinterpret_cast<uint2*>(lds + kEntBase + buf * kEntBytes + (wave * NF + a) * kEntRegion);
 #pragma unroll
             for (int j = 0; j < NB; ++j)
                 if ((unsigned)(lane >> 2) + 16u * j < ecnt[a]) dst[lane + 64 * j] = epre[a][j];
         }
     };
+    auto compute = [&](int buf, const unsigned (&cnt)[NF]) {
+        const unsigned tile_addr = lane_addr + buf * kTileBytes;
+        const unsigned ent_addr = lds0 + kEntBase + buf * kEntBytes + wave * NF * kEntRegion;
+        if constexpr (NF > 0) { if (cnt[0]) run_entries<NF, 0, CC>(tile_addr, ent_addr + 0 * kEntRegion, cnt[0]); }
+        if constexpr (NF > 1) { if (cnt[1]) run_entries<NF, 1, CC>(tile_addr, ent_addr + 1 * kEntRegion, cnt[1]); }
+    };
 
-    issue_loads(k_begin);
-    write_lds(k_begin);
-    __syncthreads();
-    for (int k = k_begin; k < k_end; ++k) {
-        const bool more = k + 1 < k_end;
-        unsigned cnt_now[NF];
+    unsigned cnt_now[NF];
+    if constexpr (!DB) {
+        issue_loads(k_begin);
+        write_lds(0);
+        __syncthreads();
+        for (int k = k_begin; k < k_end; ++k) {
+            const bool more = k + 1 < k_end;
+#pragma unroll
+            for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
+            if (more) issue_loads(k + 1);
+            compute(0, cnt_now);
+            __syncthreads();           // every wave is done reading chunk k
+            if (more) {
+                write_lds(0);
+                __syncthreads();
+            }
+        }
+    } else {
+        // Three chunks are under way at a time: k is multiplied, k+1 is written to the other buffer at the START of
+        // the step (its loads were issued a whole step earlier, and that buffer was last read before the previous
+        // barrier), and the loads of k+2 are issued right after, so their latency runs beside the multiply-adds.
+        unsigned cnt_next[NF];
+        issue_loads(k_begin);
+        write_lds(0);
 #pragma unroll
         for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
-        if (more) issue_loads(k + 1);
-        const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
-        if constexpr (NF > 0) { if (cnt_now[0]) run_entries<NF, 0, CC>(lane_addr, ent_addr + 0 * kEntRegion, cnt_now[0]); }
-        if constexpr (NF > 1) { if (cnt_now[1]) run_entries<NF, 1, CC>(lane_addr, ent_addr + 1 * kEntRegion, cnt_now[1]); }
-        __syncthreads();           // every wave is done reading chunk k
-        if (more) {
-            write_lds(k + 1);
-            __syncthreads();
+        if (k_begin + 1 < k_end) issue_loads(k_begin + 1);
+        __syncthreads();
+        for (int k = k_begin; k < k_end; ++k) {
+            const int buf = (k - k_begin) & 1;
+            if (k + 1 < k_end) {
+                write_lds(buf ^ 1);
+#pragma unroll
+                for (int a = 0; a < NF; ++a) cnt_next[a] = ecnt[a];
+                if (k + 2 < k_end) issue_loads(k + 2);
+            }
+            compute(buf, cnt_now);
+#pragma unroll
+            for (int a = 0; a < NF; ++a) cnt_now[a] = cnt_next[a];
+            __syncthreads();           // chunk k+1 is complete in LDS, and nobody reads chunk k any more
         }
     }
 
@@ -522,15 +560,15 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
 
 // The compiler may allocate 2*n vector registers under amdgpu_num_vgpr(n) on this target; the accumulators of the
 // pattern sections sit above that: 21 registers per filter slot, ending at v127.
-template <int CPW, int NB, typename T>
+template <int CPW, int NB, bool DB, typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(53))) void tiled_kernel_nf1(const TiledParams p) {
     static_assert(PCONV_ACC_BASE_S0 >= 2 * 53, "accumulators overlap the compiler's registers");
-    tiled_body<1, CPW, NB, T>(p);
+    tiled_body<1, CPW, NB, DB, T>(p);
 }
-template <int CPW, int NB, typename T>
+template <int CPW, int NB, bool DB, typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(43))) void tiled_kernel_nf2(const TiledParams p) {
     static_assert(PCONV_ACC_BASE_S1 >= 2 * 43, "accumulators overlap the compiler's registers");
-    tiled_body<2, CPW, NB, T>(p);
+    tiled_body<2, CPW, NB, DB, T>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -624,19 +662,29 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T
 
 // Splits every input plane into its four row/column parity planes: out[pl][2a+b][i][j] = x[pl][2i+a][2j+b] (zero
 // where that is outside the image).  A stride-2 convolution reads each parity plane at unit stride.
+// One workgroup per input plane and band of 4 plane rows; thread (ty, tx) walks the columns in steps of 64.
 template <typename T>
-__global__ __launch_bounds__(256) void parity_planes_kernel(const T* __restrict__ x, T* __restrict__ out,
-                                                            long long planes, int H, int W, int Hs, int Ws) {
-    const long long total = planes * 4 * Hs * Ws;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-        const int j = (int)(i % Ws);
-        long long r = i / Ws;
-        const int row = (int)(r % Hs);
-        r /= Hs;
-        const int ab = (int)(r & 3);
-        const long long pl = r >> 2;
-        const int iy = 2 * row + (ab >> 1), ix = 2 * j + (ab & 1);
-        out[i] = (iy < H && ix < W) ? x[(pl * H + iy) * (long long)W + ix] : from_f32<T>(0.f);
+__global__ __launch_bounds__(256) void parity_planes_kernel(const T* __restrict__ x, T* __restrict__ out, int H, int W,
+                                                            int Hs, int Ws) {
+    const long long pl = blockIdx.x;
+    const int i = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (i >= Hs) return;
+    const T* src = x + pl * (long long)H * W;
+    T* dst = out + pl * 4ll * Hs * Ws;
+    const T zero = from_f32<T>(0.f);
+    const bool row1 = 2 * i + 1 < H;
+    for (int j = threadIdx.x & 63; j < Ws; j += 64) {
+        const bool col1 = 2 * j + 1 < W;
+        const T* s0 = src + (long long)(2 * i) * W + 2 * j;
+        const T v00 = s0[0];
+        const T v01 = col1 ? s0[1] : zero;
+        const T v10 = row1 ? s0[W] : zero;
+        const T v11 = (row1 && col1) ? s0[W + 1] : zero;
+        const long long o = (long long)i * Ws + j, ps = (long long)Hs * Ws;
+        dst[o] = v00;
+        dst[ps + o] = v01;
+        dst[2 * ps + o] = v10;
+        dst[3 * ps + o] = v11;
     }
 }
 
@@ -652,9 +700,9 @@ static hipError_t allow_big_lds(const void* fn, size_t lds) {
 }
 
 template <typename K>
-static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int NF, int CC, hipStream_t stream) {
+static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int NF, int CC, int buffers, hipStream_t stream) {
     const int grid = (p.nblocks + 7) / 8 * 8;
-    const size_t lds = (size_t)CC * kChBytes + (size_t)waves * NF * (CC + 2) * 32;
+    const size_t lds = (size_t)buffers * ((size_t)CC * kChBytes + (size_t)waves * NF * (CC + 2) * 32);
     if (lds > 160 * 1024) return PCONV_EUNSUPPORTED;
     PCONV_HIP(allow_big_lds((const void*)kern, lds));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(waves * 64), lds, stream, p);
@@ -663,7 +711,8 @@ static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int NF, in
 }
 
 template <typename T>
-static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int waves, int CPW, int KS, hipStream_t stream) {
+static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int waves, int CPW, int KS, int buffers,
+                        hipStream_t stream) {
     const int CC = CPW * waves;
     if (CC % kBucket != 0) return PCONV_EUNSUPPORTED;   // a chunk is a whole number of buckets
     const int NB = CC / kBucket;
@@ -704,11 +753,16 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
     }
     // (filters per wave, channels per wave and chunk, buckets per chunk); waves = 16 * NB / CPW
 #define PCONV_CASE(FF, PP, BB) \
-    if (NF == FF && CPW == PP && NB == BB) \
-        return launch_tiled_inst(tiled_kernel_nf##FF<PP, BB, T>, p, waves, NF, CC, stream);
+    if (NF == FF && CPW == PP && NB == BB && buffers == 1) \
+        return launch_tiled_inst(tiled_kernel_nf##FF<PP, BB, false, T>, p, waves, NF, CC, 1, stream);
+#define PCONV_CASE_DB(FF, PP) \
+    if (NF == FF && CPW == PP && NB == 1 && buffers == 2) \
+        return launch_tiled_inst(tiled_kernel_nf##FF<PP, 1, true, T>, p, waves, NF, CC, 2, stream);
     PCONV_CASE(1, 1, 1) PCONV_CASE(1, 2, 1) PCONV_CASE(1, 4, 1) PCONV_CASE(1, 2, 2) PCONV_CASE(1, 4, 2)
     PCONV_CASE(2, 1, 1) PCONV_CASE(2, 2, 1) PCONV_CASE(2, 2, 2)
+    PCONV_CASE_DB(1, 1) PCONV_CASE_DB(1, 2) PCONV_CASE_DB(2, 1) PCONV_CASE_DB(2, 2)
 #undef PCONV_CASE
+#undef PCONV_CASE_DB
     return PCONV_EUNSUPPORTED;
 }
 
@@ -767,6 +821,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     int R = tuning ? tuning->rows : 0, NF = tuning ? tuning->filters_per_wave : 0, waves = tuning ? tuning->waves : 0;
     int CPW = tuning ? tuning->channels_per_wave : 0;
     int KS = tuning ? tuning->channel_splits : 0;
+    int buffers = tuning ? tuning->buffers : 0;
     // What the tiled kernel sees: the layer itself at stride 1; at stride 2 the layer re-packed over the four
     // row/column parity planes of the input (a stride-1 problem with 4*C channels of half the height and width).
     const int tH = stride == 1 ? H : (H + 1) / 2, tW = stride == 1 ? W : (W + 1) / 2;
@@ -791,14 +846,13 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
             PCONV_HIP(hipMalloc(&wp->d_planes, need));
             wp->planes_bytes = need;
         }
-        const long long total = (long long)N * tC * tH * tW;
-        const unsigned grid = (unsigned)std::min<long long>((total + 255) / 256, 1 << 20);
+        const dim3 grid((unsigned)((long long)N * wp->C), (unsigned)((tH + 3) / 4));
         if (wp->dtype == PCONV_F16)
-            hipLaunchKernelGGL(parity_planes_kernel<__half>, dim3(grid), dim3(256), 0, st, (const __half*)x,
-                               (__half*)wp->d_planes, (long long)N * wp->C, H, W, tH, tW);
+            hipLaunchKernelGGL(parity_planes_kernel<__half>, grid, dim3(256), 0, st, (const __half*)x,
+                               (__half*)wp->d_planes, H, W, tH, tW);
         else
-            hipLaunchKernelGGL(parity_planes_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)x,
-                               (float*)wp->d_planes, (long long)N * wp->C, H, W, tH, tW);
+            hipLaunchKernelGGL(parity_planes_kernel<float>, grid, dim3(256), 0, st, (const float*)x,
+                               (float*)wp->d_planes, H, W, tH, tW);
         PCONV_HIP(hipGetLastError());
         tx = wp->d_planes;
     }
@@ -835,7 +889,8 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
                 }
             }
         }
-        if (KS < 0) return PCONV_EINVAL;
+        if (KS < 0 || buffers < 0 || buffers > 2) return PCONV_EINVAL;
+        if (buffers == 0) buffers = 1;
         if (waves == 0) waves = 8;
         if (NF == 0) NF = 1;
         if (CPW == 0) CPW = waves >= 16 ? 2 : 32 / waves;
@@ -877,8 +932,8 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.x_bytes = (unsigned long long)N * lay->C * tH * tW * esize;
         p.img_bytes = (unsigned)((size_t)lay->C * tH * tW * esize);
         p.plane_bytes = (unsigned)((size_t)tH * tW * esize);
-        return lay->dtype == PCONV_F16 ? launch_tiled<__half>(p, wp, NF, waves, CPW, KS, st)
-                                      : launch_tiled<float>(p, wp, NF, waves, CPW, KS, st);
+        return lay->dtype == PCONV_F16 ? launch_tiled<__half>(p, lay, NF, waves, CPW, KS, buffers, st)
+                                      : launch_tiled<float>(p, lay, NF, waves, CPW, KS, buffers, st);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);

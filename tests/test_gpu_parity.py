@@ -20,7 +20,10 @@ T, G = pc.KERNEL_TILED, pc.KERNEL_GENERIC
 TILED_TUNINGS = [dict(kernel=T, rows=7, filters_per_wave=nf, waves=w, channels_per_wave=cpw)
                  for nf, w, cpw in [(1, 8, 2), (2, 8, 2), (1, 16, 1), (1, 4, 4), (2, 16, 1), (1, 8, 4),
                                     (2, 16, 2), (1, 16, 2)]]
-ALL_TUNINGS = [dict(kernel=G)] + TILED_TUNINGS + [dict()]
+# two chunk buffers in LDS (one barrier per chunk)
+DB_TUNINGS = [dict(kernel=T, rows=7, filters_per_wave=nf, waves=w, channels_per_wave=cpw, buffers=2)
+              for nf, w, cpw in [(2, 16, 1), (1, 16, 1), (1, 8, 2), (2, 8, 2)]]
+ALL_TUNINGS = [dict(kernel=G)] + TILED_TUNINGS + DB_TUNINGS + [dict()]
 
 
 def say(*a):
@@ -63,7 +66,7 @@ def test_every_one_of_the_126_patterns():
                        assign="uniform", conn="bernoulli")
     layer = GpuLayer(spec)
     assert len(np.unique(layer.pid[layer.mask != 0])) == 126
-    check(layer, L.gen_activations(spec), [dict(), dict(kernel=G), TILED_TUNINGS[1], TILED_TUNINGS[6]])
+    check(layer, L.gen_activations(spec), [dict(), dict(kernel=G), TILED_TUNINGS[1], TILED_TUNINGS[6], DB_TUNINGS[0]])
     layer.free()
 
 
@@ -87,7 +90,8 @@ def test_ragged_shapes(case, dtype):
     layer = GpuLayer(spec)
     x = L.gen_activations(spec)
     # stride 2 reaches the tiled kernels through the parity-plane form of the layer
-    tunings = [dict(), dict(kernel=G), TILED_TUNINGS[0], TILED_TUNINGS[3], TILED_TUNINGS[6], TILED_TUNINGS[7]]
+    tunings = [dict(), dict(kernel=G), TILED_TUNINGS[0], TILED_TUNINGS[3], TILED_TUNINGS[6], TILED_TUNINGS[7],
+               DB_TUNINGS[0], DB_TUNINGS[2]]
     check(layer, x, tunings)
     check(layer, x, [dict()], relu=True)
     layer.free()
@@ -131,10 +135,12 @@ def test_channel_splits_agree_and_leave_the_workspace_reusable():
     layer = GpuLayer(spec)
     x = L.gen_activations(spec)
     ref = layer.oracle(x)
-    for nf, wv, cpw in [(2, 16, 2), (1, 16, 2), (1, 8, 4), (2, 8, 2), (1, 8, 2)]:
+    for nf, wv, cpw, nbuf in [(2, 16, 2, 1), (1, 16, 2, 1), (1, 8, 4, 1), (2, 8, 2, 1), (1, 8, 2, 1), (2, 16, 1, 2),
+                              (1, 8, 2, 2)]:
         nch = -(-spec.C // (wv * cpw))
         for ks in sorted({1, 2, 3, nch}):
-            t = dict(kernel=T, rows=7, filters_per_wave=nf, waves=wv, channels_per_wave=cpw, channel_splits=ks)
+            t = dict(kernel=T, rows=7, filters_per_wave=nf, waves=wv, channels_per_wave=cpw, channel_splits=ks,
+                     buffers=nbuf)
             say("splits", t)
             a = layer.run(x, **t)
             assert rel_err(a, ref) <= TOL[spec.dtype], t
@@ -142,7 +148,7 @@ def test_channel_splits_agree_and_leave_the_workspace_reusable():
             assert a.tobytes() == b.tobytes(), t
         with pytest.raises(pc.PconvError):
             layer.run(x, kernel=T, rows=7, filters_per_wave=nf, waves=wv, channels_per_wave=cpw,
-                      channel_splits=nch + 1)
+                      channel_splits=nch + 1, buffers=nbuf)
     # a larger problem on the same handle, then the first one again; ReLU and fp16 output through the split path
     big = L.gen_activations(L.shrink(spec, N=3))
     t = dict(kernel=T, rows=7, filters_per_wave=2, waves=16, channels_per_wave=2, channel_splits=4)
@@ -165,7 +171,7 @@ def test_config1_full_size():
     layer = GpuLayer(spec)
     assert layer.packed.n_kept == 18350
     x = L.gen_activations(spec)
-    ref = check(layer, x, [dict(), dict(kernel=G)] + TILED_TUNINGS[:7])
+    ref = check(layer, x, [dict(), dict(kernel=G)] + TILED_TUNINGS[:7] + DB_TUNINGS)
     # invariant on the GPU side as well: a removed kernel contributes nothing
     f, c = np.argwhere(layer.mask == 0)[0]
     w2 = layer.w.copy()
@@ -247,7 +253,7 @@ def test_config3_resnet50_shapes(N):
         layer = GpuLayer(spec)
         x = L.gen_activations(spec)
         if N == 1:
-            tun = [dict(), dict(kernel=G), TILED_TUNINGS[1], TILED_TUNINGS[5]]
+            tun = [dict(), dict(kernel=G), TILED_TUNINGS[1], TILED_TUNINGS[5], DB_TUNINGS[1]]
             check(layer, x, tun)
         else:
             check_batched(layer, x)
