@@ -356,10 +356,9 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
         p->eptr[(size_t)F * p->n_buckets] = (uint32_t)d;
 
         // balanced layouts for the tilings of the automatic choice (waves, filters per wave, channels per chunk)
-        static const int tilings[7][3] = {{16, 2, 32}, {16, 1, 32}, {8, 1, 32}, {16, 2, 16}, {16, 1, 16}, {8, 2, 16},
-                                          {8, 1, 16}};
-        p->balanced.resize(7);
-        for (int t = 0; t < 7; ++t)
+        static const int tilings[3][3] = {{16, 2, 32}, {16, 1, 32}, {8, 1, 32}};
+        p->balanced.resize(3);
+        for (int t = 0; t < 3; ++t)
             build_balanced(p, tilings[t][0], tilings[t][1], tilings[t][2], &p->balanced[(size_t)t]);
     } catch (const std::bad_alloc&) {
         delete p;
