@@ -9,6 +9,7 @@ timed on the host cores of the same box.
     python bench.py [--gpus 1] [--steps K] [--warmup W]
     python bench.py --layers vgg_n1|resnet_n32|vgg_n64 [--K 8] [--keep 0.28]   per-layer table (stderr) + JSON line
     python bench.py --tune                                                     every tiling variant on the workload
+    python bench.py --chain [--graph]            the 13 conv layers of VGG-16 at batch 1 (+ ReLU, max-pools) as one unit
 """
 from __future__ import annotations
 
@@ -77,14 +78,15 @@ class DeviceLayer:
         self.dy = torch.empty((spec.N, spec.F, spec.Ho, spec.Wo), dtype=tdt, device="cuda")
         self.dtype_code = pc.F16 if spec.dtype == "f16" else pc.F32
 
-    def launch(self, stream, **tuning):
+    def launch(self, stream, x=None, **tuning):
         s = self.spec
         flags = self.pc.FLAG_RELU if s.relu else 0
+        dx = self.dx if x is None else x
         if tuning:
-            self.pc.conv3x3_tuned(self.dx, self.dy, self.packed, self.db, s.N, s.H, s.W, s.stride, s.pad, flags, stream,
+            self.pc.conv3x3_tuned(dx, self.dy, self.packed, self.db, s.N, s.H, s.W, s.stride, s.pad, flags, stream,
                                   **tuning)
         else:
-            self.pc.conv3x3(self.dx, self.dy, self.packed, self.db, s.N, s.H, s.W, s.stride, s.pad, flags, stream)
+            self.pc.conv3x3(dx, self.dy, self.packed, self.db, s.N, s.H, s.W, s.stride, s.pad, flags, stream)
 
     def launch_dense(self, stream, dw):
         s = self.spec
@@ -151,6 +153,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--only", default="", help="with --layers: only the layer of this name")
+    ap.add_argument("--chain", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="with --chain: replay the chain as one HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (batches shard over GPUs without any exchange)")
@@ -164,6 +168,8 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream().cuda_stream
 
+    if args.chain:
+        return chain_bench(args, torch, pc, L)
     if args.layers:
         return layer_table(args, torch, pc, L, stream)
 
@@ -239,6 +245,45 @@ def main():
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(spec, layer)
     print(json.dumps(out), flush=True)
+
+
+def chain_bench(args, torch, pc, L):
+    """The 13 conv layers of VGG-16 at batch 1 (config 2: fused ReLU, 2x2 max-pool after each stage) launched back to
+    back as one unit: eager launches, or one HIP graph replayed.  At this size the chain is bound by per-kernel
+    start-up and launch gaps, which is what this mode shows."""
+    specs = L.config2()
+    layers = [DeviceLayer(s) for s in specs]
+    pooled = [torch.empty((s.N, s.F, s.Ho // 2, s.Wo // 2), dtype=torch.float32, device="cuda") if s.pool_after else None
+              for s in specs]
+    macs = sum(effective_macs(s, l.n_kept) for s, l in zip(specs, layers))
+
+    def run(stream):
+        x = layers[0].dx
+        for s, l, pl in zip(specs, layers, pooled):
+            l.launch(stream, x=x)
+            x = l.dy
+            if pl is not None:
+                pc.maxpool2x2(l.dy, pl, l.dtype_code, s.N, s.F, s.Ho, s.Wo, stream)
+                x = pl
+
+    side = torch.cuda.Stream()          # graph capture needs a non-default stream; default priority
+    with torch.cuda.stream(side):
+        st = side.cuda_stream
+        for _ in range(3):
+            run(st)                     # also makes the layers allocate their workspaces, outside any capture
+        side.synchronize()
+        fn = lambda: run(st)
+        if args.graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                run(st)
+            fn = g.replay
+        _, ev = time_launches(torch, fn, 300, 30)
+    out = {"chain": "VGG-16, 13 conv layers + ReLU + 4 max-pools, batch 1, fp32 (config 2)", "mode": "graph" if args.graph
+           else "eager", "us_per_chain": ev * 1e3, "eff_GMACs": macs / ev / 1e6, "kernels_per_chain": 13 + sum(
+               1 for q in pooled if q is not None)}
+    log(" ".join(f"{k}={v:.4g}" if isinstance(v, float) else f"{k}={v}" for k, v in out.items()))
+    print(json.dumps(out))
 
 
 def layer_table(args, torch, pc, L, stream):

@@ -162,6 +162,50 @@ def test_channel_splits_agree_and_leave_the_workspace_reusable():
     layer16.free()
 
 
+def test_hip_graph_replays_match_eager_launches():
+    """Two layers (the first splits its channels over workgroups, the second runs at stride 2 through the parity
+    form) and a max-pool, captured into one HIP graph: every replay, with eager work and synchronisations in between
+    and with fresh input values, gives the bytes of the eager launches."""
+    import torch
+    s1 = L.shrink(L.config1(), C=64, F=32, H=28, W=28, relu=True)
+    s2 = L.LayerSpec(cfg=13, idx=0, name="g2", N=1, C=32, F=24, H=14, W=14, stride=2, pad=1, K=8, keep=0.4)
+    l1, l2 = GpuLayer(s1), GpuLayer(s2)
+    x = torch.from_numpy(L.gen_activations(s1)).cuda()
+    y1 = torch.empty((1, 32, 28, 28), device="cuda")
+    p1 = torch.empty((1, 32, 14, 14), device="cuda")
+    y2 = torch.empty((1, 24, 7, 7), device="cuda")
+
+    def run(st):
+        pc.conv3x3(x, y1, l1.packed, l1.d_bias, 1, 28, 28, 1, 1, pc.FLAG_RELU, st)
+        pc.maxpool2x2(y1, p1, pc.F32, 1, 32, 28, 28, st)
+        pc.conv3x3(p1, y2, l2.packed, l2.d_bias, 1, 14, 14, 2, 1, 0, st)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run(side.cuda_stream)            # allocates workspaces and the parity form outside the capture
+        side.synchronize()
+        eager = y2.clone()
+        ref = l2.oracle(oracle.maxpool2x2(l1.oracle(x.cpu().numpy(), True)).astype(np.float32))
+        assert rel_err(eager.cpu().numpy(), ref) <= 2 * TOL["f32"]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            run(side.cuda_stream)
+        for rep in range(4):
+            say("graph replay", rep)
+            if rep == 2:                 # new input values: the graph reads the same buffers
+                x.mul_(0.5)
+                run(side.cuda_stream)
+                side.synchronize()
+                eager = y2.clone()
+            y2.fill_(-1.0)
+            torch.cuda.synchronize()
+            g.replay()
+            side.synchronize()
+            assert torch.equal(y2, eager), rep
+    l1.free()
+    l2.free()
+
+
 # ------------------------------------------------------------------------------------------------------------------
 # config 1: VGG-16 conv3_x-shaped layer at full size (the benchmark workload)
 # ------------------------------------------------------------------------------------------------------------------
