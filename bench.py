@@ -308,8 +308,8 @@ def layer_table(args, torch, pc, L, stream):
         _, ev = time_launches(torch, lambda: layer.launch(stream), steps, max(3, steps // 10))
         best = None
         if args.tune and spec.stride == 1:
-            for nf, wv, cpw, nbuf in [(1, 8, 4, 1), (1, 16, 2, 1), (2, 16, 2, 1), (2, 16, 1, 1), (1, 16, 1, 2),
-                                      (2, 16, 1, 2), (1, 8, 2, 2), (2, 8, 2, 2)]:
+            for nf, wv, cpw, nbuf in [(1, 8, 4, 1), (1, 16, 2, 1), (2, 16, 2, 1), (2, 16, 1, 1), (2, 8, 2, 1),
+                                      (1, 8, 2, 1), (1, 16, 1, 2), (2, 16, 1, 2), (1, 8, 2, 2), (2, 8, 2, 2)]:
                 for ks in (1, 2, 4, 8, 16):
                     t = dict(kernel=pc.KERNEL_TILED, rows=7, filters_per_wave=nf, waves=wv, channels_per_wave=cpw,
                              channel_splits=ks, buffers=nbuf)

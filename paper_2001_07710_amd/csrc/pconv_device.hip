@@ -142,16 +142,26 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 constexpr uint32_t kInvalidOffset = 0x80000000u;
 
+// One element as it is stored, in the low bits of a 32-bit register.  Loading and widening are two steps on purpose:
+// a conversion right behind the load would make the wave wait for the load at once, and the point of loading a chunk
+// ahead is that it stays in flight while the chunk before it is multiplied.
 template <typename T>
-__device__ __forceinline__ float buffer_load_f32(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff);
+__device__ __forceinline__ unsigned buffer_load_raw(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff);
 template <>
-__device__ __forceinline__ float buffer_load_f32<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+__device__ __forceinline__ unsigned buffer_load_raw<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
 }
 template <>
-__device__ __forceinline__ float buffer_load_f32<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-    const unsigned short h = __builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
-    return __half2float(__builtin_bit_cast(__half, h));
+__device__ __forceinline__ unsigned buffer_load_raw<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
+}
+template <typename T>
+__device__ __forceinline__ float raw_to_f32(unsigned bits);
+template <>
+__device__ __forceinline__ float raw_to_f32<float>(unsigned bits) { return __builtin_bit_cast(float, bits); }
+template <>
+__device__ __forceinline__ float raw_to_f32<__half>(unsigned bits) {
+    return __half2float(__builtin_bit_cast(__half, (unsigned short)bits));
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -336,7 +346,7 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     // this workgroup's range of chunks (all of them unless the channels are split)
     const int k_begin = (int)((long long)split * nchunks / p.KS), k_end = (int)((long long)(split + 1) * nchunks / p.KS);
 
-    float pre[CPW][R + 2];       // the wave's share of the next chunk's activations, in flight
+    unsigned pre[CPW][R + 2];    // the wave's share of the next chunk's activations, in flight, as stored
     uint2 epre[NF][NB];          // ... and of the next chunk's entries (lane l holds dwords 2l, 2l+1 of 16 entries)
     unsigned ecnt[NF];           // entries of each of the wave's filters in the chunk that is staged or in flight
 
@@ -355,7 +365,7 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             if (c < (unsigned)p.C) {
                 const unsigned soff = c * p.plane_bytes;
 #pragma unroll
-                for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_f32<T>(rsrc, voff[i], soff);
+                for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_raw<T>(rsrc, voff[i], soff);
             }
         }
         const int b0 = k * p.bpc, b1 = min(p.nbk, b0 + p.bpc);
@@ -380,9 +390,12 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             const int cc = wave + j * FW;
             if (staged[j] < (unsigned)p.C) {
                 float* dst = reinterpret_cast<float*>(lds + buf * kTileBytes + cc * kChBytes + lane * (kPR * 4));
-                *reinterpret_cast<float4*>(dst + 0) = make_float4(pre[j][0], pre[j][1], pre[j][2], pre[j][3]);
-                *reinterpret_cast<float4*>(dst + 4) = make_float4(pre[j][4], pre[j][5], pre[j][6], pre[j][7]);
-                *reinterpret_cast<float4*>(dst + 8) = make_float4(pre[j][8], 0.f, 0.f, 0.f);
+                float v[R + 2];
+#pragma unroll
+                for (int i = 0; i < R + 2; ++i) v[i] = raw_to_f32<T>(pre[j][i]);
+                *reinterpret_cast<float4*>(dst + 0) = make_float4(v[0], v[1], v[2], v[3]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+                *reinterpret_cast<float4*>(dst + 8) = make_float4(v[8], 0.f, 0.f, 0.f);
             }
         }
         // entries, as they are
