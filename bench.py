@@ -94,6 +94,21 @@ class DeviceLayer:
                               self.pc.FLAG_RELU if s.relu else 0, stream)
 
 
+def library_dense_ms(torch, layer, dw, steps: int = 20):
+    """The same dense convolution (masked weights, explicit zeros) by the vendor library that PyTorch-ROCm calls
+    (MIOpen), in the layer's storage type: the dense reference a user would otherwise run.  Not part of the product."""
+    s = layer.spec
+    F = torch.nn.functional
+    x4 = layer.dx.view(s.N, s.C, s.H, s.W)
+    b = layer.db.to(dw.dtype)
+    try:
+        fn = lambda: F.conv2d(x4, dw, b, stride=s.stride, padding=s.pad)
+        return time_launches(torch, fn, steps, 3)[1]
+    except Exception as e:          # the library may not support a shape or type; the bench goes on without it
+        log(f"library dense convolution skipped: {e}")
+        return None
+
+
 def time_launches(torch, fn, steps: int, warmup: int):
     """(wall ms per step, HIP-event ms per step) for `steps` launches after `warmup` untimed ones."""
     for _ in range(warmup):
@@ -212,7 +227,9 @@ def main():
         dw = torch.from_numpy(np.ascontiguousarray(wm)).cuda()
         _, dense_ms = time_launches(torch, lambda: layer.launch_dense(stream, dw), 20, 3)
         dense = {"ms": dense_ms, "dense_GMACs": spec.N * spec.Ho * spec.Wo * 9 * spec.C * spec.F / dense_ms / 1e6,
-                 "kind": "plain HIP direct convolution, fp32 vector ALU"}
+                 "kind": "plain HIP direct convolution, fp32 vector ALU",
+                 "library_ms": library_dense_ms(torch, layer, dw),
+                 "library_kind": "MIOpen through torch.nn.functional.conv2d, same masked weights"}
 
     flops = 2.0 * macs
     achieved = flops / (ev_ms * 1e-3) / 1e12
@@ -331,6 +348,9 @@ def layer_table(args, torch, pc, L, stream):
             dw = torch.from_numpy(np.ascontiguousarray(wm)).cuda()
             _, dms = time_launches(torch, lambda: layer.launch_dense(stream, dw), 3, 1)
             row["dense_us"] = dms * 1e3
+            lib_ms = library_dense_ms(torch, layer, dw, 5)
+            if lib_ms is not None:
+                row["miopen_us"] = lib_ms * 1e3
         rows.append(row)
         tot_macs += macs
         tot_ms += ev
