@@ -157,8 +157,9 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
 /*
  * pconv_conv3x3 with the kernel choice in the caller's hands, for tuning sweeps and for tests that must reach every
  * kernel.  A NULL `tuning`, or a field left 0, means "choose automatically" (what pconv_conv3x3 does).
- *   kernel            PCONV_KERNEL_TILED (stride 1 only: activations staged in LDS, weights in scalar registers)
- *                     or PCONV_KERNEL_GENERIC (any stride and pad, straight from global memory)
+ *   kernel            PCONV_KERNEL_TILED (activations staged in LDS; stride 2 through the parity form of the layer,
+ *                     see pconv_packed_parity_form) or PCONV_KERNEL_GENERIC (any stride and pad, straight from
+ *                     global memory)
  *   rows              tiled: output rows held per lane (7)
  *   filters_per_wave  tiled: filters accumulated at once by one wave (1 or 2)
  *   waves             tiled: waves per workgroup, 1..16

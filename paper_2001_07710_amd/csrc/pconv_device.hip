@@ -1,8 +1,10 @@
 // Device side of libpconv for gfx950 (MI355X): kernels, launch selection, device upload of the packed weights.
 //
 // Kernels in this file
-//   tiled_kernel    pattern-sparse 3x3 convolution, stride 1: activations staged in LDS in a lane-shaped layout,
-//                   one filter (or a few) per wave, weights in scalar registers, one code section per pattern
+//   tiled_kernel    pattern-sparse 3x3 convolution at unit stride: activations staged in LDS in a lane-shaped layout,
+//                   one or two filters per wave, one generated code section per pattern; stride 2 runs through it
+//                   on the layer re-packed over the four parity planes of the input
+//   parity_planes_kernel  the split of the input into those planes
 //   generic_kernel  the same sum for any stride and pad, one thread per output, straight from global memory
 //   dense_kernel    dense 3x3 convolution of the same shape (comparison baseline)
 //   maxpool_kernel  2x2 max-pool
@@ -165,7 +167,7 @@ __device__ __forceinline__ float raw_to_f32<__half>(unsigned bits) {
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// tiled kernel (stride 1)
+// tiled kernel (unit stride; stride 2 through the parity form of the layer)
 //
 // Lane layout.  A wave owns S segments of LW lanes.  A segment is OWS consecutive output columns of R = 7
 // consecutive output rows of one image, plus one halo lane on each side; lane t of a segment holds INPUT column
