@@ -196,6 +196,26 @@ __device__ __forceinline__ float raw_to_f32<__half>(unsigned bits) {
 #include "pattern_leaves.inc"
 static_assert(PCONV_LEAF_STRIDE == kLeafStride, "host packer and generated code disagree on the section stride");
 
+// Division of a 32-bit unsigned by a divisor that is fixed for the launch, as multiply-high and two shifts (Granlund
+// and Montgomery's round-up method: exact for every 32-bit dividend).  The hardware has no integer divide, and the
+// six divisions of the lane arithmetic below cost a workgroup a few thousand clocks at its start otherwise.
+struct FastDiv {
+    unsigned m, s1, s2;
+};
+static FastDiv make_fastdiv(unsigned d) {
+    unsigned l = 0;
+    while ((1ull << l) < d) ++l;   // ceil(log2 d)
+    FastDiv f;
+    f.m = (unsigned)((((1ull << l) - d) << 32) / d + 1);
+    f.s1 = l < 1 ? l : 1;
+    f.s2 = l > 0 ? l - 1 : 0;
+    return f;
+}
+__device__ __forceinline__ unsigned fastdiv(unsigned x, const FastDiv& f) {
+    const unsigned t = __umulhi(x, f.m);
+    return (t + ((x - t) >> f.s1)) >> f.s2;
+}
+
 struct TiledParams {
     const void* x;
     void* y;
@@ -217,6 +237,7 @@ struct TiledParams {
     unsigned long long x_bytes;
     unsigned img_bytes;      // C*H*W*sizeof(T)
     unsigned plane_bytes;    // H*W*sizeof(T)
+    FastDiv div_KS, div_NG, div_LW, div_segs_per_img, div_NCS;
 };
 
 constexpr int kR = 7;                       // output rows per lane
@@ -294,22 +315,22 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     const int per_xcd = gridDim.x >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= p.nblocks) return;
-    const int tile = p.KS == 1 ? logical : logical / p.KS;     // (slot, filter group)
+    const int tile = (int)fastdiv((unsigned)logical, p.div_KS);     // (slot, filter group)
     const int split = logical - tile * p.KS;
-    const int slot = tile / p.NG;
+    const int slot = (int)fastdiv((unsigned)tile, p.div_NG);
     const int grp = tile - slot * p.NG;
 
     // lane -> (segment, column)
-    const int s_local = lane / p.LW;
+    const int s_local = (int)fastdiv((unsigned)lane, p.div_LW);
     const int t = lane - s_local * p.LW;
     const int gseg = slot * p.S + s_local;
     const bool active = (s_local < p.S) && (gseg < p.NSEG);
     const int segs_per_img = p.NCS * p.NRB;
-    const int n0 = (slot * p.S) / segs_per_img;   // image of the slot's first segment (uniform)
+    const int n0 = (int)fastdiv((unsigned)(slot * p.S), p.div_segs_per_img);   // image of the slot's first segment (uniform)
     const int gs = active ? gseg : slot * p.S;
-    const int n = gs / segs_per_img;
+    const int n = (int)fastdiv((unsigned)gs, p.div_segs_per_img);
     const int rem = gs - n * segs_per_img;
-    const int rb = rem / p.NCS;
+    const int rb = (int)fastdiv((unsigned)rem, p.div_NCS);
     const int cs = rem - rb * p.NCS;
     const int ox = cs * p.OWS + t - 1;
     const int ix = ox + 1 - p.pad;
@@ -346,7 +367,8 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     }
     const int nchunks = p.perm ? p.nbk : (p.C + CC - 1) / CC;
     // this workgroup's range of chunks (all of them unless the channels are split)
-    const int k_begin = (int)((long long)split * nchunks / p.KS), k_end = (int)((long long)(split + 1) * nchunks / p.KS);
+    const int k_begin = (int)fastdiv((unsigned)(split * nchunks), p.div_KS);   // split, nchunks < 65536
+    const int k_end = (int)fastdiv((unsigned)((split + 1) * nchunks), p.div_KS);
 
     unsigned pre[CPW][R + 2];    // the wave's share of the next chunk's activations, in flight, as stored
     uint2 epre[NF][NB];          // ... and of the next chunk's entries (lane l holds dwords 2l, 2l+1 of 16 entries)
@@ -756,6 +778,11 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
     if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
     p.nblocks = (int)nb;
     p.KS = KS;
+    p.div_KS = make_fastdiv((unsigned)KS);
+    p.div_NG = make_fastdiv((unsigned)p.NG);
+    p.div_LW = make_fastdiv((unsigned)p.LW);
+    p.div_segs_per_img = make_fastdiv((unsigned)(p.NCS * p.NRB));
+    p.div_NCS = make_fastdiv((unsigned)p.NCS);
     p.ws = nullptr;
     p.counters = nullptr;
     if (KS > 1) {
