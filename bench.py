@@ -324,7 +324,7 @@ def layer_table(args, torch, pc, L, stream):
         steps = max(10, min(1000, int(2e10 / max(macs, 1))))
         _, ev = time_launches(torch, lambda: layer.launch(stream), steps, max(3, steps // 10))
         best = None
-        if args.tune and spec.stride == 1:
+        if args.tune:
             for nf, wv, cpw, nbuf in [(1, 8, 4, 1), (1, 16, 2, 1), (2, 16, 2, 1), (2, 16, 1, 1), (2, 8, 2, 1),
                                       (1, 8, 2, 1), (1, 16, 1, 2), (2, 16, 1, 2), (1, 8, 2, 2), (2, 8, 2, 2)]:
                 for ks in (1, 2, 4, 8, 16):

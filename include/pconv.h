@@ -168,7 +168,10 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *   channel_order     tiled: PCONV_ORDER_PLAIN stages the input channels in their own order; PCONV_ORDER_BALANCED
  *                     uses the per-workgroup order computed at pack time that gives every wave the same number of
  *                     kept kernels per chunk (exists for waves x filters_per_wave = 16x2, 16x1, 8x1 with 32
- *                     channels per chunk); PCONV_ORDER_AUTO takes the balanced order where it exists
+ *                     channels per chunk); PCONV_ORDER_AUTO takes the balanced order where it exists.
+ *                     Stride 2 with even H and W and waves = 16, channels_per_wave = 2 reads the parity planes
+ *                     straight from x, channels in their own order (PLAIN or AUTO); PCONV_ORDER_BALANCED, any
+ *                     other tiling, or an odd H or W splits x into planes in a pass of its own first
  *   channel_splits    tiled: workgroups that share one output tile, each taking a contiguous range of the channel
  *                     chunks (1 = no split, no workspace; at most the number of chunks; 0 = as many as give one
  *                     round of workgroups over the GPU's compute units)

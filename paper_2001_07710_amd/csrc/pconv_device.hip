@@ -157,6 +157,25 @@ template <>
 __device__ __forceinline__ unsigned buffer_load_raw<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
     return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
 }
+// Two neighbouring elements (an even and the following odd column) in one load.
+template <typename T>
+__device__ __forceinline__ void buffer_load_raw2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, unsigned& even,
+                                                 unsigned& odd);
+template <>
+__device__ __forceinline__ void buffer_load_raw2<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff,
+                                                        unsigned& even, unsigned& odd) {
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    const v2u v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
+    even = v.x;
+    odd = v.y;
+}
+template <>
+__device__ __forceinline__ void buffer_load_raw2<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff,
+                                                         unsigned& even, unsigned& odd) {
+    const unsigned v = __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
+    even = v & 0xFFFFu;
+    odd = v >> 16;
+}
 template <typename T>
 __device__ __forceinline__ float raw_to_f32(unsigned bits);
 template <>
@@ -238,6 +257,7 @@ struct TiledParams {
     unsigned img_bytes;      // C*H*W*sizeof(T)
     unsigned plane_bytes;    // H*W*sizeof(T)
     FastDiv div_KS, div_NG, div_LW, div_segs_per_img, div_NCS;
+    int pair;                // the layer is a parity form and x is the original input (kernels with PAIR staging)
 };
 
 constexpr int kR = 7;                       // output rows per lane
@@ -290,8 +310,13 @@ __device__ __forceinline__ void run_entries(unsigned lane_addr, unsigned entry_a
 // the other and meets the others at ONE barrier per chunk, so the LDS writes of the waves that finish early run
 // beside the multiply-adds of the others.  Without DB there is one buffer and two barriers per chunk (everybody done
 // reading, everybody done writing).
-template <int NF, int CPW, int NB, bool DB, typename T>
+// PAIR: a stride-2 layer in its parity form (see derive_for_stride2), staged straight from the original input.  The
+// chunk's 32 channels are the four parity planes of 8 input channels; wave w stages the two column-parity planes of
+// (input channel w/2, row parity w%2) with one two-element load per row, so no separate pass splits the input and
+// the staging needs half the load instructions.  Needs even H and W, 16 waves, two channels per wave, channels in their own order.
+template <int NF, int CPW, int NB, bool DB, bool PAIR, typename T>
 __device__ __forceinline__ void tiled_body(const TiledParams& p) {
+    static_assert(!PAIR || (CPW == 2 && NB == 2 && !DB), "the paired staging is built for 16 waves x 2 channels");
     constexpr int R = kR;
     constexpr int CC = 16 * NB;          // channels per chunk
     constexpr int FW = CC / CPW;         // waves per workgroup
@@ -341,8 +366,10 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     for (int i = 0; i < R + 2; ++i) {
         const int iy = r0 + i - p.pad;
         const bool ok = active && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W;
-        voff[i] = ok ? (unsigned)(n - n0) * p.img_bytes + (unsigned)(iy * p.W + ix) * (unsigned)sizeof(T)
-                     : kInvalidOffset;
+        // PAIR: (iy, ix) index a parity plane; the load reads row 2*iy (+ the wave's row parity) and columns 2*ix,
+        // 2*ix+1 of the original image, whose rows are 2*W long
+        const unsigned elem = PAIR ? (unsigned)(4 * iy * p.W + 2 * ix) : (unsigned)(iy * p.W + ix);
+        voff[i] = ok ? (unsigned)(n - n0) * p.img_bytes + elem * (unsigned)sizeof(T) : kInvalidOffset;
     }
     const unsigned long long base_off = (unsigned long long)n0 * p.img_bytes;
     const unsigned long long left = p.x_bytes - base_off;
@@ -382,14 +409,26 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     };
     unsigned staged[CPW];        // channels in flight (kNoChannel: none)
     auto issue_loads = [&](int k) {
-#pragma unroll
-        for (int j = 0; j < CPW; ++j) {
-            const unsigned c = channel_at(k * CC + wave + j * FW);
-            staged[j] = c;
+        if constexpr (PAIR) {
+            // parity-form channel 4*c_in + 2*a at this wave's position of the staging order (+1: the odd columns)
+            const unsigned c = channel_at(k * CC + 2 * wave);
+            staged[0] = c < (unsigned)p.C ? c : kNoChannel;
+            staged[1] = c < (unsigned)p.C ? c + 1 : kNoChannel;
             if (c < (unsigned)p.C) {
-                const unsigned soff = c * p.plane_bytes;
+                const unsigned soff = (c >> 2) * 4u * p.plane_bytes + ((c >> 1) & 1u) * 2u * p.W * (unsigned)sizeof(T);
 #pragma unroll
-                for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_raw<T>(rsrc, voff[i], soff);
+                for (int i = 0; i < R + 2; ++i) buffer_load_raw2<T>(rsrc, voff[i], soff, pre[0][i], pre[1][i]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) {
+                const unsigned c = channel_at(k * CC + wave + j * FW);
+                staged[j] = c;
+                if (c < (unsigned)p.C) {
+                    const unsigned soff = c * p.plane_bytes;
+#pragma unroll
+                    for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_raw<T>(rsrc, voff[i], soff);
+                }
             }
         }
         const int b0 = k * p.bpc, b1 = min(p.nbk, b0 + p.bpc);
@@ -411,7 +450,7 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     auto write_lds = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < CPW; ++j) {
-            const int cc = wave + j * FW;
+            const int cc = PAIR ? 2 * wave + j : wave + j * FW;
             if (staged[j] < (unsigned)p.C) {
                 float* dst = reinterpret_cast<float*>(lds + buf * kTileBytes + cc * kChBytes + lane * (kPR * 4));
                 float v[R + 2];
@@ -597,15 +636,15 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
 
 // The compiler may allocate 2*n vector registers under amdgpu_num_vgpr(n) on this target; the accumulators of the
 // pattern sections sit above that: 21 registers per filter slot, ending at v127.
-template <int CPW, int NB, bool DB, typename T>
+template <int CPW, int NB, bool DB, bool PAIR, typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(53))) void tiled_kernel_nf1(const TiledParams p) {
     static_assert(PCONV_ACC_BASE_S0 >= 2 * 53, "accumulators overlap the compiler's registers");
-    tiled_body<1, CPW, NB, DB, T>(p);
+    tiled_body<1, CPW, NB, DB, PAIR, T>(p);
 }
-template <int CPW, int NB, bool DB, typename T>
+template <int CPW, int NB, bool DB, bool PAIR, typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(43))) void tiled_kernel_nf2(const TiledParams p) {
     static_assert(PCONV_ACC_BASE_S1 >= 2 * 43, "accumulators overlap the compiler's registers");
-    tiled_body<2, CPW, NB, DB, T>(p);
+    tiled_body<2, CPW, NB, DB, PAIR, T>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -796,10 +835,16 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
     // (filters per wave, channels per wave and chunk, buckets per chunk); waves = 16 * NB / CPW
 #define PCONV_CASE(FF, PP, BB) \
     if (NF == FF && CPW == PP && NB == BB && buffers == 1) \
-        return launch_tiled_inst(tiled_kernel_nf##FF<PP, BB, false, T>, p, waves, NF, CC, 1, stream);
+        return launch_tiled_inst(tiled_kernel_nf##FF<PP, BB, false, false, T>, p, waves, NF, CC, 1, stream);
 #define PCONV_CASE_DB(FF, PP) \
     if (NF == FF && CPW == PP && NB == 1 && buffers == 2) \
-        return launch_tiled_inst(tiled_kernel_nf##FF<PP, 1, true, T>, p, waves, NF, CC, 2, stream);
+        return launch_tiled_inst(tiled_kernel_nf##FF<PP, 1, true, false, T>, p, waves, NF, CC, 2, stream);
+    if (p.pair) {
+        if (CPW != 2 || NB != 2 || buffers != 1 || p.perm) return PCONV_EUNSUPPORTED;
+        if (NF == 1) return launch_tiled_inst(tiled_kernel_nf1<2, 2, false, true, T>, p, waves, NF, CC, 1, stream);
+        if (NF == 2) return launch_tiled_inst(tiled_kernel_nf2<2, 2, false, true, T>, p, waves, NF, CC, 1, stream);
+        return PCONV_EUNSUPPORTED;
+    }
     PCONV_CASE(1, 1, 1) PCONV_CASE(1, 2, 1) PCONV_CASE(1, 4, 1) PCONV_CASE(1, 2, 2) PCONV_CASE(1, 4, 2)
     PCONV_CASE(2, 1, 1) PCONV_CASE(2, 2, 1) PCONV_CASE(2, 2, 2)
     PCONV_CASE_DB(1, 1) PCONV_CASE_DB(1, 2) PCONV_CASE_DB(2, 1) PCONV_CASE_DB(2, 2)
@@ -873,6 +918,14 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     if (kernel == PCONV_KERNEL_TILED && !can_tile) return PCONV_EUNSUPPORTED;
     const pconv_packed* lay = wp;
     const void* tx = x;
+    // Stride 2 with even H and W: the kernels with paired staging read the parity planes straight from x (16 waves,
+    // two channels per wave, channels in their own order).  Otherwise the input is split into planes by a pass of
+    // its own first.
+    const bool automatic = waves == 0 && NF == 0 && CPW == 0;
+    const int order = tuning ? tuning->channel_order : PCONV_ORDER_AUTO;
+    const bool pair = kernel == PCONV_KERNEL_TILED && stride == 2 && H % 2 == 0 && W % 2 == 0 &&
+                      order != PCONV_ORDER_BALANCED && buffers <= 1 &&
+                      (automatic || (waves == 16 && (CPW == 0 || CPW == 2)));
     if (kernel == PCONV_KERNEL_TILED && stride == 2) {
         if (!wp->by_parity[pad]) {
             pconv_packed* child = nullptr;
@@ -880,6 +933,8 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
             wp->by_parity[pad] = child;
         }
         lay = wp->by_parity[pad];
+    }
+    if (kernel == PCONV_KERNEL_TILED && stride == 2 && !pair) {
         const size_t need = (size_t)N * tC * tH * tW * esize;
         if (need > wp->planes_bytes) {
             if (wp->d_planes) PCONV_HIP(hipFree(wp->d_planes));   // hipFree waits for work that may still use it
@@ -902,7 +957,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     if (kernel == PCONV_KERNEL_TILED) {
         if (R == 0) R = kR;
         if (R != kR) return PCONV_EUNSUPPORTED;
-        if (waves == 0 && NF == 0 && CPW == 0) {
+        if (automatic) {
             // Automatic tiling: the candidate with the smallest estimated time.  The estimate is a count of clocks
             // per workgroup from measured phase costs of this kernel on MI355X (one workgroup per CU at a time):
             // a fixed start-up, per chunk the larger of multiply-add issue and the global-load rate of the staging
@@ -915,13 +970,14 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
             double best = 0.0;
             for (int i = 0; i < 4; ++i) {
                 const int nf = cand[i][0], w = cand[i][1], cpw = cand[i][2], cc = w * cpw;
+                if (pair && (w != 16 || cpw != 2)) continue;   // the paired staging is built for this tiling
                 if (cc == 16 && lay->C > 16) continue;   // half-size chunks only pay for layers with few channels
                 const long long tiles = slots * ((lay->F + nf * w - 1) / (nf * w));
                 const int nch = (lay->C + cc - 1) / cc;
                 const double per_filter_chunk = (double)lay->n_kept / ((double)lay->F * nch);
                 for (int ks = 1; ks <= std::min(nch, 16); ks *= 2) {
                     const double issue = (w / 4) * nf * per_filter_chunk * 128.0 + 750.0;
-                    const double staging = std::min(lay->C, cc) * 9.0 * 18.0;
+                    const double staging = std::min(lay->C, cc) * 9.0 * 18.0 * (pair ? 0.5 : 1.0);
                     const double chunk = std::max(issue, staging) + 3400.0;
                     const double combine = ks == 1 ? 1500.0 * nf : nf == 1 ? 1200.0 * ks : 4500.0 + 2400.0 * ks;
                     const double wg = 9000.0 + (double)((nch + ks - 1) / ks) * chunk + combine;
@@ -957,9 +1013,9 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.bpc = (CPW * waves) / kBucket;
         p.perm = nullptr;
         p.perm_stride = 0;
+        p.pair = pair ? 1 : 0;
         // a balanced layout exists for the tilings of the automatic choice
-        const int order = tuning ? tuning->channel_order : PCONV_ORDER_AUTO;
-        if (order != PCONV_ORDER_PLAIN) {
+        if (order != PCONV_ORDER_PLAIN && !pair) {
             for (const BalancedLayout& b : lay->balanced)
                 if (b.fw == waves && b.nf == NF && b.cc == CPW * waves && b.d_ent) {
                     p.ent = b.d_ent;

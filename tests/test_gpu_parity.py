@@ -162,6 +162,26 @@ def test_channel_splits_agree_and_leave_the_workspace_reusable():
     layer16.free()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("pad", [0, 1])
+def test_stride2_both_staging_paths(pad, dtype):
+    """Stride 2 with even H and W reads the parity planes straight from the input (paired staging); with the balanced
+    channel order, or odd sizes, a separate pass splits the input first.  Both against the oracle, several images,
+    more channels than one chunk, a filter count that leaves waves without a filter."""
+    spec = L.LayerSpec(cfg=14, idx=pad, name="s2paths", N=3, C=20, F=40, H=18, W=26, stride=2, pad=pad, dtype=dtype,
+                       K=8, keep=0.45)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    paired = [dict(), dict(kernel=T, rows=7, filters_per_wave=2, waves=16, channels_per_wave=2),
+              dict(kernel=T, rows=7, filters_per_wave=1, waves=16, channels_per_wave=2, channel_splits=2)]
+    split_first = [dict(kernel=T, rows=7, filters_per_wave=2, waves=16, channels_per_wave=2,
+                        channel_order=pc.ORDER_BALANCED),
+                   dict(kernel=T, rows=7, filters_per_wave=1, waves=8, channels_per_wave=4)]
+    check(layer, x, paired + split_first + [dict(kernel=G)])
+    check(layer, x, [dict()], relu=True)
+    layer.free()
+
+
 def test_hip_graph_replays_match_eager_launches():
     """Two layers (the first splits its channels over workgroups, the second runs at stride 2 through the parity
     form) and a max-pool, captured into one HIP graph: every replay, with eager work and synchronisations in between
