@@ -63,11 +63,13 @@ class Regs:
         self.count = low - self.first
 
 
-def request_next(rg: Regs, q: int) -> list:
+def request_next(rg: Regs, q: int, rows8: bool = False) -> list:
     """The header of the next entry is in v[m]: request that entry's activations and weights into set q and the
-    header of the entry after it.  Leaves the next entry's section offset in s65."""
+    header of the entry after it.  Leaves the next entry's section offset in s65.  rows8: the layer's kernels only
+    have taps in their first two rows (a stride-2 layer over parity planes), so patch rows 8 and 9 are never read
+    and are not fetched."""
     x, w = rg.x[q], rg.w[q]
-    return [
+    lines = [
         f"v_readfirstlane_b32 s65, v{rg.m}",
         "s_and_b32 s64, s65, %[ccmask]",
         f"s_mul_i32 s64, s64, {CH_BYTES}",
@@ -80,6 +82,9 @@ def request_next(rg: Regs, q: int) -> list:
         f"v_add_u32 v{rg.ve}, 32, v{rg.ve}",
         "s_and_b32 s65, s65, 0xffffff00",
     ]
+    if rows8:
+        lines = [l for l in lines if not l.startswith("ds_read_b64")]
+    return lines
 
 
 def jump(q: int) -> list:
@@ -91,7 +96,7 @@ def jump(q: int) -> list:
     ]
 
 
-def entry_loop(nf: int, slot: int) -> list:
+def entry_loop(nf: int, slot: int, rows8: bool = False) -> list:
     rg = Regs(nf)
     base = acc_base(slot)
     ms = masks()
@@ -107,16 +112,18 @@ def entry_loop(nf: int, slot: int) -> list:
         "s_addc_u32 s59, s61, 0",
         f"ds_read_b32 v{rg.m}, v{rg.ve} offset:16",
         "s_waitcnt lgkmcnt(0)",
-    ] + request_next(rg, 0) + jump(0)
+    ] + request_next(rg, 0, rows8) + jump(0)
     for p in (0, 1):
         for i, mask in enumerate(ms):
             lines.append(f".p2align {LEAF_ALIGN_LOG2}")
             if p == 0 and i == 0:
                 lines.append("3:")
             lines.append("s_waitcnt lgkmcnt(0)")
-            lines += request_next(rg, 1 - p)
+            lines += request_next(rg, 1 - p, rows8)
             q = 0
             for t in range(9):
+                if rows8 and t >= 6 and (mask >> t) & 1:
+                    continue       # never packed for such a layer; the section stays as a placeholder of its slot
                 if (mask >> t) & 1:
                     ky, kx = divmod(t, 3)
                     for r in range(R):
@@ -157,6 +164,7 @@ def main(out_path: str):
         out.append(f"#define PCONV_SCRATCH_FIRST_NF{nf} {Regs(nf).first}")
         for s in range(nf):
             out.append(f"#define PCONV_ENTRY_LOOP_NF{nf}_S{s} \\\n    {as_c_string(entry_loop(nf, s))}")
+            out.append(f"#define PCONV_ENTRY_LOOP_ROWS8_NF{nf}_S{s} \\\n    {as_c_string(entry_loop(nf, s, True))}")
             out.append(f"#define PCONV_ENTRY_LOOP_CLOBBERS_NF{nf}_S{s} {clobbers(nf, s)}")
             out.append("")
     with open(out_path, "w") as fh:

@@ -292,24 +292,28 @@ __device__ __forceinline__ void read_acc(float (&a)[3][kR]) {
 
 // Runs `count` (>= 1) entries stored in LDS from byte address `entry_addr` on, for the filter in slot SLOT of a
 // kernel with NF slots.  `lane_addr` is the LDS byte address of this lane's patch of channel 0 of the chunk.
-template <int NF, int SLOT, int CC>
+// ROWS8: the loop variant for layers whose kernels have no tap in their third row (a stride-2 layer over parity
+// planes): patch rows 8 and 9 are not fetched.
+template <int NF, int SLOT, int CC, bool ROWS8>
 __device__ __forceinline__ void run_entries(unsigned lane_addr, unsigned entry_addr, unsigned count) {
     const unsigned cnt = __builtin_amdgcn_readfirstlane(count);
-#define PCONV_LOOP(NFv, Sv)                                                                     \
-    asm volatile(PCONV_ENTRY_LOOP_NF##NFv##_S##Sv                                               \
+#define PCONV_LOOP_ASM(TEXT, NFv, Sv)                                                           \
+    asm volatile(TEXT                                                                           \
                  :                                                                              \
                  : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr), [cnt] "s"(cnt), [ccmask] "n"(CC - 1) \
                  : "memory", PCONV_ENTRY_LOOP_CLOBBERS_NF##NFv##_S##Sv)
+#define PCONV_LOOP(NFv, Sv)                                                                     \
+    do {                                                                                        \
+        if constexpr (ROWS8) PCONV_LOOP_ASM(PCONV_ENTRY_LOOP_ROWS8_NF##NFv##_S##Sv, NFv, Sv);   \
+        else PCONV_LOOP_ASM(PCONV_ENTRY_LOOP_NF##NFv##_S##Sv, NFv, Sv);                         \
+    } while (0)
     if constexpr (NF == 1) { PCONV_LOOP(1, 0); }
     else if constexpr (NF == 2 && SLOT == 0) { PCONV_LOOP(2, 0); }
     else { PCONV_LOOP(2, 1); }
 #undef PCONV_LOOP
+#undef PCONV_LOOP_ASM
 }
 
-// DB: two chunk buffers in LDS.  A wave multiplies chunk k out of one buffer, then writes its share of chunk k+1 into
-// the other and meets the others at ONE barrier per chunk, so the LDS writes of the waves that finish early run
-// beside the multiply-adds of the others.  Without DB there is one buffer and two barriers per chunk (everybody done
-// reading, everybody done writing).
 // PAIR: a stride-2 layer in its parity form (see derive_for_stride2), staged straight from the original input.  The
 // chunk's 32 channels are the four parity planes of 8 input channels; wave w stages the two column-parity planes of
 // (input channel w/2, row parity w%2) with one two-element load per row, so no separate pass splits the input and
@@ -417,7 +421,8 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             if (c < (unsigned)p.C) {
                 const unsigned soff = (c >> 2) * 4u * p.plane_bytes + ((c >> 1) & 1u) * 2u * p.W * (unsigned)sizeof(T);
 #pragma unroll
-                for (int i = 0; i < R + 2; ++i) buffer_load_raw2<T>(rsrc, voff[i], soff, pre[0][i], pre[1][i]);
+                // kernels of a parity form have taps in their first two rows only: the last patch row is never read
+                for (int i = 0; i < R + 1; ++i) buffer_load_raw2<T>(rsrc, voff[i], soff, pre[0][i], pre[1][i]);
             }
         } else {
 #pragma unroll
@@ -455,10 +460,10 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
                 float* dst = reinterpret_cast<float*>(lds + buf * kTileBytes + cc * kChBytes + lane * (kPR * 4));
                 float v[R + 2];
 #pragma unroll
-                for (int i = 0; i < R + 2; ++i) v[i] = raw_to_f32<T>(pre[j][i]);
+                for (int i = 0; i < R + 2; ++i) v[i] = (PAIR && i > R) ? 0.f : raw_to_f32<T>(pre[j][i]);
                 *reinterpret_cast<float4*>(dst + 0) = make_float4(v[0], v[1], v[2], v[3]);
                 *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
-                *reinterpret_cast<float4*>(dst + 8) = make_float4(v[8], 0.f, 0.f, 0.f);
+                if constexpr (!PAIR) *reinterpret_cast<float4*>(dst + 8) = make_float4(v[8], 0.f, 0.f, 0.f);
             }
         }
         // entries, as they are
@@ -473,8 +478,8 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     auto compute = [&](int buf, const unsigned (&cnt)[NF]) {
         const unsigned tile_addr = lane_addr + buf * kTileBytes;
         const unsigned ent_addr = lds0 + kEntBase + buf * kEntBytes + wave * NF * kEntRegion;
-        if constexpr (NF > 0) { if (cnt[0]) run_entries<NF, 0, CC>(tile_addr, ent_addr + 0 * kEntRegion, cnt[0]); }
-        if constexpr (NF > 1) { if (cnt[1]) run_entries<NF, 1, CC>(tile_addr, ent_addr + 1 * kEntRegion, cnt[1]); }
+        if constexpr (NF > 0) { if (cnt[0]) run_entries<NF, 0, CC, PAIR>(tile_addr, ent_addr + 0 * kEntRegion, cnt[0]); }
+        if constexpr (NF > 1) { if (cnt[1]) run_entries<NF, 1, CC, PAIR>(tile_addr, ent_addr + 1 * kEntRegion, cnt[1]); }
     };
 
     unsigned cnt_now[NF];
