@@ -336,6 +336,14 @@ def layer_table(args, torch, pc, L, stream):
                         continue
                     if best is None or tv < best[0]:
                         best = (tv, nf, wv, cpw, ks, nbuf)
+            for nf in (1, 2):          # the kernel with four columns per lane
+                try:
+                    _, tv = time_launches(torch, lambda: layer.launch(stream, kernel=pc.KERNEL_QUAD, filters_per_wave=nf),
+                                          max(5, steps // 4), 2)
+                except pc.PconvError:
+                    continue
+                if best is None or tv < best[0]:
+                    best = (tv, nf, 16, 1, 1, "quad")
         ab = algorithmic_bytes(spec, layer.n_kept)
         row = {"layer": spec.name, "C": spec.C, "F": spec.F, "H": spec.H, "N": spec.N, "stride": spec.stride,
                "dtype": spec.dtype, "keep": spec.keep, "K": spec.K, "n_kept": layer.n_kept, "us": ev * 1e3,

@@ -180,7 +180,7 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *                     one chunk running beside the multiply-adds of the chunk before
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
-enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2 };
+enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2, PCONV_KERNEL_QUAD = 3 };
 enum { PCONV_ORDER_AUTO = 0, PCONV_ORDER_PLAIN = 1, PCONV_ORDER_BALANCED = 2 };
 typedef struct pconv_tuning {
     int kernel;

@@ -16,7 +16,7 @@ import numpy as np
 F32, F16 = 0, 1
 FLAG_RELU = 1
 PACK_HOST_ONLY = 1
-KERNEL_AUTO, KERNEL_TILED, KERNEL_GENERIC = 0, 1, 2
+KERNEL_AUTO, KERNEL_TILED, KERNEL_GENERIC, KERNEL_QUAD = 0, 1, 2, 3
 ORDER_AUTO, ORDER_PLAIN, ORDER_BALANCED = 0, 1, 2
 OK, EINVAL, EPATTERN, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
 

@@ -139,6 +139,106 @@ def entry_loop(nf: int, slot: int, rows8: bool = False) -> list:
     return lines
 
 
+# ---------------------------------------------------------------------------------------------------------------
+# The "quad" kernel: a lane holds FOUR neighbouring input columns of RQ + 2 input rows (six 128-bit LDS reads) and
+# accumulates RQ = 4 output rows of SIX output columns: a tap (ky,kx) on input column c (0..3) belongs to output
+# column c + 1 - kx relative to the quad, i.e. to accumulator column j = c + 2 - kx (0..5); columns 0 and 5 are
+# handed to the neighbouring lanes once, after the last channel.  16 multiply-adds per tap, 64 per kept kernel and
+# jump instead of 28: the jump, whose instruction refetch is what the one-column kernel waits for most, is paid less
+# than half as often.  One register set (the patch is 24 registers); sections are 512 bytes apart.
+# ---------------------------------------------------------------------------------------------------------------
+RQ = 4
+QUAD_ALIGN_LOG2 = 9
+QUAD_ROW_BYTES = 64 * 16          # one patch row of a channel in LDS: 64 lanes x four columns
+QUAD_CH_BYTES = (RQ + 2) * QUAD_ROW_BYTES
+
+
+def quad_acc_base(slot: int) -> int:
+    return TOP - 6 * RQ * (slot + 1)
+
+
+class QuadRegs:
+    def __init__(self, nf: int):
+        low = quad_acc_base(nf - 1)
+        self.x = (low - 4 * (RQ + 2)) & ~1      # x[i][c] = x + 4*i + c
+        self.w = self.x - 4
+        self.m = self.w - 1
+        self.va = self.w - 2
+        self.ve = self.w - 3
+        self.first = self.ve
+        self.count = low - self.first
+
+
+def quad_fetch(rg: QuadRegs) -> list:
+    """The header of the next entry is in v[m]: fetch its patch and weights and the header after it; section offset
+    of the next entry in s65."""
+    lines = [
+        f"v_readfirstlane_b32 s65, v{rg.m}",
+        "s_and_b32 s64, s65, 15",
+        f"s_mul_i32 s64, s64, {QUAD_CH_BYTES}",
+        f"v_add_u32 v{rg.va}, s64, %[vlane]",
+    ]
+    for i in range(RQ + 2):
+        lines.append(f"ds_read_b128 v[{rg.x + 4 * i}:{rg.x + 4 * i + 3}], v{rg.va} offset:{i * QUAD_ROW_BYTES}")
+    lines += [
+        f"ds_read_b128 v[{rg.w}:{rg.w + 3}], v{rg.ve}",
+        f"ds_read_b32 v{rg.m}, v{rg.ve} offset:48",
+        f"v_add_u32 v{rg.ve}, 32, v{rg.ve}",
+        "s_and_b32 s65, s65, 0xffffff00",
+        "s_lshl_b32 s65, s65, 1",
+        "s_add_u32 s62, s60, s65",
+        "s_addc_u32 s63, s61, 0",
+        "s_setpc_b64 s[62:63]",
+    ]
+    return lines
+
+
+def quad_entry_loop(nf: int, slot: int) -> list:
+    rg = QuadRegs(nf)
+    base = quad_acc_base(slot)
+    ms = masks()
+    lines = [
+        "s_sub_u32 s66, %[cnt], 1",
+        f"v_mov_b32 v{rg.ve}, %[ventry]",
+        "s_getpc_b64 s[60:61]",
+        "1:",
+        "s_add_u32 s60, s60, 3f-1b",                              # s[60:61]: the sections
+        "s_addc_u32 s61, s61, 0",
+        f"s_add_u32 s56, s60, {len(ms) << QUAD_ALIGN_LOG2}",       # s[56:57]: behind the last section
+        "s_addc_u32 s57, s61, 0",
+        f"ds_read_b32 v{rg.m}, v{rg.ve} offset:16",
+        "s_waitcnt lgkmcnt(0)",
+    ] + quad_fetch(rg)
+    for i, mask in enumerate(ms):
+        lines.append(f".p2align {QUAD_ALIGN_LOG2}")
+        if i == 0:
+            lines.append("3:")
+        lines.append("s_waitcnt lgkmcnt(0)")
+        q = 0
+        for t in range(9):
+            if (mask >> t) & 1:
+                ky, kx = divmod(t, 3)
+                for c in range(4):
+                    for r in range(RQ):
+                        lines.append(f"v_fmac_f32 v{base + 4 * (c + 2 - kx) + r}, v{rg.w + q}, v{rg.x + 4 * (r + ky) + c}")
+                q += 1
+        lines += [
+            "s_sub_u32 s66, s66, 1",                               # borrow: this was the last entry
+            "s_cbranch_scc0 2f",
+            "s_setpc_b64 s[56:57]",
+            "2:",
+        ] + quad_fetch(rg)
+    lines += [f".p2align {QUAD_ALIGN_LOG2}", "s_waitcnt lgkmcnt(0)"]
+    return lines
+
+
+def quad_clobbers(nf: int, slot: int) -> str:
+    rg = QuadRegs(nf)
+    regs = [f'"v{rg.first + i}"' for i in range(rg.count)] + [f'"v{quad_acc_base(slot) + i}"' for i in range(6 * RQ)]
+    regs += [f'"s{i}"' for i in range(56, 67)] + ['"scc"']
+    return ", ".join(regs)
+
+
 def as_c_string(lines: list) -> str:
     return " \\\n    ".join('"' + l + '\\n"' for l in lines)
 
@@ -166,6 +266,22 @@ def main(out_path: str):
             out.append(f"#define PCONV_ENTRY_LOOP_NF{nf}_S{s} \\\n    {as_c_string(entry_loop(nf, s))}")
             out.append(f"#define PCONV_ENTRY_LOOP_ROWS8_NF{nf}_S{s} \\\n    {as_c_string(entry_loop(nf, s, True))}")
             out.append(f"#define PCONV_ENTRY_LOOP_CLOBBERS_NF{nf}_S{s} {clobbers(nf, s)}")
+            out.append("")
+    out.append(f"#define PCONV_QUAD_ROWS {RQ}")
+    out.append(f"#define PCONV_QUAD_CH_BYTES {QUAD_CH_BYTES}")
+    for s in range(2):
+        b = quad_acc_base(s)
+        n = 6 * RQ
+        out.append(f"#define PCONV_QUAD_ACC_BASE_S{s} {b}")
+        out.append(f"#define PCONV_QUAD_ACC_CLOBBERS_S{s} " + ", ".join(f'"v{b + i}"' for i in range(n)))
+        out.append(f"#define PCONV_QUAD_ACC_ZERO_S{s} " + " ".join(f'"v_mov_b32 v{b + i}, 0\\n"' for i in range(n)))
+        out.append(f"#define PCONV_QUAD_ACC_READ_S{s} " + " ".join(f'"v_mov_b32 %{i}, v{b + i}\\n"' for i in range(n)))
+        out.append("")
+    for nf in (1, 2):
+        out.append(f"#define PCONV_QUAD_SCRATCH_FIRST_NF{nf} {QuadRegs(nf).first}")
+        for s in range(nf):
+            out.append(f"#define PCONV_QUAD_ENTRY_LOOP_NF{nf}_S{s} \\\n    {as_c_string(quad_entry_loop(nf, s))}")
+            out.append(f"#define PCONV_QUAD_ENTRY_LOOP_CLOBBERS_NF{nf}_S{s} {quad_clobbers(nf, s)}")
             out.append("")
     with open(out_path, "w") as fh:
         fh.write("\n".join(out) + "\n")

@@ -653,6 +653,259 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(43))) void til
 }
 
 // ---------------------------------------------------------------------------------------------------------------
+// quad kernel (unit stride, W a multiple of four)
+//
+// Lane layout.  A lane holds FOUR neighbouring input columns (a "quad") of the six input rows that four output rows
+// read, and a wave holds BL = 64 / (W/4) row blocks of W/4 quads each: whole image rows, so there are no halo lanes
+// and the zero padding left and right of the image needs no data at all.  A tap (ky,kx) of a kept kernel on the
+// lane's column c (0..3) belongs to output column c + pad - kx of the quad, which is accumulator column
+// j = c + 2 - kx of six (see gen_pattern_leaves.py); columns 0 and 5 are handed to the neighbouring lanes once, after
+// the last channel.  64 multiply-adds per kept kernel and jump.
+//
+// LDS layout.  tile[cc][6 rows][64 lanes][4 columns]: every patch row is one 128-bit read with an immediate offset,
+// neighbouring lanes read neighbouring 16 bytes.  Staging writes the same shape: wave w copies channel w of the
+// 16-channel chunk, each lane its own six rows with 128-bit loads (64-bit for fp16 storage) -- a third of the load
+// instructions per element of the one-column kernel, whose batch-1 chunks are bound by load issue.
+//
+// Work split.  Workgroup = one slot (the wave shape above) x 16 waves x NF filters; chunks of 16 channels in their
+// own order, one chunk buffer, two barriers per chunk.  No channel split yet: meant for layers with many tiles.
+// ---------------------------------------------------------------------------------------------------------------
+
+struct QuadParams {
+    const void* x;
+    void* y;
+    const DevEntry* ent;
+    const uint32_t* eptr;
+    const uint32_t* forder;
+    const float* bias;
+    int N, C, F, H, W, Ho, Wo, pad, relu;
+    int nbk;                 // eptr entries per filter position: buckets of 16 channels = chunks
+    int QW, BL, NRB;         // quads per image row, row blocks per wave, row blocks per image
+    int NBLK;                // N * NRB
+    int NG;                  // filter groups per slot
+    int nblocks;             // NG * slots (the grid is padded to a multiple of 8)
+    unsigned long long x_bytes;
+    unsigned img_bytes, plane_bytes;
+    FastDiv div_NG, div_QW, div_NRB;
+};
+
+// four neighbouring elements as they are stored
+template <typename T>
+struct RawQuad;
+template <>
+struct RawQuad<float> {
+    unsigned e0, e1, e2, e3;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        typedef unsigned v4u __attribute__((ext_vector_type(4)));
+        const v4u v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+        e0 = v[0];
+        e1 = v[1];
+        e2 = v[2];
+        e3 = v[3];
+    }
+    __device__ __forceinline__ float4 widen() const {
+        return make_float4(__builtin_bit_cast(float, e0), __builtin_bit_cast(float, e1), __builtin_bit_cast(float, e2),
+                           __builtin_bit_cast(float, e3));
+    }
+};
+template <>
+struct RawQuad<__half> {
+    unsigned lo, hi;   // elements 0, 1 and 2, 3
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        typedef unsigned v2u __attribute__((ext_vector_type(2)));
+        const v2u v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
+        lo = v[0];
+        hi = v[1];
+    }
+    __device__ __forceinline__ float4 widen() const {
+        return make_float4(raw_to_f32<__half>(lo & 0xFFFFu), raw_to_f32<__half>(lo >> 16),
+                           raw_to_f32<__half>(hi & 0xFFFFu), raw_to_f32<__half>(hi >> 16));
+    }
+};
+
+template <int SLOT>
+__device__ __forceinline__ void quad_zero_acc() {
+    if constexpr (SLOT == 0) asm volatile(PCONV_QUAD_ACC_ZERO_S0 : : : PCONV_QUAD_ACC_CLOBBERS_S0);
+    else asm volatile(PCONV_QUAD_ACC_ZERO_S1 : : : PCONV_QUAD_ACC_CLOBBERS_S1);
+}
+
+template <int SLOT>
+__device__ __forceinline__ void quad_read_acc(float (&a)[6][PCONV_QUAD_ROWS]) {
+#define PCONV_QROW(j) "=v"(a[j][0]), "=v"(a[j][1]), "=v"(a[j][2]), "=v"(a[j][3])
+    if constexpr (SLOT == 0)
+        asm volatile(PCONV_QUAD_ACC_READ_S0
+                     : PCONV_QROW(0), PCONV_QROW(1), PCONV_QROW(2), PCONV_QROW(3), PCONV_QROW(4), PCONV_QROW(5));
+    else
+        asm volatile(PCONV_QUAD_ACC_READ_S1
+                     : PCONV_QROW(0), PCONV_QROW(1), PCONV_QROW(2), PCONV_QROW(3), PCONV_QROW(4), PCONV_QROW(5));
+#undef PCONV_QROW
+}
+
+template <int NF, int SLOT>
+__device__ __forceinline__ void quad_run_entries(unsigned lane_addr, unsigned entry_addr, unsigned count) {
+    const unsigned cnt = __builtin_amdgcn_readfirstlane(count);
+#define PCONV_QLOOP(NFv, Sv)                                                                    \
+    asm volatile(PCONV_QUAD_ENTRY_LOOP_NF##NFv##_S##Sv                                          \
+                 :                                                                              \
+                 : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr), [cnt] "s"(cnt)             \
+                 : "memory", PCONV_QUAD_ENTRY_LOOP_CLOBBERS_NF##NFv##_S##Sv)
+    if constexpr (NF == 1) { PCONV_QLOOP(1, 0); }
+    else if constexpr (SLOT == 0) { PCONV_QLOOP(2, 0); }
+    else { PCONV_QLOOP(2, 1); }
+#undef PCONV_QLOOP
+}
+
+template <int NF, typename T>
+__device__ __forceinline__ void quad_body(const QuadParams& p) {
+    constexpr int R = PCONV_QUAD_ROWS;
+    constexpr int CC = 16, FW = 16;
+    constexpr unsigned kChB = PCONV_QUAD_CH_BYTES;
+    constexpr unsigned kRowB = 64 * 16;
+    static_assert(kChB == (R + 2) * kRowB, "generated code and kernel disagree on the tile shape");
+    constexpr unsigned kEntRegion = (CC + 2) * 32;
+    constexpr unsigned kEntBase = CC * kChB;
+    extern __shared__ __align__(16) unsigned char lds[];     // [CC][R+2][64] float4, then [FW][NF][CC+2] entries
+    const unsigned lds0 = (unsigned)(unsigned long long)lds;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    const int per_xcd = gridDim.x >> 3;   // see tiled_body: the filter groups of one slot share one XCD's L2
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= p.nblocks) return;
+    const int slot = (int)fastdiv((unsigned)logical, p.div_NG);
+    const int grp = logical - slot * p.NG;
+
+    // lane -> (row block, quad)
+    const int b = (int)fastdiv((unsigned)lane, p.div_QW);
+    const int q = lane - b * p.QW;
+    const int g0 = slot * p.BL;                         // first row block of the slot (uniform)
+    const bool active = b < p.BL && g0 + b < p.NBLK;
+    const int g = active ? g0 + b : g0;
+    const int n0 = (int)fastdiv((unsigned)g0, p.div_NRB);
+    const int n = (int)fastdiv((unsigned)g, p.div_NRB);
+    const int oy0 = (g - n * p.NRB) * R;
+
+    unsigned voff[R + 2];
+#pragma unroll
+    for (int i = 0; i < R + 2; ++i) {
+        const int iy = oy0 - p.pad + i;
+        const bool ok = active && iy >= 0 && iy < p.H;
+        voff[i] = ok ? (unsigned)(n - n0) * p.img_bytes + (unsigned)(iy * p.W + 4 * q) * (unsigned)sizeof(T)
+                     : kInvalidOffset;
+    }
+    const unsigned long long base_off = (unsigned long long)n0 * p.img_bytes;
+    const unsigned long long left = p.x_bytes - base_off;
+    const __amdgpu_buffer_rsrc_t rsrc =
+        make_rsrc(static_cast<const char*>(p.x) + base_off, (uint32_t)(left < 0x7FFFFFFFull ? left : 0x7FFFFFFFull));
+
+    const unsigned lane_addr = lds0 + lane * 16;
+    if constexpr (NF > 0) quad_zero_acc<0>();
+    if constexpr (NF > 1) quad_zero_acc<1>();
+
+    const int pos_base = grp * (FW * NF) + wave;
+    const int nchunks = p.nbk;
+
+    RawQuad<T> pre[R + 2];       // the wave's channel of the next chunk, in flight
+    uint2 epre[NF];
+    unsigned ecnt[NF];
+    bool staged = false;
+    auto issue_loads = [&](int k) {
+        const int c = k * CC + wave;
+        staged = c < p.C;
+        if (staged) {
+            const unsigned soff = (unsigned)c * p.plane_bytes;
+#pragma unroll
+            for (int i = 0; i < R + 2; ++i) pre[i].load(rsrc, voff[i], soff);
+        }
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            const int pos = pos_base + a * FW;
+            unsigned cnt = 0;
+            if (pos < p.F) {
+                const unsigned e0 = scalar_load_u32(p.eptr + pos * p.nbk + k);
+                cnt = scalar_load_u32(p.eptr + pos * p.nbk + k + 1) - e0;
+                const uint2* src = reinterpret_cast<const uint2*>(p.ent + e0);
+                if ((unsigned)(lane >> 2) < cnt) epre[a] = src[lane];
+            }
+            ecnt[a] = cnt;
+        }
+    };
+    auto write_lds = [&]() {
+        float4* dst = reinterpret_cast<float4*>(lds + wave * kChB + lane * 16);
+        if (staged) {
+#pragma unroll
+            for (int i = 0; i < R + 2; ++i) dst[i * (kRowB / 16)] = pre[i].widen();
+        } else {
+            // a chunk's tail beyond the last channel: no entry points there, nothing to write
+        }
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            uint2* e = reinterpret_cast<uint2*>(lds + kEntBase + (wave * NF + a) * kEntRegion);
+            if ((unsigned)(lane >> 2) < ecnt[a]) e[lane] = epre[a];
+        }
+    };
+
+    unsigned cnt_now[NF];
+    issue_loads(0);
+    write_lds();
+    __syncthreads();
+    for (int k = 0; k < nchunks; ++k) {
+        const bool more = k + 1 < nchunks;
+#pragma unroll
+        for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
+        if (more) issue_loads(k + 1);
+        const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
+        if constexpr (NF > 0) { if (cnt_now[0]) quad_run_entries<NF, 0>(lane_addr, ent_addr, cnt_now[0]); }
+        if constexpr (NF > 1) { if (cnt_now[1]) quad_run_entries<NF, 1>(lane_addr, ent_addr + kEntRegion, cnt_now[1]); }
+        __syncthreads();
+        if (more) {
+            write_lds();
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: accumulator columns 0 and 5 go to the neighbouring quads, bias, ReLU, store
+    T* __restrict__ y = static_cast<T*>(p.y);
+    const bool has_left = q > 0, has_right = q + 1 < p.QW;
+    const int o0 = 4 * q + p.pad - 1;                  // output column of accumulator column 1
+    auto finish = [&](const float (&P)[6][R], int pos) {
+        if (pos >= p.F) return;   // uniform per wave
+        const unsigned f = p.forder[pos];
+        const float bias = p.bias ? p.bias[f] : 0.f;
+        const size_t ybase = (((size_t)n * p.F + f) * p.Ho) * (size_t)p.Wo;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float from_left = __shfl_up(P[5][r], 1, 64);     // the left quad's column 5 is this quad's column 1
+            const float from_right = __shfl_down(P[0][r], 1, 64);  // the right quad's column 0 is this quad's column 4
+            float v[4] = {P[1][r] + (has_left ? from_left : 0.f), P[2][r], P[3][r],
+                          P[4][r] + (has_right ? from_right : 0.f)};
+            const int oy = oy0 + r;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                float o = v[m] + bias;
+                if (p.relu) o = fmaxf(o, 0.f);
+                const int ox = o0 + m;
+                if (active && oy < p.Ho && ox >= 0 && ox < p.Wo) y[ybase + (size_t)oy * p.Wo + ox] = from_f32<T>(o);
+            }
+        }
+    };
+    float P[6][R];
+    if constexpr (NF > 0) { quad_read_acc<0>(P); finish(P, pos_base); }
+    if constexpr (NF > 1) { quad_read_acc<1>(P); finish(P, pos_base + FW); }
+}
+
+template <typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(36))) void quad_kernel_nf1(const QuadParams p) {
+    static_assert(PCONV_QUAD_SCRATCH_FIRST_NF1 >= 2 * 36, "the entry loop's registers overlap the compiler's");
+    quad_body<1, T>(p);
+}
+template <typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(24))) void quad_kernel_nf2(const QuadParams p) {
+    static_assert(PCONV_QUAD_SCRATCH_FIRST_NF2 >= 2 * 24, "the entry loop's registers overlap the compiler's");
+    quad_body<2, T>(p);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
 // generic kernel: any stride / pad; one thread per output, one filter per workgroup row
 // ---------------------------------------------------------------------------------------------------------------
 
@@ -858,6 +1111,42 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
     return PCONV_EUNSUPPORTED;
 }
 
+template <typename T>
+static int launch_quad(QuadParams& p, int NF, hipStream_t stream) {
+    constexpr int R = PCONV_QUAD_ROWS;
+    if (p.W % 4 != 0 || p.W / 4 > 64) return PCONV_EUNSUPPORTED;
+    p.QW = p.W / 4;
+    p.BL = 64 / p.QW;
+    p.NRB = (p.Ho + R - 1) / R;
+    const long long nblk = (long long)p.N * p.NRB;
+    if (nblk > 0x7FFFFFFF) return PCONV_ESHAPE;
+    p.NBLK = (int)nblk;
+    const long long slots = (nblk + p.BL - 1) / p.BL;
+    p.NG = (p.F + 16 * NF - 1) / (16 * NF);
+    const long long nb = slots * p.NG;
+    if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
+    p.nblocks = (int)nb;
+    // 32-bit byte offsets inside the buffer descriptor: the images one slot can span
+    const unsigned long long span = (unsigned long long)((p.BL + p.NRB - 1) / p.NRB + 1);
+    if ((unsigned long long)p.img_bytes * span >= 0x7FFFFFFFull) return PCONV_EUNSUPPORTED;
+    p.div_NG = make_fastdiv((unsigned)p.NG);
+    p.div_QW = make_fastdiv((unsigned)p.QW);
+    p.div_NRB = make_fastdiv((unsigned)p.NRB);
+    const int grid = (p.nblocks + 7) / 8 * 8;
+    const size_t lds = (size_t)16 * PCONV_QUAD_CH_BYTES + (size_t)16 * NF * 18 * 32;
+    if (NF == 1) {
+        PCONV_HIP(allow_big_lds((const void*)quad_kernel_nf1<T>, lds));
+        hipLaunchKernelGGL(quad_kernel_nf1<T>, dim3(grid), dim3(1024), lds, stream, p);
+    } else if (NF == 2) {
+        PCONV_HIP(allow_big_lds((const void*)quad_kernel_nf2<T>, lds));
+        hipLaunchKernelGGL(quad_kernel_nf2<T>, dim3(grid), dim3(1024), lds, stream, p);
+    } else {
+        return PCONV_EUNSUPPORTED;
+    }
+    PCONV_HIP(hipGetLastError());
+    return PCONV_OK;
+}
+
 static bool tiled_applicable(int N, int C, int H, int W, int stride, size_t esize) {
     if (stride != 1) return false;
     // 32-bit byte offsets inside the buffer descriptor: one image, times the few images one slot can span
@@ -1037,6 +1326,32 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.plane_bytes = (unsigned)((size_t)tH * tW * esize);
         return lay->dtype == PCONV_F16 ? launch_tiled<__half>(p, lay, NF, waves, CPW, KS, buffers, st)
                                       : launch_tiled<float>(p, lay, NF, waves, CPW, KS, buffers, st);
+    }
+    if (kernel == PCONV_KERNEL_QUAD) {
+        if (stride != 1) return PCONV_EUNSUPPORTED;
+        if ((unsigned long long)wp->C * H * W * esize >= 0x7FFFFFFFull) return PCONV_EUNSUPPORTED;
+        QuadParams p{};
+        p.x = x;
+        p.y = y;
+        p.ent = wp->d_ent;
+        p.eptr = wp->d_eptr;
+        p.forder = wp->d_forder;
+        p.bias = bias;
+        p.N = N;
+        p.C = wp->C;
+        p.F = wp->F;
+        p.H = H;
+        p.W = W;
+        p.Ho = Ho;
+        p.Wo = Wo;
+        p.pad = pad;
+        p.relu = relu;
+        p.nbk = wp->n_buckets;
+        p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
+        p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
+        p.plane_bytes = (unsigned)((size_t)H * W * esize);
+        const int nf = NF == 0 ? 2 : NF;
+        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, nf, st) : launch_quad<float>(p, nf, st);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);

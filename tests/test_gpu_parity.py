@@ -182,6 +182,37 @@ def test_stride2_both_staging_paths(pad, dtype):
     layer.free()
 
 
+QUAD_SHAPES = [  # N, C, F, H, W, pad
+    (1, 16, 16, 32, 32, 1), (3, 40, 20, 13, 68, 1), (2, 20, 33, 9, 12, 0), (1, 5, 3, 4, 4, 1), (5, 12, 6, 7, 8, 1),
+    (2, 33, 17, 6, 256, 1), (1, 64, 40, 56, 56, 1), (9, 24, 16, 5, 4, 1), (2, 17, 70, 11, 28, 0),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("case", QUAD_SHAPES, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}p{c[5]}" for c in QUAD_SHAPES])
+def test_quad_kernel(case, dtype):
+    """The kernel with four columns per lane (W a multiple of four, unit stride): one and two filters per wave,
+    ragged row blocks, waves that span images, channel counts that are not a multiple of the chunk, ReLU."""
+    N, C, F, H, W, pad = case
+    spec = L.LayerSpec(cfg=15, idx=QUAD_SHAPES.index(case), name="quad", N=N, C=C, F=F, H=H, W=W, stride=1, pad=pad,
+                       dtype=dtype, K=8, keep=0.4)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    Q = pc.KERNEL_QUAD
+    check(layer, x, [dict(kernel=Q, filters_per_wave=1), dict(kernel=Q, filters_per_wave=2)])
+    check(layer, x, [dict(kernel=Q)], relu=True)
+    layer.free()
+
+
+def test_quad_kernel_refuses_what_it_cannot_do():
+    spec = L.LayerSpec(cfg=15, idx=99, name="quadno", N=1, C=8, F=8, H=8, W=10, K=8, keep=0.5)
+    layer = GpuLayer(spec)
+    with pytest.raises(pc.PconvError) as ei:
+        layer.run(L.gen_activations(spec), kernel=pc.KERNEL_QUAD)
+    assert ei.value.code == pc.EUNSUPPORTED
+    layer.free()
+
+
 def test_hip_graph_replays_match_eager_launches():
     """Two layers (the first splits its channels over workgroups, the second runs at stride 2 through the parity
     form) and a max-pool, captured into one HIP graph: every replay, with eager work and synchronisations in between
@@ -235,7 +266,8 @@ def test_config1_full_size():
     layer = GpuLayer(spec)
     assert layer.packed.n_kept == 18350
     x = L.gen_activations(spec)
-    ref = check(layer, x, [dict(), dict(kernel=G)] + TILED_TUNINGS[:7] + DB_TUNINGS)
+    ref = check(layer, x, [dict(), dict(kernel=G)] + TILED_TUNINGS[:7] + DB_TUNINGS +
+                [dict(kernel=pc.KERNEL_QUAD, filters_per_wave=1), dict(kernel=pc.KERNEL_QUAD, filters_per_wave=2)])
     # invariant on the GPU side as well: a removed kernel contributes nothing
     f, c = np.argwhere(layer.mask == 0)[0]
     w2 = layer.w.copy()
