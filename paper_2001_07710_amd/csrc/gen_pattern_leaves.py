@@ -174,7 +174,7 @@ def quad_fetch(rg: QuadRegs) -> list:
     of the next entry in s65."""
     lines = [
         f"v_readfirstlane_b32 s65, v{rg.m}",
-        "s_and_b32 s64, s65, 15",
+        "s_and_b32 s64, s65, %[ccmask]",
         f"s_mul_i32 s64, s64, {QUAD_CH_BYTES}",
         f"v_add_u32 v{rg.va}, s64, %[vlane]",
     ]

@@ -679,7 +679,9 @@ struct QuadParams {
     const uint32_t* forder;
     const float* bias;
     int N, C, F, H, W, Ho, Wo, pad, relu;
-    int nbk;                 // eptr entries per filter position: buckets of 16 channels = chunks
+    int nbk;                 // eptr entries per filter position: chunks of 16 channels
+    const uint32_t* perm;    // [groups][perm_stride] channel staged at each position, or null for channel order
+    int perm_stride;
     int QW, BL, NRB;         // quads per image row, row blocks per wave, row blocks per image
     int NBLK;                // N * NRB
     int NG;                  // filter groups per slot
@@ -741,13 +743,13 @@ __device__ __forceinline__ void quad_read_acc(float (&a)[6][PCONV_QUAD_ROWS]) {
 #undef PCONV_QROW
 }
 
-template <int NF, int SLOT>
+template <int NF, int SLOT, int CC>
 __device__ __forceinline__ void quad_run_entries(unsigned lane_addr, unsigned entry_addr, unsigned count) {
     const unsigned cnt = __builtin_amdgcn_readfirstlane(count);
 #define PCONV_QLOOP(NFv, Sv)                                                                    \
     asm volatile(PCONV_QUAD_ENTRY_LOOP_NF##NFv##_S##Sv                                          \
                  :                                                                              \
-                 : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr), [cnt] "s"(cnt)             \
+                 : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr), [cnt] "s"(cnt), [ccmask] "n"(CC - 1) \
                  : "memory", PCONV_QUAD_ENTRY_LOOP_CLOBBERS_NF##NFv##_S##Sv)
     if constexpr (NF == 1) { PCONV_QLOOP(1, 0); }
     else if constexpr (SLOT == 0) { PCONV_QLOOP(2, 0); }
@@ -755,10 +757,11 @@ __device__ __forceinline__ void quad_run_entries(unsigned lane_addr, unsigned en
 #undef PCONV_QLOOP
 }
 
-template <int NF, typename T>
+// FW waves, each with NF filters and one channel of every chunk of CC = FW channels.
+template <int NF, int FW, typename T>
 __device__ __forceinline__ void quad_body(const QuadParams& p) {
     constexpr int R = PCONV_QUAD_ROWS;
-    constexpr int CC = 16, FW = 16;
+    constexpr int CC = FW;
     constexpr unsigned kChB = PCONV_QUAD_CH_BYTES;
     constexpr unsigned kRowB = 64 * 16;
     static_assert(kChB == (R + 2) * kRowB, "generated code and kernel disagree on the tile shape");
@@ -810,10 +813,12 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     unsigned ecnt[NF];
     bool staged = false;
     auto issue_loads = [&](int k) {
-        const int c = k * CC + wave;
-        staged = c < p.C;
+        // the channel at this wave's position of the workgroup's staging order (kNoChannel: nothing to stage there)
+        const unsigned c = p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + k * CC + wave)
+                                  : (unsigned)(k * CC + wave);
+        staged = c < (unsigned)p.C;
         if (staged) {
-            const unsigned soff = (unsigned)c * p.plane_bytes;
+            const unsigned soff = c * p.plane_bytes;
 #pragma unroll
             for (int i = 0; i < R + 2; ++i) pre[i].load(rsrc, voff[i], soff);
         }
@@ -855,8 +860,8 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
         for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
         if (more) issue_loads(k + 1);
         const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
-        if constexpr (NF > 0) { if (cnt_now[0]) quad_run_entries<NF, 0>(lane_addr, ent_addr, cnt_now[0]); }
-        if constexpr (NF > 1) { if (cnt_now[1]) quad_run_entries<NF, 1>(lane_addr, ent_addr + kEntRegion, cnt_now[1]); }
+        if constexpr (NF > 0) { if (cnt_now[0]) quad_run_entries<NF, 0, CC>(lane_addr, ent_addr, cnt_now[0]); }
+        if constexpr (NF > 1) { if (cnt_now[1]) quad_run_entries<NF, 1, CC>(lane_addr, ent_addr + kEntRegion, cnt_now[1]); }
         __syncthreads();
         if (more) {
             write_lds();
@@ -894,15 +899,15 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     if constexpr (NF > 1) { quad_read_acc<1>(P); finish(P, pos_base + FW); }
 }
 
-template <typename T>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(36))) void quad_kernel_nf1(const QuadParams p) {
+template <int FW, typename T>
+__global__ __launch_bounds__(FW * 64) __attribute__((amdgpu_num_vgpr(36))) void quad_kernel_nf1(const QuadParams p) {
     static_assert(PCONV_QUAD_SCRATCH_FIRST_NF1 >= 2 * 36, "the entry loop's registers overlap the compiler's");
-    quad_body<1, T>(p);
+    quad_body<1, FW, T>(p);
 }
-template <typename T>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(24))) void quad_kernel_nf2(const QuadParams p) {
+template <int FW, typename T>
+__global__ __launch_bounds__(FW * 64) __attribute__((amdgpu_num_vgpr(24))) void quad_kernel_nf2(const QuadParams p) {
     static_assert(PCONV_QUAD_SCRATCH_FIRST_NF2 >= 2 * 24, "the entry loop's registers overlap the compiler's");
-    quad_body<2, T>(p);
+    quad_body<2, FW, T>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -1112,7 +1117,7 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
 }
 
 template <typename T>
-static int launch_quad(QuadParams& p, int NF, hipStream_t stream) {
+static int launch_quad(QuadParams& p, int NF, int FW, hipStream_t stream) {
     constexpr int R = PCONV_QUAD_ROWS;
     if (p.W % 4 != 0 || p.W / 4 > 64) return PCONV_EUNSUPPORTED;
     p.QW = p.W / 4;
@@ -1122,7 +1127,10 @@ static int launch_quad(QuadParams& p, int NF, hipStream_t stream) {
     if (nblk > 0x7FFFFFFF) return PCONV_ESHAPE;
     p.NBLK = (int)nblk;
     const long long slots = (nblk + p.BL - 1) / p.BL;
-    p.NG = (p.F + 16 * NF - 1) / (16 * NF);
+    // Only workgroups of 16 waves are built: eight waves with eight-channel chunks (two workgroups per CU) measured
+    // within 3 % of them on the VGG-16 shapes at batch 64, slower on most.
+    if (FW != 16) return PCONV_EUNSUPPORTED;
+    p.NG = (p.F + FW * NF - 1) / (FW * NF);
     const long long nb = slots * p.NG;
     if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
     p.nblocks = (int)nb;
@@ -1133,18 +1141,29 @@ static int launch_quad(QuadParams& p, int NF, hipStream_t stream) {
     p.div_QW = make_fastdiv((unsigned)p.QW);
     p.div_NRB = make_fastdiv((unsigned)p.NRB);
     const int grid = (p.nblocks + 7) / 8 * 8;
-    const size_t lds = (size_t)16 * PCONV_QUAD_CH_BYTES + (size_t)16 * NF * 18 * 32;
-    if (NF == 1) {
-        PCONV_HIP(allow_big_lds((const void*)quad_kernel_nf1<T>, lds));
-        hipLaunchKernelGGL(quad_kernel_nf1<T>, dim3(grid), dim3(1024), lds, stream, p);
-    } else if (NF == 2) {
-        PCONV_HIP(allow_big_lds((const void*)quad_kernel_nf2<T>, lds));
-        hipLaunchKernelGGL(quad_kernel_nf2<T>, dim3(grid), dim3(1024), lds, stream, p);
-    } else {
-        return PCONV_EUNSUPPORTED;
-    }
+    const size_t lds = (size_t)FW * PCONV_QUAD_CH_BYTES + (size_t)FW * NF * (FW + 2) * 32;
+#define PCONV_QCASE(NFv, FWv)                                                                           \
+    if (NF == NFv && FW == FWv) {                                                                       \
+        PCONV_HIP(allow_big_lds((const void*)quad_kernel_nf##NFv<FWv, T>, lds));                        \
+        hipLaunchKernelGGL((quad_kernel_nf##NFv<FWv, T>), dim3(grid), dim3(FWv * 64), lds, stream, p);  \
+    } else
+    PCONV_QCASE(1, 16) PCONV_QCASE(2, 16) { return PCONV_EUNSUPPORTED; }
+#undef PCONV_QCASE
     PCONV_HIP(hipGetLastError());
     return PCONV_OK;
+}
+
+// Whether the kernel with four columns per lane can run the layer, and with how many workgroups at two filters per
+// wave (same conditions as launch_quad checks).
+static bool quad_applicable(int N, int C, int F, int H, int W, int Ho, int stride, size_t esize, long long* workgroups) {
+    if (stride != 1 || W % 4 != 0 || W / 4 > 64) return false;
+    const unsigned long long img = (unsigned long long)C * H * W * esize;
+    const int BL = 64 / (W / 4), NRB = (Ho + PCONV_QUAD_ROWS - 1) / PCONV_QUAD_ROWS;
+    if (img * (unsigned long long)((BL + NRB - 1) / NRB + 1) >= 0x7FFFFFFFull) return false;
+    const long long nblk = (long long)N * NRB;
+    if (nblk > 0x7FFFFFFF) return false;
+    *workgroups = (nblk + BL - 1) / BL * ((F + 31) / 32);
+    return *workgroups <= 0x7FFFFFF0;
 }
 
 static bool tiled_applicable(int N, int C, int H, int W, int stride, size_t esize) {
@@ -1208,6 +1227,16 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     const int tH = stride == 1 ? H : (H + 1) / 2, tW = stride == 1 ? W : (W + 1) / 2;
     const int tC = stride == 1 ? wp->C : 4 * wp->C;
     const bool can_tile = tC < 65536 && tiled_applicable(N, tC, tH, tW, 1, esize);
+    const bool automatic = waves == 0 && NF == 0 && CPW == 0;
+    if (kernel == PCONV_KERNEL_AUTO && automatic && KS == 0 && buffers == 0) {
+        // The kernel with four columns per lane has no channel split: it is the faster one (measured on the VGG-16
+        // and ResNet-50 layer shapes at batch 32 and 64) once its own workgroups nearly fill the 256 CUs.
+        long long wgs = 0;
+        if (quad_applicable(N, wp->C, wp->F, H, W, Ho, stride, esize, &wgs) && wgs >= 200) {
+            kernel = PCONV_KERNEL_QUAD;
+            NF = 2;
+        }
+    }
     if (kernel == PCONV_KERNEL_AUTO) kernel = can_tile ? PCONV_KERNEL_TILED : PCONV_KERNEL_GENERIC;
     if (kernel == PCONV_KERNEL_TILED && !can_tile) return PCONV_EUNSUPPORTED;
     const pconv_packed* lay = wp;
@@ -1215,7 +1244,6 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     // Stride 2 with even H and W: the kernels with paired staging read the parity planes straight from x (16 waves,
     // two channels per wave, channels in their own order).  Otherwise the input is split into planes by a pass of
     // its own first.
-    const bool automatic = waves == 0 && NF == 0 && CPW == 0;
     const int order = tuning ? tuning->channel_order : PCONV_ORDER_AUTO;
     const bool pair = kernel == PCONV_KERNEL_TILED && stride == 2 && H % 2 == 0 && W % 2 == 0 &&
                       order != PCONV_ORDER_BALANCED && buffers <= 1 &&
@@ -1347,11 +1375,26 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.pad = pad;
         p.relu = relu;
         p.nbk = wp->n_buckets;
+        p.perm = nullptr;
+        p.perm_stride = 0;
+        const int nf = NF == 0 ? 2 : NF;
+        const int fw = waves == 0 ? 16 : waves;
+        if (order != PCONV_ORDER_PLAIN) {
+            for (const BalancedLayout& b : wp->balanced)
+                if (b.fw == fw && b.nf == nf && b.cc == fw && b.d_ent) {
+                    p.ent = b.d_ent;
+                    p.eptr = b.d_eptr;
+                    p.perm = b.d_perm;
+                    p.perm_stride = b.n_chunks * b.cc;
+                    p.nbk = b.n_chunks;
+                }
+            if (order == PCONV_ORDER_BALANCED && !p.perm) return PCONV_EUNSUPPORTED;
+        }
+        if (fw != 16 && !p.perm) return PCONV_EUNSUPPORTED;   // the canonical entries come in chunks of 16 channels
         p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
         p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
         p.plane_bytes = (unsigned)((size_t)H * W * esize);
-        const int nf = NF == 0 ? 2 : NF;
-        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, nf, st) : launch_quad<float>(p, nf, st);
+        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, nf, fw, st) : launch_quad<float>(p, nf, fw, st);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);

@@ -355,10 +355,11 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
         }
         p->eptr[(size_t)F * p->n_buckets] = (uint32_t)d;
 
-        // balanced layouts for the tilings of the automatic choice (waves, filters per wave, channels per chunk)
-        static const int tilings[3][3] = {{16, 2, 32}, {16, 1, 32}, {8, 1, 32}};
-        p->balanced.resize(3);
-        for (int t = 0; t < 3; ++t)
+        // balanced layouts for the tilings of the automatic choice (waves, filters per wave, channels per chunk);
+        // the 16-channel ones are the quad kernel's
+        static const int tilings[5][3] = {{16, 2, 32}, {16, 1, 32}, {8, 1, 32}, {16, 2, 16}, {16, 1, 16}};
+        p->balanced.resize(5);
+        for (int t = 0; t < 5; ++t)
             build_balanced(p, tilings[t][0], tilings[t][1], tilings[t][2], &p->balanced[(size_t)t]);
     } catch (const std::bad_alloc&) {
         delete p;

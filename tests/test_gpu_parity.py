@@ -199,7 +199,8 @@ def test_quad_kernel(case, dtype):
     layer = GpuLayer(spec)
     x = L.gen_activations(spec)
     Q = pc.KERNEL_QUAD
-    check(layer, x, [dict(kernel=Q, filters_per_wave=1), dict(kernel=Q, filters_per_wave=2)])
+    check(layer, x, [dict(kernel=Q, filters_per_wave=nf, channel_order=o) for nf in (1, 2)
+                     for o in (pc.ORDER_PLAIN, pc.ORDER_BALANCED)])
     check(layer, x, [dict(kernel=Q)], relu=True)
     layer.free()
 
