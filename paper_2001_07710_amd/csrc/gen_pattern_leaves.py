@@ -276,6 +276,9 @@ def main(out_path: str):
         out.append(f"#define PCONV_QUAD_ACC_CLOBBERS_S{s} " + ", ".join(f'"v{b + i}"' for i in range(n)))
         out.append(f"#define PCONV_QUAD_ACC_ZERO_S{s} " + " ".join(f'"v_mov_b32 v{b + i}, 0\\n"' for i in range(n)))
         out.append(f"#define PCONV_QUAD_ACC_READ_S{s} " + " ".join(f'"v_mov_b32 %{i}, v{b + i}\\n"' for i in range(n)))
+        for r in range(RQ):      # output row r of the six accumulator columns
+            out.append(f"#define PCONV_QUAD_ACC_READ_ROW_S{s}_R{r} " +
+                       " ".join(f'"v_mov_b32 %{j}, v{b + 4 * j + r}\\n"' for j in range(6)))
         out.append("")
     for nf in (1, 2):
         out.append(f"#define PCONV_QUAD_SCRATCH_FIRST_NF{nf} {QuadRegs(nf).first}")

@@ -14,6 +14,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 #include "pconv_internal.h"
 
@@ -685,10 +686,14 @@ struct QuadParams {
     int QW, BL, NRB;         // quads per image row, row blocks per wave, row blocks per image
     int NBLK;                // N * NRB
     int NG;                  // filter groups per slot
-    int nblocks;             // NG * slots (the grid is padded to a multiple of 8)
+    int KS;                  // workgroups per output tile (each takes a range of the chunks)
+    int nblocks;             // NG * slots * KS (the grid is padded to a multiple of 8)
+    float* ws;               // KS > 1: partial sums [KS][N][F][Ho][Wo]
+    unsigned* counters;      // KS > 1: one arrival counter per tile, zero between launches
     unsigned long long x_bytes;
     unsigned img_bytes, plane_bytes;
-    FastDiv div_NG, div_QW, div_NRB;
+    unsigned ent_bytes;      // size of ent[] (below 2^31: the kernel reads it through a buffer descriptor)
+    FastDiv div_NG, div_KS, div_QW, div_NRB;
 };
 
 // four neighbouring elements as they are stored
@@ -731,16 +736,16 @@ __device__ __forceinline__ void quad_zero_acc() {
     else asm volatile(PCONV_QUAD_ACC_ZERO_S1 : : : PCONV_QUAD_ACC_CLOBBERS_S1);
 }
 
-template <int SLOT>
-__device__ __forceinline__ void quad_read_acc(float (&a)[6][PCONV_QUAD_ROWS]) {
-#define PCONV_QROW(j) "=v"(a[j][0]), "=v"(a[j][1]), "=v"(a[j][2]), "=v"(a[j][3])
-    if constexpr (SLOT == 0)
-        asm volatile(PCONV_QUAD_ACC_READ_S0
-                     : PCONV_QROW(0), PCONV_QROW(1), PCONV_QROW(2), PCONV_QROW(3), PCONV_QROW(4), PCONV_QROW(5));
-    else
-        asm volatile(PCONV_QUAD_ACC_READ_S1
-                     : PCONV_QROW(0), PCONV_QROW(1), PCONV_QROW(2), PCONV_QROW(3), PCONV_QROW(4), PCONV_QROW(5));
-#undef PCONV_QROW
+// Output row ROW of the six accumulator columns of filter slot SLOT.
+template <int SLOT, int ROW>
+__device__ __forceinline__ void quad_read_acc_row(float (&a)[6]) {
+#define PCONV_QREAD(Sv, Rv)                                                                            \
+    if constexpr (SLOT == Sv && ROW == Rv)                                                             \
+        asm volatile(PCONV_QUAD_ACC_READ_ROW_S##Sv##_R##Rv                                             \
+                     : "=v"(a[0]), "=v"(a[1]), "=v"(a[2]), "=v"(a[3]), "=v"(a[4]), "=v"(a[5]));
+    PCONV_QREAD(0, 0) PCONV_QREAD(0, 1) PCONV_QREAD(0, 2) PCONV_QREAD(0, 3)
+    PCONV_QREAD(1, 0) PCONV_QREAD(1, 1) PCONV_QREAD(1, 2) PCONV_QREAD(1, 3)
+#undef PCONV_QREAD
 }
 
 template <int NF, int SLOT, int CC>
@@ -775,25 +780,34 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     const int per_xcd = gridDim.x >> 3;   // see tiled_body: the filter groups of one slot share one XCD's L2
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= p.nblocks) return;
-    const int slot = (int)fastdiv((unsigned)logical, p.div_NG);
-    const int grp = logical - slot * p.NG;
+    const int tile = (int)fastdiv((unsigned)logical, p.div_KS);     // (slot, filter group)
+    const int split = logical - tile * p.KS;
+    const int slot = (int)fastdiv((unsigned)tile, p.div_NG);
+    const int grp = tile - slot * p.NG;
 
-    // lane -> (row block, quad)
-    const int b = (int)fastdiv((unsigned)lane, p.div_QW);
-    const int q = lane - b * p.QW;
+    // lane -> (row block, quad), image and first output row.  Worked out twice, before the channel loop and again
+    // behind it: a handful of instructions, instead of five registers held across the loop.
     const int g0 = slot * p.BL;                         // first row block of the slot (uniform)
-    const bool active = b < p.BL && g0 + b < p.NBLK;
-    const int g = active ? g0 + b : g0;
     const int n0 = (int)fastdiv((unsigned)g0, p.div_NRB);
-    const int n = (int)fastdiv((unsigned)g, p.div_NRB);
-    const int oy0 = (g - n * p.NRB) * R;
+    struct LanePlace { int q, n, oy0; bool active; };
+    auto place_of = [&](int ln) {
+        LanePlace r;
+        const int b = (int)fastdiv((unsigned)ln, p.div_QW);
+        r.q = ln - b * p.QW;
+        r.active = b < p.BL && g0 + b < p.NBLK;
+        const int g = r.active ? g0 + b : g0;
+        r.n = (int)fastdiv((unsigned)g, p.div_NRB);
+        r.oy0 = (g - r.n * p.NRB) * R;
+        return r;
+    };
+    const LanePlace early = place_of(lane);
 
     unsigned voff[R + 2];
 #pragma unroll
     for (int i = 0; i < R + 2; ++i) {
-        const int iy = oy0 - p.pad + i;
-        const bool ok = active && iy >= 0 && iy < p.H;
-        voff[i] = ok ? (unsigned)(n - n0) * p.img_bytes + (unsigned)(iy * p.W + 4 * q) * (unsigned)sizeof(T)
+        const int iy = early.oy0 - p.pad + i;
+        const bool ok = early.active && iy >= 0 && iy < p.H;
+        voff[i] = ok ? (unsigned)(early.n - n0) * p.img_bytes + (unsigned)(iy * p.W + 4 * early.q) * (unsigned)sizeof(T)
                      : kInvalidOffset;
     }
     const unsigned long long base_off = (unsigned long long)n0 * p.img_bytes;
@@ -807,61 +821,86 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
 
     const int pos_base = grp * (FW * NF) + wave;
     const int nchunks = p.nbk;
+    // this workgroup's range of chunks (all of them unless the channels are split)
+    const int k_begin = (int)fastdiv((unsigned)(split * nchunks), p.div_KS);   // split, nchunks < 65536
+    const int k_end = (int)fastdiv((unsigned)((split + 1) * nchunks), p.div_KS);
 
+    // The loads of a chunk and their use below are unconditional (lanes and waves with nothing to fetch use an offset
+    // outside the descriptor and get zeros): with loads or uses under branches the compiler has to assume that a
+    // load of the previous chunk may still be pending when the next ones are issued, and waits for all of them
+    // there, in front of the multiply-adds that are meant to cover their latency.
     RawQuad<T> pre[R + 2];       // the wave's channel of the next chunk, in flight
-    uint2 epre[NF];
+    uint2 epre[NF];              // ... and the wave's entries of the next chunk (lane l: dwords 2l, 2l+1)
     unsigned ecnt[NF];
-    bool staged = false;
-    auto issue_loads = [&](int k) {
-        // the channel at this wave's position of the workgroup's staging order (kNoChannel: nothing to stage there)
-        const unsigned c = p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + k * CC + wave)
-                                  : (unsigned)(k * CC + wave);
-        staged = c < (unsigned)p.C;
-        if (staged) {
-            const unsigned soff = c * p.plane_bytes;
-#pragma unroll
-            for (int i = 0; i < R + 2; ++i) pre[i].load(rsrc, voff[i], soff);
-        }
+    const __amdgpu_buffer_rsrc_t ent_rsrc = make_rsrc(p.ent, p.ent_bytes);
+    // Where a chunk's entries and channel are (scalar loads) is fetched one chunk ahead of the vector loads that need
+    // it: issued back to back, the two dependent rounds of scalar loads cost every wave about 1500 clocks per chunk
+    // in which the multiply-add units have nothing to do.
+    unsigned meta_e0[NF], meta_e1[NF], meta_c;
+    auto fetch_meta = [&](int k) {
+        const bool chunk = k < k_end;
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
             const int pos = pos_base + a * FW;
-            unsigned cnt = 0;
-            if (pos < p.F) {
-                const unsigned e0 = scalar_load_u32(p.eptr + pos * p.nbk + k);
-                cnt = scalar_load_u32(p.eptr + pos * p.nbk + k + 1) - e0;
-                const uint2* src = reinterpret_cast<const uint2*>(p.ent + e0);
-                if ((unsigned)(lane >> 2) < cnt) epre[a] = src[lane];
+            meta_e0[a] = meta_e1[a] = 0;
+            if (chunk && pos < p.F) {
+                meta_e0[a] = scalar_load_u32(p.eptr + pos * p.nbk + k);
+                meta_e1[a] = scalar_load_u32(p.eptr + pos * p.nbk + k + 1);
             }
-            ecnt[a] = cnt;
         }
+        // the channel at this wave's position of the workgroup's staging order (kNoChannel: nothing to stage there)
+        meta_c = !chunk ? kNoChannel
+                 : p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + k * CC + wave)
+                          : (unsigned)(k * CC + wave);
+    };
+    auto issue_loads = [&]() {           // the chunk of the last fetch_meta
+        unsigned e0[NF];
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            e0[a] = meta_e0[a];
+            ecnt[a] = meta_e1[a] - e0[a];
+        }
+        const unsigned c = meta_c;
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            const unsigned eoff = (unsigned)(lane >> 2) < ecnt[a] ? e0[a] * 32u + (unsigned)lane * 8u : kInvalidOffset;
+            typedef unsigned v2u __attribute__((ext_vector_type(2)));
+            const v2u e = __builtin_amdgcn_raw_buffer_load_b64(ent_rsrc, (int)eoff, 0, 0);
+            epre[a] = make_uint2(e[0], e[1]);
+        }
+        const bool staged = c < (unsigned)p.C;
+        const unsigned soff = staged ? c * p.plane_bytes : 0u;
+#pragma unroll
+        for (int i = 0; i < R + 2; ++i) pre[i].load(rsrc, staged ? voff[i] : kInvalidOffset, soff);
     };
     auto write_lds = [&]() {
         float4* dst = reinterpret_cast<float4*>(lds + wave * kChB + lane * 16);
-        if (staged) {
 #pragma unroll
-            for (int i = 0; i < R + 2; ++i) dst[i * (kRowB / 16)] = pre[i].widen();
-        } else {
-            // a chunk's tail beyond the last channel: no entry points there, nothing to write
-        }
+        for (int i = 0; i < R + 2; ++i) dst[i * (kRowB / 16)] = pre[i].widen();
+        // 64 lanes x 8 bytes: 16 entries, of which the chunk's first ecnt are real; the region holds CC + 2
+        static_assert(kEntRegion >= 64 * 8, "entry region smaller than one wave's write");
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
             uint2* e = reinterpret_cast<uint2*>(lds + kEntBase + (wave * NF + a) * kEntRegion);
-            if ((unsigned)(lane >> 2) < ecnt[a]) e[lane] = epre[a];
+            e[lane] = epre[a];
         }
     };
 
     unsigned cnt_now[NF];
-    issue_loads(0);
+    fetch_meta(k_begin);
+    issue_loads();
+    fetch_meta(k_begin + 1);
     write_lds();
     __syncthreads();
-    for (int k = 0; k < nchunks; ++k) {
-        const bool more = k + 1 < nchunks;
+    for (int k = k_begin; k < k_end; ++k) {
+        const bool more = k + 1 < k_end;
 #pragma unroll
         for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
-        if (more) issue_loads(k + 1);
+        if (more) issue_loads();         // chunk k + 1
         const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
         if constexpr (NF > 0) { if (cnt_now[0]) quad_run_entries<NF, 0, CC>(lane_addr, ent_addr, cnt_now[0]); }
         if constexpr (NF > 1) { if (cnt_now[1]) quad_run_entries<NF, 1, CC>(lane_addr, ent_addr + kEntRegion, cnt_now[1]); }
+        fetch_meta(k + 2);               // lands while the workgroup meets at the barriers
         __syncthreads();
         if (more) {
             write_lds();
@@ -869,34 +908,148 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
         }
     }
 
-    // ---- epilogue: accumulator columns 0 and 5 go to the neighbouring quads, bias, ReLU, store
+    // ---- epilogue: accumulator columns 0 and 5 go to the neighbouring quads; bias, ReLU, store
     T* __restrict__ y = static_cast<T*>(p.y);
+    int lane_again = lane;
+    asm volatile("" : "+v"(lane_again));               // keeps the compiler from carrying the first result over
+    const LanePlace late = place_of(lane_again);
+    const int q = late.q, n = late.n, oy0 = late.oy0;
+    const bool active = late.active;
     const bool has_left = q > 0, has_right = q + 1 < p.QW;
     const int o0 = 4 * q + p.pad - 1;                  // output column of accumulator column 1
-    auto finish = [&](const float (&P)[6][R], int pos) {
-        if (pos >= p.F) return;   // uniform per wave
-        const unsigned f = p.forder[pos];
-        const float bias = p.bias ? p.bias[f] : 0.f;
-        const size_t ybase = (((size_t)n * p.F + f) * p.Ho) * (size_t)p.Wo;
+    const size_t plane_out = (size_t)p.Ho * p.Wo;
+    // the four sums of output row `row` of one filter slot
+    auto row_sums = [&](auto slot_c, auto row_c, float (&v)[4]) {
+        float a[6];
+        quad_read_acc_row<decltype(slot_c)::value, decltype(row_c)::value>(a);
+        const float from_left = __shfl_up(a[5], 1, 64);     // the left quad's column 5 is this quad's column 1
+        const float from_right = __shfl_down(a[0], 1, 64);  // the right quad's column 0 is this quad's column 4
+        v[0] = a[1] + (has_left ? from_left : 0.f);
+        v[1] = a[2];
+        v[2] = a[3];
+        v[3] = a[4] + (has_right ? from_right : 0.f);
+    };
+    auto store_row = [&](const float (&v)[4], unsigned f, float bias, int r) {
+        const int oy = oy0 + r;
+        const size_t at = (((size_t)n * p.F + f) * p.Ho + oy) * (size_t)p.Wo;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const float from_left = __shfl_up(P[5][r], 1, 64);     // the left quad's column 5 is this quad's column 1
-            const float from_right = __shfl_down(P[0][r], 1, 64);  // the right quad's column 0 is this quad's column 4
-            float v[4] = {P[1][r] + (has_left ? from_left : 0.f), P[2][r], P[3][r],
-                          P[4][r] + (has_right ? from_right : 0.f)};
-            const int oy = oy0 + r;
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                float o = v[m] + bias;
-                if (p.relu) o = fmaxf(o, 0.f);
-                const int ox = o0 + m;
-                if (active && oy < p.Ho && ox >= 0 && ox < p.Wo) y[ybase + (size_t)oy * p.Wo + ox] = from_f32<T>(o);
-            }
+        for (int m = 0; m < 4; ++m) {
+            float o = v[m] + bias;
+            if (p.relu) o = fmaxf(o, 0.f);
+            const int ox = o0 + m;
+            if (active && oy < p.Ho && ox >= 0 && ox < p.Wo) y[at + ox] = from_f32<T>(o);
         }
     };
-    float P[6][R];
-    if constexpr (NF > 0) { quad_read_acc<0>(P); finish(P, pos_base); }
-    if constexpr (NF > 1) { quad_read_acc<1>(P); finish(P, pos_base + FW); }
+    unsigned filt[NF];
+    float filt_bias[NF];
+#pragma unroll
+    for (int a = 0; a < NF; ++a) {
+        const int pos = pos_base + a * FW;
+        filt[a] = pos < p.F ? scalar_load_u32(p.forder + pos) : 0u;
+        filt_bias[a] = (p.bias && pos < p.F)
+                           ? __builtin_bit_cast(float, scalar_load_u32(reinterpret_cast<const uint32_t*>(p.bias + filt[a])))
+                           : 0.f;
+    }
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+#define PCONV_QROWS(BODY) { BODY(I0{}, 0) BODY(I1{}, 1) BODY(I2{}, 2) BODY(I3{}, 3) }
+    float v[4];
+    if (p.KS == 1) {
+#define PCONV_QSTORE(rc, r) row_sums(slot_c, rc, v); store_row(v, filt[a], filt_bias[a], r);
+#define PCONV_QFINISH(Sv)                                              \
+        if (pos_base + Sv * FW < p.F) {   /* uniform per wave */        \
+            constexpr int a = Sv;                                      \
+            const std::integral_constant<int, Sv> slot_c{};            \
+            PCONV_QROWS(PCONV_QSTORE)                                  \
+        }
+        if constexpr (NF > 0) { PCONV_QFINISH(0) }
+        if constexpr (NF > 1) { PCONV_QFINISH(1) }
+#undef PCONV_QFINISH
+#undef PCONV_QSTORE
+        return;
+    }
+
+    // The channels of this tile are split over KS workgroups: partial sums go to the workspace, the workgroup that
+    // arrives last adds them up in the order of the splits (see tiled_body for the memory-ordering argument; the
+    // accesses here are the same kind: device-scope buffer stores and loads, one relaxed device-scope atomic).
+    const size_t split_stride = (size_t)p.N * p.F * plane_out;
+    constexpr int kDeviceScope = 16;   // cache-policy bit "sc1" of gfx942/gfx950 buffer instructions
+    auto ws_rsrc = [&](int s) { return make_rsrc(p.ws + (size_t)s * split_stride, (uint32_t)(split_stride * sizeof(float))); };
+    unsigned woff[4];
+    auto ws_offsets = [&](unsigned f, int r) {
+        const int oy = oy0 + r;
+        const unsigned at = (((unsigned)n * p.F + f) * (unsigned)p.Ho + (unsigned)oy) * (unsigned)p.Wo;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int ox = o0 + m;
+            woff[m] = (active && oy < p.Ho && ox >= 0 && ox < p.Wo) ? (at + (unsigned)ox) * 4u : kInvalidOffset;
+        }
+    };
+    const __amdgpu_buffer_rsrc_t mine = ws_rsrc(split);
+#define PCONV_QPART(rc, r)                                                                          \
+    row_sums(slot_c, rc, v);                                                                        \
+    ws_offsets(filt[a], r);                                                                         \
+    _Pragma("unroll") for (int m = 0; m < 4; ++m)                                                   \
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[m]), mine, (int)woff[m], 0, kDeviceScope);
+#define PCONV_QPARTIAL(Sv)                                             \
+    if (pos_base + Sv * FW < p.F) {                                    \
+        constexpr int a = Sv;                                          \
+        const std::integral_constant<int, Sv> slot_c{};                \
+        PCONV_QROWS(PCONV_QPART)                                       \
+    }
+    if constexpr (NF > 0) { PCONV_QPARTIAL(0) }
+    if constexpr (NF > 1) { PCONV_QPARTIAL(1) }
+#undef PCONV_QPARTIAL
+#undef PCONV_QPART
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                 // (also: nobody reads the staged chunk any more, LDS can carry the flag)
+    volatile unsigned* flag = reinterpret_cast<volatile unsigned*>(lds);
+    if (threadIdx.x == 0) {
+        const unsigned arrived = __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = arrived == (unsigned)p.KS - 1u;
+        // everybody has arrived: leave the counter ready for the next launch
+        if (last) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *flag = last ? 1u : 0u;
+    }
+    __syncthreads();
+    if (*flag == 0u) return;
+    // partial sums of up to four splits are requested together (this workgroup's own among them: its stores have
+    // been performed), then added in split order
+#define PCONV_QRED(rc, r)                                                                           \
+    {                                                                                               \
+        ws_offsets(filt[a], r);                                                                     \
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};                                                        \
+        for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
+            float part[4][4];                                                                       \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
+                const int s = min(s0 + j, p.KS - 1);                                                \
+                const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s);                                   \
+                _Pragma("unroll") for (int m = 0; m < 4; ++m)                                       \
+                    part[j][m] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[m], 0, kDeviceScope)); \
+            }                                                                                       \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
+                const int s = s0 + j;                                                               \
+                if (s < p.KS) {                                                                     \
+                    _Pragma("unroll") for (int m = 0; m < 4; ++m)                                   \
+                        sum[m] = s == 0 ? part[j][m] : sum[m] + part[j][m];                         \
+                }                                                                                   \
+            }                                                                                       \
+        }                                                                                           \
+        store_row(sum, filt[a], filt_bias[a], r);                                                   \
+    }
+#define PCONV_QREDUCE(Sv)                                              \
+    if (pos_base + Sv * FW < p.F) {                                    \
+        constexpr int a = Sv;                                          \
+        const std::integral_constant<int, Sv> slot_c{};                \
+        PCONV_QROWS(PCONV_QRED)                                        \
+    }
+    if constexpr (NF > 0) { PCONV_QREDUCE(0) }
+    if constexpr (NF > 1) { PCONV_QREDUCE(1) }
+#undef PCONV_QREDUCE
+#undef PCONV_QRED
+#undef PCONV_QROWS
 }
 
 template <int FW, typename T>
@@ -1089,8 +1242,8 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
     p.counters = nullptr;
     if (KS > 1) {
         const size_t floats = (size_t)KS * p.N * p.F * p.Ho * p.Wo;
-        // the kernel addresses one split's partial sums with 32-bit indices
-        if ((size_t)p.N * p.F * p.Ho * p.Wo >= ((size_t)1 << 30)) return PCONV_EUNSUPPORTED;
+        // the kernel addresses one split's partial sums with 32-bit byte offsets below kInvalidOffset
+        if ((size_t)p.N * p.F * p.Ho * p.Wo >= ((size_t)1 << 29)) return PCONV_EUNSUPPORTED;
         if (int rc = ensure_workspace(wp, floats, (size_t)slots * p.NG)) return rc;
         p.ws = wp->d_ws;
         p.counters = wp->d_counters;
@@ -1117,7 +1270,7 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
 }
 
 template <typename T>
-static int launch_quad(QuadParams& p, int NF, int FW, hipStream_t stream) {
+static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, int KS, hipStream_t stream) {
     constexpr int R = PCONV_QUAD_ROWS;
     if (p.W % 4 != 0 || p.W / 4 > 64) return PCONV_EUNSUPPORTED;
     p.QW = p.W / 4;
@@ -1131,9 +1284,22 @@ static int launch_quad(QuadParams& p, int NF, int FW, hipStream_t stream) {
     // within 3 % of them on the VGG-16 shapes at batch 64, slower on most.
     if (FW != 16) return PCONV_EUNSUPPORTED;
     p.NG = (p.F + FW * NF - 1) / (FW * NF);
-    const long long nb = slots * p.NG;
+    KS = std::max(1, std::min(KS, p.nbk));
+    const long long nb = slots * p.NG * KS;
     if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
     p.nblocks = (int)nb;
+    p.KS = KS;
+    p.div_KS = make_fastdiv((unsigned)KS);
+    p.ws = nullptr;
+    p.counters = nullptr;
+    if (KS > 1) {
+        // the kernel addresses one split's partial sums with 32-bit byte offsets below kInvalidOffset
+        const size_t outs = (size_t)p.N * p.F * p.Ho * p.Wo;
+        if (outs >= ((size_t)1 << 29)) return PCONV_EUNSUPPORTED;
+        if (int rc = ensure_workspace(wp, (size_t)KS * outs, (size_t)slots * p.NG)) return rc;
+        p.ws = wp->d_ws;
+        p.counters = wp->d_counters;
+    }
     // 32-bit byte offsets inside the buffer descriptor: the images one slot can span
     const unsigned long long span = (unsigned long long)((p.BL + p.NRB - 1) / p.NRB + 1);
     if ((unsigned long long)p.img_bytes * span >= 0x7FFFFFFFull) return PCONV_EUNSUPPORTED;
@@ -1298,6 +1464,8 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
                 const int nch = (lay->C + cc - 1) / cc;
                 const double per_filter_chunk = (double)lay->n_kept / ((double)lay->F * nch);
                 for (int ks = 1; ks <= std::min(nch, 16); ks *= 2) {
+                    // (the workspace of one split is addressed with 32-bit byte offsets)
+                    if (ks > 1 && (unsigned long long)N * lay->F * Ho * Wo >= (1ull << 29)) break;
                     const double issue = (w / 4) * nf * per_filter_chunk * 128.0 + 750.0;
                     const double staging = std::min(lay->C, cc) * 9.0 * 18.0 * (pair ? 0.5 : 1.0);
                     const double chunk = std::max(issue, staging) + 3400.0;
@@ -1379,6 +1547,8 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.perm_stride = 0;
         const int nf = NF == 0 ? 2 : NF;
         const int fw = waves == 0 ? 16 : waves;
+        if (KS < 0) return PCONV_EINVAL;
+        if (KS == 0) KS = 1;
         if (order != PCONV_ORDER_PLAIN) {
             for (const BalancedLayout& b : wp->balanced)
                 if (b.fw == fw && b.nf == nf && b.cc == fw && b.d_ent) {
@@ -1391,10 +1561,12 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
             if (order == PCONV_ORDER_BALANCED && !p.perm) return PCONV_EUNSUPPORTED;
         }
         if (fw != 16 && !p.perm) return PCONV_EUNSUPPORTED;   // the canonical entries come in chunks of 16 channels
+        if ((unsigned long long)wp->n_kept * sizeof(DevEntry) >= kInvalidOffset) return PCONV_EUNSUPPORTED;
+        p.ent_bytes = (unsigned)((size_t)wp->n_kept * sizeof(DevEntry));
         p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
         p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
         p.plane_bytes = (unsigned)((size_t)H * W * esize);
-        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, nf, fw, st) : launch_quad<float>(p, nf, fw, st);
+        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, wp, nf, fw, KS, st) : launch_quad<float>(p, wp, nf, fw, KS, st);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);

@@ -201,6 +201,9 @@ def test_quad_kernel(case, dtype):
     Q = pc.KERNEL_QUAD
     check(layer, x, [dict(kernel=Q, filters_per_wave=nf, channel_order=o) for nf in (1, 2)
                      for o in (pc.ORDER_PLAIN, pc.ORDER_BALANCED)])
+    # channels split over several workgroups per tile (more splits than chunks are cut down to the chunks)
+    check(layer, x, [dict(kernel=Q, filters_per_wave=nf, channel_splits=ks) for nf in (1, 2) for ks in (2, 3, 8)])
+    check(layer, x, [dict(kernel=Q, channel_splits=2)], relu=True)
     check(layer, x, [dict(kernel=Q)], relu=True)
     layer.free()
 
