@@ -169,6 +169,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--only", default="", help="with --layers: only the layer of this name")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "tiled", "quad"],
+                    help="with --layers: the kernel the per-layer timing uses (auto: the library's choice)")
     ap.add_argument("--chain", action="store_true")
     ap.add_argument("--graph", action="store_true", help="with --chain: replay the chain as one HIP graph")
     args = ap.parse_args()
@@ -323,12 +325,13 @@ def layer_table(args, torch, pc, L, stream):
         layer = DeviceLayer(spec, batch_from_one_image=True)
         macs = effective_macs(spec, layer.n_kept)
         steps = max(10, min(1000, int(2e10 / max(macs, 1))))
+        forced = {"auto": {}, "tiled": dict(kernel=pc.KERNEL_TILED), "quad": dict(kernel=pc.KERNEL_QUAD)}[args.kernel]
         t0 = time.perf_counter()
         while time.perf_counter() - t0 < 0.05:      # bring the clocks up before the first timed launch of a layer
             for _ in range(4):
-                layer.launch(stream)
+                layer.launch(stream, **forced)
             torch.cuda.synchronize()
-        _, ev = time_launches(torch, lambda: layer.launch(stream), steps, max(3, steps // 10))
+        _, ev = time_launches(torch, lambda: layer.launch(stream, **forced), steps, max(3, steps // 10))
         best = None
         if args.tune:
             for nf, wv, cpw, nbuf in [] if args.tune == "quad" else [(1, 8, 4, 1), (1, 16, 2, 1), (2, 16, 2, 1), (2, 16, 1, 1), (2, 8, 2, 1),
