@@ -157,9 +157,13 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
 /*
  * pconv_conv3x3 with the kernel choice in the caller's hands, for tuning sweeps and for tests that must reach every
  * kernel.  A NULL `tuning`, or a field left 0, means "choose automatically" (what pconv_conv3x3 does).
- *   kernel            PCONV_KERNEL_TILED (activations staged in LDS; stride 2 through the parity form of the layer,
- *                     see pconv_packed_parity_form) or PCONV_KERNEL_GENERIC (any stride and pad, straight from
- *                     global memory)
+ *   kernel            PCONV_KERNEL_TILED (one input column per lane, activations staged in LDS; stride 2 through
+ *                     the parity form of the layer, see pconv_packed_parity_form), PCONV_KERNEL_QUAD (four input
+ *                     columns per lane, for layers with many output tiles: unit stride, W a multiple of 4 and at
+ *                     most 256; of the fields below it reads filters_per_wave (1 or 2), channel_order (balanced
+ *                     orders exist for 16-channel chunks) and channel_splits (0 = 1)) or PCONV_KERNEL_GENERIC (any
+ *                     stride and pad, straight from global memory).  Automatic: QUAD where it applies and has at
+ *                     least 200 workgroups of its own, else TILED, else GENERIC
  *   rows              tiled: output rows held per lane (7)
  *   filters_per_wave  tiled: filters accumulated at once by one wave (1 or 2)
  *   waves             tiled: waves per workgroup, 1..16

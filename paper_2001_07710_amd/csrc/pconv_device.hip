@@ -1,9 +1,11 @@
 // Device side of libpconv for gfx950 (MI355X): kernels, launch selection, device upload of the packed weights.
 //
 // Kernels in this file
-//   tiled_kernel    pattern-sparse 3x3 convolution at unit stride: activations staged in LDS in a lane-shaped layout,
-//                   one or two filters per wave, one generated code section per pattern; stride 2 runs through it
-//                   on the layer re-packed over the four parity planes of the input
+//   tiled_kernel    pattern-sparse 3x3 convolution at unit stride: one input column per lane, activations staged in
+//                   LDS in a lane-shaped layout, one or two filters per wave, one generated code section per
+//                   pattern; stride 2 runs through it on the layer re-packed over the four parity planes of the input
+//   quad_kernel     the same with four input columns per lane (64 multiply-adds per kept kernel instead of 28,
+//                   128-bit staging loads): for layers with enough output tiles to fill the chip with larger tiles
 //   parity_planes_kernel  the split of the input into those planes
 //   generic_kernel  the same sum for any stride and pad, one thread per output, straight from global memory
 //   dense_kernel    dense 3x3 convolution of the same shape (comparison baseline)
@@ -669,7 +671,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(43))) void til
 // instructions per element of the one-column kernel, whose batch-1 chunks are bound by load issue.
 //
 // Work split.  Workgroup = one slot (the wave shape above) x 16 waves x NF filters; chunks of 16 channels in their
-// own order, one chunk buffer, two barriers per chunk.  No channel split yet: meant for layers with many tiles.
+// own or in the workgroup's balanced order, one chunk buffer, two barriers per chunk.  Channels can be split over
+// several workgroups per tile as in the one-column kernel; meant for layers with many tiles, where that is not needed.
 // ---------------------------------------------------------------------------------------------------------------
 
 struct QuadParams {
