@@ -690,6 +690,7 @@ struct QuadParams {
     int NBLK;                // N * NRB
     int NG;                  // filter groups per slot
     int KS;                  // workgroups per output tile (each takes a range of the chunks)
+    int vec;                 // a lane's four outputs of a row are in range together and 16-byte aligned (pad 1, aligned y)
     int nblocks;             // NG * slots * KS (the grid is padded to a multiple of 8)
     float* ws;               // KS > 1: partial sums [KS][N][F][Ho][Wo]
     unsigned* counters;      // KS > 1: one arrival counter per tile, zero between launches
@@ -698,6 +699,10 @@ struct QuadParams {
     unsigned ent_bytes;      // size of ent[] (below 2^31: the kernel reads it through a buffer descriptor)
     FastDiv div_NG, div_KS, div_QW, div_NRB;
 };
+
+// (By value on purpose: __builtin_bit_cast applied directly to an element of an ext_vector_type value reads element 0
+// whatever the index, with this compiler.)
+__device__ __forceinline__ float bits_to_f32(unsigned u) { return __builtin_bit_cast(float, u); }
 
 // four neighbouring elements as they are stored
 template <typename T>
@@ -935,12 +940,30 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     auto store_row = [&](const float (&v)[4], unsigned f, float bias, int r) {
         const int oy = oy0 + r;
         const size_t at = (((size_t)n * p.F + f) * p.Ho + oy) * (size_t)p.Wo;
+        float o[4];
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
-            float o = v[m] + bias;
-            if (p.relu) o = fmaxf(o, 0.f);
+            o[m] = v[m] + bias;
+            if (p.relu) o[m] = fmaxf(o[m], 0.f);
+        }
+        if (p.vec) {             // uniform: one 128-bit (fp16: 64-bit) store per lane and row
+            if (active && oy < p.Ho) {
+                if constexpr (sizeof(T) == 4) {
+                    *reinterpret_cast<float4*>(y + at + o0) = make_float4(o[0], o[1], o[2], o[3]);
+                } else {
+                    const unsigned lo = (unsigned)__half_as_ushort(__float2half_rn(o[0])) |
+                                        ((unsigned)__half_as_ushort(__float2half_rn(o[1])) << 16);
+                    const unsigned hi = (unsigned)__half_as_ushort(__float2half_rn(o[2])) |
+                                        ((unsigned)__half_as_ushort(__float2half_rn(o[3])) << 16);
+                    *reinterpret_cast<uint2*>(y + at + o0) = make_uint2(lo, hi);
+                }
+            }
+            return;
+        }
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
             const int ox = o0 + m;
-            if (active && oy < p.Ho && ox >= 0 && ox < p.Wo) y[at + ox] = from_f32<T>(o);
+            if (active && oy < p.Ho && ox >= 0 && ox < p.Wo) y[at + ox] = from_f32<T>(o[m]);
         }
     };
     unsigned filt[NF];
@@ -980,10 +1003,15 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     const size_t split_stride = (size_t)p.N * p.F * plane_out;
     constexpr int kDeviceScope = 16;   // cache-policy bit "sc1" of gfx942/gfx950 buffer instructions
     auto ws_rsrc = [&](int s) { return make_rsrc(p.ws + (size_t)s * split_stride, (uint32_t)(split_stride * sizeof(float))); };
-    unsigned woff[4];
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    unsigned woff[4];            // vec: woff[0] is the offset of the lane's four partial sums of the row
     auto ws_offsets = [&](unsigned f, int r) {
         const int oy = oy0 + r;
         const unsigned at = (((unsigned)n * p.F + f) * (unsigned)p.Ho + (unsigned)oy) * (unsigned)p.Wo;
+        if (p.vec) {
+            woff[0] = (active && oy < p.Ho) ? (at + (unsigned)o0) * 4u : kInvalidOffset;
+            return;
+        }
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             const int ox = o0 + m;
@@ -994,8 +1022,14 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
 #define PCONV_QPART(rc, r)                                                                          \
     row_sums(slot_c, rc, v);                                                                        \
     ws_offsets(filt[a], r);                                                                         \
-    _Pragma("unroll") for (int m = 0; m < 4; ++m)                                                   \
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[m]), mine, (int)woff[m], 0, kDeviceScope);
+    if (p.vec) {                                                                                    \
+        const v4u q4 = {__builtin_bit_cast(unsigned, v[0]), __builtin_bit_cast(unsigned, v[1]),     \
+                        __builtin_bit_cast(unsigned, v[2]), __builtin_bit_cast(unsigned, v[3])};    \
+        __builtin_amdgcn_raw_buffer_store_b128(q4, mine, (int)woff[0], 0, kDeviceScope);            \
+    } else {                                                                                        \
+        _Pragma("unroll") for (int m = 0; m < 4; ++m)                                               \
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[m]), mine, (int)woff[m], 0, kDeviceScope); \
+    }
 #define PCONV_QPARTIAL(Sv)                                             \
     if (pos_base + Sv * FW < p.F) {                                    \
         constexpr int a = Sv;                                          \
@@ -1020,18 +1054,7 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     if (*flag == 0u) return;
     // partial sums of up to four splits are requested together (this workgroup's own among them: its stores have
     // been performed), then added in split order
-#define PCONV_QRED(rc, r)                                                                           \
-    {                                                                                               \
-        ws_offsets(filt[a], r);                                                                     \
-        float sum[4] = {0.f, 0.f, 0.f, 0.f};                                                        \
-        for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
-            float part[4][4];                                                                       \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
-                const int s = min(s0 + j, p.KS - 1);                                                \
-                const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s);                                   \
-                _Pragma("unroll") for (int m = 0; m < 4; ++m)                                       \
-                    part[j][m] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[m], 0, kDeviceScope)); \
-            }                                                                                       \
+#define PCONV_QRED_TAIL(r)                                                                          \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
                 const int s = s0 + j;                                                               \
                 if (s < p.KS) {                                                                     \
@@ -1042,16 +1065,45 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
         }                                                                                           \
         store_row(sum, filt[a], filt_bias[a], r);                                                   \
     }
+#define PCONV_QRED(rc, r)                                                                           \
+    {                                                                                               \
+        ws_offsets(filt[a], r);                                                                     \
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};                                                        \
+        for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
+            float part[4][4];                                                                       \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
+                const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(min(s0 + j, p.KS - 1));               \
+                _Pragma("unroll") for (int m = 0; m < 4; ++m)                                       \
+                    part[j][m] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[m], 0, kDeviceScope)); \
+            }                                                                                       \
+    PCONV_QRED_TAIL(r)
+#define PCONV_QRED_VEC(rc, r)                                                                       \
+    {                                                                                               \
+        ws_offsets(filt[a], r);                                                                     \
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};                                                        \
+        for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
+            float part[4][4];                                                                       \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
+                const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(min(s0 + j, p.KS - 1));               \
+                const v4u q4 = __builtin_amdgcn_raw_buffer_load_b128(theirs, (int)woff[0], 0, kDeviceScope); \
+                part[j][0] = bits_to_f32(q4[0]);                                                    \
+                part[j][1] = bits_to_f32(q4[1]);                                                    \
+                part[j][2] = bits_to_f32(q4[2]);                                                    \
+                part[j][3] = bits_to_f32(q4[3]);                                                    \
+            }                                                                                       \
+    PCONV_QRED_TAIL(r)
 #define PCONV_QREDUCE(Sv)                                              \
     if (pos_base + Sv * FW < p.F) {                                    \
         constexpr int a = Sv;                                          \
-        const std::integral_constant<int, Sv> slot_c{};                \
-        PCONV_QROWS(PCONV_QRED)                                        \
+        if (p.vec) PCONV_QROWS(PCONV_QRED_VEC)                         \
+        else PCONV_QROWS(PCONV_QRED)                                   \
     }
     if constexpr (NF > 0) { PCONV_QREDUCE(0) }
     if constexpr (NF > 1) { PCONV_QREDUCE(1) }
 #undef PCONV_QREDUCE
 #undef PCONV_QRED
+#undef PCONV_QRED_VEC
+#undef PCONV_QRED_TAIL
 #undef PCONV_QROWS
 }
 
@@ -1293,6 +1345,8 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
     p.nblocks = (int)nb;
     p.KS = KS;
     p.div_KS = make_fastdiv((unsigned)KS);
+    // pad 1: Wo == W, so a lane's four outputs of a row start at a multiple of four columns and are all inside
+    p.vec = (p.pad == 1 && reinterpret_cast<uintptr_t>(p.y) % 16 == 0) ? 1 : 0;
     p.ws = nullptr;
     p.counters = nullptr;
     if (KS > 1) {
@@ -1401,9 +1455,16 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         // The kernel with four columns per lane has no channel split: it is the faster one (measured on the VGG-16
         // and ResNet-50 layer shapes at batch 32 and 64) once its own workgroups nearly fill the 256 CUs.
         long long wgs = 0;
-        if (quad_applicable(N, wp->C, wp->F, H, W, Ho, stride, esize, &wgs) && wgs >= 200) {
-            kernel = PCONV_KERNEL_QUAD;
-            NF = 2;
+        if (quad_applicable(N, wp->C, wp->F, H, W, Ho, stride, esize, &wgs)) {
+            if (wgs >= 200) {
+                kernel = PCONV_KERNEL_QUAD;
+                NF = 2;
+            } else if (wp->C <= 16 && wgs * ((wp->F + 15) / 16) / ((wp->F + 31) / 32) >= 200) {
+                // a single chunk of channels (a network's first layer): nothing to amortise over two filters per
+                // wave, and one filter per wave gives twice the workgroups
+                kernel = PCONV_KERNEL_QUAD;
+                NF = 1;
+            }
         }
     }
     if (kernel == PCONV_KERNEL_AUTO) kernel = can_tile ? PCONV_KERNEL_TILED : PCONV_KERNEL_GENERIC;
