@@ -137,6 +137,9 @@ void pconv_free(pconv_packed* p);
  * optionally followed by max(.,0).  Asynchronous on `stream`.
  *   x       device, dtype[N*C*H*W], read only; must not overlap y
  *   y       device, dtype[N*F*Ho*Wo], every element written
+ *           (x and y need the alignment of one element only; the automatic choice uses the kernels with 64- and
+ *           128-bit accesses where x is aligned to 4 bytes -- stride 2: to two elements -- and y to 16 bytes, as
+ *           device allocations are)
  *   wp      handle from pconv_pack (with a device copy, on the current device)
  *   bias    device, float[F], or NULL for no bias
  *   stride  1 or 2;  pad 0 or 1

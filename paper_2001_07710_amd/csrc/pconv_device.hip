@@ -1455,7 +1455,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         // The kernel with four columns per lane has no channel split: it is the faster one (measured on the VGG-16
         // and ResNet-50 layer shapes at batch 32 and 64) once its own workgroups nearly fill the 256 CUs.
         long long wgs = 0;
-        if (quad_applicable(N, wp->C, wp->F, H, W, Ho, stride, esize, &wgs)) {
+        if (reinterpret_cast<uintptr_t>(x) % 4 == 0 && quad_applicable(N, wp->C, wp->F, H, W, Ho, stride, esize, &wgs)) {
             if (wgs >= 200) {
                 kernel = PCONV_KERNEL_QUAD;
                 NF = 2;
@@ -1475,7 +1475,9 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     // two channels per wave, channels in their own order).  Otherwise the input is split into planes by a pass of
     // its own first.
     const int order = tuning ? tuning->channel_order : PCONV_ORDER_AUTO;
+    // (two-element loads: x must be aligned to two elements)
     const bool pair = kernel == PCONV_KERNEL_TILED && stride == 2 && H % 2 == 0 && W % 2 == 0 &&
+                      reinterpret_cast<uintptr_t>(x) % (2 * esize) == 0 &&
                       order != PCONV_ORDER_BALANCED && buffers <= 1 &&
                       (automatic || (waves == 16 && (CPW == 0 || CPW == 2)));
     if (kernel == PCONV_KERNEL_TILED && stride == 2) {
@@ -1589,6 +1591,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     }
     if (kernel == PCONV_KERNEL_QUAD) {
         if (stride != 1) return PCONV_EUNSUPPORTED;
+        if (reinterpret_cast<uintptr_t>(x) % 4 != 0) return PCONV_EUNSUPPORTED;   // four-element loads, dword-aligned
         if ((unsigned long long)wp->C * H * W * esize >= 0x7FFFFFFFull) return PCONV_EUNSUPPORTED;
         QuadParams p{};
         p.x = x;

@@ -54,14 +54,19 @@ class GpuLayer:
         self.wm = oracle.mask_weights(self.w, self.pid, self.mask, self.lib)
         self.tdtype = torch.float16 if spec.dtype == "f16" else torch.float32
 
-    def run(self, x_np, relu=None, canary=True, **tuning):
-        """x_np [N][C][H][W] in the storage dtype -> numpy y [N][F][Ho][Wo] (storage dtype)."""
+    def run(self, x_np, relu=None, canary=True, y_shift=0, x_shift=0, **tuning):
+        """x_np [N][C][H][W] in the storage dtype -> numpy y [N][F][Ho][Wo] (storage dtype).  y_shift moves the
+        output buffer by that many elements (an output pointer that is not 16-byte aligned), x_shift the input."""
         torch, s = self.torch, self.spec
         N = x_np.shape[0]
         relu = s.relu if relu is None else relu
         dx = torch.from_numpy(np.ascontiguousarray(x_np)).cuda()
+        if x_shift:
+            xbuf = torch.zeros(dx.numel() + x_shift, dtype=dx.dtype, device="cuda")
+            xbuf[x_shift:] = dx.reshape(-1)
+            dx = xbuf[x_shift:]
         n_out = N * s.F * s.Ho * s.Wo
-        pad = 4096 if canary else 0
+        pad = (4096 if canary else 0) + y_shift
         buf = torch.full((n_out + 2 * pad,), -777.0, dtype=self.tdtype, device="cuda")
         dy = buf[pad:pad + n_out]
         flags = pc.FLAG_RELU if relu else 0

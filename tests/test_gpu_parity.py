@@ -208,6 +208,40 @@ def test_quad_kernel(case, dtype):
     layer.free()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_quad_kernel_with_an_output_pointer_that_is_not_16_byte_aligned(dtype):
+    """The 128-bit stores of the quad kernel need an aligned output; otherwise it stores element by element."""
+    spec = L.LayerSpec(cfg=15, idx=50, name="quadshift", N=2, C=24, F=20, H=10, W=16, stride=1, pad=1, dtype=dtype,
+                       K=8, keep=0.5)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    ref = layer.oracle(x)
+    for shift in (1, 2, 3):
+        for t in (dict(kernel=pc.KERNEL_QUAD), dict(kernel=pc.KERNEL_QUAD, channel_splits=2)):
+            say(spec.name, dtype, "shift", shift, t)
+            assert rel_err(layer.run(x, y_shift=shift, **t), ref) <= TOL[dtype]
+    layer.free()
+
+
+def test_an_input_pointer_aligned_to_one_element_only():
+    """fp16 activations at an odd element offset: the kernels that load two or four elements at a time are not
+    chosen (and refuse when asked for), the result is the same."""
+    for stride, N in ((1, 40), (2, 3)):
+        spec = L.LayerSpec(cfg=15, idx=60 + stride, name="xshift", N=N, C=20, F=36, H=12, W=16, stride=stride, pad=1,
+                           dtype="f16", K=8, keep=0.5)
+        layer = GpuLayer(spec)
+        x = L.gen_activations(spec)
+        ref = layer.oracle(x)
+        say(spec.name, "stride", stride, "x shifted by one element")
+        assert rel_err(layer.run(x, x_shift=1), ref) <= TOL["f16"]
+        assert rel_err(layer.run(x, x_shift=1, kernel=T), ref) <= TOL["f16"]
+        if stride == 1:
+            with pytest.raises(pc.PconvError) as ei:
+                layer.run(x, x_shift=1, kernel=pc.KERNEL_QUAD)
+            assert ei.value.code == pc.EUNSUPPORTED
+        layer.free()
+
+
 def test_quad_kernel_refuses_what_it_cannot_do():
     spec = L.LayerSpec(cfg=15, idx=99, name="quadno", N=1, C=8, F=8, H=8, W=10, K=8, keep=0.5)
     layer = GpuLayer(spec)
