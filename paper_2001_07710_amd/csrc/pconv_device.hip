@@ -620,10 +620,14 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
         for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
             float part[4][R];                                                                       \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
-                const int s = min(s0 + j, p.KS - 1);                                                \
-                const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s);                                   \
-                _Pragma("unroll") for (int r = 0; r < R; ++r)                                       \
-                    part[j][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[r], 0, kDeviceScope)); \
+                const int s = s0 + j;                                                               \
+                if (s < p.KS && s != split) {   /* uniform: only the splits that exist, not this one's own */ \
+                    const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s);                               \
+                    _Pragma("unroll") for (int r = 0; r < R; ++r)                                   \
+                        part[j][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[r], 0, kDeviceScope)); \
+                } else {                                                                            \
+                    _Pragma("unroll") for (int r = 0; r < R; ++r) part[j][r] = 0.f;                 \
+                }                                                                                   \
             }                                                                                       \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
                 const int s = s0 + j;                                                               \
@@ -1072,9 +1076,13 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
         for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
             float part[4][4];                                                                       \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
-                const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(min(s0 + j, p.KS - 1));               \
-                _Pragma("unroll") for (int m = 0; m < 4; ++m)                                       \
-                    part[j][m] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[m], 0, kDeviceScope)); \
+                if (s0 + j < p.KS) {            /* uniform: only the splits that exist */           \
+                    const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s0 + j);                          \
+                    _Pragma("unroll") for (int m = 0; m < 4; ++m)                                   \
+                        part[j][m] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[m], 0, kDeviceScope)); \
+                } else {                                                                            \
+                    _Pragma("unroll") for (int m = 0; m < 4; ++m) part[j][m] = 0.f;                 \
+                }                                                                                   \
             }                                                                                       \
     PCONV_QRED_TAIL(r)
 #define PCONV_QRED_VEC(rc, r)                                                                       \
@@ -1084,12 +1092,16 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
         for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
             float part[4][4];                                                                       \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
-                const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(min(s0 + j, p.KS - 1));               \
-                const v4u q4 = __builtin_amdgcn_raw_buffer_load_b128(theirs, (int)woff[0], 0, kDeviceScope); \
-                part[j][0] = bits_to_f32(q4[0]);                                                    \
-                part[j][1] = bits_to_f32(q4[1]);                                                    \
-                part[j][2] = bits_to_f32(q4[2]);                                                    \
-                part[j][3] = bits_to_f32(q4[3]);                                                    \
+                if (s0 + j < p.KS) {            /* uniform: only the splits that exist */           \
+                    const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s0 + j);                          \
+                    const v4u q4 = __builtin_amdgcn_raw_buffer_load_b128(theirs, (int)woff[0], 0, kDeviceScope); \
+                    part[j][0] = bits_to_f32(q4[0]);                                                \
+                    part[j][1] = bits_to_f32(q4[1]);                                                \
+                    part[j][2] = bits_to_f32(q4[2]);                                                \
+                    part[j][3] = bits_to_f32(q4[3]);                                                \
+                } else {                                                                            \
+                    part[j][0] = part[j][1] = part[j][2] = part[j][3] = 0.f;                        \
+                }                                                                                   \
             }                                                                                       \
     PCONV_QRED_TAIL(r)
 #define PCONV_QREDUCE(Sv)                                              \
