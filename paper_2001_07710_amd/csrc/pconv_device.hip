@@ -253,7 +253,8 @@ struct TiledParams {
     int LW, S, OWS, NCS, NRB, NSEG;
     int NG;                  // filter groups per slot
     int KS;                  // workgroups that share one output tile, each taking a range of the channel chunks
-    float* ws;               // KS > 1: [KS][N][F][Ho][Wo] partial sums
+    float* ws;               // KS > 1: partial sums [KS][tiles][waves][NF][64 lanes][8]: a lane's output rows, as held
+    unsigned ws_split_bytes; //         size of one split's partial sums
     unsigned* counters;      // KS > 1: [slots * NG] arrivals, zero between launches
     int nblocks;             // NG * slots * KS (the grid is padded to a multiple of 8)
     unsigned long long x_bytes;
@@ -262,6 +263,12 @@ struct TiledParams {
     FastDiv div_KS, div_NG, div_LW, div_segs_per_img, div_NCS;
     int pair;                // the layer is a parity form and x is the original input (kernels with PAIR staging)
 };
+
+// (By value on purpose: __builtin_bit_cast applied directly to an element of an ext_vector_type value reads element 0
+// whatever the index, with this compiler.)
+__device__ __forceinline__ float bits_to_f32(unsigned u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ unsigned f32_to_bits(float f) { return __builtin_bit_cast(unsigned, f); }
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kR = 7;                       // output rows per lane
 constexpr int kPR = 12;                     // patch rows per lane in LDS (R + 2, padded to a multiple of four)
@@ -573,26 +580,26 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     // write-back or invalidation is needed (a device-scope fence here writes back and invalidates the whole L2 and
     // costs more than the split saves).  Order: a wave's stores have been performed when its vmcnt is zero; the
     // barrier puts that before the arrival is counted; the last workgroup's loads are issued after its count returned.
-    // The accesses go through buffer descriptors (one per split's partial sums) with the device-scope cache policy;
-    // lanes without an output get an offset outside the descriptor, so there is no branch per access.
-    const size_t split_stride = (size_t)p.N * p.F * plane_out;
+    // The accesses go through buffer descriptors (one per split's partial sums) with the device-scope cache policy.
+    // The workspace is laid out like the registers, not like the output: filter slot a of wave w of tile t has 2 KB
+    // at (t*FW*NF + w*NF + a)*2048 of the split's part, rows 0..3 of lane l at + 16*l, rows 4..6 and a spare word
+    // at + 1024 + 16*l -- every split of a tile has the same lanes on the same outputs, so two 128-bit stores and
+    // two 128-bit loads per split move a lane's rows, each instruction covers 1 KB without gaps, and lanes without
+    // an output need no special case.
     constexpr int kDeviceScope = 16;   // cache-policy bit "sc1" of gfx942/gfx950 buffer instructions
-    auto ws_rsrc = [&](int s) { return make_rsrc(p.ws + (size_t)s * split_stride, (uint32_t)(split_stride * sizeof(float))); };
-    unsigned woff[R];
-    auto ws_offsets = [&](unsigned f) {
-        const unsigned at = ((unsigned)n * p.F + f) * (unsigned)plane_out + (unsigned)(r0 * p.Wo + ox);
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            woff[r] = (col_ok && r0 + r < p.Ho) ? (at + (unsigned)(r * p.Wo)) * 4u : kInvalidOffset;
+    auto ws_rsrc = [&](int s) {
+        return make_rsrc(reinterpret_cast<const char*>(p.ws) + (size_t)s * p.ws_split_bytes, p.ws_split_bytes);
     };
+    auto ws_offset = [&](int a) { return (unsigned)((tile * FW + wave) * NF + a) * 2048u + (unsigned)lane * 16u; };
     const __amdgpu_buffer_rsrc_t mine = ws_rsrc(split);
 #define PCONV_PARTIAL(a)                                                                            \
     if (pos_base + a * FW < p.F) {                                                                  \
         read_acc<a>(acc);                                                                           \
         combine(acc, v);                                                                            \
-        ws_offsets(filt[a]);                                                                        \
-        _Pragma("unroll") for (int r = 0; r < R; ++r)                                               \
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[r]), mine, (int)woff[r], 0, kDeviceScope); \
+        const v4u lo = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])}; \
+        const v4u hi = {f32_to_bits(v[4]), f32_to_bits(v[5]), f32_to_bits(v[6]), 0u};               \
+        __builtin_amdgcn_raw_buffer_store_b128(lo, mine, (int)ws_offset(a), 0, kDeviceScope);       \
+        __builtin_amdgcn_raw_buffer_store_b128(hi, mine, (int)ws_offset(a) + 1024, 0, kDeviceScope);  \
     }
     if constexpr (NF > 0) { PCONV_PARTIAL(0) }
     if constexpr (NF > 1) { PCONV_PARTIAL(1) }
@@ -612,9 +619,9 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     // partial sums of up to four splits are requested together, then added in split order
 #define PCONV_REDUCE(a)                                                                             \
     if (pos_base + a * FW < p.F) {                                                                  \
+        static_assert(R == 7, "two 128-bit words per lane and filter");                             \
         read_acc<a>(acc);                                                                           \
         combine(acc, v);                                                                            \
-        ws_offsets(filt[a]);                                                                        \
         float sum[R];                                                                               \
         _Pragma("unroll") for (int r = 0; r < R; ++r) sum[r] = 0.f;                                 \
         for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
@@ -623,8 +630,12 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
                 const int s = s0 + j;                                                               \
                 if (s < p.KS && s != split) {   /* uniform: only the splits that exist, not this one's own */ \
                     const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s);                               \
-                    _Pragma("unroll") for (int r = 0; r < R; ++r)                                   \
-                        part[j][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[r], 0, kDeviceScope)); \
+                    const v4u lo = __builtin_amdgcn_raw_buffer_load_b128(theirs, (int)ws_offset(a), 0, kDeviceScope); \
+                    const v4u hi = __builtin_amdgcn_raw_buffer_load_b128(theirs, (int)ws_offset(a) + 1024, 0, kDeviceScope); \
+                    part[j][0] = bits_to_f32(lo[0]); part[j][1] = bits_to_f32(lo[1]);               \
+                    part[j][2] = bits_to_f32(lo[2]); part[j][3] = bits_to_f32(lo[3]);               \
+                    part[j][4] = bits_to_f32(hi[0]); part[j][5] = bits_to_f32(hi[1]);               \
+                    part[j][6] = bits_to_f32(hi[2]);                                                \
                 } else {                                                                            \
                     _Pragma("unroll") for (int r = 0; r < R; ++r) part[j][r] = 0.f;                 \
                 }                                                                                   \
@@ -696,17 +707,14 @@ struct QuadParams {
     int KS;                  // workgroups per output tile (each takes a range of the chunks)
     int vec;                 // a lane's four outputs of a row are in range together and 16-byte aligned (pad 1, aligned y)
     int nblocks;             // NG * slots * KS (the grid is padded to a multiple of 8)
-    float* ws;               // KS > 1: partial sums [KS][N][F][Ho][Wo]
+    float* ws;               // KS > 1: partial sums [KS][tiles][16 waves][NF][64 lanes][16]: a lane's outputs, as held
+    unsigned ws_split_bytes; //         size of one split's partial sums
     unsigned* counters;      // KS > 1: one arrival counter per tile, zero between launches
     unsigned long long x_bytes;
     unsigned img_bytes, plane_bytes;
     unsigned ent_bytes;      // size of ent[] (below 2^31: the kernel reads it through a buffer descriptor)
     FastDiv div_NG, div_KS, div_QW, div_NRB;
 };
-
-// (By value on purpose: __builtin_bit_cast applied directly to an element of an ext_vector_type value reads element 0
-// whatever the index, with this compiler.)
-__device__ __forceinline__ float bits_to_f32(unsigned u) { return __builtin_bit_cast(float, u); }
 
 // four neighbouring elements as they are stored
 template <typename T>
@@ -715,7 +723,6 @@ template <>
 struct RawQuad<float> {
     unsigned e0, e1, e2, e3;
     __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-        typedef unsigned v4u __attribute__((ext_vector_type(4)));
         const v4u v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
         e0 = v[0];
         e1 = v[1];
@@ -929,7 +936,6 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     const bool active = late.active;
     const bool has_left = q > 0, has_right = q + 1 < p.QW;
     const int o0 = 4 * q + p.pad - 1;                  // output column of accumulator column 1
-    const size_t plane_out = (size_t)p.Ho * p.Wo;
     // the four sums of output row `row` of one filter slot
     auto row_sums = [&](auto slot_c, auto row_c, float (&v)[4]) {
         float a[6];
@@ -1004,35 +1010,22 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     // The channels of this tile are split over KS workgroups: partial sums go to the workspace, the workgroup that
     // arrives last adds them up in the order of the splits (see tiled_body for the memory-ordering argument; the
     // accesses here are the same kind: device-scope buffer stores and loads, one relaxed device-scope atomic).
-    const size_t split_stride = (size_t)p.N * p.F * plane_out;
+    // The workspace is laid out like the registers: filter slot a of wave w of tile t has 4 KB at
+    // (t*FW*NF + w*NF + a)*4096 of the split's part, output row r of lane l at + 1024*r + 16*l (one 128-bit access
+    // per lane and row, 1 KB without gaps per instruction).
     constexpr int kDeviceScope = 16;   // cache-policy bit "sc1" of gfx942/gfx950 buffer instructions
-    auto ws_rsrc = [&](int s) { return make_rsrc(p.ws + (size_t)s * split_stride, (uint32_t)(split_stride * sizeof(float))); };
-    typedef unsigned v4u __attribute__((ext_vector_type(4)));
-    unsigned woff[4];            // vec: woff[0] is the offset of the lane's four partial sums of the row
-    auto ws_offsets = [&](unsigned f, int r) {
-        const int oy = oy0 + r;
-        const unsigned at = (((unsigned)n * p.F + f) * (unsigned)p.Ho + (unsigned)oy) * (unsigned)p.Wo;
-        if (p.vec) {
-            woff[0] = (active && oy < p.Ho) ? (at + (unsigned)o0) * 4u : kInvalidOffset;
-            return;
-        }
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const int ox = o0 + m;
-            woff[m] = (active && oy < p.Ho && ox >= 0 && ox < p.Wo) ? (at + (unsigned)ox) * 4u : kInvalidOffset;
-        }
+    auto ws_rsrc = [&](int s) {
+        return make_rsrc(reinterpret_cast<const char*>(p.ws) + (size_t)s * p.ws_split_bytes, p.ws_split_bytes);
+    };
+    auto ws_offset = [&](int a, int r) {
+        return (unsigned)((tile * FW + wave) * NF + a) * 4096u + 1024u * r + (unsigned)lane * 16u;
     };
     const __amdgpu_buffer_rsrc_t mine = ws_rsrc(split);
 #define PCONV_QPART(rc, r)                                                                          \
-    row_sums(slot_c, rc, v);                                                                        \
-    ws_offsets(filt[a], r);                                                                         \
-    if (p.vec) {                                                                                    \
-        const v4u q4 = {__builtin_bit_cast(unsigned, v[0]), __builtin_bit_cast(unsigned, v[1]),     \
-                        __builtin_bit_cast(unsigned, v[2]), __builtin_bit_cast(unsigned, v[3])};    \
-        __builtin_amdgcn_raw_buffer_store_b128(q4, mine, (int)woff[0], 0, kDeviceScope);            \
-    } else {                                                                                        \
-        _Pragma("unroll") for (int m = 0; m < 4; ++m)                                               \
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[m]), mine, (int)woff[m], 0, kDeviceScope); \
+    {                                                                                               \
+        row_sums(slot_c, rc, v);                                                                    \
+        const v4u q4 = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])}; \
+        __builtin_amdgcn_raw_buffer_store_b128(q4, mine, (int)ws_offset(a, r), 0, kDeviceScope);    \
     }
 #define PCONV_QPARTIAL(Sv)                                             \
     if (pos_base + Sv * FW < p.F) {                                    \
@@ -1058,7 +1051,22 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     if (*flag == 0u) return;
     // partial sums of up to four splits are requested together (this workgroup's own among them: its stores have
     // been performed), then added in split order
-#define PCONV_QRED_TAIL(r)                                                                          \
+#define PCONV_QRED(rc, r)                                                                           \
+    {                                                                                               \
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};                                                        \
+        for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
+            float part[4][4];                                                                       \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
+                if (s0 + j < p.KS) {            /* uniform: only the splits that exist */           \
+                    const v4u q4 = __builtin_amdgcn_raw_buffer_load_b128(ws_rsrc(s0 + j), (int)ws_offset(a, r), 0, kDeviceScope); \
+                    part[j][0] = bits_to_f32(q4[0]);                                                \
+                    part[j][1] = bits_to_f32(q4[1]);                                                \
+                    part[j][2] = bits_to_f32(q4[2]);                                                \
+                    part[j][3] = bits_to_f32(q4[3]);                                                \
+                } else {                                                                            \
+                    part[j][0] = part[j][1] = part[j][2] = part[j][3] = 0.f;                        \
+                }                                                                                   \
+            }                                                                                       \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
                 const int s = s0 + j;                                                               \
                 if (s < p.KS) {                                                                     \
@@ -1069,53 +1077,15 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
         }                                                                                           \
         store_row(sum, filt[a], filt_bias[a], r);                                                   \
     }
-#define PCONV_QRED(rc, r)                                                                           \
-    {                                                                                               \
-        ws_offsets(filt[a], r);                                                                     \
-        float sum[4] = {0.f, 0.f, 0.f, 0.f};                                                        \
-        for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
-            float part[4][4];                                                                       \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
-                if (s0 + j < p.KS) {            /* uniform: only the splits that exist */           \
-                    const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s0 + j);                          \
-                    _Pragma("unroll") for (int m = 0; m < 4; ++m)                                   \
-                        part[j][m] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(theirs, (int)woff[m], 0, kDeviceScope)); \
-                } else {                                                                            \
-                    _Pragma("unroll") for (int m = 0; m < 4; ++m) part[j][m] = 0.f;                 \
-                }                                                                                   \
-            }                                                                                       \
-    PCONV_QRED_TAIL(r)
-#define PCONV_QRED_VEC(rc, r)                                                                       \
-    {                                                                                               \
-        ws_offsets(filt[a], r);                                                                     \
-        float sum[4] = {0.f, 0.f, 0.f, 0.f};                                                        \
-        for (int s0 = 0; s0 < p.KS; s0 += 4) {                                                      \
-            float part[4][4];                                                                       \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                         \
-                if (s0 + j < p.KS) {            /* uniform: only the splits that exist */           \
-                    const __amdgpu_buffer_rsrc_t theirs = ws_rsrc(s0 + j);                          \
-                    const v4u q4 = __builtin_amdgcn_raw_buffer_load_b128(theirs, (int)woff[0], 0, kDeviceScope); \
-                    part[j][0] = bits_to_f32(q4[0]);                                                \
-                    part[j][1] = bits_to_f32(q4[1]);                                                \
-                    part[j][2] = bits_to_f32(q4[2]);                                                \
-                    part[j][3] = bits_to_f32(q4[3]);                                                \
-                } else {                                                                            \
-                    part[j][0] = part[j][1] = part[j][2] = part[j][3] = 0.f;                        \
-                }                                                                                   \
-            }                                                                                       \
-    PCONV_QRED_TAIL(r)
 #define PCONV_QREDUCE(Sv)                                              \
     if (pos_base + Sv * FW < p.F) {                                    \
         constexpr int a = Sv;                                          \
-        if (p.vec) PCONV_QROWS(PCONV_QRED_VEC)                         \
-        else PCONV_QROWS(PCONV_QRED)                                   \
+        PCONV_QROWS(PCONV_QRED)                                        \
     }
     if constexpr (NF > 0) { PCONV_QREDUCE(0) }
     if constexpr (NF > 1) { PCONV_QREDUCE(1) }
 #undef PCONV_QREDUCE
 #undef PCONV_QRED
-#undef PCONV_QRED_VEC
-#undef PCONV_QRED_TAIL
 #undef PCONV_QROWS
 }
 
@@ -1308,11 +1278,12 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
     p.ws = nullptr;
     p.counters = nullptr;
     if (KS > 1) {
-        const size_t floats = (size_t)KS * p.N * p.F * p.Ho * p.Wo;
-        // the kernel addresses one split's partial sums with 32-bit byte offsets below kInvalidOffset
-        if ((size_t)p.N * p.F * p.Ho * p.Wo >= ((size_t)1 << 29)) return PCONV_EUNSUPPORTED;
-        if (int rc = ensure_workspace(wp, floats, (size_t)slots * p.NG)) return rc;
+        // eight words per lane, filter slot and wave of every tile; one split's part is addressed with 32-bit offsets
+        const size_t split_bytes = (size_t)slots * p.NG * waves * NF * 64 * 8 * sizeof(float);
+        if (split_bytes >= kInvalidOffset) return PCONV_EUNSUPPORTED;
+        if (int rc = ensure_workspace(wp, (size_t)KS * split_bytes / sizeof(float), (size_t)slots * p.NG)) return rc;
         p.ws = wp->d_ws;
+        p.ws_split_bytes = (unsigned)split_bytes;
         p.counters = wp->d_counters;
     }
     // (filters per wave, channels per wave and chunk, buckets per chunk); waves = 16 * NB / CPW
@@ -1362,11 +1333,12 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
     p.ws = nullptr;
     p.counters = nullptr;
     if (KS > 1) {
-        // the kernel addresses one split's partial sums with 32-bit byte offsets below kInvalidOffset
-        const size_t outs = (size_t)p.N * p.F * p.Ho * p.Wo;
-        if (outs >= ((size_t)1 << 29)) return PCONV_EUNSUPPORTED;
-        if (int rc = ensure_workspace(wp, (size_t)KS * outs, (size_t)slots * p.NG)) return rc;
+        // 16 words per lane, filter slot and wave of every tile; one split's part is addressed with 32-bit offsets
+        const size_t split_bytes = (size_t)slots * p.NG * FW * NF * 64 * 16 * sizeof(float);
+        if (split_bytes >= kInvalidOffset) return PCONV_EUNSUPPORTED;
+        if (int rc = ensure_workspace(wp, (size_t)KS * split_bytes / sizeof(float), (size_t)slots * p.NG)) return rc;
         p.ws = wp->d_ws;
+        p.ws_split_bytes = (unsigned)split_bytes;
         p.counters = wp->d_counters;
     }
     // 32-bit byte offsets inside the buffer descriptor: the images one slot can span
@@ -1543,7 +1515,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
                 const double per_filter_chunk = (double)lay->n_kept / ((double)lay->F * nch);
                 for (int ks = 1; ks <= std::min(nch, 16); ks *= 2) {
                     // (the workspace of one split is addressed with 32-bit byte offsets)
-                    if (ks > 1 && (unsigned long long)N * lay->F * Ho * Wo >= (1ull << 29)) break;
+                    if (ks > 1 && (unsigned long long)tiles * w * nf * 2048 >= kInvalidOffset) break;
                     const double issue = (w / 4) * nf * per_filter_chunk * 128.0 + 750.0;
                     const double staging = std::min(lay->C, cc) * 9.0 * 18.0 * (pair ? 0.5 : 1.0);
                     const double chunk = std::max(issue, staging) + 3400.0;
