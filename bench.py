@@ -299,7 +299,7 @@ def chain_bench(args, torch, pc, L):
                 run(st)
             fn = g.replay
         _, ev = time_launches(torch, fn, 300, 30)
-    out = {"chain": "VGG-16, 13 conv layers + ReLU + 4 max-pools, batch 1, fp32 (config 2)", "mode": "graph" if args.graph
+    out = {"chain": "VGG-16, 13 conv layers + ReLU + 5 max-pools, batch 1, fp32 (config 2)", "mode": "graph" if args.graph
            else "eager", "us_per_chain": ev * 1e3, "eff_GMACs": macs / ev / 1e6, "kernels_per_chain": 13 + sum(
                1 for q in pooled if q is not None)}
     log(" ".join(f"{k}={v:.4g}" if isinstance(v, float) else f"{k}={v}" for k, v in out.items()))
