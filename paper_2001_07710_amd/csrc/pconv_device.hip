@@ -375,15 +375,20 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     const int ix = ox + 1 - p.pad;
     const int r0 = rb * R;
 
+    // Byte offset of the lane's element in each of its R + 2 input rows, or an offset outside the descriptor.
+    // PAIR: (iy, ix) index a parity plane; the load reads row 2*iy (+ the wave's row parity) and columns 2*ix,
+    // 2*ix+1 of the original image, whose rows are 2*W long.
     unsigned voff[R + 2];
+    {
+        const bool col_in = active && ix >= 0 && ix < p.W;
+        const int iy0 = r0 - p.pad;
+        const unsigned row_bytes = (PAIR ? 4u : 1u) * (unsigned)p.W * (unsigned)sizeof(T);
+        // (modulo 2^32: for rows above the image the product is negative and the offset is not used)
+        const unsigned first = (unsigned)(n - n0) * p.img_bytes +
+                               (unsigned)(PAIR ? 4 * iy0 * p.W + 2 * ix : iy0 * p.W + ix) * (unsigned)sizeof(T);
 #pragma unroll
-    for (int i = 0; i < R + 2; ++i) {
-        const int iy = r0 + i - p.pad;
-        const bool ok = active && iy >= 0 && iy < p.H && ix >= 0 && ix < p.W;
-        // PAIR: (iy, ix) index a parity plane; the load reads row 2*iy (+ the wave's row parity) and columns 2*ix,
-        // 2*ix+1 of the original image, whose rows are 2*W long
-        const unsigned elem = PAIR ? (unsigned)(4 * iy * p.W + 2 * ix) : (unsigned)(iy * p.W + ix);
-        voff[i] = ok ? (unsigned)(n - n0) * p.img_bytes + elem * (unsigned)sizeof(T) : kInvalidOffset;
+        for (int i = 0; i < R + 2; ++i)
+            voff[i] = (col_in && (unsigned)(iy0 + i) < (unsigned)p.H) ? first + (unsigned)i * row_bytes : kInvalidOffset;
     }
     const unsigned long long base_off = (unsigned long long)n0 * p.img_bytes;
     const unsigned long long left = p.x_bytes - base_off;
@@ -391,21 +396,24 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
         make_rsrc(static_cast<const char*>(p.x) + base_off, (uint32_t)(left < 0x7FFFFFFFull ? left : 0x7FFFFFFFull));
 
     const unsigned lane_addr = lds0 + lane * (kPR * 4);
-    if constexpr (NF > 0) zero_acc<0>();
-    if constexpr (NF > 1) zero_acc<1>();
 
     const int pos_base = grp * (FW * NF) + wave;   // wave w takes positions pos_base + a*FW in the sorted filter order
-    // the wave's filters and their biases, fetched now (scalar registers) so that the epilogue does not wait for them
+    // What the first loads do not need is done behind them, while they are in flight: clearing the accumulators and
+    // fetching the wave's filters and their biases (scalar registers, so that the epilogue does not wait for them).
     unsigned filt[NF];
     float filt_bias[NF];
+    auto behind_first_loads = [&]() {
+        if constexpr (NF > 0) zero_acc<0>();
+        if constexpr (NF > 1) zero_acc<1>();
 #pragma unroll
-    for (int a = 0; a < NF; ++a) {
-        const int pos = pos_base + a * FW;
-        filt[a] = pos < p.F ? scalar_load_u32(p.forder + pos) : 0u;
-        filt_bias[a] = (p.bias && pos < p.F)
-                           ? __builtin_bit_cast(float, scalar_load_u32(reinterpret_cast<const uint32_t*>(p.bias + filt[a])))
-                           : 0.f;
-    }
+        for (int a = 0; a < NF; ++a) {
+            const int pos = pos_base + a * FW;
+            filt[a] = pos < p.F ? scalar_load_u32(p.forder + pos) : 0u;
+            filt_bias[a] = (p.bias && pos < p.F)
+                               ? __builtin_bit_cast(float, scalar_load_u32(reinterpret_cast<const uint32_t*>(p.bias + filt[a])))
+                               : 0.f;
+        }
+    };
     const int nchunks = p.perm ? p.nbk : (p.C + CC - 1) / CC;
     // this workgroup's range of chunks (all of them unless the channels are split)
     const int k_begin = (int)fastdiv((unsigned)(split * nchunks), p.div_KS);   // split, nchunks < 65536
@@ -495,6 +503,7 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     unsigned cnt_now[NF];
     if constexpr (!DB) {
         issue_loads(k_begin);
+        behind_first_loads();
         write_lds(0);
         __syncthreads();
         for (int k = k_begin; k < k_end; ++k) {
@@ -515,6 +524,7 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
         // barrier), and the loads of k+2 are issued right after, so their latency runs beside the multiply-adds.
         unsigned cnt_next[NF];
         issue_loads(k_begin);
+        behind_first_loads();
         write_lds(0);
 #pragma unroll
         for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
