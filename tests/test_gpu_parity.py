@@ -112,6 +112,17 @@ def test_no_bias_negative_inputs_and_empty_filters():
     y = layer0.run(x)
     assert np.array_equal(y, np.broadcast_to(layer0.bias[None, :, None, None], y.shape))
     layer0.free()
+    # ... with every kernel (the quad kernel needs a width that is a multiple of four)
+    spec1 = L.LayerSpec(cfg=11, idx=2, name="nothing", N=3, C=40, F=24, H=10, W=16, K=8, keep=0.0)
+    layer1 = GpuLayer(spec1)
+    assert layer1.mask.sum() == 0
+    x1 = L.gen_activations(spec1)
+    for t in (dict(kernel=pc.KERNEL_QUAD), dict(kernel=pc.KERNEL_QUAD, filters_per_wave=1, channel_splits=2),
+              dict(kernel=T, channel_splits=2), dict(kernel=G)):
+        say(spec1.name, t)
+        y1 = layer1.run(x1, **t)
+        assert np.array_equal(y1, np.broadcast_to(layer1.bias[None, :, None, None], y1.shape)), t
+    layer1.free()
 
 
 def test_batch_zero_is_a_no_op_and_runs_are_deterministic():
@@ -121,6 +132,9 @@ def test_batch_zero_is_a_no_op_and_runs_are_deterministic():
     a = layer.run(x)
     b = layer.run(x)
     assert a.tobytes() == b.tobytes()
+    # also with channels split over workgroups (the partial sums are added in a fixed order), in both kernels
+    for t in (dict(kernel=T, channel_splits=2), dict(kernel=pc.KERNEL_QUAD, channel_splits=2)):
+        assert layer.run(x, **t).tobytes() == layer.run(x, **t).tobytes(), t
     import torch
     dummy = torch.zeros(4, device="cuda")
     pc.conv3x3(dummy, dummy, layer.packed, None, 0, 28, 28)
