@@ -253,7 +253,7 @@ struct TiledParams {
     int LW, S, OWS, NCS, NRB, NSEG;
     int NG;                  // filter groups per slot
     int KS;                  // workgroups that share one output tile, each taking a range of the channel chunks
-    float* ws;               // KS > 1: partial sums [KS][tiles][waves][NF][64 lanes][8]: a lane's output rows, as held
+    float* ws;               // KS > 1: partial sums [KS][tiles][waves][NF][2][64 lanes][4]: a lane's output rows, as held
     unsigned ws_split_bytes; //         size of one split's partial sums
     unsigned* counters;      // KS > 1: [slots * NG] arrivals, zero between launches
     int nblocks;             // NG * slots * KS (the grid is padded to a multiple of 8)
@@ -717,7 +717,7 @@ struct QuadParams {
     int KS;                  // workgroups per output tile (each takes a range of the chunks)
     int vec;                 // a lane's four outputs of a row are in range together and 16-byte aligned (pad 1, aligned y)
     int nblocks;             // NG * slots * KS (the grid is padded to a multiple of 8)
-    float* ws;               // KS > 1: partial sums [KS][tiles][16 waves][NF][64 lanes][16]: a lane's outputs, as held
+    float* ws;               // KS > 1: partial sums [KS][tiles][16 waves][NF][4 rows][64 lanes][4]: a lane's outputs, as held
     unsigned ws_split_bytes; //         size of one split's partial sums
     unsigned* counters;      // KS > 1: one arrival counter per tile, zero between launches
     unsigned long long x_bytes;
