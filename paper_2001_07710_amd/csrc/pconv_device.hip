@@ -160,24 +160,23 @@ template <>
 __device__ __forceinline__ unsigned buffer_load_raw<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
     return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
 }
-// Two neighbouring elements (an even and the following odd column) in one load.
+// Two neighbouring elements (an even and the following odd column) in one load, as stored: two registers for fp32,
+// the two halves of `a` for fp16 (`b` is not written).  pair_to_f32 takes them apart, later, for the same reason.
 template <typename T>
-__device__ __forceinline__ void buffer_load_raw2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, unsigned& even,
-                                                 unsigned& odd);
+__device__ __forceinline__ void buffer_load_raw2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, unsigned& a,
+                                                 unsigned& b);
 template <>
 __device__ __forceinline__ void buffer_load_raw2<float>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff,
-                                                        unsigned& even, unsigned& odd) {
+                                                        unsigned& a, unsigned& b) {
     typedef unsigned v2u __attribute__((ext_vector_type(2)));
     const v2u v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
-    even = v.x;
-    odd = v.y;
+    a = v.x;
+    b = v.y;
 }
 template <>
 __device__ __forceinline__ void buffer_load_raw2<__half>(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff,
-                                                         unsigned& even, unsigned& odd) {
-    const unsigned v = __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
-    even = v & 0xFFFFu;
-    odd = v >> 16;
+                                                         unsigned& a, unsigned&) {
+    a = __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
 }
 template <typename T>
 __device__ __forceinline__ float raw_to_f32(unsigned bits);
@@ -186,6 +185,17 @@ __device__ __forceinline__ float raw_to_f32<float>(unsigned bits) { return __bui
 template <>
 __device__ __forceinline__ float raw_to_f32<__half>(unsigned bits) {
     return __half2float(__builtin_bit_cast(__half, (unsigned short)bits));
+}
+// element `odd` (0: the even column, 1: the odd one) of what buffer_load_raw2 left in (a, b)
+template <typename T>
+__device__ __forceinline__ float pair_to_f32(unsigned a, unsigned b, int odd);
+template <>
+__device__ __forceinline__ float pair_to_f32<float>(unsigned a, unsigned b, int odd) {
+    return __builtin_bit_cast(float, odd ? b : a);
+}
+template <>
+__device__ __forceinline__ float pair_to_f32<__half>(unsigned a, unsigned, int odd) {
+    return raw_to_f32<__half>(odd ? a >> 16 : a & 0xFFFFu);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -420,6 +430,10 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     const int k_end = (int)fastdiv((unsigned)((split + 1) * nchunks), p.div_KS);
 
     unsigned pre[CPW][R + 2];    // the wave's share of the next chunk's activations, in flight, as stored
+    if constexpr (PAIR && sizeof(T) == 2) {   // a paired fp16 load fills pre[0] only
+#pragma unroll
+        for (int i = 0; i < R + 2; ++i) pre[1][i] = 0u;
+    }
     uint2 epre[NF][NB];          // ... and of the next chunk's entries (lane l holds dwords 2l, 2l+1 of 16 entries)
     unsigned ecnt[NF];           // entries of each of the wave's filters in the chunk that is staged or in flight
 
@@ -478,7 +492,10 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
                 float* dst = reinterpret_cast<float*>(lds + buf * kTileBytes + cc * kChBytes + lane * (kPR * 4));
                 float v[R + 2];
 #pragma unroll
-                for (int i = 0; i < R + 2; ++i) v[i] = (PAIR && i > R) ? 0.f : raw_to_f32<T>(pre[j][i]);
+                for (int i = 0; i < R + 2; ++i) {
+                    if constexpr (PAIR) v[i] = i > R ? 0.f : pair_to_f32<T>(pre[0][i], pre[1][i], j);
+                    else v[i] = raw_to_f32<T>(pre[j][i]);
+                }
                 *reinterpret_cast<float4*>(dst + 0) = make_float4(v[0], v[1], v[2], v[3]);
                 *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
                 if constexpr (!PAIR) *reinterpret_cast<float4*>(dst + 8) = make_float4(v[8], 0.f, 0.f, 0.f);

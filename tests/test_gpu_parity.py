@@ -432,6 +432,52 @@ def test_config4_full_batch(name):
     layer.free()
 
 
+@pytest.mark.parametrize("stride", [1, 2])
+def test_input_and_output_beyond_4_gib(stride):
+    """2800 images of 64 x 112 x 112 in fp16: x is 4.5 GB and so is y at stride 1, so element offsets pass 2^31 and
+    byte offsets 2^32 (stride 2: in x only).  The batch repeats four generated images (copied on the device), every output image is compared on the
+    device with the first of its kind, and the first four, the last four and the four around the 4 GiB mark with
+    the oracle."""
+    import torch
+    N, reps = 2800, 700
+    spec = L.shrink([s for s in L.config4(8, 0.28, N=4) if s.name == "conv1_2"][0], H=112, W=112, stride=stride)
+    layer = GpuLayer(spec)
+    x4 = L.gen_activations(spec)
+    ref4 = layer.oracle(x4)
+    per_img = spec.F * spec.Ho * spec.Wo
+    assert (N * per_img * 2 > 1 << 32 or stride == 2) and N * spec.C * spec.H * spec.W * 2 > 1 << 32
+    dx = torch.from_numpy(x4).cuda().repeat(reps, 1, 1, 1).contiguous()
+    assert dx.shape[0] == N
+    pad = 4096
+    buf = torch.empty(N * per_img + 2 * pad, dtype=torch.float16, device="cuda")
+    dy = buf[pad:pad + N * per_img]
+    st = torch.cuda.current_stream().cuda_stream
+    mark = (1 << 32) // (spec.C * spec.H * spec.W * 2)      # the image in which byte 2^32 of x falls (y: stride 1)
+    first = mark - mark % 4
+    tol = TOL["f16"]
+    tunings = [dict(), dict(kernel=pc.KERNEL_QUAD, filters_per_wave=1), dict(kernel=T), dict(kernel=G)]
+    if stride == 2:    # paired staging (automatic), the separate pass that splits x into parity planes, generic
+        tunings = [dict(), dict(kernel=T, rows=7, filters_per_wave=1, waves=8, channels_per_wave=4), dict(kernel=G)]
+    for t in tunings:
+        say(spec.name, "112x112 stride", stride, "batch", N, "tuning", t)
+        buf.fill_(-777.0)
+        if t:
+            pc.conv3x3_tuned(dx, dy, layer.packed, layer.d_bias, N, spec.H, spec.W, stride, 1, 0, st, **t)
+        else:
+            pc.conv3x3(dx, dy, layer.packed, layer.d_bias, N, spec.H, spec.W, stride, 1, 0, st)
+        torch.cuda.synchronize()
+        assert bool((buf[:pad] == -777.0).all()) and bool((buf[pad + N * per_img:] == -777.0).all())
+        got = dy.view(reps, 4, spec.F, spec.Ho, spec.Wo)
+        for r0 in range(0, reps, 100):           # in slices: the comparison's temporaries stay small
+            assert bool((got[r0:r0 + 100] == got[0:1]).all()), (t, r0)
+        for n0 in (0, first, N - 4):
+            g = dy.view(N, spec.F, spec.Ho, spec.Wo)[n0:n0 + 4].cpu().numpy()
+            assert rel_err(g, ref4) <= tol, (t, n0)
+    del dx, buf, dy
+    torch.cuda.empty_cache()
+    layer.free()
+
+
 # ------------------------------------------------------------------------------------------------------------------
 # the comparison kernels: dense 3x3 baseline and max-pool
 # ------------------------------------------------------------------------------------------------------------------
