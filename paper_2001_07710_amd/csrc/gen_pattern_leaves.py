@@ -25,7 +25,7 @@ to the chunk size, so these reads stay inside the workgroup's LDS whatever the b
 
 Registers.  Accumulators: 3*R registers per filter slot, fixed, ending at v127 (slot s of a kernel with NF slots
 starts at v[128 - 3*R*(s+1)]); the kernel limits the compiler's own budget so that it never allocates them.  Scratch
-registers of the loop (activations x0..x9 and weights of both sets, header, addresses) are fixed too, directly below
+registers of the loop (activations x0..x8 and weights of both sets, header pair, addresses) are fixed too, directly below
 the accumulators of the last slot; they are listed as clobbered, so the compiler keeps nothing there across the
 block.  Scalar scratch: s[58:66].
 """
@@ -53,37 +53,35 @@ class Regs:
 
     def __init__(self, nf: int):
         low = acc_base(nf - 1)
-        xa = (low - 10) & ~1            # x0..x9 (x9 is never read); register tuples start at even registers
-        self.x = (xa, xa - 10)
+        xa = (low - 10) & ~1            # register tuples start at even registers
+        self.x = (xa, xa - 10)          # x0..x8 of each set; the tenth register of each block of ten holds an address
+        self.va = xa + 9                # LDS address of the activations
+        self.ve = xa - 1                # LDS address of the next entry
         self.w = (xa - 14, xa - 18)     # w0..w3 of each set
-        self.m = xa - 19                # header of the entry after the next
-        self.va = xa - 20               # LDS address of the activations
-        self.ve = xa - 21               # LDS address of the next entry
-        self.first = self.ve
+        self.m = xa - 20                # header of the entry after the next: section offset, channel offset (even pair)
+        self.first = self.m
         self.count = low - self.first
 
 
 def request_next(rg: Regs, q: int, rows8: bool = False) -> list:
-    """The header of the next entry is in v[m]: request that entry's activations and weights into set q and the
-    header of the entry after it.  Leaves the next entry's section offset in s65.  rows8: the layer's kernels only
-    have taps in their first two rows (a stride-2 layer over parity planes), so patch rows 8 and 9 are never read
-    and are not fetched."""
+    """The header of the next entry is in v[m:m+1] — the byte offset of its code section in a table and the byte
+    offset of its channel in the LDS tile, as the kernel wrote them when it staged the entries: request that entry's
+    activations and weights into set q and the header of the entry after it.  Leaves the next entry's section offset
+    in s65.  rows8: the layer's kernels only have taps in their first two rows (a stride-2 layer over parity planes),
+    so patch row 8 is never read and is not fetched."""
     x, w = rg.x[q], rg.w[q]
     lines = [
         f"v_readfirstlane_b32 s65, v{rg.m}",
-        "s_and_b32 s64, s65, %[ccmask]",
-        f"s_mul_i32 s64, s64, {CH_BYTES}",
-        f"v_add_u32 v{rg.va}, s64, %[vlane]",
+        f"v_add_u32 v{rg.va}, v{rg.m + 1}, %[vlane]",
         f"ds_read_b128 v[{x}:{x + 3}], v{rg.va}",
         f"ds_read_b128 v[{x + 4}:{x + 7}], v{rg.va} offset:16",
-        f"ds_read_b64 v[{x + 8}:{x + 9}], v{rg.va} offset:32",
+        f"ds_read_b32 v{x + 8}, v{rg.va} offset:32",
         f"ds_read_b128 v[{w}:{w + 3}], v{rg.ve}",
-        f"ds_read_b32 v{rg.m}, v{rg.ve} offset:48",
+        f"ds_read_b64 v[{rg.m}:{rg.m + 1}], v{rg.ve} offset:48",
         f"v_add_u32 v{rg.ve}, 32, v{rg.ve}",
-        "s_and_b32 s65, s65, 0xffffff00",
     ]
     if rows8:
-        lines = [l for l in lines if not l.startswith("ds_read_b64")]
+        lines = [l for l in lines if not l.startswith(f"ds_read_b32 v{x + 8},")]
     return lines
 
 
@@ -102,7 +100,6 @@ def entry_loop(nf: int, slot: int, rows8: bool = False) -> list:
     ms = masks()
     table_b = (len(ms) + 1) << LEAF_ALIGN_LOG2          # the exit stub sits between the two tables
     lines = [
-        "s_sub_u32 s66, %[cnt], 1",                    # entries still to run after the current one
         f"v_mov_b32 v{rg.ve}, %[ventry]",
         "s_getpc_b64 s[60:61]",
         "1:",
@@ -110,7 +107,7 @@ def entry_loop(nf: int, slot: int, rows8: bool = False) -> list:
         "s_addc_u32 s61, s61, 0",
         f"s_add_u32 s58, s60, {table_b}",              # s[58:59]: sections of set B
         "s_addc_u32 s59, s61, 0",
-        f"ds_read_b32 v{rg.m}, v{rg.ve} offset:16",
+        f"ds_read_b64 v[{rg.m}:{rg.m + 1}], v{rg.ve} offset:16",
         "s_waitcnt lgkmcnt(0)",
     ] + request_next(rg, 0, rows8) + jump(0)
     for p in (0, 1):
@@ -129,13 +126,12 @@ def entry_loop(nf: int, slot: int, rows8: bool = False) -> list:
                     for r in range(R):
                         lines.append(f"v_fmac_f32 v{base + kx * R + r}, v{rg.w[p] + q}, v{rg.x[p] + r + ky}")
                     q += 1
-            lines += [
-                "s_sub_u32 s66, s66, 1",               # borrow: this was the last entry
-                "s_cbranch_scc1 9f" if p == 0 else "s_cbranch_scc1 9b",   # the exit stub sits behind the sections of set A
-            ] + jump(1 - p)
+            lines += jump(1 - p)
         if p == 0:
-            lines += [f".p2align {LEAF_ALIGN_LOG2}", "9:", "s_waitcnt lgkmcnt(0)", "s_branch 8f"]
-    lines += [f".p2align {LEAF_ALIGN_LOG2}", "8:"]
+            # slot EXIT_CODE of table A: where the header behind a filter's last entry sends a section of set B
+            lines += [f".p2align {LEAF_ALIGN_LOG2}", "s_waitcnt lgkmcnt(0)", "s_branch 8f"]
+    # slot EXIT_CODE of table B is the end of the block (the fetches for the entry that is not there must land first)
+    lines += [f".p2align {LEAF_ALIGN_LOG2}", "8:", "s_waitcnt lgkmcnt(0)"]
     return lines
 
 
@@ -246,13 +242,15 @@ def as_c_string(lines: list) -> str:
 def clobbers(nf: int, slot: int) -> str:
     rg = Regs(nf)
     regs = [f'"v{rg.first + i}"' for i in range(rg.count)] + [f'"v{acc_base(slot) + i}"' for i in range(3 * R)]
-    regs += [f'"s{i}"' for i in range(58, 67)] + ['"scc"']
+    regs += [f'"s{i}"' for i in range(58, 66)] + ['"scc"']
     return ", ".join(regs)
 
 
 def main(out_path: str):
     out = ["// Generated by gen_pattern_leaves.py -- do not edit.", "",
-           f"#define PCONV_LEAF_STRIDE {1 << LEAF_ALIGN_LOG2}   // bytes between the code sections of two patterns", ""]
+           f"#define PCONV_LEAF_STRIDE {1 << LEAF_ALIGN_LOG2}   // bytes between the code sections of two patterns",
+           f"#define PCONV_EXIT_CODE {len(masks())}   // section slot behind the last mask: leaves the entry loop",
+           f"#define PCONV_CH_BYTES {CH_BYTES}", ""]
     for s in range(3):
         b = acc_base(s)
         out.append(f"#define PCONV_ACC_BASE_S{s} {b}")

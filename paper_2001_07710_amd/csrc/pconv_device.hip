@@ -298,6 +298,18 @@ __device__ __forceinline__ void zero_acc() {
     else asm volatile(PCONV_ACC_ZERO_S2 : : : PCONV_ACC_CLOBBERS_S2);
 }
 
+// An entry on its way from memory to LDS.  A lane holds dwords 2l, 2l+1 of an entry's eight (l = lane % 4); the lane
+// with the header (dword 4: channel index in its low byte, pattern code above) turns it into what the entry loop
+// uses as it is: the byte offset of the pattern's code section in a table of sections `leaf_stride` apart, and the
+// byte offset of the channel in the staged chunk of CC channels of `ch_bytes` each.
+template <int CC>
+__device__ __forceinline__ uint2 staged_entry(uint2 e, int lane, unsigned leaf_stride, unsigned ch_bytes) {
+    if ((lane & 3) == 2) return make_uint2((e.x >> 8) * leaf_stride, (e.x & (unsigned)(CC - 1)) * ch_bytes);
+    return e;
+}
+// What stands behind a filter's last entry of a chunk: a header that leads out of the entry loop.
+__device__ __forceinline__ uint2 end_marker(unsigned leaf_stride) { return make_uint2(PCONV_EXIT_CODE * leaf_stride, 0u); }
+
 template <int SLOT>
 __device__ __forceinline__ void read_acc(float (&a)[3][kR]) {
 #define PCONV_ACC_OUTPUTS                                                                                           \
@@ -310,17 +322,17 @@ __device__ __forceinline__ void read_acc(float (&a)[3][kR]) {
 #undef PCONV_ACC_OUTPUTS
 }
 
-// Runs `count` (>= 1) entries stored in LDS from byte address `entry_addr` on, for the filter in slot SLOT of a
-// kernel with NF slots.  `lane_addr` is the LDS byte address of this lane's patch of channel 0 of the chunk.
+// Runs the entries stored in LDS from byte address `entry_addr` on (at least one), up to the end marker behind the
+// last one, for the filter in slot SLOT of a kernel with NF slots.  `lane_addr` is the LDS byte address of this
+// lane's patch of channel 0 of the chunk.  The entries are in the form staged_entry() gives them.
 // ROWS8: the loop variant for layers whose kernels have no tap in their third row (a stride-2 layer over parity
-// planes): patch rows 8 and 9 are not fetched.
-template <int NF, int SLOT, int CC, bool ROWS8>
-__device__ __forceinline__ void run_entries(unsigned lane_addr, unsigned entry_addr, unsigned count) {
-    const unsigned cnt = __builtin_amdgcn_readfirstlane(count);
+// planes): patch row 8 is not fetched.
+template <int NF, int SLOT, bool ROWS8>
+__device__ __forceinline__ void run_entries(unsigned lane_addr, unsigned entry_addr) {
 #define PCONV_LOOP_ASM(TEXT, NFv, Sv)                                                           \
     asm volatile(TEXT                                                                           \
                  :                                                                              \
-                 : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr), [cnt] "s"(cnt), [ccmask] "n"(CC - 1) \
+                 : [vlane] "v"(lane_addr), [ventry] "v"(entry_addr)                             \
                  : "memory", PCONV_ENTRY_LOOP_CLOBBERS_NF##NFv##_S##Sv)
 #define PCONV_LOOP(NFv, Sv)                                                                     \
     do {                                                                                        \
@@ -501,20 +513,22 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
                 if constexpr (!PAIR) *reinterpret_cast<float4*>(dst + 8) = make_float4(v[8], 0.f, 0.f, 0.f);
             }
         }
-        // entries, as they are
+        // entries, and the end marker behind the last (at most CC entries; the region has room for CC + 2)
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
             uint2* dst = reinterpret_cast<uint2*>(lds + kEntBase + buf * kEntBytes + (wave * NF + a) * kEntRegion);
 #pragma unroll
             for (int j = 0; j < NB; ++j)
-                if ((unsigned)(lane >> 2) + 16u * j < ecnt[a]) dst[lane + 64 * j] = epre[a][j];
+                if ((unsigned)(lane >> 2) + 16u * j < ecnt[a])
+                    dst[lane + 64 * j] = staged_entry<CC>(epre[a][j], lane, PCONV_LEAF_STRIDE, kChBytes);
+            if (lane == 0) dst[ecnt[a] * 4u + 2u] = end_marker(PCONV_LEAF_STRIDE);
         }
     };
     auto compute = [&](int buf, const unsigned (&cnt)[NF]) {
         const unsigned tile_addr = lane_addr + buf * kTileBytes;
         const unsigned ent_addr = lds0 + kEntBase + buf * kEntBytes + wave * NF * kEntRegion;
-        if constexpr (NF > 0) { if (cnt[0]) run_entries<NF, 0, CC, PAIR>(tile_addr, ent_addr + 0 * kEntRegion, cnt[0]); }
-        if constexpr (NF > 1) { if (cnt[1]) run_entries<NF, 1, CC, PAIR>(tile_addr, ent_addr + 1 * kEntRegion, cnt[1]); }
+        if constexpr (NF > 0) { if (cnt[0]) run_entries<NF, 0, PAIR>(tile_addr, ent_addr + 0 * kEntRegion); }
+        if constexpr (NF > 1) { if (cnt[1]) run_entries<NF, 1, PAIR>(tile_addr, ent_addr + 1 * kEntRegion); }
     };
 
     unsigned cnt_now[NF];
