@@ -754,6 +754,10 @@ struct QuadParams {
     unsigned long long x_bytes;
     unsigned img_bytes, plane_bytes;
     unsigned ent_bytes;      // size of ent[] (below 2^31: the kernel reads it through a buffer descriptor)
+    int walkers;             // quad_walk_kernel: workgroups per filter group; one walks slots w, w + walkers, ...
+    int slots;               //                   slots in all
+    unsigned out_img_bytes;  //                   F*Ho*Wo*sizeof(T)
+    unsigned long long y_bytes;
     FastDiv div_NG, div_KS, div_QW, div_NRB;
 };
 
@@ -1130,6 +1134,186 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
 #undef PCONV_QROWS
 }
 
+// The quad kernel for layers whose input channels fit one chunk (a network's first layer) and that have many slots:
+// an ordinary workgroup would load three channels, do three kept kernels per wave and store, one dependent step after
+// the other and all of it start-up.  Here a workgroup keeps its 16 filters (one per wave) and their entries in LDS
+// and walks over the slots w, w + walkers, ...; the loads of the next slot are in flight while the current one is
+// multiplied and stored.  Loads and stores are unconditional (lanes with nothing to do use an offset outside the
+// descriptor): the wait for a slot's loads must not include the stores issued behind them, and the compiler can
+// only count those when no branch surrounds them.  Needs pad 1 and a 16-byte aligned y (one store per lane and row).
+template <typename T>
+__device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
+    constexpr int R = PCONV_QUAD_ROWS, FW = 16, CC = 16;
+    constexpr unsigned kChB = PCONV_QUAD_CH_BYTES;
+    constexpr unsigned kRowB = 64 * 16;
+    constexpr unsigned kEntRegion = (CC + 2) * 32;
+    constexpr unsigned kEntBase = CC * kChB;
+    extern __shared__ __align__(16) unsigned char lds[];     // as in quad_body
+    const unsigned lds0 = (unsigned)(unsigned long long)lds;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    const int per_xcd = gridDim.x >> 3;   // the filter groups of one walker read the same slots: same XCD, same L2
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= p.nblocks) return;
+    const int walker = (int)fastdiv((unsigned)logical, p.div_NG);
+    const int grp = logical - walker * p.NG;
+
+    struct LanePlace { int q, n, n0, oy0; bool active; };
+    auto place_of = [&](int ln, int slot) {
+        LanePlace r;
+        const int g0 = slot * p.BL;                     // first row block of the slot (uniform)
+        r.n0 = (int)fastdiv((unsigned)g0, p.div_NRB);
+        const int b = (int)fastdiv((unsigned)ln, p.div_QW);
+        r.q = ln - b * p.QW;
+        r.active = b < p.BL && g0 + b < p.NBLK;
+        const int g = r.active ? g0 + b : g0;
+        r.n = (int)fastdiv((unsigned)g, p.div_NRB);
+        r.oy0 = (g - r.n * p.NRB) * R;
+        return r;
+    };
+
+    // the wave's filter, its entries (staged once) and its channel of the one chunk
+    const int pos = grp * FW + wave;
+    const bool has_filter = pos < p.F;
+    unsigned e0 = 0, e1 = 0;
+    if (has_filter) {
+        e0 = scalar_load_u32(p.eptr + pos * p.nbk);
+        e1 = scalar_load_u32(p.eptr + pos * p.nbk + 1);
+    }
+    const unsigned c = p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + wave) : (unsigned)wave;
+    const unsigned filt = has_filter ? scalar_load_u32(p.forder + pos) : 0u;
+    const float filt_bias =
+        (p.bias && has_filter) ? __builtin_bit_cast(float, scalar_load_u32(reinterpret_cast<const uint32_t*>(p.bias + filt)))
+                               : 0.f;
+    const unsigned cnt = __builtin_amdgcn_readfirstlane(e1 - e0);
+    {
+        const __amdgpu_buffer_rsrc_t ent_rsrc = make_rsrc(p.ent, p.ent_bytes);
+        const unsigned eoff = (unsigned)(lane >> 2) < cnt ? e0 * 32u + (unsigned)lane * 8u : kInvalidOffset;
+        typedef unsigned v2u __attribute__((ext_vector_type(2)));
+        const v2u e = __builtin_amdgcn_raw_buffer_load_b64(ent_rsrc, (int)eoff, 0, 0);
+        static_assert(kEntRegion >= 64 * 8, "entry region smaller than one wave's write");
+        reinterpret_cast<uint2*>(lds + kEntBase + wave * kEntRegion)[lane] = make_uint2(e[0], e[1]);
+    }
+    const bool staged = c < (unsigned)p.C;
+    const unsigned soff = staged ? c * p.plane_bytes : 0u;
+    const unsigned lane_addr = lds0 + lane * 16;
+    const unsigned ent_addr = lds0 + kEntBase + wave * kEntRegion;
+
+    RawQuad<T> pre[R + 2];
+    // (`wanted` and `staged` are the same for the whole wave; they reach the offsets through a vector register the
+    // compiler knows nothing about, or it splits the six loads over branches, with a wait in front of each.)
+    auto issue_loads = [&](int slot, bool wanted) {
+        int fetch = (wanted && staged) ? 1 : 0;
+        asm volatile("" : "+v"(fetch));
+        const LanePlace pl = place_of(lane, slot);
+        const unsigned long long base_off = (unsigned long long)pl.n0 * p.img_bytes;
+        const unsigned long long left = p.x_bytes - base_off;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            make_rsrc(static_cast<const char*>(p.x) + base_off, (uint32_t)(left < 0x7FFFFFFFull ? left : 0x7FFFFFFFull));
+#pragma unroll
+        for (int i = 0; i < R + 2; ++i) {
+            const int iy = pl.oy0 - p.pad + i;
+            const bool ok = fetch != 0 && pl.active && iy >= 0 && iy < p.H;
+            const unsigned voff = ok ? (unsigned)(pl.n - pl.n0) * p.img_bytes +
+                                           (unsigned)(iy * p.W + 4 * pl.q) * (unsigned)sizeof(T)
+                                     : kInvalidOffset;
+            pre[i].load(rsrc, voff, soff);
+        }
+    };
+
+    int slot = walker;                 // walker < walkers <= slots
+    issue_loads(slot, true);
+    {
+        // Four stores that store nothing (their offset is outside the descriptor), so that the loop is entered the
+        // way it is re-entered: six loads with four stores behind them.  The compiler's count of what may still be
+        // pending at the top of the loop is the merge of both ways in, and without these it waits for the stores of
+        // the slot before along with the loads.
+        const __amdgpu_buffer_rsrc_t none = make_rsrc(p.y, 0u);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if constexpr (sizeof(T) == 4) {
+                v4u z = {0u, 0u, 0u, 0u};
+                __builtin_amdgcn_raw_buffer_store_b128(z, none, (int)(kInvalidOffset + 16u * r), 0, 0);   // (four different ones)
+            } else {
+                typedef unsigned v2u __attribute__((ext_vector_type(2)));
+                v2u z = {0u, 0u};
+                __builtin_amdgcn_raw_buffer_store_b64(z, none, (int)(kInvalidOffset + 16u * r), 0, 0);
+            }
+        }
+    }
+    for (;;) {
+        float4* dst = reinterpret_cast<float4*>(lds + wave * kChB + lane * 16);
+#pragma unroll
+        for (int i = 0; i < R + 2; ++i) dst[i * (kRowB / 16)] = pre[i].widen();
+        __syncthreads();
+        const int next = slot + p.walkers;
+        const bool more = next < p.slots;
+        issue_loads(more ? next : slot, more);
+        quad_zero_acc<0>();
+        if (cnt) quad_run_entries<1, 0, CC>(lane_addr, ent_addr, cnt);
+
+        // the slot's outputs: accumulator columns 0 and 5 go to the neighbouring quads; bias, ReLU, store
+        int lane_again = lane;
+        asm volatile("" : "+v"(lane_again));
+        const LanePlace pl = place_of(lane_again, slot);
+        const bool has_left = pl.q > 0, has_right = pl.q + 1 < p.QW;
+        const unsigned long long ybase = (unsigned long long)pl.n0 * p.out_img_bytes;
+        const unsigned long long yleft = p.y_bytes - ybase;
+        const __amdgpu_buffer_rsrc_t yrsrc =
+            make_rsrc(static_cast<char*>(p.y) + ybase, (uint32_t)(yleft < 0x7FFFFFFFull ? yleft : 0x7FFFFFFFull));
+        const unsigned plane_out = (unsigned)(p.Ho * p.Wo) * (unsigned)sizeof(T);
+        const unsigned at0 = (unsigned)(pl.n - pl.n0) * p.out_img_bytes + filt * plane_out +
+                             (unsigned)(pl.oy0 * p.Wo + 4 * pl.q) * (unsigned)sizeof(T);
+        int keep = has_filter ? 1 : 0;        // (as `fetch` above)
+        asm volatile("" : "+v"(keep));
+        auto finish_row = [&](auto row_c) {
+            constexpr int r = decltype(row_c)::value;
+            float a[6];
+            quad_read_acc_row<0, r>(a);
+            const float from_left = __shfl_up(a[5], 1, 64);
+            const float from_right = __shfl_down(a[0], 1, 64);
+            float o[4] = {a[1] + (has_left ? from_left : 0.f), a[2], a[3], a[4] + (has_right ? from_right : 0.f)};
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                o[m] += filt_bias;
+                if (p.relu) o[m] = fmaxf(o[m], 0.f);
+            }
+            const bool ok = keep != 0 && pl.active && pl.oy0 + r < p.Ho;
+            const unsigned off = ok ? at0 + (unsigned)(r * p.Wo) * (unsigned)sizeof(T) : kInvalidOffset;
+            if constexpr (sizeof(T) == 4) {
+                v4u q4;
+                q4[0] = f32_to_bits(o[0]);
+                q4[1] = f32_to_bits(o[1]);
+                q4[2] = f32_to_bits(o[2]);
+                q4[3] = f32_to_bits(o[3]);
+                __builtin_amdgcn_raw_buffer_store_b128(q4, yrsrc, (int)off, 0, 0);
+            } else {
+                typedef unsigned v2u __attribute__((ext_vector_type(2)));
+                v2u q2;
+                q2[0] = (unsigned)__half_as_ushort(__float2half_rn(o[0])) |
+                        ((unsigned)__half_as_ushort(__float2half_rn(o[1])) << 16);
+                q2[1] = (unsigned)__half_as_ushort(__float2half_rn(o[2])) |
+                        ((unsigned)__half_as_ushort(__float2half_rn(o[3])) << 16);
+                __builtin_amdgcn_raw_buffer_store_b64(q2, yrsrc, (int)off, 0, 0);
+            }
+        };
+        finish_row(std::integral_constant<int, 0>{});
+        finish_row(std::integral_constant<int, 1>{});
+        finish_row(std::integral_constant<int, 2>{});
+        finish_row(std::integral_constant<int, 3>{});
+        __syncthreads();               // nobody reads the staged slot any more
+        if (!more) break;
+        slot = next;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(36))) void quad_walk_kernel(const QuadParams p) {
+    static_assert(PCONV_QUAD_SCRATCH_FIRST_NF1 >= 2 * 36, "the entry loop's registers overlap the compiler's");
+    quad_walk_body<T>(p);
+}
+
 template <int FW, typename T>
 __global__ __launch_bounds__(FW * 64) __attribute__((amdgpu_num_vgpr(36))) void quad_kernel_nf1(const QuadParams p) {
     static_assert(PCONV_QUAD_SCRATCH_FIRST_NF1 >= 2 * 36, "the entry loop's registers overlap the compiler's");
@@ -1348,8 +1532,9 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
     return PCONV_EUNSUPPORTED;
 }
 
+// walk: 0 = automatic, 1 = never, 2 = always: quad_walk_kernel instead of quad_kernel_nf1
 template <typename T>
-static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, int KS, hipStream_t stream) {
+static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, int KS, int walk, hipStream_t stream) {
     constexpr int R = PCONV_QUAD_ROWS;
     if (p.W % 4 != 0 || p.W / 4 > 64) return PCONV_EUNSUPPORTED;
     p.QW = p.W / 4;
@@ -1388,8 +1573,27 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
     p.div_NG = make_fastdiv((unsigned)p.NG);
     p.div_QW = make_fastdiv((unsigned)p.QW);
     p.div_NRB = make_fastdiv((unsigned)p.NRB);
-    const int grid = (p.nblocks + 7) / 8 * 8;
     const size_t lds = (size_t)FW * PCONV_QUAD_CH_BYTES + (size_t)FW * NF * (FW + 2) * 32;
+    // One chunk of channels and many slots: workgroups that keep their filters and walk over the slots, as many as
+    // give every CU one.  (The outputs go through a buffer descriptor there, too.)
+    const unsigned long long out_img = (unsigned long long)p.F * p.Ho * p.Wo * sizeof(T);
+    const bool can_walk = NF == 1 && p.nbk == 1 && KS == 1 && p.vec && p.NG <= 256 && out_img * span < 0x7FFFFFFFull;
+    if (walk < 0 || walk > 2) return PCONV_EINVAL;
+    if (walk == 2 && !can_walk) return PCONV_EUNSUPPORTED;
+    const long long walkers = std::min<long long>(slots, std::max(1, 256 / p.NG));
+    if (can_walk && (walk == 2 || (walk == 0 && slots >= 2 * walkers))) {
+        p.walkers = (int)walkers;
+        p.slots = (int)slots;
+        p.out_img_bytes = (unsigned)out_img;
+        p.y_bytes = (unsigned long long)p.N * out_img;
+        p.nblocks = p.NG * p.walkers;
+        const int wgrid = (p.nblocks + 7) / 8 * 8;
+        PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel<T>, lds));
+        hipLaunchKernelGGL((quad_walk_kernel<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+        PCONV_HIP(hipGetLastError());
+        return PCONV_OK;
+    }
+    const int grid = (p.nblocks + 7) / 8 * 8;
 #define PCONV_QCASE(NFv, FWv)                                                                           \
     if (NF == NFv && FW == FWv) {                                                                       \
         PCONV_HIP(allow_big_lds((const void*)quad_kernel_nf##NFv<FWv, T>, lds));                        \
@@ -1481,7 +1685,16 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         // and ResNet-50 layer shapes at batch 32 and 64) once its own workgroups nearly fill the 256 CUs.
         long long wgs = 0;
         if (reinterpret_cast<uintptr_t>(x) % 4 == 0 && quad_applicable(N, wp->C, wp->F, H, W, Ho, stride, esize, &wgs)) {
-            if (wgs >= 200) {
+            // tiles (slots) of the layer, and the workgroups that would walk over them with one filter per wave
+            const long long slots = wgs / ((wp->F + 31) / 32);
+            const long long walkers = std::max(1, 256 / ((wp->F + 15) / 16));
+            if (wp->n_buckets == 1 && pad == 1 && reinterpret_cast<uintptr_t>(y) % 16 == 0 && slots >= 2 * walkers) {
+                // one chunk of channels (a network's first layer) and several tiles per CU: workgroups that keep
+                // their filters and walk over the tiles (launch_quad turns to them under the same condition);
+                // measured 13 % faster than two filters per wave and one workgroup per tile at batch 4 to 64
+                kernel = PCONV_KERNEL_QUAD;
+                NF = 1;
+            } else if (wgs >= 200) {
                 kernel = PCONV_KERNEL_QUAD;
                 NF = 2;
             } else if (wp->C <= 16 && wgs * ((wp->F + 15) / 16) / ((wp->F + 31) / 32) >= 200) {
@@ -1658,7 +1871,9 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.x_bytes = (unsigned long long)N * wp->C * H * W * esize;
         p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
         p.plane_bytes = (unsigned)((size_t)H * W * esize);
-        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, wp, nf, fw, KS, st) : launch_quad<float>(p, wp, nf, fw, KS, st);
+        const int walk = tuning ? tuning->slot_walk : 0;
+        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, wp, nf, fw, KS, walk, st)
+                                      : launch_quad<float>(p, wp, nf, fw, KS, walk, st);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);

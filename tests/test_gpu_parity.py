@@ -265,6 +265,51 @@ def test_quad_kernel_refuses_what_it_cannot_do():
     layer.free()
 
 
+WALK_SHAPES = [  # N, C, F, H, W: one chunk of channels (C <= 16), pad 1
+    (3, 3, 64, 32, 32), (2, 3, 20, 9, 12), (5, 16, 16, 7, 8), (70, 1, 5, 6, 4), (4, 12, 33, 13, 68),
+    (2, 3, 64, 30, 256), (9, 5, 3, 5, 4),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("case", WALK_SHAPES, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}" for c in WALK_SHAPES])
+def test_quad_kernel_that_walks_over_the_tiles(case, dtype):
+    """First-layer shapes through the workgroups that keep their filters and walk over the output tiles: tile counts
+    that are and are not a multiple of the number of workgroups, fewer tiles than workgroups, waves without a filter,
+    a ragged last row block, several images per wave; against the oracle and against one workgroup per tile."""
+    N, C, F, H, W = case
+    spec = L.LayerSpec(cfg=17, idx=WALK_SHAPES.index(case), name="walk", N=N, C=C, F=F, H=H, W=W, pad=1, dtype=dtype,
+                       K=8, keep=1.0 if C <= 3 else 0.6)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    walk = dict(kernel=pc.KERNEL_QUAD, filters_per_wave=1, slot_walk=2)
+    ref = check(layer, x, [walk, dict(walk, channel_order=pc.ORDER_PLAIN)])
+    check(layer, x, [walk], relu=True)
+    got_walk = layer.run(x, **walk)
+    got_tile = layer.run(x, kernel=pc.KERNEL_QUAD, filters_per_wave=1, slot_walk=1)
+    assert np.array_equal(got_walk, got_tile)       # same sums in the same order
+    assert got_walk.shape == ref.shape
+    layer.free()
+
+
+def test_walking_is_refused_where_it_does_not_apply():
+    for kw, shape in [(dict(filters_per_wave=2), dict()), (dict(filters_per_wave=1), dict(C=20)),
+                      (dict(filters_per_wave=1), dict(pad=0))]:
+        spec = L.LayerSpec(**{**dict(cfg=17, idx=50, name="walkno", N=2, C=8, F=16, H=8, W=8, K=8, keep=0.5), **shape})
+        layer = GpuLayer(spec)
+        with pytest.raises(pc.PconvError) as ei:
+            layer.run(L.gen_activations(spec), kernel=pc.KERNEL_QUAD, slot_walk=2, **kw)
+        assert ei.value.code == pc.EUNSUPPORTED, (kw, shape)
+        layer.free()
+    # an output pointer that is not 16-byte aligned
+    spec = L.LayerSpec(cfg=17, idx=51, name="walkno", N=2, C=8, F=16, H=8, W=8, K=8, keep=0.5)
+    layer = GpuLayer(spec)
+    with pytest.raises(pc.PconvError) as ei:
+        layer.run(L.gen_activations(spec), y_shift=1, kernel=pc.KERNEL_QUAD, filters_per_wave=1, slot_walk=2)
+    assert ei.value.code == pc.EUNSUPPORTED
+    layer.free()
+
+
 def test_hip_graph_replays_match_eager_launches():
     """Two layers (the first splits its channels over workgroups, the second runs at stride 2 through the parity
     form) and a max-pool, captured into one HIP graph: every replay, with eager work and synchronisations in between
