@@ -1141,7 +1141,7 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
 // multiplied and stored.  Loads and stores are unconditional (lanes with nothing to do use an offset outside the
 // descriptor): the wait for a slot's loads must not include the stores issued behind them, and the compiler can
 // only count those when no branch surrounds them.  Needs pad 1 and a 16-byte aligned y (one store per lane and row).
-template <typename T>
+template <int NF, typename T>
 __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
     constexpr int R = PCONV_QUAD_ROWS, FW = 16, CC = 16;
     constexpr unsigned kChB = PCONV_QUAD_CH_BYTES;
@@ -1173,32 +1173,37 @@ __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
         return r;
     };
 
-    // the wave's filter, its entries (staged once) and its channel of the one chunk
-    const int pos = grp * FW + wave;
-    const bool has_filter = pos < p.F;
-    unsigned e0 = 0, e1 = 0;
-    if (has_filter) {
-        e0 = scalar_load_u32(p.eptr + pos * p.nbk);
-        e1 = scalar_load_u32(p.eptr + pos * p.nbk + 1);
-    }
-    const unsigned c = p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + wave) : (unsigned)wave;
-    const unsigned filt = has_filter ? scalar_load_u32(p.forder + pos) : 0u;
-    const float filt_bias =
-        (p.bias && has_filter) ? __builtin_bit_cast(float, scalar_load_u32(reinterpret_cast<const uint32_t*>(p.bias + filt)))
-                               : 0.f;
-    const unsigned cnt = __builtin_amdgcn_readfirstlane(e1 - e0);
-    {
+    // the wave's filters, their entries (staged once) and its channel of the one chunk
+    const int pos_base = grp * (FW * NF) + wave;
+    bool has_filter[NF];
+    unsigned filt[NF], cnt[NF];
+    float filt_bias[NF];
+#pragma unroll
+    for (int a = 0; a < NF; ++a) {
+        const int pos = pos_base + a * FW;
+        has_filter[a] = pos < p.F;
+        unsigned e0 = 0, e1 = 0;
+        if (has_filter[a]) {
+            e0 = scalar_load_u32(p.eptr + pos * p.nbk);
+            e1 = scalar_load_u32(p.eptr + pos * p.nbk + 1);
+        }
+        filt[a] = has_filter[a] ? scalar_load_u32(p.forder + pos) : 0u;
+        filt_bias[a] = (p.bias && has_filter[a])
+                           ? __builtin_bit_cast(float, scalar_load_u32(reinterpret_cast<const uint32_t*>(p.bias + filt[a])))
+                           : 0.f;
+        cnt[a] = __builtin_amdgcn_readfirstlane(e1 - e0);
         const __amdgpu_buffer_rsrc_t ent_rsrc = make_rsrc(p.ent, p.ent_bytes);
-        const unsigned eoff = (unsigned)(lane >> 2) < cnt ? e0 * 32u + (unsigned)lane * 8u : kInvalidOffset;
+        const unsigned eoff = (unsigned)(lane >> 2) < cnt[a] ? e0 * 32u + (unsigned)lane * 8u : kInvalidOffset;
         typedef unsigned v2u __attribute__((ext_vector_type(2)));
         const v2u e = __builtin_amdgcn_raw_buffer_load_b64(ent_rsrc, (int)eoff, 0, 0);
         static_assert(kEntRegion >= 64 * 8, "entry region smaller than one wave's write");
-        reinterpret_cast<uint2*>(lds + kEntBase + wave * kEntRegion)[lane] = make_uint2(e[0], e[1]);
+        reinterpret_cast<uint2*>(lds + kEntBase + (wave * NF + a) * kEntRegion)[lane] = make_uint2(e[0], e[1]);
     }
+    const unsigned c = p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + wave) : (unsigned)wave;
     const bool staged = c < (unsigned)p.C;
     const unsigned soff = staged ? c * p.plane_bytes : 0u;
     const unsigned lane_addr = lds0 + lane * 16;
-    const unsigned ent_addr = lds0 + kEntBase + wave * kEntRegion;
+    const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
 
     RawQuad<T> pre[R + 2];
     // (`wanted` and `staged` are the same for the whole wave; they reach the offsets through a vector register the
@@ -1225,13 +1230,13 @@ __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
     int slot = walker;                 // walker < walkers <= slots
     issue_loads(slot, true);
     {
-        // Four stores that store nothing (their offset is outside the descriptor), so that the loop is entered the
-        // way it is re-entered: six loads with four stores behind them.  The compiler's count of what may still be
+        // Stores that store nothing (their offset is outside the descriptor), as many as a slot has, so that the loop is
+        // entered the way it is re-entered: six loads with a slot's stores behind them.  The compiler's count of what may still be
         // pending at the top of the loop is the merge of both ways in, and without these it waits for the stores of
         // the slot before along with the loads.
         const __amdgpu_buffer_rsrc_t none = make_rsrc(p.y, 0u);
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
+        for (int r = 0; r < R * NF; ++r) {
             if constexpr (sizeof(T) == 4) {
                 v4u z = {0u, 0u, 0u, 0u};
                 __builtin_amdgcn_raw_buffer_store_b128(z, none, (int)(kInvalidOffset + 16u * r), 0, 0);   // (four different ones)
@@ -1250,8 +1255,14 @@ __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
         const int next = slot + p.walkers;
         const bool more = next < p.slots;
         issue_loads(more ? next : slot, more);
-        quad_zero_acc<0>();
-        if (cnt) quad_run_entries<1, 0, CC>(lane_addr, ent_addr, cnt);
+        if constexpr (NF > 0) {
+            quad_zero_acc<0>();
+            if (cnt[0]) quad_run_entries<NF, 0, CC>(lane_addr, ent_addr, cnt[0]);
+        }
+        if constexpr (NF > 1) {
+            quad_zero_acc<1>();
+            if (cnt[1]) quad_run_entries<NF, 1, CC>(lane_addr, ent_addr + kEntRegion, cnt[1]);
+        }
 
         // the slot's outputs: accumulator columns 0 and 5 go to the neighbouring quads; bias, ReLU, store
         int lane_again = lane;
@@ -1263,24 +1274,26 @@ __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
         const __amdgpu_buffer_rsrc_t yrsrc =
             make_rsrc(static_cast<char*>(p.y) + ybase, (uint32_t)(yleft < 0x7FFFFFFFull ? yleft : 0x7FFFFFFFull));
         const unsigned plane_out = (unsigned)(p.Ho * p.Wo) * (unsigned)sizeof(T);
-        const unsigned at0 = (unsigned)(pl.n - pl.n0) * p.out_img_bytes + filt * plane_out +
-                             (unsigned)(pl.oy0 * p.Wo + 4 * pl.q) * (unsigned)sizeof(T);
-        int keep = has_filter ? 1 : 0;        // (as `fetch` above)
-        asm volatile("" : "+v"(keep));
-        auto finish_row = [&](auto row_c) {
+        const unsigned at_img = (unsigned)(pl.n - pl.n0) * p.out_img_bytes +
+                                (unsigned)(pl.oy0 * p.Wo + 4 * pl.q) * (unsigned)sizeof(T);
+        auto finish_row = [&](auto slot_c, auto row_c) {
+            constexpr int a = decltype(slot_c)::value;
             constexpr int r = decltype(row_c)::value;
-            float a[6];
-            quad_read_acc_row<0, r>(a);
-            const float from_left = __shfl_up(a[5], 1, 64);
-            const float from_right = __shfl_down(a[0], 1, 64);
-            float o[4] = {a[1] + (has_left ? from_left : 0.f), a[2], a[3], a[4] + (has_right ? from_right : 0.f)};
+            int keep = has_filter[a] ? 1 : 0;        // (as `fetch` above)
+            asm volatile("" : "+v"(keep));
+            float acc[6];
+            quad_read_acc_row<a, r>(acc);
+            const float from_left = __shfl_up(acc[5], 1, 64);
+            const float from_right = __shfl_down(acc[0], 1, 64);
+            float o[4] = {acc[1] + (has_left ? from_left : 0.f), acc[2], acc[3], acc[4] + (has_right ? from_right : 0.f)};
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                o[m] += filt_bias;
+                o[m] += filt_bias[a];
                 if (p.relu) o[m] = fmaxf(o[m], 0.f);
             }
             const bool ok = keep != 0 && pl.active && pl.oy0 + r < p.Ho;
-            const unsigned off = ok ? at0 + (unsigned)(r * p.Wo) * (unsigned)sizeof(T) : kInvalidOffset;
+            const unsigned off = ok ? at_img + filt[a] * plane_out + (unsigned)(r * p.Wo) * (unsigned)sizeof(T)
+                                    : kInvalidOffset;
             if constexpr (sizeof(T) == 4) {
                 v4u q4;
                 q4[0] = f32_to_bits(o[0]);
@@ -1298,10 +1311,12 @@ __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
                 __builtin_amdgcn_raw_buffer_store_b64(q2, yrsrc, (int)off, 0, 0);
             }
         };
-        finish_row(std::integral_constant<int, 0>{});
-        finish_row(std::integral_constant<int, 1>{});
-        finish_row(std::integral_constant<int, 2>{});
-        finish_row(std::integral_constant<int, 3>{});
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        using I3 = std::integral_constant<int, 3>;
+        if constexpr (NF > 0) { finish_row(I0{}, I0{}); finish_row(I0{}, I1{}); finish_row(I0{}, I2{}); finish_row(I0{}, I3{}); }
+        if constexpr (NF > 1) { finish_row(I1{}, I0{}); finish_row(I1{}, I1{}); finish_row(I1{}, I2{}); finish_row(I1{}, I3{}); }
         __syncthreads();               // nobody reads the staged slot any more
         if (!more) break;
         slot = next;
@@ -1309,9 +1324,14 @@ __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
 }
 
 template <typename T>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(36))) void quad_walk_kernel(const QuadParams p) {
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(36))) void quad_walk_kernel_nf1(const QuadParams p) {
     static_assert(PCONV_QUAD_SCRATCH_FIRST_NF1 >= 2 * 36, "the entry loop's registers overlap the compiler's");
-    quad_walk_body<T>(p);
+    quad_walk_body<1, T>(p);
+}
+template <typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(24))) void quad_walk_kernel_nf2(const QuadParams p) {
+    static_assert(PCONV_QUAD_SCRATCH_FIRST_NF2 >= 2 * 24, "the entry loop's registers overlap the compiler's");
+    quad_walk_body<2, T>(p);
 }
 
 template <int FW, typename T>
@@ -1577,19 +1597,26 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
     // One chunk of channels and many slots: workgroups that keep their filters and walk over the slots, as many as
     // give every CU one.  (The outputs go through a buffer descriptor there, too.)
     const unsigned long long out_img = (unsigned long long)p.F * p.Ho * p.Wo * sizeof(T);
-    const bool can_walk = NF == 1 && p.nbk == 1 && KS == 1 && p.vec && p.NG <= 256 && out_img * span < 0x7FFFFFFFull;
+    // (two filters per wave: fp16 storage only; with fp32 the six rows in flight do not fit the registers left)
+    const bool can_walk = p.nbk == 1 && KS == 1 && p.vec && p.NG <= 256 && out_img * span < 0x7FFFFFFFull &&
+                          (NF == 1 || sizeof(T) == 2);
     if (walk < 0 || walk > 2) return PCONV_EINVAL;
     if (walk == 2 && !can_walk) return PCONV_EUNSUPPORTED;
     const long long walkers = std::min<long long>(slots, std::max(1, 256 / p.NG));
-    if (can_walk && (walk == 2 || (walk == 0 && slots >= 2 * walkers))) {
+    if (can_walk && (walk == 2 || (walk == 0 && 2 * slots >= 3 * walkers))) {
         p.walkers = (int)walkers;
         p.slots = (int)slots;
         p.out_img_bytes = (unsigned)out_img;
         p.y_bytes = (unsigned long long)p.N * out_img;
         p.nblocks = p.NG * p.walkers;
         const int wgrid = (p.nblocks + 7) / 8 * 8;
-        PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel<T>, lds));
-        hipLaunchKernelGGL((quad_walk_kernel<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+        if (NF == 1) {
+            PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel_nf1<T>, lds));
+            hipLaunchKernelGGL((quad_walk_kernel_nf1<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+        } else if constexpr (sizeof(T) == 2) {
+            PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel_nf2<T>, lds));
+            hipLaunchKernelGGL((quad_walk_kernel_nf2<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+        }
         PCONV_HIP(hipGetLastError());
         return PCONV_OK;
     }
@@ -1685,15 +1712,17 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         // and ResNet-50 layer shapes at batch 32 and 64) once its own workgroups nearly fill the 256 CUs.
         long long wgs = 0;
         if (reinterpret_cast<uintptr_t>(x) % 4 == 0 && quad_applicable(N, wp->C, wp->F, H, W, Ho, stride, esize, &wgs)) {
-            // tiles (slots) of the layer, and the workgroups that would walk over them with one filter per wave
+            // tiles (slots) of the layer, and the workgroups that would walk over them (two filters per wave with
+            // fp16 storage, one with fp32: see launch_quad)
+            const int walk_nf = wp->dtype == PCONV_F16 ? 2 : 1;
             const long long slots = wgs / ((wp->F + 31) / 32);
-            const long long walkers = std::max(1, 256 / ((wp->F + 15) / 16));
-            if (wp->n_buckets == 1 && pad == 1 && reinterpret_cast<uintptr_t>(y) % 16 == 0 && slots >= 2 * walkers) {
-                // one chunk of channels (a network's first layer) and several tiles per CU: workgroups that keep
-                // their filters and walk over the tiles (launch_quad turns to them under the same condition);
-                // measured 13 % faster than two filters per wave and one workgroup per tile at batch 4 to 64
+            const long long walkers = std::max(1, 256 / ((wp->F + 16 * walk_nf - 1) / (16 * walk_nf)));
+            if (wp->n_buckets == 1 && pad == 1 && reinterpret_cast<uintptr_t>(y) % 16 == 0 && 2 * slots >= 3 * walkers) {
+                // one chunk of channels (a network's first layer) and more tiles than CUs: workgroups that keep their
+                // filters and walk over the tiles (launch_quad turns to them under the same condition); measured
+                // 13 to 32 % faster than one workgroup per tile at batch 4 to 64
                 kernel = PCONV_KERNEL_QUAD;
-                NF = 1;
+                NF = walk_nf;
             } else if (wgs >= 200) {
                 kernel = PCONV_KERNEL_QUAD;
                 NF = 2;

@@ -282,18 +282,19 @@ def test_quad_kernel_that_walks_over_the_tiles(case, dtype):
                        K=8, keep=1.0 if C <= 3 else 0.6)
     layer = GpuLayer(spec)
     x = L.gen_activations(spec)
-    walk = dict(kernel=pc.KERNEL_QUAD, filters_per_wave=1, slot_walk=2)
-    ref = check(layer, x, [walk, dict(walk, channel_order=pc.ORDER_PLAIN)])
-    check(layer, x, [walk], relu=True)
-    got_walk = layer.run(x, **walk)
-    got_tile = layer.run(x, kernel=pc.KERNEL_QUAD, filters_per_wave=1, slot_walk=1)
-    assert np.array_equal(got_walk, got_tile)       # same sums in the same order
-    assert got_walk.shape == ref.shape
+    for nf in (1, 2) if dtype == "f16" else (1,):      # two filters per wave: fp16 storage only
+        walk = dict(kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=2)
+        ref = check(layer, x, [walk, dict(walk, channel_order=pc.ORDER_PLAIN)])
+        check(layer, x, [walk], relu=True)
+        got_walk = layer.run(x, **walk)
+        got_tile = layer.run(x, kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=1)
+        assert np.array_equal(got_walk, got_tile)       # same sums in the same order
+        assert got_walk.shape == ref.shape
     layer.free()
 
 
 def test_walking_is_refused_where_it_does_not_apply():
-    for kw, shape in [(dict(filters_per_wave=2), dict()), (dict(filters_per_wave=1), dict(C=20)),
+    for kw, shape in [(dict(filters_per_wave=2), dict(dtype="f32")), (dict(filters_per_wave=1), dict(C=20)),
                       (dict(filters_per_wave=1), dict(pad=0))]:
         spec = L.LayerSpec(**{**dict(cfg=17, idx=50, name="walkno", N=2, C=8, F=16, H=8, W=8, K=8, keep=0.5), **shape})
         layer = GpuLayer(spec)
