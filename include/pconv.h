@@ -185,11 +185,11 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *   buffers           tiled: 1 = one chunk buffer in LDS and two barriers per chunk; 2 = two buffers of 16
  *                     channels (waves * channels_per_wave must be 16) and one barrier per chunk, the LDS writes of
  *                     one chunk running beside the multiply-adds of the chunk before
- *   slot_walk         quad (with two filters per wave: fp16 storage only), a layer whose input channels fit one
- *                     chunk of 16 (a network's first layer), pad 1, y aligned to 16 bytes: 2 = one workgroup per CU and filter group keeps its
- *                     filters and walks over the output tiles, loading the next tile while it multiplies and stores
- *                     the current one; 1 = one workgroup per tile as everywhere else; 0 = walk if there are at
- *                     least 1.5 tiles per workgroup (the automatic kernel choice takes this form for such layers)
+ *   slot_walk         quad (with two filters per wave: fp16 storage only; pad 1, y aligned to 16 bytes, no channel
+ *                     split): 2 = one workgroup per CU and filter group walks over the output tiles, loading the next
+ *                     tile's first chunk while it multiplies and stores the current tile (a layer whose channels fit
+ *                     one chunk of 16, a network's first layer, also keeps its entries in LDS); 1 = one workgroup per
+ *                     tile; 0 = walk if there are at least 1.5 tiles per workgroup (one chunk) or 6 (several chunks)
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
 enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2, PCONV_KERNEL_QUAD = 3 };

@@ -1323,6 +1323,257 @@ __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
     }
 }
 
+// The walking workgroup for layers of several chunks: the chunk loop of quad_body run over the (tile, chunk) pairs of
+// all the workgroup's tiles as one sequence, so that the first chunk of the next tile is loaded while the last chunk
+// of the current one is multiplied, and its outputs are stored while the next tile is under way; what a workgroup
+// pays once per tile otherwise — kernel start, scalar metadata, a memory round trip before the first multiply-add,
+// the stores' acknowledgement at the end — it pays once.  Entries are staged per chunk as in quad_body (they are the
+// same for every tile and come from the L2).  The outputs of a tile are stored between the two barriers that end
+// its last chunk, behind the LDS write of the next chunk: by then the loads in flight have been waited for, so no
+// later wait for a load has younger stores to account for, and the stores have a whole chunk's time to complete
+// before the next wait (gfx950 counts loads and stores with one counter, in order).
+template <int NF, typename T>
+__device__ __forceinline__ void quad_stream_body(const QuadParams& p) {
+    constexpr int R = PCONV_QUAD_ROWS, FW = 16, CC = 16;
+    constexpr unsigned kChB = PCONV_QUAD_CH_BYTES;
+    constexpr unsigned kRowB = 64 * 16;
+    constexpr unsigned kEntRegion = (CC + 2) * 32;
+    constexpr unsigned kEntBase = CC * kChB;
+    extern __shared__ __align__(16) unsigned char lds[];     // as in quad_body
+    const unsigned lds0 = (unsigned)(unsigned long long)lds;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    const int per_xcd = gridDim.x >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= p.nblocks) return;
+    const int walker = (int)fastdiv((unsigned)logical, p.div_NG);
+    const int g0 = logical - walker * p.NG;
+    const int K = p.nbk;                                      // chunks per tile
+    // The filter groups are in the packed order, most kept kernels first, so a workgroup that stayed with one group
+    // would do up to 15 % more or less than the average; it takes group g0 for its even tiles and NG-1-g0 for its odd
+    // ones instead.  (At any time the NG workgroups of a walker are still on the same tile, one per group.)
+    auto group_of = [&](int j) { return (j & 1) ? p.NG - 1 - g0 : g0; };
+
+    struct LanePlace { int q, n, n0, oy0; bool active; };
+    auto place_of = [&](int ln, int slot) {
+        LanePlace r;
+        const int g0 = slot * p.BL;
+        r.n0 = (int)fastdiv((unsigned)g0, p.div_NRB);
+        const int b = (int)fastdiv((unsigned)ln, p.div_QW);
+        r.q = ln - b * p.QW;
+        r.active = b < p.BL && g0 + b < p.NBLK;
+        const int g = r.active ? g0 + b : g0;
+        r.n = (int)fastdiv((unsigned)g, p.div_NRB);
+        r.oy0 = (g - r.n * p.NRB) * R;
+        return r;
+    };
+
+    // Input offsets and descriptor of the tile whose chunks are being loaded: the offset of the lane's quad in patch
+    // row 0 (modulo 2^32 where that row is above the image) and which of the six rows exist — two registers held
+    // across the loop instead of six offsets.
+    unsigned first_off, rows_ok;
+    __amdgpu_buffer_rsrc_t rsrc;
+    auto aim_at = [&](int slot) {
+        const LanePlace pl = place_of(lane, slot);
+        const int iy0 = pl.oy0 - p.pad;
+        first_off = (unsigned)(pl.n - pl.n0) * p.img_bytes + (unsigned)(iy0 * p.W + 4 * pl.q) * (unsigned)sizeof(T);
+        rows_ok = 0u;
+#pragma unroll
+        for (int i = 0; i < R + 2; ++i)
+            if (pl.active && iy0 + i >= 0 && iy0 + i < p.H) rows_ok |= 1u << i;
+        const unsigned long long base_off = (unsigned long long)pl.n0 * p.img_bytes;
+        const unsigned long long left = p.x_bytes - base_off;
+        rsrc = make_rsrc(static_cast<const char*>(p.x) + base_off, (uint32_t)(left < 0x7FFFFFFFull ? left : 0x7FFFFFFFull));
+    };
+    const unsigned row_bytes = (unsigned)p.W * (unsigned)sizeof(T);
+
+    const unsigned lane_addr = lds0 + lane * 16;
+    const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
+    // filters and biases of the tile that is multiplied (fetched when its first chunk starts)
+    unsigned filt[NF];
+    float filt_bias[NF];
+    bool has_filter[NF];
+    auto fetch_filters = [&](int grp) {
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            const int pos = grp * (FW * NF) + wave + a * FW;
+            has_filter[a] = pos < p.F;
+            filt[a] = has_filter[a] ? scalar_load_u32(p.forder + pos) : 0u;
+            filt_bias[a] = (p.bias && has_filter[a])
+                               ? __builtin_bit_cast(float, scalar_load_u32(reinterpret_cast<const uint32_t*>(p.bias + filt[a])))
+                               : 0.f;
+        }
+    };
+
+    // (see quad_body for why loads and their use are unconditional and the metadata runs a chunk ahead)
+    RawQuad<T> pre[R + 2];
+    uint2 epre[NF];
+    unsigned ecnt[NF];
+    const __amdgpu_buffer_rsrc_t ent_rsrc = make_rsrc(p.ent, p.ent_bytes);
+    unsigned meta_e0[NF], meta_e1[NF], meta_c;
+    auto fetch_meta = [&](int grp, int k, bool any) {      // chunk k of the group, or nothing
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            const int pos = grp * (FW * NF) + wave + a * FW;
+            meta_e0[a] = meta_e1[a] = 0;
+            if (any && pos < p.F) {
+                meta_e0[a] = scalar_load_u32(p.eptr + pos * p.nbk + k);
+                meta_e1[a] = scalar_load_u32(p.eptr + pos * p.nbk + k + 1);
+            }
+        }
+        meta_c = !any ? kNoChannel
+                 : p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + k * CC + wave)
+                          : (unsigned)(k * CC + wave);
+    };
+    auto issue_loads = [&]() {                    // the chunk of the last fetch_meta, of the tile last aimed at
+        unsigned e0[NF];
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            e0[a] = meta_e0[a];
+            ecnt[a] = meta_e1[a] - e0[a];
+        }
+        const unsigned c = meta_c;
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            const unsigned eoff = (unsigned)(lane >> 2) < ecnt[a] ? e0[a] * 32u + (unsigned)lane * 8u : kInvalidOffset;
+            typedef unsigned v2u __attribute__((ext_vector_type(2)));
+            const v2u e = __builtin_amdgcn_raw_buffer_load_b64(ent_rsrc, (int)eoff, 0, 0);
+            epre[a] = make_uint2(e[0], e[1]);
+        }
+        const bool staged = c < (unsigned)p.C;
+        const unsigned soff = staged ? c * p.plane_bytes : 0u;
+        const unsigned rows = staged ? rows_ok : 0u;
+#pragma unroll
+        for (int i = 0; i < R + 2; ++i)
+            pre[i].load(rsrc, ((rows >> i) & 1u) ? first_off + (unsigned)i * row_bytes : kInvalidOffset, soff);
+    };
+    auto write_lds = [&]() {
+        float4* dst = reinterpret_cast<float4*>(lds + wave * kChB + lane * 16);
+#pragma unroll
+        for (int i = 0; i < R + 2; ++i) dst[i * (kRowB / 16)] = pre[i].widen();
+        static_assert(kEntRegion >= 64 * 8, "entry region smaller than one wave's write");
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            uint2* e = reinterpret_cast<uint2*>(lds + kEntBase + (wave * NF + a) * kEntRegion);
+            e[lane] = epre[a];
+        }
+    };
+    // outputs of the tile `slot`, from the accumulators
+    auto store_tile = [&](int slot) {
+        int lane_again = lane;
+        asm volatile("" : "+v"(lane_again));
+        const LanePlace pl = place_of(lane_again, slot);
+        const bool has_left = pl.q > 0, has_right = pl.q + 1 < p.QW;
+        const unsigned long long ybase = (unsigned long long)pl.n0 * p.out_img_bytes;
+        const unsigned long long yleft = p.y_bytes - ybase;
+        const __amdgpu_buffer_rsrc_t yrsrc =
+            make_rsrc(static_cast<char*>(p.y) + ybase, (uint32_t)(yleft < 0x7FFFFFFFull ? yleft : 0x7FFFFFFFull));
+        const unsigned plane_out = (unsigned)(p.Ho * p.Wo) * (unsigned)sizeof(T);
+        const unsigned at_img = (unsigned)(pl.n - pl.n0) * p.out_img_bytes +
+                                (unsigned)(pl.oy0 * p.Wo + 4 * pl.q) * (unsigned)sizeof(T);
+        auto finish_row = [&](auto slot_c, auto row_c) {
+            constexpr int a = decltype(slot_c)::value;
+            constexpr int r = decltype(row_c)::value;
+            float acc[6];
+            quad_read_acc_row<a, r>(acc);
+            const float from_left = __shfl_up(acc[5], 1, 64);
+            const float from_right = __shfl_down(acc[0], 1, 64);
+            float o[4] = {acc[1] + (has_left ? from_left : 0.f), acc[2], acc[3], acc[4] + (has_right ? from_right : 0.f)};
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                o[m] += filt_bias[a];
+                if (p.relu) o[m] = fmaxf(o[m], 0.f);
+            }
+            const bool ok = has_filter[a] && pl.active && pl.oy0 + r < p.Ho;
+            const unsigned off = ok ? at_img + filt[a] * plane_out + (unsigned)(r * p.Wo) * (unsigned)sizeof(T)
+                                    : kInvalidOffset;
+            if constexpr (sizeof(T) == 4) {
+                v4u q4;
+                q4[0] = f32_to_bits(o[0]);
+                q4[1] = f32_to_bits(o[1]);
+                q4[2] = f32_to_bits(o[2]);
+                q4[3] = f32_to_bits(o[3]);
+                __builtin_amdgcn_raw_buffer_store_b128(q4, yrsrc, (int)off, 0, 0);
+            } else {
+                typedef unsigned v2u __attribute__((ext_vector_type(2)));
+                v2u q2;
+                q2[0] = (unsigned)__half_as_ushort(__float2half_rn(o[0])) |
+                        ((unsigned)__half_as_ushort(__float2half_rn(o[1])) << 16);
+                q2[1] = (unsigned)__half_as_ushort(__float2half_rn(o[2])) |
+                        ((unsigned)__half_as_ushort(__float2half_rn(o[3])) << 16);
+                __builtin_amdgcn_raw_buffer_store_b64(q2, yrsrc, (int)off, 0, 0);
+            }
+        };
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        using I3 = std::integral_constant<int, 3>;
+        if constexpr (NF > 0) { finish_row(I0{}, I0{}); finish_row(I0{}, I1{}); finish_row(I0{}, I2{}); finish_row(I0{}, I3{}); }
+        if constexpr (NF > 1) { finish_row(I1{}, I0{}); finish_row(I1{}, I1{}); finish_row(I1{}, I2{}); finish_row(I1{}, I3{}); }
+    };
+
+    // The sequence: tiles number j = 0, 1, ... of this workgroup (slot walker + j * walkers < slots), K chunks each.
+    // Three positions move along it: (fj, fk) the pair whose metadata is fetched next, (lj, lk) the pair whose loads
+    // are issued next, (cj, k) the pair that is multiplied.
+    auto slot_of = [&](int j) { return walker + j * p.walkers; };
+    auto step = [&](int& j, int& c) {
+        if (++c == K) {
+            c = 0;
+            ++j;
+        }
+    };
+    int cj = 0, k = 0, lj = 0, lk = 0, fj = 0, fk = 0;
+    if constexpr (NF > 0) quad_zero_acc<0>();
+    if constexpr (NF > 1) quad_zero_acc<1>();
+    aim_at(slot_of(0));
+    fetch_meta(group_of(0), 0, true);      // walker < walkers <= slots: the first pair exists
+    step(fj, fk);
+    issue_loads();
+    step(lj, lk);
+    fetch_meta(group_of(fj), fk, slot_of(fj) < p.slots);
+    step(fj, fk);
+    write_lds();
+    __syncthreads();
+    unsigned cnt_now[NF];
+    for (;;) {
+        const bool more = slot_of(lj) < p.slots;   // a pair behind the current one
+#pragma unroll
+        for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
+        if (more) {
+            if (lk == 0) aim_at(slot_of(lj));      // (uniform)
+            issue_loads();
+        }
+        step(lj, lk);
+        if (k == 0) fetch_filters(group_of(cj));   // (uniform) needed when the tile is stored
+        if constexpr (NF > 0) { if (cnt_now[0]) quad_run_entries<NF, 0, CC>(lane_addr, ent_addr, cnt_now[0]); }
+        if constexpr (NF > 1) { if (cnt_now[1]) quad_run_entries<NF, 1, CC>(lane_addr, ent_addr + kEntRegion, cnt_now[1]); }
+        fetch_meta(group_of(fj), fk, slot_of(fj) < p.slots);
+        step(fj, fk);
+        __syncthreads();                   // every wave is done reading the staged chunk
+        if (more) write_lds();
+        if (k == K - 1) {                  // (uniform) the tile is complete
+            store_tile(slot_of(cj));
+            if constexpr (NF > 0) quad_zero_acc<0>();
+            if constexpr (NF > 1) quad_zero_acc<1>();
+        }
+        if (!more) break;
+        __syncthreads();
+        step(cj, k);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(36))) void quad_stream_kernel_nf1(const QuadParams p) {
+    static_assert(PCONV_QUAD_SCRATCH_FIRST_NF1 >= 2 * 36, "the entry loop's registers overlap the compiler's");
+    quad_stream_body<1, T>(p);
+}
+template <typename T>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(24))) void quad_stream_kernel_nf2(const QuadParams p) {
+    static_assert(PCONV_QUAD_SCRATCH_FIRST_NF2 >= 2 * 24, "the entry loop's registers overlap the compiler's");
+    quad_stream_body<2, T>(p);
+}
+
 template <typename T>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_num_vgpr(36))) void quad_walk_kernel_nf1(const QuadParams p) {
     static_assert(PCONV_QUAD_SCRATCH_FIRST_NF1 >= 2 * 36, "the entry loop's registers overlap the compiler's");
@@ -1598,24 +1849,36 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
     // give every CU one.  (The outputs go through a buffer descriptor there, too.)
     const unsigned long long out_img = (unsigned long long)p.F * p.Ho * p.Wo * sizeof(T);
     // (two filters per wave: fp16 storage only; with fp32 the six rows in flight do not fit the registers left)
-    const bool can_walk = p.nbk == 1 && KS == 1 && p.vec && p.NG <= 256 && out_img * span < 0x7FFFFFFFull &&
+    const bool can_walk = KS == 1 && p.vec && p.NG <= 256 && out_img * span < 0x7FFFFFFFull && slots < 0x7FFF0000ll &&
                           (NF == 1 || sizeof(T) == 2);
     if (walk < 0 || walk > 2) return PCONV_EINVAL;
     if (walk == 2 && !can_walk) return PCONV_EUNSUPPORTED;
     const long long walkers = std::min<long long>(slots, std::max(1, 256 / p.NG));
-    if (can_walk && (walk == 2 || (walk == 0 && 2 * slots >= 3 * walkers))) {
+    // automatic: one chunk from 1.5 tiles per workgroup on; several chunks from 6 tiles on (measured on the VGG-16
+    // layers at batch 64: 2 to 14 % faster there, slower at 3 tiles per workgroup, where the tiles do not divide evenly)
+    if (can_walk && (walk == 2 || (walk == 0 && (p.nbk == 1 ? 2 * slots >= 3 * walkers : slots >= 6 * walkers)))) {
         p.walkers = (int)walkers;
         p.slots = (int)slots;
         p.out_img_bytes = (unsigned)out_img;
         p.y_bytes = (unsigned long long)p.N * out_img;
         p.nblocks = p.NG * p.walkers;
         const int wgrid = (p.nblocks + 7) / 8 * 8;
-        if (NF == 1) {
-            PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel_nf1<T>, lds));
-            hipLaunchKernelGGL((quad_walk_kernel_nf1<T>), dim3(wgrid), dim3(1024), lds, stream, p);
-        } else if constexpr (sizeof(T) == 2) {
-            PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel_nf2<T>, lds));
-            hipLaunchKernelGGL((quad_walk_kernel_nf2<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+        if (p.nbk == 1) {          // the entries stay in LDS
+            if (NF == 1) {
+                PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel_nf1<T>, lds));
+                hipLaunchKernelGGL((quad_walk_kernel_nf1<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+            } else if constexpr (sizeof(T) == 2) {
+                PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel_nf2<T>, lds));
+                hipLaunchKernelGGL((quad_walk_kernel_nf2<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+            }
+        } else {
+            if (NF == 1) {
+                PCONV_HIP(allow_big_lds((const void*)quad_stream_kernel_nf1<T>, lds));
+                hipLaunchKernelGGL((quad_stream_kernel_nf1<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+            } else if constexpr (sizeof(T) == 2) {
+                PCONV_HIP(allow_big_lds((const void*)quad_stream_kernel_nf2<T>, lds));
+                hipLaunchKernelGGL((quad_stream_kernel_nf2<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+            }
         }
         PCONV_HIP(hipGetLastError());
         return PCONV_OK;

@@ -293,8 +293,35 @@ def test_quad_kernel_that_walks_over_the_tiles(case, dtype):
     layer.free()
 
 
+STREAM_SHAPES = [  # N, C, F, H, W: several chunks of channels, pad 1
+    (3, 40, 64, 32, 32), (2, 20, 20, 9, 12), (5, 33, 16, 7, 8), (70, 17, 5, 6, 4), (4, 64, 33, 13, 68), (9, 100, 40, 5, 4),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("case", STREAM_SHAPES, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}" for c in STREAM_SHAPES])
+def test_quad_kernel_that_walks_over_tiles_of_several_chunks(case, dtype):
+    """Layers of more than one chunk through the workgroups that run the chunks of all their tiles as one sequence:
+    against the oracle, and bit for bit against one workgroup per tile; a ragged last chunk, tile counts that are
+    not a multiple of the number of workgroups, fewer tiles than workgroups, waves without a filter."""
+    N, C, F, H, W = case
+    spec = L.LayerSpec(cfg=18, idx=STREAM_SHAPES.index(case), name="stream", N=N, C=C, F=F, H=H, W=W, pad=1, dtype=dtype,
+                       K=8, keep=0.5)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    for nf in (1, 2) if dtype == "f16" else (1,):      # two filters per wave: fp16 storage only
+        walk = dict(kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=2)
+        check(layer, x, [walk, dict(walk, channel_order=pc.ORDER_PLAIN)])
+        check(layer, x, [walk], relu=True)
+        for order in (pc.ORDER_PLAIN, pc.ORDER_BALANCED):
+            got_walk = layer.run(x, channel_order=order, **walk)
+            got_tile = layer.run(x, kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=1, channel_order=order)
+            assert np.array_equal(got_walk, got_tile)       # same sums in the same order
+    layer.free()
+
+
 def test_walking_is_refused_where_it_does_not_apply():
-    for kw, shape in [(dict(filters_per_wave=2), dict(dtype="f32")), (dict(filters_per_wave=1), dict(C=20)),
+    for kw, shape in [(dict(filters_per_wave=2), dict(dtype="f32")), (dict(filters_per_wave=1, channel_splits=2), dict(C=40)),
                       (dict(filters_per_wave=1), dict(pad=0))]:
         spec = L.LayerSpec(**{**dict(cfg=17, idx=50, name="walkno", N=2, C=8, F=16, H=8, W=8, K=8, keep=0.5), **shape})
         layer = GpuLayer(spec)
