@@ -345,17 +345,18 @@ def layer_table(args, torch, pc, L, stream):
                         continue
                     if best is None or tv < best[0]:
                         best = (tv, nf, wv, cpw, ks, nbuf)
-            for nf, order, ks in [(nf, o, ks) for nf in (1, 2) for o in (1, 2) for ks in (1, 2, 4, 8, 16)]:
-                # the kernel with four columns per lane
+            for nf, order, ks, walk in [(nf, o, ks, wk) for nf in (1, 2) for o in (1, 2) for ks in (1, 2, 4, 8, 16)
+                                        for wk in ((1, 2) if ks == 1 else (1,))]:
+                # the kernel with four columns per lane; walk 1: one workgroup per tile, 2: workgroups walk over the tiles
                 wv = 16
-                t = dict(kernel=pc.KERNEL_QUAD, filters_per_wave=nf, channel_order=order, channel_splits=ks)
+                t = dict(kernel=pc.KERNEL_QUAD, filters_per_wave=nf, channel_order=order, channel_splits=ks, slot_walk=walk)
                 try:
                     _, tv = time_launches(torch, lambda: layer.launch(stream, **t), max(5, steps // 4), 2)
                 except pc.PconvError:
                     continue
-                log(f"  quad nf{nf} order{order} ks{ks}: {tv * 1e3:.1f} us")
+                log(f"  quad nf{nf} order{order} ks{ks} walk{walk}: {tv * 1e3:.1f} us")
                 if best is None or tv < best[0]:
-                    best = (tv, nf, wv, 1, ks, "quad" + ("", "plain", "balanced")[order])
+                    best = (tv, nf, wv, 1, ks, "quad" + ("", "plain", "balanced")[order] + ("", "", "walk")[walk])
         ab = algorithmic_bytes(spec, layer.n_kept)
         row = {"layer": spec.name, "C": spec.C, "F": spec.F, "H": spec.H, "N": spec.N, "stride": spec.stride,
                "dtype": spec.dtype, "keep": spec.keep, "K": spec.K, "n_kept": layer.n_kept, "us": ev * 1e3,

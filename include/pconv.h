@@ -164,7 +164,8 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *                     the parity form of the layer, see pconv_packed_parity_form), PCONV_KERNEL_QUAD (four input
  *                     columns per lane, for layers with many output tiles: unit stride, W a multiple of 4 and at
  *                     most 256; of the fields below it reads filters_per_wave (1 or 2), channel_order (balanced
- *                     orders exist for 16-channel chunks) and channel_splits (0 = 1)) or PCONV_KERNEL_GENERIC (any
+ *                     orders exist for 16-channel chunks), channel_splits (0 = 1, or 2 or 4 where that evens out the
+ *                     rounds of workgroups over the CUs) and slot_walk) or PCONV_KERNEL_GENERIC (any
  *                     stride and pad, straight from global memory).  Automatic: QUAD where it applies and has at
  *                     least 200 workgroups of its own, else TILED, else GENERIC
  *   rows              tiled: output rows held per lane (7)

@@ -1819,25 +1819,13 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
     // within 3 % of them on the VGG-16 shapes at batch 64, slower on most.
     if (FW != 16) return PCONV_EUNSUPPORTED;
     p.NG = (p.F + FW * NF - 1) / (FW * NF);
+    const bool ks_auto = KS == 0;      // decided below, once it is clear that the workgroups do not walk
     KS = std::max(1, std::min(KS, p.nbk));
-    const long long nb = slots * p.NG * KS;
-    if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
-    p.nblocks = (int)nb;
-    p.KS = KS;
-    p.div_KS = make_fastdiv((unsigned)KS);
+    if (slots * p.NG * KS > 0x7FFFFFF0) return PCONV_ESHAPE;
     // pad 1: Wo == W, so a lane's four outputs of a row start at a multiple of four columns and are all inside
     p.vec = (p.pad == 1 && reinterpret_cast<uintptr_t>(p.y) % 16 == 0) ? 1 : 0;
     p.ws = nullptr;
     p.counters = nullptr;
-    if (KS > 1) {
-        // 16 words per lane, filter slot and wave of every tile; one split's part is addressed with 32-bit offsets
-        const size_t split_bytes = (size_t)slots * p.NG * FW * NF * 64 * 16 * sizeof(float);
-        if (split_bytes >= kInvalidOffset) return PCONV_EUNSUPPORTED;
-        if (int rc = ensure_workspace(wp, (size_t)KS * split_bytes / sizeof(float), (size_t)slots * p.NG)) return rc;
-        p.ws = wp->d_ws;
-        p.ws_split_bytes = (unsigned)split_bytes;
-        p.counters = wp->d_counters;
-    }
     // 32-bit byte offsets inside the buffer descriptor: the images one slot can span
     const unsigned long long span = (unsigned long long)((p.BL + p.NRB - 1) / p.NRB + 1);
     if ((unsigned long long)p.img_bytes * span >= 0x7FFFFFFFull) return PCONV_EUNSUPPORTED;
@@ -1857,6 +1845,8 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
     // automatic: one chunk from 1.5 tiles per workgroup on; several chunks from 6 tiles on (measured on the VGG-16
     // layers at batch 64: 2 to 14 % faster there, slower at 3 tiles per workgroup, where the tiles do not divide evenly)
     if (can_walk && (walk == 2 || (walk == 0 && (p.nbk == 1 ? 2 * slots >= 3 * walkers : slots >= 6 * walkers)))) {
+        p.KS = 1;
+        p.div_KS = make_fastdiv(1u);
         p.walkers = (int)walkers;
         p.slots = (int)slots;
         p.out_img_bytes = (unsigned)out_img;
@@ -1882,6 +1872,37 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
         }
         PCONV_HIP(hipGetLastError());
         return PCONV_OK;
+    }
+    if (ks_auto) {
+        // One workgroup per tile: a split of the channels where it evens out the rounds of 256 workgroups (800 tiles
+        // are 3.1 rounds, so four; 1600 half-length workgroups are 6.25, so seven halves).  Cost in chunks: a
+        // workgroup's own chunks plus one for its start and end, plus 1.2 for partial sums and their reduction;
+        // a split is taken from 3 % predicted gain on (VGG-16 conv4_2 at batch 64: 679 -> 643 us measured).
+        const long long tiles = slots * p.NG;
+        double best = 0.0;
+        for (int ks = 1; ks <= std::min(4, p.nbk); ks *= 2) {
+            if (ks > 1 && (unsigned long long)tiles * FW * NF * 4096ull >= kInvalidOffset) break;
+            const double rounds = (double)((tiles * ks + 255) / 256);
+            const double t = rounds * ((double)((p.nbk + ks - 1) / ks) + 1.0 + (ks > 1 ? 1.2 : 0.0));
+            if (best == 0.0 || t < 0.97 * best) {
+                best = t;
+                KS = ks;
+            }
+        }
+    }
+    const long long nb = slots * p.NG * KS;
+    if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
+    p.nblocks = (int)nb;
+    p.KS = KS;
+    p.div_KS = make_fastdiv((unsigned)KS);
+    if (KS > 1) {
+        // 16 words per lane, filter slot and wave of every tile; one split's part is addressed with 32-bit offsets
+        const size_t split_bytes = (size_t)slots * p.NG * FW * NF * 64 * 16 * sizeof(float);
+        if (split_bytes >= kInvalidOffset) return PCONV_EUNSUPPORTED;
+        if (int rc = ensure_workspace(wp, (size_t)KS * split_bytes / sizeof(float), (size_t)slots * p.NG)) return rc;
+        p.ws = wp->d_ws;
+        p.ws_split_bytes = (unsigned)split_bytes;
+        p.counters = wp->d_counters;
     }
     const int grid = (p.nblocks + 7) / 8 * 8;
 #define PCONV_QCASE(NFv, FWv)                                                                           \
@@ -2144,8 +2165,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.perm_stride = 0;
         const int nf = NF == 0 ? 2 : NF;
         const int fw = waves == 0 ? 16 : waves;
-        if (KS < 0) return PCONV_EINVAL;
-        if (KS == 0) KS = 1;
+        if (KS < 0) return PCONV_EINVAL;       // (0: launch_quad decides)
         if (order != PCONV_ORDER_PLAIN) {
             for (const BalancedLayout& b : wp->balanced)
                 if (b.fw == fw && b.nf == nf && b.cc == fw && b.d_ent) {

@@ -287,7 +287,7 @@ def test_quad_kernel_that_walks_over_the_tiles(case, dtype):
         ref = check(layer, x, [walk, dict(walk, channel_order=pc.ORDER_PLAIN)])
         check(layer, x, [walk], relu=True)
         got_walk = layer.run(x, **walk)
-        got_tile = layer.run(x, kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=1)
+        got_tile = layer.run(x, kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=1, channel_splits=1)
         assert np.array_equal(got_walk, got_tile)       # same sums in the same order
         assert got_walk.shape == ref.shape
     layer.free()
@@ -315,7 +315,8 @@ def test_quad_kernel_that_walks_over_tiles_of_several_chunks(case, dtype):
         check(layer, x, [walk], relu=True)
         for order in (pc.ORDER_PLAIN, pc.ORDER_BALANCED):
             got_walk = layer.run(x, channel_order=order, **walk)
-            got_tile = layer.run(x, kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=1, channel_order=order)
+            got_tile = layer.run(x, kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=1, channel_order=order,
+                                 channel_splits=1)
             assert np.array_equal(got_walk, got_tile)       # same sums in the same order
     layer.free()
 
