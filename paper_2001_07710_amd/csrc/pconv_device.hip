@@ -1842,9 +1842,39 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
     if (walk < 0 || walk > 2) return PCONV_EINVAL;
     if (walk == 2 && !can_walk) return PCONV_EUNSUPPORTED;
     const long long walkers = std::min<long long>(slots, std::max(1, 256 / p.NG));
-    // automatic: one chunk from 1.5 tiles per workgroup on; several chunks from 6 tiles on (measured on the VGG-16
-    // layers at batch 64: 2 to 14 % faster there, slower at 3 tiles per workgroup, where the tiles do not divide evenly)
-    if (can_walk && (walk == 2 || (walk == 0 && (p.nbk == 1 ? 2 * slots >= 3 * walkers : slots >= 6 * walkers)))) {
+    // Cost of one workgroup per tile, in chunks: the rounds of 256 workgroups times a workgroup's chunks plus half a
+    // chunk for what it cannot overlap at its start and end, plus 1.2 for partial sums and their reduction if the
+    // channels are split.  A split (automatic: 2 or 4) is taken where it evens out the rounds — 800 tiles are 3.1
+    // rounds, so four; 1600 half-length workgroups are 6.25, so seven halves — from 3 % predicted gain on.
+    const long long tiles = slots * p.NG;
+    auto tile_cost = [&](int ks) {
+        const double rounds = (double)((tiles * ks + 255) / 256);
+        return rounds * ((double)((p.nbk + ks - 1) / ks) + 0.5 + (ks > 1 ? 1.2 : 0.0));
+    };
+    double best_tile = tile_cost(KS);
+    if (ks_auto)
+        for (int ks = 2; ks <= std::min(4, p.nbk); ks *= 2) {
+            if ((unsigned long long)tiles * FW * NF * 4096ull >= kInvalidOffset) break;
+            if (tile_cost(ks) < 0.97 * best_tile) {
+                best_tile = tile_cost(ks);
+                KS = ks;
+            }
+        }
+    // Walking workgroups, automatic.  One chunk: from 1.5 tiles per workgroup on (13 to 32 % faster at batch 4 to 64).
+    // Several chunks: a walker runs its tiles back to back and pays the half chunk once; with an odd number of
+    // tiles the alternation between a heavy and a light filter group leaves it 7 % of a tile off balance.  Measured
+    // on the VGG-16 layers at batch 4 to 64: 2 to 16 % faster where this estimate says so, level elsewhere.
+    bool walking = walk == 2;
+    if (walk == 0 && can_walk) {
+        const long long nt = (slots + walkers - 1) / walkers;      // tiles of the busiest walker
+        if (p.nbk == 1) {
+            walking = 2 * slots >= 3 * walkers;
+        } else {
+            const double walk_cost = (double)nt * p.nbk + 0.5 + (((nt & 1) && p.NG > 1) ? 0.07 * p.nbk : 0.0);
+            walking = nt >= 2 && walk_cost < 0.99 * best_tile;
+        }
+    }
+    if (walking) {
         p.KS = 1;
         p.div_KS = make_fastdiv(1u);
         p.walkers = (int)walkers;
@@ -1872,23 +1902,6 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
         }
         PCONV_HIP(hipGetLastError());
         return PCONV_OK;
-    }
-    if (ks_auto) {
-        // One workgroup per tile: a split of the channels where it evens out the rounds of 256 workgroups (800 tiles
-        // are 3.1 rounds, so four; 1600 half-length workgroups are 6.25, so seven halves).  Cost in chunks: a
-        // workgroup's own chunks plus one for its start and end, plus 1.2 for partial sums and their reduction;
-        // a split is taken from 3 % predicted gain on (VGG-16 conv4_2 at batch 64: 679 -> 643 us measured).
-        const long long tiles = slots * p.NG;
-        double best = 0.0;
-        for (int ks = 1; ks <= std::min(4, p.nbk); ks *= 2) {
-            if (ks > 1 && (unsigned long long)tiles * FW * NF * 4096ull >= kInvalidOffset) break;
-            const double rounds = (double)((tiles * ks + 255) / 256);
-            const double t = rounds * ((double)((p.nbk + ks - 1) / ks) + 1.0 + (ks > 1 ? 1.2 : 0.0));
-            if (best == 0.0 || t < 0.97 * best) {
-                best = t;
-                KS = ks;
-            }
-        }
     }
     const long long nb = slots * p.NG * KS;
     if (nb > 0x7FFFFFF0) return PCONV_ESHAPE;
