@@ -190,7 +190,8 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
  *                     split): 2 = one workgroup per CU and filter group walks over the output tiles, loading the next
  *                     tile's first chunk while it multiplies and stores the current tile (a layer whose channels fit
  *                     one chunk of 16, a network's first layer, also keeps its entries in LDS); 1 = one workgroup per
- *                     tile; 0 = walk if there are at least 1.5 tiles per workgroup (one chunk) or 6 (several chunks)
+ *                     tile; 0 = walk if there are at least 1.5 tiles per workgroup (one chunk), or two and an
+ *                     estimate of both forms' run time favours it (several chunks)
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
 enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2, PCONV_KERNEL_QUAD = 3 };
