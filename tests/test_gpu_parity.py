@@ -321,6 +321,30 @@ def test_quad_kernel_that_walks_over_tiles_of_several_chunks(case, dtype):
     layer.free()
 
 
+def test_walking_kernels_without_a_bias_and_with_empty_filters():
+    """The walking forms with no bias vector, and with filters that keep nothing (their outputs are zero, or the
+    bias), for one chunk and for several."""
+    for C, dtype in ((8, "f16"), (40, "f16"), (40, "f32")):
+        spec = L.LayerSpec(cfg=19, idx=C, name="walkedge", N=6, C=C, F=24, H=12, W=16, pad=1, dtype=dtype, K=8, keep=0.5)
+        w = L.gen_weights(spec)
+        layer = GpuLayer(spec, w=w, use_bias=False)
+        x = L.gen_activations(spec)
+        for nf in (1, 2) if dtype == "f16" else (1,):
+            check(layer, x, [dict(kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=2)])
+        layer.free()
+        layer = GpuLayer(spec, w=w)
+        layer.mask[::3, :] = 0                     # every third filter keeps no kernel at all
+        layer.packed.free()
+        layer.packed = pc.pack(layer.w, layer.lib, layer.pid, layer.mask)
+        layer.wm = oracle.mask_weights(layer.w, layer.pid, layer.mask, layer.lib)
+        for nf in (1, 2) if dtype == "f16" else (1,):
+            t = dict(kernel=pc.KERNEL_QUAD, filters_per_wave=nf, slot_walk=2)
+            check(layer, x, [t])
+            got = layer.run(x, **t)[:, ::3]
+            assert np.array_equal(got, np.broadcast_to(layer.bias[None, ::3, None, None], got.shape).astype(got.dtype))
+        layer.free()
+
+
 def test_walking_is_refused_where_it_does_not_apply():
     for kw, shape in [(dict(filters_per_wave=2), dict(dtype="f32")), (dict(filters_per_wave=1, channel_splits=2), dict(C=40)),
                       (dict(filters_per_wave=1), dict(pad=0))]:
