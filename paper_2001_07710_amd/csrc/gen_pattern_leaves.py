@@ -9,19 +9,25 @@ sections, one per register set.  The section of entry i (set P, the other set is
     waits for what the section before it requested: activations and weights of entry i (in P), header of entry i+1,
     requests from LDS the activations and weights of entry i+1 (into Q) and the header of entry i+2,
     does the 4*R multiply-adds of its pattern on P:   acc[kx][r] += w[q] * x[r + ky]   for every kept tap t = 3*ky + kx,
-    and jumps straight to the section of entry i+1's pattern for set Q (s_setpc to table_Q + code*256), or leaves
-    the loop after the last entry.
+    and jumps straight to the section of entry i+1's pattern for set Q (s_setpc to table_Q + section offset).
 
 So a kept kernel costs one jump and no branch tree, a wave never diverges, and the LDS latency of an entry is covered
 by the multiply-adds of the entry before it: the per-pattern access code of the paper's section 6.2, emitted for
 every possible pattern ahead of time.
 
-Entries are read from LDS (the wave copied them there with the chunk); an entry is 8 dwords:
+Entries are read from LDS, where the wave put them when it staged the chunk; an entry is 8 dwords:
     w0 w1 w2 w3   the four kept weights, taps ascending (fp32)
-    header        bits 0..7: index of the entry's channel inside the staged chunk; bits 8..: pattern code
-    (three unused)
-The loop reads up to two entries past the last one (a header, four weights, one patch); the channel index is masked
-to the chunk size, so these reads stay inside the workgroup's LDS whatever the bytes there, and nothing uses them.
+    header        two words, ready to use: the byte offset of the pattern's section in a table (code * 256) and the
+                  byte offset of the entry's channel in the staged chunk (the kernel derives both from the packed
+                  header — channel index in bits 0..7, pattern code above — when it copies the entries to LDS)
+    (two unused)
+There is no counter: behind a filter's last entry the kernel writes a header whose section number is 255, one past
+the last mask, and slot 255 of either table leaves the loop.  The section of the last entry has then already
+requested "entry" 255's weights, patch (channel offset 0) and the header behind it; nothing uses them, and all of it
+lies inside the LDS region the kernel reserves for a filter's entries (chunk size + 2 of them).
+
+The four-column loop (further down) keeps the packed header (one word, decoded in the section) and a counter: there
+the same change measured 2 % slower.
 
 Registers.  Accumulators: 3*R registers per filter slot, fixed, ending at v127 (slot s of a kernel with NF slots
 starts at v[128 - 3*R*(s+1)]); the kernel limits the compiler's own budget so that it never allocates them.  Scratch
