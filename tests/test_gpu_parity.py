@@ -520,7 +520,7 @@ def test_config4_sweep_points_small_batch(K, keep):
         layer.free()
 
 
-@pytest.mark.parametrize("name", ["conv1_1", "conv1_2", "conv4_2", "conv5_1"])
+@pytest.mark.parametrize("name", ["conv1_1", "conv1_2", "conv2_2", "conv3_2", "conv4_2", "conv5_1"])
 def test_config4_full_batch(name):
     spec = [s for s in L.config4(8, 0.28, N=64) if s.name == name][0]
     layer = GpuLayer(spec)
