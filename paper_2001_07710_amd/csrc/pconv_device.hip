@@ -276,6 +276,17 @@ struct TiledParams {
 
 // (By value on purpose: __builtin_bit_cast applied directly to an element of an ext_vector_type value reads element 0
 // whatever the index, with this compiler.)
+// The value the next lower / next higher lane of the wave holds (lane 0 / lane 63: zero): a data-parallel-primitive
+// move across the whole wavefront, a plain vector instruction, where a shuffle would go through the LDS crossbar and
+// come back a hundred clocks later.  The epilogues hand a lane's outermost partial sums to its neighbours with it.
+__device__ __forceinline__ float from_lane_below(float v) {
+    constexpr int kWaveShiftRight1 = 0x138;     // DPP control: lane i reads lane i - 1
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kWaveShiftRight1, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float from_lane_above(float v) {
+    constexpr int kWaveShiftLeft1 = 0x130;      // DPP control: lane i reads lane i + 1
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kWaveShiftLeft1, 0xF, 0xF, true));
+}
 __device__ __forceinline__ float bits_to_f32(unsigned u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ unsigned f32_to_bits(float f) { return __builtin_bit_cast(unsigned, f); }
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
@@ -583,8 +594,8 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     auto combine = [&](const float (&acc)[3][R], float (&v)[R]) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const float from_left = __shfl_up(acc[0][r], 1, 64);     // lane t-1 holds column ix-1: its kx=0 sum
-            const float from_right = __shfl_down(acc[2][r], 1, 64);  // lane t+1 holds column ix+1: its kx=2 sum
+            const float from_left = from_lane_below(acc[0][r]);     // lane t-1 holds column ix-1: its kx=0 sum
+            const float from_right = from_lane_above(acc[2][r]);  // lane t+1 holds column ix+1: its kx=2 sum
             v[r] = acc[1][r] + from_left + from_right;
         }
     };
@@ -985,8 +996,8 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
     auto row_sums = [&](auto slot_c, auto row_c, float (&v)[4]) {
         float a[6];
         quad_read_acc_row<decltype(slot_c)::value, decltype(row_c)::value>(a);
-        const float from_left = __shfl_up(a[5], 1, 64);     // the left quad's column 5 is this quad's column 1
-        const float from_right = __shfl_down(a[0], 1, 64);  // the right quad's column 0 is this quad's column 4
+        const float from_left = from_lane_below(a[5]);     // the left quad's column 5 is this quad's column 1
+        const float from_right = from_lane_above(a[0]);  // the right quad's column 0 is this quad's column 4
         v[0] = a[1] + (has_left ? from_left : 0.f);
         v[1] = a[2];
         v[2] = a[3];
@@ -1283,8 +1294,8 @@ __device__ __forceinline__ void quad_walk_body(const QuadParams& p) {
             asm volatile("" : "+v"(keep));
             float acc[6];
             quad_read_acc_row<a, r>(acc);
-            const float from_left = __shfl_up(acc[5], 1, 64);
-            const float from_right = __shfl_down(acc[0], 1, 64);
+            const float from_left = from_lane_below(acc[5]);
+            const float from_right = from_lane_above(acc[0]);
             float o[4] = {acc[1] + (has_left ? from_left : 0.f), acc[2], acc[3], acc[4] + (has_right ? from_right : 0.f)};
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
@@ -1477,8 +1488,8 @@ __device__ __forceinline__ void quad_stream_body(const QuadParams& p) {
             constexpr int r = decltype(row_c)::value;
             float acc[6];
             quad_read_acc_row<a, r>(acc);
-            const float from_left = __shfl_up(acc[5], 1, 64);
-            const float from_right = __shfl_down(acc[0], 1, 64);
+            const float from_left = from_lane_below(acc[5]);
+            const float from_right = from_lane_above(acc[0]);
             float o[4] = {acc[1] + (has_left ? from_left : 0.f), acc[2], acc[3], acc[4] + (has_right ? from_right : 0.f)};
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
