@@ -658,16 +658,19 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
 #undef PCONV_PARTIAL
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                 // (also: nobody reads the staged chunk any more, LDS can carry the flag)
-    volatile unsigned* flag = reinterpret_cast<volatile unsigned*>(lds);
+    // (the flag goes through the first word of LDS with plain LDS instructions: a volatile access through the generic
+    // pointer becomes a flat store and load, several hundred clocks slower, on a path every workgroup waits on)
     if (threadIdx.x == 0) {
         const unsigned arrived = __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const bool last = arrived == (unsigned)p.KS - 1u;
         // everybody has arrived: leave the counter ready for the next launch
         if (last) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *flag = last ? 1u : 0u;
+        asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : : "v"(lds0), "v"(last ? 1u : 0u) : "memory");
     }
     __syncthreads();
-    if (*flag == 0u) return;
+    unsigned last_arrival;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(last_arrival) : "v"(lds0) : "memory");
+    if (__builtin_amdgcn_readfirstlane(last_arrival) == 0u) return;   // (the same in every lane)
     // partial sums of up to four splits are requested together, then added in split order
 #define PCONV_REDUCE(a)                                                                             \
     if (pos_base + a * FW < p.F) {                                                                  \
@@ -1095,16 +1098,19 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
 #undef PCONV_QPART
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                 // (also: nobody reads the staged chunk any more, LDS can carry the flag)
-    volatile unsigned* flag = reinterpret_cast<volatile unsigned*>(lds);
+    // (the flag goes through the first word of LDS with plain LDS instructions: a volatile access through the generic
+    // pointer becomes a flat store and load, several hundred clocks slower, on a path every workgroup waits on)
     if (threadIdx.x == 0) {
         const unsigned arrived = __hip_atomic_fetch_add(p.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const bool last = arrived == (unsigned)p.KS - 1u;
         // everybody has arrived: leave the counter ready for the next launch
         if (last) __hip_atomic_store(p.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *flag = last ? 1u : 0u;
+        asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : : "v"(lds0), "v"(last ? 1u : 0u) : "memory");
     }
     __syncthreads();
-    if (*flag == 0u) return;
+    unsigned last_arrival;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(last_arrival) : "v"(lds0) : "memory");
+    if (__builtin_amdgcn_readfirstlane(last_arrival) == 0u) return;   // (the same in every lane)
     // partial sums of up to four splits are requested together (this workgroup's own among them: its stores have
     // been performed), then added in split order
 #define PCONV_QRED(rc, r)                                                                           \
