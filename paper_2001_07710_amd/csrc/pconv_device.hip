@@ -391,7 +391,7 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
     // memory that the workgroup sits through before its first load.)
     asm volatile("" : : "s"(p.x), "s"(p.ent), "s"(p.eptr), "s"(p.forder), "s"(p.perm), "s"(p.perm_stride), "s"(p.nbk),
                  "s"(p.x_bytes), "s"(p.img_bytes), "s"(p.plane_bytes), "s"(p.nblocks), "s"(p.NSEG), "s"(p.C), "s"(p.H),
-                 "s"(p.W));
+                 "s"(p.W), "s"(p.div_NCS.s2), "s"(p.pair));
     if (logical >= p.nblocks) return;
     const int tile = (int)fastdiv((unsigned)logical, p.div_KS);     // (slot, filter group)
     const int split = logical - tile * p.KS;
@@ -882,6 +882,10 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
 
     const int per_xcd = gridDim.x >> 3;   // see tiled_body: the filter groups of one slot share one XCD's L2
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    // (see tiled_body: the kernel arguments of the start-up in one batch)
+    asm volatile("" : : "s"(p.x), "s"(p.ent), "s"(p.eptr), "s"(p.perm), "s"(p.perm_stride), "s"(p.nbk), "s"(p.x_bytes),
+                 "s"(p.img_bytes), "s"(p.plane_bytes), "s"(p.ent_bytes), "s"(p.nblocks), "s"(p.NBLK), "s"(p.C), "s"(p.H),
+                 "s"(p.W), "s"(p.div_NRB.s2));
     if (logical >= p.nblocks) return;
     const int tile = (int)fastdiv((unsigned)logical, p.div_KS);     // (slot, filter group)
     const int split = logical - tile * p.KS;
