@@ -960,7 +960,18 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
                  : p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + k * CC + wave)
                           : (unsigned)(k * CC + wave);
     };
-    auto issue_loads = [&]() {           // the chunk of the last fetch_meta
+    // The loads of a chunk, in two parts: the address unit of the CU accepts one wave's load per 16 clocks, so 16 waves
+    // that issue all their loads at the start of a multiply phase queue for 2 k clocks before the last of them
+    // multiplies.  With two filters per wave the patch rows are requested between the two filters' entries instead,
+    // when the waves are out of step and the unit is idle (the entries stay in front: moving them too costs 2 %).
+    constexpr bool kSplit = NF > 1;
+    unsigned load_soff = 0u;
+    bool load_staged = false;
+    auto issue_row_loads = [&]() {
+#pragma unroll
+        for (int i = 0; i < R + 2; ++i) pre[i].load(rsrc, load_staged ? voff[i] : kInvalidOffset, load_soff);
+    };
+    auto issue_loads_first = [&]() {     // the chunk of the last fetch_meta
         unsigned e0[NF];
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
@@ -975,10 +986,16 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
             const v2u e = __builtin_amdgcn_raw_buffer_load_b64(ent_rsrc, (int)eoff, 0, 0);
             epre[a] = make_uint2(e[0], e[1]);
         }
-        const bool staged = c < (unsigned)p.C;
-        const unsigned soff = staged ? c * p.plane_bytes : 0u;
-#pragma unroll
-        for (int i = 0; i < R + 2; ++i) pre[i].load(rsrc, staged ? voff[i] : kInvalidOffset, soff);
+        load_staged = c < (unsigned)p.C;
+        load_soff = load_staged ? c * p.plane_bytes : 0u;
+        if constexpr (!kSplit) issue_row_loads();
+    };
+    auto issue_loads_rest = [&]() {      // (nothing fetches metadata between the two parts)
+        if constexpr (kSplit) issue_row_loads();
+    };
+    auto issue_loads = [&]() {
+        issue_loads_first();
+        issue_loads_rest();
     };
     auto write_lds = [&]() {
         float4* dst = reinterpret_cast<float4*>(lds + wave * kChB + lane * 16);
@@ -1003,9 +1020,10 @@ __device__ __forceinline__ void quad_body(const QuadParams& p) {
         const bool more = k + 1 < k_end;
 #pragma unroll
         for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
-        if (more) issue_loads();         // chunk k + 1
+        if (more) issue_loads_first();   // chunk k + 1
         const unsigned ent_addr = lds0 + kEntBase + wave * NF * kEntRegion;
         if constexpr (NF > 0) { if (cnt_now[0]) quad_run_entries<NF, 0, CC>(lane_addr, ent_addr, cnt_now[0]); }
+        if (more) issue_loads_rest();
         if constexpr (NF > 1) { if (cnt_now[1]) quad_run_entries<NF, 1, CC>(lane_addr, ent_addr + kEntRegion, cnt_now[1]); }
         fetch_meta(k + 2);               // lands while the workgroup meets at the barriers
         __syncthreads();
@@ -1472,27 +1490,39 @@ __device__ __forceinline__ void quad_stream_body(const QuadParams& p) {
                  : p.perm ? scalar_load_u32(p.perm + (size_t)grp * p.perm_stride + k * CC + wave)
                           : (unsigned)(k * CC + wave);
     };
-    auto issue_loads = [&]() {                    // the chunk of the last fetch_meta, of the tile last aimed at
-        unsigned e0[NF];
+    // (the loads of a chunk in two parts, as in quad_body: entries in front of the first filter's kept kernels, patch
+    // rows behind them)
+    constexpr bool kSplit = NF > 1;               // loads issued behind the first filter's entries
+    unsigned load_soff = 0u, load_rows = 0u;
+    auto issue_entry_loads = [&]() {
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
-            e0[a] = meta_e0[a];
-            ecnt[a] = meta_e1[a] - e0[a];
-        }
-        const unsigned c = meta_c;
-#pragma unroll
-        for (int a = 0; a < NF; ++a) {
-            const unsigned eoff = (unsigned)(lane >> 2) < ecnt[a] ? e0[a] * 32u + (unsigned)lane * 8u : kInvalidOffset;
+            const unsigned eoff = (unsigned)(lane >> 2) < ecnt[a] ? meta_e0[a] * 32u + (unsigned)lane * 8u : kInvalidOffset;
             typedef unsigned v2u __attribute__((ext_vector_type(2)));
             const v2u e = __builtin_amdgcn_raw_buffer_load_b64(ent_rsrc, (int)eoff, 0, 0);
             epre[a] = make_uint2(e[0], e[1]);
         }
-        const bool staged = c < (unsigned)p.C;
-        const unsigned soff = staged ? c * p.plane_bytes : 0u;
-        const unsigned rows = staged ? rows_ok : 0u;
+    };
+    auto issue_row_loads = [&]() {
 #pragma unroll
         for (int i = 0; i < R + 2; ++i)
-            pre[i].load(rsrc, ((rows >> i) & 1u) ? first_off + (unsigned)i * row_bytes : kInvalidOffset, soff);
+            pre[i].load(rsrc, ((load_rows >> i) & 1u) ? first_off + (unsigned)i * row_bytes : kInvalidOffset, load_soff);
+    };
+    auto issue_loads_first = [&]() {              // the chunk of the last fetch_meta, of the tile last aimed at
+#pragma unroll
+        for (int a = 0; a < NF; ++a) ecnt[a] = meta_e1[a] - meta_e0[a];
+        const bool staged = meta_c < (unsigned)p.C;
+        load_soff = staged ? meta_c * p.plane_bytes : 0u;
+        load_rows = staged ? rows_ok : 0u;
+        issue_entry_loads();                      // (measured: moving these back as well costs 2 %)
+        if constexpr (!kSplit) issue_row_loads();
+    };
+    auto issue_loads_rest = [&]() {               // (nothing fetches metadata between the two parts)
+        if constexpr (kSplit) issue_row_loads();
+    };
+    auto issue_loads = [&]() {
+        issue_loads_first();
+        issue_loads_rest();
     };
     auto write_lds = [&]() {
         float4* dst = reinterpret_cast<float4*>(lds + wave * kChB + lane * 16);
@@ -1588,11 +1618,12 @@ __device__ __forceinline__ void quad_stream_body(const QuadParams& p) {
         for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
         if (more) {
             if (lk == 0) aim_at(slot_of(lj));      // (uniform)
-            issue_loads();
+            issue_loads_first();
         }
         step(lj, lk);
         if (k == 0) fetch_filters(group_of(cj));   // (uniform) needed when the tile is stored
         if constexpr (NF > 0) { if (cnt_now[0]) quad_run_entries<NF, 0, CC>(lane_addr, ent_addr, cnt_now[0]); }
+        if (more) issue_loads_rest();
         if constexpr (NF > 1) { if (cnt_now[1]) quad_run_entries<NF, 1, CC>(lane_addr, ent_addr + kEntRegion, cnt_now[1]); }
         fetch_meta(group_of(fj), fk, slot_of(fj) < p.slots);
         step(fj, fk);
