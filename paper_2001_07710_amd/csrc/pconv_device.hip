@@ -487,18 +487,37 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             }
         }
     };
-    auto issue_loads = [&](int k) {
+    // The activations of the channels in staged[].  With two filters per wave and one chunk buffer the main loop
+    // asks for them between the two filters' kept kernels and not in front of both: the address unit of the CU accepts
+    // one wave's load per 16 clocks, and 16 waves that issue 18 loads each at the start of a multiply phase queue
+    // there while nobody multiplies.
+    constexpr bool kSplitLoads = NF > 1 && !DB;
+    auto issue_row_loads = [&]() {
         if constexpr (PAIR) {
-            // parity-form channel 4*c_in + 2*a at this wave's position of the staging order (+1: the odd columns)
-            const unsigned c = channel_at(k * CC + 2 * wave);
-            staged[0] = c < (unsigned)p.C ? c : kNoChannel;
-            staged[1] = c < (unsigned)p.C ? c + 1 : kNoChannel;
+            const unsigned c = staged[0];
             if (c < (unsigned)p.C) {
                 const unsigned soff = (c >> 2) * 4u * p.plane_bytes + ((c >> 1) & 1u) * 2u * p.W * (unsigned)sizeof(T);
 #pragma unroll
                 // kernels of a parity form have taps in their first two rows only: the last patch row is never read
                 for (int i = 0; i < R + 1; ++i) buffer_load_raw2<T>(rsrc, voff[i], soff, pre[0][i], pre[1][i]);
             }
+        } else {
+#pragma unroll
+            for (int j = 0; j < CPW; ++j) {
+                if (staged[j] < (unsigned)p.C) {
+                    const unsigned soff = staged[j] * p.plane_bytes;
+#pragma unroll
+                    for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_raw<T>(rsrc, voff[i], soff);
+                }
+            }
+        }
+    };
+    auto issue_loads = [&](int k, bool defer_rows = false) {
+        if constexpr (PAIR) {
+            // parity-form channel 4*c_in + 2*a at this wave's position of the staging order (+1: the odd columns)
+            const unsigned c = channel_at(k * CC + 2 * wave);
+            staged[0] = c < (unsigned)p.C ? c : kNoChannel;
+            staged[1] = c < (unsigned)p.C ? c + 1 : kNoChannel;
         } else {
             // (what the scalar unit has to fetch first — which channels, where the entries are — is asked for in one
             // go, so that the wave waits for one round trip and not for one per channel and filter)
@@ -513,16 +532,10 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             }
             fetch_entry_ranges(k);
 #pragma unroll
-            for (int j = 0; j < CPW; ++j) {
-                staged[j] = cs[j];
-                if (cs[j] < (unsigned)p.C) {
-                    const unsigned soff = cs[j] * p.plane_bytes;
-#pragma unroll
-                    for (int i = 0; i < R + 2; ++i) pre[j][i] = buffer_load_raw<T>(rsrc, voff[i], soff);
-                }
-            }
+            for (int j = 0; j < CPW; ++j) staged[j] = cs[j];
         }
         if constexpr (PAIR) fetch_entry_ranges(k);
+        if (!(kSplitLoads && defer_rows)) issue_row_loads();
 #pragma unroll
         for (int a = 0; a < NF; ++a) {
             const unsigned cnt = ecnt[a];
@@ -560,10 +573,11 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             if (lane == 0) dst[ecnt[a] * 4u + 2u] = end_marker(PCONV_LEAF_STRIDE);
         }
     };
-    auto compute = [&](int buf, const unsigned (&cnt)[NF]) {
+    auto compute = [&](int buf, const unsigned (&cnt)[NF], bool rows_deferred = false) {
         const unsigned tile_addr = lane_addr + buf * kTileBytes;
         const unsigned ent_addr = lds0 + kEntBase + buf * kEntBytes + wave * NF * kEntRegion;
         if constexpr (NF > 0) { if (cnt[0]) run_entries<NF, 0, PAIR>(tile_addr, ent_addr + 0 * kEntRegion); }
+        if constexpr (kSplitLoads) { if (rows_deferred) issue_row_loads(); }   // (uniform)
         if constexpr (NF > 1) { if (cnt[1]) run_entries<NF, 1, PAIR>(tile_addr, ent_addr + 1 * kEntRegion); }
     };
 
@@ -577,8 +591,8 @@ __device__ __forceinline__ void tiled_body(const TiledParams& p) {
             const bool more = k + 1 < k_end;
 #pragma unroll
             for (int a = 0; a < NF; ++a) cnt_now[a] = ecnt[a];
-            if (more) issue_loads(k + 1);
-            compute(0, cnt_now);
+            if (more) issue_loads(k + 1, true);
+            compute(0, cnt_now, more);
             __syncthreads();           // every wave is done reading chunk k
             if (more) {
                 write_lds(0);
