@@ -520,13 +520,44 @@ def test_config4_sweep_points_small_batch(K, keep):
         layer.free()
 
 
-@pytest.mark.parametrize("name", ["conv1_1", "conv1_2", "conv2_2", "conv3_2", "conv4_2", "conv5_1"])
+_BATCH64 = {}
+
+
+def batch64_activations(spec):
+    """The 64 seeded images of a config-4 layer; they depend on the layer only, not on the sweep point, so the
+    sweep-point tests generate them once per layer."""
+    key = (spec.cfg, spec.idx, spec.N)
+    if key not in _BATCH64:
+        say("generating", spec.name, "batch", spec.N)
+        _BATCH64[key] = L.gen_activations(spec)
+    return _BATCH64[key]
+
+
+# every explicit kernel form that takes the layer at this size, next to the library's own choice
+def full_batch_tunings(spec):
+    forms = [dict(), dict(kernel=T)]
+    if spec.W % 4 == 0:
+        forms.append(dict(kernel=pc.KERNEL_QUAD))
+    return forms
+
+
+@pytest.mark.parametrize("name", [L.VGG16_NAMES[i] for i in L.vgg_distinct_shapes()])
 def test_config4_full_batch(name):
+    """All nine distinct VGG-16 shapes at batch 64 at the sweep's centre point (K = 8, keep 0.28)."""
     spec = [s for s in L.config4(8, 0.28, N=64) if s.name == name][0]
     layer = GpuLayer(spec)
-    say("generating", name, "batch 64")
-    x = L.gen_activations(spec)
-    check_batched(layer, x)
+    check_batched(layer, batch64_activations(spec), full_batch_tunings(spec))
+    layer.free()
+
+
+@pytest.mark.parametrize("K,keep", [(8, 0.5), (8, 0.15), (4, 0.28), (12, 0.28), (4, 0.5), (12, 0.15)])
+@pytest.mark.parametrize("name", ["conv1_2", "conv3_2", "conv4_2", "conv5_1"])
+def test_config4_sweep_points_full_batch(name, K, keep):
+    """The other sweep points at batch 64, in the launch configuration the bench times: the kept fraction and the
+    batch decide between one workgroup per tile, walking workgroups and the channel split."""
+    spec = [s for s in L.config4(K, keep, N=64) if s.name == name][0]
+    layer = GpuLayer(spec)
+    check_batched(layer, batch64_activations(spec), full_batch_tunings(spec))
     layer.free()
 
 
