@@ -153,6 +153,13 @@ void pconv_free(pconv_packed* p);
  * is allocated (hipMalloc, which synchronises) the first time a shape needs it and kept until pconv_free; a later
  * call with the same or a smaller shape allocates nothing.  Because of it, calls that share one handle must not
  * overlap in time: issue them on one stream, or order them with events.
+ *
+ * Other work hidden in a first call.  The first stride-2 call on a handle (per padding) re-packs the layer over the
+ * four parity planes of the input on the host and uploads it (hipMalloc and synchronous copies); a stride-2 call with
+ * an odd H or W, or with a tiling other than the automatic one, also allocates a buffer for the input split into
+ * planes.  When the workspace or that buffer has to grow it is freed and allocated anew (hipFree waits for the
+ * device), so addresses recorded in a HIP graph captured before the growth are stale: run every shape once before
+ * capturing.
  */
 int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W, int stride,
                   int pad, unsigned flags, void* stream);

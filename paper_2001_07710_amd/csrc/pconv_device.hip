@@ -1899,6 +1899,7 @@ template <typename T>
 static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, int KS, int walk, hipStream_t stream) {
     constexpr int R = PCONV_QUAD_ROWS;
     if (p.W % 4 != 0 || p.W / 4 > 64) return PCONV_EUNSUPPORTED;
+    if (NF != 1 && NF != 2) return PCONV_EUNSUPPORTED;   // NG below is computed for the kernels that exist
     p.QW = p.W / 4;
     p.BL = 64 / p.QW;
     p.NRB = (p.Ho + R - 1) / R;
@@ -1981,6 +1982,8 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
             } else if constexpr (sizeof(T) == 2) {
                 PCONV_HIP(allow_big_lds((const void*)quad_walk_kernel_nf2<T>, lds));
                 hipLaunchKernelGGL((quad_walk_kernel_nf2<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+            } else {
+                return PCONV_EUNSUPPORTED;
             }
         } else {
             if (NF == 1) {
@@ -1989,6 +1992,8 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
             } else if constexpr (sizeof(T) == 2) {
                 PCONV_HIP(allow_big_lds((const void*)quad_stream_kernel_nf2<T>, lds));
                 hipLaunchKernelGGL((quad_stream_kernel_nf2<T>), dim3(wgrid), dim3(1024), lds, stream, p);
+            } else {
+                return PCONV_EUNSUPPORTED;
             }
         }
         PCONV_HIP(hipGetLastError());
@@ -2269,6 +2274,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.perm_stride = 0;
         const int nf = NF == 0 ? 2 : NF;
         const int fw = waves == 0 ? 16 : waves;
+        if (nf != 1 && nf != 2) return PCONV_EUNSUPPORTED;
         if (KS < 0) return PCONV_EINVAL;       // (0: launch_quad decides)
         if (order != PCONV_ORDER_PLAIN) {
             for (const BalancedLayout& b : wp->balanced)

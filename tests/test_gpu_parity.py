@@ -354,6 +354,15 @@ def test_walking_is_refused_where_it_does_not_apply():
             layer.run(L.gen_activations(spec), kernel=pc.KERNEL_QUAD, slot_walk=2, **kw)
         assert ei.value.code == pc.EUNSUPPORTED, (kw, shape)
         layer.free()
+    # a number of filters per wave for which the four-column kernel is not built, with and without walking
+    for dtype in ("f32", "f16"):
+        spec = L.LayerSpec(cfg=17, idx=52, name="quadnf", N=2, C=8, F=48, H=8, W=8, K=8, keep=0.5, dtype=dtype)
+        layer = GpuLayer(spec)
+        for walk in (0, 1, 2):
+            with pytest.raises(pc.PconvError) as ei:
+                layer.run(L.gen_activations(spec), kernel=pc.KERNEL_QUAD, filters_per_wave=3, slot_walk=walk)
+            assert ei.value.code == pc.EUNSUPPORTED, (dtype, walk)
+        layer.free()
     # an output pointer that is not 16-byte aligned
     spec = L.LayerSpec(cfg=17, idx=51, name="walkno", N=2, C=8, F=16, H=8, W=8, K=8, keep=0.5)
     layer = GpuLayer(spec)
