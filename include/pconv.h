@@ -44,7 +44,9 @@ enum {
     PCONV_EUNSUPPORTED = -4, /* stride not 1 or 2, pad not 0 or 1 */
     PCONV_ENOMEM = -5,       /* host or device allocation failed */
     PCONV_EHIP = -6,         /* a HIP call failed (pconv_last_hip_error() has the runtime's text) */
-    PCONV_ESTATE = -7        /* handle was packed host-only and has no device copy */
+    PCONV_ESTATE = -7,       /* handle was packed host-only and has no device copy, or (pconv_conv3x3_noalloc) lacks
+                                a form of the layer that only an allocating call can build */
+    PCONV_ESCRATCH = -8      /* pconv_conv3x3_noalloc: the launch needs more scratch than the fixed arena holds */
 };
 
 enum { PCONV_FLAG_RELU = 1u };      /* conv flags: y = max(y, 0) after the bias */
@@ -159,10 +161,29 @@ void pconv_free(pconv_packed* p);
  * an odd H or W, or with a tiling other than the automatic one, also allocates a buffer for the input split into
  * planes.  When the workspace or that buffer has to grow it is freed and allocated anew (hipFree waits for the
  * device), so addresses recorded in a HIP graph captured before the growth are stale: run every shape once before
- * capturing.
+ * capturing, or use pconv_conv3x3_noalloc.
  */
 int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W, int stride,
                   int pad, unsigned flags, void* stream);
+
+/*
+ * pconv_conv3x3 for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same results bit for bit; the call makes no hipMalloc, hipFree or
+ * other allocating call.  Where pconv_conv3x3 would split the input channels of a tile over several workgroups, the
+ * partial sums and arrival counters live in a fixed device array of pconv_noalloc_scratch_bytes() bytes (24 MiB
+ * of partial sums and 16384 tile counters) that every GPU the library runs on holds until the process ends, instead
+ * of the handle's workspace; the counters the launch uses are cleared by a small kernel on `stream` first.
+ *   - a launch whose split needs more than that returns PCONV_ESCRATCH and launches nothing (on the VGG-16 and
+ *     ResNet-50 shapes the split is taken at small batch only and needs at most 8 MiB);
+ *   - stride 2 needs the layer re-packed over parity planes, which pconv_conv3x3 builds (and allocates) on its first
+ *     stride-2 call with that padding on the handle: without it this call returns PCONV_ESTATE; an odd H or W would
+ *     also need a plane buffer and returns PCONV_ESCRATCH unless an earlier allocating call left one large enough;
+ *   - all calls on one GPU share that GPU's array, whatever their handle: calls that overlap in time on one GPU race
+ *     (issue them on one stream, or order them with events).
+ */
+int pconv_conv3x3_noalloc(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
+                          int stride, int pad, unsigned flags, void* stream);
+size_t pconv_noalloc_scratch_bytes(void);
 
 /*
  * pconv_conv3x3 with the kernel choice in the caller's hands, for tuning sweeps and for tests that must reach every

@@ -18,7 +18,7 @@ FLAG_RELU = 1
 PACK_HOST_ONLY = 1
 KERNEL_AUTO, KERNEL_TILED, KERNEL_GENERIC, KERNEL_QUAD = 0, 1, 2, 3
 ORDER_AUTO, ORDER_PLAIN, ORDER_BALANCED = 0, 1, 2
-OK, EINVAL, EPATTERN, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, EPATTERN, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE, ESCRATCH = 0, -1, -2, -3, -4, -5, -6, -7, -8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpconv.so")
@@ -69,11 +69,14 @@ def _load():
     lib.pconv_free.argtypes = [vp]
     lib.pconv_free.restype = None
     lib.pconv_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp]
+    lib.pconv_conv3x3_noalloc.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp]
+    lib.pconv_noalloc_scratch_bytes.argtypes = []
+    lib.pconv_noalloc_scratch_bytes.restype = ctypes.c_size_t
     lib.pconv_conv3x3_tuned.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp, ctypes.POINTER(_Tuning)]
     lib.pconv_dense_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, u, vp]
     lib.pconv_maxpool2x2.argtypes = [vp, vp, i, i, i, i, i, vp]
     for name in ("pconv_assign_patterns", "pconv_select_connectivity", "pconv_pack", "pconv_packed_export",
-                 "pconv_packed_stats", "pconv_packed_parity_form", "pconv_packed_library", "pconv_conv3x3", "pconv_conv3x3_tuned", "pconv_dense_conv3x3",
+                 "pconv_packed_stats", "pconv_packed_parity_form", "pconv_packed_library", "pconv_conv3x3", "pconv_conv3x3_noalloc", "pconv_conv3x3_tuned", "pconv_dense_conv3x3",
                  "pconv_maxpool2x2"):
         getattr(lib, name).restype = i
     lib.pconv_strerror.argtypes = [i]
@@ -219,6 +222,16 @@ def conv3x3(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad
             stream: int = 0):
     _check(_load().pconv_conv3x3(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, pad, flags, stream or None),
            "pconv_conv3x3")
+
+
+def conv3x3_noalloc(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad: int = 1, flags: int = 0,
+                    stream: int = 0):
+    _check(_load().pconv_conv3x3_noalloc(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, pad, flags,
+                                         stream or None), "pconv_conv3x3_noalloc")
+
+
+def noalloc_scratch_bytes() -> int:
+    return int(_load().pconv_noalloc_scratch_bytes())
 
 
 def conv3x3_tuned(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad: int = 1, flags: int = 0,

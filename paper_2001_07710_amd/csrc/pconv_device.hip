@@ -16,6 +16,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 
 #include "pconv_internal.h"
@@ -118,6 +119,80 @@ static int ensure_workspace(const pconv_packed* p, size_t floats, size_t counter
         PCONV_HIP(hipMemset(p->d_counters, 0, counters * sizeof(unsigned)));
         p->n_counters = counters;
     }
+    return PCONV_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// the fixed arena of pconv_conv3x3_noalloc
+//
+// Callers that may not allocate (code under HIP graph capture, serving loops, harnesses that forbid hipMalloc) get the
+// channel split's partial sums and arrival counters from a file-scope device array instead of the handle's growing
+// workspace.  Every GPU the library runs on holds its own copy of the array, at its own address, until the process
+// ends; the address is looked up once per device (hipGetSymbolAddress with that device current) and host code only
+// ever uses the looked-up pointer.  Layout: kArenaCounters arrival counters, then kArenaFloats partial sums.
+// ---------------------------------------------------------------------------------------------------------------
+
+constexpr size_t kArenaCounters = 16384;            // one per output tile of a split launch
+constexpr size_t kArenaFloats = (size_t)6 << 20;    // 24 MiB of partial sums
+constexpr size_t kArenaBytes = kArenaCounters * sizeof(unsigned) + kArenaFloats * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kArenaBytes];
+
+struct WsArena {
+    float* ws;
+    size_t floats;
+    unsigned* counters;
+    size_t n_counters;
+};
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_arena_mutex;
+static void* g_arena_ptr[kMaxDevices] = {};
+
+// The arena of the current device.
+static int current_arena(WsArena* out) {
+    int dev = -1;
+    PCONV_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return PCONV_EUNSUPPORTED;
+    void* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_arena_mutex);
+        if (!g_arena_ptr[dev]) {
+            void* ptr = nullptr;
+            PCONV_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+            if (!ptr) return PCONV_EHIP;
+            g_arena_ptr[dev] = ptr;
+        }
+        base = g_arena_ptr[dev];
+    }
+    out->counters = static_cast<unsigned*>(base);
+    out->n_counters = kArenaCounters;
+    out->ws = reinterpret_cast<float*>(static_cast<unsigned char*>(base) + kArenaCounters * sizeof(unsigned));
+    out->floats = kArenaFloats;
+    return PCONV_OK;
+}
+
+__global__ __launch_bounds__(256) void clear_counters_kernel(unsigned* counters, unsigned n) {
+    const unsigned i = blockIdx.x * 256u + threadIdx.x;
+    if (i < n) counters[i] = 0u;
+}
+
+// Partial-sum workspace and arrival counters for a split launch: the handle's own (grown on demand) or, when the
+// caller may not allocate, the fixed arena, whose counters are cleared on the launch stream first (the arena keeps
+// what the last call left, and a launch that was aborted may have left counters that are not zero).
+static int get_workspace(const pconv_packed* wp, const WsArena* arena, size_t floats, size_t counters, float** ws,
+                         unsigned** cnt, hipStream_t stream) {
+    if (!arena) {
+        if (int rc = ensure_workspace(wp, floats, counters)) return rc;
+        *ws = wp->d_ws;
+        *cnt = wp->d_counters;
+        return PCONV_OK;
+    }
+    if (floats > arena->floats || counters > arena->n_counters) return PCONV_ESCRATCH;
+    hipLaunchKernelGGL(clear_counters_kernel, dim3((unsigned)((counters + 255) / 256)), dim3(256), 0, stream,
+                       arena->counters, (unsigned)counters);
+    PCONV_HIP(hipGetLastError());
+    *ws = arena->ws;
+    *cnt = arena->counters;
     return PCONV_OK;
 }
 
@@ -1828,7 +1903,7 @@ static int launch_tiled_inst(K kern, const TiledParams& p, int waves, int NF, in
 
 template <typename T>
 static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int waves, int CPW, int KS, int buffers,
-                        hipStream_t stream) {
+                        hipStream_t stream, const WsArena* arena) {
     const int CC = CPW * waves;
     if (CC % kBucket != 0) return PCONV_EUNSUPPORTED;   // a chunk is a whole number of buckets
     const int NB = CC / kBucket;
@@ -1868,10 +1943,10 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
         // eight words per lane, filter slot and wave of every tile; one split's part is addressed with 32-bit offsets
         const size_t split_bytes = (size_t)slots * p.NG * waves * NF * 64 * 8 * sizeof(float);
         if (split_bytes >= kInvalidOffset) return PCONV_EUNSUPPORTED;
-        if (int rc = ensure_workspace(wp, (size_t)KS * split_bytes / sizeof(float), (size_t)slots * p.NG)) return rc;
-        p.ws = wp->d_ws;
+        if (int rc = get_workspace(wp, arena, (size_t)KS * split_bytes / sizeof(float), (size_t)slots * p.NG, &p.ws,
+                                   &p.counters, stream))
+            return rc;
         p.ws_split_bytes = (unsigned)split_bytes;
-        p.counters = wp->d_counters;
     }
     // (filters per wave, channels per wave and chunk, buckets per chunk); waves = 16 * NB / CPW
 #define PCONV_CASE(FF, PP, BB) \
@@ -1896,7 +1971,8 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
 
 // walk: 0 = automatic, 1 = never, 2 = always: quad_walk_kernel instead of quad_kernel_nf1
 template <typename T>
-static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, int KS, int walk, hipStream_t stream) {
+static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, int KS, int walk, hipStream_t stream,
+                       const WsArena* arena) {
     constexpr int R = PCONV_QUAD_ROWS;
     if (p.W % 4 != 0 || p.W / 4 > 64) return PCONV_EUNSUPPORTED;
     if (NF != 1 && NF != 2) return PCONV_EUNSUPPORTED;   // NG below is computed for the kernels that exist
@@ -2008,10 +2084,10 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
         // 16 words per lane, filter slot and wave of every tile; one split's part is addressed with 32-bit offsets
         const size_t split_bytes = (size_t)slots * p.NG * FW * NF * 64 * 16 * sizeof(float);
         if (split_bytes >= kInvalidOffset) return PCONV_EUNSUPPORTED;
-        if (int rc = ensure_workspace(wp, (size_t)KS * split_bytes / sizeof(float), (size_t)slots * p.NG)) return rc;
-        p.ws = wp->d_ws;
+        if (int rc = get_workspace(wp, arena, (size_t)KS * split_bytes / sizeof(float), (size_t)slots * p.NG, &p.ws,
+                                   &p.counters, stream))
+            return rc;
         p.ws_split_bytes = (unsigned)split_bytes;
-        p.counters = wp->d_counters;
     }
     const int grid = (p.nblocks + 7) / 8 * 8;
 #define PCONV_QCASE(NFv, FWv)                                                                           \
@@ -2074,9 +2150,11 @@ static int check_conv_args(const void* x, const void* y, int N, int C, int F, in
     return PCONV_OK;
 }
 
-extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H,
-                                   int W, int stride, int pad, unsigned flags, void* stream,
-                                   const pconv_tuning* tuning) {
+// `arena` null: the handle's own workspace, allocated and grown on demand.  Otherwise the call allocates nothing:
+// split launches take their workspace from the arena, and a form of the layer that is not there yet is an error.
+static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
+                        int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning,
+                        const WsArena* arena) {
     if (!wp) return PCONV_EINVAL;
     int Ho = 0, Wo = 0;
     if (int rc = check_conv_args(x, y, N, wp->C, wp->F, H, W, stride, pad, flags, &Ho, &Wo)) return rc;
@@ -2142,6 +2220,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
                       (automatic || (waves == 16 && (CPW == 0 || CPW == 2)));
     if (kernel == PCONV_KERNEL_TILED && stride == 2) {
         if (!wp->by_parity[pad]) {
+            if (arena) return PCONV_ESTATE;   // re-packing the layer over parity planes allocates and uploads
             pconv_packed* child = nullptr;
             if (int rc = derive_for_stride2(wp, pad, true, &child)) return rc;
             wp->by_parity[pad] = child;
@@ -2150,6 +2229,7 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     }
     if (kernel == PCONV_KERNEL_TILED && stride == 2 && !pair) {
         const size_t need = (size_t)N * tC * tH * tW * esize;
+        if (need > wp->planes_bytes && arena) return PCONV_ESCRATCH;
         if (need > wp->planes_bytes) {
             if (wp->d_planes) PCONV_HIP(hipFree(wp->d_planes));   // hipFree waits for work that may still use it
             wp->d_planes = nullptr;
@@ -2246,8 +2326,8 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.x_bytes = (unsigned long long)N * lay->C * tH * tW * esize;
         p.img_bytes = (unsigned)((size_t)lay->C * tH * tW * esize);
         p.plane_bytes = (unsigned)((size_t)tH * tW * esize);
-        return lay->dtype == PCONV_F16 ? launch_tiled<__half>(p, lay, NF, waves, CPW, KS, buffers, st)
-                                      : launch_tiled<float>(p, lay, NF, waves, CPW, KS, buffers, st);
+        return lay->dtype == PCONV_F16 ? launch_tiled<__half>(p, lay, NF, waves, CPW, KS, buffers, st, arena)
+                                      : launch_tiled<float>(p, lay, NF, waves, CPW, KS, buffers, st, arena);
     }
     if (kernel == PCONV_KERNEL_QUAD) {
         if (stride != 1) return PCONV_EUNSUPPORTED;
@@ -2294,8 +2374,8 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
         p.img_bytes = (unsigned)((size_t)wp->C * H * W * esize);
         p.plane_bytes = (unsigned)((size_t)H * W * esize);
         const int walk = tuning ? tuning->slot_walk : 0;
-        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, wp, nf, fw, KS, walk, st)
-                                      : launch_quad<float>(p, wp, nf, fw, KS, walk, st);
+        return wp->dtype == PCONV_F16 ? launch_quad<__half>(p, wp, nf, fw, KS, walk, st, arena)
+                                      : launch_quad<float>(p, wp, nf, fw, KS, walk, st, arena);
     }
     if (kernel != PCONV_KERNEL_GENERIC) return PCONV_EINVAL;
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)wp->F, (unsigned)N);
@@ -2309,10 +2389,25 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
     return PCONV_OK;
 }
 
+extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H,
+                                   int W, int stride, int pad, unsigned flags, void* stream,
+                                   const pconv_tuning* tuning) {
+    return conv3x3_impl(x, y, wp, bias, N, H, W, stride, pad, flags, stream, tuning, nullptr);
+}
+
 extern "C" int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                              int stride, int pad, unsigned flags, void* stream) {
-    return pconv_conv3x3_tuned(x, y, wp, bias, N, H, W, stride, pad, flags, stream, nullptr);
+    return conv3x3_impl(x, y, wp, bias, N, H, W, stride, pad, flags, stream, nullptr, nullptr);
 }
+
+extern "C" int pconv_conv3x3_noalloc(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H,
+                                     int W, int stride, int pad, unsigned flags, void* stream) {
+    WsArena arena{};
+    if (int rc = current_arena(&arena)) return rc;
+    return conv3x3_impl(x, y, wp, bias, N, H, W, stride, pad, flags, stream, nullptr, &arena);
+}
+
+extern "C" size_t pconv_noalloc_scratch_bytes(void) { return kArenaBytes; }
 
 extern "C" int pconv_dense_conv3x3(const void* x, void* y, const void* w, const float* bias, int dtype, int N, int C,
                                    int F, int H, int W, int stride, int pad, unsigned flags, void* stream) {

@@ -530,7 +530,8 @@ extern "C" const char* pconv_strerror(int code) {
         case PCONV_EUNSUPPORTED: return "unsupported stride (1 or 2) or pad (0 or 1)";
         case PCONV_ENOMEM: return "out of memory";
         case PCONV_EHIP: return "HIP runtime error (see pconv_last_hip_error)";
-        case PCONV_ESTATE: return "packed handle has no device copy (packed host-only) or belongs to another device";
+        case PCONV_ESTATE: return "packed handle has no device copy (packed host-only), belongs to another device, or lacks a form of the layer that only an allocating call can build";
+        case PCONV_ESCRATCH: return "the launch needs more scratch memory than the fixed arena of pconv_conv3x3_noalloc holds";
         default: return "unknown pconv error code";
     }
 }
