@@ -49,7 +49,8 @@ enum {
     PCONV_ESCRATCH = -8      /* pconv_conv3x3_noalloc: the launch needs more scratch than the fixed arena holds */
 };
 
-enum { PCONV_FLAG_RELU = 1u };      /* conv flags: y = max(y, 0) after the bias */
+enum { PCONV_FLAG_RELU = 1u,        /* conv flags: y = max(y, 0) after the bias */
+       PCONV_FLAG_DENSE_DIRECT = 2u /* pconv_dense_conv3x3 only: the plain direct kernel also for fp16 storage */ };
 enum { PCONV_PACK_HOST_ONLY = 1u }; /* pack flags: build the packed form on the host, allocate nothing on the device */
 
 /*
@@ -220,9 +221,16 @@ size_t pconv_noalloc_scratch_bytes(void);
  *                     one chunk of 16, a network's first layer, also keeps its entries in LDS); 1 = one workgroup per
  *                     tile; 0 = walk if there are at least 1.5 tiles per workgroup (one chunk), or two and an
  *                     estimate of both forms' run time favours it (several chunks)
+ *   mfma_shape        PCONV_KERNEL_MFMA (fp16 storage only; any stride and pad): the layer as a dense contraction
+ *                     over its masked weights on the matrix cores, the automatic choice for fp16 storage.  Workgroup
+ *                     tile: 0 = chosen by the library, 1 = 128 filters x 448 output pixels, 2 = 64 x 448,
+ *                     3 = 128 x 224, 4 = 64 x 224.  `rows` (0 = as many as fit) caps the output rows per tile.
+ *                     Non-finite activations reach every output whose 3x3 window holds them, also through weights
+ *                     that are pruned (0 * inf), which the vector kernels skip.
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
-enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2, PCONV_KERNEL_QUAD = 3 };
+enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2, PCONV_KERNEL_QUAD = 3,
+       PCONV_KERNEL_MFMA = 4 };
 enum { PCONV_ORDER_AUTO = 0, PCONV_ORDER_PLAIN = 1, PCONV_ORDER_BALANCED = 2 };
 typedef struct pconv_tuning {
     int kernel;
@@ -234,6 +242,7 @@ typedef struct pconv_tuning {
     int channel_splits;
     int buffers;
     int slot_walk;
+    int mfma_shape;
 } pconv_tuning;
 int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                         int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning);
@@ -242,6 +251,10 @@ int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const fl
  * Dense 3x3 convolution of the same shape, for comparison: all nine taps of all F*C kernels (give it the masked
  * dense tensor to compute the same function as pconv_conv3x3).  Same conventions and argument meaning.
  *   w_oihw  device, dtype[F*C*9]
+ * fp16 storage runs on the matrix cores (the kernel of PCONV_KERNEL_MFMA on nine taps): each call first copies the
+ * weights into that kernel's order, in a buffer the library keeps per device and grows on demand (hipMalloc on
+ * growth), so calls that overlap in time on one device race.  fp32 storage, and fp16 with PCONV_FLAG_DENSE_DIRECT,
+ * run a plain direct kernel on the vector ALUs (one thread per output, no tiling): a cross-check, not a fast kernel.
  */
 int pconv_dense_conv3x3(const void* x, void* y, const void* w_oihw, const float* bias, int dtype, int N, int C, int F,
                         int H, int W, int stride, int pad, unsigned flags, void* stream);

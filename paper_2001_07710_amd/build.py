@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpconv.so")
-SOURCES = ["pconv_host.cpp", "pconv_device.hip"]
+SOURCES = ["pconv_host.cpp", "pconv_device.hip", "pconv_mfma.hip"]
 
 # Packed fp32 instructions are switched off for every HIP translation unit of this project.
 HIPCC_FLAGS = [

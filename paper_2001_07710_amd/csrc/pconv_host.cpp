@@ -240,6 +240,48 @@ void build_balanced(const pconv_packed* p, int fw, int nf, int cc, pconv::Balanc
     out->eptr[(size_t)F * nch] = (uint32_t)d;
 }
 
+// The layer's weights in matrix-core order for workgroup tiles of mt filters (see pconv::MfmaWeights), from the
+// canonical arrays.  fp16 storage only: the 16-bit patterns are copied as they are.
+void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) {
+    const int F = p->F, C = p->C, K = p->K;
+    out->mt = mt;
+    out->n_mtiles = (F + mt - 1) / mt;
+    out->n_cblocks = (C + 15) / 16;
+    // taps that occur: the union of the masks of the patterns that have kept kernels
+    unsigned present = 0;
+    for (int i = 0; i < F; ++i)
+        for (int j = 0; j < K; ++j)
+            if (p->grp_ptr[(size_t)i * K + j + 1] > p->grp_ptr[(size_t)i * K + j]) present |= p->lib[(size_t)j];
+    int slot_of[9];
+    out->n_taps = 0;
+    for (int t = 0; t < 9; ++t) {
+        slot_of[t] = -1;
+        if ((present >> t) & 1u) {
+            slot_of[t] = out->n_taps;
+            out->taps[out->n_taps++] = (uint8_t)t;
+        }
+    }
+    const int nt = out->n_taps;
+    out->w.assign((size_t)out->n_mtiles * out->n_cblocks * nt * 2 * mt * 8, 0);
+    for (int i = 0; i < F; ++i) {
+        const uint32_t f = p->filter_order[(size_t)i];
+        const size_t tile = f / (uint32_t)mt, fl = f % (uint32_t)mt;
+        for (int j = 0; j < K; ++j) {
+            int taps[4], q = 0;
+            for (int t = 0; t < 9; ++t)
+                if ((p->lib[(size_t)j] >> t) & 1u) taps[q++] = t;
+            for (uint32_t e = p->grp_ptr[(size_t)i * K + j]; e < p->grp_ptr[(size_t)i * K + j + 1]; ++e) {
+                const size_t c = p->cin[e], cb = c / 16, kb = (c % 16) / 8, c8 = c % 8;
+                for (int k = 0; k < q; ++k) {
+                    const size_t ts = (size_t)slot_of[taps[k]];
+                    const size_t at = ((((tile * out->n_cblocks + cb) * nt + ts) * 2 + kb) * mt + fl) * 8 + c8;
+                    std::memcpy(&out->w[at], &p->w4[((size_t)e * 4 + k) * 2], 2);
+                }
+            }
+        }
+    }
+}
+
 }  // namespace
 
 // pconv_pack, and the packing of a layer re-packed over parity planes (`partial`: masks of one to four taps, up to
@@ -322,7 +364,8 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
         p->ent.resize(n_kept);
         p->ent_of_canonical.resize(n_kept);
         p->eptr.assign((size_t)F * p->n_buckets + 1, 0);
-        std::vector<uint32_t> cursor((size_t)K);
+        std::vector<uint32_t> cursor((size_t)K), code_of((size_t)K);
+        for (int j = 0; j < K; ++j) code_of[(size_t)j] = mask_rank(lib[j]);
         size_t d = 0;
         for (int i = 0; i < F; ++i) {
             for (int j = 0; j < K; ++j) cursor[(size_t)j] = p->grp_ptr[(size_t)i * K + j];
@@ -346,7 +389,7 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
                         }
                         de.c = p->cin[cur];
                         de.mask9 = lib[j];
-                        de.code = mask_rank(lib[j]);
+                        de.code = code_of[(size_t)j];
                         de.hdr = (de.c & 0xFFu) | (de.code << 8);
                         ++cur;
                     }
@@ -361,6 +404,11 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
         p->balanced.resize(5);
         for (int t = 0; t < 5; ++t)
             build_balanced(p, tilings[t][0], tilings[t][1], tilings[t][2], &p->balanced[(size_t)t]);
+        if (dtype == PCONV_F16 && !partial) {
+            const int nh = (int)(sizeof(pconv::kMfmaTileHeights) / sizeof(int));
+            p->mfma.resize((size_t)nh);
+            for (int h = 0; h < nh; ++h) build_mfma_weights(p, pconv::kMfmaTileHeights[h], &p->mfma[(size_t)h]);
+        }
     } catch (const std::bad_alloc&) {
         delete p;
         return PCONV_ENOMEM;

@@ -47,6 +47,21 @@ struct BalancedLayout {
 
 constexpr uint32_t kNoChannel = 0xFFFFFFFFu;
 
+// The layer's weights as the matrix-core kernel (fp16 storage) stages them: dense over the taps that occur in the
+// layer, explicit zeros where a kernel is removed or a tap lies outside its pattern.  For workgroup tiles of `mt`
+// filters: w[m-tile][c-block of 16][tap slot][half of the c-block (8 channels)][filter in tile][8 channels], fp16,
+// so that the weights one workgroup needs for one c-block are one contiguous piece that is copied to LDS as it is,
+// and a lane's operand of v_mfma_f32_32x32x16_f16 (8 consecutive channels of one filter and tap) is 16 contiguous
+// bytes.  Filters beyond F and channels beyond C are zero.
+struct MfmaWeights {
+    int mt = 0;
+    int n_mtiles = 0, n_cblocks = 0, n_taps = 0;
+    uint8_t taps[9] = {};             // tap index t = 3*ky + kx of every tap slot, ascending
+    std::vector<uint16_t> w;          // host copy (fp16 bit patterns)
+    void* d_w = nullptr;
+    size_t bytes() const { return w.size() * sizeof(uint16_t); }
+};
+
 }  // namespace pconv
 
 struct pconv_packed {
@@ -68,6 +83,9 @@ struct pconv_packed {
 
     // balanced layouts for the tilings that the automatic choice uses (see pconv::BalancedLayout)
     std::vector<pconv::BalancedLayout> balanced;
+
+    // fp16 storage only: the weights in matrix-core order, one copy per workgroup tile height (see MfmaWeights)
+    std::vector<pconv::MfmaWeights> mfma;
 
     // Workspace of the tiled kernel when it splits the input channels of one output tile over several workgroups:
     // their partial sums and one arrival counter per tile.  Grown on demand by the convolution call, so calls that
@@ -95,6 +113,27 @@ namespace pconv {
 // is the plane x[c][2i+a][2j+b]; tap (ky,kx) of kernel (f,c) becomes tap (ky',kx') of kernel (f, 4*c + 2*a + b) with
 // a = (ky-pad) mod 2, ky' = floor((ky-pad)/2) + pad, likewise for columns.  Weights keep their storage type.
 int derive_for_stride2(const pconv_packed* p, int pad, bool upload, pconv_packed** out);
+// implemented in pconv_mfma.hip: the matrix-core kernel for fp16 storage
+struct MfmaConv {
+    const void* x;
+    void* y;
+    const float* bias;          // device, or null
+    const void* d_w;            // MfmaWeights::d_w
+    int mt, n_taps;
+    uint8_t taps[9];
+    int N, C, F, H, W, Ho, Wo, stride, pad, relu;
+    int shape;                  // 0: chosen by the library; 1..kMfmaShapes: a tile shape of mfma_shape_table()
+    int rows;                   // 0: as many output rows per tile as fit; else that many
+    int walk;                   // 1: one workgroup per tile; otherwise persistent workgroups that walk over the tiles
+};
+constexpr int kMfmaShapes = 4;
+// tile heights (filters per workgroup) that the kernel's tile shapes use; weights are kept for each
+constexpr int kMfmaTileHeights[2] = {128, 64};
+bool mfma_applicable(const MfmaConv& a);
+int launch_mfma_conv(const MfmaConv& a, void* stream);
+// dense fp16 weights OIHW on the device -> MfmaWeights order for tile height mt, all nine taps (the dense baseline)
+int launch_mfma_arrange(const void* w_oihw, void* out, int F, int C, int mt, void* stream);
+size_t mfma_weight_bytes(int F, int C, int mt, int n_taps);
 // implemented in pconv_device.hip
 int upload_packed(pconv_packed* p);
 void release_device(pconv_packed* p);

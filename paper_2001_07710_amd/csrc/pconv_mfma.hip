@@ -1,0 +1,735 @@
+// Matrix-core kernel of libpconv for fp16 storage on gfx950 (MI355X): the pruned layer as an implicit GEMM on
+// v_mfma_f32_32x32x16_f16, fp32 accumulation.
+//
+// Why a dense contraction for a sparse layer.  Pattern and connectivity sparsity leave 4/9 * keep of the weights
+// (12 % at the paper's 8x compression), unstructured at the granularity of a matrix-core operand: for a tile of 32
+// filters and 16 channels of one tap, the chance that all 512 weights are pruned is nil, and no re-ordering of
+// filters or channels changes that for connectivity chosen by kernel norm.  So the matrix cores can only run the
+// layer as the dense convolution with explicit zeros that it equals (section 3 of the paper: pruning is a mask on the
+// weights) -- and on this chip that is still the faster way for fp16 storage: 2.5 PFLOP/s of fp16 MFMA against
+// 157 TFLOP/s of fp32 vector multiply-adds is a factor of 16, the layer has 8 times fewer multiply-adds.  What the
+// sparsity still buys here: taps that no kept kernel of the layer uses are skipped altogether.
+//
+// Roles.  D[filter][pixel] += A[filter][channel] * B[channel][pixel] per tap: A = weights, B = activations shifted by
+// the tap.  With that assignment a lane of the result holds one pixel and its registers hold filters, so NCHW rows
+// are contiguous across lanes.
+//
+// Tile.  A workgroup of WM x WN waves owns MT = WM*AF*32 filters and R consecutive output rows of the batch (rows
+// numbered n*Ho + oy, so a tile may run from one image into the next) = up to NT = WN*BF*32 output pixels; a wave
+// owns AF x BF operand tiles of 32 x 32.  Channels are taken in blocks of 16 (one MFMA K step); per block the
+// workgroup stages, in LDS, the weights of its filters for every tap and the input rows that its pixels read.
+//
+// LDS layouts (both double-buffered; one barrier per channel block).
+//   weights      [tap slot][half: channels 0-7 | 8-15][filter in tile][8 channels]   as they lie in global memory
+//   activations  [half][input row slot][position = column + pad][8 channels]         channel-minor, 16 B per position
+// A lane's operand (8 consecutive channels of one filter, or of one pixel) is one 128-bit LDS read; lanes that are
+// neighbours in the filter or pixel index read neighbouring 16-byte pieces, so the reads are free of bank
+// conflicts, and a tap is nothing but a constant added to the pixel's byte offset: stride 2, either padding and any
+// image width come for free.  The activations arrive from global memory row by row (NCHW: pixel-minor), 1, 2 or 4
+// pixels of one channel per load; a lane gathers the same pixels of 8 channels and interleaves them in registers
+// (v_perm_b32) before the 128-bit LDS writes.  Positions left and right of the image are zeroed once per tile; rows
+// above and below it, images beyond the batch and channels beyond C are loads at an offset outside the buffer
+// descriptor, which return zero.
+//
+// Epilogue.  Bias, ReLU and the rounding to fp16 in registers; the tile goes through LDS once more, [filter][pixel],
+// and leaves in pieces of 8, 4, 2 or 1 pixels of one filter per lane (whatever divides the row length), coalesced.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+
+#include "pconv_internal.h"
+
+namespace pconv {
+
+#define PCONV_HIP(call)                                  \
+    do {                                                 \
+        hipError_t e_ = (call);                          \
+        if (e_ != hipSuccess) {                          \
+            pconv::set_hip_error(#call, (int)e_);        \
+            return PCONV_EHIP;                           \
+        }                                                \
+    } while (0)
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+
+#ifndef PCONV_VARIANT
+#define PCONV_VARIANT 0
+#endif
+constexpr uint32_t kInvalid = 0x80000000u;
+
+// Division by a divisor fixed for the launch (Granlund and Montgomery's round-up method, exact for 32-bit dividends).
+struct FastDiv {
+    unsigned m, s1, s2;
+};
+FastDiv make_fastdiv(unsigned d) {
+    unsigned l = 0;
+    while ((1ull << l) < d) ++l;
+    FastDiv f;
+    f.m = (unsigned)((((1ull << l) - d) << 32) / d + 1);
+    f.s1 = l < 1 ? l : 1;
+    f.s2 = l > 0 ? l - 1 : 0;
+    return f;
+}
+__device__ __forceinline__ unsigned fastdiv(unsigned x, const FastDiv& f) {
+    const unsigned t = __umulhi(x, f.m);
+    return (t + ((x - t) >> f.s1)) >> f.s2;
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+struct MfmaParams {
+    const unsigned char* x;
+    unsigned char* y;
+    const float* bias;
+    const unsigned char* wq;
+    int N, C, F, H, W, Ho, Wo, stride, pad, relu;
+    int CB;                 // channel blocks of 16
+    int nt;                 // tap slots
+    int tap_off[9];         // byte offset of a tap inside an activation plane: (ky*PW + kx) * 16
+    int R;                  // output rows (of the batch, n*Ho + oy) per tile
+    int PW;                 // positions per input row slot: W + 2*pad
+    int max_slots;          // input row slots reserved per buffer
+    int cnt_full;           // input row slots of a whole image: (Ho-1)*stride + 3
+    int tiles_n, tiles_m;
+    int G;                  // pieces per input row: W / LW
+    int a_bytes;            // weights of one channel block: nt * 2 * MT * 16
+    int plane_bytes;        // one half (8 channels) of the activations of one block: max_slots * PW * 16
+    int bias_off;           // byte offset in LDS of the bias values (three tiles), behind the staging buffers
+    int sw;                 // pixels per store piece: 8, 4, 2 or 1
+    unsigned long long x_bytes;
+    unsigned wq_bytes;
+    unsigned chan_bytes;    // H*W*2
+    unsigned img_bytes;     // C*H*W*2
+    FastDiv div_Wo, div_Ho, div_G, div_cnt_full, div_tiles_m, div_sw_groups;
+    int sw_groups;          // store pieces per output row: Wo / sw
+};
+
+template <int LW>
+struct Piece;   // LW pixels of one channel, as loaded
+template <>
+struct Piece<8> {
+    uint4v v;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+    }
+    __device__ __forceinline__ unsigned dword(int i) const { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+};
+template <>
+struct Piece<4> {
+    uint2v v;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
+    }
+    __device__ __forceinline__ unsigned dword(int i) const { return i ? v.y : v.x; }
+};
+template <>
+struct Piece<2> {
+    unsigned v;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        v = __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
+    }
+    __device__ __forceinline__ unsigned dword(int) const { return v; }
+};
+template <>
+struct Piece<1> {
+    unsigned v;
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+        v = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
+    }
+    __device__ __forceinline__ unsigned dword(int) const { return v; }
+};
+
+// pixel `px` (0: low halves, 1: high halves) of two channels' dwords -> one dword {channel a, channel b}
+__device__ __forceinline__ unsigned interleave(unsigned a, unsigned b, int px) {
+    return px ? __builtin_amdgcn_perm(b, a, 0x07060302u) : __builtin_amdgcn_perm(b, a, 0x05040100u);
+}
+
+// Geometry of one tile (all wave-uniform): the m-tile, and the R consecutive output rows of the batch it covers.
+struct TileGeo {
+    int tm;            // which MT filters
+    int Rv;            // output rows in the tile (the last tile of the batch may have fewer than R)
+    int n0, oy0;       // image and row of its first output row
+    int cnt0;          // input row slots of the part in image n0
+    int used_slots;    // input row slots in all
+};
+
+// KI: staging pieces of the activations per lane and channel block.  FULL: all nine taps occur; the channel block is
+// then one straight run of code in which the loads of the next block are issued a few at a time between the MFMAs.
+//
+// Workgroups are persistent: workgroup w takes tiles w, w + G, w + 2G, ... and runs the (tile, channel block) pairs of
+// all of them as one sequence, so the first block of the next tile is loaded while the last block of the current one
+// is multiplied, and the stores of a tile drain while the next tile is computed.
+template <int AF, int BF, int WM, int WN, int LW, int KI, bool FULL>
+__global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams p) {
+    constexpr int kItems = KI;
+    constexpr int NW = WM * WN, NTH = NW * 64, MT = WM * AF * 32, HALF = NTH / 2;
+    constexpr int WPIECES = (9 * 2 * MT + NTH - 1) / NTH;      // 16-byte pieces of weights per lane and block, at most
+    constexpr int WP = BF * 32 + 8;                            // halves between two filters of a wave's output window
+    extern __shared__ __align__(16) unsigned char lds[];
+
+    // ---- which tiles: consecutive workgroup ids go round the XCDs; workgroups of one XCD get consecutive tiles, so
+    // the m-tiles of one n-tile (which read the same activations) and n-tiles that are neighbours in memory share
+    // an L2.  gridDim.x is a multiple of 8.
+    const unsigned nwg = gridDim.x;
+    const unsigned w0 = (blockIdx.x & 7u) * (nwg >> 3) + (blockIdx.x >> 3);
+    const unsigned ntiles = (unsigned)p.tiles_n * (unsigned)p.tiles_m;
+    if (w0 >= ntiles) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (tells the compiler that it is wave-uniform)
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int s = p.stride, Ho = p.Ho, Wo = p.Wo, PW = p.PW;
+
+    auto geometry = [&](unsigned T) {
+        TileGeo g;
+        const unsigned tn = fastdiv(T, p.div_tiles_m);
+        g.tm = (int)(T - tn * (unsigned)p.tiles_m);
+        const int R0 = (int)tn * p.R;
+        g.Rv = min(p.R, p.N * Ho - R0);
+        g.n0 = (int)fastdiv((unsigned)R0, p.div_Ho);
+        g.oy0 = R0 - g.n0 * Ho;
+        const int rows0 = min(g.Rv, Ho - g.oy0);                   // rows in the first image
+        g.cnt0 = (rows0 - 1) * s + 3;
+        const int last_g = (int)fastdiv((unsigned)(g.oy0 + g.Rv - 1), p.div_Ho);
+        const int rows_last = last_g == 0 ? rows0 : g.oy0 + g.Rv - last_g * Ho;
+        g.used_slots = last_g == 0 ? g.cnt0 : g.cnt0 + (last_g - 1) * p.cnt_full + (rows_last - 1) * s + 3;
+        return g;
+    };
+
+    unsigned char* const ldsA = lds;
+    unsigned char* const ldsB = lds + 2 * p.a_bytes;
+    float* const ldsBias = reinterpret_cast<float*>(lds + p.bias_off);          // [3][MT]: by tile count modulo 3
+    _Float16* const win = reinterpret_cast<_Float16*>(lds + p.bias_off + 3 * MT * 4) + wave * (8 * WP);
+
+    // ---- once: zero columns left and right of the image (no tile's staging ever writes them)
+    if (p.pad) {
+        const uint4v zero = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < p.max_slots * 8; i += NTH) {
+            const int sl = i >> 3, which = i & 7;               // buffer (2) x half (2) x side (2)
+            const int pos = (which & 1) ? PW - 1 : 0;
+            *reinterpret_cast<uint4v*>(ldsB + (which >> 1) * p.plane_bytes + (sl * PW + pos) * 16) = zero;
+        }
+    }
+    auto stage_bias = [&](int tm, int slot) {
+        for (int i = tid; i < MT; i += NTH) {
+            const int f = tm * MT + i;
+            ldsBias[slot * MT + i] = (p.bias && f < p.F) ? p.bias[f] : 0.f;
+        }
+    };
+
+    // ---- staging state: descriptors of this lane for the tile whose blocks are being loaded
+    const int kbs = wave >= NW / 2 ? 1 : 0;                     // which half of the block's channels this wave stages
+    const int ltid = tid - kbs * HALF;
+    uint32_t goff[kItems];
+    int loff[kItems];
+    int stage_tm = 0;
+    bool stage_on = !(PCONV_VARIANT & 32);                      // false: nothing left to load (offsets outside)
+    // (the descriptor of x is put together where it is used, from three scalars that are marked wave-uniform: as a
+    // variable that changes from tile to tile the compiler would keep it in vector registers and wrap every load in
+    // a loop over its distinct values)
+    unsigned xb_lo = 0, xb_hi = 0, x_records = 0;
+    const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.wq_bytes);
+    auto stage_descriptors = [&](const TileGeo& g) {
+        stage_tm = g.tm;
+#pragma unroll
+        for (int i = 0; i < kItems; ++i) {
+            const unsigned it = (unsigned)(ltid + i * HALF);
+            const unsigned sl = fastdiv(it, p.div_G), gg = it - sl * (unsigned)p.G;
+            goff[i] = kInvalid;
+            loff[i] = -1;
+            if ((int)sl < g.used_slots) {
+                int seg, iy;
+                if ((int)sl < g.cnt0) {
+                    seg = 0;
+                    iy = g.oy0 * s - p.pad + (int)sl;
+                } else {
+                    const unsigned t = sl - (unsigned)g.cnt0, q = fastdiv(t, p.div_cnt_full);
+                    seg = 1 + (int)q;
+                    iy = (int)(t - q * (unsigned)p.cnt_full) - p.pad;
+                }
+                if (g.n0 + seg < p.N && iy >= 0 && iy < p.H)
+                    goff[i] = (uint32_t)seg * p.img_bytes + (uint32_t)(iy * p.W + (int)gg * LW) * 2u;
+                loff[i] = kbs * p.plane_bytes + ((int)sl * PW + p.pad + (int)gg * LW) * 16;
+            }
+        }
+        // (at most 2^31 - 1 bytes, so that the offset that stands for "nothing to load" is outside whatever the
+        // tensor's size; the host has checked that the images one tile touches end below that)
+        const unsigned long long x_off = (unsigned long long)g.n0 * p.img_bytes;
+        const unsigned long long x_left = p.x_bytes - x_off;
+        const unsigned long long xb = reinterpret_cast<unsigned long long>(p.x) + x_off;
+        xb_lo = __builtin_amdgcn_readfirstlane((unsigned)xb);
+        xb_hi = __builtin_amdgcn_readfirstlane((unsigned)(xb >> 32));
+        x_records = __builtin_amdgcn_readfirstlane(x_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (unsigned)x_left);
+    };
+
+    Piece<LW> stg[kItems][8];
+    uint4v wst[WPIECES];
+    const int w_pieces = p.a_bytes >> 4;
+
+    // One of the loads of channel block cb: j < 8*kItems: channel j%8 of piece j/8 of the activations; then the
+    // 16-byte pieces of the weights.
+    constexpr int NLOADS = 8 * kItems + WPIECES;
+    auto issue_one = [&](int cb, int j) {
+        if (PCONV_VARIANT & 2) return;
+        if (j < 8 * kItems) {
+            const int i = j >> 3, ch = j & 7;
+            const int chan = cb * 16 + kbs * 8 + ch;
+            const __amdgpu_buffer_rsrc_t xr =
+                make_rsrc(reinterpret_cast<const void*>(((unsigned long long)xb_hi << 32) | xb_lo), x_records);
+            stg[i][ch].load(xr, (chan < p.C && stage_on) ? goff[i] : kInvalid, (uint32_t)chan * p.chan_bytes);
+        } else {
+            const int piece = tid + (j - 8 * kItems) * NTH;
+            const uint32_t wsoff = (uint32_t)((stage_tm * p.CB + cb) * p.a_bytes);
+            wst[j - 8 * kItems] = __builtin_amdgcn_raw_buffer_load_b128(
+                wr, (piece < w_pieces && stage_on) ? piece * 16 : (int)kInvalid, (int)wsoff, 0);
+        }
+    };
+    auto write_lds = [&](int buf) {
+        if (PCONV_VARIANT & 4) return;
+        unsigned char* const b = ldsB + buf * 2 * p.plane_bytes;
+#pragma unroll
+        for (int i = 0; i < kItems; ++i) {
+            if (loff[i] >= 0) {
+#pragma unroll
+                for (int px = 0; px < LW; ++px) {
+                    uint4v v;
+                    v.x = interleave(stg[i][0].dword(px >> 1), stg[i][1].dword(px >> 1), px & 1);
+                    v.y = interleave(stg[i][2].dword(px >> 1), stg[i][3].dword(px >> 1), px & 1);
+                    v.z = interleave(stg[i][4].dword(px >> 1), stg[i][5].dword(px >> 1), px & 1);
+                    v.w = interleave(stg[i][6].dword(px >> 1), stg[i][7].dword(px >> 1), px & 1);
+                    *reinterpret_cast<uint4v*>(b + loff[i] + px * 16) = v;
+                }
+            }
+        }
+        unsigned char* const a = ldsA + buf * p.a_bytes;
+#pragma unroll
+        for (int j = 0; j < WPIECES; ++j) {
+            const int piece = tid + j * NTH;
+            if (piece < w_pieces) *reinterpret_cast<uint4v*>(a + piece * 16) = wst[j];
+        }
+    };
+
+    // ---- compute state: operand offsets of this lane for the tile being multiplied
+    const int li = lane & 31, lk = lane >> 5;                   // row/column of the operand tile, half of its K
+    const int aoff = (lk * MT + wm * AF * 32 + li) * 16;
+    int boff[BF];
+    auto compute_descriptors = [&](const TileGeo& g) {
+#pragma unroll
+        for (int bf = 0; bf < BF; ++bf) {
+            const unsigned q = (unsigned)((wn * BF + bf) * 32 + li);
+            const unsigned r = fastdiv(q, p.div_Wo), ox = q - r * (unsigned)Wo;
+            int off = 0;
+            if ((int)r < g.Rv) {
+                const unsigned rr = (unsigned)g.oy0 + r, sg = fastdiv(rr, p.div_Ho), oy = rr - sg * (unsigned)Ho;
+                const int slot = sg == 0 ? (int)r * s : g.cnt0 + ((int)sg - 1) * p.cnt_full + (int)oy * s;
+                off = (slot * PW + (int)ox * s) * 16;
+            }
+            boff[bf] = off + lk * p.plane_bytes;
+        }
+    };
+
+    float16v acc[AF][BF];
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int af = 0; af < AF; ++af)
+#pragma unroll
+            for (int bf = 0; bf < BF; ++bf)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[af][bf][r] = 0.f;
+    };
+
+    // Bias, ReLU, fp16; eight filters of the wave's pixels at a time through the wave's own window in LDS
+    // ([filter][pixel]), from where they leave in pieces of sw pixels of one filter per lane.  No workgroup barrier:
+    // a wave reads back only what it wrote itself, and LDS operations of one wave complete in order.
+    auto epilogue = [&](const TileGeo& g, int bias_slot) {
+        // (the lane index as the compiler cannot see through it: everything below depends on it and is computed
+        // here, not ahead of the channel blocks, where it would sit in registers that the multiply loop needs)
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int li = lane_e & 31, lk = lane_e >> 5, lane = lane_e;
+        const float* const bias = ldsBias + bias_slot * MT;
+        const size_t plane = (size_t)Ho * Wo;
+        const int valid = g.Rv * Wo - wn * BF * 32;              // pixels of the wave's range that exist
+        const int groups = valid <= 0 ? 0 : min(valid, BF * 32) / p.sw;   // store pieces per filter (sw divides Wo)
+        _Float16* const ytile = reinterpret_cast<_Float16*>(p.y) + (size_t)g.n0 * p.F * plane;
+#pragma unroll
+        for (int af = 0; af < AF; ++af) {
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int fbase = (wm * AF + af) * 32 + rq * 8;          // first of the eight filters, in the tile
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float bv = bias[fbase + lk * 4 + i];
+#pragma unroll
+                    for (int bf = 0; bf < BF; ++bf) {
+                        float v = acc[af][bf][rq * 4 + i] + bv;
+                        if (p.relu) v = fmaxf(v, 0.f);
+                        win[(lk * 4 + i) * WP + bf * 32 + li] = (_Float16)v;
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+                if (!(PCONV_VARIANT & 8)) {
+                    // where a piece of pixels of filter fi goes, or null
+                    auto target = [&](int fi, int gq) -> _Float16* {
+                        const int f = g.tm * MT + fbase + fi;
+                        if (f >= p.F || gq >= groups) return nullptr;
+                        const unsigned q0 = (unsigned)(wn * BF * 32 + gq * p.sw);      // pixel in the tile
+                        const unsigned row = fastdiv(q0, p.div_Wo), ox = q0 - row * (unsigned)Wo;
+                        const unsigned rr = (unsigned)g.oy0 + row, sg = fastdiv(rr, p.div_Ho), oy = rr - sg * (unsigned)Ho;
+                        return ytile + ((size_t)sg * p.F + (size_t)f) * plane + (size_t)oy * Wo + ox;
+                    };
+                    if (p.sw == 8) {        // at most 28 pieces per filter: two filters per pass of the wave
+                        for (int k = 0; k < 4; ++k) {
+                            const int fi = 2 * k + (lane >> 5), gq = lane & 31;
+                            if (_Float16* dst = target(fi, gq))
+                                *reinterpret_cast<uint4v*>(dst) = *reinterpret_cast<const uint4v*>(win + fi * WP + gq * 8);
+                        }
+                    } else {
+                        for (int fi = 0; fi < 8; ++fi)
+                            for (int gq = lane; gq < groups; gq += 64)
+                                if (_Float16* dst = target(fi, gq)) {
+                                    const _Float16* src = win + fi * WP + gq * p.sw;
+                                    if (p.sw == 4) *reinterpret_cast<uint2v*>(dst) = *reinterpret_cast<const uint2v*>(src);
+                                    else if (p.sw == 2) *reinterpret_cast<unsigned*>(dst) = *reinterpret_cast<const unsigned*>(src);
+                                    else *dst = *src;
+                                }
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    };
+
+    // ---- the sequence of (tile, channel block) pairs
+    unsigned T = w0;
+    TileGeo gc = geometry(T);
+    stage_descriptors(gc);
+    stage_bias(gc.tm, 0);
+#pragma unroll
+    for (int j = 0; j < NLOADS; ++j) issue_one(0, j);
+    write_lds(0);
+    __syncthreads();
+    compute_descriptors(gc);
+    clear_acc();
+#ifndef PCONV_SPAN_TAPS
+#define PCONV_SPAN_TAPS 7
+#endif
+    constexpr int SPAN_TAPS = PCONV_SPAN_TAPS;
+    int buf = 0, bias_slot = 0;
+    for (;;) {
+        const unsigned Tn = T + nwg;
+        TileGeo gn = gc;
+        for (int cb = 0; cb < p.CB; ++cb) {
+            // what is loaded during this block: the tile's next block, or the first block of the workgroup's next
+            // tile, or (behind the last tile) nothing
+            int ncb = cb + 1;
+            if (ncb == p.CB) {
+                ncb = 0;
+                if (Tn < ntiles) {
+                    gn = geometry(Tn);
+                    stage_descriptors(gn);
+                    stage_bias(gn.tm, bias_slot == 2 ? 0 : bias_slot + 1);
+                } else {
+                    stage_on = false;
+                }
+            }
+            const unsigned char* const a = ldsA + buf * p.a_bytes + aoff;
+            const unsigned char* const b = ldsB + buf * 2 * p.plane_bytes;
+            auto load_a = [&](int ts, int af) {
+                return *reinterpret_cast<const half8*>(a + (ts * 2 * MT + af * 32) * 16);
+            };
+            auto load_b = [&](int ts, int bf) {
+                return *reinterpret_cast<const half8*>(b + boff[bf] + p.tap_off[ts]);
+            };
+            if constexpr (FULL) {
+                // One straight run of code for the nine taps.  The operands of a tap sit in one set of registers for
+                // the activations and two for the weights; as soon as the MFMAs that read an activation operand
+                // have been issued, the same registers are asked to fetch that operand of the next tap, which leaves
+                // the LDS a whole tap's time to answer.  The loads of the next channel block are issued one at a
+                // time between those groups, evenly over the first SPAN_TAPS taps.  The order is pinned group by
+                // group: left alone, the scheduler hoists reads and address arithmetic far ahead, and the registers
+                // that costs are paid for with spills to memory in this loop.
+                half8 fa[2][AF], fb[BF];
+#pragma unroll
+                for (int af = 0; af < AF; ++af) fa[0][af] = load_a(0, af);
+#pragma unroll
+                for (int bf = 0; bf < BF; ++bf) fb[bf] = load_b(0, bf);
+                constexpr int NGROUPS = SPAN_TAPS * BF;          // (tap, activation operand) groups that carry loads
+#pragma unroll
+                for (int ts = 0; ts < 9; ++ts) {
+#pragma unroll
+                    for (int bf = 0; bf < BF; ++bf) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (!(PCONV_VARIANT & 1)) {
+#pragma unroll
+                            for (int af = 0; af < AF; ++af)
+                                acc[af][bf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ts & 1][af], fb[bf], acc[af][bf], 0, 0, 0);
+                        }
+                        if (ts < 8) {
+                            if (!(PCONV_VARIANT & 16)) fb[bf] = load_b(ts + 1, bf);
+                            if (bf < AF && !(PCONV_VARIANT & 16)) fa[(ts + 1) & 1][bf] = load_a(ts + 1, bf);
+                        }
+#pragma unroll
+                        for (int j = 0; j < NLOADS; ++j)
+                            if ((j * NGROUPS) / NLOADS == ts * BF + bf) issue_one(ncb, j);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                half8 fa[2][AF], fb[2][BF];
+                auto fetch = [&](int ts, int set) {
+#pragma unroll
+                    for (int af = 0; af < AF; ++af) fa[set][af] = load_a(ts, af);
+#pragma unroll
+                    for (int bf = 0; bf < BF; ++bf) fb[set][bf] = load_b(ts, bf);
+                };
+                fetch(0, 0);
+#pragma unroll
+                for (int j = 0; j < NLOADS; ++j) issue_one(ncb, j);
+#pragma unroll
+                for (int ts = 0; ts < 9; ++ts) {
+                    if (ts < p.nt) {
+                        if (ts + 1 < p.nt) fetch(ts + 1, (ts + 1) & 1);
+                        if (!(PCONV_VARIANT & 1)) {
+#pragma unroll
+                            for (int bf = 0; bf < BF; ++bf)
+#pragma unroll
+                                for (int af = 0; af < AF; ++af)
+                                    acc[af][bf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ts & 1][af], fb[ts & 1][bf],
+                                                                                        acc[af][bf], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+            write_lds(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+        epilogue(gc, bias_slot);
+        if (Tn >= ntiles) break;
+        T = Tn;
+        gc = gn;
+        bias_slot = bias_slot == 2 ? 0 : bias_slot + 1;
+        compute_descriptors(gc);
+        clear_acc();
+    }
+}
+
+// dense OIHW fp16 weights on the device -> MfmaWeights order, all nine taps
+__global__ __launch_bounds__(256) void mfma_arrange_kernel(const unsigned short* __restrict__ w, unsigned short* __restrict__ out,
+                                                           int F, int C, int mt, int CB, long long total) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        long long r = i;
+        const int c8 = (int)(r % 8); r /= 8;
+        const int fl = (int)(r % mt); r /= mt;
+        const int kb = (int)(r % 2); r /= 2;
+        const int ts = (int)(r % 9); r /= 9;
+        const int cb = (int)(r % CB); r /= CB;
+        const int f = (int)r * mt + fl, c = cb * 16 + kb * 8 + c8;
+        out[i] = (f < F && c < C) ? w[((size_t)f * C + c) * 9 + ts] : (unsigned short)0;
+    }
+}
+
+struct Shape {
+    int af, bf, wm, wn;
+};
+
+// Compute units of the current device (asked once per device).
+int compute_units() {
+    static std::mutex mu;
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!cached[dev]) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+// tile shapes: (128 filters x 448 pixels), (64 x 448), (128 x 224), (64 x 224)
+const Shape kShapes[kMfmaShapes] = {{2, 7, 2, 2}, {1, 7, 2, 2}, {1, 7, 4, 1}, {1, 7, 2, 1}};
+
+// Workgroups of the persistent grid: as many as the device holds at once (compute units x workgroups that fit one),
+// no more than there are tiles, a multiple of 8 (one share per XCD).
+int persistent_grid(const void* kern, int threads, size_t lds, long long ntiles, int walk) {
+    if (walk == 1) return (int)std::min<long long>((ntiles + 7) / 8 * 8, 0x7FFFFFF8);   // one workgroup per tile
+    int per_cu = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, lds) != hipSuccess || per_cu < 1) per_cu = 1;
+    const long long resident = (long long)compute_units() * per_cu / 8 * 8;
+    return (int)std::max<long long>(8, std::min<long long>((ntiles + 7) / 8 * 8, resident));
+}
+
+template <int AF, int BF, int WM, int WN>
+int launch_shape(const MfmaParams& p, int lw, int ki, size_t lds, int walk, hipStream_t st) {
+    const bool full = p.nt == 9;
+    const long long ntiles = (long long)p.tiles_n * p.tiles_m;
+#define PCONV_MFMA_CASE1(LWv, KIv, FULLv)                                                                       \
+    if (lw == LWv && ki == KIv && full == FULLv) {                                                              \
+        auto kern = mfma_conv_kernel<AF, BF, WM, WN, LWv, KIv, FULLv>;                                          \
+        if (lds > 64 * 1024)                                                                                    \
+            PCONV_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+        const int grid = persistent_grid((const void*)kern, WM * WN * 64, lds, ntiles, walk);                        \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(WM* WN * 64), lds, st, p);                                    \
+        PCONV_HIP(hipGetLastError());                                                                           \
+        return PCONV_OK;                                                                                        \
+    }
+#define PCONV_MFMA_CASE(LWv, KIv) PCONV_MFMA_CASE1(LWv, KIv, true) PCONV_MFMA_CASE1(LWv, KIv, false)
+    PCONV_MFMA_CASE(8, 1) PCONV_MFMA_CASE(8, 2) PCONV_MFMA_CASE(4, 2) PCONV_MFMA_CASE(4, 3) PCONV_MFMA_CASE(2, 3)
+    PCONV_MFMA_CASE(1, 3)
+#undef PCONV_MFMA_CASE
+#undef PCONV_MFMA_CASE1
+    return PCONV_EUNSUPPORTED;
+}
+
+// Fills the launch parameters for one tile shape; false if the shape cannot take the layer.
+bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, int* ki_out, size_t* lds_out,
+          int* grid_out) {
+    const Shape& sh = kShapes[shape];
+    const int MT = sh.wm * sh.af * 32, NT = sh.wn * sh.bf * 32, NTH = sh.wm * sh.wn * 64;
+    if (MT != a.mt) return false;
+    MfmaParams p{};
+    p.x = static_cast<const unsigned char*>(a.x);
+    p.y = static_cast<unsigned char*>(a.y);
+    p.bias = a.bias;
+    p.wq = static_cast<const unsigned char*>(a.d_w);
+    p.N = a.N; p.C = a.C; p.F = a.F; p.H = a.H; p.W = a.W; p.Ho = a.Ho; p.Wo = a.Wo;
+    p.stride = a.stride; p.pad = a.pad; p.relu = a.relu;
+    p.CB = (a.C + 15) / 16;
+    p.nt = a.n_taps;
+    if (p.nt < 0 || p.nt > 9) return false;
+    if (a.Wo > NT) return false;                                   // a tile is made of whole output rows
+    int R = NT / a.Wo;
+    if (rows > 0) R = std::min(R, rows);
+    const long long total_rows = (long long)a.N * a.Ho;
+    if (total_rows > 0x3FFFFFFF) return false;
+    R = (int)std::min<long long>(R, total_rows);
+    const uintptr_t xa = reinterpret_cast<uintptr_t>(a.x), ya = reinterpret_cast<uintptr_t>(a.y);
+    int lw = (a.W % 8 == 0 && xa % 16 == 0) ? 8 : (a.W % 4 == 0 && xa % 8 == 0) ? 4 : (a.W % 2 == 0 && xa % 4 == 0) ? 2 : 1;
+    // pieces of the activations per lane that the kernels are built for, by load width
+    auto max_items = [](int w) { return w == 8 ? 2 : 3; };
+    p.PW = a.W + 2 * a.pad;
+    p.cnt_full = (a.Ho - 1) * a.stride + 3;
+    // rows per tile: as many as fit the pixels of the tile, the staging pieces of a lane and the LDS
+    // Input row slots: a tile of R output rows that touches k images needs (R - k)*stride + 3k of them, most for the
+    // largest k: at most (R + Ho - 2)/Ho + 1 images, and no more than it has rows.
+    size_t lds = 0;
+    int segs = 1;
+    for (;; --R) {
+        if (R < 1) return false;
+        segs = std::min(R, (R + a.Ho - 2) / a.Ho + 1);
+        p.max_slots = (R - segs) * a.stride + 3 * segs;
+        p.a_bytes = p.nt * 2 * MT * 16;
+        p.plane_bytes = p.max_slots * p.PW * 16;
+        const size_t staging = 2 * (size_t)p.a_bytes + 4 * (size_t)p.plane_bytes;
+        p.bias_off = (int)staging;
+        // behind the staging buffers: the bias of three tiles, and per wave a window of 8 filters x its pixels
+        lds = staging + 3 * (size_t)MT * 4 + (size_t)(NTH / 64) * 8 * (sh.bf * 32 + 8) * 2;
+        if (lds > 160 * 1024) continue;
+        // widest loads whose pieces fit the lanes; fewer rows only when even the narrowest fit nowhere
+        int w = lw;
+        while (w > 1 && (long long)p.max_slots * (a.W / w) > (long long)max_items(w) * (NTH / 2)) w /= 2;
+        if ((long long)p.max_slots * (a.W / w) <= (long long)max_items(w) * (NTH / 2)) {
+            lw = w;
+            break;
+        }
+    }
+    p.G = a.W / lw;
+    const int need_items = (int)(((long long)p.max_slots * p.G + NTH / 2 - 1) / (NTH / 2));
+    const int ki = lw == 8 ? std::max(need_items, 1) : lw == 4 ? std::max(need_items, 2) : 3;
+    p.R = R;
+    p.tiles_n = (int)((total_rows + R - 1) / R);
+    p.tiles_m = (a.F + MT - 1) / MT;
+    p.sw = (a.Wo % 8 == 0 && ya % 16 == 0) ? 8 : (a.Wo % 4 == 0 && ya % 8 == 0) ? 4 : (a.Wo % 2 == 0 && ya % 4 == 0) ? 2 : 1;
+    p.sw_groups = a.Wo / p.sw;
+    for (int t = 0; t < p.nt; ++t) p.tap_off[t] = ((a.taps[t] / 3) * p.PW + a.taps[t] % 3) * 16;
+    p.x_bytes = (unsigned long long)a.N * a.C * a.H * a.W * 2ull;
+    p.chan_bytes = (unsigned)((size_t)a.H * a.W * 2);
+    const unsigned long long img = (unsigned long long)a.C * a.H * a.W * 2ull;
+    if (img * (unsigned long long)(segs + 1) >= 0x7FFFFFFFull) return false;   // 32-bit offsets inside a tile's images
+    p.img_bytes = (unsigned)img;
+    const size_t wq_bytes = mfma_weight_bytes(a.F, a.C, MT, p.nt);
+    if (wq_bytes >= 0x7FFFFFFFull) return false;
+    p.wq_bytes = (unsigned)wq_bytes;
+    p.div_Wo = make_fastdiv((unsigned)a.Wo);
+    p.div_Ho = make_fastdiv((unsigned)a.Ho);
+    p.div_G = make_fastdiv((unsigned)p.G);
+    p.div_cnt_full = make_fastdiv((unsigned)p.cnt_full);
+    p.div_tiles_m = make_fastdiv((unsigned)p.tiles_m);
+    p.div_sw_groups = make_fastdiv((unsigned)p.sw_groups);
+    const long long ntiles = (long long)p.tiles_n * p.tiles_m;
+    if (ntiles > 0x7FFFFFF0) return false;
+    const long long grid = 0;   // (decided at launch: persistent workgroups, see persistent_grid)
+    *out = p;
+    *lw_out = lw;
+    *ki_out = ki;
+    *lds_out = lds;
+    *grid_out = (int)grid;
+    return true;
+}
+
+}  // namespace
+
+size_t mfma_weight_bytes(int F, int C, int mt, int n_taps) {
+    return (size_t)((F + mt - 1) / mt) * ((C + 15) / 16) * n_taps * 2 * mt * 8 * sizeof(uint16_t);
+}
+
+bool mfma_applicable(const MfmaConv& a) {
+    MfmaParams p;
+    int lw, ki, grid;
+    size_t lds;
+    for (int sh = 0; sh < kMfmaShapes; ++sh)
+        if (kShapes[sh].wm * kShapes[sh].af * 32 == a.mt && plan(a, sh, a.rows, &p, &lw, &ki, &lds, &grid)) return true;
+    return false;
+}
+
+int launch_mfma_conv(const MfmaConv& a, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MfmaParams p;
+    int lw = 0, ki = 0, grid = 0;
+    size_t lds = 0;
+    int shape = a.shape - 1;
+    if (shape < 0) {
+        // the first shape of this tile height whose grid fills the GPU, else the one with the most workgroups
+        int best = -1, best_grid = 0;
+        for (int sh = 0; sh < kMfmaShapes; ++sh) {
+            if (!plan(a, sh, a.rows, &p, &lw, &ki, &lds, &grid)) continue;
+            const int wgs = p.tiles_n * p.tiles_m;
+            if (wgs >= 256) { best = sh; break; }
+            if (wgs > best_grid) { best = sh; best_grid = wgs; }
+        }
+        shape = best;
+    }
+    if (shape < 0 || shape >= kMfmaShapes) return PCONV_EUNSUPPORTED;
+    if (!plan(a, shape, a.rows, &p, &lw, &ki, &lds, &grid)) return PCONV_EUNSUPPORTED;
+    switch (shape) {
+        case 0: return launch_shape<2, 7, 2, 2>(p, lw, ki, lds, a.walk, st);
+        case 1: return launch_shape<1, 7, 2, 2>(p, lw, ki, lds, a.walk, st);
+        case 2: return launch_shape<1, 7, 4, 1>(p, lw, ki, lds, a.walk, st);
+        case 3: return launch_shape<1, 7, 2, 1>(p, lw, ki, lds, a.walk, st);
+    }
+    return PCONV_EUNSUPPORTED;
+}
+
+int launch_mfma_arrange(const void* w_oihw, void* out, int F, int C, int mt, void* stream) {
+    const int CB = (C + 15) / 16;
+    const long long total = (long long)((F + mt - 1) / mt) * CB * 9 * 2 * mt * 8;
+    const unsigned grid = (unsigned)std::min<long long>((total + 255) / 256, 65535);
+    hipLaunchKernelGGL(mfma_arrange_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const unsigned short*>(w_oihw), static_cast<unsigned short*>(out), F, C, mt, CB, total);
+    PCONV_HIP(hipGetLastError());
+    return PCONV_OK;
+}
+
+}  // namespace pconv

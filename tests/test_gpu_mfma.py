@@ -1,0 +1,133 @@
+"""The matrix-core kernel (fp16 storage) against the oracle: every tile shape, forced, on shapes chosen to hit what its
+indexing distinguishes -- tiles that run from one image into the next, a ragged last tile, rows capped per tile,
+both strides and paddings, widths that allow 4-, 2- and 1-pixel loads and 8-, 4-, 2- and 1-pixel stores, channel and
+filter counts that are not multiples of the 16-channel block and the 32-filter operand, a library that leaves taps
+unused, unaligned pointers.  The automatic choice for fp16 storage is this kernel, so every other fp16 parity test
+runs it as well."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2001_07710_amd as pc
+from workloads import layers as L
+
+from gpu_util import TOL, GpuLayer, rel_err
+
+pytestmark = pytest.mark.gpu
+M = pc.KERNEL_MFMA
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+
+
+def run_forms(layer, x, forms, relu=None):
+    ref = layer.oracle(x, relu)
+    for t in forms:
+        say(layer.spec.name, "x", x.shape, "stride", layer.spec.stride, "pad", layer.spec.pad, "form", t)
+        try:
+            got = layer.run(x, relu, **t)
+        except pc.PconvError as e:
+            assert e.code == pc.EUNSUPPORTED, t       # a tile shape that cannot take the layer says so
+            assert t.get("mfma_shape", 0) != 0, "the automatic choice must find a shape or fall back"
+            say("  unsupported")
+            continue
+        err = rel_err(got, ref)
+        assert err <= TOL["f16"], (layer.spec, t, err)
+
+
+SHAPES = [  # N, C, F, H, W, stride, pad
+    (3, 40, 70, 13, 28, 1, 1),      # 4-pixel loads and stores, 13 rows: tiles cross images
+    (2, 33, 130, 9, 12, 1, 1),      # C and F ragged against 16 / 32 / 128
+    (5, 16, 64, 7, 7, 1, 1),        # odd width: 1-pixel loads and stores; several images per tile
+    (33, 24, 40, 7, 7, 1, 1),       # more images than one tile holds
+    (2, 20, 33, 14, 14, 1, 1),      # 2-pixel loads and stores
+    (2, 31, 13, 15, 18, 2, 1),      # stride 2, odd height
+    (3, 8, 8, 16, 16, 2, 0),        # stride 2, no padding
+    (1, 7, 9, 5, 130, 1, 0),        # no padding, a row wider than a 128-pixel operand group
+    (2, 64, 10, 8, 8, 1, 0),
+    (1, 5, 3, 1, 1, 1, 1),          # a single pixel
+    (2, 3, 64, 30, 224, 1, 1),      # a first layer at full width: one or two rows per tile
+    (2, 48, 96, 20, 56, 2, 1),
+]
+
+
+@pytest.mark.parametrize("case", SHAPES, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}s{c[5]}p{c[6]}" for c in SHAPES])
+def test_every_tile_shape(case):
+    N, C, F, H, W, stride, pad = case
+    spec = L.LayerSpec(cfg=20, idx=SHAPES.index(case), name="mfma", N=N, C=C, F=F, H=H, W=W, stride=stride, pad=pad,
+                       dtype="f16", K=8, keep=0.4)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    forms = [dict()] + [dict(kernel=M, mfma_shape=sh) for sh in (1, 2, 3, 4)]
+    forms += [dict(kernel=M, mfma_shape=sh, rows=r) for sh in (1, 4) for r in (1, 3)]
+    run_forms(layer, x, forms)
+    run_forms(layer, x, [dict(kernel=M)], relu=True)
+    layer.free()
+
+
+def test_library_that_leaves_taps_unused():
+    """Two patterns over taps {0,1,2,3} and {0,1,2,4}: four of the nine taps carry no weight and are skipped."""
+    spec = L.LayerSpec(cfg=21, idx=0, name="taps", N=2, C=24, F=40, H=12, W=20, dtype="f16", K=2, keep=0.5,
+                       lib_kind="all126", assign="uniform", conn="bernoulli")
+    layer = GpuLayer(spec)
+    assert sorted(int(m) for m in layer.lib) == [0x00F, 0x017]
+    x = L.gen_activations(spec)
+    run_forms(layer, x, [dict(kernel=M, mfma_shape=sh) for sh in (0, 1, 2, 3, 4)])
+    layer.free()
+
+
+def test_nothing_kept_and_no_bias():
+    spec = L.LayerSpec(cfg=21, idx=1, name="none", N=2, C=16, F=32, H=8, W=8, dtype="f16", K=8, keep=0.0)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    y = layer.run(x, kernel=M)
+    assert np.array_equal(y, np.broadcast_to(layer.bias[None, :, None, None], y.shape).astype(np.float16))
+    layer.free()
+    layer = GpuLayer(L.shrink(spec, keep=0.5, idx=2), use_bias=False)
+    run_forms(layer, x, [dict(kernel=M)])
+    layer.free()
+
+
+def test_unaligned_pointers_and_fp32_refusal():
+    spec = L.LayerSpec(cfg=21, idx=3, name="shift", N=2, C=20, F=24, H=12, W=16, dtype="f16", K=8, keep=0.5)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    ref = layer.oracle(x)
+    for xs, ys in ((1, 0), (0, 1), (3, 5), (2, 4)):
+        say("x shifted by", xs, "elements, y by", ys)
+        assert rel_err(layer.run(x, x_shift=xs, y_shift=ys, kernel=M), ref) <= TOL["f16"]
+    layer.free()
+    spec32 = L.shrink(spec, dtype="f32", idx=4)
+    layer = GpuLayer(spec32)
+    with pytest.raises(pc.PconvError) as e:
+        layer.run(L.gen_activations(spec32), kernel=M)
+    assert e.value.code == pc.EUNSUPPORTED
+    layer.free()
+
+
+def test_runs_are_bit_reproducible():
+    spec = L.LayerSpec(cfg=21, idx=5, name="repro", N=4, C=64, F=128, H=28, W=28, dtype="f16", K=8, keep=0.28)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    first = layer.run(x)
+    for _ in range(5):
+        assert np.array_equal(layer.run(x).view(np.uint16), first.view(np.uint16))
+    layer.free()
+
+
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1), (1, 0)])
+def test_dense_baseline_on_the_matrix_cores_and_direct(stride, pad):
+    import torch
+    spec = L.LayerSpec(cfg=22, idx=stride * 2 + pad, name="dense16", N=3, C=40, F=72, H=14, W=20, stride=stride,
+                       pad=pad, dtype="f16")
+    w, x, b = L.gen_weights(spec), L.gen_activations(spec), L.gen_bias(spec)
+    dx, dw, db = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
+    ref = oracle.conv3x3(x, w, b, stride, pad, relu=True)
+    for flags in (pc.FLAG_RELU, pc.FLAG_RELU | pc.FLAG_DENSE_DIRECT):
+        say("dense fp16", stride, pad, "flags", flags)
+        dy = torch.full((3, 72, spec.Ho, spec.Wo), -7.0, dtype=torch.float16, device="cuda")
+        pc.dense_conv3x3(dx, dy, dw, db, pc.F16, 3, 40, 72, 14, 20, stride, pad, flags,
+                         torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert rel_err(dy.cpu().numpy(), ref) <= TOL["f16"]
