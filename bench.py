@@ -1,12 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the pattern-sparse 3x3 convolution path on one MI355X.
 
-Default run: the VGG-16 conv3_x-shaped layer (256 -> 256 channels, 56x56, batch 1, fp32, 8-pattern library,
-connectivity keep 0.28), inputs resident in HBM, K launches of pconv_conv3x3 timed after W warm-up launches.
-Prints ONE JSON line: effective GMAC/s over non-zero weights, the roofline position of the kernel and the CPU oracle
-timed on the host cores of the same box.
+Default run: the nine distinct VGG-16 3x3 layers at batch 64, fp16 storage with fp32 accumulation, 8-pattern library,
+connectivity keep 0.28 (the centre point of the throughput sweep), inputs resident in HBM.  A step is one pass over
+the nine layers (nine pconv_conv3x3 launches, weights packed once); K steps are timed after W warm-up steps.
+Prints ONE JSON line: effective GMAC/s over non-zero weights, per-layer rows, the roofline position of the dominant
+kernel, the dense baseline of this library, the CPU oracle timed on the host cores of the same box, and short
+measurements of the other configurations (batch-1 layer, batch-1 VGG-16 chain, ResNet-50 shapes at batch 32).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras]
+    python bench.py --config1                                                  the batch-1 fp32 layer alone
+    python bench.py --peaks                                                    measured peaks of this chip
     python bench.py --layers vgg_n1|resnet_n32|vgg_n64 [--K 8] [--keep 0.28]   per-layer table (stderr) + JSON line
     python bench.py --tune                                                     every tiling variant on the workload
     python bench.py --chain [--graph]            the 13 conv layers of VGG-16 at batch 1 (+ ReLU, max-pools) as one unit
@@ -26,6 +30,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_VECTOR_TFLOPS = 157.3    # MI355X published fp32 vector peak (256 CUs x 2.4 GHz x 256 flop/clk/CU)
+PEAK_FP16_MFMA_TFLOPS = 2500.0     # MI355X published dense fp16 matrix-core peak
 PEAK_HBM_GBS = 8000.0              # MI355X published HBM3E bandwidth
 
 
@@ -159,8 +164,11 @@ def read_traffic(path: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config1", action="store_true", help="time the batch-1 fp32 layer of config 1 alone")
+    ap.add_argument("--peaks", action="store_true", help="measured peaks of this chip (copy, fp32 FMA, LDS, MFMA)")
+    ap.add_argument("--no-extras", action="store_true", help="default run without the other configurations")
     ap.add_argument("--layers", default="")
     ap.add_argument("--K", type=int, default=8)
     ap.add_argument("--keep", type=float, default=0.28)
@@ -186,10 +194,16 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream().cuda_stream
 
+    if args.peaks:
+        return peaks_bench(args, torch)
     if args.chain:
         return chain_bench(args, torch, pc, L)
     if args.layers:
         return layer_table(args, torch, pc, L, stream)
+    if not args.config1 and not args.tune:
+        return sweep_bench(args, torch, pc, L, stream)
+    if args.steps == 50 and args.warmup == 5:
+        args.steps, args.warmup = 2000, 200
 
     spec = L.config1()
     layer = DeviceLayer(spec)
@@ -264,6 +278,180 @@ def main():
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(spec, layer)
+    print(json.dumps(out), flush=True)
+
+
+
+def executed_macs(spec, layer) -> int:
+    """Multiply-adds the kernel that runs the layer really executes: the kept weights for the vector kernels, the
+    dense contraction over the taps that occur for the matrix-core kernel (which multiplies the explicit zeros)."""
+    if spec.dtype == "f16":
+        taps = 0
+        for j in np.unique(layer.pid[layer.mask != 0]):
+            taps |= int(layer.lib[j])
+        return spec.N * spec.Ho * spec.Wo * bin(taps).count("1") * spec.C * spec.F
+    return effective_macs(spec, layer.n_kept)
+
+
+def time_per_layer(torch, layers, stream, steps, warmup, dense_w=None):
+    """One step = one launch of every layer, in order.  Returns (wall ms per step, [event ms per step and layer])."""
+    def step(record=None):
+        for i, l in enumerate(layers):
+            if record:
+                record[i][0].record()
+            if dense_w is None:
+                l.launch(stream)
+            else:
+                l.launch_dense(stream, dense_w[i])
+            if record:
+                record[i][1].record()
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in layers]
+           for _ in range(steps)]
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    per = [sum(evs[k][i][0].elapsed_time(evs[k][i][1]) for k in range(steps)) / steps for i in range(len(layers))]
+    return wall, per
+
+
+def short_sweep(torch, specs, stream, steps=30):
+    """Total and per-layer times of a list of layers (one launch each per step)."""
+    layers = [DeviceLayer(s, batch_from_one_image=True) for s in specs]
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.05:
+        for l in layers:
+            l.launch(stream)
+        torch.cuda.synchronize()
+    _, per = time_per_layer(torch, layers, stream, steps, 3)
+    macs = [effective_macs(s, l.n_kept) for s, l in zip(specs, layers)]
+    out = {"total_us": sum(per) * 1e3, "eff_GMACs": sum(macs) / sum(per) / 1e6,
+           "frac_of_fp32_vector_peak": 2 * sum(macs) / (sum(per) * 1e-3) / 1e12 / PEAK_FP32_VECTOR_TFLOPS,
+           "layers": {s.name: round(t * 1e3, 2) for s, t in zip(specs, per)}}
+    for l in layers:
+        l.packed.free()
+    return out
+
+
+def sweep_bench(args, torch, pc, L, stream):
+    """The default run: the nine VGG-16 shapes at batch 64 (config 4 at K = 8, keep 0.28)."""
+    specs = L.config4(args.K, args.keep, 64)
+    layers = [DeviceLayer(s, batch_from_one_image=True) for s in specs]
+    eff = [effective_macs(s, l.n_kept) for s, l in zip(specs, layers)]
+    exe = [executed_macs(s, l) for s, l in zip(specs, layers)]
+    ab = [algorithmic_bytes(s, l.n_kept) for s, l in zip(specs, layers)]
+    # plain device-to-device copy of known size: the calibration point of FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc
+    calib = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    calib2 = torch.empty_like(calib)
+    calib2.copy_(calib)
+    torch.cuda.synchronize()
+    del calib, calib2
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.1:              # bring the clocks up
+        for l in layers:
+            l.launch(stream)
+        torch.cuda.synchronize()
+    wall_ms, per = time_per_layer(torch, layers, stream, args.steps, args.warmup)
+
+    dense_per = None
+    if not args.no_dense:
+        dws = []
+        for l in layers:
+            wm = np.where(l.mask[:, :, None, None] != 0, l.w, 0).astype(l.w.dtype)
+            dws.append(torch.from_numpy(np.ascontiguousarray(wm)).cuda())
+        _, dense_per = time_per_layer(torch, layers, stream, max(3, args.steps // 5), 2, dense_w=dws)
+
+    rows = []
+    for i, (s, l) in enumerate(zip(specs, layers)):
+        t = per[i] * 1e-3
+        mfma_frac = 2 * exe[i] / t / 1e12 / PEAK_FP16_MFMA_TFLOPS
+        hbm_frac = ab[i] / t / 1e9 / PEAK_HBM_GBS
+        rows.append({"layer": s.name, "C": s.C, "F": s.F, "H": s.H, "n_kept": l.n_kept, "us": per[i] * 1e3,
+                     "eff_GMACs": eff[i] / t / 1e9, "executed_TFLOPs": 2 * exe[i] / t / 1e12,
+                     "bound": "hbm" if hbm_frac > mfma_frac else "mfma", "frac": max(mfma_frac, hbm_frac),
+                     "mfma_frac": mfma_frac, "alg_GBs": ab[i] / t / 1e9, "hbm_frac": hbm_frac,
+                     "eff_frac_of_fp32_vector_peak": 2 * eff[i] / t / 1e12 / PEAK_FP32_VECTOR_TFLOPS,
+                     "dense_us": None if dense_per is None else dense_per[i] * 1e3})
+    tot_t = sum(per) * 1e-3
+    # the dominant kernel: mfma_conv_kernel runs every layer of this workload; per launch = the mean over the nine
+    exe_flops = 2.0 * sum(exe) / len(specs)
+    alg_flops = 2.0 * sum(eff) / len(specs)
+    kernel_ms = sum(per) / len(specs)
+    achieved = exe_flops / (kernel_ms * 1e-3) / 1e12
+    traffic = read_traffic(os.path.join(ROOT, "profiles", "mfma_conv_kernel_vgg_n64_hbm_counters.txt"))
+    out = {
+        "metric": "effective GMAC/s (nonzero weights), VGG-16 3x3 layers",
+        "value": sum(eff) / (wall_ms * 1e-3) / 1e9,
+        "unit": "GMAC/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 storage, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"configs[4] at K={args.K}, keep {args.keep}: the nine distinct VGG-16 3x3 conv shapes, "
+                               "batch 64, fp16 storage (conv1_1 at keep 1.0)",
+                   "step": "one pconv_conv3x3 launch per layer, nine launches (weights packed once)"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP16_MFMA_TFLOPS, "traffic": traffic,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, mean per launch, "
+                                       "profiles/mfma_conv_kernel_vgg_n64_hbm_counters.txt",
+                     "kernel": "mfma_conv_kernel", "kernel_ms": kernel_ms, "launches_per_step": len(specs),
+                     "flops_per_launch": exe_flops, "algorithmic_flops_per_launch": alg_flops,
+                     "algorithmic_achieved_TFLOPs": alg_flops / (kernel_ms * 1e-3) / 1e12,
+                     "algorithmic_frac_of_fp32_vector_peak": alg_flops / (kernel_ms * 1e-3) / 1e12 / PEAK_FP32_VECTOR_TFLOPS,
+                     "algorithmic_bytes_per_launch": sum(ab) / len(specs),
+                     "algorithmic_GBs": sum(ab) / tot_t / 1e9, "hbm_frac_of_8TBs": sum(ab) / tot_t / 1e9 / PEAK_HBM_GBS,
+                     "note": "the kernel runs the layer as a dense fp16 contraction over its masked weights on the "
+                             "matrix cores; 'achieved' counts the multiply-adds it executes (every tap that occurs, "
+                             "explicit zeros included) against the published dense fp16 MFMA peak; the method's own "
+                             "flops (non-zero weights only) are 'algorithmic_*', with the fp32 vector peak, which "
+                             "bounds any kernel that skips the zeros, beside them"},
+        "layers": rows,
+        "dense_baseline": None if dense_per is None else {
+            "total_us": sum(dense_per) * 1e3, "kind": "pconv_dense_conv3x3: the same matrix-core kernel on all nine "
+            "taps of the masked dense tensor, including the re-ordering of the weights on every call"},
+        "host_once": {k: sum(l.host_ms[k] for l in layers) for k in layers[0].host_ms},
+    }
+    if not args.no_cpu:
+        big = max(range(len(specs)), key=lambda i: per[i])
+        out["cpu_baseline"] = cpu_baseline(specs[big], layers[big])
+        out["cpu_baseline"]["sample"] = f"layer {specs[big].name}: " + out["cpu_baseline"]["sample"]
+    for l in layers:
+        l.packed.free()
+    del layers
+    torch.cuda.empty_cache()
+    if not args.no_extras:
+        c1 = L.config1()
+        l1 = DeviceLayer(c1)
+        _, ev = time_launches(torch, lambda: l1.launch(stream), 500, 50)
+        m1 = effective_macs(c1, l1.n_kept)
+        out["other_configs"] = {
+            "config1_batch1_fp32": {"us": ev * 1e3, "eff_GMACs": m1 / ev / 1e6,
+                                    "frac_of_fp32_vector_peak": 2 * m1 / (ev * 1e-3) / 1e12 / PEAK_FP32_VECTOR_TFLOPS},
+            "config2_vgg16_batch1_fp32_per_layer_sum": short_sweep(torch, L.config2(), stream, 50),
+            "config3_resnet50_batch32_fp16": short_sweep(torch, L.config3(32), stream, 50),
+            "config3_resnet50_batch1_fp16": short_sweep(torch, L.config3(1), stream, 50),
+        }
+        l1.packed.free()
+    print(json.dumps(out), flush=True)
+
+
+def peaks_bench(args, torch):
+    """Register-, LDS- and memory-only kernels of libpconv_peaks.so: what the chip delivers, next to the published
+    peaks the roofline fractions are quoted against."""
+    import paper_2001_07710_amd as pc
+    out = {"peaks": pc.peaks(),
+           "published": {"hbm_GBs": PEAK_HBM_GBS, "fp32_vector_TFLOPs": PEAK_FP32_VECTOR_TFLOPS,
+                         "fp16_mfma_TFLOPs": PEAK_FP16_MFMA_TFLOPS},
+           "note": "copy_GBs counts bytes read plus bytes written; per-clock figures use the nominal engine clock"}
     print(json.dumps(out), flush=True)
 
 

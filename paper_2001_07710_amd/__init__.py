@@ -23,6 +23,7 @@ OK, EINVAL, EPATTERN, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE, ESCRATCH = 0, 
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpconv.so")
+PEAKS_LIB_PATH = os.path.join(_HERE, "libpconv_peaks.so")     # measured-peaks kernels, separate from the product
 _lib = None
 
 
@@ -42,7 +43,7 @@ class _Tuning(ctypes.Structure):
 
 def ensure_built() -> str:
     """Build the library if no built one is there (tests, smoke and bench call this; the binding itself never builds)."""
-    if not os.path.exists(LIB_PATH):
+    if not os.path.exists(LIB_PATH) or not os.path.exists(PEAKS_LIB_PATH):
         from .build import build_library
         build_library()
     return LIB_PATH
@@ -112,6 +113,29 @@ def _dtype_code(np_dtype) -> int:
     if np.dtype(np_dtype) == np.float16:
         return F16
     raise TypeError("storage type must be float32 or float16")
+
+
+def peaks() -> dict:
+    """Measured peaks of the current GPU (libpconv_peaks.so; see include/pconv_peaks.h)."""
+    lib = ctypes.CDLL(PEAKS_LIB_PATH)
+    d, i = ctypes.c_double, ctypes.c_int
+    for name in ("pconv_peak_copy_gbs", "pconv_peak_fma_tflops", "pconv_peak_lds_read_bytes_per_clk",
+                 "pconv_peak_vmem_clk_per_load", "pconv_peak_mfma_f16_tflops"):
+        getattr(lib, name).argtypes = [i]
+        getattr(lib, name).restype = d
+    lib.pconv_peak_device.argtypes = [ctypes.POINTER(i), ctypes.POINTER(d)]
+    lib.pconv_peak_device.restype = i
+    cus, mhz = i(0), d(0.0)
+    if lib.pconv_peak_device(ctypes.byref(cus), ctypes.byref(mhz)) != 0:
+        raise RuntimeError("pconv_peak_device failed")
+    return {
+        "compute_units": cus.value, "nominal_clock_MHz": mhz.value,
+        "copy_GBs": {f"{m}MiB": lib.pconv_peak_copy_gbs(m) for m in (256, 1024)},
+        "fp32_fma_TFLOPs": {f"{w}_waves_per_simd": lib.pconv_peak_fma_tflops(w) for w in (1, 2, 4)},
+        "lds_read_b128_bytes_per_clk_per_cu": {f"{w}_waves": lib.pconv_peak_lds_read_bytes_per_clk(w) for w in (4, 8, 16)},
+        "vmem_clk_per_wave_load": {f"{b}B_per_lane": lib.pconv_peak_vmem_clk_per_load(b) for b in (4, 16)},
+        "mfma_f16_TFLOPs": {f"{w}_waves_per_simd": lib.pconv_peak_mfma_f16_tflops(w) for w in (1, 2)},
+    }
 
 
 def strerror(code: int) -> str:

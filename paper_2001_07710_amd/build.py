@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpconv.so")
+PEAKS_LIB = os.path.join(HERE, "libpconv_peaks.so")
 SOURCES = ["pconv_host.cpp", "pconv_device.hip", "pconv_mfma.hip"]
 
 # Packed fp32 instructions are switched off for every HIP translation unit of this project.
@@ -38,6 +39,13 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    # the measured-peaks kernels: a library of their own, not linked into libpconv.so
+    cmd = [hipcc, *HIPCC_FLAGS, "-I" + os.path.join(ROOT, "include"), "-o", PEAKS_LIB, os.path.join(CSRC, "pconv_peaks.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + proc.stdout)
     return LIB
 
 

@@ -2201,9 +2201,11 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
     int CPW = tuning ? tuning->channels_per_wave : 0;
     int KS = tuning ? tuning->channel_splits : 0;
     int buffers = tuning ? tuning->buffers : 0;
-    // The matrix-core kernel (fp16 storage): the layer as a dense contraction over its masked weights.  Chosen
-    // automatically wherever it applies: measured faster than the vector kernels on every VGG-16 and ResNet-50 shape
-    // from batch 1 up (fp16 MFMA runs 16 times the rate of fp32 vector multiply-adds, the layer has 8 times fewer).
+    // The matrix-core kernel (fp16 storage): the layer as a dense contraction over its masked weights.  Automatic
+    // choice: the tile shape with the smallest estimated time, if that is below an estimate for the vector kernels
+    // (effective multiply-adds at the rate they reach on such a layer plus a fixed part: measured 20 TMAC/s at unit
+    // stride, half of that on maps narrower than 14 columns, 5 TMAC/s at stride 2).  Layers with few output tiles
+    // (batch 1, small maps with many channels) stay with the vector kernels, whose channel split fills the GPU.
     const bool all_auto = !tuning || (tuning->rows == 0 && tuning->filters_per_wave == 0 && tuning->waves == 0 &&
                                       tuning->channels_per_wave == 0 && tuning->channel_order == 0 &&
                                       tuning->channel_splits == 0 && tuning->buffers == 0);
@@ -2218,18 +2220,30 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         a.rows = tuning ? tuning->rows : 0;
         a.walk = tuning ? tuning->slot_walk : 0;
         if (a.shape < 0 || a.shape > kMfmaShapes) return PCONV_EINVAL;
-        int rc = PCONV_EUNSUPPORTED;
-        for (const MfmaWeights& m : wp->mfma) {
-            if (!m.d_w) continue;
-            // a layer with at most 64 filters takes the 64-filter tiles, others the 128-filter ones (automatic)
-            if (!a.shape && (m.mt == 64) != (wp->F <= 64)) continue;
-            a.d_w = m.d_w; a.mt = m.mt; a.n_taps = m.n_taps;
-            std::memcpy(a.taps, m.taps, sizeof(a.taps));
-            rc = launch_mfma_conv(a, stream);
-            if (rc != PCONV_EUNSUPPORTED) return rc;
+        if (!wp->mfma.empty()) a.n_taps = wp->mfma[0].n_taps;
+        double best_us = -1.0;
+        if (a.shape == 0) {
+            for (int sh = 1; sh <= kMfmaShapes; ++sh) {
+                const double t = mfma_estimate_us(a, sh);
+                if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; }
+            }
         }
-        if (forced) return rc;
-        // (no shape takes the layer: the vector kernels below)
+        bool take = a.shape != 0;
+        if (take && !forced) {
+            const double macs = (double)N * Ho * Wo * 4.0 * (double)wp->n_kept;
+            const double rate = stride == 2 ? 5e6 : Wo < 14 ? 10e6 : 20e6;      // multiply-adds per microsecond
+            take = best_us < macs / rate + 8.0;
+        }
+        int rc = PCONV_EUNSUPPORTED;
+        if (take)
+            for (const MfmaWeights& m : wp->mfma) {
+                if (!m.d_w || m.mt != mfma_shape_height(a.shape)) continue;
+                a.d_w = m.d_w; a.mt = m.mt; a.n_taps = m.n_taps;
+                std::memcpy(a.taps, m.taps, sizeof(a.taps));
+                rc = launch_mfma_conv(a, stream);
+            }
+        if (rc != PCONV_EUNSUPPORTED || forced) return rc;
+        // (no tile shape takes the layer, or the vector kernels are expected to be faster: go on below)
     }
     // What the tiled kernel sees: the layer itself at stride 1; at stride 2 the layer re-packed over the four
     // row/column parity planes of the input (a stride-1 problem with 4*C channels of half the height and width).
@@ -2481,17 +2495,23 @@ extern "C" int pconv_dense_conv3x3(const void* x, void* y, const void* w, const 
     if (dtype == PCONV_F16 && !(flags & PCONV_FLAG_DENSE_DIRECT)) {
         // the matrix-core kernel on all nine taps of all kernels; the weights are brought into its order by a small
         // kernel first (part of the call), in a buffer that the library keeps per device and grows on demand
-        const int mt = F <= 64 ? 64 : 128;
+        MfmaConv a{};
+        a.x = x; a.y = y; a.bias = bias; a.n_taps = 9;
+        for (int t = 0; t < 9; ++t) a.taps[t] = (uint8_t)t;
+        a.N = N; a.C = C; a.F = F; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo;
+        a.stride = stride; a.pad = pad; a.relu = relu;
+        double best_us = -1.0;
+        for (int sh = 1; sh <= kMfmaShapes; ++sh) {
+            const double t = mfma_estimate_us(a, sh);
+            if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; }
+        }
+        const int mt = a.shape ? mfma_shape_height(a.shape) : 128;
         const size_t need = mfma_weight_bytes(F, C, mt, 9);
         void* buf = nullptr;
         if (int rc = dense_weight_buffer(need, &buf)) return rc;
         if (int rc = launch_mfma_arrange(w, buf, F, C, mt, stream)) return rc;
-        MfmaConv a{};
-        a.x = x; a.y = y; a.bias = bias; a.d_w = buf; a.mt = mt; a.n_taps = 9;
-        for (int t = 0; t < 9; ++t) a.taps[t] = (uint8_t)t;
-        a.N = N; a.C = C; a.F = F; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo;
-        a.stride = stride; a.pad = pad; a.relu = relu;
-        const int rc = launch_mfma_conv(a, stream);
+        a.d_w = buf; a.mt = mt;
+        const int rc = a.shape ? launch_mfma_conv(a, stream) : PCONV_EUNSUPPORTED;
         if (rc != PCONV_EUNSUPPORTED) return rc;
     }
     const dim3 grid((unsigned)(((long long)Ho * Wo + 255) / 256), (unsigned)F, (unsigned)N);

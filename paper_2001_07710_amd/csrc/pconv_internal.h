@@ -122,14 +122,15 @@ struct MfmaConv {
     int mt, n_taps;
     uint8_t taps[9];
     int N, C, F, H, W, Ho, Wo, stride, pad, relu;
-    int shape;                  // 0: chosen by the library; 1..kMfmaShapes: a tile shape of mfma_shape_table()
+    int shape;                  // 1..kMfmaShapes: the tile shape (mt must be its height)
     int rows;                   // 0: as many output rows per tile as fit; else that many
     int walk;                   // 1: one workgroup per tile; otherwise persistent workgroups that walk over the tiles
 };
 constexpr int kMfmaShapes = 4;
 // tile heights (filters per workgroup) that the kernel's tile shapes use; weights are kept for each
 constexpr int kMfmaTileHeights[2] = {128, 64};
-bool mfma_applicable(const MfmaConv& a);
+int mfma_shape_height(int shape);
+double mfma_estimate_us(const MfmaConv& a, int shape);
 int launch_mfma_conv(const MfmaConv& a, void* stream);
 // dense fp16 weights OIHW on the device -> MfmaWeights order for tile height mt, all nine taps (the dense baseline)
 int launch_mfma_arrange(const void* w_oihw, void* out, int F, int C, int mt, void* stream);

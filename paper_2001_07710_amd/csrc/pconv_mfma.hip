@@ -685,13 +685,28 @@ size_t mfma_weight_bytes(int F, int C, int mt, int n_taps) {
     return (size_t)((F + mt - 1) / mt) * ((C + 15) / 16) * n_taps * 2 * mt * 8 * sizeof(uint16_t);
 }
 
-bool mfma_applicable(const MfmaConv& a) {
+int mfma_shape_height(int shape) {
+    return shape >= 1 && shape <= kMfmaShapes ? kShapes[shape - 1].wm * kShapes[shape - 1].af * 32 : 0;
+}
+
+// Estimated run time, in microseconds, of the layer with tile shape `shape` (1..kMfmaShapes); negative if the shape
+// cannot take it.  Rounds of resident workgroups times (a fixed part + channel blocks x time per block).  The block
+// times are measured ones (MI355X, VGG-16 and ResNet-50 shapes); while a workgroup has its compute unit to itself a
+// block cannot take less than the round trip of the loads that fetch the next one.
+double mfma_estimate_us(const MfmaConv& a0, int shape) {
+    if (shape < 1 || shape > kMfmaShapes) return -1.0;
+    MfmaConv a = a0;
+    a.mt = mfma_shape_height(shape);
     MfmaParams p;
-    int lw, ki, grid;
-    size_t lds;
-    for (int sh = 0; sh < kMfmaShapes; ++sh)
-        if (kShapes[sh].wm * kShapes[sh].af * 32 == a.mt && plan(a, sh, a.rows, &p, &lw, &ki, &lds, &grid)) return true;
-    return false;
+    int lw = 0, ki = 0, grid = 0;
+    size_t lds = 0;
+    if (!plan(a, shape - 1, a.rows, &p, &lw, &ki, &lds, &grid)) return -1.0;
+    static const double block_us[kMfmaShapes] = {3.3, 1.9, 1.9, 1.25};
+    const long long tiles = (long long)p.tiles_n * p.tiles_m;
+    const long long resident = (long long)compute_units() * (shape == 4 ? 2 : 1);
+    const double rounds = (double)((tiles + resident - 1) / resident);
+    const double floor_us = tiles < 2 * resident ? 2.4 : 0.0;
+    return rounds * (8.0 + p.CB * std::max(block_us[shape - 1], floor_us));
 }
 
 int launch_mfma_conv(const MfmaConv& a, void* stream) {
@@ -699,18 +714,7 @@ int launch_mfma_conv(const MfmaConv& a, void* stream) {
     MfmaParams p;
     int lw = 0, ki = 0, grid = 0;
     size_t lds = 0;
-    int shape = a.shape - 1;
-    if (shape < 0) {
-        // the first shape of this tile height whose grid fills the GPU, else the one with the most workgroups
-        int best = -1, best_grid = 0;
-        for (int sh = 0; sh < kMfmaShapes; ++sh) {
-            if (!plan(a, sh, a.rows, &p, &lw, &ki, &lds, &grid)) continue;
-            const int wgs = p.tiles_n * p.tiles_m;
-            if (wgs >= 256) { best = sh; break; }
-            if (wgs > best_grid) { best = sh; best_grid = wgs; }
-        }
-        shape = best;
-    }
+    const int shape = a.shape - 1;
     if (shape < 0 || shape >= kMfmaShapes) return PCONV_EUNSUPPORTED;
     if (!plan(a, shape, a.rows, &p, &lw, &ki, &lds, &grid)) return PCONV_EUNSUPPORTED;
     switch (shape) {
