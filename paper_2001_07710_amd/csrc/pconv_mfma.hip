@@ -273,13 +273,15 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     };
 
     Piece<LW> stg[kItems][8];
-    uint4v wst[WPIECES];
-    const int w_pieces = p.a_bytes >> 4;
+    const int w_pieces = p.a_bytes >> 4;                       // (a multiple of 128: whole waves)
 
-    // One of the loads of channel block cb: j < 8*kItems: channel j%8 of piece j/8 of the activations; then the
-    // 16-byte pieces of the weights.
+    // One of the loads of channel block cb, which will be multiplied out of LDS buffer `buf`.  j < 8*kItems: channel
+    // j%8 of piece j/8 of the activations, into registers.  Then the weights, 1 KB per wave and load, straight into
+    // LDS (buffer_load ... lds: lane l's 16 bytes land at the wave's base + 16*l, no registers in between); the
+    // buffer is free from the barrier that ended the block before the current one.
     constexpr int NLOADS = 8 * kItems + WPIECES;
-    auto issue_one = [&](int cb, int j) {
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    auto issue_one = [&](int cb, int buf, int j) {
         if (PCONV_VARIANT & 2) return;
         if (j < 8 * kItems) {
             const int i = j >> 3, ch = j & 7;
@@ -288,12 +290,16 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
                 make_rsrc(reinterpret_cast<const void*>(((unsigned long long)xb_hi << 32) | xb_lo), x_records);
             stg[i][ch].load(xr, (chan < p.C && stage_on) ? goff[i] : kInvalid, (uint32_t)chan * p.chan_bytes);
         } else {
-            const int piece = tid + (j - 8 * kItems) * NTH;
-            const uint32_t wsoff = (uint32_t)((stage_tm * p.CB + cb) * p.a_bytes);
-            wst[j - 8 * kItems] = __builtin_amdgcn_raw_buffer_load_b128(
-                wr, (piece < w_pieces && stage_on) ? piece * 16 : (int)kInvalid, (int)wsoff, 0);
+            const int first = ((j - 8 * kItems) * NW + wave) * 64;        // the wave's first piece (uniform)
+            if (first < w_pieces && stage_on) {
+                const uint32_t wsoff = (uint32_t)((stage_tm * p.CB + cb) * p.a_bytes);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_ptr)(ldsA + buf * p.a_bytes + first * 16), 16,
+                                                         (first + lane) * 16, (int)wsoff, 0, 0);
+            }
         }
     };
+    // The staged activations of the next block: interleave the channels and write them to LDS; then wait for the
+    // weights that are on their way into LDS, so that the barrier behind this publishes both.
     auto write_lds = [&](int buf) {
         if (PCONV_VARIANT & 4) return;
         unsigned char* const b = ldsB + buf * 2 * p.plane_bytes;
@@ -311,12 +317,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
                 }
             }
         }
-        unsigned char* const a = ldsA + buf * p.a_bytes;
-#pragma unroll
-        for (int j = 0; j < WPIECES; ++j) {
-            const int piece = tid + j * NTH;
-            if (piece < w_pieces) *reinterpret_cast<uint4v*>(a + piece * 16) = wst[j];
-        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
     };
 
     // ---- compute state: operand offsets of this lane for the tile being multiplied
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     stage_descriptors(gc);
     stage_bias(gc.tm, 0);
 #pragma unroll
-    for (int j = 0; j < NLOADS; ++j) issue_one(0, j);
+    for (int j = 0; j < NLOADS; ++j) issue_one(0, 0, j);
     write_lds(0);
     __syncthreads();
     compute_descriptors(gc);
@@ -481,7 +482,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
                         }
 #pragma unroll
                         for (int j = 0; j < NLOADS; ++j)
-                            if ((j * NGROUPS) / NLOADS == ts * BF + bf) issue_one(ncb, j);
+                            if ((j * NGROUPS) / NLOADS == ts * BF + bf) issue_one(ncb, buf ^ 1, j);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -495,7 +496,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
                 };
                 fetch(0, 0);
 #pragma unroll
-                for (int j = 0; j < NLOADS; ++j) issue_one(ncb, j);
+                for (int j = 0; j < NLOADS; ++j) issue_one(ncb, buf ^ 1, j);
 #pragma unroll
                 for (int ts = 0; ts < 9; ++ts) {
                     if (ts < p.nt) {
@@ -701,11 +702,13 @@ double mfma_estimate_us(const MfmaConv& a0, int shape) {
     int lw = 0, ki = 0, grid = 0;
     size_t lds = 0;
     if (!plan(a, shape - 1, a.rows, &p, &lw, &ki, &lds, &grid)) return -1.0;
-    static const double block_us[kMfmaShapes] = {3.3, 1.9, 1.9, 1.25};
+    static const double block_us[kMfmaShapes] = {3.2, 1.6, 1.6, 1.7};
     const long long tiles = (long long)p.tiles_n * p.tiles_m;
-    const long long resident = (long long)compute_units() * (shape == 4 ? 2 : 1);
+    // the two-wave shape leaves registers for a second workgroup on a compute unit, if its LDS fits twice
+    const int per_cu = shape == 4 && 2 * lds <= 160 * 1024 ? 2 : 1;
+    const long long resident = (long long)compute_units() * per_cu;
     const double rounds = (double)((tiles + resident - 1) / resident);
-    const double floor_us = tiles < 2 * resident ? 2.4 : 0.0;
+    const double floor_us = tiles < 2 * resident ? 2.1 : 0.0;
     return rounds * (8.0 + p.CB * std::max(block_us[shape - 1], floor_us));
 }
 

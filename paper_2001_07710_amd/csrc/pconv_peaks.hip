@@ -62,12 +62,22 @@ __global__ __launch_bounds__(256) void copy_kernel(const float4v* __restrict__ s
 // ---- fp32 multiply-adds on registers only: 16 independent accumulators per lane
 __global__ __launch_bounds__(1024) void fma_kernel(float* out, int iters) {
     float a[16];
-    const float x = 1.0f + threadIdx.x * 1e-7f, y = 0.999f;
+    // (both operands per lane, in vector registers: a multiply-add with an operand in a scalar register or a literal
+    // runs at half the rate on this chip)
+    const float x = 1.0f + threadIdx.x * 1e-7f, y = 0.999f + threadIdx.x * 1e-8f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) a[i] = (float)i;
+    // (v_fmac_f32 spelled out: the three-address v_fma_f32 that the compiler picks for a[i] = fma(a[i], x, y)
+    // reads three vector registers per lane and reaches two thirds of this rate)
     for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) a[i] = __builtin_fmaf(a[i], x, y);
+        asm volatile(
+            "v_fmac_f32 %0, %16, %17\n v_fmac_f32 %1, %16, %17\n v_fmac_f32 %2, %16, %17\n v_fmac_f32 %3, %16, %17\n"
+            "v_fmac_f32 %4, %16, %17\n v_fmac_f32 %5, %16, %17\n v_fmac_f32 %6, %16, %17\n v_fmac_f32 %7, %16, %17\n"
+            "v_fmac_f32 %8, %16, %17\n v_fmac_f32 %9, %16, %17\n v_fmac_f32 %10, %16, %17\n v_fmac_f32 %11, %16, %17\n"
+            "v_fmac_f32 %12, %16, %17\n v_fmac_f32 %13, %16, %17\n v_fmac_f32 %14, %16, %17\n v_fmac_f32 %15, %16, %17"
+            : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]), "+v"(a[8]),
+              "+v"(a[9]), "+v"(a[10]), "+v"(a[11]), "+v"(a[12]), "+v"(a[13]), "+v"(a[14]), "+v"(a[15])
+            : "v"(x), "v"(y));
     }
     float s = 0.f;
 #pragma unroll
