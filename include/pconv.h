@@ -17,8 +17,10 @@
  *     image read as zero;
  *   - dtype is the STORAGE type of x, y and w (PCONV_F32 or PCONV_F16); sums are always accumulated in fp32, the
  *     bias is always fp32, fp16 results are rounded to nearest even once, at the store;
- *   - every function returns PCONV_OK (0) or a negative error code; nothing throws; the library keeps no global
- *     mutable state and distinct handles may be used from distinct threads;
+ *   - every function returns PCONV_OK (0) or a negative error code; nothing throws; distinct handles may be used
+ *     from distinct threads.  Process-wide state is limited to three per-device caches behind mutexes: the number of
+ *     compute units, the address of the fixed scratch array of pconv_conv3x3_noalloc, and the weight buffer of
+ *     pconv_dense_conv3x3 for fp16 storage;
  *   - "host" / "device" in a parameter comment says where the pointer must point.  Device buffers are owned by the
  *     caller; the library owns what it allocates behind a pconv_packed handle until pconv_free.
  */
@@ -224,7 +226,13 @@ size_t pconv_noalloc_scratch_bytes(void);
  *   mfma_shape        PCONV_KERNEL_MFMA (fp16 storage only; any stride and pad): the layer as a dense contraction
  *                     over its masked weights on the matrix cores, the automatic choice for fp16 storage.  Workgroup
  *                     tile: 0 = chosen by the library, 1 = 128 filters x 448 output pixels, 2 = 64 x 448,
- *                     3 = 128 x 224, 4 = 64 x 224.  `rows` (0 = as many as fit) caps the output rows per tile.
+ *                     3 = 128 x 224, 4 = 64 x 224.  `rows` (0 = as many as fit) caps the output rows per tile;
+ *                     slot_walk = 1 gives every tile a workgroup of its own instead of persistent workgroups that
+ *                     walk over the tiles; channel_splits (0 = 1, or 2, 4, 8, 16, at most the number of 16-channel
+ *                     blocks) lets that many workgroups share a tile, each with a part of the channel blocks: their
+ *                     partial sums meet in the handle's workspace and are added in a fixed order (reproducible);
+ *                     never chosen automatically, the round trip of the partial sums costs more than it gains on
+ *                     every shape measured.
  *                     Non-finite activations reach every output whose 3x3 window holds them, also through weights
  *                     that are pruned (0 * inf), which the vector kernels skip.
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.

@@ -1930,9 +1930,9 @@ static int launch_tiled(TiledParams& p, const pconv_packed* wp, int NF, int wave
     p.NG = (p.F + waves * NF - 1) / (waves * NF);
     const int nchunks = p.perm ? p.nbk : (p.C + CC - 1) / CC;
     if (KS == 0) {
-        // Automatic: one round of workgroups over the 256 CUs when the tiles alone are fewer than that
+        // Automatic: one round of workgroups over the compute units when the tiles alone are fewer than that
         const long long tiles = (long long)slots * p.NG;
-        KS = (int)std::max<long long>(1, std::min<long long>(256 / std::max<long long>(tiles, 1), 16));
+        KS = (int)std::max<long long>(1, std::min<long long>(compute_units() / std::max<long long>(tiles, 1), 16));
         KS = std::min(KS, nchunks);
     }
     if (KS < 1 || KS > nchunks || KS > 64) return PCONV_EUNSUPPORTED;
@@ -2017,14 +2017,15 @@ static int launch_quad(QuadParams& p, const pconv_packed* wp, int NF, int FW, in
                           (NF == 1 || sizeof(T) == 2);
     if (walk < 0 || walk > 2) return PCONV_EINVAL;
     if (walk == 2 && !can_walk) return PCONV_EUNSUPPORTED;
-    const long long walkers = std::min<long long>(slots, std::max(1, 256 / p.NG));
+    const int cus = compute_units();
+    const long long walkers = std::min<long long>(slots, std::max(1, cus / p.NG));
     // Cost of one workgroup per tile, in chunks: the rounds of 256 workgroups times a workgroup's chunks plus half a
     // chunk for what it cannot overlap at its start and end, plus 1.2 for partial sums and their reduction if the
     // channels are split.  A split (automatic: 2 or 4) is taken where it evens out the rounds — 800 tiles are 3.1
     // rounds, so four; 1600 half-length workgroups are 6.25, so seven halves — from 3 % predicted gain on.
     const long long tiles = slots * p.NG;
     auto tile_cost = [&](int ks) {
-        const double rounds = (double)((tiles * ks + 255) / 256);
+        const double rounds = (double)((tiles * ks + cus - 1) / cus);
         return rounds * ((double)((p.nbk + ks - 1) / ks) + 0.5 + (ks > 1 ? 1.2 : 0.0));
     };
     double best_tile = tile_cost(KS);
@@ -2221,14 +2222,26 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         a.walk = tuning ? tuning->slot_walk : 0;
         if (a.shape < 0 || a.shape > kMfmaShapes) return PCONV_EINVAL;
         if (!wp->mfma.empty()) a.n_taps = wp->mfma[0].n_taps;
+        // tile shape and number of workgroups per tile (each with a part of the channel blocks), where not given
         double best_us = -1.0;
-        if (a.shape == 0) {
-            for (int sh = 1; sh <= kMfmaShapes; ++sh) {
-                const double t = mfma_estimate_us(a, sh);
-                if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; }
+        const int want_shape = a.shape, want_splits = tuning ? tuning->channel_splits : 0;
+        if (want_splits < 0) return PCONV_EINVAL;
+        for (int sh = 1; sh <= kMfmaShapes; ++sh) {
+            if (want_shape && sh != want_shape) continue;
+            // (a split is only taken when asked for: the partial sums are MT x NT floats per part, twice the tile's
+            // output, and on the measured shapes their round trip through memory cost more than the parallelism
+            // gained -- ResNet-50's 64 -> 64 layer at 56x56, batch 32: 17 us unsplit, 53 us in two parts)
+            for (int ks = 1; ks <= 16; ks *= 2) {
+                if (ks != (want_splits ? want_splits : 1)) continue;
+                const double t = mfma_estimate_us(a, sh, ks);
+                if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; a.splits = ks; }
             }
         }
-        bool take = a.shape != 0;
+        if (best_us < 0.0) {
+            a.shape = want_shape;                // (nothing fits: launch_mfma_conv says so)
+            a.splits = want_splits ? want_splits : 1;
+        }
+        bool take = best_us >= 0.0 || forced;
         if (take && !forced) {
             const double macs = (double)N * Ho * Wo * 4.0 * (double)wp->n_kept;
             const double rate = stride == 2 ? 5e6 : Wo < 14 ? 10e6 : 20e6;      // multiply-adds per microsecond
@@ -2240,6 +2253,12 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
                 if (!m.d_w || m.mt != mfma_shape_height(a.shape)) continue;
                 a.d_w = m.d_w; a.mt = m.mt; a.n_taps = m.n_taps;
                 std::memcpy(a.taps, m.taps, sizeof(a.taps));
+                if (a.splits > 1) {
+                    size_t floats = 0, counters = 0;
+                    rc = mfma_workspace(a, &floats, &counters);
+                    if (rc == PCONV_OK) rc = get_workspace(wp, arena, floats, counters, &a.ws, &a.counters, st);
+                    if (rc != PCONV_OK) break;
+                }
                 rc = launch_mfma_conv(a, stream);
             }
         if (rc != PCONV_EUNSUPPORTED || forced) return rc;
@@ -2260,17 +2279,19 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
             // fp16 storage, one with fp32: see launch_quad)
             const int walk_nf = wp->dtype == PCONV_F16 ? 2 : 1;
             const long long slots = wgs / ((wp->F + 31) / 32);
-            const long long walkers = std::max(1, 256 / ((wp->F + 16 * walk_nf - 1) / (16 * walk_nf)));
+            const int cus = compute_units();
+            const long long nearly_full = (long long)cus * 25 / 32;       // 200 of 256: measured break-even
+            const long long walkers = std::max(1, cus / ((wp->F + 16 * walk_nf - 1) / (16 * walk_nf)));
             if (wp->n_buckets == 1 && pad == 1 && reinterpret_cast<uintptr_t>(y) % 16 == 0 && 2 * slots >= 3 * walkers) {
                 // one chunk of channels (a network's first layer) and more tiles than CUs: workgroups that keep their
                 // filters and walk over the tiles (launch_quad turns to them under the same condition); measured
                 // 13 to 32 % faster than one workgroup per tile at batch 4 to 64
                 kernel = PCONV_KERNEL_QUAD;
                 NF = walk_nf;
-            } else if (wgs >= 200) {
+            } else if (wgs >= nearly_full) {
                 kernel = PCONV_KERNEL_QUAD;
                 NF = 2;
-            } else if (wp->C <= 16 && wgs * ((wp->F + 15) / 16) / ((wp->F + 31) / 32) >= 200) {
+            } else if (wp->C <= 16 && wgs * ((wp->F + 15) / 16) / ((wp->F + 31) / 32) >= nearly_full) {
                 // a single chunk of channels (a network's first layer): nothing to amortise over two filters per
                 // wave, and one filter per wave gives twice the workgroups
                 kernel = PCONV_KERNEL_QUAD;
@@ -2350,7 +2371,7 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
                     const double chunk = std::max(issue, staging) + 3400.0;
                     const double combine = ks == 1 ? 1500.0 * nf : nf == 1 ? 1200.0 * ks : 4500.0 + 2400.0 * ks;
                     const double wg = 9000.0 + (double)((nch + ks - 1) / ks) * chunk + combine;
-                    const double rounds = (double)((tiles * ks + 255) / 256);
+                    const double rounds = (double)((tiles * ks + compute_units() - 1) / compute_units());
                     const double t = rounds * wg;
                     if (best == 0.0 || t < best) { best = t; NF = nf; waves = w; CPW = cpw; KS = ks; }
                 }
@@ -2502,9 +2523,10 @@ extern "C" int pconv_dense_conv3x3(const void* x, void* y, const void* w, const 
         a.stride = stride; a.pad = pad; a.relu = relu;
         double best_us = -1.0;
         for (int sh = 1; sh <= kMfmaShapes; ++sh) {
-            const double t = mfma_estimate_us(a, sh);
+            const double t = mfma_estimate_us(a, sh, 1);
             if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; }
         }
+        a.splits = 1;
         const int mt = a.shape ? mfma_shape_height(a.shape) : 128;
         const size_t need = mfma_weight_bytes(F, C, mt, 9);
         void* buf = nullptr;

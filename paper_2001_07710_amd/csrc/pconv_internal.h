@@ -125,12 +125,19 @@ struct MfmaConv {
     int shape;                  // 1..kMfmaShapes: the tile shape (mt must be its height)
     int rows;                   // 0: as many output rows per tile as fit; else that many
     int walk;                   // 1: one workgroup per tile; otherwise persistent workgroups that walk over the tiles
+    int splits;                 // workgroups per tile, each with a part of the channel blocks (1: no split)
+    float* ws;                  // splits > 1: workspace of mfma_workspace() floats
+    unsigned* counters;         // splits > 1: mfma_workspace() counters, zero
 };
 constexpr int kMfmaShapes = 4;
 // tile heights (filters per workgroup) that the kernel's tile shapes use; weights are kept for each
 constexpr int kMfmaTileHeights[2] = {128, 64};
+int compute_units();        // of the current device
 int mfma_shape_height(int shape);
-double mfma_estimate_us(const MfmaConv& a, int shape);
+// estimated run time in microseconds of shape `shape` with `splits` workgroups per tile, negative if it cannot run
+double mfma_estimate_us(const MfmaConv& a, int shape, int splits);
+// workspace that a launch with a.shape and a.splits > 1 needs
+int mfma_workspace(const MfmaConv& a, size_t* floats, size_t* counters);
 int launch_mfma_conv(const MfmaConv& a, void* stream);
 // dense fp16 weights OIHW on the device -> MfmaWeights order for tile height mt, all nine taps (the dense baseline)
 int launch_mfma_arrange(const void* w_oihw, void* out, int F, int C, int mt, void* stream);

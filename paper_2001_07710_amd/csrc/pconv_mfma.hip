@@ -60,9 +60,6 @@ typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 typedef unsigned uint2v __attribute__((ext_vector_type(2)));
 
-#ifndef PCONV_VARIANT
-#define PCONV_VARIANT 0
-#endif
 constexpr uint32_t kInvalid = 0x80000000u;
 
 // Division by a divisor fixed for the launch (Granlund and Montgomery's round-up method, exact for 32-bit dividends).
@@ -110,6 +107,11 @@ struct MfmaParams {
     unsigned wq_bytes;
     unsigned chan_bytes;    // H*W*2
     unsigned img_bytes;     // C*H*W*2
+    int KS;                 // workgroups that share one tile, each taking a contiguous range of the channel blocks
+    float* ws;              // KS > 1: partial sums [tile][split][wave][operand tile][4 rows][64 lanes][4], as held
+    unsigned* counters;     // KS > 1: one arrival counter per tile, zero between launches
+    int flag_off;           // byte offset in LDS of the word that tells a workgroup's waves whether it arrived last
+    FastDiv div_KS;
     FastDiv div_Wo, div_Ho, div_G, div_cnt_full, div_tiles_m, div_sw_groups;
     int sw_groups;          // store pieces per output row: Wo / sw
 };
@@ -156,6 +158,8 @@ __device__ __forceinline__ unsigned interleave(unsigned a, unsigned b, int px) {
 
 // Geometry of one tile (all wave-uniform): the m-tile, and the R consecutive output rows of the batch it covers.
 struct TileGeo {
+    int tile, split;   // the tile and, if its channel blocks are split over several workgroups, which part
+    int cb0, cb1;      // the channel blocks of this part
     int tm;            // which MT filters
     int Rv;            // output rows in the tile (the last tile of the batch may have fewer than R)
     int n0, oy0;       // image and row of its first output row
@@ -182,7 +186,8 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     // an L2.  gridDim.x is a multiple of 8.
     const unsigned nwg = gridDim.x;
     const unsigned w0 = (blockIdx.x & 7u) * (nwg >> 3) + (blockIdx.x >> 3);
-    const unsigned ntiles = (unsigned)p.tiles_n * (unsigned)p.tiles_m;
+    // (a work item is a tile, or one of the KS parts of a tile's channel blocks; the parts of a tile are neighbours)
+    const unsigned ntiles = (unsigned)p.tiles_n * (unsigned)p.tiles_m * (unsigned)p.KS;
     if (w0 >= ntiles) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -190,8 +195,13 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     const int wm = wave / WN, wn = wave - wm * WN;
     const int s = p.stride, Ho = p.Ho, Wo = p.Wo, PW = p.PW;
 
-    auto geometry = [&](unsigned T) {
+    auto geometry = [&](unsigned item) {
         TileGeo g;
+        const unsigned T = fastdiv(item, p.div_KS);
+        g.tile = (int)T;
+        g.split = (int)(item - T * (unsigned)p.KS);
+        g.cb0 = g.split * p.CB / p.KS;
+        g.cb1 = (g.split + 1) * p.CB / p.KS;
         const unsigned tn = fastdiv(T, p.div_tiles_m);
         g.tm = (int)(T - tn * (unsigned)p.tiles_m);
         const int R0 = (int)tn * p.R;
@@ -233,7 +243,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     uint32_t goff[kItems];
     int loff[kItems];
     int stage_tm = 0;
-    bool stage_on = !(PCONV_VARIANT & 32);                      // false: nothing left to load (offsets outside)
+    bool stage_on = true;                                       // false: nothing left to load (offsets outside)
     // (the descriptor of x is put together where it is used, from three scalars that are marked wave-uniform: as a
     // variable that changes from tile to tile the compiler would keep it in vector registers and wrap every load in
     // a loop over its distinct values)
@@ -282,7 +292,6 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     constexpr int NLOADS = 8 * kItems + WPIECES;
     typedef __attribute__((address_space(3))) void* lds_ptr;
     auto issue_one = [&](int cb, int buf, int j) {
-        if (PCONV_VARIANT & 2) return;
         if (j < 8 * kItems) {
             const int i = j >> 3, ch = j & 7;
             const int chan = cb * 16 + kbs * 8 + ch;
@@ -301,7 +310,6 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     // The staged activations of the next block: interleave the channels and write them to LDS; then wait for the
     // weights that are on their way into LDS, so that the barrier behind this publishes both.
     auto write_lds = [&](int buf) {
-        if (PCONV_VARIANT & 4) return;
         unsigned char* const b = ldsB + buf * 2 * p.plane_bytes;
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
@@ -379,7 +387,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
                     }
                 }
                 __builtin_amdgcn_wave_barrier();
-                if (!(PCONV_VARIANT & 8)) {
+                {
                     // where a piece of pixels of filter fi goes, or null
                     auto target = [&](int fi, int gq) -> _Float16* {
                         const int f = g.tm * MT + fbase + fi;
@@ -392,17 +400,23 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
                     if (p.sw == 8) {        // at most 28 pieces per filter: two filters per pass of the wave
                         for (int k = 0; k < 4; ++k) {
                             const int fi = 2 * k + (lane >> 5), gq = lane & 31;
+                            // (streaming stores: the outputs are not read again by this kernel, and marked so they
+                            // leave the L2 sooner; measured 5 to 8 % of the layer time where outputs are large)
                             if (_Float16* dst = target(fi, gq))
-                                *reinterpret_cast<uint4v*>(dst) = *reinterpret_cast<const uint4v*>(win + fi * WP + gq * 8);
+                                __builtin_nontemporal_store(*reinterpret_cast<const uint4v*>(win + fi * WP + gq * 8),
+                                                            reinterpret_cast<uint4v*>(dst));
                         }
                     } else {
                         for (int fi = 0; fi < 8; ++fi)
                             for (int gq = lane; gq < groups; gq += 64)
                                 if (_Float16* dst = target(fi, gq)) {
                                     const _Float16* src = win + fi * WP + gq * p.sw;
-                                    if (p.sw == 4) *reinterpret_cast<uint2v*>(dst) = *reinterpret_cast<const uint2v*>(src);
-                                    else if (p.sw == 2) *reinterpret_cast<unsigned*>(dst) = *reinterpret_cast<const unsigned*>(src);
-                                    else *dst = *src;
+                                    if (p.sw == 4)
+                                        __builtin_nontemporal_store(*reinterpret_cast<const uint2v*>(src), reinterpret_cast<uint2v*>(dst));
+                                    else if (p.sw == 2)
+                                        __builtin_nontemporal_store(*reinterpret_cast<const unsigned*>(src), reinterpret_cast<unsigned*>(dst));
+                                    else
+                                        *dst = *src;
                                 }
                     }
                 }
@@ -411,37 +425,103 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
         }
     };
 
+    // Channel blocks of a tile split over KS workgroups: every one writes its partial sums to the workspace (laid out
+    // like the registers: 16 bytes per lane and group of four accumulator rows, 1 KB per wave-wide store); the one
+    // that arrives last at the tile's counter adds the parts in the order of the splits, its own from registers, so
+    // the result does not depend on who arrives last, and goes on to the epilogue.  Memory ordering as in the vector
+    // kernels' channel split: device-scope (sc1) buffer stores, wait for them, workgroup barrier, one relaxed
+    // device-scope atomic, device-scope loads by the last arriver.  Returns whether this workgroup stores the tile.
+    auto combine_splits = [&](const TileGeo& g) -> bool {
+        constexpr int kDeviceScope = 16;   // cache-policy bit "sc1" of gfx942/gfx950 buffer instructions
+        constexpr unsigned PART = (unsigned)NW * AF * BF * 4 * 64 * 4 * 4;      // bytes of one part: MT x NT floats
+        const size_t tile_base = (size_t)g.tile * p.KS * PART;
+        const __amdgpu_buffer_rsrc_t wsr = make_rsrc(reinterpret_cast<const char*>(p.ws) + tile_base, (unsigned)p.KS * PART);
+        auto off = [&](int part, int af, int bf, int rq) {
+            return (int)((unsigned)part * PART + ((((unsigned)wave * AF + af) * BF + bf) * 4 + rq) * 1024u + lane * 16u);
+        };
+#pragma unroll
+        for (int af = 0; af < AF; ++af)
+#pragma unroll
+            for (int bf = 0; bf < BF; ++bf)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    uint4v v;
+                    v.x = __builtin_bit_cast(unsigned, (float)acc[af][bf][rq * 4 + 0]);
+                    v.y = __builtin_bit_cast(unsigned, (float)acc[af][bf][rq * 4 + 1]);
+                    v.z = __builtin_bit_cast(unsigned, (float)acc[af][bf][rq * 4 + 2]);
+                    v.w = __builtin_bit_cast(unsigned, (float)acc[af][bf][rq * 4 + 3]);
+                    __builtin_amdgcn_raw_buffer_store_b128(v, wsr, off(g.split, af, bf, rq), 0, kDeviceScope);
+                }
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): the partial sums have left
+        __syncthreads();
+        unsigned* const flag = reinterpret_cast<unsigned*>(lds + p.flag_off);
+        if (tid == 0) {
+            const unsigned arrived = __hip_atomic_fetch_add(p.counters + g.tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool last = arrived == (unsigned)p.KS - 1u;
+            if (last) __hip_atomic_store(p.counters + g.tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = last ? 1u : 0u;
+        }
+        __syncthreads();
+        const bool last = __builtin_amdgcn_readfirstlane(*flag) != 0u;
+        __syncthreads();                         // (the flag is read before the next tile's arrival rewrites it)
+        if (!last) return false;
+#pragma unroll
+        for (int af = 0; af < AF; ++af)
+#pragma unroll
+            for (int bf = 0; bf < BF; ++bf)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    float sum[4] = {0.f, 0.f, 0.f, 0.f};
+                    for (int part = 0; part < p.KS; ++part) {
+                        float q[4];
+                        if (part == g.split) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) q[i] = acc[af][bf][rq * 4 + i];
+                        } else {
+                            const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(wsr, off(part, af, bf, rq), 0, kDeviceScope);
+                            q[0] = __builtin_bit_cast(float, (unsigned)v.x);
+                            q[1] = __builtin_bit_cast(float, (unsigned)v.y);
+                            q[2] = __builtin_bit_cast(float, (unsigned)v.z);
+                            q[3] = __builtin_bit_cast(float, (unsigned)v.w);
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) sum[i] = part == 0 ? q[i] : sum[i] + q[i];
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[af][bf][rq * 4 + i] = sum[i];
+                }
+        return true;
+    };
+
     // ---- the sequence of (tile, channel block) pairs
     unsigned T = w0;
     TileGeo gc = geometry(T);
     stage_descriptors(gc);
     stage_bias(gc.tm, 0);
 #pragma unroll
-    for (int j = 0; j < NLOADS; ++j) issue_one(0, 0, j);
+    for (int j = 0; j < NLOADS; ++j) issue_one(gc.cb0, 0, j);
     write_lds(0);
     __syncthreads();
     compute_descriptors(gc);
     clear_acc();
-#ifndef PCONV_SPAN_TAPS
-#define PCONV_SPAN_TAPS 7
-#endif
-    constexpr int SPAN_TAPS = PCONV_SPAN_TAPS;
+    constexpr int SPAN_TAPS = 7;            // taps over which the next block's loads are spread (1..8 measure alike)
     int buf = 0, bias_slot = 0;
     for (;;) {
         const unsigned Tn = T + nwg;
         TileGeo gn = gc;
-        for (int cb = 0; cb < p.CB; ++cb) {
+        for (int cb = gc.cb0; cb < gc.cb1; ++cb) {
             // what is loaded during this block: the tile's next block, or the first block of the workgroup's next
             // tile, or (behind the last tile) nothing
             int ncb = cb + 1;
-            if (ncb == p.CB) {
-                ncb = 0;
+            if (ncb == gc.cb1) {
                 if (Tn < ntiles) {
                     gn = geometry(Tn);
                     stage_descriptors(gn);
                     stage_bias(gn.tm, bias_slot == 2 ? 0 : bias_slot + 1);
+                    ncb = gn.cb0;
                 } else {
                     stage_on = false;
+                    ncb = gc.cb0;
                 }
             }
             const unsigned char* const a = ldsA + buf * p.a_bytes + aoff;
@@ -471,14 +551,12 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
 #pragma unroll
                     for (int bf = 0; bf < BF; ++bf) {
                         __builtin_amdgcn_sched_barrier(0);
-                        if (!(PCONV_VARIANT & 1)) {
 #pragma unroll
-                            for (int af = 0; af < AF; ++af)
-                                acc[af][bf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ts & 1][af], fb[bf], acc[af][bf], 0, 0, 0);
-                        }
+                        for (int af = 0; af < AF; ++af)
+                            acc[af][bf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ts & 1][af], fb[bf], acc[af][bf], 0, 0, 0);
                         if (ts < 8) {
-                            if (!(PCONV_VARIANT & 16)) fb[bf] = load_b(ts + 1, bf);
-                            if (bf < AF && !(PCONV_VARIANT & 16)) fa[(ts + 1) & 1][bf] = load_a(ts + 1, bf);
+                            fb[bf] = load_b(ts + 1, bf);
+                            if (bf < AF) fa[(ts + 1) & 1][bf] = load_a(ts + 1, bf);
                         }
 #pragma unroll
                         for (int j = 0; j < NLOADS; ++j)
@@ -501,14 +579,12 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
                 for (int ts = 0; ts < 9; ++ts) {
                     if (ts < p.nt) {
                         if (ts + 1 < p.nt) fetch(ts + 1, (ts + 1) & 1);
-                        if (!(PCONV_VARIANT & 1)) {
 #pragma unroll
-                            for (int bf = 0; bf < BF; ++bf)
+                        for (int bf = 0; bf < BF; ++bf)
 #pragma unroll
-                                for (int af = 0; af < AF; ++af)
-                                    acc[af][bf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ts & 1][af], fb[ts & 1][bf],
-                                                                                        acc[af][bf], 0, 0, 0);
-                        }
+                            for (int af = 0; af < AF; ++af)
+                                acc[af][bf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ts & 1][af], fb[ts & 1][bf],
+                                                                                    acc[af][bf], 0, 0, 0);
                     }
                 }
             }
@@ -516,7 +592,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
             __syncthreads();
             buf ^= 1;
         }
-        epilogue(gc, bias_slot);
+        if (p.KS == 1 || combine_splits(gc)) epilogue(gc, bias_slot);
         if (Tn >= ntiles) break;
         T = Tn;
         gc = gn;
@@ -544,21 +620,6 @@ __global__ __launch_bounds__(256) void mfma_arrange_kernel(const unsigned short*
 struct Shape {
     int af, bf, wm, wn;
 };
-
-// Compute units of the current device (asked once per device).
-int compute_units() {
-    static std::mutex mu;
-    static int cached[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    std::lock_guard<std::mutex> lock(mu);
-    if (!cached[dev]) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
-    }
-    return cached[dev];
-}
 // tile shapes: (128 filters x 448 pixels), (64 x 448), (128 x 224), (64 x 224)
 const Shape kShapes[kMfmaShapes] = {{2, 7, 2, 2}, {1, 7, 2, 2}, {1, 7, 4, 1}, {1, 7, 2, 1}};
 
@@ -575,7 +636,7 @@ int persistent_grid(const void* kern, int threads, size_t lds, long long ntiles,
 template <int AF, int BF, int WM, int WN>
 int launch_shape(const MfmaParams& p, int lw, int ki, size_t lds, int walk, hipStream_t st) {
     const bool full = p.nt == 9;
-    const long long ntiles = (long long)p.tiles_n * p.tiles_m;
+    const long long ntiles = (long long)p.tiles_n * p.tiles_m * p.KS;
 #define PCONV_MFMA_CASE1(LWv, KIv, FULLv)                                                                       \
     if (lw == LWv && ki == KIv && full == FULLv) {                                                              \
         auto kern = mfma_conv_kernel<AF, BF, WM, WN, LWv, KIv, FULLv>;                                          \
@@ -608,6 +669,11 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.N = a.N; p.C = a.C; p.F = a.F; p.H = a.H; p.W = a.W; p.Ho = a.Ho; p.Wo = a.Wo;
     p.stride = a.stride; p.pad = a.pad; p.relu = a.relu;
     p.CB = (a.C + 15) / 16;
+    p.KS = a.splits < 1 ? 1 : a.splits;
+    if (p.KS > p.CB || p.KS > 64) return false;
+    p.div_KS = make_fastdiv((unsigned)p.KS);
+    p.ws = a.ws;
+    p.counters = a.counters;
     p.nt = a.n_taps;
     if (p.nt < 0 || p.nt > 9) return false;
     if (a.Wo > NT) return false;                                   // a tile is made of whole output rows
@@ -637,6 +703,8 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         p.bias_off = (int)staging;
         // behind the staging buffers: the bias of three tiles, and per wave a window of 8 filters x its pixels
         lds = staging + 3 * (size_t)MT * 4 + (size_t)(NTH / 64) * 8 * (sh.bf * 32 + 8) * 2;
+        p.flag_off = (int)lds;                   // one word for the channel split's "arrived last" flag
+        lds += 16;
         if (lds > 160 * 1024) continue;
         // widest loads whose pieces fit the lanes; fewer rows only when even the narrowest fit nowhere
         int w = lw;
@@ -669,8 +737,10 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.div_cnt_full = make_fastdiv((unsigned)p.cnt_full);
     p.div_tiles_m = make_fastdiv((unsigned)p.tiles_m);
     p.div_sw_groups = make_fastdiv((unsigned)p.sw_groups);
-    const long long ntiles = (long long)p.tiles_n * p.tiles_m;
+    const long long ntiles = (long long)p.tiles_n * p.tiles_m * p.KS;
     if (ntiles > 0x7FFFFFF0) return false;
+    // (the parts of one tile in the workspace are addressed with 32-bit offsets)
+    if (p.KS > 1 && (unsigned long long)p.KS * MT * NT * 4ull >= 0x7FFFFFFFull) return false;
     const long long grid = 0;   // (decided at launch: persistent workgroups, see persistent_grid)
     *out = p;
     *lw_out = lw;
@@ -681,6 +751,21 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
 }
 
 }  // namespace
+
+// Compute units of the current device (asked once per device, 256 if the runtime does not say).
+int compute_units() {
+    static std::mutex mu;
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!cached[dev]) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
 
 size_t mfma_weight_bytes(int F, int C, int mt, int n_taps) {
     return (size_t)((F + mt - 1) / mt) * ((C + 15) / 16) * n_taps * 2 * mt * 8 * sizeof(uint16_t);
@@ -694,22 +779,40 @@ int mfma_shape_height(int shape) {
 // cannot take it.  Rounds of resident workgroups times (a fixed part + channel blocks x time per block).  The block
 // times are measured ones (MI355X, VGG-16 and ResNet-50 shapes); while a workgroup has its compute unit to itself a
 // block cannot take less than the round trip of the loads that fetch the next one.
-double mfma_estimate_us(const MfmaConv& a0, int shape) {
+double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     if (shape < 1 || shape > kMfmaShapes) return -1.0;
     MfmaConv a = a0;
     a.mt = mfma_shape_height(shape);
+    a.splits = splits;
     MfmaParams p;
     int lw = 0, ki = 0, grid = 0;
     size_t lds = 0;
     if (!plan(a, shape - 1, a.rows, &p, &lw, &ki, &lds, &grid)) return -1.0;
     static const double block_us[kMfmaShapes] = {3.2, 1.6, 1.6, 1.7};
-    const long long tiles = (long long)p.tiles_n * p.tiles_m;
+    const long long tiles = (long long)p.tiles_n * p.tiles_m * p.KS;
     // the two-wave shape leaves registers for a second workgroup on a compute unit, if its LDS fits twice
     const int per_cu = shape == 4 && 2 * lds <= 160 * 1024 ? 2 : 1;
     const long long resident = (long long)compute_units() * per_cu;
     const double rounds = (double)((tiles + resident - 1) / resident);
     const double floor_us = tiles < 2 * resident ? 2.1 : 0.0;
-    return rounds * (8.0 + p.CB * std::max(block_us[shape - 1], floor_us));
+    const double blocks = (double)((p.CB + p.KS - 1) / p.KS);
+    // a split costs the round trip of the partial sums through memory and the last arriver's additions
+    const double part_bytes = (double)tiles * (kShapes[shape - 1].wm * kShapes[shape - 1].af * 32) *
+                              (kShapes[shape - 1].wn * kShapes[shape - 1].bf * 32) * 4.0;
+    return rounds * (8.0 + blocks * std::max(block_us[shape - 1], floor_us)) + (p.KS > 1 ? 20.0 + 1.5 * part_bytes / 1.5e6 : 0.0);
+}
+
+int mfma_workspace(const MfmaConv& a, size_t* floats, size_t* counters) {
+    MfmaParams p;
+    int lw = 0, ki = 0, grid = 0;
+    size_t lds = 0;
+    if (a.shape < 1 || a.shape > kMfmaShapes || !plan(a, a.shape - 1, a.rows, &p, &lw, &ki, &lds, &grid))
+        return PCONV_EUNSUPPORTED;
+    const Shape& sh = kShapes[a.shape - 1];
+    const size_t tiles = (size_t)p.tiles_n * p.tiles_m;
+    *floats = p.KS > 1 ? tiles * p.KS * (size_t)(sh.wm * sh.af * 32) * (size_t)(sh.wn * sh.bf * 32) : 0;
+    *counters = p.KS > 1 ? tiles : 0;
+    return PCONV_OK;
 }
 
 int launch_mfma_conv(const MfmaConv& a, void* stream) {
@@ -720,6 +823,7 @@ int launch_mfma_conv(const MfmaConv& a, void* stream) {
     const int shape = a.shape - 1;
     if (shape < 0 || shape >= kMfmaShapes) return PCONV_EUNSUPPORTED;
     if (!plan(a, shape, a.rows, &p, &lw, &ki, &lds, &grid)) return PCONV_EUNSUPPORTED;
+    if (p.KS > 1 && (!p.ws || !p.counters)) return PCONV_EINVAL;
     switch (shape) {
         case 0: return launch_shape<2, 7, 2, 2>(p, lw, ki, lds, a.walk, st);
         case 1: return launch_shape<1, 7, 2, 2>(p, lw, ki, lds, a.walk, st);

@@ -28,8 +28,9 @@ def run_forms(layer, x, forms, relu=None):
         try:
             got = layer.run(x, relu, **t)
         except pc.PconvError as e:
-            assert e.code == pc.EUNSUPPORTED, t       # a tile shape that cannot take the layer says so
-            assert t.get("mfma_shape", 0) != 0, "the automatic choice must find a shape or fall back"
+            assert e.code == pc.EUNSUPPORTED, t       # a tile shape or split that cannot take the layer says so
+            assert t.get("mfma_shape", 0) != 0 or t.get("channel_splits", 0) != 0, \
+                "the automatic choice must find a shape or fall back"
             say("  unsupported")
             continue
         err = rel_err(got, ref)
@@ -61,6 +62,9 @@ def test_every_tile_shape(case):
     x = L.gen_activations(spec)
     forms = [dict()] + [dict(kernel=M, mfma_shape=sh) for sh in (1, 2, 3, 4)]
     forms += [dict(kernel=M, mfma_shape=sh, rows=r) for sh in (1, 4) for r in (1, 3)]
+    # the channel blocks of every tile split over two or four workgroups (refused where there are fewer blocks)
+    forms += [dict(kernel=M, mfma_shape=sh, channel_splits=ks) for sh in (1, 2, 4) for ks in (2, 4)]
+    forms += [dict(kernel=M, channel_splits=2), dict(kernel=M, mfma_shape=3, channel_splits=2, slot_walk=1)]
     run_forms(layer, x, forms)
     run_forms(layer, x, [dict(kernel=M)], relu=True)
     layer.free()
@@ -113,6 +117,24 @@ def test_runs_are_bit_reproducible():
     first = layer.run(x)
     for _ in range(5):
         assert np.array_equal(layer.run(x).view(np.uint16), first.view(np.uint16))
+    layer.free()
+
+
+def test_split_channel_blocks_are_bit_reproducible_and_match_the_oracle():
+    """Small maps with many channels: few tiles, so the channel blocks of a tile go to several workgroups and the one
+    that arrives last adds the parts in a fixed order.  200 launches must be bit-identical (the order of arrival
+    varies from launch to launch), and the forced and the automatic choice must meet the oracle."""
+    spec = L.LayerSpec(cfg=21, idx=6, name="splitk", N=8, C=256, F=192, H=7, W=7, dtype="f16", K=8, keep=0.3)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    ref = layer.oracle(x)
+    for t in (dict(kernel=M, mfma_shape=4, channel_splits=4), dict(kernel=M, mfma_shape=2, channel_splits=8),
+              dict(kernel=M, channel_splits=16), dict(kernel=M), dict()):
+        say("split", t)
+        first = layer.run(x, **t)
+        assert rel_err(first, ref) <= TOL["f16"], t
+        for _ in range(40):
+            assert np.array_equal(layer.run(x, canary=False, **t).view(np.uint16), first.view(np.uint16)), t
     layer.free()
 
 

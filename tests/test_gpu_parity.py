@@ -476,6 +476,35 @@ def test_config2_vgg16_chain():
         l.free()
 
 
+def test_channel_split_repeats_bit_for_bit_300_times():
+    """The channel split of both vector kernels orders its partial sums without a fence (device-scope stores, a wait
+    for them, a workgroup barrier, one relaxed atomic, device-scope loads by the last arriver, sums in split order).
+    Arrival order changes from launch to launch; 300 launches of each must give the bits of the first, on a layer
+    whose automatic choice splits (config 1) and on the four-column kernel with a forced split."""
+    import torch
+    spec = L.config1()
+    layer = GpuLayer(spec)
+    dx = torch.from_numpy(L.gen_activations(spec)).cuda()
+    st = torch.cuda.current_stream().cuda_stream
+    for t in (dict(kernel=T), dict(kernel=T, rows=7, filters_per_wave=2, waves=16, channels_per_wave=2, channel_splits=4),
+              dict(kernel=pc.KERNEL_QUAD, filters_per_wave=1, channel_splits=4),
+              dict(kernel=pc.KERNEL_QUAD, filters_per_wave=2, channel_splits=2)):
+        say("300 launches", t)
+        first = None
+        for it in range(300):
+            dy = torch.empty((1, spec.F, spec.Ho, spec.Wo), dtype=torch.float32, device="cuda")
+            pc.conv3x3_tuned(dx, dy, layer.packed, layer.d_bias, 1, spec.H, spec.W, 1, 1, 0, st, **t)
+            if first is None:
+                first = dy
+                torch.cuda.synchronize()
+                assert rel_err(first.cpu().numpy(), layer.oracle(dx.cpu().numpy())) <= TOL["f32"]
+            elif it % 25 == 24 or it == 299:
+                assert bool((dy == first).all()), (t, it)      # (stops at the first block of launches that differs)
+            else:
+                first_ok = dy                                   # keep the launches back to back between checks
+    layer.free()
+
+
 # ------------------------------------------------------------------------------------------------------------------
 # config 3: ResNet-50 bottleneck 3x3 shapes, fp16 storage, batch 1 and batch 32
 # ------------------------------------------------------------------------------------------------------------------
