@@ -256,6 +256,13 @@ int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const fl
                         int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning);
 
 /*
+ * Which kernel pconv_conv3x3 takes for a shape, for device buffers aligned as allocations are (introspection; nothing
+ * is launched or allocated): *kernel receives PCONV_KERNEL_TILED, _QUAD, _GENERIC or _MFMA, *mfma_shape the tile
+ * shape of the matrix-core kernel (0 otherwise).  Either output pointer may be NULL.
+ */
+int pconv_conv3x3_choice(const pconv_packed* wp, int N, int H, int W, int stride, int pad, int* kernel, int* mfma_shape);
+
+/*
  * Dense 3x3 convolution of the same shape, for comparison: all nine taps of all F*C kernels (give it the masked
  * dense tensor to compute the same function as pconv_conv3x3).  Same conventions and argument meaning.
  *   w_oihw  device, dtype[F*C*9]

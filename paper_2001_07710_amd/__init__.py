@@ -74,6 +74,8 @@ def _load():
     lib.pconv_conv3x3_noalloc.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp]
     lib.pconv_noalloc_scratch_bytes.argtypes = []
     lib.pconv_noalloc_scratch_bytes.restype = ctypes.c_size_t
+    lib.pconv_conv3x3_choice.argtypes = [vp, i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+    lib.pconv_conv3x3_choice.restype = i
     lib.pconv_conv3x3_tuned.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp, ctypes.POINTER(_Tuning)]
     lib.pconv_dense_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, u, vp]
     lib.pconv_maxpool2x2.argtypes = [vp, vp, i, i, i, i, i, vp]
@@ -253,6 +255,14 @@ def conv3x3_noalloc(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int 
                     stream: int = 0):
     _check(_load().pconv_conv3x3_noalloc(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, pad, flags,
                                          stream or None), "pconv_conv3x3_noalloc")
+
+
+def conv3x3_choice(wp: Packed, N: int, H: int, W: int, stride: int = 1, pad: int = 1):
+    """(kernel family, tile shape of the matrix-core kernel or 0) that conv3x3 takes for this shape."""
+    k, sh = ctypes.c_int(0), ctypes.c_int(0)
+    _check(_load().pconv_conv3x3_choice(wp.handle, N, H, W, stride, pad, ctypes.byref(k), ctypes.byref(sh)),
+           "pconv_conv3x3_choice")
+    return k.value, sh.value
 
 
 def noalloc_scratch_bytes() -> int:

@@ -2182,9 +2182,14 @@ static int check_conv_args(const void* x, const void* y, int N, int C, int F, in
 
 // `arena` null: the handle's own workspace, allocated and grown on demand.  Otherwise the call allocates nothing:
 // split launches take their workspace from the arena, and a form of the layer that is not there yet is an error.
+// `plan` not null: nothing is launched or allocated; the kernel family that the call would take (and for the
+// matrix-core kernel its tile shape) is written there.
+struct PlanOut {
+    int kernel, mfma_shape;
+};
 static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                         int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning,
-                        const WsArena* arena) {
+                        const WsArena* arena, PlanOut* plan = nullptr) {
     if (!wp) return PCONV_EINVAL;
     int Ho = 0, Wo = 0;
     if (int rc = check_conv_args(x, y, N, wp->C, wp->F, H, W, stride, pad, flags, &Ho, &Wo)) return rc;
@@ -2247,6 +2252,11 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
             const double rate = stride == 2 ? 5e6 : Wo < 14 ? 10e6 : 20e6;      // multiply-adds per microsecond
             take = best_us < macs / rate + 8.0;
         }
+        if (take && plan && best_us >= 0.0) {
+            plan->kernel = PCONV_KERNEL_MFMA;
+            plan->mfma_shape = a.shape;
+            return PCONV_OK;
+        }
         int rc = PCONV_EUNSUPPORTED;
         if (take)
             for (const MfmaWeights& m : wp->mfma) {
@@ -2301,6 +2311,11 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
     }
     if (kernel == PCONV_KERNEL_AUTO) kernel = can_tile ? PCONV_KERNEL_TILED : PCONV_KERNEL_GENERIC;
     if (kernel == PCONV_KERNEL_TILED && !can_tile) return PCONV_EUNSUPPORTED;
+    if (plan) {
+        plan->kernel = kernel;
+        plan->mfma_shape = 0;
+        return PCONV_OK;
+    }
     const pconv_packed* lay = wp;
     const void* tx = x;
     // Stride 2 with even H and W: the kernels with paired staging read the parity planes straight from x (16 waves,
@@ -2502,6 +2517,18 @@ extern "C" int pconv_conv3x3_noalloc(const void* x, void* y, const pconv_packed*
 }
 
 extern "C" size_t pconv_noalloc_scratch_bytes(void) { return kArenaBytes; }
+
+extern "C" int pconv_conv3x3_choice(const pconv_packed* wp, int N, int H, int W, int stride, int pad, int* kernel,
+                                    int* mfma_shape) {
+    PlanOut out{0, 0};
+    // (pointers that are aligned as device allocations are; nothing is read through them)
+    void* const aligned = reinterpret_cast<void*>(static_cast<uintptr_t>(4096));
+    const int rc = conv3x3_impl(aligned, aligned, wp, nullptr, N, H, W, stride, pad, 0, nullptr, nullptr, nullptr, &out);
+    if (rc != PCONV_OK) return rc;
+    if (kernel) *kernel = out.kernel;
+    if (mfma_shape) *mfma_shape = out.mfma_shape;
+    return PCONV_OK;
+}
 
 extern "C" int pconv_dense_conv3x3(const void* x, void* y, const void* w, const float* bias, int dtype, int N, int C,
                                    int F, int H, int W, int stride, int pad, unsigned flags, void* stream) {

@@ -253,11 +253,16 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
         stage_tm = g.tm;
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
+            // Neighbouring lanes take neighbouring ROWS of the same column group, not neighbouring groups of one row:
+            // a lane writes its LW positions to LDS one after the other, so the 16 lanes that one 128-bit LDS write
+            // serves together are LW*16 bytes apart along a row -- with 8 pixels per lane only two different bank
+            // groups, an 8-way conflict -- but a row pitch of W + 2 positions apart across rows, which spreads them
+            // (measured before the change: 37 to 48 % of the LDS's busy time were bank conflicts).
             const unsigned it = (unsigned)(ltid + i * HALF);
-            const unsigned sl = fastdiv(it, p.div_G), gg = it - sl * (unsigned)p.G;
+            const unsigned gg = it / (unsigned)g.used_slots, sl = it - gg * (unsigned)g.used_slots;
             goff[i] = kInvalid;
             loff[i] = -1;
-            if ((int)sl < g.used_slots) {
+            if (gg < (unsigned)p.G) {
                 int seg, iy;
                 if ((int)sl < g.cnt0) {
                     seg = 0;
@@ -788,7 +793,7 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     int lw = 0, ki = 0, grid = 0;
     size_t lds = 0;
     if (!plan(a, shape - 1, a.rows, &p, &lw, &ki, &lds, &grid)) return -1.0;
-    static const double block_us[kMfmaShapes] = {3.2, 1.6, 1.6, 1.7};
+    static const double block_us[kMfmaShapes] = {3.2, 1.7, 1.7, 1.8};
     const long long tiles = (long long)p.tiles_n * p.tiles_m * p.KS;
     // the two-wave shape leaves registers for a second workgroup on a compute unit, if its LDS fits twice
     const int per_cu = shape == 4 && 2 * lds <= 160 * 1024 ? 2 : 1;
