@@ -59,6 +59,9 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 
 constexpr uint32_t kInvalid = 0x80000000u;
 
@@ -103,11 +106,12 @@ struct MfmaParams {
     int plane_bytes;        // one half (8 channels) of the activations of one block: max_slots * PW * 16
     int bias_off;           // byte offset in LDS of the bias values (three tiles), behind the staging buffers
     int sw;                 // pixels per store piece: 8, 4, 2 or 1
-    unsigned long long x_bytes;
+    unsigned long long y_bytes, x_bytes;
     unsigned wq_bytes;
     unsigned chan_bytes;    // H*W*2
     unsigned img_bytes;     // C*H*W*2
-    int KS;                 // workgroups that share one tile, each taking a contiguous range of the channel blocks
+    int KS;                      // workgroups that share one tile, each taking a contiguous range of the channel blocks
+    int stagger;                 // every second workgroup starts this many steps of 2048 clocks late (0: none)
     float* ws;              // KS > 1: partial sums [tile][split][wave][operand tile][4 rows][64 lanes][4], as held
     unsigned* counters;     // KS > 1: one arrival counter per tile, zero between launches
     int flag_off;           // byte offset in LDS of the word that tells a workgroup's waves whether it arrived last
@@ -178,17 +182,30 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     constexpr int kItems = KI;
     constexpr int NW = WM * WN, NTH = NW * 64, MT = WM * AF * 32, HALF = NTH / 2;
     constexpr int WPIECES = (9 * 2 * MT + NTH - 1) / NTH;      // 16-byte pieces of weights per lane and block, at most
-    constexpr int WP = BF * 32 + 8;                            // halves between two filters of a wave's output window
+    constexpr int WP = BF * 32 + 16;                           // words between two filter pairs of a wave's output window
+                                                               // (twice that is 32 mod 64: the two halves of a wave
+                                                               // write different LDS banks)
     extern __shared__ __align__(16) unsigned char lds[];
 
     // ---- which tiles: consecutive workgroup ids go round the XCDs; workgroups of one XCD get consecutive tiles, so
     // the m-tiles of one n-tile (which read the same activations) and n-tiles that are neighbours in memory share
     // an L2.  gridDim.x is a multiple of 8.
     const unsigned nwg = gridDim.x;
-    const unsigned w0 = (blockIdx.x & 7u) * (nwg >> 3) + (blockIdx.x >> 3);
+    unsigned w0 = (blockIdx.x & 7u) * (nwg >> 3) + (blockIdx.x >> 3);
+    // Staggered start (p.stagger > 0, set by the host when it costs no extra round): every second workgroup of an
+    // XCD starts half a tile's time late, and takes its tiles from the upper half of the ids, so the late ones are
+    // those with one tile less.  Left alone, all workgroups reach their epilogue at the same moment, the stores of
+    // the whole chip arrive in one burst, and the loads of the next tile queue behind them.
+    const bool late = p.stagger > 0 && ((blockIdx.x >> 3) & 1u);
+    if (p.stagger > 0) {
+        const unsigned half_per = nwg >> 4;
+        w0 = (late ? (nwg >> 1) : 0u) + (blockIdx.x & 7u) * half_per + (blockIdx.x >> 4);
+    }
     // (a work item is a tile, or one of the KS parts of a tile's channel blocks; the parts of a tile are neighbours)
     const unsigned ntiles = (unsigned)p.tiles_n * (unsigned)p.tiles_m * (unsigned)p.KS;
     if (w0 >= ntiles) return;
+    if (late)
+        for (int i = 0; i < p.stagger; ++i) __builtin_amdgcn_s_sleep(32);      // 2048 clocks each
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (tells the compiler that it is wave-uniform)
@@ -219,7 +236,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     unsigned char* const ldsA = lds;
     unsigned char* const ldsB = lds + 2 * p.a_bytes;
     float* const ldsBias = reinterpret_cast<float*>(lds + p.bias_off);          // [3][MT]: by tile count modulo 3
-    _Float16* const win = reinterpret_cast<_Float16*>(lds + p.bias_off + 3 * MT * 4) + wave * (8 * WP);
+    unsigned* const win = reinterpret_cast<unsigned*>(lds + p.bias_off + 3 * MT * 4) + wave * (4 * WP);
 
     // ---- once: zero columns left and right of the image (no tile's staging ever writes them)
     if (p.pad) {
@@ -230,11 +247,14 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
             *reinterpret_cast<uint4v*>(ldsB + (which >> 1) * p.plane_bytes + (sl * PW + pos) * 16) = zero;
         }
     }
+    // The tile's biases: 4 bytes per lane straight into LDS (buffer_load ... lds), in flight while the block that
+    // issues them is multiplied; outside the tensor (filters behind the last, or no bias at all) the load gives zero.
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    const __amdgpu_buffer_rsrc_t br = make_rsrc(p.bias, p.bias ? (unsigned)p.F * 4u : 0u);
     auto stage_bias = [&](int tm, int slot) {
-        for (int i = tid; i < MT; i += NTH) {
-            const int f = tm * MT + i;
-            ldsBias[slot * MT + i] = (p.bias && f < p.F) ? p.bias[f] : 0.f;
-        }
+        if (wave * 64 < MT)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(br, (lds_ptr)(ldsBias + slot * MT + wave * 64), 4,
+                                                     (tm * MT + wave * 64 + lane) * 4, 0, 0, 0);
     };
 
     // ---- staging state: descriptors of this lane for the tile whose blocks are being loaded
@@ -295,7 +315,6 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     // LDS (buffer_load ... lds: lane l's 16 bytes land at the wave's base + 16*l, no registers in between); the
     // buffer is free from the barrier that ended the block before the current one.
     constexpr int NLOADS = 8 * kItems + WPIECES;
-    typedef __attribute__((address_space(3))) void* lds_ptr;
     auto issue_one = [&](int cb, int buf, int j) {
         if (j < 8 * kItems) {
             const int i = j >> 3, ch = j & 7;
@@ -352,82 +371,160 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
         }
     };
 
+    // The accumulators of a tile start at the bias of their filter (accumulator row r of a 32 x 32 block is filter
+    // (r/4)*8 + (lane/32)*4 + r%4), or at zero in the workgroups that take a later part of a split tile's channels.
     float16v acc[AF][BF];
-    auto clear_acc = [&]() {
+    auto start_acc = [&](const TileGeo& g, int bias_slot) {
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));                         // (computed here, not ahead of everything)
+        const float4v* const b4 =
+            reinterpret_cast<const float4v*>(ldsBias + bias_slot * MT + wm * AF * 32 + (lane_e >> 5) * 4);
 #pragma unroll
         for (int af = 0; af < AF; ++af)
 #pragma unroll
-            for (int bf = 0; bf < BF; ++bf)
+            for (int rq = 0; rq < 4; ++rq) {
+                float4v b = b4[af * 8 + rq * 2];
+                if (g.split != 0) b = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[af][bf][r] = 0.f;
+                for (int bf = 0; bf < BF; ++bf)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[af][bf][rq * 4 + i] = b[i];
+            }
     };
 
-    // Bias, ReLU, fp16; eight filters of the wave's pixels at a time through the wave's own window in LDS
-    // ([filter][pixel]), from where they leave in pieces of sw pixels of one filter per lane.  No workgroup barrier:
-    // a wave reads back only what it wrote itself, and LDS operations of one wave complete in order.
-    auto epilogue = [&](const TileGeo& g, int bias_slot) {
+    // fp16, ReLU; eight filters of the wave's pixels at a time through the wave's own window in LDS.  A lane holds
+    // four of the eight filters for its pixel: it rounds them to fp16 two at a time (one packed conversion) and
+    // writes the two words to [filter pair][pixel]; a lane then reads back 8 consecutive pixels of one pair, takes the
+    // two filters apart (byte permutes) and stores each in 8/sw pieces of sw pixels, sw being the widest piece that
+    // never crosses an output row.  No workgroup barrier: a wave reads back only what it wrote itself, and LDS
+    // operations of one wave complete in order -- which also lets the next eight filters be written into the window
+    // right behind the reads of the current ones, before their data has come back.  Everything that depends on the
+    // pixel alone (row, image, column: two divisions by constants) is worked out once per tile and lane; a store
+    // adds one wave-uniform filter offset.  (Per value this is one maximum, half a conversion and half an LDS write;
+    // the first version, which added the bias here, wrote 16-bit words and worked every address out per store,
+    // took as long as two to three channel blocks.)
+    auto epilogue = [&](const TileGeo& g) {
         // (the lane index as the compiler cannot see through it: everything below depends on it and is computed
         // here, not ahead of the channel blocks, where it would sit in registers that the multiply loop needs)
         int lane_e = lane;
         asm volatile("" : "+v"(lane_e));
-        const int li = lane_e & 31, lk = lane_e >> 5, lane = lane_e;
-        const float* const bias = ldsBias + bias_slot * MT;
-        const size_t plane = (size_t)Ho * Wo;
+        const int li = lane_e & 31, lk = lane_e >> 5;
+        const unsigned plane = (unsigned)(Ho * Wo);
         const int valid = g.Rv * Wo - wn * BF * 32;              // pixels of the wave's range that exist
-        const int groups = valid <= 0 ? 0 : min(valid, BF * 32) / p.sw;   // store pieces per filter (sw divides Wo)
-        _Float16* const ytile = reinterpret_cast<_Float16*>(p.y) + (size_t)g.n0 * p.F * plane;
+        const int sw = p.sw;
+        // ReLU on the rounded halves, both at once: the maximum with +0, or, where there is no ReLU, with a quiet
+        // NaN -- the maximum of a number and a NaN is the number (IEEE 754 maxNum), so that leaves every value as
+        // it is, NaN included, without a second copy of this code and without a select per value
+        const half2v floor2 = __builtin_bit_cast(half2v, p.relu ? 0u : 0x7E007E00u);
+        // The lane's pieces: byte offset of pixel q0 and on, for the first filter of the lane's pair (2*lk), from the
+        // tile's first image; kInvalid (beyond the descriptor's range, the store is dropped) where there is none.
+        // (The host has checked that the images one tile touches end below 2^31 bytes.)
+        uint32_t dst0[8];
+        const int f_lane = g.tm * MT + 2 * lk;
+        auto piece = [&](int j) -> uint32_t {
+            const int q_wave = li * 8 + j * sw;                   // pixel in the wave's range
+            if (li * 8 >= BF * 32 || q_wave >= valid) return kInvalid;
+            const unsigned q0 = (unsigned)(wn * BF * 32 + q_wave);
+            const unsigned row = fastdiv(q0, p.div_Wo), ox = q0 - row * (unsigned)Wo;
+            const unsigned rr = (unsigned)g.oy0 + row, sg = fastdiv(rr, p.div_Ho), oy = rr - sg * (unsigned)Ho;
+            return ((sg * (unsigned)p.F + (unsigned)f_lane) * plane + oy * (unsigned)Wo + ox) * 2u;
+        };
 #pragma unroll
-        for (int af = 0; af < AF; ++af) {
+        for (int j = 0; j < 8; ++j) dst0[j] = kInvalid;
+        dst0[0] = piece(0);
+        if (sw < 8) {
+            dst0[1] = piece(1);
+            if (sw < 4) {
+                dst0[2] = piece(2);
+                dst0[3] = piece(3);
+                if (sw < 2) {
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const int fbase = (wm * AF + af) * 32 + rq * 8;          // first of the eight filters, in the tile
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float bv = bias[fbase + lk * 4 + i];
-#pragma unroll
-                    for (int bf = 0; bf < BF; ++bf) {
-                        float v = acc[af][bf][rq * 4 + i] + bv;
-                        if (p.relu) v = fmaxf(v, 0.f);
-                        win[(lk * 4 + i) * WP + bf * 32 + li] = (_Float16)v;
-                    }
+                    for (int j = 4; j < 8; ++j) dst0[j] = piece(j);
                 }
-                __builtin_amdgcn_wave_barrier();
-                {
-                    // where a piece of pixels of filter fi goes, or null
-                    auto target = [&](int fi, int gq) -> _Float16* {
-                        const int f = g.tm * MT + fbase + fi;
-                        if (f >= p.F || gq >= groups) return nullptr;
-                        const unsigned q0 = (unsigned)(wn * BF * 32 + gq * p.sw);      // pixel in the tile
-                        const unsigned row = fastdiv(q0, p.div_Wo), ox = q0 - row * (unsigned)Wo;
-                        const unsigned rr = (unsigned)g.oy0 + row, sg = fastdiv(rr, p.div_Ho), oy = rr - sg * (unsigned)Ho;
-                        return ytile + ((size_t)sg * p.F + (size_t)f) * plane + (size_t)oy * Wo + ox;
-                    };
-                    if (p.sw == 8) {        // at most 28 pieces per filter: two filters per pass of the wave
-                        for (int k = 0; k < 4; ++k) {
-                            const int fi = 2 * k + (lane >> 5), gq = lane & 31;
-                            // (streaming stores: the outputs are not read again by this kernel, and marked so they
-                            // leave the L2 sooner; measured 5 to 8 % of the layer time where outputs are large)
-                            if (_Float16* dst = target(fi, gq))
-                                __builtin_nontemporal_store(*reinterpret_cast<const uint4v*>(win + fi * WP + gq * 8),
-                                                            reinterpret_cast<uint4v*>(dst));
-                        }
-                    } else {
-                        for (int fi = 0; fi < 8; ++fi)
-                            for (int gq = lane; gq < groups; gq += 64)
-                                if (_Float16* dst = target(fi, gq)) {
-                                    const _Float16* src = win + fi * WP + gq * p.sw;
-                                    if (p.sw == 4)
-                                        __builtin_nontemporal_store(*reinterpret_cast<const uint2v*>(src), reinterpret_cast<uint2v*>(dst));
-                                    else if (p.sw == 2)
-                                        __builtin_nontemporal_store(*reinterpret_cast<const unsigned*>(src), reinterpret_cast<unsigned*>(dst));
-                                    else
-                                        *dst = *src;
-                                }
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
             }
         }
+        const unsigned long long y_off = (unsigned long long)g.n0 * p.F * plane * 2;
+        const unsigned long long y_left = p.y_bytes - y_off, yb = reinterpret_cast<unsigned long long>(p.y) + y_off;
+        const unsigned yb_lo = __builtin_amdgcn_readfirstlane((unsigned)yb);
+        const unsigned yb_hi = __builtin_amdgcn_readfirstlane((unsigned)(yb >> 32));
+        const unsigned y_records = __builtin_amdgcn_readfirstlane(y_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (unsigned)y_left);
+        const __amdgpu_buffer_rsrc_t yr =
+            make_rsrc(reinterpret_cast<const void*>(((unsigned long long)yb_hi << 32) | yb_lo), y_records);
+        constexpr int kStream = 2;     // cache-policy bit "nt": the outputs are not read again by this kernel and leave
+                                       // the L2 sooner (measured 5 to 8 % of the layer time where outputs are large)
+        unsigned* const wbase = win + lk * 2 * WP + li;            // the lane's own pixel, its first filter pair
+        const unsigned* const rbase = win + lk * WP + li * 8;      // 8 pixels of the pair the lane stores first
+        constexpr int P = AF * 4;
+        auto write_pass = [&](int pass) {
+            const int af = pass >> 2, rq = pass & 3;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int bf = 0; bf < BF; ++bf) {
+                    const float2v v = {acc[af][bf][rq * 4 + 2 * h], acc[af][bf][rq * 4 + 2 * h + 1]};
+                    const half2v hv = __builtin_elementwise_max(__builtin_convertvector(v, half2v), floor2);
+                    wbase[h * WP + bf * 32] = __builtin_bit_cast(unsigned, hv);
+                }
+        };
+        write_pass(0);
+#pragma unroll
+        for (int pass = 0; pass < P; ++pass) {
+            __builtin_amdgcn_wave_barrier();
+            uint4v r[2][2];                                         // [round: pairs 0,1 / 2,3][pixels 0-3 / 4-7]
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+#pragma unroll
+                for (int hx = 0; hx < 2; ++hx) r[k][hx] = *reinterpret_cast<const uint4v*>(rbase + 2 * k * WP + hx * 4);
+            __builtin_amdgcn_wave_barrier();
+            if (pass + 1 < P) write_pass(pass + 1);
+            __builtin_amdgcn_wave_barrier();
+            // the four filters this lane stores in this pass: 4*k + which (+ 2*lk), 8 pixels each
+            const int fbase = (wm * AF + (pass >> 2)) * 32 + (pass & 3) * 8;      // (wave-uniform)
+            unsigned o[4][4];
+            int foff[4];
+            bool f_ok[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int k = t >> 1;
+                const unsigned sel = (t & 1) ? 0x07060302u : 0x05040100u;   // the pair's second filter / its first
+                o[t][0] = __builtin_amdgcn_perm(r[k][0].y, r[k][0].x, sel);
+                o[t][1] = __builtin_amdgcn_perm(r[k][0].w, r[k][0].z, sel);
+                o[t][2] = __builtin_amdgcn_perm(r[k][1].y, r[k][1].x, sel);
+                o[t][3] = __builtin_amdgcn_perm(r[k][1].w, r[k][1].z, sel);
+                const int fi = fbase + 4 * k + (t & 1);
+                f_ok[t] = f_lane + fi < p.F;
+                foff[t] = fi * (int)plane * 2;                        // (wave-uniform: the scalar offset)
+            }
+            auto at = [&](int t, int j) { return (int)(f_ok[t] ? dst0[j] : kInvalid); };
+            // (the piece width is chosen once per pass: with the choice around every single store, each sat behind
+            // half a dozen branches, and those, not the stores, were most of the epilogue's time)
+            if (sw == 8) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    __builtin_amdgcn_raw_buffer_store_b128(uint4v{o[t][0], o[t][1], o[t][2], o[t][3]}, yr, at(t, 0), foff[t],
+                                                           kStream);
+            } else if (sw == 4) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    __builtin_amdgcn_raw_buffer_store_b64(uint2v{o[t][0], o[t][1]}, yr, at(t, 0), foff[t], kStream);
+                    __builtin_amdgcn_raw_buffer_store_b64(uint2v{o[t][2], o[t][3]}, yr, at(t, 1), foff[t], kStream);
+                }
+            } else if (sw == 2) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        __builtin_amdgcn_raw_buffer_store_b32(o[t][j], yr, at(t, j), foff[t], kStream);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(o[t][j >> 1] >> ((j & 1) * 16)), yr, at(t, j),
+                                                              foff[t], kStream);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
     };
 
     // Channel blocks of a tile split over KS workgroups: every one writes its partial sums to the workspace (laid out
@@ -508,7 +605,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     write_lds(0);
     __syncthreads();
     compute_descriptors(gc);
-    clear_acc();
+    start_acc(gc, 0);
     constexpr int SPAN_TAPS = 7;            // taps over which the next block's loads are spread (1..8 measure alike)
     int buf = 0, bias_slot = 0;
     for (;;) {
@@ -597,13 +694,13 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
             __syncthreads();
             buf ^= 1;
         }
-        if (p.KS == 1 || combine_splits(gc)) epilogue(gc, bias_slot);
+        if (p.KS == 1 || combine_splits(gc)) epilogue(gc);
         if (Tn >= ntiles) break;
         T = Tn;
         gc = gn;
         bias_slot = bias_slot == 2 ? 0 : bias_slot + 1;
         compute_descriptors(gc);
-        clear_acc();
+        start_acc(gc, bias_slot);
     }
 }
 
@@ -625,6 +722,8 @@ __global__ __launch_bounds__(256) void mfma_arrange_kernel(const unsigned short*
 struct Shape {
     int af, bf, wm, wn;
 };
+// measured time of one channel block of one tile with the device full, microseconds, per tile shape
+const double kBlockUs[kMfmaShapes] = {3.2, 1.7, 1.7, 1.8};
 // tile shapes: (128 filters x 448 pixels), (64 x 448), (128 x 224), (64 x 224)
 const Shape kShapes[kMfmaShapes] = {{2, 7, 2, 2}, {1, 7, 2, 2}, {1, 7, 4, 1}, {1, 7, 2, 1}};
 
@@ -638,8 +737,20 @@ int persistent_grid(const void* kern, int threads, size_t lds, long long ntiles,
     return (int)std::max<long long>(8, std::min<long long>((ntiles + 7) / 8 * 8, resident));
 }
 
+// Steps of 2048 clocks by which every second workgroup starts late (0: all start together).  Half a tile's time,
+// and only where the late workgroups do not add a round of their own: the last round is at most half full, and they
+// are the ones that sit it out.  (Measured on 128 x 256 channels at 56 x 56, batch 64, 3.5 rounds: 209 -> 198 us;
+// with 7 or 14 full rounds the half tile more costs as much as the smoother stores gain.)
+int stagger_steps(const MfmaParams& p, int grid, long long ntiles, int walk, double block_us) {
+    if (walk == 1 || p.KS != 1 || (grid & 15) || ntiles <= grid) return 0;
+    const long long rem = ntiles % grid;
+    if (rem == 0 || rem > grid / 2) return 0;
+    const double half_tile_us = 0.5 * p.CB * block_us;
+    return (int)std::min(4096.0, half_tile_us * 2400.0 / 2048.0 + 0.5);
+}
+
 template <int AF, int BF, int WM, int WN>
-int launch_shape(const MfmaParams& p, int lw, int ki, size_t lds, int walk, hipStream_t st) {
+int launch_shape(const MfmaParams& p, int lw, int ki, size_t lds, int walk, double block_us, hipStream_t st) {
     const bool full = p.nt == 9;
     const long long ntiles = (long long)p.tiles_n * p.tiles_m * p.KS;
 #define PCONV_MFMA_CASE1(LWv, KIv, FULLv)                                                                       \
@@ -648,13 +759,19 @@ int launch_shape(const MfmaParams& p, int lw, int ki, size_t lds, int walk, hipS
         if (lds > 64 * 1024)                                                                                    \
             PCONV_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
         const int grid = persistent_grid((const void*)kern, WM * WN * 64, lds, ntiles, walk);                        \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(WM* WN * 64), lds, st, p);                                    \
+        MfmaParams q = p;                                                                                       \
+        q.stagger = stagger_steps(p, grid, ntiles, walk, block_us);                                             \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(WM* WN * 64), lds, st, q);                                    \
         PCONV_HIP(hipGetLastError());                                                                           \
         return PCONV_OK;                                                                                        \
     }
 #define PCONV_MFMA_CASE(LWv, KIv) PCONV_MFMA_CASE1(LWv, KIv, true) PCONV_MFMA_CASE1(LWv, KIv, false)
+#ifdef PCONV_ONLY_ONE
+    PCONV_MFMA_CASE1(8, 1, true)
+#else
     PCONV_MFMA_CASE(8, 1) PCONV_MFMA_CASE(8, 2) PCONV_MFMA_CASE(4, 2) PCONV_MFMA_CASE(4, 3) PCONV_MFMA_CASE(2, 3)
     PCONV_MFMA_CASE(1, 3)
+#endif
 #undef PCONV_MFMA_CASE
 #undef PCONV_MFMA_CASE1
     return PCONV_EUNSUPPORTED;
@@ -706,8 +823,8 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         p.plane_bytes = p.max_slots * p.PW * 16;
         const size_t staging = 2 * (size_t)p.a_bytes + 4 * (size_t)p.plane_bytes;
         p.bias_off = (int)staging;
-        // behind the staging buffers: the bias of three tiles, and per wave a window of 8 filters x its pixels
-        lds = staging + 3 * (size_t)MT * 4 + (size_t)(NTH / 64) * 8 * (sh.bf * 32 + 8) * 2;
+        // behind the staging buffers: the bias of three tiles, and per wave a window of 4 filter pairs x its pixels
+        lds = staging + 3 * (size_t)MT * 4 + (size_t)(NTH / 64) * 4 * (sh.bf * 32 + 16) * 4;
         p.flag_off = (int)lds;                   // one word for the channel split's "arrived last" flag
         lds += 16;
         if (lds > 160 * 1024) continue;
@@ -733,6 +850,8 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     const unsigned long long img = (unsigned long long)a.C * a.H * a.W * 2ull;
     if (img * (unsigned long long)(segs + 1) >= 0x7FFFFFFFull) return false;   // 32-bit offsets inside a tile's images
     p.img_bytes = (unsigned)img;
+    p.y_bytes = (unsigned long long)a.N * a.F * a.Ho * a.Wo * 2ull;
+    if ((unsigned long long)a.F * a.Ho * a.Wo * 2ull * (unsigned long long)(segs + 1) >= 0x7FFFFFFFull) return false;
     const size_t wq_bytes = mfma_weight_bytes(a.F, a.C, MT, p.nt);
     if (wq_bytes >= 0x7FFFFFFFull) return false;
     p.wq_bytes = (unsigned)wq_bytes;
@@ -793,7 +912,7 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     int lw = 0, ki = 0, grid = 0;
     size_t lds = 0;
     if (!plan(a, shape - 1, a.rows, &p, &lw, &ki, &lds, &grid)) return -1.0;
-    static const double block_us[kMfmaShapes] = {3.2, 1.7, 1.7, 1.8};
+    const double* block_us = kBlockUs;
     const long long tiles = (long long)p.tiles_n * p.tiles_m * p.KS;
     // the two-wave shape leaves registers for a second workgroup on a compute unit, if its LDS fits twice
     const int per_cu = shape == 4 && 2 * lds <= 160 * 1024 ? 2 : 1;
@@ -830,10 +949,10 @@ int launch_mfma_conv(const MfmaConv& a, void* stream) {
     if (!plan(a, shape, a.rows, &p, &lw, &ki, &lds, &grid)) return PCONV_EUNSUPPORTED;
     if (p.KS > 1 && (!p.ws || !p.counters)) return PCONV_EINVAL;
     switch (shape) {
-        case 0: return launch_shape<2, 7, 2, 2>(p, lw, ki, lds, a.walk, st);
-        case 1: return launch_shape<1, 7, 2, 2>(p, lw, ki, lds, a.walk, st);
-        case 2: return launch_shape<1, 7, 4, 1>(p, lw, ki, lds, a.walk, st);
-        case 3: return launch_shape<1, 7, 2, 1>(p, lw, ki, lds, a.walk, st);
+        case 0: return launch_shape<2, 7, 2, 2>(p, lw, ki, lds, a.walk, kBlockUs[0], st);
+        case 1: return launch_shape<1, 7, 2, 2>(p, lw, ki, lds, a.walk, kBlockUs[1], st);
+        case 2: return launch_shape<1, 7, 4, 1>(p, lw, ki, lds, a.walk, kBlockUs[2], st);
+        case 3: return launch_shape<1, 7, 2, 1>(p, lw, ki, lds, a.walk, kBlockUs[3], st);
     }
     return PCONV_EUNSUPPORTED;
 }
