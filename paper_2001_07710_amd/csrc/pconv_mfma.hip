@@ -271,6 +271,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.wq_bytes);
     auto stage_descriptors = [&](const TileGeo& g) {
         stage_tm = g.tm;
+        const float inv_slots = 1.0f / (float)g.used_slots;
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
             // Neighbouring lanes take neighbouring ROWS of the same column group, not neighbouring groups of one row:
@@ -278,8 +279,11 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
             // serves together are LW*16 bytes apart along a row -- with 8 pixels per lane only two different bank
             // groups, an 8-way conflict -- but a row pitch of W + 2 positions apart across rows, which spreads them
             // (measured before the change: 37 to 48 % of the LDS's busy time were bank conflicts).
+            // (the quotient by way of the reciprocal: exact for these sizes, the remainder of (it + 1/2) / slots is
+            // at least 1/(2 slots) away from a whole number, far more than the rounding errors; an integer division
+            // by a number that is not known when compiling is some forty instructions)
             const unsigned it = (unsigned)(ltid + i * HALF);
-            const unsigned gg = it / (unsigned)g.used_slots, sl = it - gg * (unsigned)g.used_slots;
+            const unsigned gg = (unsigned)(((float)it + 0.5f) * inv_slots), sl = it - gg * (unsigned)g.used_slots;
             goff[i] = kInvalid;
             loff[i] = -1;
             if (gg < (unsigned)p.G) {
@@ -356,7 +360,11 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     const int li = lane & 31, lk = lane >> 5;                   // row/column of the operand tile, half of its K
     const int aoff = (lk * MT + wm * AF * 32 + li) * 16;
     int boff[BF];
+    int boff_rows = -1;             // >= 0: boff is that of a tile of so many rows inside one image (the same for all)
     auto compute_descriptors = [&](const TileGeo& g) {
+        const int rows_key = g.oy0 + g.Rv <= Ho ? g.Rv : -1;
+        if (rows_key >= 0 && rows_key == boff_rows) return;
+        boff_rows = rows_key;
 #pragma unroll
         for (int bf = 0; bf < BF; ++bf) {
             const unsigned q = (unsigned)((wn * BF + bf) * 32 + li);
@@ -724,7 +732,8 @@ struct Shape {
 };
 // measured time of one channel block of one tile with the device full, microseconds, per tile shape
 const double kBlockUs[kMfmaShapes] = {3.2, 1.7, 1.7, 1.8};
-// tile shapes: (128 filters x 448 pixels), (64 x 448), (128 x 224), (64 x 224)
+// tile shapes: (128 filters x 448 pixels), (64 x 448), (128 x 224), (64 x 224).  (64 x 896, four waves side by
+// side, was tried for layers of 64 filters at 224 x 224 and measured no faster than 64 x 448 there.)
 const Shape kShapes[kMfmaShapes] = {{2, 7, 2, 2}, {1, 7, 2, 2}, {1, 7, 4, 1}, {1, 7, 2, 1}};
 
 // Workgroups of the persistent grid: as many as the device holds at once (compute units x workgroups that fit one),
@@ -818,6 +827,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     for (;; --R) {
         if (R < 1) return false;
         segs = std::min(R, (R + a.Ho - 2) / a.Ho + 1);
+        if (a.Ho % R == 0) segs = 1;                         // (tiles never cross from one image into the next)
         p.max_slots = (R - segs) * a.stride + 3 * segs;
         p.a_bytes = p.nt * 2 * MT * 16;
         p.plane_bytes = p.max_slots * p.PW * 16;
