@@ -32,6 +32,10 @@ double pconv_peak_lds_read_bytes_per_clk(int waves);
  * spends per wave-wide load instruction (the issue rate of its address unit). */
 double pconv_peak_vmem_clk_per_load(int bytes_per_lane);
 
+/* Streaming global stores of 16 bytes per lane to lines that stay in the L2, `waves` (1..16) waves per compute unit:
+ * clocks a compute unit spends per wave-wide store instruction (1 KB). */
+double pconv_peak_vmem_clk_per_store(int waves);
+
 /* Dense fp16 matrix-core multiply-adds (v_mfma_f32_32x32x16_f16) on registers only, `waves_per_simd` = 1 or 2:
  * TFLOP/s. */
 double pconv_peak_mfma_f16_tflops(int waves_per_simd);

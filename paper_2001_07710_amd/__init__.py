@@ -122,7 +122,7 @@ def peaks() -> dict:
     lib = ctypes.CDLL(PEAKS_LIB_PATH)
     d, i = ctypes.c_double, ctypes.c_int
     for name in ("pconv_peak_copy_gbs", "pconv_peak_fma_tflops", "pconv_peak_lds_read_bytes_per_clk",
-                 "pconv_peak_vmem_clk_per_load", "pconv_peak_mfma_f16_tflops"):
+                 "pconv_peak_vmem_clk_per_load", "pconv_peak_vmem_clk_per_store", "pconv_peak_mfma_f16_tflops"):
         getattr(lib, name).argtypes = [i]
         getattr(lib, name).restype = d
     lib.pconv_peak_device.argtypes = [ctypes.POINTER(i), ctypes.POINTER(d)]
@@ -136,6 +136,7 @@ def peaks() -> dict:
         "fp32_fma_TFLOPs": {f"{w}_waves_per_simd": lib.pconv_peak_fma_tflops(w) for w in (1, 2, 4)},
         "lds_read_b128_bytes_per_clk_per_cu": {f"{w}_waves": lib.pconv_peak_lds_read_bytes_per_clk(w) for w in (4, 8, 16)},
         "vmem_clk_per_wave_load": {f"{b}B_per_lane": lib.pconv_peak_vmem_clk_per_load(b) for b in (4, 16)},
+        "vmem_clk_per_wave_store_16B_per_lane": {f"{w}_waves": lib.pconv_peak_vmem_clk_per_store(w) for w in (4, 16)},
         "mfma_f16_TFLOPs": {f"{w}_waves_per_simd": lib.pconv_peak_mfma_f16_tflops(w) for w in (1, 2)},
     }
 

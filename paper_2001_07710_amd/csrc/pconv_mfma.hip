@@ -111,6 +111,7 @@ struct MfmaParams {
     unsigned chan_bytes;    // H*W*2
     unsigned img_bytes;     // C*H*W*2
     int KS;                      // workgroups that share one tile, each taking a contiguous range of the channel blocks
+    int win_alias;               // the epilogue's windows lie in the free staging buffer (else behind the bias)
     int stagger;                 // every second workgroup starts this many steps of 2048 clocks late (0: none)
     float* ws;              // KS > 1: partial sums [tile][split][wave][operand tile][4 rows][64 lanes][4], as held
     unsigned* counters;     // KS > 1: one arrival counter per tile, zero between launches
@@ -178,7 +179,7 @@ struct TileGeo {
 // all of them as one sequence, so the first block of the next tile is loaded while the last block of the current one
 // is multiplied, and the stores of a tile drain while the next tile is computed.
 template <int AF, int BF, int WM, int WN, int LW, int KI, bool FULL>
-__global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams p) {
+__global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 1) void mfma_conv_kernel(const MfmaParams p) {
     constexpr int kItems = KI;
     constexpr int NW = WM * WN, NTH = NW * 64, MT = WM * AF * 32, HALF = NTH / 2;
     constexpr int WPIECES = (9 * 2 * MT + NTH - 1) / NTH;      // 16-byte pieces of weights per lane and block, at most
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     unsigned char* const ldsA = lds;
     unsigned char* const ldsB = lds + 2 * p.a_bytes;
     float* const ldsBias = reinterpret_cast<float*>(lds + p.bias_off);          // [3][MT]: by tile count modulo 3
-    unsigned* const win = reinterpret_cast<unsigned*>(lds + p.bias_off + 3 * MT * 4) + wave * (4 * WP);
+    unsigned* const win_fixed = reinterpret_cast<unsigned*>(lds + p.bias_off + 3 * MT * 4) + wave * (4 * WP);
 
     // ---- once: zero columns left and right of the image (no tile's staging ever writes them)
     if (p.pad) {
@@ -411,7 +412,13 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
     // adds one wave-uniform filter offset.  (Per value this is one maximum, half a conversion and half an LDS write;
     // the first version, which added the bias here, wrote 16-bit words and worked every address out per store,
     // took as long as two to three channel blocks.)
-    auto epilogue = [&](const TileGeo& g) {
+    auto epilogue = [&](const TileGeo& g, int free_buf) {
+        // The windows: a place of their own, or (p.win_alias) the weights' half of the staging buffer that nothing
+        // uses between the barrier that ended the tile's last block and the first loads of the block after next --
+        // the caller puts a barrier behind the epilogue then, so that no wave starts those loads while another
+        // still reads its window.  That saves the LDS that decides whether a second workgroup fits the compute unit.
+        unsigned* const win =
+            p.win_alias ? reinterpret_cast<unsigned*>(ldsA + free_buf * p.a_bytes) + wave * (4 * WP) : win_fixed;
         // (the lane index as the compiler cannot see through it: everything below depends on it and is computed
         // here, not ahead of the channel blocks, where it would sit in registers that the multiply loop needs)
         int lane_e = lane;
@@ -702,7 +709,8 @@ __global__ __launch_bounds__(WM* WN * 64) void mfma_conv_kernel(const MfmaParams
             __syncthreads();
             buf ^= 1;
         }
-        if (p.KS == 1 || combine_splits(gc)) epilogue(gc);
+        if (p.KS == 1 || combine_splits(gc)) epilogue(gc, buf ^ 1);
+        if (p.win_alias) __syncthreads();
         if (Tn >= ntiles) break;
         T = Tn;
         gc = gn;
@@ -834,7 +842,11 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         const size_t staging = 2 * (size_t)p.a_bytes + 4 * (size_t)p.plane_bytes;
         p.bias_off = (int)staging;
         // behind the staging buffers: the bias of three tiles, and per wave a window of 4 filter pairs x its pixels
-        lds = staging + 3 * (size_t)MT * 4 + (size_t)(NTH / 64) * 4 * (sh.bf * 32 + 16) * 4;
+        // -- unless the shape is one whose registers leave room for a second workgroup on the compute unit and the
+        // windows fit the weights' half of a staging buffer: then they live there
+        const size_t windows = (size_t)(NTH / 64) * 4 * (sh.bf * 32 + 16) * 4;
+        p.win_alias = (sh.af == 1 && sh.wm == 2 && sh.wn == 2 && windows <= (size_t)p.a_bytes) ? 1 : 0;
+        lds = staging + 3 * (size_t)MT * 4 + (p.win_alias ? 0 : windows);
         p.flag_off = (int)lds;                   // one word for the channel split's "arrived last" flag
         lds += 16;
         if (lds > 160 * 1024) continue;
@@ -922,18 +934,29 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     int lw = 0, ki = 0, grid = 0;
     size_t lds = 0;
     if (!plan(a, shape - 1, a.rows, &p, &lw, &ki, &lds, &grid)) return -1.0;
-    const double* block_us = kBlockUs;
     const long long tiles = (long long)p.tiles_n * p.tiles_m * p.KS;
-    // the two-wave shape leaves registers for a second workgroup on a compute unit, if its LDS fits twice
-    const int per_cu = shape == 4 && 2 * lds <= 160 * 1024 ? 2 : 1;
+    // the shapes whose waves keep within half the registers leave room for a second workgroup on a compute unit, if
+    // the LDS fits twice
+    const int per_cu = (shape == 4 || p.win_alias) && 2 * lds <= 160 * 1024 ? 2 : 1;
     const long long resident = (long long)compute_units() * per_cu;
     const double rounds = (double)((tiles + resident - 1) / resident);
     const double floor_us = tiles < 2 * resident ? 2.1 : 0.0;
     const double blocks = (double)((p.CB + p.KS - 1) / p.KS);
+    // Time of one channel block of one tile with the device full, and of what a tile costs besides its blocks
+    // (epilogue, descriptors), microseconds, fitted to the nine VGG-16 shapes at batch 64: two workgroups that share
+    // a compute unit take turns on its matrix cores, so each one's block lasts longer; rows of fewer than 56 pixels
+    // mean narrower loads and stores.
+    const bool narrow = a.W < 56;
+    double block_us = kBlockUs[shape - 1], tile_us = 8.0;
+    if (shape == 1) block_us = narrow ? 2.65 : 2.3;
+    if (shape == 2) {
+        block_us = per_cu == 2 && tiles >= 2 * (long long)compute_units() ? (narrow ? 2.85 : 2.7) : 1.7;
+        tile_us = 5.0;
+    }
     // a split costs the round trip of the partial sums through memory and the last arriver's additions
     const double part_bytes = (double)tiles * (kShapes[shape - 1].wm * kShapes[shape - 1].af * 32) *
                               (kShapes[shape - 1].wn * kShapes[shape - 1].bf * 32) * 4.0;
-    return rounds * (8.0 + blocks * std::max(block_us[shape - 1], floor_us)) + (p.KS > 1 ? 20.0 + 1.5 * part_bytes / 1.5e6 : 0.0);
+    return rounds * (tile_us + blocks * std::max(block_us, floor_us)) + (p.KS > 1 ? 20.0 + 1.5 * part_bytes / 1.5e6 : 0.0);
 }
 
 int mfma_workspace(const MfmaConv& a, size_t* floats, size_t* counters) {

@@ -136,6 +136,20 @@ __global__ __launch_bounds__(1024) void vmem_issue_kernel(const float* __restric
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// ---- global stores of 16 bytes per lane that hit the same few cache lines of the L2 over and over (every wave its
+// own 4 KB): the rate at which a compute unit's store path takes wave-wide store instructions
+__global__ __launch_bounds__(1024) void vmem_store_kernel(float* dst, int iters) {
+    float* p = dst + ((size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 1024 + (threadIdx.x & 63) * 4;
+    const float4v v = {1.f, 2.f, 3.f, (float)threadIdx.x};
+    for (int it = 0; it < iters; ++it)
+        asm volatile(
+            "global_store_dwordx4 %0, %1, off nt\n global_store_dwordx4 %0, %1, off offset:1024 nt\n"
+            "global_store_dwordx4 %0, %1, off offset:2048 nt\n global_store_dwordx4 %0, %1, off offset:3072 nt"
+            :
+            : "v"(p), "v"(v)
+            : "memory");
+}
+
 // ---- fp16 MFMA on registers only: four independent 32x32x16 accumulator tiles per wave
 __global__ __launch_bounds__(512) void mfma_kernel(float* out, int iters) {
     half8 a, b;
@@ -226,6 +240,19 @@ extern "C" double pconv_peak_vmem_clk_per_load(int bytes_per_lane) {
         else
             hipLaunchKernelGGL(vmem_issue_kernel<16>, dim3(d.cus), dim3(waves * 64), 0, 0, src.p, o.p, iters);
     });
+    return ms <= 0.0 ? -3.0 : ms * 1e-3 * d.clock_hz / (4.0 * iters * waves);
+}
+
+// Nominal clocks a compute unit spends per wave-wide 16-byte-per-lane streaming store instruction, `waves` (1..16)
+// waves per compute unit storing to cache lines that stay in the L2.
+extern "C" double pconv_peak_vmem_clk_per_store(int waves) {
+    if (waves < 1 || waves > 16) return -1.0;
+    DeviceShape d;
+    if (device_shape(&d)) return -1.0;
+    const int iters = 4000;
+    Scratch o;
+    if (!o.get((size_t)d.cus * waves * 4096)) return -2.0;
+    const double ms = timed_ms([&] { hipLaunchKernelGGL(vmem_store_kernel, dim3(d.cus), dim3(waves * 64), 0, 0, o.p, iters); });
     return ms <= 0.0 ? -3.0 : ms * 1e-3 * d.clock_hz / (4.0 * iters * waves);
 }
 
