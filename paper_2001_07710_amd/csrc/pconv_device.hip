@@ -2233,11 +2233,13 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         if (want_splits < 0) return PCONV_EINVAL;
         for (int sh = 1; sh <= kMfmaShapes; ++sh) {
             if (want_shape && sh != want_shape) continue;
-            // (a split is only taken when asked for: the partial sums are MT x NT floats per part, twice the tile's
-            // output, and on the measured shapes their round trip through memory cost more than the parallelism
-            // gained -- ResNet-50's 64 -> 64 layer at 56x56, batch 32: 17 us unsplit, 53 us in two parts)
+            // (A split pays where a layer has fewer tiles than compute units and many channel blocks in sequence --
+            // ResNet-50's 512 -> 512 layers at batch 32: 83 -> 55 us in two parts at 14x14 stride 2, 69 -> 40 us in
+            // four at 7x7 -- and costs the round trip of MT x NT floats per part otherwise: the 64 -> 64 layer at
+            // 56x56 goes from 17 to 53 us in two parts.  The estimate carries both.  Not asked for, the choice is
+            // between 1, 2 and, at stride 1, 4 parts: more lost on every shape measured.)
             for (int ks = 1; ks <= 16; ks *= 2) {
-                if (ks != (want_splits ? want_splits : 1)) continue;
+                if (want_splits ? ks != want_splits : ks > (stride == 2 ? 2 : 4)) continue;
                 const double t = mfma_estimate_us(a, sh, ks);
                 if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; a.splits = ks; }
             }
@@ -2267,6 +2269,14 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
                     size_t floats = 0, counters = 0;
                     rc = mfma_workspace(a, &floats, &counters);
                     if (rc == PCONV_OK) rc = get_workspace(wp, arena, floats, counters, &a.ws, &a.counters, st);
+                    // (a split that the library chose itself and whose partial sums do not fit the fixed array of
+                    // the entry point that allocates nothing: the same tile shape, unsplit)
+                    if (rc == PCONV_ESCRATCH && !want_splits) {
+                        a.splits = 1;
+                        a.ws = nullptr;
+                        a.counters = nullptr;
+                        rc = PCONV_OK;
+                    }
                     if (rc != PCONV_OK) break;
                 }
                 rc = launch_mfma_conv(a, stream);

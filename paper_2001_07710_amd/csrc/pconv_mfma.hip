@@ -582,30 +582,34 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         const bool last = __builtin_amdgcn_readfirstlane(*flag) != 0u;
         __syncthreads();                         // (the flag is read before the next tile's arrival rewrites it)
         if (!last) return false;
+        // All parts come from the workspace, this workgroup's own too, in the order of the splits.  Per group of 32
+        // filters, the loads of half a part are issued before the first is used: two round trips to memory per part
+        // and group, not one per 16 bytes (which is what a loop over the parts around each single load came to, and
+        // made the last arriver of 8 parts take 200 us).
 #pragma unroll
         for (int af = 0; af < AF; ++af)
 #pragma unroll
-            for (int bf = 0; bf < BF; ++bf)
+            for (int b0 = 0; b0 < BF; b0 += 4)                   // (half a group at a time: 64 registers in flight)
+                for (int part = 0; part < p.KS; ++part) {
+                    uint4v v[4][4];
 #pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    float sum[4] = {0.f, 0.f, 0.f, 0.f};
-                    for (int part = 0; part < p.KS; ++part) {
-                        float q[4];
-                        if (part == g.split) {
+                    for (int bf = b0; bf < BF && bf < b0 + 4; ++bf)
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) q[i] = acc[af][bf][rq * 4 + i];
-                        } else {
-                            const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(wsr, off(part, af, bf, rq), 0, kDeviceScope);
-                            q[0] = __builtin_bit_cast(float, (unsigned)v.x);
-                            q[1] = __builtin_bit_cast(float, (unsigned)v.y);
-                            q[2] = __builtin_bit_cast(float, (unsigned)v.z);
-                            q[3] = __builtin_bit_cast(float, (unsigned)v.w);
+                        for (int rq = 0; rq < 4; ++rq)
+                            v[bf - b0][rq] =
+                                __builtin_amdgcn_raw_buffer_load_b128(wsr, off(part, af, bf, rq), 0, kDeviceScope);
+#pragma unroll
+                    for (int bf = b0; bf < BF && bf < b0 + 4; ++bf)
+#pragma unroll
+                        for (int rq = 0; rq < 4; ++rq) {
+                            const uint4v u = v[bf - b0][rq];
+                            const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float q = __builtin_bit_cast(float, w[i]);
+                                acc[af][bf][rq * 4 + i] = part == 0 ? q : acc[af][bf][rq * 4 + i] + q;
+                            }
                         }
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) sum[i] = part == 0 ? q[i] : sum[i] + q[i];
-                    }
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) acc[af][bf][rq * 4 + i] = sum[i];
                 }
         return true;
     };
@@ -940,7 +944,10 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     const int per_cu = (shape == 4 || p.win_alias) && 2 * lds <= 160 * 1024 ? 2 : 1;
     const long long resident = (long long)compute_units() * per_cu;
     const double rounds = (double)((tiles + resident - 1) / resident);
-    const double floor_us = tiles < 2 * resident ? 2.1 : 0.0;
+    // (while the device is not full a block lasts as long as the loads of the next one take to come back: measured
+    // on ResNet-50's layers at batch 32, per shape, stride 1 / stride 2 -- a wider tile stages more rows per block)
+    static const double kFloorUs[kMfmaShapes][2] = {{2.8, 2.8}, {2.0, 2.7}, {1.9, 2.2}, {1.75, 1.85}};
+    const double floor_us = tiles <= resident ? kFloorUs[shape - 1][a.stride == 2 ? 1 : 0] : 0.0;
     const double blocks = (double)((p.CB + p.KS - 1) / p.KS);
     // Time of one channel block of one tile with the device full, and of what a tile costs besides its blocks
     // (epilogue, descriptors), microseconds, fitted to the nine VGG-16 shapes at batch 64: two workgroups that share
@@ -950,13 +957,20 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     double block_us = kBlockUs[shape - 1], tile_us = 8.0;
     if (shape == 1) block_us = narrow ? 2.65 : 2.3;
     if (shape == 2) {
-        block_us = per_cu == 2 && tiles >= 2 * (long long)compute_units() ? (narrow ? 2.85 : 2.7) : 1.7;
+        block_us = per_cu == 2 && tiles > (long long)compute_units() ? (narrow ? 2.85 : 2.7) : 1.7;
         tile_us = 5.0;
+    }
+    if (shape == 3) tile_us = 5.0;
+    if (shape == 4) {
+        if (per_cu == 2 && tiles > (long long)compute_units()) block_us = 2.4;
+        tile_us = 4.0;
     }
     // a split costs the round trip of the partial sums through memory and the last arriver's additions
     const double part_bytes = (double)tiles * (kShapes[shape - 1].wm * kShapes[shape - 1].af * 32) *
                               (kShapes[shape - 1].wn * kShapes[shape - 1].bf * 32) * 4.0;
-    return rounds * (tile_us + blocks * std::max(block_us, floor_us)) + (p.KS > 1 ? 20.0 + 1.5 * part_bytes / 1.5e6 : 0.0);
+    // (fitted to ResNet-50's 14 x 14 and 7 x 7 layers at batch 32 in 2, 4 and 8 parts)
+    const double split_us = p.KS > 1 ? 4.0 + 1.5 * (p.KS - 1) + part_bytes / 1.8e6 : 0.0;
+    return rounds * (tile_us + blocks * std::max(block_us, floor_us)) + split_us;
 }
 
 int mfma_workspace(const MfmaConv& a, size_t* floats, size_t* counters) {
