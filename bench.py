@@ -385,7 +385,7 @@ def sweep_bench(args, torch, pc, L, stream):
                      "eff_frac_of_fp32_vector_peak": 2 * eff[i] / t / 1e12 / PEAK_FP32_VECTOR_TFLOPS,
                      "dense_us": None if dense_per is None else dense_per[i] * 1e3})
     tot_t = sum(per) * 1e-3
-    # the dominant kernel: mfma_conv_kernel, which runs all layers but the first; per launch = the mean over them
+    # the dominant kernel: mfma_conv_kernel, on the layers the library runs with it; per launch = the mean over them
     dom = on_mfma if on_mfma else list(range(len(specs)))
     exe_flops = 2.0 * sum(exe[i] for i in dom) / len(dom)
     alg_flops = 2.0 * sum(eff[i] for i in dom) / len(dom)
@@ -420,6 +420,11 @@ def sweep_bench(args, torch, pc, L, stream):
                      "algorithmic_bytes_per_launch": sum(ab[i] for i in dom) / len(dom),
                      "algorithmic_GBs": sum(ab[i] for i in dom) / (kernel_ms * 1e-3 * len(dom)) / 1e9,
                      "hbm_frac_of_8TBs": sum(ab[i] for i in dom) / (kernel_ms * 1e-3 * len(dom)) / 1e9 / PEAK_HBM_GBS,
+                     # per launch the time that the roof which binds it allows (executed flops at the MFMA peak or
+                     # algorithmic bytes at the HBM peak, whichever is longer), summed, over the measured time
+                     "frac_of_binding_roof_time_weighted":
+                         sum(max(2.0 * exe[i] / (PEAK_FP16_MFMA_TFLOPS * 1e12), ab[i] / (PEAK_HBM_GBS * 1e9)) for i in dom)
+                         / (sum(per[i] for i in dom) * 1e-3),
                      "note": "the kernel runs the layer as a dense fp16 contraction over its masked weights on the "
                              "matrix cores; 'achieved' counts the multiply-adds it executes (every tap that occurs, "
                              "explicit zeros included) against the published dense fp16 MFMA peak; the method's own "

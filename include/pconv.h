@@ -228,11 +228,13 @@ size_t pconv_noalloc_scratch_bytes(void);
  *                     tile: 0 = chosen by the library, 1 = 128 filters x 448 output pixels, 2 = 64 x 448,
  *                     3 = 128 x 224, 4 = 64 x 224.  `rows` (0 = as many as fit) caps the output rows per tile;
  *                     slot_walk = 1 gives every tile a workgroup of its own instead of persistent workgroups that
- *                     walk over the tiles; channel_splits (0 = 1, or 2, 4, 8, 16, at most the number of 16-channel
- *                     blocks) lets that many workgroups share a tile, each with a part of the channel blocks: their
- *                     partial sums meet in the handle's workspace and are added in a fixed order (reproducible);
- *                     never chosen automatically, the round trip of the partial sums costs more than it gains on
- *                     every shape measured.
+ *                     walk over the tiles; channel_splits (0 = chosen by the library: 1, 2 or, at stride 1, 4;
+ *                     or 1, 2, 4, 8, 16, at most the number of 16-channel blocks) lets that many workgroups share a
+ *                     tile, each with a part of the channel blocks: their partial sums meet in the handle's workspace
+ *                     and are added in a fixed order (reproducible).  The library splits where a layer has fewer
+ *                     tiles than compute units and many channel blocks; like the vector kernels' split this uses
+ *                     the workspace (allocated on first use; pconv_conv3x3_noalloc takes it from its fixed array
+ *                     and runs the layer unsplit if a split of the library's own choosing does not fit there).
  *                     Non-finite activations reach every output whose 3x3 window holds them, also through weights
  *                     that are pruned (0 * inf), which the vector kernels skip.
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.

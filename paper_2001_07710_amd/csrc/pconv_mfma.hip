@@ -957,8 +957,9 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     double block_us = kBlockUs[shape - 1], tile_us = 8.0;
     if (shape == 1) block_us = narrow ? 2.65 : 2.3;
     if (shape == 2) {
-        block_us = per_cu == 2 && tiles > (long long)compute_units() ? (narrow ? 2.85 : 2.7) : 1.7;
-        tile_us = 5.0;
+        const bool shared = per_cu == 2 && tiles > (long long)compute_units();
+        block_us = shared ? (narrow ? 2.85 : 2.7) : 1.7;
+        tile_us = shared ? 5.0 : 2.8;
     }
     if (shape == 3) tile_us = 5.0;
     if (shape == 4) {
