@@ -171,7 +171,9 @@ int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* b
 
 /*
  * pconv_conv3x3 for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
- * forbid hipMalloc.  Same arguments, same kernels, same results bit for bit; the call makes no hipMalloc, hipFree or
+ * forbid hipMalloc.  Same arguments, same kernels, same results bit for bit (with one exception: an fp16 layer whose
+ * tiles the library itself chose to split, and whose partial sums do not fit the fixed array, runs unsplit here --
+ * the same sums added in another order, within the tolerance of the type); the call makes no hipMalloc, hipFree or
  * other allocating call.  Where pconv_conv3x3 would split the input channels of a tile over several workgroups, the
  * partial sums and arrival counters live in a fixed device array of pconv_noalloc_scratch_bytes() bytes (24 MiB
  * of partial sums and 16384 tile counters) that every GPU the library runs on holds until the process ends, instead
