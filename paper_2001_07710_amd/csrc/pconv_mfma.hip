@@ -745,7 +745,10 @@ struct Shape {
 // measured time of one channel block of one tile with the device full, microseconds, per tile shape
 const double kBlockUs[kMfmaShapes] = {3.2, 1.7, 1.7, 1.8};
 // tile shapes: (128 filters x 448 pixels), (64 x 448), (128 x 224), (64 x 224).  (64 x 896, four waves side by
-// side, was tried for layers of 64 filters at 224 x 224 and measured no faster than 64 x 448 there.)
+// side, was tried for layers of 64 filters at 224 x 224 and measured no faster than 64 x 448 there; 128 x 512 on
+// eight waves of 64 x 128 each -- two waves per SIMD with the first shape's operand economy -- fits 256 registers
+// only with spills, wastes the pixels that 512 has over a multiple of the row, and measured 4 to 45 % slower than the
+// first shape on the 112-, 56- and 28-column layers of VGG-16 at batch 64.)
 const Shape kShapes[kMfmaShapes] = {{2, 7, 2, 2}, {1, 7, 2, 2}, {1, 7, 4, 1}, {1, 7, 2, 1}};
 
 // Workgroups of the persistent grid: as many as the device holds at once (compute units x workgroups that fit one),
