@@ -4,6 +4,7 @@ package never does.
 
 conv_oracle.c   direct convolution over masked dense weights, double accumulation (built by `build()` with gcc)
 pattern_oracle  masking, pattern assignment, connectivity selection, canonical packing (numpy, float64)
+admm_oracle     the selection-variable steps of the pruning framework: simplex projection, multiplier update, argmax
 """
 from __future__ import annotations
 
@@ -13,6 +14,7 @@ import subprocess
 
 import numpy as np
 
+from .admm_oracle import binarize, proximal_step, simplex_project  # noqa: F401
 from .pattern_oracle import (  # noqa: F401
     assign_patterns, library_bits, mask_weights, pack_canonical, retained_energy, select_connectivity,
     unpack_canonical,
