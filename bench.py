@@ -169,6 +169,8 @@ def main():
     ap.add_argument("--config1", action="store_true", help="time the batch-1 fp32 layer of config 1 alone")
     ap.add_argument("--peaks", action="store_true", help="measured peaks of this chip (copy, fp32 FMA, LDS, MFMA)")
     ap.add_argument("--no-extras", action="store_true", help="default run without the other configurations")
+    ap.add_argument("--admm", action="store_true",
+                    help="the selection-variable steps of the pruning framework over all kernels of VGG-16")
     ap.add_argument("--layers", default="")
     ap.add_argument("--K", type=int, default=8)
     ap.add_argument("--keep", type=float, default=0.28)
@@ -196,6 +198,8 @@ def main():
 
     if args.peaks:
         return peaks_bench(args, torch)
+    if args.admm:
+        return admm_bench(args, torch, pc, L)
     if args.chain:
         return chain_bench(args, torch, pc, L)
     if args.layers:
@@ -468,6 +472,69 @@ def peaks_bench(args, torch):
            "published": {"hbm_GBs": PEAK_HBM_GBS, "fp32_vector_TFLOPs": PEAK_FP32_VECTOR_TFLOPS,
                          "fp16_mfma_TFLOPs": PEAK_FP16_MFMA_TFLOPS},
            "note": "copy_GBs counts bytes read plus bytes written; per-clock figures use the nominal engine clock"}
+    print(json.dumps(out), flush=True)
+
+
+def admm_bench(args, torch, pc, L):
+    """The per-kernel steps of the pruning framework (include/pconv_admm.h) over every 3x3 kernel of VGG-16's 13
+    conv layers (1,634,496 kernels), K patterns: one proximal step with multiplier update, the argmax projection, and
+    the pattern assignment from fp32 weights.  Each is one launch, bound by HBM: algorithmic bytes = what it must read
+    and write once (proximal: four float vectors of K per kernel; argmax: K floats in, one int out; assignment: nine
+    floats in, one int out)."""
+    import oracle
+    from workloads import rng
+    n, K = sum(sp.C * sp.F for sp in L.config2()), args.K
+    z = (rng.normal(rng.stream_seed(93, 1, K), n * K).reshape(n, K) * 0.5 + 1.0 / K).astype(np.float32)
+    mu = (rng.normal(rng.stream_seed(93, 2, K), n * K).reshape(n, K) * 0.1).astype(np.float32)
+    w = rng.normal(rng.stream_seed(93, 3), n * 9).reshape(n, 9).astype(np.float32)
+    lib = np.array(L.drawn_library(4, K), dtype=np.uint16)
+    # four copies of every buffer, used in turn: 0.6 GB per proximal launch set, so that a launch finds none of its
+    # data in the 256 MB memory-side cache and the rate is that of HBM
+    R = 4
+    dz = [torch.from_numpy(z).cuda() for _ in range(R)]
+    dmu = [torch.from_numpy(mu).cuda() for _ in range(R)]
+    dw = [torch.from_numpy(w).cuda() for _ in range(R)]
+    du, dm2 = [torch.empty_like(dz[0]) for _ in range(R)], [torch.empty_like(dz[0]) for _ in range(R)]
+    pid = [torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(R)]
+    st = torch.cuda.current_stream().cuda_stream
+    turn = [0]
+
+    def rot():
+        turn[0] = (turn[0] + 1) % R
+        return turn[0]
+
+    def prox():
+        r = rot()
+        pc.admm_proximal(dz[r], dmu[r], 0.75, n, K, du[r], dm2[r], st)
+
+    def binz():
+        r = rot()
+        pc.admm_binarize(dz[r], n, K, pid[r], st)
+
+    def asg():
+        r = rot()
+        pc.assign_patterns_device(dw[r], pc.F32, n, lib, pid[r], st)
+
+    rows = {}
+    for name, fn, nbytes in (("proximal", prox, 16 * K * n), ("binarize", binz, (4 * K + 4) * n),
+                             ("assign_patterns_device", asg, 40 * n)):
+        _, ev = time_launches(torch, fn, args.steps, args.warmup)
+        rows[name] = {"us": ev * 1e3, "algorithmic_bytes": nbytes, "GBs": nbytes / (ev * 1e-3) / 1e9,
+                      "frac_of_8TBs": nbytes / (ev * 1e-3) / 1e9 / PEAK_HBM_GBS, "kernels_per_s": n / (ev * 1e-3)}
+    # the oracle on a bounded sample of the same vectors, timed on the host
+    m = 20000
+    t0 = time.perf_counter()
+    oracle.proximal_step(z[:m], mu[:m], 0.75)
+    el = time.perf_counter() - t0
+    out = {"metric": "kernels/s, proximal step with multiplier update", "value": rows["proximal"]["kernels_per_s"],
+           "unit": "kernels/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": rows["proximal"]["us"] * 1e-3, "higher_is_better": True, "dtype": "f32 storage, f64 arithmetic",
+           "data": "synthetic", "config": {"workload": f"all {n} 3x3 kernels of VGG-16's 13 conv layers, K={K}"},
+           "roofline": {"bound": "hbm", "achieved": rows["proximal"]["GBs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": rows["proximal"]["frac_of_8TBs"], "traffic": None, "kernel": "proximal_kernel"},
+           "steps_table": rows,
+           "cpu_baseline": {"value": m / el, "unit": "kernels/s", "cores": 1, "kind": "oracle",
+                            "sample": f"the first {m} kernels, {el:.1f} s"}}
     print(json.dumps(out), flush=True)
 
 

@@ -79,6 +79,12 @@ def _load():
     lib.pconv_conv3x3_tuned.argtypes = [vp, vp, vp, vp, i, i, i, i, i, u, vp, ctypes.POINTER(_Tuning)]
     lib.pconv_dense_conv3x3.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, i, u, vp]
     lib.pconv_maxpool2x2.argtypes = [vp, vp, i, i, i, i, i, vp]
+    ll = ctypes.c_longlong
+    lib.pconv_admm_proximal.argtypes = [vp, vp, ctypes.c_float, ll, i, vp, vp, vp]
+    lib.pconv_admm_binarize.argtypes = [vp, ll, i, vp, vp]
+    lib.pconv_assign_patterns_device.argtypes = [vp, i, ll, vp, i, vp, vp]
+    for name in ("pconv_admm_proximal", "pconv_admm_binarize", "pconv_assign_patterns_device"):
+        getattr(lib, name).restype = i
     for name in ("pconv_assign_patterns", "pconv_select_connectivity", "pconv_pack", "pconv_packed_export",
                  "pconv_packed_stats", "pconv_packed_parity_form", "pconv_packed_library", "pconv_conv3x3", "pconv_conv3x3_noalloc", "pconv_conv3x3_tuned", "pconv_dense_conv3x3",
                  "pconv_maxpool2x2"):
@@ -288,3 +294,20 @@ def dense_conv3x3(x, y, w_oihw_dev, bias, dtype: int, N: int, C: int, F: int, H:
 
 def maxpool2x2(x, y, dtype: int, N: int, C: int, H: int, W: int, stream: int = 0):
     _check(_load().pconv_maxpool2x2(_dp(x), _dp(y), dtype, N, C, H, W, stream or None), "pconv_maxpool2x2")
+
+
+# ---- the selection-variable steps of the pruning framework (include/pconv_admm.h); device tensors in, device tensors out
+
+def admm_proximal(z, mu, rho: float, n: int, K: int, u=None, mu_out=None, stream: int = 0):
+    _check(_load().pconv_admm_proximal(_dp(z), _dp(mu), float(rho), n, K, _dp(u), _dp(mu_out), stream),
+           "pconv_admm_proximal")
+
+
+def admm_binarize(z, n: int, K: int, pid, stream: int = 0):
+    _check(_load().pconv_admm_binarize(_dp(z), n, K, _dp(pid), stream), "pconv_admm_binarize")
+
+
+def assign_patterns_device(w, dtype: int, n: int, lib, pid, stream: int = 0):
+    lib_h = _host(lib, np.uint16)
+    _check(_load().pconv_assign_patterns_device(_dp(w), dtype, n, _hp(lib_h), int(lib_h.size), _dp(pid), stream),
+           "pconv_assign_patterns_device")

@@ -41,6 +41,36 @@ def test_peaks_library_exports_every_declared_symbol():
         assert hasattr(lib, n), f"{n} is declared in pconv_peaks.h but not exported"
 
 
+def test_admm_entry_points_are_exported_and_refuse_bad_arguments_without_a_gpu():
+    hdr = open(os.path.join(ROOT, "include", "pconv_admm.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(pconv_[a-z0-9_]+)\s*\(", hdr))
+    assert names == {"pconv_admm_proximal", "pconv_admm_binarize", "pconv_assign_patterns_device"}
+    lib = ctypes.CDLL(pc.LIB_PATH)
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} is declared in pconv_admm.h but not exported"
+    # argument checks come before any device call (no compute here: every call below returns before a launch)
+    vp, ll, i = ctypes.c_void_p, ctypes.c_longlong, ctypes.c_int
+    lib.pconv_admm_proximal.argtypes = [vp, vp, ctypes.c_float, ll, i, vp, vp, vp]
+    lib.pconv_admm_binarize.argtypes = [vp, ll, i, vp, vp]
+    lib.pconv_assign_patterns_device.argtypes = [vp, i, ll, vp, i, vp, vp]
+    fake = 4096                                             # never dereferenced by the calls below
+    assert lib.pconv_admm_proximal(None, None, 1.0, 4, 8, fake, None, None) == pc.EINVAL
+    assert lib.pconv_admm_proximal(fake, None, 0.0, 4, 8, fake, None, None) == pc.EINVAL
+    assert lib.pconv_admm_proximal(fake, None, float("nan"), 4, 8, fake, None, None) == pc.EINVAL
+    assert lib.pconv_admm_proximal(fake, None, 1.0, 4, 33, fake, None, None) == pc.EINVAL
+    assert lib.pconv_admm_proximal(fake, None, 1.0, -1, 8, fake, None, None) == pc.EINVAL
+    assert lib.pconv_admm_proximal(fake, None, 1.0, 0, 8, fake, None, None) == pc.OK       # nothing to do
+    assert lib.pconv_admm_binarize(fake, 4, 0, fake, None) == pc.EINVAL
+    assert lib.pconv_admm_binarize(fake, 0, 8, fake, None) == pc.OK
+    good = np.array([0x01B, 0x036], dtype=np.uint16)
+    bad = np.array([0x01B, 0x007], dtype=np.uint16)
+    assert lib.pconv_assign_patterns_device(fake, pc.F32, 4, bad.ctypes.data, 2, fake, None) == pc.EPATTERN
+    assert lib.pconv_assign_patterns_device(fake, pc.F32, 4, good.ctypes.data, 0, fake, None) == pc.EPATTERN
+    assert lib.pconv_assign_patterns_device(fake, 7, 4, good.ctypes.data, 2, fake, None) == pc.EINVAL
+    assert lib.pconv_assign_patterns_device(fake, pc.F32, 0, good.ctypes.data, 2, fake, None) == pc.OK
+
+
 def _layer(spec):
     w = L.gen_weights(spec)
     lib = spec.library()
