@@ -10,13 +10,15 @@
  * an auxiliary copy u on the probability simplex, a multiplier mu, and the penalty rho > 0.  Vectors are stored one
  * kernel after the other: v[i*K + j], i < n, j < K; float storage; the arithmetic inside is double.
  *
- * All pointers except `lib` are DEVICE pointers, caller-owned; `stream` is a hipStream_t passed as void* (NULL = the
- * default stream); calls are asynchronous on it and allocate nothing.  n = 0 is a no-op.  Non-finite inputs give
+ * All pointers except `lib` (and the size word of the selection's workspace) are DEVICE pointers, caller-owned;
+ * `stream` is a hipStream_t passed as void* (NULL = the default stream); calls are asynchronous on it and allocate
+ * nothing.  n = 0 is a no-op.  Non-finite inputs give
  * unspecified values (no fault).
  */
 #ifndef PCONV_ADMM_H
 #define PCONV_ADMM_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -60,6 +62,27 @@ int pconv_admm_binarize(const float* z, long long n, int K, int32_t* pid, void* 
  */
 int pconv_assign_patterns_device(const void* w, int dtype, long long n, const uint16_t* lib, int K, int32_t* pid,
                                  void* stream);
+
+/*
+ * Connectivity selection on the device (sections 3 and 6.1: the kernels with the smallest L2 norm are cut): of the
+ * n = F*C kernels of a layer, the k = floor(keep*n + 0.5) with the largest squared norm of the pattern-pruned kernel
+ * W o M_pid are kept; equal norms go to the lower index f*C + c.  Same rule and arithmetic as the host entry
+ * pconv_select_connectivity (norms in double, taps ascending): the two agree bit for bit on finite weights.
+ * The selection is a stable radix sort of (norm, index) pairs (the hipCUB device primitive) between two small
+ * kernels of this library.
+ *   w          in,  device, n kernels of 9 weights, storage type `dtype`
+ *   lib        in,  HOST, uint16[K]
+ *   pid        in,  device, int32[n], every entry in [0, K) (not checked on the device: an entry outside reads
+ *              an arbitrary mask of the library's storage, never outside it)
+ *   keep       in [0, 1]
+ *   mask       out, device, uint8[n]: 1 = kept
+ *   workspace  device scratch of *workspace_bytes bytes, 256-byte aligned.  Called with workspace == NULL the
+ *              function only writes the size it needs for this n to *workspace_bytes and returns PCONV_OK; it never
+ *              allocates.  A workspace that is too small gives PCONV_ESCRATCH.
+ */
+int pconv_select_connectivity_device(const void* w, int dtype, long long n, const uint16_t* lib, int K,
+                                     const int32_t* pid, double keep, uint8_t* mask, void* workspace,
+                                     size_t* workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -83,7 +83,10 @@ def _load():
     lib.pconv_admm_proximal.argtypes = [vp, vp, ctypes.c_float, ll, i, vp, vp, vp]
     lib.pconv_admm_binarize.argtypes = [vp, ll, i, vp, vp]
     lib.pconv_assign_patterns_device.argtypes = [vp, i, ll, vp, i, vp, vp]
-    for name in ("pconv_admm_proximal", "pconv_admm_binarize", "pconv_assign_patterns_device"):
+    lib.pconv_select_connectivity_device.argtypes = [vp, i, ll, vp, i, vp, ctypes.c_double, vp, vp,
+                                                     ctypes.POINTER(ctypes.c_size_t), vp]
+    for name in ("pconv_admm_proximal", "pconv_admm_binarize", "pconv_assign_patterns_device",
+                 "pconv_select_connectivity_device"):
         getattr(lib, name).restype = i
     for name in ("pconv_assign_patterns", "pconv_select_connectivity", "pconv_pack", "pconv_packed_export",
                  "pconv_packed_stats", "pconv_packed_parity_form", "pconv_packed_library", "pconv_conv3x3", "pconv_conv3x3_noalloc", "pconv_conv3x3_tuned", "pconv_dense_conv3x3",
@@ -311,3 +314,20 @@ def assign_patterns_device(w, dtype: int, n: int, lib, pid, stream: int = 0):
     lib_h = _host(lib, np.uint16)
     _check(_load().pconv_assign_patterns_device(_dp(w), dtype, n, _hp(lib_h), int(lib_h.size), _dp(pid), stream),
            "pconv_assign_patterns_device")
+
+
+def select_connectivity_device_workspace(n: int) -> int:
+    """Bytes of device scratch pconv_select_connectivity_device needs for n kernels."""
+    need = ctypes.c_size_t(0)
+    _check(_load().pconv_select_connectivity_device(None, F32, n, None, 0, None, 0.0, None, None, ctypes.byref(need), None),
+           "pconv_select_connectivity_device (size query)")
+    return int(need.value)
+
+
+def select_connectivity_device(w, dtype: int, n: int, lib, pid, keep: float, mask, workspace, workspace_bytes: int,
+                               stream: int = 0):
+    lib_h = _host(lib, np.uint16)
+    have = ctypes.c_size_t(workspace_bytes)
+    _check(_load().pconv_select_connectivity_device(_dp(w), dtype, n, _hp(lib_h), int(lib_h.size), _dp(pid), float(keep),
+                                                    _dp(mask), _dp(workspace), ctypes.byref(have), stream),
+           "pconv_select_connectivity_device")

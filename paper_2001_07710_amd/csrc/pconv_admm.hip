@@ -3,6 +3,7 @@
 // include/pconv_admm.h.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
+#include <hipcub/device/device_radix_sort.hpp>
 
 #include <cmath>
 #include <cstdint>
@@ -209,10 +210,91 @@ __global__ __launch_bounds__(kThreads) void assign_kernel(const T* __restrict__ 
     pid[first + threadIdx.x] = arg;
 }
 
+// squared norm of the pattern-pruned kernel as a sort key: a non-negative double's bit pattern orders like its value
+template <typename T>
+__global__ __launch_bounds__(kThreads) void norm_key_kernel(const T* __restrict__ w, long long n, Library lib, int K,
+                                                            const int32_t* __restrict__ pid, uint64_t* __restrict__ key,
+                                                            uint32_t* __restrict__ idx) {
+    __shared__ uint32_t masks[126];
+    if ((int)threadIdx.x < K) masks[threadIdx.x] = lib.mask[threadIdx.x];
+    __syncthreads();
+    const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    const int32_t j = pid[i];
+    const unsigned m = masks[(j >= 0 && j < K) ? j : 0];
+    double e = 0.0;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const double v = (double)(float)w[i * 9 + t];
+        if (m >> t & 1u) e = e + v * v;                       // (taps ascending, product and sum rounded separately)
+    }
+    key[i] = __builtin_bit_cast(uint64_t, e);
+    idx[i] = (uint32_t)i;
+}
+
+__global__ __launch_bounds__(kThreads) void mark_kept_kernel(const uint32_t* __restrict__ order, long long n, long long k,
+                                                             uint8_t* __restrict__ mask) {
+    const long long r = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (r < n) mask[order[r]] = r < k ? 1 : 0;
+}
+
+size_t round256(size_t b) {
+    return (b + 255) / 256 * 256;
+}
+
 }  // namespace
 }  // namespace pconv
 
 using namespace pconv;
+
+extern "C" int pconv_select_connectivity_device(const void* w, int dtype, long long n, const uint16_t* lib, int K,
+                                                const int32_t* pid, double keep, uint8_t* mask, void* workspace,
+                                                size_t* workspace_bytes, void* stream) {
+    if (!workspace_bytes || n < 0 || (dtype != PCONV_F32 && dtype != PCONV_F16)) return PCONV_EINVAL;
+    if (n > 0x7FFFFFFFll) return PCONV_ESHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // workspace: keys in, keys out (8 bytes each), indices in, indices out (4 bytes each), the sort's own scratch
+    size_t sort_bytes = 0;
+    PCONV_HIP(hipcub::DeviceRadixSort::SortPairsDescending(nullptr, sort_bytes, (const uint64_t*)nullptr, (uint64_t*)nullptr,
+                                                          (const uint32_t*)nullptr, (uint32_t*)nullptr, (int)n, 0, 64, st));
+    const size_t kb = round256((size_t)n * 8), ib = round256((size_t)n * 4);
+    const size_t need = 2 * kb + 2 * ib + round256(sort_bytes) + 256;
+    if (!workspace) {
+        *workspace_bytes = need;
+        return PCONV_OK;
+    }
+    if (!w || !lib || !pid || !mask || !(keep >= 0.0 && keep <= 1.0)) return PCONV_EINVAL;
+    if (K < 1 || K > 126) return PCONV_EPATTERN;
+    Library l{};
+    for (int j = 0; j < K; ++j) {
+        if (lib[j] >= 512 || __builtin_popcount(lib[j]) != 4) return PCONV_EPATTERN;
+        l.mask[j] = lib[j];
+    }
+    if (*workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return PCONV_ESCRATCH;
+    if (n == 0) return PCONV_OK;
+    long long k = (long long)std::floor(keep * (double)n + 0.5);
+    k = k < 0 ? 0 : (k > n ? n : k);
+    char* base = static_cast<char*>(workspace);
+    uint64_t* key_in = reinterpret_cast<uint64_t*>(base);
+    uint64_t* key_out = reinterpret_cast<uint64_t*>(base + kb);
+    uint32_t* idx_in = reinterpret_cast<uint32_t*>(base + 2 * kb);
+    uint32_t* idx_out = reinterpret_cast<uint32_t*>(base + 2 * kb + ib);
+    void* sort_tmp = base + 2 * kb + 2 * ib;
+    const dim3 grid(grid_for(n)), block(kThreads);
+    if (dtype == PCONV_F32)
+        hipLaunchKernelGGL(norm_key_kernel<float>, grid, block, 0, st, static_cast<const float*>(w), n, l, K, pid, key_in,
+                           idx_in);
+    else
+        hipLaunchKernelGGL(norm_key_kernel<_Float16>, grid, block, 0, st, static_cast<const _Float16*>(w), n, l, K, pid,
+                           key_in, idx_in);
+    PCONV_HIP(hipGetLastError());
+    // a stable sort, largest key first: equal norms stay in ascending index order
+    PCONV_HIP(hipcub::DeviceRadixSort::SortPairsDescending(sort_tmp, sort_bytes, key_in, key_out, idx_in, idx_out, (int)n, 0,
+                                                          64, st));
+    hipLaunchKernelGGL(mark_kept_kernel, grid, block, 0, st, idx_out, n, k, mask);
+    PCONV_HIP(hipGetLastError());
+    return PCONV_OK;
+}
 
 extern "C" int pconv_admm_proximal(const float* z, const float* mu, float rho, long long n, int K, float* u,
                                    float* mu_out, void* stream) {

@@ -95,3 +95,71 @@ def test_device_pattern_assignment_matches_the_oracle_bit_for_bit(dtype, K):
     got = pid.cpu().numpy().reshape(F, C)
     np.testing.assert_array_equal(got, ref)
     np.testing.assert_array_equal(got, pc.assign_patterns(w.astype(np.float32), lib))      # and the host entry
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("keep", [0.0, 0.15, 0.28, 0.5, 1.0])
+def test_device_connectivity_selection_matches_the_oracle_bit_for_bit(dtype, keep):
+    import torch
+    import paper_2001_07710_amd as pc
+    from workloads import layers as L
+    F, C, K = 77, 163, 8                                       # 12551 kernels
+    w = rng.normal(rng.stream_seed(94, K), F * C * 9).reshape(F, C, 3, 3)
+    w = w.astype(np.float16 if dtype == "f16" else np.float32)
+    w[5:9] = w[1:5]                                           # whole filters repeated: many equal norms, ties by index
+    w[20, :40] = 0
+    lib = np.array(L.drawn_library(4, K), dtype=np.uint16)
+    pid = oracle.assign_patterns(w, lib)
+    ref = oracle.select_connectivity(w, lib, pid, keep)
+    n = F * C
+    st = torch.cuda.current_stream().cuda_stream
+    need = pc.select_connectivity_device_workspace(n)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    dw = torch.from_numpy(w).cuda()
+    dpid = torch.from_numpy(pid.astype(np.int32).reshape(-1)).cuda()
+    mask = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+    code = pc.F16 if dtype == "f16" else pc.F32
+    pc.select_connectivity_device(dw, code, n, lib, dpid, keep, mask, ws, need, st)
+    torch.cuda.synchronize()
+    got = mask.cpu().numpy().reshape(F, C)
+    np.testing.assert_array_equal(got, np.asarray(ref, dtype=np.uint8))
+    assert int(got.sum()) == int(np.floor(keep * n + 0.5))
+    np.testing.assert_array_equal(got, pc.select_connectivity(w.astype(np.float32), lib, pid, keep))   # the host entry
+    # a workspace that is too small is refused, nothing is written
+    mask.fill_(7)
+    with pytest.raises(pc.PconvError) as e:
+        pc.select_connectivity_device(dw, code, n, lib, dpid, keep, mask, ws, need - 256, st)
+    assert e.value.code == pc.ESCRATCH
+    torch.cuda.synchronize()
+    assert int(mask.min()) == 7
+
+
+def test_assign_then_select_on_the_device_feed_pack_like_the_host_steps():
+    """The two device steps chained, their outputs handed to pconv_pack: the packed layer is the one the host steps
+    give (canonical form compared bit for bit)."""
+    import torch
+    import paper_2001_07710_amd as pc
+    from workloads import layers as L
+    spec = L.shrink(L.config1(), C=48, F=40)
+    w = L.gen_weights(spec).astype(np.float32)
+    lib = spec.library()
+    n = spec.F * spec.C
+    st = torch.cuda.current_stream().cuda_stream
+    dw = torch.from_numpy(w).cuda()
+    dpid = torch.empty(n, dtype=torch.int32, device="cuda")
+    pc.assign_patterns_device(dw, pc.F32, n, lib, dpid, st)
+    need = pc.select_connectivity_device_workspace(n)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    dmask = torch.empty(n, dtype=torch.uint8, device="cuda")
+    pc.select_connectivity_device(dw, pc.F32, n, lib, dpid, spec.keep, dmask, ws, need, st)
+    torch.cuda.synchronize()
+    pid_d = dpid.cpu().numpy().reshape(spec.F, spec.C).astype(np.uint8)
+    mask_d = dmask.cpu().numpy().reshape(spec.F, spec.C)
+    pid_h = pc.assign_patterns(w, lib)
+    mask_h = pc.select_connectivity(w, lib, pid_h, spec.keep)
+    np.testing.assert_array_equal(pid_d, pid_h)
+    np.testing.assert_array_equal(mask_d, mask_h)
+    a = pc.packed_export(pc.pack(w, lib, pid_d, mask_d, flags=1))
+    b = pc.packed_export(pc.pack(w, lib, pid_h, mask_h, flags=1))
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(np.asarray(x), np.asarray(y))

@@ -45,7 +45,8 @@ def test_admm_entry_points_are_exported_and_refuse_bad_arguments_without_a_gpu()
     hdr = open(os.path.join(ROOT, "include", "pconv_admm.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(pconv_[a-z0-9_]+)\s*\(", hdr))
-    assert names == {"pconv_admm_proximal", "pconv_admm_binarize", "pconv_assign_patterns_device"}
+    assert names == {"pconv_admm_proximal", "pconv_admm_binarize", "pconv_assign_patterns_device",
+                     "pconv_select_connectivity_device"}
     lib = ctypes.CDLL(pc.LIB_PATH)
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} is declared in pconv_admm.h but not exported"
