@@ -88,3 +88,33 @@ def test_one_column_kernel_forms_on_random_shapes(seed):
         ok += _run_cases(layer, x, tunings, rnd)
         layer.free()
     assert ok >= 50
+
+
+@pytest.mark.parametrize("seed", [7, 8])
+def test_matrix_core_kernel_forms_on_random_shapes(seed):
+    """Every tile shape, with and without channel splits, row caps and one workgroup per tile; both strides and pads,
+    any width (all four piece widths of the loads and of the stores), filter and channel counts around the tile and
+    block sizes, batches that make tiles run from one image into the next.  fp16 storage only."""
+    M = pc.KERNEL_MFMA
+    rnd = random.Random(seed)
+    ok = 0
+    for it in range(36):
+        N = rnd.choice([1, 2, 3, 5, 9, 33, 70])
+        C = rnd.choice([1, 3, 8, 16, 17, 33, 48, 70, 130])
+        F = rnd.choice([1, 5, 16, 33, 64, 65, 130])
+        H, W = rnd.randint(1, 34), rnd.choice([rnd.randint(1, 70), 8 * rnd.randint(1, 8), 4 * rnd.randint(1, 16)])
+        stride, pad = rnd.choice([1, 1, 2]), rnd.choice([0, 1, 1])
+        keep = rnd.choice([0.05, 0.3, 0.6, 1.0])
+        if H + 2 * pad < 3 or W + 2 * pad < 3 or N * C * F * H * W > 6e7:
+            continue
+        spec = L.LayerSpec(cfg=32, idx=100 * seed + it, name="randomM", N=N, C=C, F=F, H=H, W=W, stride=stride, pad=pad,
+                           dtype="f16", K=rnd.choice([4, 8, 12]), keep=keep)
+        layer = GpuLayer(spec)
+        x = L.gen_activations(spec)
+        tunings = [dict(), dict(kernel=M)]
+        for _ in range(4):
+            tunings.append(dict(kernel=M, mfma_shape=rnd.choice([1, 2, 3, 4]), channel_splits=rnd.choice([0, 0, 1, 2, 4]),
+                                rows=rnd.choice([0, 0, 1, 3]), slot_walk=rnd.choice([0, 0, 1])))
+        ok += _run_cases(layer, x, tunings, rnd)
+        layer.free()
+    assert ok >= 80
