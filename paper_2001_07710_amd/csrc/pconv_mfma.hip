@@ -111,7 +111,9 @@ struct MfmaParams {
     unsigned chan_bytes;    // H*W*2
     unsigned img_bytes;     // C*H*W*2
     int KS;                      // workgroups that share one tile, each taking a contiguous range of the channel blocks
-    int win_alias;               // the epilogue's windows lie in the free staging buffer (else behind the bias)
+    int win_alias;               // the epilogue's windows lie in the staging buffer that is free meanwhile: 1 = its
+                                 // weights, 2 = its activations; 0 = in a place of their own behind the bias
+    int a_stages;                // 2; or 1: the layer has a single block of weights, staged once per workgroup
     int stagger;                 // every second workgroup starts this many steps of 2048 clocks late (0: none)
     float* ws;              // KS > 1: partial sums [tile][split][wave][operand tile][4 rows][64 lanes][4], as held
     unsigned* counters;     // KS > 1: one arrival counter per tile, zero between launches
@@ -181,6 +183,7 @@ struct TileGeo {
 template <int AF, int BF, int WM, int WN, int LW, int KI, bool FULL>
 __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 1) void mfma_conv_kernel(const MfmaParams p) {
     constexpr int kItems = KI;
+    constexpr bool CAN_ALIAS = AF == 1 && WM == 2 && WN == 2;
     constexpr int NW = WM * WN, NTH = NW * 64, MT = WM * AF * 32, HALF = NTH / 2;
     constexpr int WPIECES = (9 * 2 * MT + NTH - 1) / NTH;      // 16-byte pieces of weights per lane and block, at most
     constexpr int WP = BF * 32 + 16;                           // words between two filter pairs of a wave's output window
@@ -235,19 +238,24 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     };
 
     unsigned char* const ldsA = lds;
-    unsigned char* const ldsB = lds + 2 * p.a_bytes;
+    const int a_stages = CAN_ALIAS ? p.a_stages : 2;           // (plan() keeps the weights resident for that shape only)
+    unsigned char* const ldsB = lds + a_stages * p.a_bytes;
     float* const ldsBias = reinterpret_cast<float*>(lds + p.bias_off);          // [3][MT]: by tile count modulo 3
     unsigned* const win_fixed = reinterpret_cast<unsigned*>(lds + p.bias_off + 3 * MT * 4) + wave * (4 * WP);
 
-    // ---- once: zero columns left and right of the image (no tile's staging ever writes them)
-    if (p.pad) {
+    // ---- zero columns left and right of the image, in one staging buffer: once per workgroup (no tile's staging
+    // ever writes them), and again behind an epilogue whose windows lay in that buffer
+    auto zero_halo = [&](int stage) {
+        if (!p.pad) return;
         const uint4v zero = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < p.max_slots * 8; i += NTH) {
-            const int sl = i >> 3, which = i & 7;               // buffer (2) x half (2) x side (2)
+        for (int i = tid; i < p.max_slots * 4; i += NTH) {
+            const int sl = i >> 2, which = i & 3;               // half (2) x side (2)
             const int pos = (which & 1) ? PW - 1 : 0;
-            *reinterpret_cast<uint4v*>(ldsB + (which >> 1) * p.plane_bytes + (sl * PW + pos) * 16) = zero;
+            *reinterpret_cast<uint4v*>(ldsB + (stage * 2 + (which >> 1)) * p.plane_bytes + (sl * PW + pos) * 16) = zero;
         }
-    }
+    };
+    zero_halo(0);
+    zero_halo(1);
     // The tile's biases: 4 bytes per lane straight into LDS (buffer_load ... lds), in flight while the block that
     // issues them is multiplied; outside the tensor (filters behind the last, or no bias at all) the load gives zero.
     typedef __attribute__((address_space(3))) void* lds_ptr;
@@ -265,6 +273,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     int loff[kItems];
     int stage_tm = 0;
     bool stage_on = true;                                       // false: nothing left to load (offsets outside)
+    bool weights_on = true;                                     // false: the only block of weights is in LDS for good
     // (the descriptor of x is put together where it is used, from three scalars that are marked wave-uniform: as a
     // variable that changes from tile to tile the compiler would keep it in vector registers and wrap every load in
     // a loop over its distinct values)
@@ -329,9 +338,10 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
             stg[i][ch].load(xr, (chan < p.C && stage_on) ? goff[i] : kInvalid, (uint32_t)chan * p.chan_bytes);
         } else {
             const int first = ((j - 8 * kItems) * NW + wave) * 64;        // the wave's first piece (uniform)
-            if (first < w_pieces && stage_on) {
+            if (first < w_pieces && stage_on && weights_on) {
                 const uint32_t wsoff = (uint32_t)((stage_tm * p.CB + cb) * p.a_bytes);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_ptr)(ldsA + buf * p.a_bytes + first * 16), 16,
+                const int abuf = a_stages == 2 ? buf : 0;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_ptr)(ldsA + abuf * p.a_bytes + first * 16), 16,
                                                          (first + lane) * 16, (int)wsoff, 0, 0);
             }
         }
@@ -417,8 +427,11 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         // uses between the barrier that ended the tile's last block and the first loads of the block after next --
         // the caller puts a barrier behind the epilogue then, so that no wave starts those loads while another
         // still reads its window.  That saves the LDS that decides whether a second workgroup fits the compute unit.
-        unsigned* const win =
-            p.win_alias ? reinterpret_cast<unsigned*>(ldsA + free_buf * p.a_bytes) + wave * (4 * WP) : win_fixed;
+        unsigned* win = win_fixed;
+        if constexpr (CAN_ALIAS) {                 // (only the shape that can share a compute unit: plan() agrees)
+            if (p.win_alias == 1) win = reinterpret_cast<unsigned*>(ldsA + free_buf * p.a_bytes) + wave * (4 * WP);
+            if (p.win_alias == 2) win = reinterpret_cast<unsigned*>(ldsB + free_buf * 2 * p.plane_bytes) + wave * (4 * WP);
+        }
         // (the lane index as the compiler cannot see through it: everything below depends on it and is computed
         // here, not ahead of the channel blocks, where it would sit in registers that the multiply loop needs)
         int lane_e = lane;
@@ -621,6 +634,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     stage_bias(gc.tm, 0);
 #pragma unroll
     for (int j = 0; j < NLOADS; ++j) issue_one(gc.cb0, 0, j);
+    if (a_stages == 1) weights_on = false;
     write_lds(0);
     __syncthreads();
     compute_descriptors(gc);
@@ -645,7 +659,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
                     ncb = gc.cb0;
                 }
             }
-            const unsigned char* const a = ldsA + buf * p.a_bytes + aoff;
+            const unsigned char* const a = ldsA + (a_stages == 2 ? buf : 0) * p.a_bytes + aoff;
             const unsigned char* const b = ldsB + buf * 2 * p.plane_bytes;
             auto load_a = [&](int ts, int af) {
                 return *reinterpret_cast<const half8*>(a + (ts * 2 * MT + af * 32) * 16);
@@ -714,7 +728,10 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
             buf ^= 1;
         }
         if (p.KS == 1 || combine_splits(gc)) epilogue(gc, buf ^ 1);
-        if (p.win_alias) __syncthreads();
+        if constexpr (CAN_ALIAS) {
+            if (p.win_alias) __syncthreads();
+            if (p.win_alias == 2) zero_halo(buf ^ 1);    // (the windows lay over that buffer's zero columns)
+        }
         if (Tn >= ntiles) break;
         T = Tn;
         gc = gn;
@@ -846,13 +863,21 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         p.max_slots = (R - segs) * a.stride + 3 * segs;
         p.a_bytes = p.nt * 2 * MT * 16;
         p.plane_bytes = p.max_slots * p.PW * 16;
-        const size_t staging = 2 * (size_t)p.a_bytes + 4 * (size_t)p.plane_bytes;
+        // (a layer of at most 16 channels and one tile of filters has a single block of weights: staged once)
+        const bool shares_cu = sh.af == 1 && sh.wm == 2 && sh.wn == 2;    // (the shape two workgroups of which fit)
+        p.a_stages = (shares_cu && p.CB == 1 && (a.F + MT - 1) / MT == 1 && p.KS == 1) ? 1 : 2;
+        const size_t staging = (size_t)p.a_stages * p.a_bytes + 4 * (size_t)p.plane_bytes;
         p.bias_off = (int)staging;
         // behind the staging buffers: the bias of three tiles, and per wave a window of 4 filter pairs x its pixels
         // -- unless the shape is one whose registers leave room for a second workgroup on the compute unit and the
-        // windows fit the weights' half of a staging buffer: then they live there
+        // windows fit the weights' half of a staging buffer (or, where the weights stay, the activations' half): then
+        // they live there
         const size_t windows = (size_t)(NTH / 64) * 4 * (sh.bf * 32 + 16) * 4;
-        p.win_alias = (sh.af == 1 && sh.wm == 2 && sh.wn == 2 && windows <= (size_t)p.a_bytes) ? 1 : 0;
+        p.win_alias = 0;
+        if (shares_cu) {
+            if (p.a_stages == 2 && windows <= (size_t)p.a_bytes) p.win_alias = 1;
+            if (p.a_stages == 1 && windows <= 2 * (size_t)p.plane_bytes) p.win_alias = 2;
+        }
         lds = staging + 3 * (size_t)MT * 4 + (p.win_alias ? 0 : windows);
         p.flag_off = (int)lds;                   // one word for the channel split's "arrived last" flag
         lds += 16;
