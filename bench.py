@@ -419,7 +419,8 @@ def sweep_bench(args, torch, pc, L, stream):
                    "step": "one pconv_conv3x3 launch per layer, nine launches (weights packed once)"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP16_MFMA_TFLOPS, "traffic": traffic,
-                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, mean over all launches of the kernel, "
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, mean over all launches of the kernel "
+                                       "(compare all_launches_of_the_kernel.algorithmic_bytes_per_launch), "
                                        "profiles/mfma_conv_kernel_vgg16_batch64_hbm_counters.txt",
                      "kernel": "mfma_conv_kernel", "kernel_ms": kernel_ms, "launches_per_step": len(dom),
                      "layers": [specs[i].name for i in dom],
@@ -436,6 +437,7 @@ def sweep_bench(args, torch, pc, L, stream):
                          / (sum(per[i] for i in all_mfma) * 1e-3),
                      "all_launches_of_the_kernel": {
                          "layers": [specs[i].name for i in all_mfma],
+                         "algorithmic_bytes_per_launch": sum(ab[i] for i in all_mfma) / len(all_mfma),
                          "executed_TFLOPs": 2.0 * sum(exe[i] for i in all_mfma) / (sum(per[i] for i in all_mfma) * 1e-3) / 1e12},
                      "note": "the kernel runs the layer as a dense fp16 contraction over its masked weights on the "
                              "matrix cores; 'achieved' counts the multiply-adds it executes (every tap that occurs, "
