@@ -114,6 +114,8 @@ struct MfmaParams {
     int win_alias;               // the epilogue's windows lie in the staging buffer that is free meanwhile: 1 = its
                                  // weights, 2 = its activations; 0 = in a place of their own behind the bias
     int a_stages;                // 2; or 1: the layer has a single block of weights, staged once per workgroup
+    int b_stages;                // 2; or 1: one buffer for the activations, written between two barriers (where that
+                                 // makes the LDS small enough for a second workgroup on the compute unit)
     int stagger;                 // every second workgroup starts this many steps of 2048 clocks late (0: none)
     float* ws;              // KS > 1: partial sums [tile][split][wave][operand tile][4 rows][64 lanes][4], as held
     unsigned* counters;     // KS > 1: one arrival counter per tile, zero between launches
@@ -240,6 +242,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     unsigned char* const ldsA = lds;
     const int a_stages = CAN_ALIAS ? p.a_stages : 2;           // (plan() keeps the weights resident for that shape only)
     unsigned char* const ldsB = lds + a_stages * p.a_bytes;
+    const int b_stages = CAN_ALIAS ? p.b_stages : 2;
     float* const ldsBias = reinterpret_cast<float*>(lds + p.bias_off);          // [3][MT]: by tile count modulo 3
     unsigned* const win_fixed = reinterpret_cast<unsigned*>(lds + p.bias_off + 3 * MT * 4) + wave * (4 * WP);
 
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         }
     };
     zero_halo(0);
-    zero_halo(1);
+    if (b_stages == 2) zero_halo(1);
     // The tile's biases: 4 bytes per lane straight into LDS (buffer_load ... lds), in flight while the block that
     // issues them is multiplied; outside the tensor (filters behind the last, or no bias at all) the load gives zero.
     typedef __attribute__((address_space(3))) void* lds_ptr;
@@ -349,7 +352,9 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     // The staged activations of the next block: interleave the channels and write them to LDS; then wait for the
     // weights that are on their way into LDS, so that the barrier behind this publishes both.
     auto write_lds = [&](int buf) {
-        unsigned char* const b = ldsB + buf * 2 * p.plane_bytes;
+        // (a single buffer: every wave must be done reading the current block before the next one is written over it)
+        if (b_stages == 1) __syncthreads();
+        unsigned char* const b = ldsB + (b_stages == 2 ? buf : 0) * 2 * p.plane_bytes;
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
             if (loff[i] >= 0) {
@@ -660,7 +665,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
                 }
             }
             const unsigned char* const a = ldsA + (a_stages == 2 ? buf : 0) * p.a_bytes + aoff;
-            const unsigned char* const b = ldsB + buf * 2 * p.plane_bytes;
+            const unsigned char* const b = ldsB + (b_stages == 2 ? buf : 0) * 2 * p.plane_bytes;
             auto load_a = [&](int ts, int af) {
                 return *reinterpret_cast<const half8*>(a + (ts * 2 * MT + af * 32) * 16);
             };
@@ -866,7 +871,13 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         // (a layer of at most 16 channels and one tile of filters has a single block of weights: staged once)
         const bool shares_cu = sh.af == 1 && sh.wm == 2 && sh.wn == 2;    // (the shape two workgroups of which fit)
         p.a_stages = (shares_cu && p.CB == 1 && (a.F + MT - 1) / MT == 1 && p.KS == 1) ? 1 : 2;
-        const size_t staging = (size_t)p.a_stages * p.a_bytes + 4 * (size_t)p.plane_bytes;
+        // (one buffer for the activations instead of two where that, and nothing less, lets a second workgroup in)
+        p.b_stages = 2;
+        const size_t extra = 3 * (size_t)MT * 4 + 16;
+        if (shares_cu && p.a_stages == 2 && (size_t)p.a_stages * p.a_bytes + 4 * (size_t)p.plane_bytes + extra > 80 * 1024 &&
+            (size_t)p.a_stages * p.a_bytes + 2 * (size_t)p.plane_bytes + extra <= 80 * 1024)
+            p.b_stages = 1;
+        const size_t staging = (size_t)p.a_stages * p.a_bytes + 2 * (size_t)p.b_stages * p.plane_bytes;
         p.bias_off = (int)staging;
         // behind the staging buffers: the bias of three tiles, and per wave a window of 4 filter pairs x its pixels
         // -- unless the shape is one whose registers leave room for a second workgroup on the compute unit and the
