@@ -19,20 +19,27 @@
 // owns AF x BF operand tiles of 32 x 32.  Channels are taken in blocks of 16 (one MFMA K step); per block the
 // workgroup stages, in LDS, the weights of its filters for every tap and the input rows that its pixels read.
 //
-// LDS layouts (both double-buffered; one barrier per channel block).
-//   weights      [tap slot][half: channels 0-7 | 8-15][filter in tile][8 channels]   as they lie in global memory
+// LDS layouts (two stages each, one barrier per channel block; a layer with a single block of weights keeps it
+// in one stage for good, and one stage of activations written between two barriers is used where that lets a second
+// workgroup share the compute unit).
+//   weights      [tap slot][half: channels 0-7 | 8-15][filter in tile][8 channels]   as they lie in global memory,
+//                                                                                    copied by buffer_load ... lds
 //   activations  [half][input row slot][position = column + pad][8 channels]         channel-minor, 16 B per position
 // A lane's operand (8 consecutive channels of one filter, or of one pixel) is one 128-bit LDS read; lanes that are
 // neighbours in the filter or pixel index read neighbouring 16-byte pieces, so the reads are free of bank
 // conflicts, and a tap is nothing but a constant added to the pixel's byte offset: stride 2, either padding and any
-// image width come for free.  The activations arrive from global memory row by row (NCHW: pixel-minor), 1, 2 or 4
+// image width come for free.  The activations arrive from global memory row by row (NCHW: pixel-minor), 1, 2, 4 or 8
 // pixels of one channel per load; a lane gathers the same pixels of 8 channels and interleaves them in registers
-// (v_perm_b32) before the 128-bit LDS writes.  Positions left and right of the image are zeroed once per tile; rows
-// above and below it, images beyond the batch and channels beyond C are loads at an offset outside the buffer
+// (v_perm_b32) before the 128-bit LDS writes.  Positions left and right of the image are zeroed once per workgroup;
+// rows above and below it, images beyond the batch and channels beyond C are loads at an offset outside the buffer
 // descriptor, which return zero.
 //
-// Epilogue.  Bias, ReLU and the rounding to fp16 in registers; the tile goes through LDS once more, [filter][pixel],
-// and leaves in pieces of 8, 4, 2 or 1 pixels of one filter per lane (whatever divides the row length), coalesced.
+// Workgroups are persistent: each walks a sequence of (tile, channel block) pairs and fetches the next pair while it
+// multiplies the current one, also across tiles.
+//
+// Epilogue.  The accumulators start at the bias; ReLU and the rounding to fp16 in registers, two filters packed per
+// word; the tile goes through a wave-private window in LDS once more, [filter pair][pixel], and leaves in pieces of
+// 8, 4, 2 or 1 pixels of one filter per lane (whatever divides the row length), coalesced, as streaming stores.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
