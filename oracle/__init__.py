@@ -5,6 +5,7 @@ package never does.
 conv_oracle.c   direct convolution over masked dense weights, double accumulation (built by `build()` with gcc)
 pattern_oracle  masking, pattern assignment, connectivity selection, canonical packing (numpy, float64)
 admm_oracle     the selection-variable steps of the pruning framework: simplex projection, multiplier update, argmax
+backward_oracle input and masked weight gradients of the pruned layer; the 1x1 layer grouped into 3x3 patterns
 """
 from __future__ import annotations
 
@@ -15,6 +16,9 @@ import subprocess
 import numpy as np
 
 from .admm_oracle import binarize, proximal_step, simplex_project  # noqa: F401
+from .backward_oracle import (  # noqa: F401
+    conv1x1, conv3x3_grad_input, conv3x3_grad_weight, group_mask_1x1, masked_grad_weight,
+)
 from .pattern_oracle import (  # noqa: F401
     assign_patterns, library_bits, mask_weights, pack_canonical, retained_energy, select_connectivity,
     unpack_canonical,

@@ -104,7 +104,7 @@ struct MfmaParams {
     int nt;                 // tap slots
     int tap_off[9];         // byte offset of a tap inside an activation plane: (ky*PW + kx) * 16
     int R;                  // output rows (of the batch, n*Ho + oy) per tile
-    int PW;                 // positions per input row slot: W + 2*pad
+    int PW;                 // positions per input row slot: W + 2*pad, or more (plan())
     int max_slots;          // input row slots reserved per buffer
     int cnt_full;           // input row slots of a whole image: (Ho-1)*stride + 3
     int tiles_n, tiles_m;
@@ -260,7 +260,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         const uint4v zero = {0u, 0u, 0u, 0u};
         for (int i = tid; i < p.max_slots * 4; i += NTH) {
             const int sl = i >> 2, which = i & 3;               // half (2) x side (2)
-            const int pos = (which & 1) ? PW - 1 : 0;
+            const int pos = (which & 1) ? p.pad + p.W : 0;
             *reinterpret_cast<uint4v*>(ldsB + (stage * 2 + (which >> 1)) * p.plane_bytes + (sl * PW + pos) * 16) = zero;
         }
     };
@@ -862,6 +862,13 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     // pieces of the activations per lane that the kernels are built for, by load width
     auto max_items = [](int w) { return w == 8 ? 2 : 3; };
     p.PW = a.W + 2 * a.pad;
+    // Maps of at most 16 columns: 32 consecutive pixels span three or more rows, and a lane's operand read jumps by
+    // PW - Wo positions at every row end.  With that gap a multiple of 8 positions (128 bytes, all LDS banks once) the
+    // pieces of a read fall on the banks like one straight run (512 -> 512 channels at 14 x 14, batch 64: 69.5 ->
+    // 66 us).  Wider maps are left alone: there the row pitch this gives makes the staging writes collide instead
+    // (256 -> 256 channels at 56 x 56: 180 -> 194 us).
+    if (a.stride == 1 && a.W <= 16)
+        while ((p.PW - a.Wo) % 8) ++p.PW;
     p.cnt_full = (a.Ho - 1) * a.stride + 3;
     // rows per tile: as many as fit the pixels of the tile, the staging pieces of a lane and the LDS
     // Input row slots: a tile of R output rows that touches k images needs (R - k)*stride + 3k of them, most for the
