@@ -17,7 +17,7 @@ import numpy as np
 
 from .admm_oracle import binarize, proximal_step, simplex_project  # noqa: F401
 from .backward_oracle import (  # noqa: F401
-    conv1x1, conv3x3_grad_input, conv3x3_grad_weight, group_mask_1x1, masked_grad_weight,
+    conv1x1, conv3x3_grad_input, conv3x3_grad_weight, conv3x3_grad_weight_at, group_mask_1x1, masked_grad_weight,
 )
 from .pattern_oracle import (  # noqa: F401
     assign_patterns, library_bits, mask_weights, pack_canonical, retained_energy, select_connectivity,

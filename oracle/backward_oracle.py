@@ -61,6 +61,26 @@ def conv3x3_grad_weight(x, dy, stride: int = 1, pad: int = 1) -> np.ndarray:
     return G
 
 
+def conv3x3_grad_weight_at(x, dy, coords, stride: int = 1, pad: int = 1) -> np.ndarray:
+    """The same sum for the listed weights only: coords [npts][4] = (f, c, ky, kx); float64 [npts].  For layers too
+    large to take the whole gradient of."""
+    x = np.asarray(x)
+    dy = np.asarray(dy)
+    N, C, H, W = x.shape
+    Ho, Wo = dy.shape[2:]
+    out = np.zeros(len(coords), dtype=np.float64)
+    for i, (f, c, ky, kx) in enumerate(np.asarray(coords, dtype=np.int64).reshape(-1, 4)):
+        # output rows and columns whose tap (ky, kx) lies inside the image
+        oy = np.arange(Ho)
+        ox = np.arange(Wo)
+        oy = oy[(oy * stride + ky - pad >= 0) & (oy * stride + ky - pad < H)]
+        ox = ox[(ox * stride + kx - pad >= 0) & (ox * stride + kx - pad < W)]
+        a = dy[:, f][:, oy][:, :, ox].astype(np.float64)
+        b = x[:, c][:, oy * stride + ky - pad][:, :, ox * stride + kx - pad].astype(np.float64)
+        out[i] = np.sum(a * b)
+    return out
+
+
 def masked_grad_weight(x, dy, pid, mask, lib, stride: int = 1, pad: int = 1) -> np.ndarray:
     """G o M: the gradient of the weights that the layer keeps, zero elsewhere (float64 [F][C][3][3])."""
     from .pattern_oracle import mask_weights

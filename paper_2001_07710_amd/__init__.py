@@ -92,6 +92,15 @@ def _load():
                  "pconv_packed_stats", "pconv_packed_parity_form", "pconv_packed_library", "pconv_conv3x3", "pconv_conv3x3_noalloc", "pconv_conv3x3_tuned", "pconv_dense_conv3x3",
                  "pconv_maxpool2x2"):
         getattr(lib, name).restype = i
+    lib.pconv_packed_transpose.argtypes = [vp, u, ctypes.POINTER(vp)]
+    lib.pconv_conv3x3_grad_input.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.pconv_conv3x3_grad_weight_workspace.argtypes = [vp, i, i, i, i, i, ctypes.POINTER(ctypes.c_size_t)]
+    lib.pconv_conv3x3_grad_weight.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, ctypes.c_size_t, vp]
+    lib.pconv_pack_1x1.argtypes = [vp, i, i, i, vp, i, vp, vp, u, ctypes.POINTER(vp)]
+    lib.pconv_conv1x1.argtypes = [vp, vp, vp, vp, i, i, i, i, u, vp]
+    for name in ("pconv_packed_transpose", "pconv_conv3x3_grad_input", "pconv_conv3x3_grad_weight_workspace",
+                 "pconv_conv3x3_grad_weight", "pconv_pack_1x1", "pconv_conv1x1"):
+        getattr(lib, name).restype = i
     lib.pconv_strerror.argtypes = [i]
     lib.pconv_strerror.restype = ctypes.c_char_p
     lib.pconv_last_hip_error.argtypes = []
@@ -331,3 +340,48 @@ def select_connectivity_device(w, dtype: int, n: int, lib, pid, keep: float, mas
     _check(_load().pconv_select_connectivity_device(_dp(w), dtype, n, _hp(lib_h), int(lib_h.size), _dp(pid), float(keep),
                                                     _dp(mask), _dp(workspace), ctypes.byref(have), stream),
            "pconv_select_connectivity_device")
+
+
+# ---- pconv_backward.h: backward pass of the pruned layer, 1x1 layers grouped into 3x3 patterns
+
+def packed_transpose(p: Packed, flags: int = 0) -> Packed:
+    out = ctypes.c_void_p(None)
+    _check(_load().pconv_packed_transpose(p.handle, int(flags), ctypes.byref(out)), "pconv_packed_transpose")
+    return Packed(out.value, p.C, p.F, p.K, p.np_dtype)
+
+
+def conv3x3_grad_input(dy, dx, wpt: Packed, N: int, H: int, W: int, stream: int = 0):
+    _check(_load().pconv_conv3x3_grad_input(_dp(dy), _dp(dx), wpt.handle, N, H, W, stream or None),
+           "pconv_conv3x3_grad_input")
+
+
+def conv3x3_grad_weight_workspace(p: Packed, N: int, H: int, W: int, stride: int = 1, pad: int = 1) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_load().pconv_conv3x3_grad_weight_workspace(p.handle, N, H, W, stride, pad, ctypes.byref(n)),
+           "pconv_conv3x3_grad_weight_workspace")
+    return int(n.value)
+
+
+def conv3x3_grad_weight(x, dy, p: Packed, dw4, N: int, H: int, W: int, stride: int = 1, pad: int = 1, workspace=None,
+                        workspace_bytes: int = 0, stream: int = 0):
+    _check(_load().pconv_conv3x3_grad_weight(_dp(x), _dp(dy), p.handle, _dp(dw4), N, H, W, stride, pad,
+                                             _dp(workspace), int(workspace_bytes), stream or None),
+           "pconv_conv3x3_grad_weight")
+
+
+def pack_1x1(w_fc, lib, pid, mask, flags: int = 0) -> Packed:
+    w = np.ascontiguousarray(w_fc)
+    code = _dtype_code(w.dtype)
+    F, C = w.shape
+    lb = _host(lib, np.uint16)
+    pd = _host(pid, np.uint8)
+    mk = _host(mask, np.uint8)
+    out = ctypes.c_void_p(None)
+    _check(_load().pconv_pack_1x1(_hp(w), code, F, C, _hp(lb), int(lb.size), _hp(pd), _hp(mk), int(flags),
+                                  ctypes.byref(out)), "pconv_pack_1x1")
+    return Packed(out.value, F, C, 1, w.dtype)
+
+
+def conv1x1(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, flags: int = 0, stream: int = 0):
+    _check(_load().pconv_conv1x1(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, flags, stream or None),
+           "pconv_conv1x1")

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpconv.so")
 PEAKS_LIB = os.path.join(HERE, "libpconv_peaks.so")
-SOURCES = ["pconv_host.cpp", "pconv_device.hip", "pconv_mfma.hip", "pconv_admm.hip"]
+SOURCES = ["pconv_host.cpp", "pconv_device.hip", "pconv_mfma.hip", "pconv_admm.hip", "pconv_backward.hip"]
 
 # Packed fp32 instructions are switched off for every HIP translation unit of this project.
 HIPCC_FLAGS = [

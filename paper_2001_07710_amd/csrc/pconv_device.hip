@@ -70,6 +70,9 @@ int upload_packed(pconv_packed* p) {
         if (!b.perm.empty())
             PCONV_HIP(hipMemcpy(b.d_perm, b.perm.data(), b.perm.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     }
+    PCONV_HIP(hipMalloc((void**)&p->d_canon, std::max<size_t>(p->canon.size(), 2) * sizeof(uint32_t)));
+    if (!p->canon.empty())
+        PCONV_HIP(hipMemcpy(p->d_canon, p->canon.data(), p->canon.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
     for (MfmaWeights& m : p->mfma) {
         PCONV_HIP(hipMalloc(&m.d_w, std::max<size_t>(m.bytes(), 16)));
         if (m.bytes()) PCONV_HIP(hipMemcpy(m.d_w, m.w.data(), m.bytes(), hipMemcpyHostToDevice));
@@ -83,6 +86,8 @@ void release_device(pconv_packed* p) {
         if (m.d_w) (void)hipFree(m.d_w);
         m.d_w = nullptr;
     }
+    if (p->d_canon) (void)hipFree(p->d_canon);
+    p->d_canon = nullptr;
     if (p->d_ent) (void)hipFree(p->d_ent);
     if (p->d_eptr) (void)hipFree(p->d_eptr);
     if (p->d_forder) (void)hipFree(p->d_forder);
@@ -2517,6 +2522,20 @@ extern "C" int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* w
 extern "C" int pconv_conv3x3(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                              int stride, int pad, unsigned flags, void* stream) {
     return conv3x3_impl(x, y, wp, bias, N, H, W, stride, pad, flags, stream, nullptr, nullptr);
+}
+
+// A 1x1 layer packed by pconv_pack_1x1 is a 3x3 layer of centre taps: at padding 1 its output is the 1x1 layer's.
+extern "C" int pconv_conv1x1(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
+                             int stride, unsigned flags, void* stream) {
+    if (!wp) return PCONV_EINVAL;
+    if (!wp->is_1x1) return PCONV_ESTATE;
+    return conv3x3_impl(x, y, wp, bias, N, H, W, stride, 1, flags, stream, nullptr, nullptr);
+}
+
+// The input gradient of a layer at stride 1 and padding 1 is the forward pass of its transposed layer over dy.
+extern "C" int pconv_conv3x3_grad_input(const void* dy, void* dx, const pconv_packed* wpt, int N, int H, int W,
+                                        void* stream) {
+    return conv3x3_impl(dy, dx, wpt, nullptr, N, H, W, 1, 1, 0, stream, nullptr, nullptr);
 }
 
 extern "C" int pconv_conv3x3_noalloc(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H,

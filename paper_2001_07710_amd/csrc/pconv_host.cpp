@@ -287,7 +287,7 @@ void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) 
 // pconv_pack, and the packing of a layer re-packed over parity planes (`partial`: masks of one to four taps, up to
 // 255 of them; missing taps of a kernel are stored as zero weights).
 static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
-                     const uint8_t* mask, unsigned flags, bool partial, pconv_packed** out) {
+                     const uint8_t* mask, unsigned flags, bool partial, bool want_mfma, pconv_packed** out) {
     if (!out) return PCONV_EINVAL;
     *out = nullptr;
     if (!w_oihw || !pid || !mask) return PCONV_EINVAL;
@@ -356,6 +356,13 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
             }
         }
         p->grp_ptr[(size_t)F * K] = (uint32_t)e;
+        p->canon.resize(n_kept * 2);
+        for (int i = 0; i < F; ++i)
+            for (int j = 0; j < K; ++j)
+                for (uint32_t q = p->grp_ptr[(size_t)i * K + j]; q < p->grp_ptr[(size_t)i * K + j + 1]; ++q) {
+                    p->canon[(size_t)q * 2] = p->filter_order[(size_t)i];
+                    p->canon[(size_t)q * 2 + 1] = (uint32_t)p->cin[q] | ((uint32_t)lib[j] << 16);
+                }
 
         // device layout, derived from the canonical one: per (position i, channel bucket) the entries by pattern,
         // then channel; weights widened to fp32
@@ -404,7 +411,7 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
         p->balanced.resize(5);
         for (int t = 0; t < 5; ++t)
             build_balanced(p, tilings[t][0], tilings[t][1], tilings[t][2], &p->balanced[(size_t)t]);
-        if (dtype == PCONV_F16 && !partial) {
+        if (dtype == PCONV_F16 && want_mfma) {
             const int nh = (int)(sizeof(pconv::kMfmaTileHeights) / sizeof(int));
             p->mfma.resize((size_t)nh);
             for (int h = 0; h < nh; ++h) build_mfma_weights(p, pconv::kMfmaTileHeights[h], &p->mfma[(size_t)h]);
@@ -428,7 +435,85 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
 
 extern "C" int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
                           const uint8_t* mask, unsigned flags, pconv_packed** out) {
-    return pack_impl(w_oihw, dtype, F, C, lib, K, pid, mask, flags, false, out);
+    return pack_impl(w_oihw, dtype, F, C, lib, K, pid, mask, flags, false, true, out);
+}
+
+// Bit t = 3*ky + kx of a mask moved to 3*(2-ky) + (2-kx) = 8 - t: the kernel rotated by 180 degrees.
+static inline uint16_t rotate_mask(uint16_t m) {
+    unsigned r = 0;
+    for (int t = 0; t < 9; ++t)
+        if ((m >> t) & 1u) r |= 1u << (8 - t);
+    return (uint16_t)r;
+}
+
+extern "C" int pconv_packed_transpose(const pconv_packed* p, unsigned flags, pconv_packed** out) {
+    if (!out) return PCONV_EINVAL;
+    *out = nullptr;
+    if (!p) return PCONV_EINVAL;
+    if (flags & ~(unsigned)PCONV_PACK_HOST_ONLY) return PCONV_EINVAL;
+    if (check_library(p->lib.data(), p->K) != PCONV_OK || p->is_1x1) return PCONV_EUNSUPPORTED;   // (a derived form)
+    const int F = p->F, C = p->C, K = p->K;
+    if (F >= 65536) return PCONV_ESHAPE;                 // (the filters become the input channels: 16-bit indices)
+    const size_t esize = p->dtype == PCONV_F16 ? 2 : 4;
+    try {
+        std::vector<uint16_t> lib((size_t)K);
+        for (int j = 0; j < K; ++j) lib[(size_t)j] = rotate_mask(p->lib[(size_t)j]);
+        std::vector<unsigned char> w((size_t)C * F * 9 * esize, 0);
+        std::vector<uint8_t> pid((size_t)C * F, 0), mask((size_t)C * F, 0);
+        for (int i = 0; i < F; ++i) {
+            const uint32_t f = p->filter_order[(size_t)i];
+            for (int j = 0; j < K; ++j) {
+                int taps[4], q = 0;
+                for (int t = 0; t < 9; ++t)
+                    if ((p->lib[(size_t)j] >> t) & 1u) taps[q++] = t;
+                for (uint32_t e = p->grp_ptr[(size_t)i * K + j]; e < p->grp_ptr[(size_t)i * K + j + 1]; ++e) {
+                    const size_t cf = (size_t)p->cin[e] * F + f;
+                    pid[cf] = (uint8_t)j;
+                    mask[cf] = 1;
+                    for (int k = 0; k < 4; ++k)
+                        std::memcpy(&w[(cf * 9 + (size_t)(8 - taps[k])) * esize], &p->w4[((size_t)e * 4 + k) * esize], esize);
+                }
+            }
+        }
+        return pack_impl(w.data(), p->dtype, C, F, lib.data(), K, pid.data(), mask.data(), flags, false, true, out);
+    } catch (const std::bad_alloc&) {
+        return PCONV_ENOMEM;
+    }
+}
+
+extern "C" int pconv_pack_1x1(const void* w_fc, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
+                              const uint8_t* mask, unsigned flags, pconv_packed** out) {
+    if (!out) return PCONV_EINVAL;
+    *out = nullptr;
+    if (!w_fc || !pid || !mask) return PCONV_EINVAL;
+    if (dtype != PCONV_F32 && dtype != PCONV_F16) return PCONV_EINVAL;
+    if (int rc = check_library(lib, K)) return rc;
+    if (int rc = check_fc(F, C)) return rc;
+    const int G = (C + 8) / 9;
+    for (long long i = 0; i < (long long)F * G; ++i)
+        if (mask[i] && pid[i] >= K) return PCONV_EPATTERN;
+    const size_t esize = dtype == PCONV_F16 ? 2 : 4;
+    const unsigned char* wb = static_cast<const unsigned char*>(w_fc);
+    try {
+        // the same layer as a 3x3 layer whose kernels keep their centre tap only: kernel (f,c) exists where channel c
+        // is a kept position of its group's pattern
+        std::vector<unsigned char> w9((size_t)F * C * 9 * esize, 0);
+        std::vector<uint8_t> pid9((size_t)F * C, 0), mask9((size_t)F * C, 0);
+        for (int f = 0; f < F; ++f)
+            for (int c = 0; c < C; ++c) {
+                const size_t fg = (size_t)f * G + (size_t)(c / 9);
+                if (!mask[fg] || !((lib[pid[fg]] >> (c % 9)) & 1u)) continue;
+                const size_t fc = (size_t)f * C + c;
+                mask9[fc] = 1;
+                std::memcpy(&w9[(fc * 9 + 4) * esize], wb + fc * esize, esize);
+            }
+        const uint16_t centre = 0x010;
+        const int rc = pack_impl(w9.data(), dtype, F, C, &centre, 1, pid9.data(), mask9.data(), flags, true, true, out);
+        if (rc == PCONV_OK) (*out)->is_1x1 = true;
+        return rc;
+    } catch (const std::bad_alloc&) {
+        return PCONV_ENOMEM;
+    }
 }
 
 int pconv::derive_for_stride2(const pconv_packed* p, int pad, bool upload, pconv_packed** out) {
@@ -457,7 +542,7 @@ int pconv::derive_for_stride2(const pconv_packed* p, int pad, bool upload, pconv
                     if ((p->lib[(size_t)j] >> t) & 1u) taps[q++] = t;
                 for (uint32_t e = p->grp_ptr[(size_t)i * K + j]; e < p->grp_ptr[(size_t)i * K + j + 1]; ++e) {
                     const size_t c = p->cin[e];
-                    for (int k = 0; k < 4; ++k) {
+                    for (int k = 0; k < q; ++k) {          // (q < 4: a layer whose kernels keep fewer taps, the 1x1 form)
                         const size_t fc = (size_t)f * C4 + 4 * c + (size_t)plane_of[taps[k]];
                         std::memcpy(&w[(fc * 9 + (size_t)tap_of[taps[k]]) * esize], &p->w4[((size_t)e * 4 + k) * esize], esize);
                         m9[fc] |= (uint16_t)(1u << tap_of[taps[k]]);
@@ -483,7 +568,7 @@ int pconv::derive_for_stride2(const pconv_packed* p, int pad, bool upload, pconv
                 mask[i] = 1;
             }
         return pack_impl(w.data(), p->dtype, F, C4, lib.data(), (int)lib.size(), pid.data(), mask.data(),
-                         upload ? 0u : (unsigned)PCONV_PACK_HOST_ONLY, true, out);
+                         upload ? 0u : (unsigned)PCONV_PACK_HOST_ONLY, true, false, out);
     } catch (const std::bad_alloc&) {
         return PCONV_ENOMEM;
     }

@@ -67,6 +67,7 @@ struct MfmaWeights {
 struct pconv_packed {
     int F = 0, C = 0, K = 0, dtype = 0;
     size_t n_kept = 0;
+    bool is_1x1 = false;                  // made by pconv_pack_1x1: every entry is one weight of a 1x1 layer (centre tap)
     std::vector<uint16_t> lib;
 
     // canonical form (what pconv_packed_export returns)
@@ -80,6 +81,9 @@ struct pconv_packed {
     std::vector<pconv::DevEntry> ent;     // [n_kept]
     std::vector<uint32_t> eptr;           // [F*n_buckets + 1]: entries of (i, bucket) are eptr[i*n_buckets+bucket] ..
     std::vector<uint32_t> ent_of_canonical;   // [n_kept]: index in `ent` of each canonical entry
+    // per canonical entry {filter, channel | mask << 16}: what the weight-gradient pass needs to find an entry's sums
+    std::vector<uint32_t> canon;              // [n_kept*2]
+    uint32_t* d_canon = nullptr;
 
     // balanced layouts for the tilings that the automatic choice uses (see pconv::BalancedLayout)
     std::vector<pconv::BalancedLayout> balanced;

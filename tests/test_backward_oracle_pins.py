@@ -66,6 +66,16 @@ def test_gradients_equal_float64_autograd(shape):
     np.testing.assert_allclose(B.conv3x3_grad_weight(x, dy, s, p), tw.grad.numpy(), rtol=1e-11, atol=1e-11)
 
 
+@pytest.mark.parametrize("shape", [(2, 3, 4, 6, 7, 1, 1), (1, 2, 3, 7, 6, 2, 1), (2, 2, 2, 5, 5, 1, 0)])
+def test_weight_gradient_at_listed_coordinates_equals_the_full_one(shape):
+    N, C, F, H, W, s, p = shape
+    x, _, dy, _, _ = _case(*shape)
+    G = B.conv3x3_grad_weight(x, dy, s, p)
+    coords = [(f, c, ky, kx) for f in range(F) for c in range(C) for ky in range(3) for kx in range(3)]
+    got = B.conv3x3_grad_weight_at(x, dy, coords, s, p)
+    np.testing.assert_allclose(got, G.reshape(-1), rtol=1e-12, atol=1e-12)
+
+
 def test_closed_forms():
     # a centre-only kernel of value a: dx = a * dy (stride 1, pad 1); its weight gradient is <dy, x>
     x, _, dy, _, _ = _case(2, 1, 1, 6, 5, 1, 1)

@@ -1,0 +1,164 @@
+"""The backward pass of the pruned layer and the grouped 1x1 layer on the GPU against the oracle: the input gradient
+through the transposed layer (both storage types), the masked weight gradient on the matrix cores (fp16 storage) for
+shapes that hit what its chunking distinguishes -- every load width, several column blocks, ragged last row blocks,
+filter and channel counts that are not multiples of the 64 x 64 tile, more chunks than workgroups -- and at a full
+benchmark shape on sampled weights; the 1x1 layer for both storage types and strides."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2001_07710_amd as pc
+from workloads import layers as L
+
+from gpu_util import TOL, GpuLayer, rel_err
+
+pytestmark = pytest.mark.gpu
+
+# fp32 accumulation of up to 2e5 exact fp16 x fp16 products per weight, result not rounded to fp16: rounding errors of
+# 2^-24 relative to the running sum, sqrt(n) of them at random signs is 3e-5 of the result's rms; the bound asked for
+# leaves a factor of a few
+TOL_DW = 2e-4
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+
+
+def _spec(i, N, C, F, H, W, dtype, keep=0.4):
+    return L.LayerSpec(cfg=30, idx=i, name="bwd", N=N, C=C, F=F, H=H, W=W, stride=1, pad=1, dtype=dtype, K=8, keep=keep)
+
+
+def _gauss(shape, seed, np_dtype):
+    return np.random.default_rng(seed).standard_normal(shape).astype(np_dtype)
+
+
+GI = [(2, 20, 33, 9, 12, "f32"), (3, 40, 70, 13, 28, "f16"), (1, 64, 64, 14, 14, "f32"), (2, 16, 48, 7, 7, "f16"),
+      (2, 130, 24, 20, 56, "f16")]
+
+
+@pytest.mark.parametrize("case", GI, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}{c[5]}" for c in GI])
+def test_input_gradient_through_the_transposed_layer(case):
+    import torch
+    N, C, F, H, W, dt = case
+    say("grad_input", case)
+    layer = GpuLayer(_spec(GI.index(case), N, C, F, H, W, dt), use_bias=False)
+    npd = np.float16 if dt == "f16" else np.float32
+    dy = _gauss((N, F, H, W), 11 + GI.index(case), npd)
+    t = pc.packed_transpose(layer.packed)
+    d_dy = torch.from_numpy(dy).cuda()
+    d_dx = torch.full((N, C, H, W), -777.0, dtype=d_dy.dtype, device="cuda")
+    pc.conv3x3_grad_input(d_dy, d_dx, t, N, H, W, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ref = oracle.conv3x3_grad_input(dy, layer.wm, H, W, 1, 1)
+    err = rel_err(d_dx.cpu().numpy(), ref)
+    assert err <= TOL[dt], (case, err)
+    t.free()
+    layer.free()
+
+
+def _grad_weight(layer, x, dy):
+    import torch
+    s = layer.spec
+    d_x, d_dy = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
+    nbytes = pc.conv3x3_grad_weight_workspace(layer.packed, s.N, s.H, s.W)
+    ws = torch.empty(max(nbytes, 16) + 4096, dtype=torch.uint8, device="cuda")
+    ws[nbytes:] = 0x5A
+    nk = layer.packed.n_kept
+    out = torch.full((nk * 4 + 64,), -777.0, dtype=torch.float32, device="cuda")
+    pc.conv3x3_grad_weight(d_x, d_dy, layer.packed, out, s.N, s.H, s.W, 1, 1, ws, nbytes,
+                           torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert bool((ws[nbytes:] == 0x5A).all()), "write outside the workspace"
+    o = out.cpu().numpy()
+    assert np.all(o[nk * 4:] == -777.0), "write outside the gradient buffer"
+    return o[:nk * 4].reshape(nk, 4)
+
+
+GW = [  # N, C, F, H, W
+    (2, 64, 64, 8, 56),       # whole tiles, 16-byte loads
+    (3, 40, 70, 13, 28),      # ragged filters and channels; 8-byte loads; odd height: a ragged last row block
+    (2, 33, 130, 9, 12),      # three filter tiles; 12 columns: two groups, the second half empty
+    (5, 16, 20, 7, 7),        # 2-byte loads, one group
+    (2, 20, 33, 14, 14),      # 4-byte loads
+    (1, 24, 16, 6, 224),      # four column blocks
+    (2, 8, 8, 5, 130),        # a ragged last column block, 4-byte loads
+    (40, 64, 64, 28, 28),     # more chunks than workgroups per tile: every workgroup walks several
+    (1, 5, 3, 1, 1),          # a single pixel
+    (2, 100, 96, 10, 72),     # nine groups: two column blocks of five and four
+]
+
+
+@pytest.mark.parametrize("case", GW, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}" for c in GW])
+def test_masked_weight_gradient(case):
+    N, C, F, H, W = case
+    say("grad_weight", case)
+    layer = GpuLayer(_spec(10 + GW.index(case), N, C, F, H, W, "f16"), use_bias=False)
+    x = L.gen_activations(layer.spec)
+    dy = _gauss((N, F, H, W), 23 + GW.index(case), np.float16)
+    got = _grad_weight(layer, x, dy)
+    G = oracle.conv3x3_grad_weight(x, dy, 1, 1)
+    ref = oracle.pack_canonical(G, layer.pid, layer.mask, layer.lib)[3]        # the kept taps in canonical order
+    assert got.shape == ref.shape
+    err = rel_err(got, ref)
+    assert err <= TOL_DW, (case, err)
+    again = _grad_weight(layer, x, dy)
+    assert got.tobytes() == again.tobytes(), "the weight gradient is not reproducible"
+    layer.free()
+
+
+def test_masked_weight_gradient_at_a_benchmark_shape_on_sampled_weights():
+    # 256 -> 256 channels at 56 x 56, batch 64 (config 4's conv3_2): 2e5 pixels per weight
+    spec = [s for s in L.config4(8, 0.28, 64) if s.name == "conv3_2"][0]
+    say("grad_weight full", spec.name)
+    layer = GpuLayer(spec, use_bias=False)
+    x = L.gen_activations(spec)
+    dy = _gauss((spec.N, spec.F, spec.H, spec.W), 5, np.float16)
+    got = _grad_weight(layer, x, dy)
+    fo, gp, cin, _ = pc.packed_export(layer.packed)
+    rng = np.random.default_rng(9)
+    es = np.concatenate([[0, layer.packed.n_kept - 1], rng.integers(0, layer.packed.n_kept, 160)])
+    pos = np.searchsorted(gp, es, side="right") - 1                 # group i*K + j of every sampled entry
+    coords, idx = [], []
+    for e, g in zip(es, pos):
+        f, j = int(fo[g // spec.K]), int(g % spec.K)
+        taps = [t for t in range(9) if (int(layer.lib[j]) >> t) & 1]
+        q = int(rng.integers(0, 4))
+        coords.append((f, int(cin[e]), taps[q] // 3, taps[q] % 3))
+        idx.append((int(e), q))
+    ref = oracle.conv3x3_grad_weight_at(x, dy, coords, 1, 1)
+    g = np.array([got[e, q] for e, q in idx], dtype=np.float64)
+    scale = float(np.sqrt(np.mean(ref * ref)))
+    assert np.max(np.abs(g - ref) / np.maximum(np.abs(ref), scale)) <= TOL_DW
+    layer.free()
+
+
+C1 = [(2, 64, 40, 14, 14, 1, "f16"), (3, 100, 33, 9, 12, 1, "f32"), (2, 256, 64, 28, 28, 1, "f16"),
+      (2, 48, 96, 20, 56, 2, "f16"), (2, 21, 10, 15, 18, 2, "f32"), (1, 5, 3, 1, 1, 1, "f16")]
+
+
+@pytest.mark.parametrize("case", C1, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}s{c[5]}{c[6]}" for c in C1])
+def test_grouped_1x1_layer(case):
+    import torch
+    N, C, F, H, W, stride, dt = case
+    say("conv1x1", case)
+    i = C1.index(case)
+    npd = np.float16 if dt == "f16" else np.float32
+    rng = np.random.default_rng(300 + i)
+    lib = _spec(0, 1, 1, 1, 1, 1, dt).library()
+    G = (C + 8) // 9
+    w = (rng.standard_normal((F, C)) * np.sqrt(2.0 / C)).astype(npd)
+    b = (rng.standard_normal(F) * 0.1).astype(np.float32)
+    x = np.maximum(rng.standard_normal((N, C, H, W)), 0).astype(npd)
+    pid = rng.integers(0, len(lib), size=(F, G)).astype(np.uint8)
+    mask = (rng.random((F, G)) < 0.5).astype(np.uint8)
+    p = pc.pack_1x1(w, lib, pid, mask)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    d_x, d_b = torch.from_numpy(x).cuda(), torch.from_numpy(b).cuda()
+    d_y = torch.full((N, F, Ho, Wo), -777.0, dtype=d_x.dtype, device="cuda")
+    for relu in (False, True):
+        pc.conv1x1(d_x, d_y, p, d_b, N, H, W, stride, pc.FLAG_RELU if relu else 0, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        ref = oracle.conv1x1(x, w, pid, mask, lib, b, stride, relu)
+        err = rel_err(d_y.cpu().numpy(), ref)
+        assert err <= TOL[dt], (case, relu, err)
+    p.free()
