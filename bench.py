@@ -171,6 +171,10 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="default run without the other configurations")
     ap.add_argument("--admm", action="store_true",
                     help="the selection-variable steps of the pruning framework over all kernels of VGG-16")
+    ap.add_argument("--backward", action="store_true",
+                    help="backward pass of the nine VGG-16 shapes at batch 64: masked weight gradient and input gradient")
+    ap.add_argument("--conv1x1", action="store_true",
+                    help="the 1x1 convolutions of ResNet-50's bottlenecks at batch 32, grouped into 3x3 patterns")
     ap.add_argument("--layers", default="")
     ap.add_argument("--K", type=int, default=8)
     ap.add_argument("--keep", type=float, default=0.28)
@@ -200,6 +204,10 @@ def main():
         return peaks_bench(args, torch)
     if args.admm:
         return admm_bench(args, torch, pc, L)
+    if args.backward:
+        return backward_bench(args, torch, pc, L)
+    if args.conv1x1:
+        return conv1x1_bench(args, torch, pc, L)
     if args.chain:
         return chain_bench(args, torch, pc, L)
     if args.layers:
@@ -564,6 +572,127 @@ def admm_bench(args, torch, pc, L):
            "steps_table": rows,
            "cpu_baseline": {"value": m / el, "unit": "kernels/s", "cores": 1, "kind": "oracle",
                             "sample": f"the first {m} kernels, {el:.1f} s"}}
+    print(json.dumps(out), flush=True)
+
+
+def backward_bench(args, torch, pc, L):
+    """Backward pass (include/pconv_backward.h) of config 4's nine VGG-16 shapes at batch 64, fp16 storage, K and keep
+    from the command line: per layer one masked weight gradient (grad_weight_kernel + gather) and one input gradient
+    (the forward kernel on the transposed layer; the first layer has none to hand back).  The weight gradient is a
+    dense contraction over the pixels on the matrix cores: executed flops = 2 * pixels * 9 * F' * C' with F', C'
+    rounded up to the 64 x 64 tile, against the dense fp16 MFMA peak; algorithmic bytes = x and dy read once."""
+    import oracle
+    st = torch.cuda.current_stream().cuda_stream
+    rows, tot_gw, tot_gi, flops_sum = [], 0.0, 0.0, 0.0
+    worst = None
+    for spec in L.config4(args.K, args.keep, 64):
+        if args.only and spec.name != args.only:
+            continue
+        layer = DeviceLayer(spec, batch_from_one_image=True)
+        g = np.random.default_rng(1000 + spec.idx).standard_normal((4, spec.F, spec.Ho, spec.Wo)).astype(np.float16)
+        dy = torch.from_numpy(np.concatenate([g] * (spec.N // 4), axis=0)).cuda()
+        nbytes = pc.conv3x3_grad_weight_workspace(layer.packed, spec.N, spec.H, spec.W)
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+        dw4 = torch.empty((layer.n_kept, 4), dtype=torch.float32, device="cuda")
+        gw = lambda: pc.conv3x3_grad_weight(layer.dx, dy, layer.packed, dw4, spec.N, spec.H, spec.W, 1, 1, ws, nbytes, st)
+        _, gw_ms = time_launches(torch, gw, args.steps, args.warmup)
+        pix = spec.N * spec.H * spec.W
+        f64, c64 = (spec.F + 63) // 64 * 64, (spec.C + 63) // 64 * 64
+        flops = 2.0 * pix * 9 * f64 * c64
+        row = {"layer": spec.name, "C": spec.C, "F": spec.F, "H": spec.H, "n_kept": layer.n_kept,
+               "grad_weight_us": gw_ms * 1e3, "executed_TFLOPs": flops / gw_ms / 1e9,
+               "mfma_frac": flops / gw_ms / 1e9 / PEAK_FP16_MFMA_TFLOPS,
+               "alg_GBs": 2.0 * pix * (spec.C + spec.F) / gw_ms / 1e6,
+               "eff_GMACs": pix * 4.0 * layer.n_kept / gw_ms / 1e6, "workspace_MB": nbytes / 1e6}
+        if spec.C >= 16:
+            t = pc.packed_transpose(layer.packed)
+            dxg = torch.empty_like(layer.dx)
+            gi = lambda: pc.conv3x3_grad_input(dy, dxg, t, spec.N, spec.H, spec.W, st)
+            _, gi_ms = time_launches(torch, gi, args.steps, args.warmup)
+            row["grad_input_us"] = gi_ms * 1e3
+            tot_gi += gi_ms
+            t.free()
+        tot_gw += gw_ms
+        flops_sum += flops
+        if worst is None or gw_ms > worst[1]:
+            worst = (spec, gw_ms, layer.x[:1].copy(), g[:1].copy())
+        rows.append(row)
+        log(json.dumps(row))
+        layer.packed.free()
+        del layer, dy, ws, dw4
+        torch.cuda.empty_cache()
+    # the oracle on one image of the slowest layer, timed on the host
+    spec, _, x1, g1 = worst
+    t0 = time.perf_counter()
+    oracle.conv3x3_grad_weight(x1, g1, 1, 1)
+    el = time.perf_counter() - t0
+    out = {"metric": "executed TFLOP/s, masked weight gradient of VGG-16 3x3 layers", "value": flops_sum / tot_gw / 1e9,
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": tot_gw,
+           "higher_is_better": True, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+           "config": {"workload": f"backward pass of configs[4] at K={args.K}, keep {args.keep}: nine VGG-16 shapes, batch 64"},
+           "roofline": {"bound": "mfma", "achieved": flops_sum / tot_gw / 1e9, "peak": PEAK_FP16_MFMA_TFLOPS,
+                        "unit": "TFLOP/s", "frac": flops_sum / tot_gw / 1e9 / PEAK_FP16_MFMA_TFLOPS, "traffic": None,
+                        "kernel": "grad_weight_kernel"},
+           "grad_input_total_us": tot_gi * 1e3, "layers": rows,
+           "cpu_baseline": {"value": 2.0 * spec.H * spec.W * 9 * spec.F * spec.C / el / 1e12, "unit": "TFLOP/s",
+                            "cores": oracle.threads(), "kind": "oracle",
+                            "sample": f"dense weight gradient of one image of {spec.name}, {el:.1f} s"}}
+    print(json.dumps(out), flush=True)
+
+
+def conv1x1_bench(args, torch, pc, L):
+    """The 1x1 convolutions of ResNet-50's bottleneck blocks (reduce and expand of each stage) at batch 32, fp16
+    storage, grouped into 3x3 patterns (include/pconv_backward.h): K patterns, keep from the command line.  These
+    layers move their activations once for C*F*4/9*keep multiply-adds per pixel: the roofline is HBM, algorithmic
+    bytes = input + output + kept weights."""
+    import oracle
+    st = torch.cuda.current_stream().cuda_stream
+    shapes = [("s1_reduce", 256, 64, 56), ("s1_expand", 64, 256, 56), ("s2_reduce", 512, 128, 28),
+              ("s2_expand", 128, 512, 28), ("s3_reduce", 1024, 256, 14), ("s3_expand", 256, 1024, 14),
+              ("s4_reduce", 2048, 512, 7), ("s4_expand", 512, 2048, 7)]
+    N = 32
+    lib = np.array(L.drawn_library(3, args.K), dtype=np.uint16)
+    rows, tot_ms, tot_bytes, sample = [], 0.0, 0.0, None
+    for i, (name, C, F, H) in enumerate(shapes):
+        rng = np.random.default_rng(500 + i)
+        G = (C + 8) // 9
+        w = (rng.standard_normal((F, C)) * np.sqrt(2.0 / C)).astype(np.float16)
+        b = (rng.standard_normal(F) * 0.1).astype(np.float32)
+        x1 = np.maximum(rng.standard_normal((4, C, H, H)), 0).astype(np.float16)
+        pid = rng.integers(0, args.K, size=(F, G)).astype(np.uint8)
+        mask = (rng.random((F, G)) < args.keep).astype(np.uint8)
+        p = pc.pack_1x1(w, lib, pid, mask)
+        dx = torch.from_numpy(np.concatenate([x1] * (N // 4), axis=0)).cuda()
+        db = torch.from_numpy(b).cuda()
+        dy = torch.empty((N, F, H, H), dtype=torch.float16, device="cuda")
+        fn = lambda: pc.conv1x1(dx, dy, p, db, N, H, H, 1, pc.FLAG_RELU, st)
+        _, ms = time_launches(torch, fn, args.steps, args.warmup)
+        nbytes = 2.0 * N * H * H * (C + F) + 2.0 * p.n_kept
+        row = {"layer": name, "C": C, "F": F, "H": H, "n_kept_weights": p.n_kept, "us": ms * 1e3,
+               "alg_GBs": nbytes / ms / 1e6, "hbm_frac": nbytes / ms / 1e6 / PEAK_HBM_GBS,
+               "eff_GMACs": N * H * H * float(p.n_kept) / ms / 1e6,
+               "executed_TFLOPs": 2.0 * N * H * H * ((C + 15) // 16 * 16) * F / ms / 1e9}
+        rows.append(row)
+        log(json.dumps(row))
+        tot_ms += ms
+        tot_bytes += nbytes
+        if i == 0:
+            sample = (name, x1[:1], w, pid, mask, b)
+        p.free()
+    name, x1, w, pid, mask, b = sample
+    t0 = time.perf_counter()
+    oracle.conv1x1(x1, w, pid, mask, lib, b, 1, True)
+    el = time.perf_counter() - t0
+    kept = int(oracle.group_mask_1x1(pid, mask, lib, *w.shape).sum())
+    out = {"metric": "algorithmic GB/s, ResNet-50 1x1 layers grouped into 3x3 patterns", "value": tot_bytes / tot_ms / 1e6,
+           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": tot_ms,
+           "higher_is_better": True, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+           "config": {"workload": f"eight 1x1 layers of ResNet-50's bottlenecks, batch 32, K={args.K}, keep {args.keep}"},
+           "roofline": {"bound": "hbm", "achieved": tot_bytes / tot_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": tot_bytes / tot_ms / 1e6 / PEAK_HBM_GBS, "traffic": None, "kernel": "mfma_conv_kernel"},
+           "layers": rows,
+           "cpu_baseline": {"value": x1.shape[2] * x1.shape[3] * kept / el / 1e9, "unit": "effective GMAC/s", "cores": 1,
+                            "kind": "oracle", "sample": f"one image of {name}, {el:.2f} s"}}
     print(json.dumps(out), flush=True)
 
 

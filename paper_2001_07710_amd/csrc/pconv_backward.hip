@@ -10,14 +10,20 @@
 //
 // Tile.  A workgroup of four waves owns 64 filters x 64 channels x 9 taps (a wave: 32 x 32 x 9, 144 accumulators)
 // and walks over chunks of the pixels: R output rows x Gc groups of 8 columns of one image.  Per chunk it stages
-//   dy  [row r][group g][filter][8 pixels]                    one 16-byte piece per (filter, r, g)
-//   x   [input row r'][group j][channel][8 pixels]            rows oy0-1 .. oy0+R, groups one left and one right more
+//   x   [input row r'][group g][channel][8 pixels]            rows oy0-1 .. oy0+R, one 16-byte piece per (channel, r', g)
+//   dy  [row r][group j][filter][8 pixels]                    groups one left and one right more than x has
 // 1040 bytes from one (row, group) to the next, so that neighbouring groups of one channel fall on different banks
 // when they are written and the 32 filters (channels) of an operand read lie side by side.  The three taps of a
-// kernel row share one read: the group itself is kx = 1, and kx = 0 / 2 are the same eight pixels moved by one
-// with the last / first pixel of the neighbouring group (five v_alignbyte_b32).  Zero padding, columns beyond the
-// image, rows beyond it, filters beyond F and channels beyond C are loads at an offset outside the buffer descriptor.
-// The loads of the next chunk are in flight, in registers, while the current one is multiplied.
+// kernel row share one read of x: the sum over ox of dy[ox] * x[ox+kx-1] is the sum over x's own columns ox' of
+// dy[ox'+1-kx] * x[ox'], so kx = 1 multiplies x with dy's group as it is, and kx = 0 / 2 with the same eight pixels of
+// dy moved by one with the first / last pixel of the neighbouring group (eight v_alignbyte_b32 per K step of nine
+// MFMAs).  Those neighbour words are staged a second time, 8 bytes per (row, group, filter) side by side over the
+// filters, so that dy is one 128-bit and one 64-bit read free of bank conflicts.  Zero padding is nothing but dy's
+// zero halo: columns beyond the image, rows beyond it, filters beyond F and channels beyond C are loads at an
+// offset outside the buffer descriptor.  The loads of the next chunk are in flight, in registers, while the current
+// one is multiplied.  (First version: the shifts on the x side, three per kernel row -- 24 vector instructions, seven
+// LDS reads and a dozen of address arithmetic per nine MFMAs, and the one wave a SIMD has here cannot issue that many
+// beside its MFMAs: 19 to 26 % of the matrix cores' rate.)
 //
 // The pixels are split over S workgroups per tile; each writes its 9 x 64 x 64 partial sums to the workspace, and a
 // second kernel adds the S parts in order for the kept weights only and writes them in the canonical entry order of
@@ -50,7 +56,8 @@ typedef unsigned uint2v __attribute__((ext_vector_type(2)));
 
 constexpr uint32_t kInvalid = 0x80000000u;
 constexpr int kPitch = 64 * 16 + 16;          // bytes from one (row, group) of a staged operand to the next
-constexpr int kMaxX = 14, kMaxD = 8;          // 16-byte pieces per thread and chunk, at most: x, dy
+constexpr int kPitchE = 64 * 8 + 8;           // the same for the neighbour words of dy (8 bytes per filter)
+constexpr int kMaxX = 12, kMaxD = 10;         // 16-byte pieces per thread and chunk, at most: x, dy
 constexpr int kTile = 64;
 
 struct GwParams {
@@ -58,7 +65,7 @@ struct GwParams {
     const unsigned char* dy;
     float* ws;
     int N, C, F, H, W;
-    int R, Gc, NJ;            // output rows and column groups per chunk; NJ = Gc + 2 staged groups of x
+    int R, Gc, NJ;            // output rows and column groups per chunk; NJ = Gc + 2 staged groups of dy
     int nrb, ncb;             // row blocks and column blocks per image
     int chunks;               // N * nrb * ncb
     int S;                    // workgroups per tile
@@ -104,32 +111,33 @@ __global__ __launch_bounds__(256, 1) void grad_weight_kernel(const GwParams p) {
     const int tile = (int)blockIdx.x / p.S, split = (int)blockIdx.x - tile * p.S;
     const int tf = tile / p.tiles_c, tc = tile - tf * p.tiles_c;
     const int R = p.R, Gc = p.Gc, NJ = p.NJ, H = p.H, W = p.W;
-    unsigned char* const dyL = lds;
-    unsigned char* const xL = lds + R * Gc * kPitch;
+    unsigned char* const dyL = lds;                               // [r][j < NJ][filter][8 pixels]
+    unsigned char* const eL = dyL + R * NJ * kPitch;              // [r][j][filter]{left neighbours, right neighbours}
+    unsigned char* const xL = eL + R * NJ * kPitchE;              // [r' < R + 2][g < Gc][channel][8 pixels]
 
     // ---- this thread's pieces of a chunk (the same for every chunk): where they go in LDS, and where they come
     // from relative to the chunk's first output row and column
-    int xl[kMaxX], xrel[kMaxX], xrj[kMaxX];      // xrj: row r' | group j << 8
-    int dl[kMaxD], drel[kMaxD], drg[kMaxD];
+    int xl[kMaxX], xrel[kMaxX], xrg[kMaxX];      // xrg: row r' | group g << 8
+    int dl[kMaxD], drel[kMaxD], drj[kMaxD];      // drj: row r | group j << 8
 #pragma unroll
     for (int i = 0; i < kMaxX; ++i) {
         const int idx = tid + i * 256;
-        const int j = idx % NJ, q = idx / NJ, c = q & 63, r = q >> 6;
+        const int g = idx % Gc, q = idx / Gc, c = q & 63, r = q >> 6;
         const int chan = tc * kTile + c;
         const bool ok = r < R + 2 && chan < p.C;
-        xl[i] = r < R + 2 ? (r * NJ + j) * kPitch + c * 16 : -1;
-        xrel[i] = ok ? (chan * H * W + (r - 1) * W + (j - 1) * 8) * 2 : (int)kInvalid;
-        xrj[i] = r | (j << 8);
+        xl[i] = r < R + 2 ? (r * Gc + g) * kPitch + c * 16 : -1;
+        xrel[i] = ok ? (chan * H * W + (r - 1) * W + g * 8) * 2 : (int)kInvalid;
+        xrg[i] = r | (g << 8);
     }
 #pragma unroll
     for (int i = 0; i < kMaxD; ++i) {
         const int idx = tid + i * 256;
-        const int g = idx % Gc, q = idx / Gc, f = q & 63, r = q >> 6;
+        const int j = idx % NJ, q = idx / NJ, f = q & 63, r = q >> 6;
         const int filt = tf * kTile + f;
         const bool ok = r < R && filt < p.F;
-        dl[i] = r < R ? (r * Gc + g) * kPitch + f * 16 : -1;
-        drel[i] = ok ? (filt * H * W + r * W + g * 8) * 2 : (int)kInvalid;
-        drg[i] = r | (g << 8);
+        dl[i] = r < R ? (r * NJ + j) * kPitch + f * 16 : -1;
+        drel[i] = ok ? (filt * H * W + r * W + (j - 1) * 8) * 2 : (int)kInvalid;
+        drj[i] = r | (j << 8);
     }
 
     uint4v xs[kMaxX], ds[kMaxD];
@@ -142,27 +150,25 @@ __global__ __launch_bounds__(256, 1) void grad_weight_kernel(const GwParams p) {
 #pragma unroll
         for (int i = 0; i < kMaxX; ++i) {
             if (i < p.npx) {
-                const int iy = oy0 + (xrj[i] & 255) - 1, col = col0 + ((xrj[i] >> 8) - 1) * 8;
+                const int iy = oy0 + (xrg[i] & 255) - 1, col = col0 + (xrg[i] >> 8) * 8;
                 const bool row_ok = xrel[i] != (int)kInvalid && iy >= 0 && iy < H;
                 uint32_t off[8 / LW];
 #pragma unroll
-                for (int u = 0; u < 8 / LW; ++u) {
-                    const int cc = col + u * LW;
-                    off[u] = (row_ok && cc >= 0 && cc < W) ? (uint32_t)(xrel[i] + shift + u * LW * 2) : kInvalid;
-                }
+                for (int u = 0; u < 8 / LW; ++u)
+                    off[u] = (row_ok && col + u * LW < W) ? (uint32_t)(xrel[i] + shift + u * LW * 2) : kInvalid;
                 xs[i] = load8<LW>(xr, off);
             }
         }
 #pragma unroll
         for (int i = 0; i < kMaxD; ++i) {
             if (i < p.npd) {
-                const int oy = oy0 + (drg[i] & 255), col = col0 + (drg[i] >> 8) * 8;
+                const int oy = oy0 + (drj[i] & 255), col = col0 + ((drj[i] >> 8) - 1) * 8;
                 const bool row_ok = drel[i] != (int)kInvalid && oy < H;
                 uint32_t off[8 / LW];
 #pragma unroll
                 for (int u = 0; u < 8 / LW; ++u) {
                     const int cc = col + u * LW;
-                    off[u] = (row_ok && cc < W) ? (uint32_t)(drel[i] + shift + u * LW * 2) : kInvalid;
+                    off[u] = (row_ok && cc >= 0 && cc < W) ? (uint32_t)(drel[i] + shift + u * LW * 2) : kInvalid;
                 }
                 ds[i] = load8<LW>(dr, off);
             }
@@ -174,7 +180,15 @@ __global__ __launch_bounds__(256, 1) void grad_weight_kernel(const GwParams p) {
             if (i < p.npx && xl[i] >= 0) *reinterpret_cast<uint4v*>(xL + xl[i]) = xs[i];
 #pragma unroll
         for (int i = 0; i < kMaxD; ++i)
-            if (i < p.npd && dl[i] >= 0) *reinterpret_cast<uint4v*>(dyL + dl[i]) = ds[i];
+            if (i < p.npd && dl[i] >= 0) {
+                *reinterpret_cast<uint4v*>(dyL + dl[i]) = ds[i];
+                // this piece's last two pixels are the left neighbours of the group to its right, its first two the
+                // right neighbours of the group to its left (only groups 1 .. Gc are ever multiplied)
+                const int j = drj[i] >> 8;
+                const int e = (dl[i] / kPitch) * kPitchE + ((dl[i] % kPitch) >> 1);
+                if (j < NJ - 1) *reinterpret_cast<unsigned*>(eL + e + kPitchE) = ds[i].w;
+                if (j >= 1) *reinterpret_cast<unsigned*>(eL + e - kPitchE + 4) = ds[i].x;
+            }
     };
 
     float16v acc[3][3];
@@ -187,6 +201,23 @@ __global__ __launch_bounds__(256, 1) void grad_weight_kernel(const GwParams p) {
 
     const int nk = R * Gc / 2;                  // K steps of 16 pixels per chunk (R*Gc is even)
     const int a_lane = (wf * 32 + li) * 16, b_lane = (wc * 32 + li) * 16;
+    // This half-wave's items are lk, lk + 2, ...; item = r*Gc + g.  x has no halo groups, so an item's x slot is the
+    // item number plus ky rows; its dy slot is r*NJ + g + 1, which skips the two halo groups at every row end.
+    const bool one_group = Gc == 1;             // (then every item is a row of its own: three dy slots per item)
+    const int a_slot0 = one_group ? lk * 3 + 1 : lk + 1;
+    const int row_b = Gc * kPitch;
+    struct RawA {
+        uint4v cur;
+        uint2v nb;
+    };
+    auto read_a = [&](int slot) {
+        RawA w;
+        w.cur = *reinterpret_cast<const uint4v*>(dyL + slot * kPitch + a_lane);
+        w.nb = *reinterpret_cast<const uint2v*>(eL + slot * kPitchE + (a_lane >> 1));
+        return w;
+    };
+    auto read_b = [&](int off, int ky) { return *reinterpret_cast<const half8*>(xL + off + ky * row_b); };
+
     int chunk = split;
     if (chunk < p.chunks) fetch(chunk);
     while (chunk < p.chunks) {
@@ -194,32 +225,50 @@ __global__ __launch_bounds__(256, 1) void grad_weight_kernel(const GwParams p) {
         __syncthreads();
         const int next = chunk + p.S;
         if (next < p.chunks) fetch(next);
-        // this half-wave's items: lk, lk + 2, ... (item = r*Gc + g)
-        int r = 0, g = lk;
-        while (g >= Gc) { g -= Gc; ++r; }
+        // The operands of a K step are requested one step ahead, each as soon as its registers are free, so the LDS
+        // has nine MFMAs' time to answer.  The shifts by one pixel are made on the dy side: the sum over ox of
+        // dy[ox] * x[ox + kx - 1] is the sum over x's own columns ox' of dy[ox' + 1 - kx] * x[ox'], so one read of x
+        // per kernel row serves its three taps, and dy is read once per step and moved left and right by one pixel
+        // with its neighbour words (eight v_alignbyte_b32 per nine MFMAs; with the shifts on the x side it was 24
+        // vector instructions per step, and a single wave per SIMD cannot issue that many beside its MFMAs).
+        int g = lk, a_slot = a_slot0, b_off = lk * kPitch + b_lane;
+        RawA ra = read_a(a_slot);
+        half8 b[3];
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) b[ky] = read_b(b_off, ky);
         for (int k = 0; k < nk; ++k) {
-            const half8 a = *reinterpret_cast<const half8*>(dyL + (r * Gc + g) * kPitch + a_lane);
+            // the items after these (behind the last: the first again, whose operands are read and not used)
+            g += 2;
+            const bool wrap = g >= Gc;
+            g = wrap ? g - Gc : g;
+            a_slot += one_group ? 6 : wrap ? 4 : 2;
+            b_off += 2 * kPitch;
+            if (k + 1 == nk) {
+                g = lk;
+                a_slot = a_slot0;
+                b_off = lk * kPitch + b_lane;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const uint4v cur = ra.cur;
+            const unsigned l0 = __builtin_amdgcn_alignbyte(cur.x, ra.nb.x, 2);
+            const unsigned l1 = __builtin_amdgcn_alignbyte(cur.y, cur.x, 2);
+            const unsigned l2 = __builtin_amdgcn_alignbyte(cur.z, cur.y, 2);
+            const unsigned l3 = __builtin_amdgcn_alignbyte(cur.w, cur.z, 2);
+            const unsigned r3 = __builtin_amdgcn_alignbyte(ra.nb.y, cur.w, 2);
+            const half8 a2 = __builtin_bit_cast(half8, uint4v{l0, l1, l2, l3});      // dy at column ox' - 1: tap kx = 2
+            const half8 a1 = __builtin_bit_cast(half8, cur);                          // ox': kx = 1
+            const half8 a0 = __builtin_bit_cast(half8, uint4v{l1, l2, l3, r3});      // ox' + 1: kx = 0
+            ra = read_a(a_slot);
 #pragma unroll
             for (int ky = 0; ky < 3; ++ky) {
-                const unsigned char* const base = xL + ((r + ky) * NJ + g + 1) * kPitch + b_lane;
-                const uint4v cur = *reinterpret_cast<const uint4v*>(base);
-                const unsigned prev = *reinterpret_cast<const unsigned*>(base - kPitch + 12);
-                const unsigned nxt = *reinterpret_cast<const unsigned*>(base + kPitch);
-                const unsigned l0 = __builtin_amdgcn_alignbyte(cur.x, prev, 2);
-                const unsigned l1 = __builtin_amdgcn_alignbyte(cur.y, cur.x, 2);
-                const unsigned l2 = __builtin_amdgcn_alignbyte(cur.z, cur.y, 2);
-                const unsigned l3 = __builtin_amdgcn_alignbyte(cur.w, cur.z, 2);
-                const unsigned r3 = __builtin_amdgcn_alignbyte(nxt, cur.w, 2);
-                const half8 b0 = __builtin_bit_cast(half8, uint4v{l0, l1, l2, l3});      // x at column ox - 1
-                const half8 b1 = __builtin_bit_cast(half8, cur);                          // ox
-                const half8 b2 = __builtin_bit_cast(half8, uint4v{l1, l2, l3, r3});      // ox + 1
-                acc[ky][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b0, acc[ky][0], 0, 0, 0);
-                acc[ky][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b1, acc[ky][1], 0, 0, 0);
-                acc[ky][2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b2, acc[ky][2], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                acc[ky][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b[ky], acc[ky][0], 0, 0, 0);
+                acc[ky][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b[ky], acc[ky][1], 0, 0, 0);
+                acc[ky][2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, b[ky], acc[ky][2], 0, 0, 0);
+                b[ky] = read_b(b_off, ky);
             }
-            g += 2;
-            while (g >= Gc) { g -= Gc; ++r; }
         }
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         chunk = next;
     }
@@ -273,8 +322,8 @@ bool plan(const pconv_packed* p, int N, int H, int W, GwParams* out, int* lw, si
     g.NJ = g.Gc + 2;
     // rows per chunk: even (a K step is two items), as many as the pieces per thread allow, evened out over the image
     int R = 2;
-    while (R + 2 <= 254 && ((R + 4) * g.NJ * 64 + 255) / 256 <= kMaxX && ((R + 2) * g.Gc * 64 + 255) / 256 <= kMaxD) R += 2;
-    if (((R + 2) * g.NJ * 64 + 255) / 256 > kMaxX || (R * g.Gc * 64 + 255) / 256 > kMaxD) return false;
+    while (R + 2 <= 254 && ((R + 4) * g.Gc * 64 + 255) / 256 <= kMaxX && ((R + 2) * g.NJ * 64 + 255) / 256 <= kMaxD) R += 2;
+    if (((R + 2) * g.Gc * 64 + 255) / 256 > kMaxX || (R * g.NJ * 64 + 255) / 256 > kMaxD) return false;
     int nrb = (H + R - 1) / R;
     R = std::min(R, ((H + nrb - 1) / nrb + 1) / 2 * 2);
     nrb = (H + R - 1) / R;
@@ -287,14 +336,14 @@ bool plan(const pconv_packed* p, int N, int H, int W, GwParams* out, int* lw, si
     g.tiles = g.tiles_c * ((p->F + kTile - 1) / kTile);
     const int cus = compute_units();
     g.S = (int)std::max<long long>(1, std::min<long long>(chunks, (cus + g.tiles - 1) / g.tiles));
-    g.npx = ((R + 2) * g.NJ * 64 + 255) / 256;
-    g.npd = (R * g.Gc * 64 + 255) / 256;
+    g.npx = ((R + 2) * g.Gc * 64 + 255) / 256;
+    g.npd = (R * g.NJ * 64 + 255) / 256;
     const unsigned long long ximg = (unsigned long long)p->C * H * W * 2ull, dimg = (unsigned long long)p->F * H * W * 2ull;
     if (ximg >= 0x7FFFFFFFull || dimg >= 0x7FFFFFFFull) return false;
     g.x_img_bytes = (unsigned)ximg;
     g.dy_img_bytes = (unsigned)dimg;
     *lw = W % 8 == 0 ? 8 : W % 4 == 0 ? 4 : W % 2 == 0 ? 2 : 1;
-    *lds = (size_t)(R * g.Gc + (R + 2) * g.NJ) * kPitch;
+    *lds = (size_t)(R * g.NJ + (R + 2) * g.Gc) * kPitch + (size_t)R * g.NJ * kPitchE;
     if (*lds > 160 * 1024) return false;
     *ws_floats = (size_t)g.S * g.tiles * 9 * kTile * kTile;
     *out = g;
