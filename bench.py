@@ -623,9 +623,11 @@ def backward_bench(args, torch, pc, L):
         torch.cuda.empty_cache()
     # the oracle on one image of the slowest layer, timed on the host
     spec, _, x1, g1 = worst
-    t0 = time.perf_counter()
-    oracle.conv3x3_grad_weight(x1, g1, 1, 1)
-    el = time.perf_counter() - t0
+    t0, runs = time.perf_counter(), 0
+    while time.perf_counter() - t0 < 10.0:
+        oracle.conv3x3_grad_weight(x1, g1, 1, 1)
+        runs += 1
+    el = (time.perf_counter() - t0) / runs
     out = {"metric": "executed TFLOP/s, masked weight gradient of VGG-16 3x3 layers", "value": flops_sum / tot_gw / 1e9,
            "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": tot_gw,
            "higher_is_better": True, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
@@ -636,7 +638,7 @@ def backward_bench(args, torch, pc, L):
            "grad_input_total_us": tot_gi * 1e3, "layers": rows,
            "cpu_baseline": {"value": 2.0 * spec.H * spec.W * 9 * spec.F * spec.C / el / 1e12, "unit": "TFLOP/s",
                             "cores": oracle.threads(), "kind": "oracle",
-                            "sample": f"dense weight gradient of one image of {spec.name}, {el:.1f} s"}}
+                            "sample": f"{runs} runs of the dense weight gradient of one image of {spec.name}, {el * runs:.1f} s"}}
     print(json.dumps(out), flush=True)
 
 
@@ -680,9 +682,11 @@ def conv1x1_bench(args, torch, pc, L):
             sample = (name, x1[:1], w, pid, mask, b)
         p.free()
     name, x1, w, pid, mask, b = sample
-    t0 = time.perf_counter()
-    oracle.conv1x1(x1, w, pid, mask, lib, b, 1, True)
-    el = time.perf_counter() - t0
+    t0, runs = time.perf_counter(), 0
+    while time.perf_counter() - t0 < 5.0:
+        oracle.conv1x1(x1, w, pid, mask, lib, b, 1, True)
+        runs += 1
+    el = (time.perf_counter() - t0) / runs
     kept = int(oracle.group_mask_1x1(pid, mask, lib, *w.shape).sum())
     out = {"metric": "algorithmic GB/s, ResNet-50 1x1 layers grouped into 3x3 patterns", "value": tot_bytes / tot_ms / 1e6,
            "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": tot_ms,
@@ -692,7 +696,7 @@ def conv1x1_bench(args, torch, pc, L):
                         "frac": tot_bytes / tot_ms / 1e6 / PEAK_HBM_GBS, "traffic": None, "kernel": "mfma_conv_kernel"},
            "layers": rows,
            "cpu_baseline": {"value": x1.shape[2] * x1.shape[3] * kept / el / 1e9, "unit": "effective GMAC/s", "cores": 1,
-                            "kind": "oracle", "sample": f"one image of {name}, {el:.2f} s"}}
+                            "kind": "oracle", "sample": f"{runs} runs of one image of {name}, {el * runs:.1f} s"}}
     print(json.dumps(out), flush=True)
 
 

@@ -25,9 +25,9 @@
 // LDS reads and a dozen of address arithmetic per nine MFMAs, and the one wave a SIMD has here cannot issue that many
 // beside its MFMAs: 19 to 26 % of the matrix cores' rate.)
 //
-// The pixels are split over S workgroups per tile; each writes its 9 x 64 x 64 partial sums to the workspace, and a
-// second kernel adds the S parts in order for the kept weights only and writes them in the canonical entry order of
-// the packed layer (deterministic: no atomics).
+// The pixels are split over S workgroups per tile; each writes its 9 x 64 x 64 partial sums to the workspace, a second
+// kernel adds the S parts in order, and a third gathers the sums of the kept weights into the canonical entry order
+// of the packed layer (deterministic: no atomics).
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -287,6 +287,22 @@ __global__ __launch_bounds__(256, 1) void grad_weight_kernel(const GwParams p) {
             }
 }
 
+// The S parts of every tile added into part 0, in order: a dense pass, four neighbouring sums per thread, so the parts
+// are read at the rate of a copy.  (Summed inside the gather below instead, one scattered 4-byte read per part and kept
+// weight, the parts of a layer with a single tile -- 256 of them -- took 90 us.)
+__global__ __launch_bounds__(256) void grad_weight_reduce_kernel(float* __restrict__ ws, long long n4, long long part4, int S,
+                                                                 int step, int cnt) {
+    // group blockIdx.y: parts (group*cnt + s)*step, s < cnt, as far as there are parts, added into the group's first
+    typedef float float4v __attribute__((ext_vector_type(4)));
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    float4v* const w4 = reinterpret_cast<float4v*>(ws);
+    const long long first = (long long)blockIdx.y * cnt * step;
+    float4v sum = w4[first * part4 + i];
+    for (int s = 1; s < cnt && first + (long long)s * step < S; ++s) sum += w4[(first + (long long)s * step) * part4 + i];
+    w4[first * part4 + i] = sum;
+}
+
 // dw4[e][q] = sum over the S parts, in order, of the partial sum of entry e's filter and channel at the q-th tap of
 // its pattern
 __global__ __launch_bounds__(256) void grad_weight_gather_kernel(const float* __restrict__ ws, const uint32_t* __restrict__ canon,
@@ -414,8 +430,23 @@ extern "C" int pconv_conv3x3_grad_weight(const void* x, const void* dy, const pc
     PCONV_GW_CASE(8) PCONV_GW_CASE(4) PCONV_GW_CASE(2) PCONV_GW_CASE(1)
 #undef PCONV_GW_CASE
     PCONV_HIP(hipGetLastError());
+    if (g.S > 1) {
+        const long long part4 = (long long)g.tiles * 9 * kTile * kTile / 4;
+        // (in two levels where there are many parts, so that the first level has workgroups enough: groups of 16
+        // consecutive parts, then the groups' sums; the order of the additions is fixed either way)
+        const unsigned blocks = (unsigned)((part4 + 255) / 256);
+        const int groups = g.S > 16 ? (g.S + 15) / 16 : 1;
+        if (groups > 1) {
+            hipLaunchKernelGGL(grad_weight_reduce_kernel, dim3(blocks, (unsigned)groups), dim3(256), 0, st,
+                               static_cast<float*>(workspace), part4, part4, g.S, 1, 16);
+            PCONV_HIP(hipGetLastError());
+        }
+        hipLaunchKernelGGL(grad_weight_reduce_kernel, dim3(blocks, 1u), dim3(256), 0, st, static_cast<float*>(workspace),
+                           part4, part4, g.S, groups > 1 ? 16 : 1, groups > 1 ? groups : g.S);
+        PCONV_HIP(hipGetLastError());
+    }
     hipLaunchKernelGGL(grad_weight_gather_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const float*>(workspace), p->d_canon, dw4, n4, g.S, g.tiles, g.tiles_c);
+                       static_cast<const float*>(workspace), p->d_canon, dw4, n4, 1, g.tiles, g.tiles_c);
     PCONV_HIP(hipGetLastError());
     return PCONV_OK;
 }

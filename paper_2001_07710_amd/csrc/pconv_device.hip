@@ -2244,7 +2244,9 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
             // 56x56 goes from 17 to 53 us in two parts.  The estimate carries both.  Not asked for, the choice is
             // between 1, 2 and, at stride 1, 4 parts: more lost on every shape measured.)
             for (int ks = 1; ks <= 16; ks *= 2) {
-                if (want_splits ? ks != want_splits : ks > (stride == 2 ? 2 : 4)) continue;
+                // (layers of one or two taps have channel blocks too short to hide their loads: more parts in flight)
+                const int most = a.n_taps <= 2 ? 16 : stride == 2 ? 2 : 4;
+                if (want_splits ? ks != want_splits : ks > most) continue;
                 const double t = mfma_estimate_us(a, sh, ks);
                 if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; a.splits = ks; }
             }
@@ -2255,7 +2257,9 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         }
         bool take = best_us >= 0.0 || forced;
         if (take && !forced) {
-            const double macs = (double)N * Ho * Wo * 4.0 * (double)wp->n_kept;
+            // (an entry of a 1x1 layer is one tap with the loop overhead of four: measured 3.1 entries per nanosecond
+            // against 5 for the 3x3 layers the rate below is quoted for)
+            const double macs = (double)N * Ho * Wo * (wp->is_1x1 ? 6.4 : 4.0) * (double)wp->n_kept;
             const double rate = stride == 2 ? 5e6 : Wo < 14 ? 10e6 : 20e6;      // multiply-adds per microsecond
             take = best_us < macs / rate + 8.0;
         }

@@ -1000,7 +1000,12 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     // (while the device is not full a block lasts as long as the loads of the next one take to come back: measured
     // on ResNet-50's layers at batch 32, per shape, stride 1 / stride 2 -- a wider tile stages more rows per block)
     static const double kFloorUs[kMfmaShapes][2] = {{2.8, 2.8}, {2.0, 2.7}, {1.9, 2.2}, {1.75, 1.85}};
-    const double floor_us = tiles <= resident ? kFloorUs[shape - 1][a.stride == 2 ? 1 : 0] : 0.0;
+    // (a layer of one or two taps -- a 1x1 layer is a layer of centre taps -- multiplies for a fraction of the time its
+    // next block's loads are under way, however full the device is: the round trip binds every block)
+    const bool few_taps = p.nt <= 2;
+    // (measured on the 1x1 layers of ResNet-50's bottlenecks at batch 32: 0.65 of the 3x3 layers' figure, whose blocks
+    // stage three rows of halo besides)
+    const double floor_us = (tiles <= resident || few_taps) ? kFloorUs[shape - 1][a.stride == 2 ? 1 : 0] * (few_taps ? 0.65 : 1.0) : 0.0;
     const double blocks = (double)((p.CB + p.KS - 1) / p.KS);
     // Time of one channel block of one tile with the device full, and of what a tile costs besides its blocks
     // (epilogue, descriptors), microseconds, fitted to the nine VGG-16 shapes at batch 64: two workgroups that share
@@ -1024,6 +1029,7 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
                               (kShapes[shape - 1].wn * kShapes[shape - 1].bf * 32) * 4.0;
     // (fitted to ResNet-50's 14 x 14 and 7 x 7 layers at batch 32 in 2, 4 and 8 parts)
     const double split_us = p.KS > 1 ? 4.0 + 1.5 * (p.KS - 1) + part_bytes / 1.8e6 : 0.0;
+    if (p.nt < 9) block_us *= (double)std::max(p.nt, 1) / 9.0;
     return rounds * (tile_us + blocks * std::max(block_us, floor_us)) + split_us;
 }
 
