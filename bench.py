@@ -175,6 +175,8 @@ def main():
                     help="backward pass of the nine VGG-16 shapes at batch 64: masked weight gradient and input gradient")
     ap.add_argument("--conv1x1", action="store_true",
                     help="the 1x1 convolutions of ResNet-50's bottlenecks at batch 32, grouped into 3x3 patterns")
+    ap.add_argument("--clustered", action="store_true",
+                    help="VGG-16 shapes with clustered connectivity: filters in their own order against similarity order")
     ap.add_argument("--layers", default="")
     ap.add_argument("--K", type=int, default=8)
     ap.add_argument("--keep", type=float, default=0.28)
@@ -204,6 +206,8 @@ def main():
         return peaks_bench(args, torch)
     if args.admm:
         return admm_bench(args, torch, pc, L)
+    if args.clustered:
+        return clustered_bench(args, torch, pc, L)
     if args.backward:
         return backward_bench(args, torch, pc, L)
     if args.conv1x1:
@@ -572,6 +576,70 @@ def admm_bench(args, torch, pc, L):
            "steps_table": rows,
            "cpu_baseline": {"value": m / el, "unit": "kernels/s", "cores": 1, "kind": "oracle",
                             "sample": f"the first {m} kernels, {el:.1f} s"}}
+    print(json.dumps(out), flush=True)
+
+
+def clustered_bench(args, torch, pc, L):
+    """What filter re-ordering buys on the matrix cores (pconv_filter_similarity_order + the channel lists of the
+    matrix-core kernel).  Config 4's shapes from conv2_2 on at batch 64, fp16, K and keep from the command line, but
+    with weights whose connectivity is clustered as in a trained, pruned model: filters in groups of 128 scattered
+    over the indices, each group keeping its kernels inside its own subset of 1.25 * keep of the input channels
+    (workloads.gen_clustered_weights; pattern assignment and top-k selection are the method's own steps, as always).
+    Each layer is timed packed in its own filter order and packed in similarity order."""
+    import oracle
+    st = torch.cuda.current_stream().cuda_stream
+    rows, t_nat, t_ord, macs = [], 0.0, 0.0, 0.0
+    sample = None
+    for spec in L.config4(args.K, args.keep, 64):
+        if spec.C < 128 or (args.only and spec.name != args.only):
+            continue
+        clusters = max(1, spec.F // 128)
+        if clusters < 2:
+            continue
+        w, _ = L.gen_clustered_weights(spec, clusters, min(1.0, 1.25 * spec.keep))
+        lib, w32 = spec.library(), None
+        w32 = w.astype(np.float32)
+        pid = pc.assign_patterns(w32, lib)
+        mask = pc.select_connectivity(w32, lib, pid, spec.keep)
+        t0 = time.perf_counter()
+        order = pc.filter_similarity_order(mask, 128)
+        order_ms = (time.perf_counter() - t0) * 1e3
+        base = L.gen_activations(spec, images=[0, 1, 2, 3])
+        dx = torch.from_numpy(np.concatenate([base] * (spec.N // 4), axis=0)).cuda()
+        bias = L.gen_bias(spec)
+        dy = torch.empty((spec.N, spec.F, spec.Ho, spec.Wo), dtype=torch.float16, device="cuda")
+        row = {"layer": spec.name, "C": spec.C, "F": spec.F, "H": spec.H, "n_kept": int(mask.sum()), "order_ms": order_ms}
+        for tag, o in (("own_order", np.arange(spec.F)), ("similarity_order", order)):
+            p = pc.pack(w[o], lib, pid[o], mask[o])
+            db = torch.from_numpy(bias[o]).cuda()
+            fn = lambda: pc.conv3x3(dx, dy, p, db, spec.N, spec.H, spec.W, 1, 1, pc.FLAG_RELU, st)
+            _, ms = time_launches(torch, fn, args.steps, args.warmup)
+            listed, dense = pc.packed_mfma_blocks(p, 128)
+            row[tag] = {"us": ms * 1e3, "blocks": listed, "of": dense,
+                        "eff_GMACs": effective_macs(spec, int(mask.sum())) / ms / 1e6}
+            p.free()
+        t_nat += row["own_order"]["us"]
+        t_ord += row["similarity_order"]["us"]
+        macs += effective_macs(spec, int(mask.sum()))
+        rows.append(row)
+        log(json.dumps(row))
+        if sample is None:
+            sample = (spec, base[:1], oracle.mask_weights(w, pid, mask, lib), bias)
+    spec, x1, wm, b = sample
+    t0, runs = time.perf_counter(), 0
+    while time.perf_counter() - t0 < 8.0:
+        oracle.conv3x3(x1, wm, b, 1, 1, True)
+        runs += 1
+    el = (time.perf_counter() - t0) / runs
+    out = {"metric": "effective GMAC/s (nonzero weights), VGG-16 3x3 layers with clustered connectivity, similarity order",
+           "value": macs / t_ord / 1e3, "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": t_ord * 1e-3, "higher_is_better": True, "dtype": "f16 storage, f32 accumulate",
+           "data": "synthetic", "config": {"workload": f"configs[4] shapes with 128 or more channels, batch 64, K={args.K}, "
+                                                       f"keep {args.keep}, clustered connectivity (groups of 128 filters)"},
+           "own_order_us": t_nat, "similarity_order_us": t_ord, "speedup": t_nat / t_ord, "layers": rows,
+           "cpu_baseline": {"value": effective_macs(spec, int((wm != 0).any(axis=(2, 3)).sum())) / spec.N / el / 1e9,
+                            "unit": "effective GMAC/s", "cores": oracle.threads(), "kind": "oracle",
+                            "sample": f"{runs} runs of one image of {spec.name}, {el * runs:.1f} s"}}
     print(json.dumps(out), flush=True)
 
 

@@ -132,6 +132,32 @@ int pconv_packed_balance(const pconv_packed* p, int waves, int filters_per_wave,
 int pconv_packed_parity_form(const pconv_packed* p, int pad, pconv_packed** out);
 int pconv_packed_library(const pconv_packed* p, uint16_t* lib_out);
 
+/*
+ * Filter re-ordering by similarity (section 6.2 of the paper: filters with similar kernels are grouped together so that
+ * a group's work is compact and regular).  On this chip the unit that matters is the tile of `group` consecutive
+ * filters that one workgroup computes (128 or 64 for fp16 storage, 32 or 16 for fp32): a tile only stages the input
+ * channels that some filter of it keeps, so filters that keep the same channels belong into one tile.  This returns
+ * an order of the filters, group after group of `group` filters: a group starts with the not yet placed filter that
+ * keeps the most kernels (lowest index among equals) and then takes, one at a time, the filter that adds the fewest
+ * channels to the union of the group's kept channels (among equals the one that shares the most channels with it,
+ * then the lowest index).  The caller applies it: row order_out[i] of weights, pattern ids and mask becomes filter i
+ * of the layer it packs, output channel i of that layer is the original filter order_out[i] (a renaming that the
+ * next layer's input channels absorb, as in the paper's compiler).  Host only; O(F^2 C / 64).
+ *   mask       host, uint8[F*C], 1 = kept
+ *   order_out  host, uint32[F]: a permutation of 0..F-1
+ */
+int pconv_filter_similarity_order(const uint8_t* mask, int F, int C, int group, uint32_t* order_out);
+
+/*
+ * Introspection of the matrix-core path (fp16 storage).  A workgroup tile of `tile_filters` (128 or 64) filters takes
+ * the input channels in blocks of 16.  Where the filters of the layer's tiles keep only part of the channels, pconv_pack
+ * gives every tile the list of the channels it keeps, and the kernel stages and multiplies those blocks only:
+ * listed_blocks is the number of blocks over all tiles that are multiplied, all_blocks = tiles * ceil(C / 16) what
+ * it would be without lists (equal when the layer has none: lists are made where they save a tenth or more).
+ * PCONV_EUNSUPPORTED for fp32 storage or another tile height.
+ */
+int pconv_packed_mfma_blocks(const pconv_packed* p, int tile_filters, int* listed_blocks, int* all_blocks);
+
 /* Releases host and device memory of a handle (NULL is allowed).  The caller makes sure no launch still uses it. */
 void pconv_free(pconv_packed* p);
 

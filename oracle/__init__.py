@@ -20,8 +20,8 @@ from .backward_oracle import (  # noqa: F401
     conv1x1, conv3x3_grad_input, conv3x3_grad_weight, conv3x3_grad_weight_at, group_mask_1x1, masked_grad_weight,
 )
 from .pattern_oracle import (  # noqa: F401
-    assign_patterns, library_bits, mask_weights, pack_canonical, retained_energy, select_connectivity,
-    unpack_canonical,
+    assign_patterns, filter_similarity_order, library_bits, mask_weights, pack_canonical, retained_energy,
+    select_connectivity, unpack_canonical,
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -129,3 +129,32 @@ def unpack_canonical(filter_order, grp_ptr, cin, w4, lib, F: int, C: int) -> np.
             for e in range(a, b):
                 out[f, int(cin[e]), taps] = w4[e]
     return out.reshape(F, C, 3, 3)
+
+
+def filter_similarity_order(mask, group: int) -> np.ndarray:
+    """Filter re-ordering by similarity (the grouping of similar filters of section 6.2, made concrete as a greedy
+    rule): groups of `group` filters; a group starts with the unplaced filter that keeps the most kernels (lowest
+    index among equals) and takes, one at a time, the unplaced filter that adds the fewest channels to the union of the
+    group's kept channels, among equals the one sharing the most channels with that union, then the lowest index."""
+    keep = np.asarray(mask) != 0
+    F = keep.shape[0]
+    counts = keep.sum(axis=1).astype(np.int64)
+    free = np.ones(F, dtype=bool)
+    order = []
+    while len(order) < F:
+        cand = np.nonzero(free)[0]
+        seed = int(cand[np.argmax(counts[cand])])           # argmax returns the first (lowest index) of equals
+        free[seed] = False
+        order.append(seed)
+        union = keep[seed].copy()
+        for _ in range(1, group):
+            cand = np.nonzero(free)[0]
+            if cand.size == 0:
+                break
+            add = (keep[cand] & ~union).sum(axis=1).astype(np.int64)
+            share = (keep[cand] & union).sum(axis=1).astype(np.int64)
+            best = int(cand[np.lexsort((cand, -share, add))[0]])
+            free[best] = False
+            order.append(best)
+            union |= keep[best]
+    return np.asarray(order, dtype=np.uint32)

@@ -101,6 +101,10 @@ def _load():
     for name in ("pconv_packed_transpose", "pconv_conv3x3_grad_input", "pconv_conv3x3_grad_weight_workspace",
                  "pconv_conv3x3_grad_weight", "pconv_pack_1x1", "pconv_conv1x1"):
         getattr(lib, name).restype = i
+    lib.pconv_filter_similarity_order.argtypes = [vp, i, i, i, vp]
+    lib.pconv_filter_similarity_order.restype = i
+    lib.pconv_packed_mfma_blocks.argtypes = [vp, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+    lib.pconv_packed_mfma_blocks.restype = i
     lib.pconv_strerror.argtypes = [i]
     lib.pconv_strerror.restype = ctypes.c_char_p
     lib.pconv_last_hip_error.argtypes = []
@@ -385,3 +389,19 @@ def pack_1x1(w_fc, lib, pid, mask, flags: int = 0) -> Packed:
 def conv1x1(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, flags: int = 0, stream: int = 0):
     _check(_load().pconv_conv1x1(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, flags, stream or None),
            "pconv_conv1x1")
+
+
+def filter_similarity_order(mask, group: int) -> np.ndarray:
+    mk = _host(mask, np.uint8)
+    F, C = mk.shape
+    out = np.empty(F, dtype=np.uint32)
+    _check(_load().pconv_filter_similarity_order(_hp(mk), F, C, int(group), _hp(out)), "pconv_filter_similarity_order")
+    return out
+
+
+def packed_mfma_blocks(p: Packed, tile_filters: int):
+    """(channel blocks that the matrix-core kernel multiplies over all filter tiles, what it would be without lists)."""
+    a, b = ctypes.c_int(), ctypes.c_int()
+    _check(_load().pconv_packed_mfma_blocks(p.handle, int(tile_filters), ctypes.byref(a), ctypes.byref(b)),
+           "pconv_packed_mfma_blocks")
+    return a.value, b.value

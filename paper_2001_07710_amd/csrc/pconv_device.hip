@@ -76,6 +76,12 @@ int upload_packed(pconv_packed* p) {
     for (MfmaWeights& m : p->mfma) {
         PCONV_HIP(hipMalloc(&m.d_w, std::max<size_t>(m.bytes(), 16)));
         if (m.bytes()) PCONV_HIP(hipMemcpy(m.d_w, m.w.data(), m.bytes(), hipMemcpyHostToDevice));
+        if (!m.clist.empty()) {
+            PCONV_HIP(hipMalloc((void**)&m.d_clist, m.clist.size() * sizeof(uint32_t)));
+            PCONV_HIP(hipMemcpy(m.d_clist, m.clist.data(), m.clist.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+            PCONV_HIP(hipMalloc((void**)&m.d_tinfo, m.tinfo.size() * sizeof(uint32_t)));
+            PCONV_HIP(hipMemcpy(m.d_tinfo, m.tinfo.data(), m.tinfo.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+        }
     }
     p->device = dev;
     return PCONV_OK;
@@ -84,7 +90,11 @@ int upload_packed(pconv_packed* p) {
 void release_device(pconv_packed* p) {
     for (MfmaWeights& m : p->mfma) {
         if (m.d_w) (void)hipFree(m.d_w);
+        if (m.d_clist) (void)hipFree(m.d_clist);
+        if (m.d_tinfo) (void)hipFree(m.d_tinfo);
         m.d_w = nullptr;
+        m.d_clist = nullptr;
+        m.d_tinfo = nullptr;
     }
     if (p->d_canon) (void)hipFree(p->d_canon);
     p->d_canon = nullptr;
@@ -2247,6 +2257,12 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
                 // (layers of one or two taps have channel blocks too short to hide their loads: more parts in flight)
                 const int most = a.n_taps <= 2 ? 16 : stride == 2 ? 2 : 4;
                 if (want_splits ? ks != want_splits : ks > most) continue;
+                // (the weights kept for this shape's tile height say whether its tiles have channel lists)
+                for (const MfmaWeights& m : wp->mfma)
+                    if (m.mt == mfma_shape_height(sh)) {
+                        a.d_clist = m.d_clist; a.d_tinfo = m.d_tinfo;
+                        a.min_blocks = m.min_blocks; a.total_blocks = m.total_blocks;
+                    }
                 const double t = mfma_estimate_us(a, sh, ks);
                 if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; a.splits = ks; }
             }
@@ -2273,6 +2289,8 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
             for (const MfmaWeights& m : wp->mfma) {
                 if (!m.d_w || m.mt != mfma_shape_height(a.shape)) continue;
                 a.d_w = m.d_w; a.mt = m.mt; a.n_taps = m.n_taps;
+                a.d_clist = m.d_clist; a.d_tinfo = m.d_tinfo;
+                a.min_blocks = m.min_blocks; a.total_blocks = m.total_blocks; a.w_bytes = m.bytes();
                 std::memcpy(a.taps, m.taps, sizeof(a.taps));
                 if (a.splits > 1) {
                     size_t floats = 0, counters = 0;

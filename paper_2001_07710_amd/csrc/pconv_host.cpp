@@ -262,7 +262,51 @@ void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) 
         }
     }
     const int nt = out->n_taps;
-    out->w.assign((size_t)out->n_mtiles * out->n_cblocks * nt * 2 * mt * 8, 0);
+    // Channels that the filters of every tile keep.  Lists are made where they save at least a tenth of the blocks;
+    // otherwise every tile takes all channels in their own order.
+    std::vector<std::vector<uint8_t>> used((size_t)out->n_mtiles, std::vector<uint8_t>((size_t)C, 0));
+    for (int i = 0; i < F; ++i) {
+        const uint32_t f = p->filter_order[(size_t)i];
+        for (uint32_t e = p->grp_ptr[(size_t)i * K]; e < p->grp_ptr[(size_t)(i + 1) * K]; ++e)
+            used[f / (uint32_t)mt][p->cin[e]] = 1;
+    }
+    std::vector<std::vector<uint32_t>> pos_of((size_t)out->n_mtiles);     // with lists: position of a channel in its tile
+    std::vector<size_t> first_block((size_t)out->n_mtiles, 0);
+    size_t listed = 0;
+    for (int t = 0; t < out->n_mtiles; ++t) {
+        size_t n = 0;
+        for (int c = 0; c < C; ++c) n += used[(size_t)t][(size_t)c];
+        listed += std::max<size_t>(1, (n + 15) / 16);
+    }
+    const bool lists = listed * 10 <= (size_t)out->n_mtiles * out->n_cblocks * 9;
+    out->clist.clear();
+    out->tinfo.clear();
+    out->min_blocks = out->n_cblocks;
+    out->total_blocks = out->n_mtiles * out->n_cblocks;
+    if (lists) {
+        out->min_blocks = 1 << 30;
+        size_t at_block = 0;
+        for (int t = 0; t < out->n_mtiles; ++t) {
+            pos_of[(size_t)t].assign((size_t)C, 0);
+            size_t n = 0;
+            for (int c = 0; c < C; ++c)
+                if (used[(size_t)t][(size_t)c]) {
+                    pos_of[(size_t)t][(size_t)c] = (uint32_t)n++;
+                    out->clist.push_back((uint32_t)c);
+                }
+            const size_t nb = std::max<size_t>(1, (n + 15) / 16);
+            out->clist.resize((at_block + nb) * 16, pconv::kNoChannel);
+            out->tinfo.push_back((uint32_t)nb);
+            out->tinfo.push_back((uint32_t)at_block);
+            first_block[(size_t)t] = at_block;
+            out->min_blocks = std::min(out->min_blocks, (int)nb);
+            at_block += nb;
+        }
+        out->total_blocks = (int)at_block;
+    } else {
+        for (int t = 0; t < out->n_mtiles; ++t) first_block[(size_t)t] = (size_t)t * out->n_cblocks;
+    }
+    out->w.assign((size_t)out->total_blocks * nt * 2 * mt * 8, 0);
     for (int i = 0; i < F; ++i) {
         const uint32_t f = p->filter_order[(size_t)i];
         const size_t tile = f / (uint32_t)mt, fl = f % (uint32_t)mt;
@@ -271,10 +315,11 @@ void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) 
             for (int t = 0; t < 9; ++t)
                 if ((p->lib[(size_t)j] >> t) & 1u) taps[q++] = t;
             for (uint32_t e = p->grp_ptr[(size_t)i * K + j]; e < p->grp_ptr[(size_t)i * K + j + 1]; ++e) {
-                const size_t c = p->cin[e], cb = c / 16, kb = (c % 16) / 8, c8 = c % 8;
+                const size_t c = lists ? pos_of[tile][p->cin[e]] : p->cin[e];      // position among the tile's channels
+                const size_t cb = c / 16, kb = (c % 16) / 8, c8 = c % 8;
                 for (int k = 0; k < q; ++k) {
                     const size_t ts = (size_t)slot_of[taps[k]];
-                    const size_t at = ((((tile * out->n_cblocks + cb) * nt + ts) * 2 + kb) * mt + fl) * 8 + c8;
+                    const size_t at = ((((first_block[tile] + cb) * nt + ts) * 2 + kb) * mt + fl) * 8 + c8;
                     std::memcpy(&out->w[at], &p->w4[((size_t)e * 4 + k) * 2], 2);
                 }
             }
@@ -572,6 +617,74 @@ int pconv::derive_for_stride2(const pconv_packed* p, int pad, bool upload, pconv
     } catch (const std::bad_alloc&) {
         return PCONV_ENOMEM;
     }
+}
+
+extern "C" int pconv_filter_similarity_order(const uint8_t* mask, int F, int C, int group, uint32_t* order_out) {
+    if (!mask || !order_out) return PCONV_EINVAL;
+    if (int rc = check_fc(F, C)) return rc;
+    if (group < 1) return PCONV_EINVAL;
+    try {
+        // the channels every filter keeps, as bit sets
+        const size_t words = ((size_t)C + 63) / 64;
+        std::vector<uint64_t> support((size_t)F * words, 0);
+        std::vector<uint32_t> count((size_t)F, 0);
+        for (int f = 0; f < F; ++f)
+            for (int c = 0; c < C; ++c)
+                if (mask[(size_t)f * C + c]) {
+                    support[(size_t)f * words + (size_t)c / 64] |= 1ull << (c % 64);
+                    ++count[(size_t)f];
+                }
+        std::vector<char> taken((size_t)F, 0);
+        std::vector<uint64_t> uni(words);
+        int placed = 0;
+        while (placed < F) {
+            // a group starts with the filter that keeps the most kernels (lowest index among equals) ...
+            int seed = -1;
+            for (int f = 0; f < F; ++f)
+                if (!taken[(size_t)f] && (seed < 0 || count[(size_t)f] > count[(size_t)seed])) seed = f;
+            taken[(size_t)seed] = 1;
+            order_out[placed++] = (uint32_t)seed;
+            std::copy(support.begin() + (size_t)seed * words, support.begin() + (size_t)(seed + 1) * words, uni.begin());
+            // ... and takes, one at a time, the filter that adds the fewest channels to the group's union; among
+            // equals the one that shares the most with it, then the lowest index
+            for (int k = 1; k < group && placed < F; ++k) {
+                int best = -1;
+                uint32_t best_add = 0, best_share = 0;
+                for (int f = 0; f < F; ++f) {
+                    if (taken[(size_t)f]) continue;
+                    uint32_t add = 0, share = 0;
+                    const uint64_t* sf = &support[(size_t)f * words];
+                    for (size_t w = 0; w < words; ++w) {
+                        add += (uint32_t)__builtin_popcountll(sf[w] & ~uni[w]);
+                        share += (uint32_t)__builtin_popcountll(sf[w] & uni[w]);
+                    }
+                    if (best < 0 || add < best_add || (add == best_add && share > best_share)) {
+                        best = f;
+                        best_add = add;
+                        best_share = share;
+                    }
+                }
+                taken[(size_t)best] = 1;
+                order_out[placed++] = (uint32_t)best;
+                const uint64_t* sb = &support[(size_t)best * words];
+                for (size_t w = 0; w < words; ++w) uni[w] |= sb[w];
+            }
+        }
+    } catch (const std::bad_alloc&) {
+        return PCONV_ENOMEM;
+    }
+    return PCONV_OK;
+}
+
+extern "C" int pconv_packed_mfma_blocks(const pconv_packed* p, int tile_filters, int* listed_blocks, int* all_blocks) {
+    if (!p) return PCONV_EINVAL;
+    for (const pconv::MfmaWeights& m : p->mfma)
+        if (m.mt == tile_filters) {
+            if (listed_blocks) *listed_blocks = m.total_blocks;
+            if (all_blocks) *all_blocks = m.n_mtiles * m.n_cblocks;
+            return PCONV_OK;
+        }
+    return PCONV_EUNSUPPORTED;
 }
 
 extern "C" int pconv_packed_parity_form(const pconv_packed* p, int pad, pconv_packed** out) {

@@ -60,6 +60,18 @@ struct MfmaWeights {
     std::vector<uint16_t> w;          // host copy (fp16 bit patterns)
     void* d_w = nullptr;
     size_t bytes() const { return w.size() * sizeof(uint16_t); }
+    // Channel lists (empty: every filter tile takes the channels in their own order, n_cblocks blocks each).  Where
+    // the filters of a tile keep only part of the input channels -- connectivity pruning that removes the same
+    // channels for similar filters, and filters ordered so that similar ones share a tile -- the tile's blocks are
+    // made of the channels it keeps, ascending, 16 per block, the last padded with kNoChannel (zero weights; the
+    // kernel loads nothing for it): tile t has tinfo[2t] blocks, the first of them block tinfo[2t+1] of `clist`
+    // and of the weights, which are stored for the listed blocks only.  This is the compact, re-ordered kernel
+    // storage of section 6.2 of the paper at the granularity the matrix cores work at.
+    std::vector<uint32_t> clist;      // [total blocks][16] channel of every position
+    std::vector<uint32_t> tinfo;      // [n_mtiles][2]
+    int min_blocks = 0, total_blocks = 0;
+    uint32_t* d_clist = nullptr;
+    uint32_t* d_tinfo = nullptr;
 };
 
 }  // namespace pconv
@@ -123,6 +135,10 @@ struct MfmaConv {
     void* y;
     const float* bias;          // device, or null
     const void* d_w;            // MfmaWeights::d_w
+    const uint32_t* d_clist;    // MfmaWeights::d_clist, d_tinfo: null where the tiles take the channels in their own order
+    const uint32_t* d_tinfo;
+    int min_blocks, total_blocks;   // with channel lists: the fewest blocks any tile has, and all of them
+    size_t w_bytes;             // bytes of the weights at d_w
     int mt, n_taps;
     uint8_t taps[9];
     int N, C, F, H, W, Ho, Wo, stride, pad, relu;

@@ -44,6 +44,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 
@@ -99,6 +100,8 @@ struct MfmaParams {
     unsigned char* y;
     const float* bias;
     const unsigned char* wq;
+    const unsigned* clist;  // null: every filter tile takes the channels in their own order, CB blocks.  Else the channels
+    const unsigned* tinfo;  // of every block of every tile (16 each, kNoChannel = none), and per tile {blocks, first block}
     int N, C, F, H, W, Ho, Wo, stride, pad, relu;
     int CB;                 // channel blocks of 16
     int nt;                 // tap slots
@@ -175,7 +178,8 @@ __device__ __forceinline__ unsigned interleave(unsigned a, unsigned b, int px) {
 // Geometry of one tile (all wave-uniform): the m-tile, and the R consecutive output rows of the batch it covers.
 struct TileGeo {
     int tile, split;   // the tile and, if its channel blocks are split over several workgroups, which part
-    int cb0, cb1;      // the channel blocks of this part
+    int cb0, cb1;      // the channel blocks of this part (positions in the tile's list of blocks)
+    int wb;            // the tile's first block in the weights (and in the channel list)
     int tm;            // which MT filters
     int Rv;            // output rows in the tile (the last tile of the batch may have fewer than R)
     int n0, oy0;       // image and row of its first output row
@@ -230,10 +234,16 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         const unsigned T = fastdiv(item, p.div_KS);
         g.tile = (int)T;
         g.split = (int)(item - T * (unsigned)p.KS);
-        g.cb0 = g.split * p.CB / p.KS;
-        g.cb1 = (g.split + 1) * p.CB / p.KS;
         const unsigned tn = fastdiv(T, p.div_tiles_m);
         g.tm = (int)(T - tn * (unsigned)p.tiles_m);
+        int blocks = p.CB;
+        g.wb = g.tm * p.CB;
+        if (p.clist) {
+            blocks = (int)__builtin_amdgcn_readfirstlane(p.tinfo[2 * g.tm]);
+            g.wb = (int)__builtin_amdgcn_readfirstlane(p.tinfo[2 * g.tm + 1]);
+        }
+        g.cb0 = g.split * blocks / p.KS;
+        g.cb1 = (g.split + 1) * blocks / p.KS;
         const int R0 = (int)tn * p.R;
         g.Rv = min(p.R, p.N * Ho - R0);
         g.n0 = (int)fastdiv((unsigned)R0, p.div_Ho);
@@ -281,7 +291,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     const int ltid = tid - kbs * HALF;
     uint32_t goff[kItems];
     int loff[kItems];
-    int stage_tm = 0;
+    int stage_wb = 0;                                           // first block of the tile being loaded, in the weights
     bool stage_on = true;                                       // false: nothing left to load (offsets outside)
     bool weights_on = true;                                     // false: the only block of weights is in LDS for good
     // (the descriptor of x is put together where it is used, from three scalars that are marked wave-uniform: as a
@@ -290,7 +300,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     unsigned xb_lo = 0, xb_hi = 0, x_records = 0;
     const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.wq_bytes);
     auto stage_descriptors = [&](const TileGeo& g) {
-        stage_tm = g.tm;
+        stage_wb = g.wb;
         const float inv_slots = 1.0f / (float)g.used_slots;
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
@@ -339,17 +349,28 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     // LDS (buffer_load ... lds: lane l's 16 bytes land at the wave's base + 16*l, no registers in between); the
     // buffer is free from the barrier that ended the block before the current one.
     constexpr int NLOADS = 8 * kItems + WPIECES;
+    // The eight channels of block `cb` that this wave stages: consecutive ones, or (channel lists) whichever the
+    // tile's list names at that place -- kNoChannel, beyond any C, where the list's last block is not full.
+    int chans[8];
+    auto block_channels = [&](int cb) {
+#pragma unroll
+        for (int ch = 0; ch < 8; ++ch) {
+            chans[ch] = cb * 16 + kbs * 8 + ch;
+            if (p.clist) chans[ch] = (int)__builtin_amdgcn_readfirstlane(p.clist[(stage_wb + cb) * 16 + kbs * 8 + ch]);
+        }
+    };
     auto issue_one = [&](int cb, int buf, int j) {
         if (j < 8 * kItems) {
             const int i = j >> 3, ch = j & 7;
-            const int chan = cb * 16 + kbs * 8 + ch;
+            const unsigned chan = (unsigned)chans[ch];
             const __amdgpu_buffer_rsrc_t xr =
                 make_rsrc(reinterpret_cast<const void*>(((unsigned long long)xb_hi << 32) | xb_lo), x_records);
-            stg[i][ch].load(xr, (chan < p.C && stage_on) ? goff[i] : kInvalid, (uint32_t)chan * p.chan_bytes);
+            stg[i][ch].load(xr, (chan < (unsigned)p.C && stage_on) ? goff[i] : kInvalid,
+                            chan < (unsigned)p.C ? chan * p.chan_bytes : 0u);
         } else {
             const int first = ((j - 8 * kItems) * NW + wave) * 64;        // the wave's first piece (uniform)
             if (first < w_pieces && stage_on && weights_on) {
-                const uint32_t wsoff = (uint32_t)((stage_tm * p.CB + cb) * p.a_bytes);
+                const uint32_t wsoff = (uint32_t)((stage_wb + cb) * p.a_bytes);
                 const int abuf = a_stages == 2 ? buf : 0;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_ptr)(ldsA + abuf * p.a_bytes + first * 16), 16,
                                                          (first + lane) * 16, (int)wsoff, 0, 0);
@@ -644,6 +665,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     TileGeo gc = geometry(T);
     stage_descriptors(gc);
     stage_bias(gc.tm, 0);
+    block_channels(gc.cb0);
 #pragma unroll
     for (int j = 0; j < NLOADS; ++j) issue_one(gc.cb0, 0, j);
     if (a_stages == 1) weights_on = false;
@@ -671,6 +693,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
                     ncb = gc.cb0;
                 }
             }
+            block_channels(ncb);
             const unsigned char* const a = ldsA + (a_stages == 2 ? buf : 0) * p.a_bytes + aoff;
             const unsigned char* const b = ldsB + (b_stages == 2 ? buf : 0) * 2 * p.plane_bytes;
             auto load_a = [&](int ts, int af) {
@@ -844,8 +867,11 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.N = a.N; p.C = a.C; p.F = a.F; p.H = a.H; p.W = a.W; p.Ho = a.Ho; p.Wo = a.Wo;
     p.stride = a.stride; p.pad = a.pad; p.relu = a.relu;
     p.CB = (a.C + 15) / 16;
+    p.clist = a.d_clist;
+    p.tinfo = a.d_tinfo;
     p.KS = a.splits < 1 ? 1 : a.splits;
-    if (p.KS > p.CB || p.KS > 64) return false;
+    // (every part of a split tile has at least one block: the sequence of (tile, block) pairs has no empty member)
+    if (p.KS > (a.d_clist ? a.min_blocks : p.CB) || p.KS > 64) return false;
     p.div_KS = make_fastdiv((unsigned)p.KS);
     p.ws = a.ws;
     p.counters = a.counters;
@@ -931,7 +957,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.img_bytes = (unsigned)img;
     p.y_bytes = (unsigned long long)a.N * a.F * a.Ho * a.Wo * 2ull;
     if ((unsigned long long)a.F * a.Ho * a.Wo * 2ull * (unsigned long long)(segs + 1) >= 0x7FFFFFFFull) return false;
-    const size_t wq_bytes = mfma_weight_bytes(a.F, a.C, MT, p.nt);
+    const size_t wq_bytes = a.d_clist ? a.w_bytes : mfma_weight_bytes(a.F, a.C, MT, p.nt);
     if (wq_bytes >= 0x7FFFFFFFull) return false;
     p.wq_bytes = (unsigned)wq_bytes;
     p.div_Wo = make_fastdiv((unsigned)a.Wo);
@@ -1006,7 +1032,9 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     // (measured on the 1x1 layers of ResNet-50's bottlenecks at batch 32: 0.65 of the 3x3 layers' figure, whose blocks
     // stage three rows of halo besides)
     const double floor_us = (tiles <= resident || few_taps) ? kFloorUs[shape - 1][a.stride == 2 ? 1 : 0] * (few_taps ? 0.65 : 1.0) : 0.0;
-    const double blocks = (double)((p.CB + p.KS - 1) / p.KS);
+    // (with channel lists: the mean number of blocks of a tile)
+    const double all_blocks = a.d_clist ? (double)a.total_blocks / std::max(1, p.tiles_m) : (double)p.CB;
+    const double blocks = std::ceil(all_blocks / p.KS);
     // Time of one channel block of one tile with the device full, and of what a tile costs besides its blocks
     // (epilogue, descriptors), microseconds, fitted to the nine VGG-16 shapes at batch 64: two workgroups that share
     // a compute unit take turns on its matrix cores, so each one's block lasts longer; rows of fewer than 56 pixels

@@ -99,6 +99,30 @@ def gen_weights(s: LayerSpec) -> np.ndarray:
     return w.astype(s.np_dtype).reshape(s.F, s.C, 3, 3)
 
 
+KIND_CLUSTER = 6
+
+
+def gen_clustered_weights(s: LayerSpec, clusters: int, share: float, damp: float = 0.05) -> np.ndarray:
+    """Weights with the connectivity structure of a trained, pruned model rather than of a random draw: every filter
+    belongs to one of `clusters` groups (seeded, scattered over the filter indices, equal sizes), every group has its
+    own seeded subset of share*C input channels, and a filter's kernels on channels outside its group's subset are
+    scaled by `damp` -- so that selection by kernel norm keeps, for similar filters, the same channels.  Same
+    distribution otherwise as gen_weights.  Returns (weights, group of every filter)."""
+    w = gen_weights(s).astype(np.float32)
+    seed = rng.stream_seed(s.cfg, s.idx, KIND_CLUSTER)
+    filters = rng.shuffle(seed, list(range(s.F)))
+    group = np.empty(s.F, dtype=np.int64)
+    for pos, f in enumerate(filters):
+        group[f] = pos * clusters // s.F
+    n_in = max(1, int(round(share * s.C)))
+    for g in range(clusters):
+        inside = np.zeros(s.C, dtype=bool)
+        inside[rng.shuffle(rng.stream_seed(s.cfg, s.idx, KIND_CLUSTER, g + 1), list(range(s.C)))[:n_in]] = True
+        rows = np.nonzero(group == g)[0]
+        w[np.ix_(rows, np.nonzero(~inside)[0])] *= damp
+    return w.astype(s.np_dtype), group
+
+
 def gen_bias(s: LayerSpec) -> np.ndarray:
     """[F] fp32, N(0, 0.01) (variance, so sigma = 0.1)."""
     z = rng.normal(rng.stream_seed(s.cfg, s.idx, KIND_B), s.F)
