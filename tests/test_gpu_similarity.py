@@ -91,3 +91,40 @@ def test_clustered_layer_in_similarity_order(case):
         assert np.all(got_nat[:, :5] == np.maximum(bias[:5], 0).astype(np.float16)[None, :, None, None])
     natural.free()
     packed.free()
+
+
+def test_transposed_and_non_allocating_calls_on_a_layer_with_channel_lists():
+    # the input gradient of a clustered layer runs on its transposed layer, whose tiles (of the original channels) have
+    # lists of their own or none; the entry point that allocates nothing takes a layer with lists like any other
+    import torch
+    spec = L.LayerSpec(cfg=41, idx=9, name="clustered", N=2, C=128, F=256, H=14, W=14, dtype="f16", K=8, keep=0.24)
+    w, _ = L.gen_clustered_weights(spec, 4, 0.30)
+    lib, w32 = spec.library(), w.astype(np.float32)
+    pid = pc.assign_patterns(w32, lib)
+    mask = pc.select_connectivity(w32, lib, pid, spec.keep)
+    order = pc.filter_similarity_order(mask, 64)
+    wo, po, mo = w[order], pid[order], mask[order]
+    packed = pc.pack(wo, lib, po, mo)
+    assert pc.packed_mfma_blocks(packed, 64)[0] < pc.packed_mfma_blocks(packed, 64)[1]
+    wm = oracle.mask_weights(wo, po, mo, lib)
+    st = torch.cuda.current_stream().cuda_stream
+    # input gradient
+    dy = np.random.default_rng(3).standard_normal((spec.N, spec.F, spec.H, spec.W)).astype(np.float16)
+    t = pc.packed_transpose(packed)
+    d_dy = torch.from_numpy(dy).cuda()
+    d_dx = torch.full((spec.N, spec.C, spec.H, spec.W), -777.0, dtype=torch.float16, device="cuda")
+    pc.conv3x3_grad_input(d_dy, d_dx, t, spec.N, spec.H, spec.W, st)
+    torch.cuda.synchronize()
+    assert rel_err(d_dx.cpu().numpy(), oracle.conv3x3_grad_input(dy, wm, spec.H, spec.W, 1, 1)) <= TOL["f16"]
+    # the non-allocating entry point: bit-equal to the allocating one
+    x = L.gen_activations(spec)
+    d_x = torch.from_numpy(x).cuda()
+    y0 = torch.empty((spec.N, spec.F, spec.H, spec.W), dtype=torch.float16, device="cuda")
+    y1 = torch.empty_like(y0)
+    pc.conv3x3(d_x, y0, packed, None, spec.N, spec.H, spec.W, 1, 1, 0, st)
+    pc.conv3x3_noalloc(d_x, y1, packed, None, spec.N, spec.H, spec.W, 1, 1, 0, st)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    assert rel_err(y0.cpu().numpy(), oracle.conv3x3(x, wm, None, 1, 1)) <= TOL["f16"]
+    t.free()
+    packed.free()
