@@ -175,6 +175,8 @@ def main():
                     help="backward pass of the nine VGG-16 shapes at batch 64: masked weight gradient and input gradient")
     ap.add_argument("--conv1x1", action="store_true",
                     help="the 1x1 convolutions of ResNet-50's bottlenecks at batch 32, grouped into 3x3 patterns")
+    ap.add_argument("--nhwc", action="store_true",
+                    help="the nine VGG-16 shapes at batch 64 with channel-minor activations and outputs (PCONV_FLAG_NHWC)")
     ap.add_argument("--clustered", action="store_true",
                     help="VGG-16 shapes with clustered connectivity: filters in their own order against similarity order")
     ap.add_argument("--layers", default="")
@@ -206,6 +208,8 @@ def main():
         return peaks_bench(args, torch)
     if args.admm:
         return admm_bench(args, torch, pc, L)
+    if args.nhwc:
+        return nhwc_bench(args, torch, pc, L)
     if args.clustered:
         return clustered_bench(args, torch, pc, L)
     if args.backward:
@@ -576,6 +580,78 @@ def admm_bench(args, torch, pc, L):
            "steps_table": rows,
            "cpu_baseline": {"value": m / el, "unit": "kernels/s", "cores": 1, "kind": "oracle",
                             "sample": f"the first {m} kernels, {el:.1f} s"}}
+    print(json.dumps(out), flush=True)
+
+
+def nhwc_bench(args, torch, pc, L):
+    """The default workload (config 4 at K, keep from the command line: nine VGG-16 shapes, batch 64, fp16) with
+    channel-minor activations and outputs, x [N][H][W][C] and y [N][Ho][Wo][F] (PCONV_FLAG_NHWC), next to the same
+    layers in the channel-major layout of the benchmark configuration.  The three-channel first layer is run with its
+    input padded to eight channels (the added channels' kernels are removed, so the layer is the same)."""
+    import oracle
+    st = torch.cuda.current_stream().cuda_stream
+    rows, t_nhwc, t_nchw, macs, flops = [], 0.0, 0.0, 0.0, 0.0
+    sample = None
+    for spec in L.config4(args.K, args.keep, 64):
+        if args.only and spec.name != args.only:
+            continue
+        w, lib = L.gen_weights(spec), spec.library()
+        w32 = w.astype(np.float32)
+        pid = pc.assign_patterns(w32, lib)
+        mask = pc.select_connectivity(w32, lib, pid, spec.keep)
+        base = L.gen_activations(spec, images=[0, 1, 2, 3])
+        C = spec.C
+        if C % 8:
+            C8 = (C + 7) // 8 * 8
+            w = np.concatenate([w, np.zeros((spec.F, C8 - C, 3, 3), w.dtype)], axis=1)
+            pid = np.concatenate([pid, np.zeros((spec.F, C8 - C), pid.dtype)], axis=1)
+            mask = np.concatenate([mask, np.zeros((spec.F, C8 - C), mask.dtype)], axis=1)
+            base = np.concatenate([base, np.zeros((4, C8 - C, spec.H, spec.W), base.dtype)], axis=1)
+            C = C8
+        p = pc.pack(w, lib, pid, mask)
+        x = np.concatenate([base] * (spec.N // 4), axis=0)
+        d_nchw = torch.from_numpy(x).cuda()
+        d_nhwc = d_nchw.permute(0, 2, 3, 1).contiguous()
+        db = torch.from_numpy(L.gen_bias(spec)).cuda()
+        dy = torch.empty(spec.N * spec.F * spec.Ho * spec.Wo, dtype=torch.float16, device="cuda")
+        f1 = lambda: pc.conv3x3(d_nhwc, dy, p, db, spec.N, spec.H, spec.W, 1, 1, pc.FLAG_RELU | pc.FLAG_NHWC, st)
+        f0 = lambda: pc.conv3x3(d_nchw, dy, p, db, spec.N, spec.H, spec.W, 1, 1, pc.FLAG_RELU, st)
+        _, ms1 = time_launches(torch, f1, args.steps, args.warmup)
+        _, ms0 = time_launches(torch, f0, args.steps, args.warmup)
+        nk = int(mask.sum())
+        ex = 2.0 * spec.N * spec.Ho * spec.Wo * 9 * ((spec.F + 63) // 64 * 64) * ((C + 15) // 16 * 16)
+        nbytes = 2.0 * spec.N * (C * spec.H * spec.W + spec.F * spec.Ho * spec.Wo)
+        row = {"layer": spec.name, "C": C, "F": spec.F, "H": spec.H, "n_kept": nk, "nhwc_us": ms1 * 1e3,
+               "nchw_us": ms0 * 1e3, "executed_TFLOPs": ex / ms1 / 1e9, "mfma_frac": ex / ms1 / 1e9 / PEAK_FP16_MFMA_TFLOPS,
+               "alg_GBs": nbytes / ms1 / 1e6, "hbm_frac": nbytes / ms1 / 1e6 / PEAK_HBM_GBS,
+               "eff_GMACs": effective_macs(spec, nk) / ms1 / 1e6}
+        rows.append(row)
+        log(json.dumps(row))
+        t_nhwc += ms1
+        t_nchw += ms0
+        macs += effective_macs(spec, nk)
+        if spec.C >= 64:
+            flops += ex
+        if spec.name == "conv1_2":
+            sample = (spec, base[:1], oracle.mask_weights(w, pid, mask, lib), L.gen_bias(spec))
+        p.free()
+        del d_nchw, d_nhwc, dy
+        torch.cuda.empty_cache()
+    out = {"metric": "effective GMAC/s (nonzero weights), VGG-16 3x3 layers, channel-minor layout", "value": macs / t_nhwc / 1e6,
+           "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_nhwc,
+           "higher_is_better": True, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+           "config": {"workload": f"configs[4] at K={args.K}, keep {args.keep}, batch 64, x and y channel-minor (NHWC)"},
+           "nchw_ms_per_step": t_nchw, "layers": rows}
+    if sample is not None:
+        spec, x1, wm, b = sample
+        t0, runs = time.perf_counter(), 0
+        while time.perf_counter() - t0 < 8.0:
+            oracle.conv3x3(x1, wm, b, 1, 1, True)
+            runs += 1
+        el = (time.perf_counter() - t0) / runs
+        out["cpu_baseline"] = {"value": effective_macs(spec, int((wm != 0).any(axis=(2, 3)).sum())) / spec.N / el / 1e9,
+                               "unit": "effective GMAC/s", "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"{runs} runs of one image of {spec.name}, {el * runs:.1f} s"}
     print(json.dumps(out), flush=True)
 
 

@@ -52,7 +52,8 @@ enum {
 };
 
 enum { PCONV_FLAG_RELU = 1u,        /* conv flags: y = max(y, 0) after the bias */
-       PCONV_FLAG_DENSE_DIRECT = 2u /* pconv_dense_conv3x3 only: the plain direct kernel also for fp16 storage */ };
+       PCONV_FLAG_DENSE_DIRECT = 2u, /* pconv_dense_conv3x3 only: the plain direct kernel also for fp16 storage */
+       PCONV_FLAG_NHWC = 4u         /* pconv_conv3x3 and its variants: x is [N][H][W][C], y is [N][Ho][Wo][F] (below) */ };
 enum { PCONV_PACK_HOST_ONLY = 1u }; /* pack flags: build the packed form on the host, allocate nothing on the device */
 
 /*
@@ -174,9 +175,14 @@ void pconv_free(pconv_packed* p);
  *   wp      handle from pconv_pack (with a device copy, on the current device)
  *   bias    device, float[F], or NULL for no bias
  *   stride  1 or 2;  pad 0 or 1
- *   flags   0 or PCONV_FLAG_RELU
+ *   flags   0, PCONV_FLAG_RELU, PCONV_FLAG_NHWC or both
  *   stream  a hipStream_t passed as void* (NULL = the default stream)
  * Launch errors are returned; execution errors surface at the caller's next synchronisation.  N = 0 is a no-op.
+ *
+ * Channel-minor layout.  With PCONV_FLAG_NHWC x is dtype[N][H][W][C] and y dtype[N][Ho][Wo][F]: the order in which the
+ * matrix-core kernel keeps activations on chip, so they travel from memory to LDS without passing registers.  fp16
+ * storage only, C and F multiples of 8 (pad a three-channel input to eight), x and y aligned to 16 bytes, and a layer
+ * without per-tile channel lists (pconv_packed_mfma_blocks reports equal counts); PCONV_EUNSUPPORTED otherwise.
  *
  * Workspace.  When a layer has too few output tiles to occupy the GPU (small batch, small feature map) the library
  * splits the input channels of each tile over several workgroups, which add their partial sums in a workspace that

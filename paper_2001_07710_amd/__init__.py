@@ -16,6 +16,7 @@ import numpy as np
 F32, F16 = 0, 1
 FLAG_RELU = 1
 FLAG_DENSE_DIRECT = 2
+FLAG_NHWC = 4
 PACK_HOST_ONLY = 1
 KERNEL_AUTO, KERNEL_TILED, KERNEL_GENERIC, KERNEL_QUAD, KERNEL_MFMA = 0, 1, 2, 3, 4
 ORDER_AUTO, ORDER_PLAIN, ORDER_BALANCED = 0, 1, 2

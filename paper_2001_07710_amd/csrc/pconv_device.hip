@@ -2182,7 +2182,7 @@ extern "C" const char* pconv_last_hip_error(void) { return g_hip_error; }
 static int check_conv_args(const void* x, const void* y, int N, int C, int F, int H, int W, int stride, int pad,
                            unsigned flags, int* Ho, int* Wo) {
     if (!x || !y) return PCONV_EINVAL;
-    if (flags & ~(unsigned)PCONV_FLAG_RELU) return PCONV_EINVAL;
+    if (flags & ~(unsigned)(PCONV_FLAG_RELU | PCONV_FLAG_NHWC)) return PCONV_EINVAL;
     if (stride != 1 && stride != 2) return PCONV_EUNSUPPORTED;
     if (pad != 0 && pad != 1) return PCONV_EUNSUPPORTED;
     if (N < 0 || C <= 0 || F <= 0 || H <= 0 || W <= 0) return PCONV_ESHAPE;
@@ -2218,6 +2218,15 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
     const int relu = (flags & PCONV_FLAG_RELU) ? 1 : 0;
 
     int kernel = tuning ? tuning->kernel : PCONV_KERNEL_AUTO;
+    // Channel-minor activations and outputs: the matrix-core kernel only (fp16 storage, C and F multiples of 8,
+    // buffers aligned to 16 bytes, a layer without channel lists).
+    const bool nhwc = (flags & PCONV_FLAG_NHWC) != 0;
+    if (nhwc) {
+        if (wp->dtype != PCONV_F16 || wp->C % 8 || wp->F % 8 || wp->mfma.empty()) return PCONV_EUNSUPPORTED;
+        if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) % 16) return PCONV_EUNSUPPORTED;
+        if (kernel != PCONV_KERNEL_AUTO && kernel != PCONV_KERNEL_MFMA) return PCONV_EUNSUPPORTED;
+        kernel = PCONV_KERNEL_MFMA;
+    }
     int R = tuning ? tuning->rows : 0, NF = tuning ? tuning->filters_per_wave : 0, waves = tuning ? tuning->waves : 0;
     int CPW = tuning ? tuning->channels_per_wave : 0;
     int KS = tuning ? tuning->channel_splits : 0;
@@ -2237,6 +2246,7 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         a.x = x; a.y = y; a.bias = bias;
         a.N = N; a.C = wp->C; a.F = wp->F; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo;
         a.stride = stride; a.pad = pad; a.relu = relu;
+        a.nhwc = nhwc ? 1 : 0;
         a.shape = tuning ? tuning->mfma_shape : 0;
         a.rows = tuning ? tuning->rows : 0;
         a.walk = tuning ? tuning->slot_walk : 0;

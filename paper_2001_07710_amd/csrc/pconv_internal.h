@@ -142,6 +142,7 @@ struct MfmaConv {
     int mt, n_taps;
     uint8_t taps[9];
     int N, C, F, H, W, Ho, Wo, stride, pad, relu;
+    int nhwc;                   // x is [N][H][W][C] and y [N][Ho][Wo][F] (C and F multiples of 8, no channel lists)
     int shape;                  // 1..kMfmaShapes: the tile shape (mt must be its height)
     int rows;                   // 0: as many output rows per tile as fit; else that many
     int walk;                   // 1: one workgroup per tile; otherwise persistent workgroups that walk over the tiles

@@ -120,6 +120,9 @@ struct MfmaParams {
     unsigned wq_bytes;
     unsigned chan_bytes;    // H*W*2
     unsigned img_bytes;     // C*H*W*2
+    int nhwc;                    // activations and outputs channel-minor ([N][H][W][C], [N][Ho][Wo][F])
+    int P;                       // nhwc: 1 KB pieces (64 positions) per half of a staged block: ceil(max_slots * PW / 64)
+    FastDiv div_PW;
     int KS;                      // workgroups that share one tile, each taking a contiguous range of the channel blocks
     int win_alias;               // the epilogue's windows lie in the staging buffer that is free meanwhile: 1 = its
                                  // weights, 2 = its activations; 0 = in a place of their own behind the bias
@@ -193,9 +196,16 @@ struct TileGeo {
 // Workgroups are persistent: workgroup w takes tiles w, w + G, w + 2G, ... and runs the (tile, channel block) pairs of
 // all of them as one sequence, so the first block of the next tile is loaded while the last block of the current one
 // is multiplied, and the stores of a tile drain while the next tile is computed.
-template <int AF, int BF, int WM, int WN, int LW, int KI, bool FULL>
+// NHWC: activations and outputs are channel-minor in memory.  That is the order the staged activations have in LDS
+// anyway, so they go from memory straight into LDS like the weights (buffer_load ... lds, 16 bytes = 8 channels of one
+// position per lane, 64 consecutive positions per wave-wide load; positions outside the image are loads outside the
+// descriptor and arrive as zeros, which is the padding): no staging registers, no byte permutes, no LDS writes.  The
+// epilogue turns 32 pixels at a time through a wave-private LDS window so that whole runs of a pixel's filters are
+// stored.
+template <int AF, int BF, int WM, int WN, int LW, int KI, bool FULL, bool NHWC>
 __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 1) void mfma_conv_kernel(const MfmaParams p) {
-    constexpr int kItems = KI;
+    constexpr int kItems = NHWC ? 0 : KI;
+    constexpr int kAL = NHWC ? 12 : 0;      // NHWC: wave-wide activation loads per wave and block, at most
     constexpr bool CAN_ALIAS = AF == 1 && WM == 2 && WN == 2;
     constexpr int NW = WM * WN, NTH = NW * 64, MT = WM * AF * 32, HALF = NTH / 2;
     constexpr int WPIECES = (9 * 2 * MT + NTH - 1) / NTH;      // 16-byte pieces of weights per lane and block, at most
@@ -261,12 +271,13 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     unsigned char* const ldsB = lds + a_stages * p.a_bytes;
     const int b_stages = CAN_ALIAS ? p.b_stages : 2;
     float* const ldsBias = reinterpret_cast<float*>(lds + p.bias_off);          // [3][MT]: by tile count modulo 3
-    unsigned* const win_fixed = reinterpret_cast<unsigned*>(lds + p.bias_off + 3 * MT * 4) + wave * (4 * WP);
+    unsigned* const win_fixed = reinterpret_cast<unsigned*>(lds + p.bias_off + 3 * MT * 4) +
+                                wave * (NHWC ? 32 * (AF * 64 + 8) / 4 : 4 * WP);
 
     // ---- zero columns left and right of the image, in one staging buffer: once per workgroup (no tile's staging
     // ever writes them), and again behind an epilogue whose windows lay in that buffer
     auto zero_halo = [&](int stage) {
-        if (!p.pad) return;
+        if (NHWC || !p.pad) return;
         const uint4v zero = {0u, 0u, 0u, 0u};
         for (int i = tid; i < p.max_slots * 4; i += NTH) {
             const int sl = i >> 2, which = i & 3;               // half (2) x side (2)
@@ -289,8 +300,9 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     // ---- staging state: descriptors of this lane for the tile whose blocks are being loaded
     const int kbs = wave >= NW / 2 ? 1 : 0;                     // which half of the block's channels this wave stages
     const int ltid = tid - kbs * HALF;
-    uint32_t goff[kItems];
-    int loff[kItems];
+    uint32_t goff[kItems > 0 ? kItems : 1];
+    int loff[kItems > 0 ? kItems : 1];
+    uint32_t agoff[kAL > 0 ? kAL : 1];      // NHWC: this lane's byte offset in x for each of the wave's activation loads
     int stage_wb = 0;                                           // first block of the tile being loaded, in the weights
     bool stage_on = true;                                       // false: nothing left to load (offsets outside)
     bool weights_on = true;                                     // false: the only block of weights is in LDS for good
@@ -301,6 +313,32 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.wq_bytes);
     auto stage_descriptors = [&](const TileGeo& g) {
         stage_wb = g.wb;
+        if constexpr (NHWC) {
+            // load `id` of a block = piece id % P of half id / P; piece k holds positions 64k .. 64k+63 of the
+            // half's [row slot][position] array; wave w issues loads w, w + NW, ...
+#pragma unroll
+            for (int i = 0; i < kAL; ++i) {
+                const int id = wave + i * NW;
+                const int half = id >= p.P ? 1 : 0, k = id - half * p.P;
+                const unsigned q = (unsigned)(k * 64 + lane);
+                const unsigned sl = fastdiv(q, p.div_PW), pos = q - sl * (unsigned)PW;
+                const int col = (int)pos - p.pad;
+                agoff[i] = kInvalid;
+                if (id < 2 * p.P && (int)sl < g.used_slots && col >= 0 && col < p.W) {
+                    int seg, iy;
+                    if ((int)sl < g.cnt0) {
+                        seg = 0;
+                        iy = g.oy0 * s - p.pad + (int)sl;
+                    } else {
+                        const unsigned t = sl - (unsigned)g.cnt0, qq = fastdiv(t, p.div_cnt_full);
+                        seg = 1 + (int)qq;
+                        iy = (int)(t - qq * (unsigned)p.cnt_full) - p.pad;
+                    }
+                    if (g.n0 + seg < p.N && iy >= 0 && iy < p.H)
+                        agoff[i] = (uint32_t)seg * p.img_bytes + (uint32_t)((iy * p.W + col) * p.C + half * 8) * 2u;
+                }
+            }
+        }
         const float inv_slots = 1.0f / (float)g.used_slots;
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
@@ -341,14 +379,15 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         x_records = __builtin_amdgcn_readfirstlane(x_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (unsigned)x_left);
     };
 
-    Piece<LW> stg[kItems][8];
+    Piece<LW> stg[kItems > 0 ? kItems : 1][8];
     const int w_pieces = p.a_bytes >> 4;                       // (a multiple of 128: whole waves)
 
     // One of the loads of channel block cb, which will be multiplied out of LDS buffer `buf`.  j < 8*kItems: channel
     // j%8 of piece j/8 of the activations, into registers.  Then the weights, 1 KB per wave and load, straight into
     // LDS (buffer_load ... lds: lane l's 16 bytes land at the wave's base + 16*l, no registers in between); the
     // buffer is free from the barrier that ended the block before the current one.
-    constexpr int NLOADS = 8 * kItems + WPIECES;
+    constexpr int NLOADS = (NHWC ? kAL : 8 * kItems) + WPIECES;
+    constexpr int NACT = NHWC ? kAL : 8 * kItems;
     // The eight channels of block `cb` that this wave stages: consecutive ones, or (channel lists) whichever the
     // tile's list names at that place -- kNoChannel, beyond any C, where the list's last block is not full.
     int chans[8];
@@ -360,15 +399,26 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         }
     };
     auto issue_one = [&](int cb, int buf, int j) {
-        if (j < 8 * kItems) {
+        if (j < NACT) {
+          if constexpr (NHWC) {
+            const int id = wave + j * NW;
+            if (id < 2 * p.P) {
+                const int half = id >= p.P ? 1 : 0, k = id - half * p.P;
+                const __amdgpu_buffer_rsrc_t xr =
+                    make_rsrc(reinterpret_cast<const void*>(((unsigned long long)xb_hi << 32) | xb_lo), x_records);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr)(ldsB + (buf * 2 + half) * p.plane_bytes + k * 1024),
+                                                         16, (int)(stage_on ? agoff[j] : kInvalid), cb * 32, 0, 0);
+            }
+          } else {
             const int i = j >> 3, ch = j & 7;
             const unsigned chan = (unsigned)chans[ch];
             const __amdgpu_buffer_rsrc_t xr =
                 make_rsrc(reinterpret_cast<const void*>(((unsigned long long)xb_hi << 32) | xb_lo), x_records);
             stg[i][ch].load(xr, (chan < (unsigned)p.C && stage_on) ? goff[i] : kInvalid,
                             chan < (unsigned)p.C ? chan * p.chan_bytes : 0u);
+          }
         } else {
-            const int first = ((j - 8 * kItems) * NW + wave) * 64;        // the wave's first piece (uniform)
+            const int first = ((j - NACT) * NW + wave) * 64;              // the wave's first piece (uniform)
             if (first < w_pieces && stage_on && weights_on) {
                 const uint32_t wsoff = (uint32_t)((stage_wb + cb) * p.a_bytes);
                 const int abuf = a_stages == 2 ? buf : 0;
@@ -588,6 +638,67 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         __builtin_amdgcn_wave_barrier();
     };
 
+    // NHWC outputs.  A lane holds, for its pixel, filters (r/4)*8 + (lane/32)*4 + r%4 of each 32-filter block.  Written
+    // out as they lie that is 8 bytes per lane and pixel, scattered over the pixels' lines (measured: the first layer
+    // at batch 64 took 559 us, five times the channel-major form).  So 32 pixels at a time go through a wave-private
+    // window in LDS, [pixel][the wave's AF*32 filters] (8 bytes of padding per pixel against bank conflicts): the lanes
+    // write their groups of four filters, then AF*4 neighbouring lanes read back the AF*64 bytes of one pixel, 16 bytes
+    // each, and a wave-wide store writes whole runs of AF*64 bytes.  LDS operations of one wave complete in order, so
+    // no barrier is needed between the two phases.
+    auto epilogue_nhwc = [&](const TileGeo& g) {
+        constexpr int PITCH = AF * 64 + 8;                       // bytes per pixel in the window
+        constexpr int LPP = AF * 4, PPR = 64 / LPP;              // lanes per pixel when reading back; pixels per read
+        unsigned char* const win = reinterpret_cast<unsigned char*>(win_fixed);
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int li = lane_e & 31, lk = lane_e >> 5;
+        const int valid = g.Rv * Wo - wn * BF * 32;              // pixels of the wave's range that exist
+        const half2v floor2 = __builtin_bit_cast(half2v, p.relu ? 0u : 0x7E007E00u);
+        const unsigned long long y_off = (unsigned long long)g.n0 * p.F * (unsigned)(Ho * Wo) * 2;
+        const unsigned long long y_left = p.y_bytes - y_off, yb = reinterpret_cast<unsigned long long>(p.y) + y_off;
+        const unsigned yb_lo = __builtin_amdgcn_readfirstlane((unsigned)yb);
+        const unsigned yb_hi = __builtin_amdgcn_readfirstlane((unsigned)(yb >> 32));
+        const unsigned y_records = __builtin_amdgcn_readfirstlane(y_left > 0x7FFFFFFFull ? 0x7FFFFFFFu : (unsigned)y_left);
+        const __amdgpu_buffer_rsrc_t yr =
+            make_rsrc(reinterpret_cast<const void*>(((unsigned long long)yb_hi << 32) | yb_lo), y_records);
+        constexpr int kStream = 2;
+        auto pack2 = [&](float a, float b) {
+            const float2v v = {a, b};
+            return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_convertvector(v, half2v), floor2));
+        };
+        const int part = lane_e % LPP, rpix = lane_e / LPP;      // reading back: which 16 bytes of which pixel of a read
+        const int fwave = g.tm * MT + wm * AF * 32;              // the wave's first filter (uniform)
+        const bool f_ok = fwave + part * 8 < p.F;                // (F is a multiple of 8)
+#pragma unroll
+        for (int bf = 0; bf < BF; ++bf) {
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int af = 0; af < AF; ++af)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint2v v = {pack2(acc[af][bf][q * 4 + 0], acc[af][bf][q * 4 + 1]),
+                                      pack2(acc[af][bf][q * 4 + 2], acc[af][bf][q * 4 + 3])};
+                    *reinterpret_cast<uint2v*>(win + li * PITCH + (af * 32 + q * 8 + lk * 4) * 2) = v;
+                }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int r = 0; r < 32 / PPR; ++r) {
+                const int px = r * PPR + rpix;                   // pixel of the 32
+                const uint4v v = *reinterpret_cast<const uint4v*>(win + px * PITCH + part * 16);
+                const int q_wave = bf * 32 + px;
+                uint32_t dst = kInvalid;
+                if (q_wave < valid && f_ok) {
+                    const unsigned q0 = (unsigned)(wn * BF * 32 + q_wave);
+                    const unsigned row = fastdiv(q0, p.div_Wo), ox = q0 - row * (unsigned)Wo;
+                    const unsigned rr = (unsigned)g.oy0 + row, sg = fastdiv(rr, p.div_Ho), oy = rr - sg * (unsigned)Ho;
+                    dst = (((sg * (unsigned)Ho + oy) * (unsigned)Wo + ox) * (unsigned)p.F) * 2u + (unsigned)part * 16u;
+                }
+                __builtin_amdgcn_raw_buffer_store_b128(v, yr, (int)dst, fwave * 2, kStream);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
     // Channel blocks of a tile split over KS workgroups: every one writes its partial sums to the workspace (laid out
     // like the registers: 16 bytes per lane and group of four accumulator rows, 1 KB per wave-wide store); the one
     // that arrives last at the tile's counter adds the parts in the order of the splits, its own from registers, so
@@ -762,7 +873,12 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
             __syncthreads();
             buf ^= 1;
         }
-        if (p.KS == 1 || combine_splits(gc)) epilogue(gc, buf ^ 1);
+        if (p.KS == 1 || combine_splits(gc)) {
+            if constexpr (NHWC)
+                epilogue_nhwc(gc);
+            else
+                epilogue(gc, buf ^ 1);
+        }
         if constexpr (CAN_ALIAS) {
             if (p.win_alias) __syncthreads();
             if (p.win_alias == 2) zero_halo(buf ^ 1);    // (the windows lay over that buffer's zero columns)
@@ -829,9 +945,10 @@ template <int AF, int BF, int WM, int WN>
 int launch_shape(const MfmaParams& p, int lw, int ki, size_t lds, int walk, double block_us, hipStream_t st) {
     const bool full = p.nt == 9;
     const long long ntiles = (long long)p.tiles_n * p.tiles_m * p.KS;
-#define PCONV_MFMA_CASE1(LWv, KIv, FULLv)                                                                       \
-    if (lw == LWv && ki == KIv && full == FULLv) {                                                              \
-        auto kern = mfma_conv_kernel<AF, BF, WM, WN, LWv, KIv, FULLv>;                                          \
+#define PCONV_MFMA_CASE1(LWv, KIv, FULLv) PCONV_MFMA_CASE2(LWv, KIv, FULLv, false)
+#define PCONV_MFMA_CASE2(LWv, KIv, FULLv, NHWCv)                                                                \
+    if (lw == LWv && ki == KIv && full == FULLv && (p.nhwc != 0) == NHWCv) {                                    \
+        auto kern = mfma_conv_kernel<AF, BF, WM, WN, LWv, KIv, FULLv, NHWCv>;                                   \
         if (lds > 64 * 1024)                                                                                    \
             PCONV_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
         const int grid = persistent_grid((const void*)kern, WM * WN * 64, lds, ntiles, walk);                        \
@@ -847,9 +964,11 @@ int launch_shape(const MfmaParams& p, int lw, int ki, size_t lds, int walk, doub
 #else
     PCONV_MFMA_CASE(8, 1) PCONV_MFMA_CASE(8, 2) PCONV_MFMA_CASE(4, 2) PCONV_MFMA_CASE(4, 3) PCONV_MFMA_CASE(2, 3)
     PCONV_MFMA_CASE(1, 3)
+    PCONV_MFMA_CASE2(8, 1, true, true) PCONV_MFMA_CASE2(8, 1, false, true)
 #endif
 #undef PCONV_MFMA_CASE
 #undef PCONV_MFMA_CASE1
+#undef PCONV_MFMA_CASE2
     return PCONV_EUNSUPPORTED;
 }
 
@@ -869,6 +988,8 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.CB = (a.C + 15) / 16;
     p.clist = a.d_clist;
     p.tinfo = a.d_tinfo;
+    // (channel-minor activations are loaded eight channels at a time as they lie: no channel lists, whole groups)
+    if (a.nhwc && (a.d_clist || a.C % 8 || a.F % 8)) return false;
     p.KS = a.splits < 1 ? 1 : a.splits;
     // (every part of a split tile has at least one block: the sequence of (tile, block) pairs has no empty member)
     if (p.KS > (a.d_clist ? a.min_blocks : p.CB) || p.KS > 64) return false;
@@ -908,13 +1029,18 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         p.max_slots = (R - segs) * a.stride + 3 * segs;
         p.a_bytes = p.nt * 2 * MT * 16;
         p.plane_bytes = p.max_slots * p.PW * 16;
+        // (channel-minor activations arrive in wave-wide pieces of 64 positions: a half's buffer is whole pieces)
+        p.P = (p.max_slots * p.PW + 63) / 64;
+        if (a.nhwc) p.plane_bytes = p.P * 1024;
         // (a layer of at most 16 channels and one tile of filters has a single block of weights: staged once)
         const bool shares_cu = sh.af == 1 && sh.wm == 2 && sh.wn == 2;    // (the shape two workgroups of which fit)
         p.a_stages = (shares_cu && p.CB == 1 && (a.F + MT - 1) / MT == 1 && p.KS == 1) ? 1 : 2;
         // (one buffer for the activations instead of two where that, and nothing less, lets a second workgroup in)
         p.b_stages = 2;
         const size_t extra = 3 * (size_t)MT * 4 + 16;
-        if (shares_cu && p.a_stages == 2 && (size_t)p.a_stages * p.a_bytes + 4 * (size_t)p.plane_bytes + extra > 80 * 1024 &&
+        // (not with channel-minor activations: their loads write the next block's buffer while this one is read)
+        if (!a.nhwc && shares_cu && p.a_stages == 2 &&
+            (size_t)p.a_stages * p.a_bytes + 4 * (size_t)p.plane_bytes + extra > 80 * 1024 &&
             (size_t)p.a_stages * p.a_bytes + 2 * (size_t)p.plane_bytes + extra <= 80 * 1024)
             p.b_stages = 1;
         const size_t staging = (size_t)p.a_stages * p.a_bytes + 2 * (size_t)p.b_stages * p.plane_bytes;
@@ -923,9 +1049,10 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         // -- unless the shape is one whose registers leave room for a second workgroup on the compute unit and the
         // windows fit the weights' half of a staging buffer (or, where the weights stay, the activations' half): then
         // they live there
-        const size_t windows = (size_t)(NTH / 64) * 4 * (sh.bf * 32 + 16) * 4;
+        // (channel-minor outputs: 32 pixels x the wave's filters, see epilogue_nhwc)
+        const size_t windows = a.nhwc ? (size_t)(NTH / 64) * 32 * (sh.af * 64 + 8) : (size_t)(NTH / 64) * 4 * (sh.bf * 32 + 16) * 4;
         p.win_alias = 0;
-        if (shares_cu) {
+        if (shares_cu && !a.nhwc) {
             if (p.a_stages == 2 && windows <= (size_t)p.a_bytes) p.win_alias = 1;
             if (p.a_stages == 1 && windows <= 2 * (size_t)p.plane_bytes) p.win_alias = 2;
         }
@@ -933,6 +1060,11 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         p.flag_off = (int)lds;                   // one word for the channel split's "arrived last" flag
         lds += 16;
         if (lds > 160 * 1024) continue;
+        if (a.nhwc) {
+            if (2 * p.P > 12 * (NTH / 64)) continue;          // (pieces per wave that the kernel is built for)
+            lw = 8;
+            break;
+        }
         // widest loads whose pieces fit the lanes; fewer rows only when even the narrowest fit nowhere
         int w = lw;
         while (w > 1 && (long long)p.max_slots * (a.W / w) > (long long)max_items(w) * (NTH / 2)) w /= 2;
@@ -941,9 +1073,11 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
             break;
         }
     }
-    p.G = a.W / lw;
+    p.G = a.nhwc ? 1 : a.W / lw;                  // (channel-minor staging has no pieces of lw pixels)
     const int need_items = (int)(((long long)p.max_slots * p.G + NTH / 2 - 1) / (NTH / 2));
-    const int ki = lw == 8 ? std::max(need_items, 1) : lw == 4 ? std::max(need_items, 2) : 3;
+    const int ki = a.nhwc ? 1 : lw == 8 ? std::max(need_items, 1) : lw == 4 ? std::max(need_items, 2) : 3;
+    p.nhwc = a.nhwc ? 1 : 0;
+    p.div_PW = make_fastdiv((unsigned)p.PW);
     p.R = R;
     p.tiles_n = (int)((total_rows + R - 1) / R);
     p.tiles_m = (a.F + MT - 1) / MT;

@@ -197,7 +197,8 @@ def test_error_codes():
     assert f(one, one, p.handle, None, 1, 8, 8, 1, 2, 0, None) == pc.EUNSUPPORTED
     assert f(one, one, p.handle, None, 1, 0, 8, 1, 1, 0, None) == pc.ESHAPE
     assert f(one, one, p.handle, None, 1, 2, 2, 1, 0, 0, None) == pc.ESHAPE           # no output
-    assert f(one, one, p.handle, None, 1, 8, 8, 1, 1, 4, None) == pc.EINVAL           # unknown flag
+    assert f(one, one, p.handle, None, 1, 8, 8, 1, 1, 64, None) == pc.EINVAL          # unknown flag
+    assert f(one, one, p.handle, None, 1, 8, 8, 1, 1, pc.FLAG_NHWC, None) in (pc.EUNSUPPORTED, pc.ESTATE)   # fp32 layer
     assert f(one, one, p.handle, None, 1, 8, 8, 1, 1, 0, None) == pc.ESTATE           # host-only handle
     assert f(one, one, None, None, 1, 8, 8, 1, 1, 0, None) == pc.EINVAL
     assert raw.pconv_maxpool2x2(one, one, 0, 1, 1, 1, 8, None) == pc.ESHAPE
