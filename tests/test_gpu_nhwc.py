@@ -114,3 +114,27 @@ def test_what_the_form_refuses():
     assert e.value.code == pc.EUNSUPPORTED
     layer.free()
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["conv1_2", "conv3_2", "conv5_1"])
+def test_channel_minor_form_at_benchmark_shapes(name):
+    # config 4 at batch 64 (K = 8, keep 0.28), as bench.py --nhwc launches it: the first and the last image whole,
+    # and 65,536 outputs sampled over the batch
+    spec = [s for s in L.config4(8, 0.28, 64) if s.name == name][0]
+    say("nhwc full", name)
+    layer = GpuLayer(spec)
+    base = L.gen_activations(spec, images=[0, 1, 2, 3])
+    x = np.concatenate([base] * (spec.N // 4), axis=0)
+    x[spec.N - 1] = L.gen_image(spec, spec.N - 1)
+    got = run_nhwc(layer, x, spec.relu)
+    ref_first, ref_last = layer.oracle(x[:1]), layer.oracle(x[spec.N - 1:])
+    tol = TOL["f16"]
+    assert rel_err(got[0], ref_first[0]) <= tol and rel_err(got[spec.N - 1], ref_last[0]) <= tol
+    rng = np.random.default_rng(77 + spec.idx)
+    coords = np.stack([rng.integers(0, spec.N, 65536), rng.integers(0, spec.F, 65536), rng.integers(0, spec.Ho, 65536),
+                       rng.integers(0, spec.Wo, 65536)], axis=1).astype(np.int32)
+    ref_pts = layer.oracle_at(x, coords)
+    pts = got[coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]].astype(np.float64)
+    rms = float(np.sqrt(np.mean(ref_first ** 2)))
+    assert np.max(np.abs(pts - ref_pts) / np.maximum(np.abs(ref_pts), rms)) <= tol
+    layer.free()

@@ -128,3 +128,36 @@ def test_transposed_and_non_allocating_calls_on_a_layer_with_channel_lists():
     assert rel_err(y0.cpu().numpy(), oracle.conv3x3(x, wm, None, 1, 1)) <= TOL["f16"]
     t.free()
     packed.free()
+
+
+def test_clustered_layer_at_a_benchmark_shape():
+    # 512 -> 512 channels at 28 x 28, batch 64, as bench.py --clustered launches it in similarity order: the first and
+    # the last image whole, 65,536 outputs sampled over the batch
+    import torch
+    spec = [s for s in L.config4(8, 0.28, 64) if s.name == "conv4_2"][0]
+    say("clustered full", spec.name)
+    w, _ = L.gen_clustered_weights(spec, spec.F // 128, 1.25 * spec.keep)
+    lib, w32 = spec.library(), w.astype(np.float32)
+    pid = pc.assign_patterns(w32, lib)
+    mask = pc.select_connectivity(w32, lib, pid, spec.keep)
+    order = pc.filter_similarity_order(mask, 128)
+    wo, po, mo, bo = w[order], pid[order], mask[order], L.gen_bias(spec)[order]
+    packed = pc.pack(wo, lib, po, mo)
+    listed, dense = pc.packed_mfma_blocks(packed, 128)
+    assert listed * 2 <= dense
+    base = L.gen_activations(spec, images=[0, 1, 2, 3])
+    x = np.concatenate([base] * (spec.N // 4), axis=0)
+    x[spec.N - 1] = L.gen_image(spec, spec.N - 1)
+    got = run(torch, packed, x, bo, spec, True)
+    wm = oracle.mask_weights(wo, po, mo, lib)
+    tol = TOL["f16"]
+    ref_first, ref_last = oracle.conv3x3(x[:1], wm, bo, 1, 1, True), oracle.conv3x3(x[spec.N - 1:], wm, bo, 1, 1, True)
+    assert rel_err(got[0], ref_first[0]) <= tol and rel_err(got[spec.N - 1], ref_last[0]) <= tol
+    rng = np.random.default_rng(5)
+    coords = np.stack([rng.integers(0, spec.N, 65536), rng.integers(0, spec.F, 65536), rng.integers(0, spec.Ho, 65536),
+                       rng.integers(0, spec.Wo, 65536)], axis=1).astype(np.int32)
+    ref_pts = oracle.conv3x3_at(x, wm, coords, bo, 1, 1, True)
+    pts = got[coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]].astype(np.float64)
+    rms = float(np.sqrt(np.mean(ref_first ** 2)))
+    assert np.max(np.abs(pts - ref_pts) / np.maximum(np.abs(ref_pts), rms)) <= tol
+    packed.free()
