@@ -494,6 +494,18 @@ def sweep_bench(args, torch, pc, L, stream):
             "config3_resnet50_batch1_fp16": short_sweep(torch, L.config3(1), stream, 50),
         }
         l1.packed.free()
+        # what the other modes of this file time, in brief (10 launches each, no host baseline): the backward pass,
+        # 1x1 layers grouped into 3x3 patterns, filter re-ordering on clustered connectivity, the channel-minor layout
+        import copy
+        b = copy.copy(args)
+        b.steps, b.warmup, b.only, b.keep = 10, 2, "", 0.28
+        out["beyond_the_forward_pass"] = {
+            "backward_vgg16_batch64_fp16": backward_bench(b, torch, pc, L, brief=True),
+            "clustered_connectivity_vgg16_batch64_fp16": clustered_bench(b, torch, pc, L, brief=True),
+            "channel_minor_layout_vgg16_batch64_fp16": nhwc_bench(b, torch, pc, L, brief=True),
+        }
+        b.keep = 0.3
+        out["beyond_the_forward_pass"]["conv1x1_resnet50_batch32_fp16"] = conv1x1_bench(b, torch, pc, L, brief=True)
     print(json.dumps(out), flush=True)
 
 
@@ -583,7 +595,7 @@ def admm_bench(args, torch, pc, L):
     print(json.dumps(out), flush=True)
 
 
-def nhwc_bench(args, torch, pc, L):
+def nhwc_bench(args, torch, pc, L, brief=False):
     """The default workload (config 4 at K, keep from the command line: nine VGG-16 shapes, batch 64, fp16) with
     channel-minor activations and outputs, x [N][H][W][C] and y [N][Ho][Wo][F] (PCONV_FLAG_NHWC), next to the same
     layers in the channel-major layout of the benchmark configuration.  The three-channel first layer is run with its
@@ -642,6 +654,9 @@ def nhwc_bench(args, torch, pc, L):
            "higher_is_better": True, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
            "config": {"workload": f"configs[4] at K={args.K}, keep {args.keep}, batch 64, x and y channel-minor (NHWC)"},
            "nchw_ms_per_step": t_nchw, "layers": rows}
+    if brief:
+        return {"us": t_nhwc * 1e3, "channel_major_us_same_run": t_nchw * 1e3, "eff_GMACs": macs / t_nhwc / 1e6,
+                "layers": {r["layer"]: round(r["nhwc_us"], 1) for r in rows}}
     if sample is not None:
         spec, x1, wm, b = sample
         t0, runs = time.perf_counter(), 0
@@ -655,7 +670,7 @@ def nhwc_bench(args, torch, pc, L):
     print(json.dumps(out), flush=True)
 
 
-def clustered_bench(args, torch, pc, L):
+def clustered_bench(args, torch, pc, L, brief=False):
     """What filter re-ordering buys on the matrix cores (pconv_filter_similarity_order + the channel lists of the
     matrix-core kernel).  Config 4's shapes from conv2_2 on at batch 64, fp16, K and keep from the command line, but
     with weights whose connectivity is clustered as in a trained, pruned model: filters in groups of 128 scattered
@@ -701,6 +716,12 @@ def clustered_bench(args, torch, pc, L):
         log(json.dumps(row))
         if sample is None:
             sample = (spec, base[:1], oracle.mask_weights(w, pid, mask, lib), bias)
+    if brief:
+        return {"own_order_us": t_nat, "similarity_order_us": t_ord, "eff_GMACs_similarity_order": macs / t_ord / 1e3,
+                "layers": {r["layer"]: {"own_order_us": round(r["own_order"]["us"], 1),
+                                        "similarity_order_us": round(r["similarity_order"]["us"], 1),
+                                        "blocks": [r["own_order"]["blocks"], r["similarity_order"]["blocks"], r["own_order"]["of"]]}
+                           for r in rows}}
     spec, x1, wm, b = sample
     t0, runs = time.perf_counter(), 0
     while time.perf_counter() - t0 < 8.0:
@@ -719,7 +740,7 @@ def clustered_bench(args, torch, pc, L):
     print(json.dumps(out), flush=True)
 
 
-def backward_bench(args, torch, pc, L):
+def backward_bench(args, torch, pc, L, brief=False):
     """Backward pass (include/pconv_backward.h) of config 4's nine VGG-16 shapes at batch 64, fp16 storage, K and keep
     from the command line: per layer one masked weight gradient (grad_weight_kernel + gather) and one input gradient
     (the forward kernel on the transposed layer; the first layer has none to hand back).  The weight gradient is a
@@ -765,6 +786,11 @@ def backward_bench(args, torch, pc, L):
         layer.packed.free()
         del layer, dy, ws, dw4
         torch.cuda.empty_cache()
+    if brief:
+        return {"grad_weight_us": tot_gw * 1e3, "grad_weight_executed_TFLOPs": flops_sum / tot_gw / 1e9,
+                "grad_weight_frac_of_fp16_mfma_peak": flops_sum / tot_gw / 1e9 / PEAK_FP16_MFMA_TFLOPS,
+                "grad_input_us": tot_gi * 1e3,
+                "layers": {r["layer"]: [round(r["grad_weight_us"], 1), round(r.get("grad_input_us", 0.0), 1)] for r in rows}}
     # the oracle on one image of the slowest layer, timed on the host
     spec, _, x1, g1 = worst
     t0, runs = time.perf_counter(), 0
@@ -786,7 +812,7 @@ def backward_bench(args, torch, pc, L):
     print(json.dumps(out), flush=True)
 
 
-def conv1x1_bench(args, torch, pc, L):
+def conv1x1_bench(args, torch, pc, L, brief=False):
     """The 1x1 convolutions of ResNet-50's bottleneck blocks (reduce and expand of each stage) at batch 32, fp16
     storage, grouped into 3x3 patterns (include/pconv_backward.h): K patterns, keep from the command line.  These
     layers move their activations once for C*F*4/9*keep multiply-adds per pixel: the roofline is HBM, algorithmic
@@ -825,6 +851,9 @@ def conv1x1_bench(args, torch, pc, L):
         if i == 0:
             sample = (name, x1[:1], w, pid, mask, b)
         p.free()
+    if brief:
+        return {"us": tot_ms * 1e3, "alg_GBs": tot_bytes / tot_ms / 1e6, "frac_of_8TBs": tot_bytes / tot_ms / 1e6 / PEAK_HBM_GBS,
+                "layers": {r["layer"]: round(r["us"], 1) for r in rows}}
     name, x1, w, pid, mask, b = sample
     t0, runs = time.perf_counter(), 0
     while time.perf_counter() - t0 < 5.0:
