@@ -262,7 +262,7 @@ size_t pconv_noalloc_scratch_bytes(void);
  *                     tile: 0 = chosen by the library, 1 = 128 filters x 448 output pixels, 2 = 64 x 448,
  *                     3 = 128 x 224, 4 = 64 x 224.  `rows` (0 = as many as fit) caps the output rows per tile;
  *                     slot_walk = 1 gives every tile a workgroup of its own instead of persistent workgroups that
- *                     walk over the tiles; channel_splits (0 = chosen by the library: 1, 2 or, at stride 1, 4;
+ *                     walk over the tiles; channel_splits (0 = chosen by the library: 1, 2, 4 or 8;
  *                     or 1, 2, 4, 8, 16, at most the number of 16-channel blocks) lets that many workgroups share a
  *                     tile, each with a part of the channel blocks: their partial sums meet in the handle's workspace
  *                     and are added in a fixed order (reproducible).  The library splits where a layer has fewer
@@ -271,6 +271,11 @@ size_t pconv_noalloc_scratch_bytes(void);
  *                     and runs the layer unsplit if a split of the library's own choosing does not fit there).
  *                     Non-finite activations reach every output whose 3x3 window holds them, also through weights
  *                     that are pruned (0 * inf), which the vector kernels skip.
+ *   split_reduce      PCONV_KERNEL_MFMA with channel_splits > 1: who adds the parts.  1 = the workgroup that arrives
+ *                     last at a tile reads the other parts back and stores the tile (one launch); 2 = every part only
+ *                     writes its partial sums and a second kernel adds them and stores (a launch more, but the parts
+ *                     are read by the whole chip: pays from about four parts on); 0 = chosen by the library's
+ *                     estimate.  Both add the parts in the same order: the results are equal bit for bit.
  * A combination the library has no kernel for returns PCONV_EUNSUPPORTED.
  */
 enum { PCONV_KERNEL_AUTO = 0, PCONV_KERNEL_TILED = 1, PCONV_KERNEL_GENERIC = 2, PCONV_KERNEL_QUAD = 3,
@@ -287,6 +292,7 @@ typedef struct pconv_tuning {
     int buffers;
     int slot_walk;
     int mfma_shape;
+    int split_reduce;
 } pconv_tuning;
 int pconv_conv3x3_tuned(const void* x, void* y, const pconv_packed* wp, const float* bias, int N, int H, int W,
                         int stride, int pad, unsigned flags, void* stream, const pconv_tuning* tuning);

@@ -39,7 +39,7 @@ class PconvError(RuntimeError):
 class _Tuning(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int), ("rows", ctypes.c_int), ("filters_per_wave", ctypes.c_int),
                 ("waves", ctypes.c_int), ("channels_per_wave", ctypes.c_int), ("channel_order", ctypes.c_int), ("channel_splits", ctypes.c_int), ("buffers", ctypes.c_int),
-                ("slot_walk", ctypes.c_int), ("mfma_shape", ctypes.c_int)]
+                ("slot_walk", ctypes.c_int), ("mfma_shape", ctypes.c_int), ("split_reduce", ctypes.c_int)]
 
 
 def ensure_built() -> str:
@@ -296,9 +296,9 @@ def noalloc_scratch_bytes() -> int:
 def conv3x3_tuned(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad: int = 1, flags: int = 0,
                   stream: int = 0, kernel: int = 0, rows: int = 0, filters_per_wave: int = 0, waves: int = 0,
                   channels_per_wave: int = 0, channel_order: int = 0, channel_splits: int = 0, buffers: int = 0,
-                  slot_walk: int = 0, mfma_shape: int = 0):
+                  slot_walk: int = 0, mfma_shape: int = 0, split_reduce: int = 0):
     t = _Tuning(kernel, rows, filters_per_wave, waves, channels_per_wave, channel_order, channel_splits, buffers,
-                slot_walk, mfma_shape)
+                slot_walk, mfma_shape, split_reduce)
     _check(_load().pconv_conv3x3_tuned(_dp(x), _dp(y), wp.handle, _dp(bias), N, H, W, stride, pad, flags,
                                        stream or None, ctypes.byref(t)), "pconv_conv3x3_tuned")
 

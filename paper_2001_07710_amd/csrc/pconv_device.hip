@@ -2238,7 +2238,7 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
     // (batch 1, small maps with many channels) stay with the vector kernels, whose channel split fills the GPU.
     const bool all_auto = !tuning || (tuning->rows == 0 && tuning->filters_per_wave == 0 && tuning->waves == 0 &&
                                       tuning->channels_per_wave == 0 && tuning->channel_order == 0 &&
-                                      tuning->channel_splits == 0 && tuning->buffers == 0);
+                                      tuning->channel_splits == 0 && tuning->buffers == 0 && tuning->split_reduce == 0);
     if (kernel == PCONV_KERNEL_MFMA || (kernel == PCONV_KERNEL_AUTO && wp->dtype == PCONV_F16 && all_auto)) {
         const bool forced = kernel == PCONV_KERNEL_MFMA;
         if (wp->dtype != PCONV_F16) return PCONV_EUNSUPPORTED;
@@ -2255,7 +2255,9 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         // tile shape and number of workgroups per tile (each with a part of the channel blocks), where not given
         double best_us = -1.0;
         const int want_shape = a.shape, want_splits = tuning ? tuning->channel_splits : 0;
-        if (want_splits < 0) return PCONV_EINVAL;
+        const int want_reduce = tuning ? tuning->split_reduce : 0;
+        int best_sp = 0;
+        if (want_splits < 0 || want_reduce < 0 || want_reduce > 2) return PCONV_EINVAL;
         for (int sh = 1; sh <= kMfmaShapes; ++sh) {
             if (want_shape && sh != want_shape) continue;
             // (A split pays where a layer has fewer tiles than compute units and many channel blocks in sequence --
@@ -2263,23 +2265,32 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
             // four at 7x7 -- and costs the round trip of MT x NT floats per part otherwise: the 64 -> 64 layer at
             // 56x56 goes from 17 to 53 us in two parts.  The estimate carries both.  Not asked for, the choice is
             // between 1, 2 and, at stride 1, 4 parts: more lost on every shape measured.)
-            for (int ks = 1; ks <= 16; ks *= 2) {
-                // (layers of one or two taps have channel blocks too short to hide their loads: more parts in flight)
-                const int most = a.n_taps <= 2 ? 16 : stride == 2 ? 2 : 4;
-                if (want_splits ? ks != want_splits : ks > most) continue;
-                // (the weights kept for this shape's tile height say whether its tiles have channel lists)
-                for (const MfmaWeights& m : wp->mfma)
-                    if (m.mt == mfma_shape_height(sh)) {
-                        a.d_clist = m.d_clist; a.d_tinfo = m.d_tinfo;
-                        a.min_blocks = m.min_blocks; a.total_blocks = m.total_blocks;
+            for (int ks = 1; ks <= 16; ks *= 2)
+                for (int sp = 0; sp <= (ks > 1 ? 1 : 0); ++sp) {
+                    // sp = 1: the parts are added by a second kernel, which lets more of them pay: up to 8 (layers
+                    // of one or two taps, whose blocks are too short to hide their loads: 16); added by the last
+                    // arriver: 2 or, at stride 1, 4
+                    if (want_reduce && ks > 1 && sp != want_reduce - 1) continue;
+                    const int most = a.n_taps <= 2 ? 16 : sp ? 8 : stride == 2 ? 2 : 4;
+                    if (want_splits ? ks != want_splits : ks > most) continue;
+                    // (the weights kept for this shape's tile height say whether its tiles have channel lists)
+                    for (const MfmaWeights& m : wp->mfma)
+                        if (m.mt == mfma_shape_height(sh)) {
+                            a.d_clist = m.d_clist; a.d_tinfo = m.d_tinfo;
+                            a.min_blocks = m.min_blocks; a.total_blocks = m.total_blocks;
+                        }
+                    a.second_pass = sp;
+                    const double t = mfma_estimate_us(a, sh, ks);
+                    if (t >= 0.0 && (best_us < 0.0 || t < best_us)) {
+                        best_us = t; a.shape = sh; a.splits = ks; best_sp = sp;
                     }
-                const double t = mfma_estimate_us(a, sh, ks);
-                if (t >= 0.0 && (best_us < 0.0 || t < best_us)) { best_us = t; a.shape = sh; a.splits = ks; }
-            }
+                }
         }
+        a.second_pass = best_sp;
         if (best_us < 0.0) {
             a.shape = want_shape;                // (nothing fits: launch_mfma_conv says so)
             a.splits = want_splits ? want_splits : 1;
+            a.second_pass = want_reduce == 2 ? 1 : 0;
         }
         bool take = best_us >= 0.0 || forced;
         if (take && !forced) {
@@ -2310,6 +2321,7 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
                     // the entry point that allocates nothing: the same tile shape, unsplit)
                     if (rc == PCONV_ESCRATCH && !want_splits) {
                         a.splits = 1;
+                        a.second_pass = 0;
                         a.ws = nullptr;
                         a.counters = nullptr;
                         rc = PCONV_OK;

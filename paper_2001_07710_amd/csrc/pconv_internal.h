@@ -147,6 +147,7 @@ struct MfmaConv {
     int rows;                   // 0: as many output rows per tile as fit; else that many
     int walk;                   // 1: one workgroup per tile; otherwise persistent workgroups that walk over the tiles
     int splits;                 // workgroups per tile, each with a part of the channel blocks (1: no split)
+    int second_pass;            // splits > 1: the parts are added and stored by a second kernel, not by the last arriver
     float* ws;                  // splits > 1: workspace of mfma_workspace() floats
     unsigned* counters;         // splits > 1: mfma_workspace() counters, zero
 };

@@ -124,6 +124,7 @@ struct MfmaParams {
     int P;                       // nhwc: 1 KB pieces (64 positions) per half of a staged block: ceil(max_slots * PW / 64)
     FastDiv div_PW;
     int KS;                      // workgroups that share one tile, each taking a contiguous range of the channel blocks
+    int second_pass;             // KS > 1: every part only writes its partial sums; mfma_split_reduce_kernel adds and stores
     int win_alias;               // the epilogue's windows lie in the staging buffer that is free meanwhile: 1 = its
                                  // weights, 2 = its activations; 0 = in a place of their own behind the bias
     int a_stages;                // 2; or 1: the layer has a single block of weights, staged once per workgroup
@@ -726,6 +727,9 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
                     v.w = __builtin_bit_cast(unsigned, (float)acc[af][bf][rq * 4 + 3]);
                     __builtin_amdgcn_raw_buffer_store_b128(v, wsr, off(g.split, af, bf, rq), 0, kDeviceScope);
                 }
+        // (added and stored by a second kernel: nothing to wait for or to count here -- the end of this kernel is what
+        // makes the parts visible)
+        if (p.second_pass) return false;
         __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): the partial sums have left
         __syncthreads();
         unsigned* const flag = reinterpret_cast<unsigned*>(lds + p.flag_off);
@@ -892,6 +896,61 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     }
 }
 
+// Second pass of a split layer (MfmaParams::second_pass): the KS parts of every tile, which lie in the workspace as the
+// accumulators held them ([tile][part][wave][filter block][pixel block][four rows][lane][4]), added in the order of
+// the parts (the first of which started from the bias); ReLU, fp16, store.  One thread per 16 bytes of a part: lane `lane` of wave
+// `wave` holds, for pixel (lane % 32) of its pixel block, the four filters 8*rq + 4*(lane/32) + 0..3 of its filter block.
+// Every workgroup of the first pass took part, so the sum needs neither counters nor an order of arrival, and however
+// many parts there are they are read at the rate of a copy (the last arriver of the other form reads them alone).
+struct ReduceParams {
+    const float* ws;
+    unsigned char* y;
+    int N, F, Ho, Wo, relu, nhwc;
+    int KS, R, tiles_m;
+    int AF, BF, WM, WN;
+    long long threads;      // tiles * NW * AF * BF * 4 * 64
+};
+__global__ __launch_bounds__(256) void mfma_split_reduce_kernel(const ReduceParams p) {
+    typedef float float4v __attribute__((ext_vector_type(4)));
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= p.threads) return;
+    const int lane = (int)(t & 63);
+    long long r = t >> 6;
+    const int rq = (int)(r & 3); r >>= 2;
+    const int bf = (int)(r % p.BF); r /= p.BF;
+    const int af = (int)(r % p.AF); r /= p.AF;
+    const int NW = p.WM * p.WN;
+    const int wave = (int)(r % NW);
+    const long long tile = r / NW;
+    const int wm = wave / p.WN, wn = wave - wm * p.WN;
+    const int MT = p.WM * p.AF * 32;
+    const long long part4 = (long long)NW * p.AF * p.BF * 4 * 64;                 // float4s per part
+    const long long at = t - tile * part4;                                          // this thread's float4 within a part
+    const float4v* const w4 = reinterpret_cast<const float4v*>(p.ws) + tile * p.KS * part4 + at;
+    const int tm = (int)(tile % p.tiles_m);
+    const long long tn = tile / p.tiles_m;
+    const int f0 = tm * MT + (wm * p.AF + af) * 32 + rq * 8 + (lane >> 5) * 4;
+    // (the first part started from the bias; the same additions in the same order as the last arriver of the other form)
+    float4v sum = w4[0];
+    for (int k = 1; k < p.KS; ++k) sum += w4[(long long)k * part4];
+    // the pixel: number q of the tile's R rows of the batch
+    const int q = (wn * p.BF + bf) * 32 + (lane & 31);
+    const int row = q / p.Wo, ox = q - row * p.Wo;
+    const long long rr = tn * p.R + row;
+    if (row >= p.R || rr >= (long long)p.N * p.Ho) return;
+    const long long n = rr / p.Ho;
+    const int oy = (int)(rr - n * p.Ho);
+    _Float16* const y = reinterpret_cast<_Float16*>(p.y);
+    for (int i = 0; i < 4; ++i) {
+        if (f0 + i >= p.F) break;
+        float v = sum[i];
+        if (p.relu) v = v > 0.f ? v : 0.f;
+        const long long idx = p.nhwc ? (((n * p.Ho + oy) * p.Wo + ox) * p.F + f0 + i)
+                                     : (((n * p.F + f0 + i) * p.Ho + oy) * p.Wo + ox);
+        y[idx] = (_Float16)v;
+    }
+}
+
 // dense OIHW fp16 weights on the device -> MfmaWeights order, all nine taps
 __global__ __launch_bounds__(256) void mfma_arrange_kernel(const unsigned short* __restrict__ w, unsigned short* __restrict__ out,
                                                            int F, int C, int mt, int CB, long long total) {
@@ -991,6 +1050,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     // (channel-minor activations are loaded eight channels at a time as they lie: no channel lists, whole groups)
     if (a.nhwc && (a.d_clist || a.C % 8 || a.F % 8)) return false;
     p.KS = a.splits < 1 ? 1 : a.splits;
+    p.second_pass = (p.KS > 1 && a.second_pass) ? 1 : 0;
     // (every part of a split tile has at least one block: the sequence of (tile, block) pairs has no empty member)
     if (p.KS > (a.d_clist ? a.min_blocks : p.CB) || p.KS > 64) return false;
     p.div_KS = make_fastdiv((unsigned)p.KS);
@@ -1190,7 +1250,10 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     const double part_bytes = (double)tiles * (kShapes[shape - 1].wm * kShapes[shape - 1].af * 32) *
                               (kShapes[shape - 1].wn * kShapes[shape - 1].bf * 32) * 4.0;
     // (fitted to ResNet-50's 14 x 14 and 7 x 7 layers at batch 32 in 2, 4 and 8 parts)
-    const double split_us = p.KS > 1 ? 4.0 + 1.5 * (p.KS - 1) + part_bytes / 1.8e6 : 0.0;
+    // (second pass: a launch, and the parts written once and read once -- fitted to ResNet-50's 3x3 and 1x1 layers
+    // at batch 32: 4.5 TB/s, the parts of such layers staying in the memory-side cache)
+    const double split_us = p.KS <= 1 ? 0.0 : a.second_pass ? 4.0 + 2.0 * part_bytes / 4.5e6
+                                                             : 4.0 + 1.5 * (p.KS - 1) + part_bytes / 1.8e6;
     if (p.nt < 9) block_us *= (double)std::max(p.nt, 1) / 9.0;
     return rounds * (tile_us + blocks * std::max(block_us, floor_us)) + split_us;
 }
@@ -1217,13 +1280,27 @@ int launch_mfma_conv(const MfmaConv& a, void* stream) {
     if (shape < 0 || shape >= kMfmaShapes) return PCONV_EUNSUPPORTED;
     if (!plan(a, shape, a.rows, &p, &lw, &ki, &lds, &grid)) return PCONV_EUNSUPPORTED;
     if (p.KS > 1 && (!p.ws || !p.counters)) return PCONV_EINVAL;
+    int rc = PCONV_EUNSUPPORTED;
     switch (shape) {
-        case 0: return launch_shape<2, 7, 2, 2>(p, lw, ki, lds, a.walk, kBlockUs[0], st);
-        case 1: return launch_shape<1, 7, 2, 2>(p, lw, ki, lds, a.walk, kBlockUs[1], st);
-        case 2: return launch_shape<1, 7, 4, 1>(p, lw, ki, lds, a.walk, kBlockUs[2], st);
-        case 3: return launch_shape<1, 7, 2, 1>(p, lw, ki, lds, a.walk, kBlockUs[3], st);
+        case 0: rc = launch_shape<2, 7, 2, 2>(p, lw, ki, lds, a.walk, kBlockUs[0], st); break;
+        case 1: rc = launch_shape<1, 7, 2, 2>(p, lw, ki, lds, a.walk, kBlockUs[1], st); break;
+        case 2: rc = launch_shape<1, 7, 4, 1>(p, lw, ki, lds, a.walk, kBlockUs[2], st); break;
+        case 3: rc = launch_shape<1, 7, 2, 1>(p, lw, ki, lds, a.walk, kBlockUs[3], st); break;
     }
-    return PCONV_EUNSUPPORTED;
+    if (rc != PCONV_OK || !p.second_pass) return rc;
+    const Shape& sh = kShapes[shape];
+    ReduceParams r{};
+    r.ws = p.ws;
+    r.y = p.y;
+    r.N = p.N; r.F = p.F; r.Ho = p.Ho; r.Wo = p.Wo; r.relu = p.relu; r.nhwc = p.nhwc;
+    r.KS = p.KS; r.R = p.R; r.tiles_m = p.tiles_m;
+    r.AF = sh.af; r.BF = sh.bf; r.WM = sh.wm; r.WN = sh.wn;
+    r.threads = (long long)p.tiles_n * p.tiles_m * (sh.wm * sh.wn) * sh.af * sh.bf * 4 * 64;
+    const long long blocks = (r.threads + 255) / 256;
+    if (blocks > 0x7FFFFFFF) return PCONV_EUNSUPPORTED;
+    hipLaunchKernelGGL(mfma_split_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, r);
+    PCONV_HIP(hipGetLastError());
+    return PCONV_OK;
 }
 
 int launch_mfma_arrange(const void* w_oihw, void* out, int F, int C, int mt, void* stream) {

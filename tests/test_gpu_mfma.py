@@ -65,6 +65,8 @@ def test_every_tile_shape(case):
     # the channel blocks of every tile split over two or four workgroups (refused where there are fewer blocks)
     forms += [dict(kernel=M, mfma_shape=sh, channel_splits=ks) for sh in (1, 2, 4) for ks in (2, 4)]
     forms += [dict(kernel=M, channel_splits=2), dict(kernel=M, mfma_shape=3, channel_splits=2, slot_walk=1)]
+    # ... with the parts added by the second kernel instead of by the last arriver
+    forms += [dict(kernel=M, mfma_shape=sh, channel_splits=ks, split_reduce=2) for sh in (1, 2, 3, 4) for ks in (2, 4)]
     run_forms(layer, x, forms)
     run_forms(layer, x, [dict(kernel=M)], relu=True)
     layer.free()
@@ -135,6 +137,35 @@ def test_split_channel_blocks_are_bit_reproducible_and_match_the_oracle():
         assert rel_err(first, ref) <= TOL["f16"], t
         for _ in range(40):
             assert np.array_equal(layer.run(x, canary=False, **t).view(np.uint16), first.view(np.uint16)), t
+    layer.free()
+
+
+def test_parts_added_by_a_second_kernel_equal_the_last_arrivers_sum_bit_for_bit():
+    """Both ways of adding the parts of a split tile add them in the order of the parts, starting from the part that
+    started from the bias: equal outputs bit for bit, with and without ReLU, channel-major and channel-minor; and the
+    oracle is met."""
+    import torch
+    spec = L.LayerSpec(cfg=21, idx=7, name="splitk2", N=9, C=256, F=136, H=7, W=14, dtype="f16", K=8, keep=0.3)
+    layer = GpuLayer(spec)
+    x = L.gen_activations(spec)
+    for relu in (False, True):
+        ref = layer.oracle(x, relu)
+        for sh, ks in ((1, 2), (2, 8), (3, 4), (4, 16), (4, 3)):
+            say("second pass", sh, ks, relu)
+            a = layer.run(x, relu, kernel=M, mfma_shape=sh, channel_splits=ks, split_reduce=1)
+            b = layer.run(x, relu, kernel=M, mfma_shape=sh, channel_splits=ks, split_reduce=2)
+            assert np.array_equal(a.view(np.uint16), b.view(np.uint16)), (sh, ks, relu)
+            assert rel_err(b, ref) <= TOL["f16"]
+    # channel-minor outputs of the second kernel
+    s = spec
+    dx = torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1))).cuda()
+    dy = torch.full((s.N, s.Ho, s.Wo, s.F), -7.0, dtype=torch.float16, device="cuda")
+    pc.conv3x3_tuned(dx, dy, layer.packed, layer.d_bias, s.N, s.H, s.W, 1, 1, pc.FLAG_NHWC | pc.FLAG_RELU,
+                     torch.cuda.current_stream().cuda_stream, kernel=M, mfma_shape=4, channel_splits=4, split_reduce=2)
+    torch.cuda.synchronize()
+    assert rel_err(dy.cpu().numpy().transpose(0, 3, 1, 2), layer.oracle(x, True)) <= TOL["f16"]
+    with pytest.raises(pc.PconvError):
+        layer.run(x, kernel=M, split_reduce=3)
     layer.free()
 
 
