@@ -106,6 +106,18 @@ int pconv_pack(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib,
 int pconv_packed_export(const pconv_packed* p, uint32_t* filter_order, uint32_t* grp_ptr, uint16_t* cin, void* w4,
                         size_t* n_kept);
 
+/*
+ * A packed layer from its canonical form (the arrays pconv_packed_export writes, all host pointers, not kept after the
+ * call; lib and K as in pconv_pack, dtype the type of w4): the stored form of a pruned layer (section 6.2's compact
+ * weight storage) read back.  The handle is the one pconv_pack makes from the weights the arrays describe, so
+ * pconv_packed_export of it returns the same arrays bit for bit when they were canonical; filter_order may be any
+ * permutation of the filters (it is put into the canonical order).  PCONV_EINVAL for a filter_order that is no
+ * permutation, a grp_ptr that does not start at 0 or descends, a channel >= C, channels that do not ascend inside a
+ * group or come twice in one filter; the other codes as pconv_pack.  flags: 0 or PCONV_PACK_HOST_ONLY.
+ */
+int pconv_packed_import(const uint32_t* filter_order, const uint32_t* grp_ptr, const uint16_t* cin, const void* w4,
+                        int dtype, int F, int C, const uint16_t* lib, int K, unsigned flags, pconv_packed** out);
+
 /* Shape of a packed layer; any output pointer may be NULL. */
 int pconv_packed_stats(const pconv_packed* p, int* F, int* C, int* K, int* dtype, size_t* n_kept);
 

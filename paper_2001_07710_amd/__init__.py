@@ -63,6 +63,8 @@ def _load():
     lib.pconv_select_connectivity.argtypes = [vp, i, i, vp, i, vp, ctypes.c_double, vp]
     lib.pconv_pack.argtypes = [vp, i, i, i, vp, i, vp, vp, u, ctypes.POINTER(vp)]
     lib.pconv_packed_export.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.pconv_packed_import.argtypes = [vp, vp, vp, vp, i, i, i, vp, i, u, ctypes.POINTER(vp)]
+    lib.pconv_packed_import.restype = i
     lib.pconv_packed_stats.argtypes = [vp, ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i), ctypes.POINTER(i),
                                        ctypes.POINTER(ctypes.c_size_t)]
     lib.pconv_packed_balance.argtypes = [vp, i, i, i, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -267,6 +269,23 @@ def packed_export(p: Packed):
            "pconv_packed_export")
     assert nk.value == n
     return fo, gp, cin, w4
+
+
+def packed_import(filter_order, grp_ptr, cin, w4, F: int, C: int, lib, flags: int = 0) -> Packed:
+    """A packed layer from the arrays packed_export returns; w4's dtype (float32 or float16) is the layer's."""
+    fo = np.ascontiguousarray(filter_order, dtype=np.uint32)
+    gp = np.ascontiguousarray(grp_ptr, dtype=np.uint32)
+    ci = np.ascontiguousarray(cin, dtype=np.uint16)
+    w4 = np.ascontiguousarray(w4)
+    lb = np.ascontiguousarray(lib, dtype=np.uint16)
+    code = _dtype_code(w4.dtype)
+    if fo.size != F or gp.size != F * lb.size + 1 or ci.size < int(gp[-1]) or w4.size < 4 * int(gp[-1]):
+        raise ValueError("array sizes do not fit F, K and grp_ptr's last entry")
+    out = ctypes.c_void_p(None)
+    _check(_load().pconv_packed_import(_hp(fo), _hp(gp), _hp(ci) if ci.size else None, _hp(w4) if w4.size else None,
+                                       code, F, C, _hp(lb), int(lb.size), flags, ctypes.byref(out)),
+           "pconv_packed_import")
+    return Packed(out.value, F, C, int(lb.size), w4.dtype)
 
 
 def conv3x3(x, y, wp: Packed, bias, N: int, H: int, W: int, stride: int = 1, pad: int = 1, flags: int = 0,

@@ -708,6 +708,62 @@ extern "C" int pconv_packed_export(const pconv_packed* p, uint32_t* filter_order
     return PCONV_OK;
 }
 
+// The inverse of pconv_packed_export: the canonical arrays are checked, spread back into a dense masked tensor with its
+// pattern ids and connectivity mask, and packed again, so that an imported layer is in every respect the layer that
+// pconv_pack would have made from the original weights.
+extern "C" int pconv_packed_import(const uint32_t* filter_order, const uint32_t* grp_ptr, const uint16_t* cin,
+                                   const void* w4, int dtype, int F, int C, const uint16_t* lib, int K,
+                                   unsigned flags, pconv_packed** out) {
+    if (!out) return PCONV_EINVAL;
+    *out = nullptr;
+    if (!filter_order || !grp_ptr) return PCONV_EINVAL;
+    if (dtype != PCONV_F32 && dtype != PCONV_F16) return PCONV_EINVAL;
+    if (int rc = check_library(lib, K)) return rc;
+    if (int rc = check_fc(F, C)) return rc;
+    const size_t esize = dtype == PCONV_F16 ? 2 : 4;
+    const size_t n_groups = (size_t)F * K;
+    const size_t n_kept = grp_ptr[n_groups];
+    if (grp_ptr[0] != 0 || n_kept > (size_t)F * C) return PCONV_EINVAL;
+    for (size_t g = 0; g < n_groups; ++g)
+        if (grp_ptr[g] > grp_ptr[g + 1]) return PCONV_EINVAL;
+    if (n_kept && (!cin || !w4)) return PCONV_EINVAL;
+    try {
+        std::vector<unsigned char> seen((size_t)F, 0);
+        for (int i = 0; i < F; ++i) {
+            if (filter_order[i] >= (uint32_t)F || seen[filter_order[i]]) return PCONV_EINVAL;
+            seen[filter_order[i]] = 1;
+        }
+        std::vector<int> taps((size_t)K * 4);
+        for (int j = 0; j < K; ++j) {
+            int n = 0;
+            for (int t = 0; t < 9; ++t)
+                if (lib[j] >> t & 1) taps[(size_t)j * 4 + n++] = t;
+        }
+        std::vector<unsigned char> w((size_t)F * C * 9 * esize, 0);
+        std::vector<uint8_t> pid((size_t)F * C, 0), mask((size_t)F * C, 0);
+        const unsigned char* src = static_cast<const unsigned char*>(w4);
+        for (int i = 0; i < F; ++i) {
+            const size_t f = filter_order[i];
+            for (int j = 0; j < K; ++j) {
+                const size_t a = grp_ptr[(size_t)i * K + j], b = grp_ptr[(size_t)i * K + j + 1];
+                for (size_t e = a; e < b; ++e) {
+                    const size_t c = cin[e];
+                    // inside a group channels ascend; over the groups of a filter no channel comes twice
+                    if (c >= (size_t)C || (e > a && cin[e - 1] >= c) || mask[f * C + c]) return PCONV_EINVAL;
+                    mask[f * C + c] = 1;
+                    pid[f * C + c] = (uint8_t)j;
+                    for (int k = 0; k < 4; ++k)
+                        std::memcpy(&w[((f * C + c) * 9 + taps[(size_t)j * 4 + k]) * esize], src + (e * 4 + k) * esize,
+                                    esize);
+                }
+            }
+        }
+        return pack_impl(w.data(), dtype, F, C, lib, K, pid.data(), mask.data(), flags, false, true, out);
+    } catch (const std::bad_alloc&) {
+        return PCONV_ENOMEM;
+    }
+}
+
 extern "C" int pconv_packed_balance(const pconv_packed* p, int waves, int filters_per_wave, int balanced,
                                     double* mean_per_wave, double* mean_of_max) {
     if (!p || !mean_per_wave || !mean_of_max) return PCONV_EINVAL;
