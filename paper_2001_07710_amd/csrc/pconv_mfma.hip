@@ -25,6 +25,8 @@
 //   weights      [tap slot][half: channels 0-7 | 8-15][filter in tile][8 channels]   as they lie in global memory,
 //                                                                                    copied by buffer_load ... lds
 //   activations  [half][input row slot][position = column + pad][8 channels]         channel-minor, 16 B per position
+//                (channel-minor tensors: [input row slot][position][half][8 channels], 32 B per position, as their
+//                 loads deliver them)
 // A lane's operand (8 consecutive channels of one filter, or of one pixel) is one 128-bit LDS read; lanes that are
 // neighbours in the filter or pixel index read neighbouring 16-byte pieces, so the reads are free of bank
 // conflicts, and a tap is nothing but a constant added to the pixel's byte offset: stride 2, either padding and any
@@ -105,7 +107,7 @@ struct MfmaParams {
     int N, C, F, H, W, Ho, Wo, stride, pad, relu;
     int CB;                 // channel blocks of 16
     int nt;                 // tap slots
-    int tap_off[9];         // byte offset of a tap inside an activation plane: (ky*PW + kx) * 16
+    int tap_off[9];         // byte offset of a tap inside an activation plane: (ky*PW + kx) * 16 (channel-minor: * 32)
     int R;                  // output rows (of the batch, n*Ho + oy) per tile
     int PW;                 // positions per input row slot: W + 2*pad, or more (plan())
     int max_slots;          // input row slots reserved per buffer
@@ -315,13 +317,16 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     auto stage_descriptors = [&](const TileGeo& g) {
         stage_wb = g.wb;
         if constexpr (NHWC) {
-            // load `id` of a block = piece id % P of half id / P; piece k holds positions 64k .. 64k+63 of the
-            // half's [row slot][position] array; wave w issues loads w, w + NW, ...
+            // load `id` of a block = positions 32 id .. 32 id + 31 of the [row slot][position] array, both halves:
+            // a pair of neighbouring lanes takes the 32 consecutive bytes of one pixel's sixteen channels, so LDS
+            // holds [position][half][8 channels] and the load touches 32 memory lines, not 64 (with one half per
+            // load, 16 bytes per line and lane, the address unit's line rate bound the 64-channel layers); wave w
+            // issues loads w, w + NW, ...
 #pragma unroll
             for (int i = 0; i < kAL; ++i) {
                 const int id = wave + i * NW;
-                const int half = id >= p.P ? 1 : 0, k = id - half * p.P;
-                const unsigned q = (unsigned)(k * 64 + lane);
+                const int half = lane & 1;
+                const unsigned q = (unsigned)(id * 32 + (lane >> 1));
                 const unsigned sl = fastdiv(q, p.div_PW), pos = q - sl * (unsigned)PW;
                 const int col = (int)pos - p.pad;
                 agoff[i] = kInvalid;
@@ -404,10 +409,9 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
           if constexpr (NHWC) {
             const int id = wave + j * NW;
             if (id < 2 * p.P) {
-                const int half = id >= p.P ? 1 : 0, k = id - half * p.P;
                 const __amdgpu_buffer_rsrc_t xr =
                     make_rsrc(reinterpret_cast<const void*>(((unsigned long long)xb_hi << 32) | xb_lo), x_records);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr)(ldsB + (buf * 2 + half) * p.plane_bytes + k * 1024),
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr)(ldsB + buf * 2 * p.plane_bytes + id * 1024),
                                                          16, (int)(stage_on ? agoff[j] : kInvalid), cb * 32, 0, 0);
             }
           } else {
@@ -470,7 +474,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
                 const int slot = sg == 0 ? (int)r * s : g.cnt0 + ((int)sg - 1) * p.cnt_full + (int)oy * s;
                 off = (slot * PW + (int)ox * s) * 16;
             }
-            boff[bf] = off + lk * p.plane_bytes;
+            boff[bf] = NHWC ? off * 2 + lk * 16 : off + lk * p.plane_bytes;
         }
     };
 
@@ -1089,7 +1093,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         p.max_slots = (R - segs) * a.stride + 3 * segs;
         p.a_bytes = p.nt * 2 * MT * 16;
         p.plane_bytes = p.max_slots * p.PW * 16;
-        // (channel-minor activations arrive in wave-wide pieces of 64 positions: a half's buffer is whole pieces)
+        // (channel-minor activations arrive in wave-wide pieces of 32 positions, both halves: a stage is 2 P pieces)
         p.P = (p.max_slots * p.PW + 63) / 64;
         if (a.nhwc) p.plane_bytes = p.P * 1024;
         // (a layer of at most 16 channels and one tile of filters has a single block of weights: staged once)
@@ -1143,7 +1147,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.tiles_m = (a.F + MT - 1) / MT;
     p.sw = (a.Wo % 8 == 0 && ya % 16 == 0) ? 8 : (a.Wo % 4 == 0 && ya % 8 == 0) ? 4 : (a.Wo % 2 == 0 && ya % 4 == 0) ? 2 : 1;
     p.sw_groups = a.Wo / p.sw;
-    for (int t = 0; t < p.nt; ++t) p.tap_off[t] = ((a.taps[t] / 3) * p.PW + a.taps[t] % 3) * 16;
+    for (int t = 0; t < p.nt; ++t) p.tap_off[t] = ((a.taps[t] / 3) * p.PW + a.taps[t] % 3) * (a.nhwc ? 32 : 16);
     p.x_bytes = (unsigned long long)a.N * a.C * a.H * a.W * 2ull;
     p.chan_bytes = (unsigned)((size_t)a.H * a.W * 2);
     const unsigned long long img = (unsigned long long)a.C * a.H * a.W * 2ull;
