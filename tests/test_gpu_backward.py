@@ -162,3 +162,37 @@ def test_grouped_1x1_layer(case):
         err = rel_err(d_y.cpu().numpy(), ref)
         assert err <= TOL[dt], (case, relu, err)
     p.free()
+
+
+C1_FULL = [("s1_expand", 64, 256, 56), ("s3_reduce", 1024, 256, 14), ("s4_reduce", 2048, 512, 7), ("s4_expand", 512, 2048, 7)]
+
+
+@pytest.mark.parametrize("case", C1_FULL, ids=[c[0] for c in C1_FULL])
+def test_grouped_1x1_layer_at_benchmark_shapes(case):
+    """The bottleneck layers as bench.py --conv1x1 times them (batch 32, keep 0.3, the library's own choice of kernel,
+    channel parts and who adds them): the first and the last image whole against the oracle."""
+    import torch
+    name, C, F, H = case
+    say("conv1x1 at batch 32", case)
+    N = 32
+    rng = np.random.default_rng(700 + C1_FULL.index(case))
+    lib = _spec(0, 1, 1, 1, 1, 1, "f16").library()
+    G = (C + 8) // 9
+    w = (rng.standard_normal((F, C)) * np.sqrt(2.0 / C)).astype(np.float16)
+    b = (rng.standard_normal(F) * 0.1).astype(np.float32)
+    x4 = np.maximum(rng.standard_normal((4, C, H, H)), 0).astype(np.float16)
+    pid = rng.integers(0, len(lib), size=(F, G)).astype(np.uint8)
+    mask = (rng.random((F, G)) < 0.3).astype(np.uint8)
+    p = pc.pack_1x1(w, lib, pid, mask)
+    d_x = torch.from_numpy(np.concatenate([x4] * (N // 4), axis=0)).cuda()
+    d_b = torch.from_numpy(b).cuda()
+    d_y = torch.full((N, F, H, H), -777.0, dtype=torch.float16, device="cuda")
+    pc.conv1x1(d_x, d_y, p, d_b, N, H, H, 1, pc.FLAG_RELU, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = d_y.cpu().numpy()
+    ref = oracle.conv1x1(x4, w, pid, mask, lib, b, 1, True)
+    assert rel_err(got[0], ref[0]) <= TOL["f16"]
+    assert rel_err(got[N - 1], ref[3]) <= TOL["f16"]
+    # every image is one of the four: the batch's other images against the first four, bit for bit
+    assert all(got[n].tobytes() == got[n % 4].tobytes() for n in range(4, N))
+    p.free()
