@@ -2251,7 +2251,19 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         a.rows = tuning ? tuning->rows : 0;
         a.walk = tuning ? tuning->slot_walk : 0;
         if (a.shape < 0 || a.shape > kMfmaShapes) return PCONV_EINVAL;
-        if (!wp->mfma.empty()) a.n_taps = wp->mfma[0].n_taps;
+        // (a 1x1 layer on a map of 9 to 16 columns: the copy of its weights with channel ranges in the place of
+        // taps, if the layer has one -- half as many blocks, each twice as deep; channel-major tensors only.
+        // Measured at batch 32: 1024 -> 256 channels at 14 x 14 44 -> 37 us, 256 -> 1024 37 -> 30; at 7 x 7, where a
+        // lane stages one-pixel pieces, level)
+        a.groups = 1;
+        if (wp->is_1x1 && W > 8 && W <= 16 && !nhwc)
+            for (const MfmaWeights& m : wp->mfma)
+                if (m.groups > 1) a.groups = m.groups;
+        for (const MfmaWeights& m : wp->mfma)
+            if (m.groups == a.groups) {
+                a.n_taps = m.n_taps;
+                break;
+            }
         // tile shape and number of workgroups per tile (each with a part of the channel blocks), where not given
         double best_us = -1.0;
         const int want_shape = a.shape, want_splits = tuning ? tuning->channel_splits : 0;
@@ -2275,7 +2287,7 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
                     if (want_splits ? ks != want_splits : ks > most) continue;
                     // (the weights kept for this shape's tile height say whether its tiles have channel lists)
                     for (const MfmaWeights& m : wp->mfma)
-                        if (m.mt == mfma_shape_height(sh)) {
+                        if (m.mt == mfma_shape_height(sh) && m.groups == a.groups) {
                             a.d_clist = m.d_clist; a.d_tinfo = m.d_tinfo;
                             a.min_blocks = m.min_blocks; a.total_blocks = m.total_blocks;
                         }
@@ -2308,7 +2320,7 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         int rc = PCONV_EUNSUPPORTED;
         if (take)
             for (const MfmaWeights& m : wp->mfma) {
-                if (!m.d_w || m.mt != mfma_shape_height(a.shape)) continue;
+                if (!m.d_w || m.mt != mfma_shape_height(a.shape) || m.groups != a.groups) continue;
                 a.d_w = m.d_w; a.mt = m.mt; a.n_taps = m.n_taps;
                 a.d_clist = m.d_clist; a.d_tinfo = m.d_tinfo;
                 a.min_blocks = m.min_blocks; a.total_blocks = m.total_blocks; a.w_bytes = m.bytes();

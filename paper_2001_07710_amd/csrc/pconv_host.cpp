@@ -242,11 +242,12 @@ void build_balanced(const pconv_packed* p, int fw, int nf, int cc, pconv::Balanc
 
 // The layer's weights in matrix-core order for workgroup tiles of mt filters (see pconv::MfmaWeights), from the
 // canonical arrays.  fp16 storage only: the 16-bit patterns are copied as they are.
-void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) {
+void build_mfma_weights(const pconv_packed* p, int mt, int groups, pconv::MfmaWeights* out) {
     const int F = p->F, C = p->C, K = p->K;
     out->mt = mt;
+    out->groups = groups;
     out->n_mtiles = (F + mt - 1) / mt;
-    out->n_cblocks = (C + 15) / 16;
+    out->n_cblocks = (C / groups + 15) / 16;
     // taps that occur: the union of the masks of the patterns that have kept kernels
     unsigned present = 0;
     for (int i = 0; i < F; ++i)
@@ -261,7 +262,13 @@ void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) 
             out->taps[out->n_taps++] = (uint8_t)t;
         }
     }
+    // (channel ranges in the place of taps: as many tap slots as ranges, all of them the layer's one tap)
+    if (groups > 1) {
+        for (int g = 1; g < groups; ++g) out->taps[g] = out->taps[0];
+        out->n_taps = groups;
+    }
     const int nt = out->n_taps;
+    const size_t group_channels = (size_t)(C / groups);
     // Channels that the filters of every tile keep.  Lists are made where they save at least a tenth of the blocks;
     // otherwise every tile takes all channels in their own order.
     std::vector<std::vector<uint8_t>> used((size_t)out->n_mtiles, std::vector<uint8_t>((size_t)C, 0));
@@ -278,7 +285,7 @@ void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) 
         for (int c = 0; c < C; ++c) n += used[(size_t)t][(size_t)c];
         listed += std::max<size_t>(1, (n + 15) / 16);
     }
-    const bool lists = listed * 10 <= (size_t)out->n_mtiles * out->n_cblocks * 9;
+    const bool lists = groups == 1 && listed * 10 <= (size_t)out->n_mtiles * out->n_cblocks * 9;
     out->clist.clear();
     out->tinfo.clear();
     out->min_blocks = out->n_cblocks;
@@ -315,10 +322,12 @@ void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) 
             for (int t = 0; t < 9; ++t)
                 if ((p->lib[(size_t)j] >> t) & 1u) taps[q++] = t;
             for (uint32_t e = p->grp_ptr[(size_t)i * K + j]; e < p->grp_ptr[(size_t)i * K + j + 1]; ++e) {
-                const size_t c = lists ? pos_of[tile][p->cin[e]] : p->cin[e];      // position among the tile's channels
+                size_t c = lists ? pos_of[tile][p->cin[e]] : p->cin[e];      // position among the tile's channels
+                const size_t range = groups > 1 ? c / group_channels : 0;
+                if (groups > 1) c -= range * group_channels;
                 const size_t cb = c / 16, kb = (c % 16) / 8, c8 = c % 8;
                 for (int k = 0; k < q; ++k) {
-                    const size_t ts = (size_t)slot_of[taps[k]];
+                    const size_t ts = groups > 1 ? range : (size_t)slot_of[taps[k]];
                     const size_t at = ((((first_block[tile] + cb) * nt + ts) * 2 + kb) * mt + fl) * 8 + c8;
                     std::memcpy(&out->w[at], &p->w4[((size_t)e * 4 + k) * 2], 2);
                 }
@@ -332,7 +341,8 @@ void build_mfma_weights(const pconv_packed* p, int mt, pconv::MfmaWeights* out) 
 // pconv_pack, and the packing of a layer re-packed over parity planes (`partial`: masks of one to four taps, up to
 // 255 of them; missing taps of a kernel are stored as zero weights).
 static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
-                     const uint8_t* mask, unsigned flags, bool partial, bool want_mfma, pconv_packed** out) {
+                     const uint8_t* mask, unsigned flags, bool partial, bool want_mfma, pconv_packed** out,
+                     bool one_by_one = false) {
     if (!out) return PCONV_EINVAL;
     *out = nullptr;
     if (!w_oihw || !pid || !mask) return PCONV_EINVAL;
@@ -459,7 +469,14 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
         if (dtype == PCONV_F16 && want_mfma) {
             const int nh = (int)(sizeof(pconv::kMfmaTileHeights) / sizeof(int));
             p->mfma.resize((size_t)nh);
-            for (int h = 0; h < nh; ++h) build_mfma_weights(p, pconv::kMfmaTileHeights[h], &p->mfma[(size_t)h]);
+            for (int h = 0; h < nh; ++h) build_mfma_weights(p, pconv::kMfmaTileHeights[h], 1, &p->mfma[(size_t)h]);
+            // (a 1x1 layer on a small map is bound by the round trips of its many short channel blocks: kept a second
+            // time with two channel ranges per block, which the launch takes for maps of 9 to 16 columns)
+            if (one_by_one && K == 1 && C % (16 * pconv::kOneByOneGroups) == 0) {
+                p->mfma.resize((size_t)(2 * nh));
+                for (int h = 0; h < nh; ++h)
+                    build_mfma_weights(p, pconv::kMfmaTileHeights[h], pconv::kOneByOneGroups, &p->mfma[(size_t)(nh + h)]);
+            }
         }
     } catch (const std::bad_alloc&) {
         delete p;
@@ -553,7 +570,7 @@ extern "C" int pconv_pack_1x1(const void* w_fc, int dtype, int F, int C, const u
                 std::memcpy(&w9[(fc * 9 + 4) * esize], wb + fc * esize, esize);
             }
         const uint16_t centre = 0x010;
-        const int rc = pack_impl(w9.data(), dtype, F, C, &centre, 1, pid9.data(), mask9.data(), flags, true, true, out);
+        const int rc = pack_impl(w9.data(), dtype, F, C, &centre, 1, pid9.data(), mask9.data(), flags, true, true, out, true);
         if (rc == PCONV_OK) (*out)->is_1x1 = true;
         return rc;
     } catch (const std::bad_alloc&) {

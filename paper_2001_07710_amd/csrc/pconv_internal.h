@@ -72,6 +72,10 @@ struct MfmaWeights {
     int min_blocks = 0, total_blocks = 0;
     uint32_t* d_clist = nullptr;
     uint32_t* d_tinfo = nullptr;
+    // A layer of 1x1 kernels (one tap) can be kept a second time with its channels in `groups` equal ranges that take
+    // the place of taps: block b, tap slot t holds channels t*C/groups + 16b .. +15, so a block of the contraction is
+    // 16*groups channels deep and a layer has C/(16*groups) of them (n_cblocks and n_taps say so).  1: not so.
+    int groups = 1;
 };
 
 }  // namespace pconv
@@ -141,6 +145,7 @@ struct MfmaConv {
     size_t w_bytes;             // bytes of the weights at d_w
     int mt, n_taps;
     uint8_t taps[9];
+    int groups;                 // MfmaWeights::groups
     int N, C, F, H, W, Ho, Wo, stride, pad, relu;
     int nhwc;                   // x is [N][H][W][C] and y [N][Ho][Wo][F] (C and F multiples of 8, no channel lists)
     int shape;                  // 1..kMfmaShapes: the tile shape (mt must be its height)
@@ -154,6 +159,7 @@ struct MfmaConv {
 constexpr int kMfmaShapes = 4;
 // tile heights (filters per workgroup) that the kernel's tile shapes use; weights are kept for each
 constexpr int kMfmaTileHeights[2] = {128, 64};
+constexpr int kOneByOneGroups = 2;       // channel ranges per block of the second copy of a 1x1 layer's weights
 int compute_units();        // of the current device
 int mfma_shape_height(int shape);
 // estimated run time in microseconds of shape `shape` with `splits` workgroups per tile, negative if it cannot run

@@ -125,6 +125,9 @@ struct MfmaParams {
     int nhwc;                    // activations and outputs channel-minor ([N][H][W][C], [N][Ho][Wo][F])
     int P;                       // nhwc: 1 KB pieces (64 positions) per half of a staged block: ceil(max_slots * PW / 64)
     FastDiv div_PW;
+    int groups;                  // 1; or (1x1 layers) channel ranges in the place of taps: C is the channels of ONE range,
+                                 // range t of a block is staged in row slots t*max_slots .. and read as tap slot t
+    unsigned group_bytes;        // bytes from a range's channel to the same channel of the next range
     int KS;                      // workgroups that share one tile, each taking a contiguous range of the channel blocks
     int second_pass;             // KS > 1: every part only writes its partial sums; mfma_split_reduce_kernel adds and stores
     int win_alias;               // the epilogue's windows lie in the staging buffer that is free meanwhile: 1 = its
@@ -282,7 +285,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
     auto zero_halo = [&](int stage) {
         if (NHWC || !p.pad) return;
         const uint4v zero = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < p.max_slots * 4; i += NTH) {
+        for (int i = tid; i < p.max_slots * p.groups * 4; i += NTH) {
             const int sl = i >> 2, which = i & 3;               // half (2) x side (2)
             const int pos = (which & 1) ? p.pad + p.W : 0;
             *reinterpret_cast<uint4v*>(ldsB + (stage * 2 + (which >> 1)) * p.plane_bytes + (sl * PW + pos) * 16) = zero;
@@ -345,7 +348,8 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
                 }
             }
         }
-        const float inv_slots = 1.0f / (float)g.used_slots;
+        const int slots_all = g.used_slots * p.groups;         // (with channel ranges: the row slots of every range)
+        const float inv_slots = 1.0f / (float)slots_all;
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
             // Neighbouring lanes take neighbouring ROWS of the same column group, not neighbouring groups of one row:
@@ -357,7 +361,12 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
             // at least 1/(2 slots) away from a whole number, far more than the rounding errors; an integer division
             // by a number that is not known when compiling is some forty instructions)
             const unsigned it = (unsigned)(ltid + i * HALF);
-            const unsigned gg = (unsigned)(((float)it + 0.5f) * inv_slots), sl = it - gg * (unsigned)g.used_slots;
+            const unsigned gg = (unsigned)(((float)it + 0.5f) * inv_slots);
+            unsigned sl = it - gg * (unsigned)slots_all, range = 0;
+            while (sl >= (unsigned)g.used_slots) {              // (at most groups - 1 times)
+                sl -= (unsigned)g.used_slots;
+                ++range;
+            }
             goff[i] = kInvalid;
             loff[i] = -1;
             if (gg < (unsigned)p.G) {
@@ -371,8 +380,8 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
                     iy = (int)(t - q * (unsigned)p.cnt_full) - p.pad;
                 }
                 if (g.n0 + seg < p.N && iy >= 0 && iy < p.H)
-                    goff[i] = (uint32_t)seg * p.img_bytes + (uint32_t)(iy * p.W + (int)gg * LW) * 2u;
-                loff[i] = kbs * p.plane_bytes + ((int)sl * PW + p.pad + (int)gg * LW) * 16;
+                    goff[i] = (uint32_t)seg * p.img_bytes + (uint32_t)(iy * p.W + (int)gg * LW) * 2u + range * p.group_bytes;
+                loff[i] = kbs * p.plane_bytes + (((int)range * p.max_slots + (int)sl) * PW + p.pad + (int)gg * LW) * 16;
             }
         }
         // (at most 2^31 - 1 bytes, so that the offset that stands for "nothing to load" is outside whatever the
@@ -1048,7 +1057,10 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.wq = static_cast<const unsigned char*>(a.d_w);
     p.N = a.N; p.C = a.C; p.F = a.F; p.H = a.H; p.W = a.W; p.Ho = a.Ho; p.Wo = a.Wo;
     p.stride = a.stride; p.pad = a.pad; p.relu = a.relu;
-    p.CB = (a.C + 15) / 16;
+    p.groups = a.groups > 1 ? a.groups : 1;
+    if (p.groups > 1 && (a.nhwc || a.d_clist || a.C % (16 * p.groups) || a.n_taps != p.groups)) return false;
+    p.C = a.C / p.groups;
+    p.CB = (p.C + 15) / 16;
     p.clist = a.d_clist;
     p.tinfo = a.d_tinfo;
     // (channel-minor activations are loaded eight channels at a time as they lie: no channel lists, whole groups)
@@ -1092,7 +1104,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         if (a.Ho % R == 0) segs = 1;                         // (tiles never cross from one image into the next)
         p.max_slots = (R - segs) * a.stride + 3 * segs;
         p.a_bytes = p.nt * 2 * MT * 16;
-        p.plane_bytes = p.max_slots * p.PW * 16;
+        p.plane_bytes = p.groups * p.max_slots * p.PW * 16;
         // (channel-minor activations arrive in wave-wide pieces of 32 positions, both halves: a stage is 2 P pieces)
         p.P = (p.max_slots * p.PW + 63) / 64;
         if (a.nhwc) p.plane_bytes = p.P * 1024;
@@ -1131,14 +1143,15 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         }
         // widest loads whose pieces fit the lanes; fewer rows only when even the narrowest fit nowhere
         int w = lw;
-        while (w > 1 && (long long)p.max_slots * (a.W / w) > (long long)max_items(w) * (NTH / 2)) w /= 2;
-        if ((long long)p.max_slots * (a.W / w) <= (long long)max_items(w) * (NTH / 2)) {
+        const long long slots_all = (long long)p.max_slots * p.groups;
+        while (w > 1 && slots_all * (a.W / w) > (long long)max_items(w) * (NTH / 2)) w /= 2;
+        if (slots_all * (a.W / w) <= (long long)max_items(w) * (NTH / 2)) {
             lw = w;
             break;
         }
     }
     p.G = a.nhwc ? 1 : a.W / lw;                  // (channel-minor staging has no pieces of lw pixels)
-    const int need_items = (int)(((long long)p.max_slots * p.G + NTH / 2 - 1) / (NTH / 2));
+    const int need_items = (int)(((long long)p.max_slots * p.groups * p.G + NTH / 2 - 1) / (NTH / 2));
     const int ki = a.nhwc ? 1 : lw == 8 ? std::max(need_items, 1) : lw == 4 ? std::max(need_items, 2) : 3;
     p.nhwc = a.nhwc ? 1 : 0;
     p.div_PW = make_fastdiv((unsigned)p.PW);
@@ -1148,14 +1161,18 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.sw = (a.Wo % 8 == 0 && ya % 16 == 0) ? 8 : (a.Wo % 4 == 0 && ya % 8 == 0) ? 4 : (a.Wo % 2 == 0 && ya % 4 == 0) ? 2 : 1;
     p.sw_groups = a.Wo / p.sw;
     for (int t = 0; t < p.nt; ++t) p.tap_off[t] = ((a.taps[t] / 3) * p.PW + a.taps[t] % 3) * (a.nhwc ? 32 : 16);
+    // (channel ranges in the place of taps: range t lies max_slots row slots behind range t - 1)
+    if (p.groups > 1)
+        for (int t = 0; t < p.nt; ++t) p.tap_off[t] += t * p.max_slots * p.PW * 16;
     p.x_bytes = (unsigned long long)a.N * a.C * a.H * a.W * 2ull;
     p.chan_bytes = (unsigned)((size_t)a.H * a.W * 2);
+    p.group_bytes = p.groups > 1 ? (unsigned)p.C * p.chan_bytes : 0u;
     const unsigned long long img = (unsigned long long)a.C * a.H * a.W * 2ull;
     if (img * (unsigned long long)(segs + 1) >= 0x7FFFFFFFull) return false;   // 32-bit offsets inside a tile's images
     p.img_bytes = (unsigned)img;
     p.y_bytes = (unsigned long long)a.N * a.F * a.Ho * a.Wo * 2ull;
     if ((unsigned long long)a.F * a.Ho * a.Wo * 2ull * (unsigned long long)(segs + 1) >= 0x7FFFFFFFull) return false;
-    const size_t wq_bytes = a.d_clist ? a.w_bytes : mfma_weight_bytes(a.F, a.C, MT, p.nt);
+    const size_t wq_bytes = a.d_clist ? a.w_bytes : mfma_weight_bytes(a.F, p.C, MT, p.nt);
     if (wq_bytes >= 0x7FFFFFFFull) return false;
     p.wq_bytes = (unsigned)wq_bytes;
     p.div_Wo = make_fastdiv((unsigned)a.Wo);
