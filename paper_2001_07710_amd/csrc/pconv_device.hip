@@ -2251,12 +2251,35 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         a.rows = tuning ? tuning->rows : 0;
         a.walk = tuning ? tuning->slot_walk : 0;
         if (a.shape < 0 || a.shape > kMfmaShapes) return PCONV_EINVAL;
-        // (a 1x1 layer on a map of 9 to 16 columns: the copy of its weights with channel ranges in the place of
-        // taps, if the layer has one -- half as many blocks, each twice as deep; channel-major tensors only.
-        // Measured at batch 32: 1024 -> 256 channels at 14 x 14 44 -> 37 us, 256 -> 1024 37 -> 30; at 7 x 7, where a
-        // lane stages one-pixel pieces, level)
+        // (a layer of 1x1 kernels: its one tap is the centre of a 3x3 kernel at padding 1, which is tap 0 of a kernel
+        // of extent 1 at padding 0 -- the same outputs, and no halo rows and columns to stage; and the copy of its
+        // weights with channel ranges in the place of taps, if the layer has one: a quarter of the blocks, each four
+        // times as deep; channel-major tensors only)
         a.groups = 1;
-        if (wp->is_1x1 && W > 8 && W <= 16 && !nhwc)
+        a.kext = 3;
+        if (wp->is_1x1 && pad == 1) {
+            a.kext = 1;
+            a.pad = 0;
+            // (at stride 1 a 1x1 layer does not know rows from columns: an image's H*W pixels, contiguous in either
+            // layout, are cut into rows of whatever length suits the kernel -- a multiple of 8 pixels for the widest
+            // loads where H*W has such a divisor, and rows that fill a tile of 224 pixels)
+            if (stride == 1) {
+                const long long hw = (long long)H * W;
+                long long best_w = W;
+                int best_lw = 0, best_fill = 0;
+                for (int w2 = 1; w2 <= 224 && w2 <= hw; ++w2) {
+                    if (hw % w2) continue;
+                    const int lw2 = w2 % 8 == 0 ? 8 : w2 % 4 == 0 ? 4 : w2 % 2 == 0 ? 2 : 1;
+                    const int fill = (224 / w2) * w2;
+                    if (lw2 > best_lw || (lw2 == best_lw && fill >= best_fill)) {
+                        best_lw = lw2; best_fill = fill; best_w = w2;
+                    }
+                }
+                a.W = a.Wo = (int)best_w;
+                a.H = a.Ho = (int)(hw / best_w);
+            }
+        }
+        if (wp->is_1x1 && a.kext == 1 && !nhwc)
             for (const MfmaWeights& m : wp->mfma)
                 if (m.groups > 1) a.groups = m.groups;
         for (const MfmaWeights& m : wp->mfma)
@@ -2325,6 +2348,7 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
                 a.d_clist = m.d_clist; a.d_tinfo = m.d_tinfo;
                 a.min_blocks = m.min_blocks; a.total_blocks = m.total_blocks; a.w_bytes = m.bytes();
                 std::memcpy(a.taps, m.taps, sizeof(a.taps));
+                if (a.kext == 1) std::memset(a.taps, 0, sizeof(a.taps));
                 if (a.splits > 1) {
                     size_t floats = 0, counters = 0;
                     rc = mfma_workspace(a, &floats, &counters);

@@ -470,8 +470,8 @@ static int pack_impl(const void* w_oihw, int dtype, int F, int C, const uint16_t
             const int nh = (int)(sizeof(pconv::kMfmaTileHeights) / sizeof(int));
             p->mfma.resize((size_t)nh);
             for (int h = 0; h < nh; ++h) build_mfma_weights(p, pconv::kMfmaTileHeights[h], 1, &p->mfma[(size_t)h]);
-            // (a 1x1 layer on a small map is bound by the round trips of its many short channel blocks: kept a second
-            // time with two channel ranges per block, which the launch takes for maps of 9 to 16 columns)
+            // (a 1x1 layer is bound by the round trips of its many short channel blocks: kept a second time with
+            // several channel ranges per block)
             if (one_by_one && K == 1 && C % (16 * pconv::kOneByOneGroups) == 0) {
                 p->mfma.resize((size_t)(2 * nh));
                 for (int h = 0; h < nh; ++h)

@@ -146,6 +146,8 @@ struct MfmaConv {
     int mt, n_taps;
     uint8_t taps[9];
     int groups;                 // MfmaWeights::groups
+    int kext;                   // rows and columns of the kernel's extent: 3, or 1 for a layer of 1x1 kernels (its one tap
+                                // is then tap 0 at padding 0: no halo rows or columns are staged); 0 means 3
     int N, C, F, H, W, Ho, Wo, stride, pad, relu;
     int nhwc;                   // x is [N][H][W][C] and y [N][Ho][Wo][F] (C and F multiples of 8, no channel lists)
     int shape;                  // 1..kMfmaShapes: the tile shape (mt must be its height)
@@ -159,7 +161,7 @@ struct MfmaConv {
 constexpr int kMfmaShapes = 4;
 // tile heights (filters per workgroup) that the kernel's tile shapes use; weights are kept for each
 constexpr int kMfmaTileHeights[2] = {128, 64};
-constexpr int kOneByOneGroups = 2;       // channel ranges per block of the second copy of a 1x1 layer's weights
+constexpr int kOneByOneGroups = 4;       // channel ranges per block of the second copy of a 1x1 layer's weights
 int compute_units();        // of the current device
 int mfma_shape_height(int shape);
 // estimated run time in microseconds of shape `shape` with `splits` workgroups per tile, negative if it cannot run

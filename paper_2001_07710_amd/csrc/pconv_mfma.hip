@@ -111,7 +111,8 @@ struct MfmaParams {
     int R;                  // output rows (of the batch, n*Ho + oy) per tile
     int PW;                 // positions per input row slot: W + 2*pad, or more (plan())
     int max_slots;          // input row slots reserved per buffer
-    int cnt_full;           // input row slots of a whole image: (Ho-1)*stride + 3
+    int kext;               // the kernel's extent in rows (3; 1 for a layer of 1x1 kernels)
+    int cnt_full;           // input row slots of a whole image: (Ho-1)*stride + kext
     int tiles_n, tiles_m;
     int G;                  // pieces per input row: W / LW
     int a_bytes;            // weights of one channel block: nt * 2 * MT * 16
@@ -265,10 +266,10 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
         g.n0 = (int)fastdiv((unsigned)R0, p.div_Ho);
         g.oy0 = R0 - g.n0 * Ho;
         const int rows0 = min(g.Rv, Ho - g.oy0);                   // rows in the first image
-        g.cnt0 = (rows0 - 1) * s + 3;
+        g.cnt0 = (rows0 - 1) * s + p.kext;
         const int last_g = (int)fastdiv((unsigned)(g.oy0 + g.Rv - 1), p.div_Ho);
         const int rows_last = last_g == 0 ? rows0 : g.oy0 + g.Rv - last_g * Ho;
-        g.used_slots = last_g == 0 ? g.cnt0 : g.cnt0 + (last_g - 1) * p.cnt_full + (rows_last - 1) * s + 3;
+        g.used_slots = last_g == 0 ? g.cnt0 : g.cnt0 + (last_g - 1) * p.cnt_full + (rows_last - 1) * s + p.kext;
         return g;
     };
 
@@ -1035,7 +1036,7 @@ int launch_shape(const MfmaParams& p, int lw, int ki, size_t lds, int walk, doub
     PCONV_MFMA_CASE1(8, 1, true)
 #else
     PCONV_MFMA_CASE(8, 1) PCONV_MFMA_CASE(8, 2) PCONV_MFMA_CASE(4, 2) PCONV_MFMA_CASE(4, 3) PCONV_MFMA_CASE(2, 3)
-    PCONV_MFMA_CASE(1, 3)
+    PCONV_MFMA_CASE(1, 3) PCONV_MFMA_CASE1(2, 4, false) PCONV_MFMA_CASE1(1, 7, false)
     PCONV_MFMA_CASE2(8, 1, true, true) PCONV_MFMA_CASE2(8, 1, false, true)
 #endif
 #undef PCONV_MFMA_CASE
@@ -1083,7 +1084,8 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     const uintptr_t xa = reinterpret_cast<uintptr_t>(a.x), ya = reinterpret_cast<uintptr_t>(a.y);
     int lw = (a.W % 8 == 0 && xa % 16 == 0) ? 8 : (a.W % 4 == 0 && xa % 8 == 0) ? 4 : (a.W % 2 == 0 && xa % 4 == 0) ? 2 : 1;
     // pieces of the activations per lane that the kernels are built for, by load width
-    auto max_items = [](int w) { return w == 8 ? 2 : 3; };
+    // (1x1 layers with channel ranges in the place of taps stage several ranges per block: more of the narrow pieces)
+    auto max_items = [&](int w) { return w == 8 ? 2 : a.groups > 1 ? (w == 2 ? 4 : w == 1 ? 7 : 3) : 3; };
     p.PW = a.W + 2 * a.pad;
     // Maps of at most 16 columns: 32 consecutive pixels span three or more rows, and a lane's operand read jumps by
     // PW - Wo positions at every row end.  With that gap a multiple of 8 positions (128 bytes, all LDS banks once) the
@@ -1092,7 +1094,8 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     // (256 -> 256 channels at 56 x 56: 180 -> 194 us).
     if (a.stride == 1 && a.W <= 16)
         while ((p.PW - a.Wo) % 8) ++p.PW;
-    p.cnt_full = (a.Ho - 1) * a.stride + 3;
+    p.kext = a.kext == 1 ? 1 : 3;
+    p.cnt_full = (a.Ho - 1) * a.stride + p.kext;
     // rows per tile: as many as fit the pixels of the tile, the staging pieces of a lane and the LDS
     // Input row slots: a tile of R output rows that touches k images needs (R - k)*stride + 3k of them, most for the
     // largest k: at most (R + Ho - 2)/Ho + 1 images, and no more than it has rows.
@@ -1102,7 +1105,10 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         if (R < 1) return false;
         segs = std::min(R, (R + a.Ho - 2) / a.Ho + 1);
         if (a.Ho % R == 0) segs = 1;                         // (tiles never cross from one image into the next)
-        p.max_slots = (R - segs) * a.stride + 3 * segs;
+        // (a kernel of extent 1 at stride 2 is the other way round: every further image SAVES a row slot, so the most
+        // are needed by a tile that touches as few images as its rows allow)
+        const int most_at = a.stride > p.kext ? std::max(1, (R + a.Ho - 1) / a.Ho) : segs;
+        p.max_slots = (R - most_at) * a.stride + p.kext * most_at;
         p.a_bytes = p.nt * 2 * MT * 16;
         p.plane_bytes = p.groups * p.max_slots * p.PW * 16;
         // (channel-minor activations arrive in wave-wide pieces of 32 positions, both halves: a stage is 2 P pieces)
@@ -1152,7 +1158,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     }
     p.G = a.nhwc ? 1 : a.W / lw;                  // (channel-minor staging has no pieces of lw pixels)
     const int need_items = (int)(((long long)p.max_slots * p.groups * p.G + NTH / 2 - 1) / (NTH / 2));
-    const int ki = a.nhwc ? 1 : lw == 8 ? std::max(need_items, 1) : lw == 4 ? std::max(need_items, 2) : 3;
+    const int ki = a.nhwc ? 1 : lw == 8 ? std::max(need_items, 1) : lw == 4 ? std::max(need_items, 2) : need_items <= 3 ? 3 : lw == 2 ? 4 : 7;
     p.nhwc = a.nhwc ? 1 : 0;
     p.div_PW = make_fastdiv((unsigned)p.PW);
     p.R = R;
@@ -1276,6 +1282,15 @@ double mfma_estimate_us(const MfmaConv& a0, int shape, int splits) {
     const double split_us = p.KS <= 1 ? 0.0 : a.second_pass ? 4.0 + 2.0 * part_bytes / 4.5e6
                                                              : 4.0 + 1.5 * (p.KS - 1) + part_bytes / 1.8e6;
     if (p.nt < 9) block_us *= (double)std::max(p.nt, 1) / 9.0;
+    // A 1x1 layer with channel ranges in the place of taps multiplies for a fraction of the time that staging a
+    // block takes its waves: 8 ki load instructions per lane and block with their address arithmetic, transposition
+    // and LDS writes.  Fitted to ResNet-50's bottleneck layers at batch 32 (56 x 56 to 7 x 7 maps, 128 x 224 tiles):
+    // 0.8 us + 0.1 us per load; 8 us per tile.  The other tile shapes stage twice the pieces per lane, or share the
+    // compute unit, and lost on every one of those layers: they are priced out of the automatic choice.
+    if (a.groups > 1) {
+        const double staged_us = 0.8 + 0.1 * 8.0 * ki;
+        return (rounds * (8.0 + blocks * staged_us) + split_us) * (shape == 3 ? 1.0 : 2.0);
+    }
     return rounds * (tile_us + blocks * std::max(block_us, floor_us)) + split_us;
 }
 

@@ -133,7 +133,12 @@ def test_masked_weight_gradient_at_a_benchmark_shape_on_sampled_weights():
 
 
 C1 = [(2, 64, 40, 14, 14, 1, "f16"), (3, 100, 33, 9, 12, 1, "f32"), (2, 256, 64, 28, 28, 1, "f16"),
-      (2, 48, 96, 20, 56, 2, "f16"), (2, 21, 10, 15, 18, 2, "f32"), (1, 5, 3, 1, 1, 1, "f16")]
+      (2, 48, 96, 20, 56, 2, "f16"), (2, 21, 10, 15, 18, 2, "f32"), (1, 5, 3, 1, 1, 1, "f16"),
+      # channel counts that are multiples of 64 (the matrix-core kernel then takes four channel ranges per block):
+      # stride 2 on small images, so that tiles run across several of them; 7 x 7 maps (one-pixel pieces); a map whose
+      # pixels have no even divisor; many blocks, so that the channel split is taken
+      (5, 128, 64, 10, 12, 2, "f16"), (9, 64, 160, 7, 7, 1, "f16"), (3, 192, 40, 5, 5, 2, "f16"),
+      (4, 1024, 96, 14, 14, 1, "f16"), (2, 64, 64, 9, 11, 1, "f16")]
 
 
 @pytest.mark.parametrize("case", C1, ids=[f"n{c[0]}c{c[1]}f{c[2]}h{c[3]}w{c[4]}s{c[5]}{c[6]}" for c in C1])
@@ -161,6 +166,25 @@ def test_grouped_1x1_layer(case):
         ref = oracle.conv1x1(x, w, pid, mask, lib, b, stride, relu)
         err = rel_err(d_y.cpu().numpy(), ref)
         assert err <= TOL[dt], (case, relu, err)
+    if dt == "f16":
+        # every tile shape of the matrix-core kernel, unsplit and in two parts added either way (the layer is the
+        # centre-tap 3x3 layer at padding 1 to this entry point)
+        ran = 0
+        for sh in (1, 2, 3, 4):
+            for ks, sr in ((1, 0), (2, 1), (2, 2)):
+                d_y.fill_(-777.0)
+                try:
+                    pc.conv3x3_tuned(d_x, d_y, p, d_b, N, H, W, stride, 1, pc.FLAG_RELU, torch.cuda.current_stream().cuda_stream,
+                                     kernel=pc.KERNEL_MFMA, mfma_shape=sh, channel_splits=ks, split_reduce=sr)
+                except pc.PconvError as e:
+                    assert e.code == pc.EUNSUPPORTED, (case, sh, ks, sr)
+                    continue
+                torch.cuda.synchronize()
+                err = rel_err(d_y.cpu().numpy(), ref)
+                assert err <= TOL[dt], (case, sh, ks, sr, err)
+                ran += 1
+        say("  matrix-core forms run:", ran)
+        assert ran >= 4 or C < 16
     p.free()
 
 
