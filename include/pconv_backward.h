@@ -79,7 +79,9 @@ int pconv_conv3x3_grad_weight(const void* x, const void* dy, const pconv_packed*
  *   mask   host, uint8[F][G]: 1 = the group is kept
  * The handle is a 3x3 layer whose kept kernels hold their centre tap only: pconv_packed_export lists, per filter,
  * the kept channels ascending with the weight bit-identical in w4[e][0] (slots 1..3 zero), K = 1.  Errors as
- * pconv_pack.
+ * pconv_pack.  For fp16 storage and C a multiple of 64 the handle holds the matrix-core kernel's copy of the weights
+ * twice (the second time with the channels in four ranges that the kernel walks like taps): 2 * 2 * F * C bytes more
+ * on the device.
  */
 int pconv_pack_1x1(const void* w_fc, int dtype, int F, int C, const uint16_t* lib, int K, const uint8_t* pid,
                    const uint8_t* mask, unsigned flags, pconv_packed** out);
