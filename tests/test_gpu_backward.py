@@ -185,6 +185,14 @@ def test_grouped_1x1_layer(case):
                 ran += 1
         say("  matrix-core forms run:", ran)
         assert ran >= 4 or C < 16
+        if C % 8 == 0 and F % 8 == 0:
+            # channel-minor tensors: x [N][H][W][C], y [N][Ho][Wo][F]
+            d_xh = d_x.permute(0, 2, 3, 1).contiguous()
+            d_yh = torch.full((N, Ho, Wo, F), -777.0, dtype=d_x.dtype, device="cuda")
+            pc.conv1x1(d_xh, d_yh, p, d_b, N, H, W, stride, pc.FLAG_RELU | pc.FLAG_NHWC, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            err = rel_err(d_yh.permute(0, 3, 1, 2).contiguous().cpu().numpy(), ref)
+            assert err <= TOL[dt], (case, "channel-minor", err)
     p.free()
 
 
