@@ -208,7 +208,7 @@ def main():
         return peaks_bench(args, torch)
     if args.admm:
         return admm_bench(args, torch, pc, L)
-    if args.nhwc:
+    if args.nhwc and not args.conv1x1:
         return nhwc_bench(args, torch, pc, L)
     if args.clustered:
         return clustered_bench(args, torch, pc, L)
@@ -837,7 +837,12 @@ def conv1x1_bench(args, torch, pc, L, brief=False):
         dx = torch.from_numpy(np.concatenate([x1] * (N // 4), axis=0)).cuda()
         db = torch.from_numpy(b).cuda()
         dy = torch.empty((N, F, H, H), dtype=torch.float16, device="cuda")
-        fn = lambda: pc.conv1x1(dx, dy, p, db, N, H, H, 1, pc.FLAG_RELU, st)
+        fl = pc.FLAG_RELU
+        if getattr(args, "nhwc", False):        # (--conv1x1 --nhwc: the same layers on channel-minor tensors)
+            dx = dx.permute(0, 2, 3, 1).contiguous()
+            dy = torch.empty((N, H, H, F), dtype=torch.float16, device="cuda")
+            fl |= pc.FLAG_NHWC
+        fn = lambda: pc.conv1x1(dx, dy, p, db, N, H, H, 1, fl, st)
         _, ms = time_launches(torch, fn, args.steps, args.warmup)
         nbytes = 2.0 * N * H * H * (C + F) + 2.0 * p.n_kept
         row = {"layer": name, "C": C, "F": F, "H": H, "n_kept_weights": p.n_kept, "us": ms * 1e3,
@@ -864,7 +869,8 @@ def conv1x1_bench(args, torch, pc, L, brief=False):
     out = {"metric": "algorithmic GB/s, ResNet-50 1x1 layers grouped into 3x3 patterns", "value": tot_bytes / tot_ms / 1e6,
            "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": tot_ms,
            "higher_is_better": True, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
-           "config": {"workload": f"eight 1x1 layers of ResNet-50's bottlenecks, batch 32, K={args.K}, keep {args.keep}"},
+           "config": {"workload": f"eight 1x1 layers of ResNet-50's bottlenecks, batch 32, K={args.K}, keep {args.keep}"
+                                  + (", x and y channel-minor (NHWC)" if getattr(args, "nhwc", False) else "")},
            "roofline": {"bound": "hbm", "achieved": tot_bytes / tot_ms / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": tot_bytes / tot_ms / 1e6 / PEAK_HBM_GBS, "traffic": None, "kernel": "mfma_conv_kernel"},
            "layers": rows,

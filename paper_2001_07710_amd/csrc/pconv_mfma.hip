@@ -128,7 +128,9 @@ struct MfmaParams {
     FastDiv div_PW;
     int groups;                  // 1; or (1x1 layers) channel ranges in the place of taps: C is the channels of ONE range,
                                  // range t of a block is staged in row slots t*max_slots .. and read as tap slot t
-    unsigned group_bytes;        // bytes from a range's channel to the same channel of the next range
+    unsigned group_bytes;        // bytes from a range's channel to the same channel of the next range (channel-major: whole
+                                 // planes; channel-minor: inside a pixel's channel vector)
+    int Cpix;                    // channel-minor: channels per pixel in memory (C, or C * groups with channel ranges)
     int KS;                      // workgroups that share one tile, each taking a contiguous range of the channel blocks
     int second_pass;             // KS > 1: every part only writes its partial sums; mfma_split_reduce_kernel adds and stores
     int win_alias;               // the epilogue's windows lie in the staging buffer that is free meanwhile: 1 = its
@@ -345,7 +347,7 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
                         iy = (int)(t - qq * (unsigned)p.cnt_full) - p.pad;
                     }
                     if (g.n0 + seg < p.N && iy >= 0 && iy < p.H)
-                        agoff[i] = (uint32_t)seg * p.img_bytes + (uint32_t)((iy * p.W + col) * p.C + half * 8) * 2u;
+                        agoff[i] = (uint32_t)seg * p.img_bytes + (uint32_t)((iy * p.W + col) * p.Cpix + half * 8) * 2u;
                 }
             }
         }
@@ -421,8 +423,12 @@ __global__ __launch_bounds__(WM* WN * 64, (AF == 1 && WM == 2 && WN == 2) ? 2 : 
             if (id < 2 * p.P) {
                 const __amdgpu_buffer_rsrc_t xr =
                     make_rsrc(reinterpret_cast<const void*>(((unsigned long long)xb_hi << 32) | xb_lo), x_records);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_ptr)(ldsB + buf * 2 * p.plane_bytes + id * 1024),
-                                                         16, (int)(stage_on ? agoff[j] : kInvalid), cb * 32, 0, 0);
+                // (with channel ranges in the place of taps: the same positions of every range, each range into its
+                // own part of the stage, 2 P pieces long)
+                for (int t = 0; t < p.groups; ++t)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        xr, (lds_ptr)(ldsB + buf * 2 * p.plane_bytes + t * (2 * p.P * 1024) + id * 1024), 16,
+                        (int)(stage_on ? agoff[j] : kInvalid), cb * 32 + t * (int)p.group_bytes, 0, 0);
             }
           } else {
             const int i = j >> 3, ch = j & 7;
@@ -1059,7 +1065,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     p.N = a.N; p.C = a.C; p.F = a.F; p.H = a.H; p.W = a.W; p.Ho = a.Ho; p.Wo = a.Wo;
     p.stride = a.stride; p.pad = a.pad; p.relu = a.relu;
     p.groups = a.groups > 1 ? a.groups : 1;
-    if (p.groups > 1 && (a.nhwc || a.d_clist || a.C % (16 * p.groups) || a.n_taps != p.groups)) return false;
+    if (p.groups > 1 && (a.d_clist || a.C % (16 * p.groups) || a.n_taps != p.groups)) return false;
     p.C = a.C / p.groups;
     p.CB = (p.C + 15) / 16;
     p.clist = a.d_clist;
@@ -1113,7 +1119,7 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
         p.plane_bytes = p.groups * p.max_slots * p.PW * 16;
         // (channel-minor activations arrive in wave-wide pieces of 32 positions, both halves: a stage is 2 P pieces)
         p.P = (p.max_slots * p.PW + 63) / 64;
-        if (a.nhwc) p.plane_bytes = p.P * 1024;
+        if (a.nhwc) p.plane_bytes = p.groups * p.P * 1024;
         // (a layer of at most 16 channels and one tile of filters has a single block of weights: staged once)
         const bool shares_cu = sh.af == 1 && sh.wm == 2 && sh.wn == 2;    // (the shape two workgroups of which fit)
         p.a_stages = (shares_cu && p.CB == 1 && (a.F + MT - 1) / MT == 1 && p.KS == 1) ? 1 : 2;
@@ -1169,10 +1175,11 @@ bool plan(const MfmaConv& a, int shape, int rows, MfmaParams* out, int* lw_out, 
     for (int t = 0; t < p.nt; ++t) p.tap_off[t] = ((a.taps[t] / 3) * p.PW + a.taps[t] % 3) * (a.nhwc ? 32 : 16);
     // (channel ranges in the place of taps: range t lies max_slots row slots behind range t - 1)
     if (p.groups > 1)
-        for (int t = 0; t < p.nt; ++t) p.tap_off[t] += t * p.max_slots * p.PW * 16;
+        for (int t = 0; t < p.nt; ++t) p.tap_off[t] += a.nhwc ? t * (2 * p.P * 1024) : t * p.max_slots * p.PW * 16;
     p.x_bytes = (unsigned long long)a.N * a.C * a.H * a.W * 2ull;
     p.chan_bytes = (unsigned)((size_t)a.H * a.W * 2);
-    p.group_bytes = p.groups > 1 ? (unsigned)p.C * p.chan_bytes : 0u;
+    p.group_bytes = p.groups > 1 ? (a.nhwc ? (unsigned)p.C * 2u : (unsigned)p.C * p.chan_bytes) : 0u;
+    p.Cpix = a.C;
     const unsigned long long img = (unsigned long long)a.C * a.H * a.W * 2ull;
     if (img * (unsigned long long)(segs + 1) >= 0x7FFFFFFFull) return false;   // 32-bit offsets inside a tile's images
     p.img_bytes = (unsigned)img;
