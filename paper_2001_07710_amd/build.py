@@ -29,16 +29,31 @@ def build_library(verbose: bool = False) -> str:
         gen_pattern_leaves.main(os.path.join(CSRC, "pattern_leaves.inc"))
     finally:
         sys.path.pop(0)
-    cmd = [hipcc, *HIPCC_FLAGS, "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-o", LIB,
-           *[os.path.join(CSRC, s) for s in SOURCES]]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+    # one object per source, compiled side by side (the matrix-core kernel's instantiations alone take minutes), then
+    # one link; the objects live in a build folder that is not committed
+    from concurrent.futures import ThreadPoolExecutor
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + out)
+        if verbose and out.strip():
+            print(out)
+
+    def compile_one(src):
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+        run([hipcc, *flags, "-c", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-o", obj, os.path.join(CSRC, src)])
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), max(1, (os.cpu_count() or 2) - 1))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    run([hipcc, "-shared", "--offload-arch=gfx950", "-o", LIB, *objs])
     # the measured-peaks kernels: a library of their own, not linked into libpconv.so
     cmd = [hipcc, *HIPCC_FLAGS, "-I" + os.path.join(ROOT, "include"), "-o", PEAKS_LIB, os.path.join(CSRC, "pconv_peaks.hip")]
     if verbose:
