@@ -505,7 +505,10 @@ def sweep_bench(args, torch, pc, L, stream):
             "channel_minor_layout_vgg16_batch64_fp16": nhwc_bench(b, torch, pc, L, brief=True),
         }
         b.keep = 0.3
+        b.nhwc = False
         out["beyond_the_forward_pass"]["conv1x1_resnet50_batch32_fp16"] = conv1x1_bench(b, torch, pc, L, brief=True)
+        b.nhwc = True
+        out["beyond_the_forward_pass"]["conv1x1_resnet50_batch32_fp16_channel_minor"] = conv1x1_bench(b, torch, pc, L, brief=True)
     print(json.dumps(out), flush=True)
 
 
