@@ -2254,10 +2254,11 @@ static int conv3x3_impl(const void* x, void* y, const pconv_packed* wp, const fl
         // (a layer of 1x1 kernels: its one tap is the centre of a 3x3 kernel at padding 1, which is tap 0 of a kernel
         // of extent 1 at padding 0 -- the same outputs, and no halo rows and columns to stage; and the copy of its
         // weights with channel ranges in the place of taps, if the layer has one: a quarter of the blocks, each four
-        // times as deep -- for maps of at most 1024 pixels: the 56 x 56 layers of ResNet-50 lost a tenth with it)
+        // times as deep.  Both for maps of at most 1024 pixels (and for channel-minor tensors): the 56 x 56 layers of
+        // ResNet-50, channel-major, whose 8-pixel loads and four-row tiles are fine as they are, lost a tenth)
         a.groups = 1;
         a.kext = 3;
-        if (wp->is_1x1 && pad == 1) {
+        if (wp->is_1x1 && pad == 1 && ((long long)H * W <= 1024 || nhwc)) {
             a.kext = 1;
             a.pad = 0;
             // (at stride 1 a 1x1 layer does not know rows from columns: an image's H*W pixels, contiguous in either
